@@ -1,0 +1,147 @@
+"""Seeded synthetic layer inputs (A, G) for the per-example clipping path.
+
+This module only draws random tensors.  It holds none of the method's
+arithmetic (no norms, no clip factors, no gradients): both the CPU oracle's
+tests and the HIP path's tests/bench read their inputs from here so that the
+two sides consume identical bits.
+
+The paper measured on MNIST / FMNIST / CIFAR10 / IMDB / LSUN models
+(Section 6).  None of that data is needed by the path, which consumes only a
+layer's inputs X^(l) and the back-propagated dLoss/dZ^(l) (Section 5, last
+paragraph before 5.1).  The generators below stand in for those datasets:
+they reproduce layer *shapes* and value *distributions* (post-ReLU half-zero
+activations, tanh activations, small Gaussian output gradients).
+
+Layouts: A is [B, T, d_in], G is [B, T, d_out], row-major, example-major.
+fp32 tensors are numpy float32.  bf16 tensors are numpy uint16 holding the
+upper 16 bits of the float32 value after round-to-nearest-even.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Tuple
+
+import numpy as np
+
+BASE_SEED = 20090310
+
+
+@dataclass(frozen=True)
+class LayerSpec:
+    name: str
+    T: int
+    d_in: int
+    d_out: int
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One benchmark configuration: a list of linear layers sharing a batch."""
+    name: str
+    index: int            # position in the configuration list (also the seed offset)
+    B: int
+    dtype: str            # "f32" or "bf16"
+    C: float              # clipping threshold
+    layers: Tuple[LayerSpec, ...]
+    a_dist: str           # "normal" | "relu" | "tanh"
+    g_std: float
+    typical_norm: float   # rough size of one example's gradient norm (only used to centre the straddle variant)
+    noise_std: float = 0.0
+    noise_seed: int = 0x5EED2009
+
+
+WORKLOADS = {
+    "dense": Workload("dense", 0, 32, "f32", 1.0,
+                      (LayerSpec("fc", 1, 64, 32),), "normal", 0.1, 4.5),
+    "mlp": Workload("mlp", 1, 256, "f32", 1.0,
+                    (LayerSpec("fc1", 1, 784, 512), LayerSpec("fc2", 1, 512, 256),
+                     LayerSpec("fc3", 1, 256, 10)), "relu", 0.01, 5.2),
+    "rnn": Workload("rnn", 2, 128, "bf16", 0.5,
+                    (LayerSpec("shared_linear", 64, 256, 256),), "tanh", 0.01, 12.9),
+    "conv": Workload("conv", 3, 128, "bf16", 1.0,
+                     (LayerSpec("conv3x3_im2col", 1024, 576, 128),), "relu", 0.001, 6.1),
+    "transformer": Workload("transformer", 4, 64, "bf16", 1.0,
+                            (LayerSpec("qkv", 512, 768, 2304), LayerSpec("attn_out", 512, 768, 768),
+                             LayerSpec("ffn_up", 512, 768, 3072), LayerSpec("ffn_down", 512, 3072, 768)),
+                            "normal", 1e-3, 60.0, noise_std=1.0),
+}
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns.
+    Inputs here are finite, so NaN handling is not needed."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns to float32."""
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _draw(rng: np.random.Generator, shape, dist: str, std: float = 1.0) -> np.ndarray:
+    x = rng.standard_normal(size=shape, dtype=np.float32)
+    if dist == "relu":
+        np.maximum(x, 0.0, out=x)
+    elif dist == "tanh":
+        np.tanh(x, out=x)
+    elif dist != "normal":
+        raise ValueError(dist)
+    if std != 1.0:
+        x *= np.float32(std)
+    return x
+
+
+def _store(x: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "f32":
+        return x
+    if dtype == "bf16":
+        return f32_to_bf16_bits(x)
+    raise ValueError(dtype)
+
+
+def make_layer(rng: np.random.Generator, B: int, spec: LayerSpec, dtype: str,
+               a_dist: str, g_std: float, g_row_scale: np.ndarray | None = None):
+    """Draw one layer's (A, G).  g_row_scale, if given, is a per-example factor on G."""
+    A = _draw(rng, (B, spec.T, spec.d_in), a_dist)
+    G = _draw(rng, (B, spec.T, spec.d_out), "normal", g_std)
+    if g_row_scale is not None:
+        G *= g_row_scale.astype(np.float32)[:, None, None]
+    return _store(A, dtype), _store(G, dtype)
+
+
+def generate(name: str, B: int | None = None, straddle: bool = False,
+             layers: Tuple[int, ...] | None = None):
+    """Return (workload, [(A, G), ...]) for the named configuration.
+
+    B overrides the batch size (used for bounded CPU samples and scaled sweeps).
+    straddle=True multiplies each example's G by (C / typical_norm) times a
+    log-uniform factor in [0.1, 10] so that roughly half of the examples end up
+    below the clipping threshold and both branches of the clip function are
+    exercised.
+    layers selects a subset of layer indices (all layers are still drawn so
+    the random stream of the remaining ones does not change).
+    """
+    w = WORKLOADS[name]
+    B = w.B if B is None else int(B)
+    rng = np.random.default_rng(BASE_SEED + w.index + (1000 if straddle else 0))
+    scale = None
+    if straddle:
+        scale = (w.C / w.typical_norm) * np.exp(rng.uniform(np.log(0.1), np.log(10.0), size=B))
+    out = []
+    for li, spec in enumerate(w.layers):
+        pair = make_layer(rng, B, spec, w.dtype, w.a_dist, w.g_std, scale)
+        if layers is None or li in layers:
+            out.append(pair)
+        else:
+            out.append(None)
+    return w, out
+
+
+def random_layer(seed: int, B: int, T: int, d_in: int, d_out: int, dtype: str,
+                 a_dist: str = "normal", g_std: float = 0.05, g_row_scale=None):
+    """Free-form shapes for edge-case tests (ragged tiles, tiny sizes)."""
+    rng = np.random.default_rng(seed)
+    return make_layer(rng, B, LayerSpec("adhoc", T, d_in, d_out), dtype, a_dist, g_std, g_row_scale)

@@ -1,0 +1,359 @@
+"""Pins for the CPU oracle: each check ties it to something other than itself
+(closed forms, hand-worked numbers, scalar brute force, library routines,
+invariants), chosen so that a dropped term, a wrong sign/index or a transposed
+operand fails at least one of them.  CPU only."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import dp_oracle as orc
+from paper_2009_03106_amd import workloads as wl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _rand(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ---------------------------------------------------------------- hand cases
+def _eval_expr(e):
+    return float(eval(str(e), {"__builtins__": {}}, {"sqrt": math.sqrt}))
+
+
+def test_hand_worked_cases():
+    with open(os.path.join(HERE, "golden", "hand_cases.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        A = np.array(c["A"], dtype=np.float64)
+        G = np.array(c["G"], dtype=np.float64)
+        for i in range(A.shape[0]):
+            np.testing.assert_array_equal(orc.per_example_grad(A[i], G[i]), np.array(c["grad"][i], dtype=np.float64))
+        s = orc.layer_sqnorm(A, G)
+        np.testing.assert_array_equal(s, np.array(c["sqnorm"], dtype=np.float64))
+        np.testing.assert_array_equal(orc.layer_sqnorm_gram(A, G), s)
+        nu = orc.clip_factors(s, c["C"])
+        np.testing.assert_allclose(nu, [_eval_expr(e) for e in c["clip"]], rtol=1e-15)
+        if "clipped_sum" in c:
+            np.testing.assert_allclose(orc.clipped_grad(A, G, nu), np.array(c["clipped_sum"], dtype=np.float64),
+                                       rtol=1e-15, atol=1e-15)
+
+
+# ---------------------------------------------------------------- brute force
+def _brute_sqnorm(A, G):
+    """Scalar loops straight from the entrywise definition
+    g_i[p, q] = sum_t A[i, t, p] * G[i, t, q]."""
+    B, T, di = A.shape
+    do = G.shape[2]
+    out = []
+    for i in range(B):
+        tot = 0.0
+        for p in range(di):
+            for q in range(do):
+                e = 0.0
+                for t in range(T):
+                    e += A[i][t][p] * G[i][t][q]
+                tot += e * e
+        out.append(tot)
+    return np.array(out)
+
+
+@pytest.mark.parametrize("B,T,di,do", [(1, 1, 1, 1), (2, 1, 3, 2), (3, 4, 5, 2), (2, 3, 2, 5), (3, 2, 4, 4)])
+def test_brute_force_tiny(B, T, di, do):
+    A = _rand(10 + B + T, B, T, di)
+    G = _rand(20 + di + do, B, T, do)
+    ref = _brute_sqnorm(A, G)
+    np.testing.assert_allclose(orc.layer_sqnorm(A, G), ref, rtol=1e-12)
+    np.testing.assert_allclose(orc.layer_sqnorm_gram(A, G), ref, rtol=1e-12)
+
+
+def test_brute_force_asymmetric_integers():
+    """Small integers, non-square everything, so a transposed operand or an
+    off-by-one time index changes the exact integer result."""
+    A = np.arange(1, 1 + 2 * 3 * 4, dtype=np.float64).reshape(2, 3, 4) % 7 - 3
+    G = (np.arange(1, 1 + 2 * 3 * 2, dtype=np.float64).reshape(2, 3, 2) * 5) % 11 - 4
+    ref = _brute_sqnorm(A, G)
+    assert np.all(ref == np.round(ref))
+    np.testing.assert_array_equal(orc.layer_sqnorm(A, G), ref)
+    np.testing.assert_array_equal(orc.layer_sqnorm_gram(A, G), ref)
+
+
+# ---------------------------------------------------------------- closed forms
+def test_dense_closed_form_matches_materialised():
+    """Section 4: for one dense layer ||dL/dW||_F^2 = ||dL/dz||^2 ||h||^2."""
+    A = _rand(1, 17, 1, 33)
+    G = _rand(2, 17, 1, 9)
+    np.testing.assert_allclose(orc.layer_sqnorm(A, G), orc.layer_sqnorm_dense_closed_form(A, G), rtol=1e-12)
+    # and the closed form itself against a literal numpy expression of the two vector norms
+    ref = np.linalg.norm(A[:, 0, :], axis=1) ** 2 * np.linalg.norm(G[:, 0, :], axis=1) ** 2
+    np.testing.assert_allclose(orc.layer_sqnorm_dense_closed_form(A, G), ref, rtol=1e-12)
+
+
+def test_gram_equals_direct_random():
+    for seed, (B, T, di, do) in enumerate([(4, 7, 13, 5), (3, 16, 4, 20), (2, 33, 8, 8)]):
+        A = _rand(100 + seed, B, T, di)
+        G = _rand(200 + seed, B, T, do)
+        np.testing.assert_allclose(orc.layer_sqnorm_gram(A, G), orc.layer_sqnorm(A, G), rtol=1e-12)
+
+
+def test_repeated_rows():
+    """All T time steps identical: g = T * outer(a, g), so s = T^2 ||a||^2 ||g||^2."""
+    a = _rand(3, 6)
+    g = _rand(4, 5)
+    T = 7
+    A = np.tile(a, (1, T, 1))
+    G = np.tile(g, (1, T, 1))
+    ref = T * T * np.sum(a * a) * np.sum(g * g)
+    np.testing.assert_allclose(orc.layer_sqnorm(A, G), [ref], rtol=1e-12)
+    np.testing.assert_allclose(orc.layer_sqnorm_gram(A, G), [ref], rtol=1e-12)
+
+
+def test_orthonormal_rows():
+    """If the T rows of A_i are orthonormal then ||A_i^T G_i||_F = ||G_i||_F."""
+    T, di, do = 5, 9, 4
+    Q, _ = np.linalg.qr(_rand(5, di, T))       # di x T with orthonormal columns
+    A = Q.T[None]                              # rows orthonormal
+    G = _rand(6, 1, T, do)
+    np.testing.assert_allclose(orc.layer_sqnorm(A, G), [np.sum(G * G)], rtol=1e-12)
+    np.testing.assert_allclose(orc.layer_sqnorm_gram(A, G), [np.sum(G * G)], rtol=1e-12)
+
+
+def test_scaling_law():
+    A = _rand(7, 3, 4, 6)
+    G = _rand(8, 3, 4, 5)
+    s = orc.layer_sqnorm(A, G)
+    np.testing.assert_allclose(orc.layer_sqnorm(2.5 * A, -0.5 * G), (2.5 * 0.5) ** 2 * s, rtol=1e-12)
+
+
+def test_additivity_over_output_split_and_layers():
+    """A fused projection (e.g. Q, K, V stacked along d_out, Section 5.6) has
+    squared norm equal to the sum over the separate blocks; the whole-model
+    squared norm is the sum over layers (Section 5 preamble)."""
+    A = _rand(9, 4, 6, 8)
+    G = _rand(10, 4, 6, 12)
+    parts = sum(orc.layer_sqnorm(A, G[:, :, 4 * j:4 * j + 4]) for j in range(3))
+    np.testing.assert_allclose(orc.layer_sqnorm(A, G), parts, rtol=1e-12)
+    A2 = _rand(11, 4, 1, 5)
+    G2 = _rand(12, 4, 1, 3)
+    tot = orc.total_sqnorm([(A, G), (A2, G2)])
+    np.testing.assert_allclose(tot, orc.layer_sqnorm(A, G) + orc.layer_sqnorm(A2, G2), rtol=1e-15)
+
+
+def test_per_example_grad_orientation():
+    """g is [d_in, d_out]: entry (p, q) pairs input p with output q."""
+    A = np.zeros((1, 2, 3))
+    G = np.zeros((1, 2, 4))
+    A[0, 1, 2] = 2.0
+    G[0, 1, 3] = 5.0
+    g = orc.per_example_grad(A[0], G[0])
+    assert g.shape == (3, 4)
+    assert g[2, 3] == 10.0 and np.count_nonzero(g) == 1
+
+
+# ---------------------------------------------------------------- clipping
+def test_clip_factor_cases():
+    s = np.array([0.0, 0.25, 1.0, 4.0, 100.0])
+    nu = orc.clip_factors(s, 1.0)
+    np.testing.assert_array_equal(nu[:3], [1.0, 1.0, 1.0])      # norm <= C: untouched, incl. zero norm and norm == C
+    np.testing.assert_allclose(nu[3:], [0.5, 0.1], rtol=1e-15)
+    # min(1, C/norm) form of Eq. per_example_weight agrees with the max form of the clip function
+    n = np.sqrt(s[1:])
+    np.testing.assert_allclose(orc.clip_factors(s[1:], 0.7), np.minimum(1.0, 0.7 / n), rtol=1e-15)
+
+
+def test_clip_invariant_and_materialised_clip():
+    """Every clipped per-example gradient has norm <= C (Section 3.2), and the
+    weighted sum equals the sum of clip_C(g_i) written with the clip function."""
+    rng = np.random.default_rng(13)
+    A = rng.standard_normal((8, 3, 5))
+    G = rng.standard_normal((8, 3, 4)) * np.exp(rng.uniform(-3, 2, size=8))[:, None, None]
+    C = 1.3
+    s = orc.layer_sqnorm(A, G)
+    nu = orc.clip_factors(s, C)
+    assert (nu < 1).any() and (nu == 1).any()
+    for i in range(8):
+        gi = orc.per_example_grad(A[i], G[i]) * nu[i]
+        assert np.linalg.norm(gi) <= C * (1 + 1e-12)
+        if nu[i] < 1:
+            assert abs(np.linalg.norm(gi) - C) <= 1e-12 * C
+    np.testing.assert_allclose(orc.clipped_grad(A, G, nu), orc.clipped_grad_by_clip_function(A, G, C), rtol=1e-12, atol=1e-14)
+
+
+def test_unclipped_reduces_to_batch_gradient():
+    """With every norm below C the result is the ordinary batch gradient
+    X^T dZ, a textbook matrix product."""
+    A = _rand(14, 6, 4, 7)
+    G = _rand(15, 6, 4, 3) * 1e-3
+    s = orc.layer_sqnorm(A, G)
+    nu = orc.clip_factors(s, 10.0)
+    assert np.all(nu == 1.0)
+    ref = A.reshape(-1, 7).T @ G.reshape(-1, 3)
+    np.testing.assert_allclose(orc.clipped_grad(A, G, nu), ref, rtol=1e-12, atol=1e-15)
+    ref2 = np.einsum("btp,btq->pq", A, G)
+    np.testing.assert_allclose(orc.clipped_grad(A, G, nu), ref2, rtol=1e-12, atol=1e-15)
+
+
+def test_single_example_clipped_sum():
+    A = _rand(16, 1, 3, 4)
+    G = _rand(17, 1, 3, 2)
+    np.testing.assert_allclose(orc.clipped_grad(A, G, np.array([0.25])), 0.25 * (A[0].T @ G[0]), rtol=1e-15)
+
+
+def test_multi_layer_global_clip():
+    """Clip factor uses the norm over all layers; clipped whole-model gradient has norm <= C."""
+    L1 = (_rand(18, 5, 1, 6), _rand(19, 5, 1, 4))
+    L2 = (_rand(20, 5, 3, 4), _rand(21, 5, 3, 2))
+    C = 0.9
+    s, c, grads = orc.run_pipeline([L1, L2], C)
+    for i in range(5):
+        g1 = c[i] * orc.per_example_grad(L1[0][i], L1[1][i])
+        g2 = c[i] * orc.per_example_grad(L2[0][i], L2[1][i])
+        assert math.sqrt(np.sum(g1 * g1) + np.sum(g2 * g2)) <= C * (1 + 1e-12)
+    other = orc.layer_sqnorm(*L2)
+    np.testing.assert_allclose(grads[0], orc.clipped_grad_by_clip_function(L1[0], L1[1], C, other), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- storage widening
+def test_bf16_widening_exact():
+    x = np.array([1.0, -2.5, 0.15625, 3.0e-5, 1e20], dtype=np.float32)
+    bits = wl.f32_to_bf16_bits(x)
+    back = orc.widen(bits)
+    # bf16 keeps 8 significant bits: relative error <= 2^-9, and exactly representable values survive
+    assert back[0] == 1.0 and back[1] == -2.5 and back[2] == 0.15625
+    assert np.all(np.abs(back - x.astype(np.float64)) <= np.abs(x) * 2.0 ** -8)
+    np.testing.assert_array_equal(back, wl.bf16_bits_to_f32(bits).astype(np.float64))
+
+
+def test_bf16_rounding_ties_to_even():
+    # 1 + 2^-8 lies exactly between bf16 neighbours 1.0 and 1 + 2^-7 -> even mantissa (1.0)
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8], dtype=np.float32)
+    b = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x))
+    assert b[0] == 1.0 and b[1] == np.float32(1.0 + 2.0 ** -6)
+
+
+# ---------------------------------------------------------------- path choice
+def test_choose_path_on_configs():
+    assert orc.choose_path(64, 256, 256) == "gram"        # rnn
+    assert orc.choose_path(1024, 576, 128) == "direct"    # conv
+    for di, do in [(768, 2304), (768, 768), (768, 3072), (3072, 768)]:
+        assert orc.choose_path(512, di, do) == "gram"     # transformer
+    assert orc.choose_path(1, 64, 32) in ("gram", "direct")
+
+
+# ---------------------------------------------------------------- noise
+def test_philox_scalar_equals_vectorised():
+    seed = 0xDEADBEEFCAFEF00D
+    first = (1 << 32) - 3          # crosses the low-word carry
+    w = orc.philox_words(8, seed, first)
+    for q in range(8):
+        ctr = first + q
+        ref = orc.philox4x32_10((ctr & 0xFFFFFFFF, ctr >> 32, 0, 0), (seed & 0xFFFFFFFF, seed >> 32))
+        assert tuple(int(v) for v in w[q]) == ref
+
+
+def test_philox_against_independent_engine(tmp_path):
+    """Independent implementation: ATen's header-only Philox4x32-10 engine
+    (shipped with PyTorch), compiled here and called -- not copied.  Its
+    constructor takes (seed, subsequence, offset) = key, counter words 2-3,
+    counter words 0-1, which is exactly our (seed, 0, counter) mapping."""
+    import ctypes
+    import shutil
+    import subprocess
+    import torch
+    inc = os.path.join(os.path.dirname(torch.__file__), "include")
+    hdr = os.path.join(inc, "ATen", "core", "PhiloxRNGEngine.h")
+    if not os.path.exists(hdr) or shutil.which("g++") is None:
+        pytest.skip("ATen Philox header or g++ not available")
+    src = tmp_path / "aten_philox_probe.cpp"
+    src.write_text(
+        "#include <ATen/core/PhiloxRNGEngine.h>\n#include <cstdint>\n"
+        "extern \"C\" void aten_philox_words(uint64_t seed, uint64_t first, int64_t n, uint32_t* out) {\n"
+        "  for (int64_t q = 0; q < n; ++q) { at::Philox4_32 e(seed, 0, first + (uint64_t)q);\n"
+        "    for (int r = 0; r < 4; ++r) out[4*q + r] = e(); } }\n")
+    so = tmp_path / "aten_philox_probe.so"
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", "-I", inc, str(src), "-o", str(so)])
+    lib = ctypes.CDLL(str(so))
+    for seed, first in [(0, 0), (1, 0), (0x0123456789ABCDEF, 12345), (0xFFFFFFFFFFFFFFFF, (1 << 32) - 100),
+                        (20090310, (1 << 40) + 7)]:
+        n = 300
+        out = np.zeros(4 * n, dtype=np.uint32)
+        lib.aten_philox_words(ctypes.c_uint64(seed), ctypes.c_uint64(first), ctypes.c_int64(n),
+                              out.ctypes.data_as(ctypes.c_void_p))
+        np.testing.assert_array_equal(orc.philox_words(n, seed, first).reshape(-1), out)
+
+
+def test_philox_distinct_counters_distinct_outputs():
+    w = orc.philox_words(200000, 42, 0)
+    packed = w.view(np.dtype((np.void, 16))).reshape(-1)
+    assert np.unique(packed).size == w.shape[0]
+    # bits look uniform: each of the 32 bit positions is set about half the time
+    bits = np.unpackbits(w.view(np.uint8)).mean()
+    assert abs(bits - 0.5) < 1e-3
+
+
+def test_normals_moments_and_ks():
+    from scipy import stats
+    n = 2_000_000
+    z = orc.standard_normals(n, seed=7, offset=0)
+    assert abs(z.mean()) < 4.0 / math.sqrt(n)
+    assert abs(z.var() - 1.0) < 5e-3
+    assert abs(stats.kurtosis(z, fisher=False) - 3.0) < 2e-2
+    assert abs(stats.skew(z)) < 1e-2
+    assert stats.kstest(z[:200000], "norm").pvalue > 1e-3
+    # slots are uncorrelated with each other (cos/sin pairing and word pairing)
+    zz = z.reshape(-1, 4)
+    c = np.corrcoef(zz.T)
+    assert np.max(np.abs(c - np.eye(4))) < 5e-3
+    assert np.max(np.abs(z)) <= math.sqrt(-2.0 * math.log(2.0 ** -24)) + 1e-12
+
+
+def test_normals_box_muller_structure():
+    """Slots 0/1 of one counter share a radius: z0^2 + z1^2 = -2 ln u_a with
+    u_a from the top 23 bits of word 0, and atan2 recovers u_b from word 1."""
+    seed, q = 99, 12345
+    w = orc.philox4x32_10((q, 0, 0, 0), (seed, 0))
+    z = orc.standard_normals(4, seed, 4 * q)
+    ua = ((w[0] >> 9) + 0.5) / 2 ** 23
+    ub = ((w[1] >> 9) + 0.5) / 2 ** 23
+    assert abs(z[0] ** 2 + z[1] ** 2 - (-2 * math.log(ua))) < 1e-12
+    ang = math.atan2(z[1], z[0]) % (2 * math.pi)
+    assert abs(ang - 2 * math.pi * ub) < 1e-9
+    ua2 = ((w[2] >> 9) + 0.5) / 2 ** 23
+    assert abs(z[2] ** 2 + z[3] ** 2 - (-2 * math.log(ua2))) < 1e-12
+
+
+def test_noise_offset_continuity():
+    a = orc.standard_normals(50, 5, 0)
+    for k in (1, 2, 3, 4, 7, 13):
+        b = orc.standard_normals(50 - k, 5, k)
+        np.testing.assert_array_equal(b, a[k:])
+    g = np.ones((3, 4))
+    out = orc.add_noise(g, 2.0, 5, 8)
+    np.testing.assert_array_equal(out, 1.0 + 2.0 * orc.standard_normals(12, 5, 8).reshape(3, 4))
+
+
+# ---------------------------------------------------------------- workloads
+def test_workload_shapes_and_determinism():
+    w, layers = wl.generate("mlp", B=4)
+    assert [a.shape for a, _ in layers] == [(4, 1, 784), (4, 1, 512), (4, 1, 256)]
+    assert [g.shape for _, g in layers] == [(4, 1, 512), (4, 1, 256), (4, 1, 10)]
+    _, again = wl.generate("mlp", B=4)
+    for (a, g), (a2, g2) in zip(layers, again):
+        np.testing.assert_array_equal(a, a2)
+        np.testing.assert_array_equal(g, g2)
+    assert (layers[0][0] == 0).mean() > 0.4          # post-ReLU: about half zeros
+    w, layers = wl.generate("rnn", B=2)
+    assert layers[0][0].dtype == np.uint16 and layers[0][0].shape == (2, 64, 256)
+    assert np.abs(orc.widen(layers[0][0])).max() <= 1.0     # tanh range
+
+
+def test_straddle_variant_clips_about_half():
+    for name in ("dense", "mlp", "rnn"):
+        w, layers = wl.generate(name, straddle=True)
+        s = orc.total_sqnorm(layers)
+        c = orc.clip_factors(s, w.C)
+        frac = (c < 1).mean()
+        assert 0.2 < frac < 0.8, (name, frac)
