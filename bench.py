@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-example clipping hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch of the chosen
+configuration: squared norms of every layer (accumulated over layers), clip
+factors, the clipped gradient sum of every layer, and Gaussian noise where the
+configuration asks for it.  Inputs are resident in HBM before timing starts.
+
+Prints ONE JSON line (see README/DESIGN for the fields).  Only one GPU is
+supported: --gpus above 1 exits with a message.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def to_dev(x, torch):
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x).cuda()
+
+
+class Pipeline:
+    """Device buffers and the call sequence for one configuration; nothing is allocated inside step()."""
+
+    def __init__(self, w, layers_np, torch, dp, path="auto"):
+        self.w, self.torch, self.dp, self.path = w, torch, dp, path
+        self.dev = [(to_dev(A, torch), to_dev(G, torch)) for A, G in layers_np]
+        self.B = self.dev[0][0].shape[0]
+        dt = dp.DP_BF16 if w.dtype == "bf16" else dp.DP_F32
+        self.s = torch.zeros(self.B, dtype=torch.float32, device="cuda")
+        self.c = torch.zeros(self.B, dtype=torch.float32, device="cuda")
+        self.grads, self.ws_sq, self.ws_cg = [], [], []
+        for spec in w.layers:
+            self.grads.append(torch.zeros((spec.d_in, spec.d_out), dtype=torch.float32, device="cuda"))
+            n1 = dp.workspace_bytes(dp.DP_OP_SQNORM, self.B, spec.T, spec.d_in, spec.d_out, dt, path)
+            n2 = dp.workspace_bytes(dp.DP_OP_CLIPPED_GRAD, self.B, spec.T, spec.d_in, spec.d_out, dt)
+            self.ws_sq.append(torch.empty(max(n1, 16), dtype=torch.uint8, device="cuda"))
+            self.ws_cg.append(torch.empty(max(n2, 16), dtype=torch.uint8, device="cuda"))
+
+    def phase_sqnorm(self):
+        for li, (A, G) in enumerate(self.dev):
+            self.dp.layer_sqnorm(A, G, self.s, path=self.path, accumulate=li > 0, workspace=self.ws_sq[li])
+
+    def phase_clip(self):
+        self.dp.clip_factors(self.s, self.w.C, self.c)
+
+    def phase_grad(self):
+        for li, (A, G) in enumerate(self.dev):
+            self.dp.clipped_grad(A, G, self.c, self.grads[li], workspace=self.ws_cg[li])
+
+    def phase_noise(self):
+        if self.w.noise_std > 0:
+            off = 0
+            for g in self.grads:
+                self.dp.add_noise(g, self.w.noise_std, self.w.noise_seed, off)
+                off += g.numel()
+
+    def step(self, events=None):
+        if events is not None:
+            events[0].record()
+        self.phase_sqnorm()
+        if events is not None:
+            events[1].record()
+        self.phase_clip()
+        if events is not None:
+            events[2].record()
+        self.phase_grad()
+        if events is not None:
+            events[3].record()
+        self.phase_noise()
+        if events is not None:
+            events[4].record()
+
+
+def algorithmic_work(w, B):
+    """Flops and HBM bytes per step that the method itself needs (no re-reads, no scratch)."""
+    es = 2 if w.dtype == "bf16" else 4
+    out = {"norm_flops": 0, "gemm_flops": 0, "norm_bytes": 0, "gemm_bytes": 0, "noise_bytes": 0}
+    for spec in w.layers:
+        T, di, do = spec.T, spec.d_in, spec.d_out
+        if T == 1:
+            out["norm_flops"] += 2 * B * (di + do)
+        else:
+            gram = T * (T + 1) * (di + do)
+            direct = 2 * T * di * do
+            out["norm_flops"] += B * min(gram, direct)
+        out["gemm_flops"] += 2 * B * T * di * do
+        out["norm_bytes"] += B * T * (di + do) * es + 4 * B
+        out["gemm_bytes"] += B * T * (di + do) * es + 4 * di * do
+        if w.noise_std > 0:
+            out["noise_bytes"] += 8 * di * do
+    return out
+
+
+def time_steps(pipe, torch, steps, warmup):
+    for _ in range(warmup):
+        pipe.step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        pipe.step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    phases = np.zeros(4)
+    for k in range(steps):
+        for p in range(4):
+            phases[p] += evs[k][p].elapsed_time(evs[k][p + 1])
+    return (t1 - t0) * 1e3 / steps, phases / steps      # ms per step, ms per phase
+
+
+def cpu_baseline(name, sample_B):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    from oracle import dp_oracle as orc
+    from paper_2009_03106_amd import workloads as wl
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    w, layers = wl.generate(name, B=sample_B)
+    t0 = time.perf_counter()
+    orc.run_pipeline(layers, w.C, w.noise_std, w.noise_seed)
+    dt = time.perf_counter() - t0
+    return {"value": sample_B / dt, "unit": "examples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{name} configuration with B={sample_B} of {w.B} examples, all layers, float64, "
+                      f"{dt:.2f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="transformer")
+    ap.add_argument("--path", default="auto", choices=["auto", "gram", "direct"])
+    ap.add_argument("--batch", type=int, default=None, help="override the configuration's batch size (sweeps)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2009_03106_amd import dpclip as dp, workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dp.load_library()
+
+    w, layers = wl.generate(args.workload, B=args.batch)
+    pipe = Pipeline(w, layers, torch, dp, args.path)
+    del layers
+    B = pipe.B
+    ms, phases = time_steps(pipe, torch, args.steps, args.warmup)
+    work = algorithmic_work(w, B)
+
+    # dominant kernel = the phase that takes the most time
+    norm_ms, clip_ms, grad_ms, noise_ms = phases
+    nlayers = len(w.layers)
+    if grad_ms >= norm_ms:
+        flops, byts, dur_ms, kname = work["gemm_flops"], work["gemm_bytes"], grad_ms, "clipped-sum GEMM (dp_clipped_grad)"
+    else:
+        flops, byts, dur_ms, kname = work["norm_flops"], work["norm_bytes"], norm_ms, "squared-norm kernel (dp_layer_sqnorm)"
+    peak_tf = PEAK_MFMA_TFLOPS[w.dtype]
+    ai = flops / max(byts, 1)
+    if ai >= peak_tf * 1e12 / (PEAK_HBM_GBS * 1e9):
+        ach = flops / (dur_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach / peak_tf}
+    else:
+        ach = byts / (dur_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+    roof.update({"traffic": None, "kernel": kname, "launches_per_step": nlayers,
+                 "avg_launch_ms": dur_ms / nlayers,
+                 "algorithmic_flops_per_step": flops, "algorithmic_bytes_per_step": byts})
+
+    phases_out = {
+        "sqnorm_ms": norm_ms, "clip_ms": clip_ms, "clipped_grad_ms": grad_ms, "noise_ms": noise_ms,
+        "sqnorm_tflops": work["norm_flops"] / (norm_ms * 1e-3) / 1e12,
+        "sqnorm_gbs": work["norm_bytes"] / (norm_ms * 1e-3) / 1e9,
+        "clipped_grad_tflops": work["gemm_flops"] / (grad_ms * 1e-3) / 1e12,
+        "clipped_grad_gbs": work["gemm_bytes"] / (grad_ms * 1e-3) / 1e9,
+    }
+    if noise_ms > 0 and work["noise_bytes"]:
+        phases_out["noise_gbs"] = work["noise_bytes"] / (noise_ms * 1e-3) / 1e9
+
+    others = {}
+    if not args.no_others and args.batch is None:
+        for name in wl.WORKLOADS:
+            if name == args.workload:
+                continue
+            w2, l2 = wl.generate(name)
+            p2 = Pipeline(w2, l2, torch, dp, "auto")
+            ms2, ph2 = time_steps(p2, torch, 50, 5)
+            wk2 = algorithmic_work(w2, p2.B)
+            others[name] = {"examples_per_s": p2.B / (ms2 * 1e-3), "ms_per_step": ms2,
+                            "sqnorm_ms": ph2[0], "clipped_grad_ms": ph2[2],
+                            "sqnorm_gbs": wk2["norm_bytes"] / (ph2[0] * 1e-3) / 1e9,
+                            "sqnorm_tflops": wk2["norm_flops"] / (ph2[0] * 1e-3) / 1e12,
+                            "clipped_grad_tflops": wk2["gemm_flops"] / (ph2[2] * 1e-3) / 1e12,
+                            "clipped_grad_gbs": wk2["gemm_bytes"] / (ph2[2] * 1e-3) / 1e9}
+            del p2, l2
+
+    out = {
+        "metric": "examples/sec for norm+clip+clipped-sum per layer",
+        "value": B / (ms * 1e-3), "unit": "examples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={B}, " + ", ".join(f"{s.name} T={s.T} {s.d_in}->{s.d_out}" for s in w.layers)
+                   + f", C={w.C}" + (f", noise std={w.noise_std}" if w.noise_std > 0 else ""),
+                   "path": args.path, "parallelism": "single GPU"},
+        "roofline": roof, "phases": phases_out, "other_workloads": others,
+    }
+    if not args.no_cpu_baseline:
+        sample = {"transformer": 32, "conv": 128, "rnn": 128, "mlp": 256, "dense": 32}[w.name]
+        out["cpu_baseline"] = cpu_baseline(w.name, min(sample, B))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

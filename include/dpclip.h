@@ -1,0 +1,147 @@
+/*
+ * dpclip -- per-example gradient norms, clip factors and clipped gradient sums
+ * for differentially private training, on one AMD MI355X (gfx950).
+ *
+ * The calls follow the problem statement of Lee & Kifer, "Scaling up
+ * Differentially Private Deep Learning with Fast Per-Example Gradient
+ * Clipping": for every layer only its mini-batch inputs X^(l) and the
+ * gradients with respect to its pre-activations dLoss/dZ^(l) are needed
+ * (Section 5, last paragraph before 5.1).  Here
+ *     A[B, T, d_in]   layer inputs   (T = 1 dense; sequence length for a
+ *                     recurrent / attention projection; number of output
+ *                     positions for an unfolded convolution, Algorithm 3)
+ *     G[B, T, d_out]  per-example pre-activation gradients, position-major
+ * and example i's weight gradient is g_i = A_i^T G_i (Eq. grad_linear_layer,
+ * Eq. recurrent_gradient, Algorithm 3, Section 5.6), which is never written
+ * to memory by this library.
+ *
+ * Conventions for every entry point
+ *  - All data pointers are DEVICE pointers owned by the caller, contiguous,
+ *    row-major and 16-byte aligned.  The library never allocates, frees or
+ *    synchronises.  Scratch space is passed in as `workspace`.
+ *  - Every call is asynchronous on `hip_stream` (a hipStream_t passed as
+ *    void*; NULL is the default stream).  Results are valid once the caller
+ *    has synchronised that stream.
+ *  - Errors come back as dp_status; on any error nothing is launched and the
+ *    outputs are untouched.  Negative sizes, NULL required pointers, C <= 0,
+ *    stddev < 0 or unknown enum values give DP_ERR_INVALID_ARG.  B*T must be
+ *    below 2^31 and d_in, d_out below 2^24, else DP_ERR_UNSUPPORTED.
+ *  - A zero B, T, d_in or d_out is a valid empty problem: DP_OK, and with
+ *    accumulate == 0 the output is zero-filled.
+ *  - NaN / Inf inputs are not detected; they propagate into the outputs.
+ *  - Results are bit-reproducible for fixed inputs, sizes and build: all
+ *    reductions run in a fixed order and no floating-point atomics are used.
+ *  - bf16 inputs are the upper 16 bits of an IEEE float32; all accumulation
+ *    and all outputs are float32.
+ */
+#ifndef DPCLIP_H
+#define DPCLIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DP_OK = 0,
+    DP_ERR_INVALID_ARG = 1,
+    DP_ERR_UNSUPPORTED = 2,
+    DP_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than dp_workspace_bytes() */
+    DP_ERR_HIP = 4          /* a kernel launch failed; hipGetLastError() has the cause */
+} dp_status;
+
+typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
+
+/* How dp_layer_sqnorm evaluates ||A_i^T G_i||_F^2 when T > 1.
+ *   DIRECT: a tile of g_i = sum_t outer(A_i[t], G_i[t]) is accumulated in
+ *           registers, squared and reduced (Algorithm 3 / Algorithm 4 without
+ *           storing their output).           2*T*d_in*d_out flops per example.
+ *   GRAM:   sum_{t,s} (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}, an identity of the
+ *           Frobenius norm; T x T tiles stay on chip and only t <= s tiles are
+ *           formed.                          T*(T+1)*(d_in+d_out) flops.
+ *   AUTO:   GRAM iff its flop count is strictly smaller (dp_choose_path). */
+typedef enum { DP_PATH_AUTO = 0, DP_PATH_GRAM = 1, DP_PATH_DIRECT = 2 } dp_path;
+
+typedef enum { DP_OP_SQNORM = 0, DP_OP_CLIPPED_GRAD = 1 } dp_op;
+
+/* Squared per-example gradient norms of one layer (Section 4 for T = 1;
+ * Sections 5.2-5.6 otherwise):
+ *     sqnorm[i]  =  (accumulate ? sqnorm[i] : 0) + ||A_i^T G_i||_F^2,  i in [0, B).
+ * T == 1 always uses the closed form ||A_i||^2 ||G_i||^2 and ignores `path`.
+ * Summing over the layers of a model (accumulate = 0 for the first layer, 1
+ * for the rest) gives the squared norm of the whole parameter gradient
+ * (Section 5, paragraph before 5.1; weights only).
+ *   A, G       device, [B,T,d_in] and [B,T,d_out] of `dtype`, read only
+ *   sqnorm     device, float32[B], written (read first if accumulate)
+ *   workspace  device scratch of at least dp_workspace_bytes(DP_OP_SQNORM, ...)
+ *              bytes; may be NULL when that size is 0 (T == 1)
+ * DP_PATH_GRAM with DP_F32 inputs is DP_ERR_UNSUPPORTED (AUTO then takes DIRECT). */
+dp_status dp_layer_sqnorm(const void* A, const void* G,
+                          int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                          dp_dtype dtype, dp_path path, int accumulate,
+                          float* sqnorm, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/* Clip factors (Algorithm 1, the line defining nu_i; Eq. per_example_weight;
+ * clip function of Section 3.2):
+ *     clip[i] = 1 / max(1, sqrt(sqnorm[i]) / C)  =  min(1, C / ||g_i||),
+ * so a zero norm and a norm equal to C both give exactly 1.
+ *   sqnorm  device float32[B], read only;  clip  device float32[B], written
+ *   (clip may alias sqnorm).  C must be > 0. */
+dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C,
+                          float* clip, void* hip_stream);
+
+/* Clipped batch gradient of one layer (gradient of the re-weighted loss,
+ * Eq. weighted_loss, without the 1/tau factor):
+ *     grad  =  (accumulate ? grad : 0) + sum_i clip[i] * A_i^T G_i
+ * as one GEMM over K = B*T rows with clip[i] folded into the rows of A.
+ *   grad       device float32[d_in, d_out] row-major
+ *   clip       device float32[B]
+ *   workspace  device scratch of at least
+ *              dp_workspace_bytes(DP_OP_CLIPPED_GRAD, ...) bytes
+ * With bf16 inputs clip[i]*A is rounded back to bf16 before the matrix
+ * multiply (relative error 2^-9 per element, unbiased). */
+dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
+                          int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                          dp_dtype dtype, int accumulate, float* grad,
+                          void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/* Gaussian mechanism (Section 2, Gaussian-mechanism lemma; Algorithm 1, the
+ * update line): grad[j] += stddev * z[offset + j], j in [0, n), with z an
+ * i.i.d. N(0,1) stream that is a pure function of (seed, element index):
+ *   element e uses Philox4x32-10 with key = (lo32(seed), hi32(seed)) and
+ *   counter = (lo32(e>>2), hi32(e>>2), 0, 0); output words (w0,w1) feed slots
+ *   e&3 = 0,1 and (w2,w3) feed slots 2,3 through Box-Muller with
+ *   u = ((w >> 9) + 0.5) * 2^-23:  r = sqrt(-2 ln u_a),
+ *   z_even = r cos(2 pi u_b), z_odd = r sin(2 pi u_b).
+ * Layers of one model use disjoint ranges: offset_l = sum of earlier n.
+ * Resuming a run needs only (seed, offset).  stddev is absolute (sigma, not a
+ * multiple of C). */
+dp_status dp_add_noise(float* grad, int64_t n, float stddev,
+                       uint64_t seed, uint64_t offset, void* hip_stream);
+
+/* Scratch bytes needed by dp_layer_sqnorm (op = DP_OP_SQNORM, for the path
+ * that `path` resolves to) or dp_clipped_grad (op = DP_OP_CLIPPED_GRAD; `path`
+ * ignored).  Returns 0 for invalid arguments. */
+size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                          dp_dtype dtype, dp_path path);
+
+/* The AUTO rule: DP_PATH_GRAM iff T*(T+1)*(d_in+d_out) < 2*T*d_in*d_out,
+ * else DP_PATH_DIRECT (a tie goes to DIRECT). */
+dp_path dp_choose_path(int64_t T, int64_t d_in, int64_t d_out);
+
+/* Static, never-NULL description of a status code. */
+const char* dp_status_string(dp_status status);
+
+/* Test hook: raw Philox words.  out[4*q + r] = word r of the block with
+ * counter first_counter + q, q in [0, n_counters).  out is a device pointer. */
+dp_status dp_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed,
+                        uint64_t first_counter, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPCLIP_H */

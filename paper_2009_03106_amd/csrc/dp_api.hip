@@ -1,0 +1,188 @@
+// C-ABI entry points declared in include/dpclip.h: argument checks, path
+// choice, workspace carving and kernel launches.  No allocation, no
+// synchronisation, no host reads of device memory.
+#include "../../include/dpclip.h"
+#include "dp_internal.h"
+
+using namespace dpk;
+
+namespace {
+
+constexpr int64_t kMaxRows = (int64_t(1) << 31) - 1;   // B*T
+constexpr int64_t kMaxDim = int64_t(1) << 24;          // d_in, d_out
+
+bool valid_dtype(dp_dtype d) { return d == DP_F32 || d == DP_BF16; }
+bool valid_path(dp_path p) { return p == DP_PATH_AUTO || p == DP_PATH_GRAM || p == DP_PATH_DIRECT; }
+
+dp_status check_dims(int64_t B, int64_t T, int64_t d_in, int64_t d_out) {
+    if (B < 0 || T < 0 || d_in < 0 || d_out < 0) return DP_ERR_INVALID_ARG;
+    if (d_in >= kMaxDim || d_out >= kMaxDim) return DP_ERR_UNSUPPORTED;
+    if (B > kMaxRows || T > kMaxRows) return DP_ERR_UNSUPPORTED;
+    if (B > 0 && T > 0 && B > kMaxRows / T) return DP_ERR_UNSUPPORTED;
+    return DP_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+dp_path resolve_path(dp_path path, dp_dtype dtype, int64_t T, int64_t d_in, int64_t d_out) {
+    if (path != DP_PATH_AUTO) return path;
+    if (dtype == DP_F32) return DP_PATH_DIRECT;
+    return dp_choose_path(T, d_in, d_out);
+}
+
+// bytes of scratch for the squared-norm call on an already resolved path (T > 1)
+size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
+    if (path == DP_PATH_GRAM) {
+        GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
+        return (size_t)B * g.npairs * sizeof(float);
+    }
+    TnPlan p = (dtype == DP_BF16) ? plan_direct_bf16((int)T, (int)d_in, (int)d_out)
+                                  : plan_direct_f32((int)T, (int)d_in, (int)d_out);
+    return (size_t)B * p.tiles_m * p.tiles_n * sizeof(float);
+}
+
+size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
+    TnPlan p = (dtype == DP_BF16) ? plan_clipped_bf16(B * T, (int)d_in, (int)d_out)
+                                  : plan_clipped_f32(B * T, (int)d_in, (int)d_out);
+    if (p.splits <= 1) return 0;
+    return (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dp_status_string(dp_status s) {
+    switch (s) {
+        case DP_OK: return "ok";
+        case DP_ERR_INVALID_ARG: return "invalid argument";
+        case DP_ERR_UNSUPPORTED: return "unsupported size, dtype or path";
+        case DP_ERR_WORKSPACE: return "workspace missing or too small";
+        case DP_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+dp_path dp_choose_path(int64_t T, int64_t d_in, int64_t d_out) {
+    if (T <= 0 || d_in <= 0 || d_out <= 0) return DP_PATH_DIRECT;
+    // T*(T+1)*(d_in+d_out) < 2*T*d_in*d_out  <=>  (T+1)*(d_in+d_out) < 2*d_in*d_out ; values stay below 2^57
+    const int64_t gram = (T + 1) * (d_in + d_out);
+    const int64_t direct = 2 * d_in * d_out;
+    return gram < direct ? DP_PATH_GRAM : DP_PATH_DIRECT;
+}
+
+size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
+    if (check_dims(B, T, d_in, d_out) != DP_OK || !valid_dtype(dtype) || !valid_path(path)) return 0;
+    if (B == 0 || T == 0 || d_in == 0 || d_out == 0) return 0;
+    if (op == DP_OP_SQNORM) {
+        if (T == 1) return 0;
+        const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
+        if (p == DP_PATH_GRAM && dtype != DP_BF16) return 0;
+        return sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
+    }
+    if (op == DP_OP_CLIPPED_GRAD) return clipped_ws_bytes(B, T, d_in, d_out, dtype);
+    return 0;
+}
+
+dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                          dp_dtype dtype, dp_path path, int accumulate, float* sqnorm,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+    dp_status st = check_dims(B, T, d_in, d_out);
+    if (st != DP_OK) return st;
+    if (!valid_dtype(dtype) || !valid_path(path)) return DP_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (B == 0) return DP_OK;
+    if (!sqnorm) return DP_ERR_INVALID_ARG;
+    if (T == 0 || d_in == 0 || d_out == 0) {
+        if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (!A || !G || !aligned16(A) || !aligned16(G)) return DP_ERR_INVALID_ARG;
+
+    hipError_t e;
+    if (T == 1) {
+        e = launch_sqnorm_dense(A, G, (int)B, (int)d_in, (int)d_out, dtype == DP_BF16, accumulate != 0, sqnorm, stream);
+        return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+    }
+    const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
+    if (p == DP_PATH_GRAM && dtype != DP_BF16) return DP_ERR_UNSUPPORTED;
+    const size_t need = sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
+    if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;           // > 2^31 partial sums
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
+    float* partial = static_cast<float*>(workspace);
+
+    if (p == DP_PATH_GRAM) {
+        GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
+        e = launch_gram_bf16(g, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
+                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
+    } else if (dtype == DP_BF16) {
+        TnPlan t = plan_direct_bf16((int)T, (int)d_in, (int)d_out);
+        e = launch_direct_bf16(t, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
+                               (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
+    } else {
+        TnPlan t = plan_direct_f32((int)T, (int)d_in, (int)d_out);
+        e = launch_direct_f32(t, static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
+                              (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
+    }
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C, float* clip, void* hip_stream) {
+    if (B < 0 || !(C > 0.0f)) return DP_ERR_INVALID_ARG;
+    if (B > kMaxRows) return DP_ERR_UNSUPPORTED;
+    if (B == 0) return DP_OK;
+    if (!sqnorm || !clip) return DP_ERR_INVALID_ARG;
+    hipError_t e = launch_clip_factors(sqnorm, (int)B, C, clip, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_clipped_grad(const void* A, const void* G, const float* clip, int64_t B, int64_t T, int64_t d_in,
+                          int64_t d_out, dp_dtype dtype, int accumulate, float* grad, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    dp_status st = check_dims(B, T, d_in, d_out);
+    if (st != DP_OK) return st;
+    if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (d_in == 0 || d_out == 0) return DP_OK;
+    if (!grad || !aligned16(grad)) return DP_ERR_INVALID_ARG;
+    if (B == 0 || T == 0) {
+        if (!accumulate && launch_fill_zero(grad, d_in * d_out, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (!A || !G || !clip || !aligned16(A) || !aligned16(G)) return DP_ERR_INVALID_ARG;
+    const size_t need = clipped_ws_bytes(B, T, d_in, d_out, dtype);
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
+    float* ws = static_cast<float*>(workspace);
+
+    hipError_t e;
+    if (dtype == DP_BF16) {
+        TnPlan p = plan_clipped_bf16(B * T, (int)d_in, (int)d_out);
+        e = launch_clipped_bf16(p, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), clip, (int)B, (int)T,
+                                (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream);
+    } else {
+        TnPlan p = plan_clipped_f32(B * T, (int)d_in, (int)d_out);
+        e = launch_clipped_f32(p, static_cast<const float*>(A), static_cast<const float*>(G), clip, (int)B, (int)T,
+                               (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream);
+    }
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, void* hip_stream) {
+    if (n < 0 || !(stddev >= 0.0f)) return DP_ERR_INVALID_ARG;
+    if (n == 0) return DP_OK;
+    if (!grad) return DP_ERR_INVALID_ARG;
+    if (offset > ~uint64_t(0) - (uint64_t)n) return DP_ERR_INVALID_ARG;    // offset + n must not wrap
+    if (stddev == 0.0f) return DP_OK;
+    hipError_t e = launch_add_noise(grad, n, stddev, seed, offset, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64_t first_counter, void* hip_stream) {
+    if (n_counters < 0) return DP_ERR_INVALID_ARG;
+    if (n_counters == 0) return DP_OK;
+    if (!out) return DP_ERR_INVALID_ARG;
+    hipError_t e = launch_philox_raw(out, n_counters, seed, first_counter, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,173 @@
+// Gram path for the per-example squared norm (bf16 inputs):
+//     ||A_i^T G_i||_F^2 = sum_{t,s} (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}.
+// One workgroup owns one (example, t-tile, s-tile) with t-tile <= s-tile.  It
+// forms the tile of A_i A_i^T (contraction over d_in) and then the tile of
+// G_i G_i^T (contraction over d_out) in MFMA accumulators that share one
+// register layout, multiplies them lane by lane, and reduces to one float.
+// Off-diagonal tile pairs stand for their mirror image too and are weighted by
+// two.  Nothing of size T x T leaves the chip; the per-pair partial sums are
+// folded per example in a fixed order by a second small kernel.
+//
+// Both Gram products contract over the contiguous axis of their operand, so
+// the 16-byte global pieces are already what an MFMA lane needs (8 consecutive
+// k for one row): tiles are copied to LDS unchanged (swizzled by row).
+#include "dp_common.h"
+#include "dp_internal.h"
+
+namespace dpk {
+
+namespace {
+
+constexpr int GBK = 64;      // contraction elements per LDS stage
+
+struct GramArgs {
+    const uint16_t* A;
+    const uint16_t* G;
+    float* partial;      // [B][npairs]
+    int T, d_in, d_out;
+    int nt, npairs;
+};
+
+// Rows [row0, row0 + TT) x columns [k0, k0 + 64) of X_i[T, D] -> LDS tile (zero padded).
+template <int TT>
+__device__ __forceinline__ void gram_fetch(const uint16_t* __restrict__ Xi, int T, int D, bool vec_ok,
+                                           int row0, int k0, int tid, uint4 (&st)[TT / 32]) {
+    const int c = tid & 7;
+#pragma unroll
+    for (int it = 0; it < TT / 32; ++it) {
+        const int row = row0 + (tid >> 3) + it * 32;
+        const int col = k0 + c * 8;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (row < T) {
+            const uint16_t* p = Xi + (size_t)row * D;
+            if (vec_ok) {
+                if (col < D) v = *reinterpret_cast<const uint4*>(p + col);
+            } else {
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t e = (col + j < D) ? (uint32_t)p[col + j] : 0u;
+                    w[j >> 1] |= e << ((j & 1) * 16);
+                }
+                v = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        st[it] = v;
+    }
+}
+
+template <int TT>
+__device__ __forceinline__ void gram_commit(unsigned char* lds_tile, int tid, const uint4 (&st)[TT / 32]) {
+    const int c = tid & 7;
+#pragma unroll
+    for (int it = 0; it < TT / 32; ++it) {
+        const int r = (tid >> 3) + it * 32;
+        *reinterpret_cast<uint4*>(lds_tile + lds_off_bytes(r, c)) = st[it];
+    }
+}
+
+// One Gram product tile: acc[i][j] += X[t-tile rows] . X[s-tile rows]^T over D.
+template <int TT>
+__device__ __forceinline__ void gram_product(const uint16_t* __restrict__ Xi, int T, int D, int t0, int s0, bool diag,
+                                             unsigned char* lds, f32x16 (&acc)[TT / 64][TT / 64]) {
+    constexpr int WT = TT / 2;       // rows (and columns) per wave
+    constexpr int NF = WT / 32;      // MFMA tiles per wave per side
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const bool vec_ok = (D & 7) == 0;
+    unsigned char* lds_t = lds;
+    unsigned char* lds_s = diag ? lds : lds + TT * 128;
+
+    uint4 st_t[TT / 32], st_s[TT / 32];
+    gram_fetch<TT>(Xi, T, D, vec_ok, t0, 0, tid, st_t);
+    if (!diag) gram_fetch<TT>(Xi, T, D, vec_ok, s0, 0, tid, st_s);
+    for (int k0 = 0; k0 < D; k0 += GBK) {
+        gram_commit<TT>(lds_t, tid, st_t);
+        if (!diag) gram_commit<TT>(lds_s, tid, st_s);
+        __syncthreads();
+        if (k0 + GBK < D) {
+            gram_fetch<TT>(Xi, T, D, vec_ok, t0, k0 + GBK, tid, st_t);
+            if (!diag) gram_fetch<TT>(Xi, T, D, vec_ok, s0, k0 + GBK, tid, st_s);
+        }
+#pragma unroll
+        for (int ks = 0; ks < GBK / 16; ++ks) {
+            bf16x8 fa[NF], fb[NF];
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8*>(lds_t + lds_off_bytes(wm * WT + i * 32 + lrow, ks * 2 + lhalf));
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8*>(lds_s + lds_off_bytes(wn * WT + j * 32 + lrow, ks * 2 + lhalf));
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+#pragma unroll
+                for (int j = 0; j < NF; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+}
+
+template <int TT>
+__global__ __launch_bounds__(kThreads, 2) void k_gram_bf16(GramArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TT * 128];
+    __shared__ float red[4];
+    constexpr int NF = TT / 64;
+
+    const int ex = blockIdx.x / a.npairs;
+    int pair = blockIdx.x - ex * a.npairs;
+    // pair -> (tt, ss), tt <= ss, rows of the upper triangle in order
+    int tt = 0;
+    while (pair >= a.nt - tt) { pair -= a.nt - tt; ++tt; }
+    const int ss = tt + pair;
+    const bool diag = (tt == ss);
+
+    f32x16 accP[NF][NF], accQ[NF][NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { accP[i][j][r] = 0.f; accQ[i][j][r] = 0.f; }
+
+    gram_product<TT>(a.A + (size_t)ex * a.T * a.d_in, a.T, a.d_in, tt * TT, ss * TT, diag, lds, accP);
+    gram_product<TT>(a.G + (size_t)ex * a.T * a.d_out, a.T, a.d_out, tt * TT, ss * TT, diag, lds, accQ);
+
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NF; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s += accP[i][j][r] * accQ[i][j][r];
+    s = block_sum_256(s, red);
+    if (threadIdx.x == 0) a.partial[blockIdx.x] = diag ? s : 2.0f * s;
+}
+
+}  // namespace
+
+GramPlan plan_gram_bf16(int T, int d_in, int d_out) {
+    (void)d_in; (void)d_out;
+    GramPlan p;
+    p.tile = (T <= 64) ? 64 : 128;
+    p.nt = (T + p.tile - 1) / p.tile;
+    p.npairs = p.nt * (p.nt + 1) / 2;
+    return p;
+}
+
+hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                            bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+    GramArgs a;
+    a.A = A; a.G = G; a.partial = partial;
+    a.T = T; a.d_in = d_in; a.d_out = d_out;
+    a.nt = p.nt; a.npairs = p.npairs;
+    const unsigned grid = (unsigned)((int64_t)B * p.npairs);
+    if (p.tile == 64) k_gram_bf16<64><<<grid, kThreads, 0, st>>>(a);
+    else              k_gram_bf16<128><<<grid, kThreads, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);
+}
+
+}  // namespace dpk

@@ -1,0 +1,58 @@
+// Host-side launcher interface between the C-ABI layer (dp_api.hip) and the
+// kernel translation units.  Every launcher validates nothing: dp_api.hip has
+// already checked sizes and the workspace.  Each returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dpk {
+
+// ---- small elementwise / reduction kernels (dp_small_kernels.hip)
+hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, bool bf16,
+                               bool accumulate, float* sqnorm, hipStream_t st);
+hipError_t launch_finalize_partials(const float* partial, int B, int n_per_example, bool accumulate,
+                                    float* sqnorm, hipStream_t st);
+hipError_t launch_clip_factors(const float* sqnorm, int B, float C, float* clip, hipStream_t st);
+// distance in floats between consecutive split-K slices of an n-element output
+inline int64_t splitk_slice_elems(int64_t n) { return (n + 3) & ~(int64_t)3; }
+hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st);
+hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st);
+hipError_t launch_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64_t first, hipStream_t st);
+
+// ---- K-major ("TN") products  sum_k A[k,:]^T G[k,:]  (dp_tn_bf16.hip, dp_tn_f32.hip)
+struct TnPlan {
+    int tile_m, tile_n;     // block tile
+    int tiles_m, tiles_n;
+    int splits;             // clipped grad: number of K slices; direct sqnorm: unused
+    int kchunk;             // rows of K per slice (multiple of the kernel's BK)
+};
+TnPlan plan_clipped_bf16(int64_t K, int M, int N);
+TnPlan plan_clipped_f32(int64_t K, int M, int N);
+TnPlan plan_direct_bf16(int T, int M, int N);
+TnPlan plan_direct_f32(int T, int M, int N);
+
+// out: splits == 1 -> nullptr workspace allowed and the tile goes straight to `grad` (overwrite
+// or accumulate); otherwise slices go to ws[splits][M][N] and a second kernel folds them.
+hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
+                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
+hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
+                              int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
+// partial[B][tiles_m*tiles_n] then finalize into sqnorm
+hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
+                              bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, int B, int T, int M, int N,
+                             bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+
+// ---- Gram path (dp_gram_bf16.hip)
+struct GramPlan {
+    int tile;     // rows of T per tile
+    int nt;       // tiles along T
+    int npairs;   // nt*(nt+1)/2 upper-triangular tile pairs per example
+};
+GramPlan plan_gram_bf16(int T, int d_in, int d_out);
+hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                            bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+
+}  // namespace dpk

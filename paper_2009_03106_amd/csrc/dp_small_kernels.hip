@@ -1,0 +1,241 @@
+// Bandwidth-bound kernels: dense-layer (T = 1) squared norms, clip factors,
+// fixed-order folds of partial results, zero fill, Philox Gaussian noise.
+#include "dp_common.h"
+#include "dp_internal.h"
+
+namespace dpk {
+
+// ---------------------------------------------------------------------------
+// T = 1: s_i = ||A_i||^2 * ||G_i||^2 (closed form of Section 4).  One wave per
+// example; each lane streams 16-byte pieces of the row, then a wave shuffle
+// reduction.  Rows whose length is not a multiple of the vector width (or
+// whose start is therefore unaligned) take the scalar loop.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float row_sumsq_f32(const float* __restrict__ row, int d, int lane) {
+    float acc = 0.f;
+    if ((d & 3) == 0) {
+        const float4* r4 = reinterpret_cast<const float4*>(row);
+        for (int c = lane; c < (d >> 2); c += kWave) {
+            float4 v = r4[c];
+            acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+    } else {
+        for (int c = lane; c < d; c += kWave) { float v = row[c]; acc += v * v; }
+    }
+    return wave_sum(acc);
+}
+
+__device__ __forceinline__ float row_sumsq_bf16(const uint16_t* __restrict__ row, int d, int lane) {
+    float acc = 0.f;
+    if ((d & 7) == 0) {
+        const uint4* r8 = reinterpret_cast<const uint4*>(row);
+        for (int c = lane; c < (d >> 3); c += kWave) {
+            uint4 v = r8[c];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float lo = bf16_lo(w[j]), hi = bf16_hi(w[j]);
+                acc += lo * lo + hi * hi;
+            }
+        }
+    } else {
+        for (int c = lane; c < d; c += kWave) { float v = bf16_to_f32(row[c]); acc += v * v; }
+    }
+    return wave_sum(acc);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restrict__ A, const void* __restrict__ G,
+                                                           int B, int d_in, int d_out, int accumulate,
+                                                           float* __restrict__ sqnorm) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    if (ex >= B) return;
+    float sa, sg;
+    if (BF16) {
+        sa = row_sumsq_bf16(static_cast<const uint16_t*>(A) + (size_t)ex * d_in, d_in, lane);
+        sg = row_sumsq_bf16(static_cast<const uint16_t*>(G) + (size_t)ex * d_out, d_out, lane);
+    } else {
+        sa = row_sumsq_f32(static_cast<const float*>(A) + (size_t)ex * d_in, d_in, lane);
+        sg = row_sumsq_f32(static_cast<const float*>(G) + (size_t)ex * d_out, d_out, lane);
+    }
+    if (lane == 0) {
+        float s = sa * sg;
+        sqnorm[ex] = accumulate ? sqnorm[ex] + s : s;
+    }
+}
+
+hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, bool bf16,
+                               bool accumulate, float* sqnorm, hipStream_t st) {
+    const int per_block = kThreads / kWave;
+    dim3 grid((B + per_block - 1) / per_block);
+    if (bf16) k_sqnorm_dense<true><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
+    else      k_sqnorm_dense<false><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// s_i (+)= sum_j partial[i][j], j ascending: the fixed-order second stage of
+// the tiled norm kernels.  One thread per example (n is tens at most).
+// ---------------------------------------------------------------------------
+__global__ void k_finalize_partials(const float* __restrict__ partial, int B, int n, int accumulate,
+                                    float* __restrict__ sqnorm) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    const float* p = partial + (size_t)i * n;
+    float s = 0.f;
+    for (int j = 0; j < n; ++j) s += p[j];
+    sqnorm[i] = accumulate ? sqnorm[i] + s : s;
+}
+
+hipError_t launch_finalize_partials(const float* partial, int B, int n, bool accumulate, float* sqnorm, hipStream_t st) {
+    k_finalize_partials<<<(B + 63) / 64, 64, 0, st>>>(partial, B, n, accumulate ? 1 : 0, sqnorm);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// nu_i = 1 / max(1, sqrt(s_i) / C)   (clip function of Section 3.2)
+// ---------------------------------------------------------------------------
+__global__ void k_clip_factors(const float* __restrict__ sqnorm, int B, float C, float* __restrict__ clip) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    const float n = sqrtf(sqnorm[i]);
+    const float m = n / C;
+    clip[i] = 1.0f / (!(m <= 1.0f) ? m : 1.0f);     // max(1, m) that lets a NaN norm through
+}
+
+hipError_t launch_clip_factors(const float* sqnorm, int B, float C, float* clip, hipStream_t st) {
+    k_clip_factors<<<(B + 255) / 256, 256, 0, st>>>(sqnorm, B, C, clip);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// grad[j] (+)= sum_z ws[z][j], z ascending: second stage of the split-K GEMM.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__ ws, int64_t n, int64_t slice, int splits,
+                                                       int accumulate, float* __restrict__ grad) {
+    const int64_t n4 = n >> 2;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < n4; c += stride) {
+        float4 acc = reinterpret_cast<const float4*>(ws)[c];
+        for (int z = 1; z < splits; ++z) {
+            float4 v = reinterpret_cast<const float4*>(ws + (size_t)z * slice)[c];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        float4* o = reinterpret_cast<float4*>(grad) + c;
+        if (accumulate) { float4 g = *o; acc.x += g.x; acc.y += g.y; acc.z += g.z; acc.w += g.w; }
+        *o = acc;
+    }
+    // tail (n not a multiple of 4)
+    for (int64_t j = (n4 << 2) + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) {
+        float acc = ws[j];
+        for (int z = 1; z < splits; ++z) acc += ws[(size_t)z * slice + j];
+        grad[j] = accumulate ? grad[j] + acc : acc;
+    }
+}
+
+hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st) {
+    // slices are spaced splitk_slice_elems(n) apart, a multiple of 4 floats, so each starts 16-byte aligned
+    int64_t blocks = ((n >> 2) + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    k_splitk_reduce<<<(unsigned)blocks, 256, 0, st>>>(ws, n, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad);
+    return hipGetLastError();
+}
+
+__global__ void k_fill_zero(float* __restrict__ p, int64_t n) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) p[j] = 0.f;
+}
+
+hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    k_fill_zero<<<(unsigned)blocks, 256, 0, st>>>(p, n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11) and Box-Muller normals.
+// ---------------------------------------------------------------------------
+struct U4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += W0; k1 += W1;
+    }
+    return U4{c0, c1, c2, c3};
+}
+
+// u = ((w >> 9) + 1/2) / 2^23, exact in float32 and strictly inside (0, 1)
+__device__ __forceinline__ float uniform23(uint32_t w) { return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f; }
+
+__device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float& z_even, float& z_odd) {
+    const float r = sqrtf(-2.0f * logf(uniform23(wa)));
+    float s, c;
+    sincospif(2.0f * uniform23(wb), &s, &c);
+    z_even = r * c;
+    z_odd = r * s;
+}
+
+__global__ __launch_bounds__(256) void k_add_noise(float* __restrict__ grad, int64_t n, float stddev,
+                                                   uint32_t k0, uint32_t k1, uint64_t offset) {
+    const uint64_t q_first = offset >> 2;
+    const uint64_t nq = ((offset + (uint64_t)n - 1) >> 2) - q_first + 1;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t qi = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; qi < nq; qi += stride) {
+        const uint64_t q = q_first + qi;
+        const U4 w = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), 0u, 0u, k0, k1);
+        float z[4];
+        box_muller(w.x, w.y, z[0], z[1]);
+        box_muller(w.z, w.w, z[2], z[3]);
+        const int64_t j0 = (int64_t)(q << 2) - (int64_t)offset;   // index of slot 0 in grad (may be < 0 on the first block)
+        float* p = grad + j0;
+        if (j0 >= 0 && j0 + 3 < n && ((reinterpret_cast<uintptr_t>(p) & 15) == 0)) {
+            float4 g = *reinterpret_cast<float4*>(p);
+            g.x += stddev * z[0]; g.y += stddev * z[1]; g.z += stddev * z[2]; g.w += stddev * z[3];
+            *reinterpret_cast<float4*>(p) = g;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t j = j0 + r;
+                if (j >= 0 && j < n) grad[j] += stddev * z[r];
+            }
+        }
+    }
+}
+
+hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    const uint64_t nq = ((offset + (uint64_t)n - 1) >> 2) - (offset >> 2) + 1;
+    uint64_t blocks = (nq + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    k_add_noise<<<(unsigned)blocks, 256, 0, st>>>(grad, n, stddev, (uint32_t)seed, (uint32_t)(seed >> 32), offset);
+    return hipGetLastError();
+}
+
+__global__ void k_philox_raw(uint32_t* __restrict__ out, int64_t nq, uint32_t k0, uint32_t k1, uint64_t first) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t qi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; qi < nq; qi += stride) {
+        const uint64_t q = first + (uint64_t)qi;
+        const U4 w = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), 0u, 0u, k0, k1);
+        out[4 * qi + 0] = w.x; out[4 * qi + 1] = w.y; out[4 * qi + 2] = w.z; out[4 * qi + 3] = w.w;
+    }
+}
+
+hipError_t launch_philox_raw(uint32_t* out, int64_t nq, uint64_t seed, uint64_t first, hipStream_t st) {
+    if (nq <= 0) return hipSuccess;
+    int64_t blocks = (nq + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    k_philox_raw<<<(unsigned)blocks, 256, 0, st>>>(out, nq, (uint32_t)seed, (uint32_t)(seed >> 32), first);
+    return hipGetLastError();
+}
+
+}  // namespace dpk

@@ -1,0 +1,307 @@
+// bf16 K-major products  P = sum_k A[k, m-tile]^T G[k, n-tile]  on MFMA.
+//
+// Both operands are stored with the contraction index k (example-major rows
+// of the flattened [B*T, d] matrices) as the slow axis, while the MFMA wants
+// each lane to hold 8 consecutive k for one m (or n).  The 16-bit transpose is
+// done in registers on the way from global memory to LDS: a thread loads an
+// 8(k) x 8(col) block as eight 16-byte row pieces, repacks it into eight
+// 16-byte column pieces and stores those.  For the clipped sum the rows of A
+// are multiplied by their example's clip factor in the same step (the values
+// are in float registers anyway for the repack), then rounded back to bf16.
+//
+// Two uses:
+//   * clipped sum (dp_clipped_grad): grid = tiles x K-slices; every slice's
+//     tile goes to the workspace and is folded in a fixed order afterwards.
+//   * direct squared norm (dp_layer_sqnorm, DIRECT): grid = tiles x examples;
+//     K = that example's T rows; the accumulator tile is squared and reduced,
+//     never stored (Algorithm 3 / Algorithm 4 of the paper without their
+//     output tensor).
+#include "dp_common.h"
+#include "dp_internal.h"
+
+namespace dpk {
+
+namespace {
+
+constexpr int BK = 64;           // k rows per LDS stage
+constexpr int BM = 128, BN = 128;
+
+struct TnArgs {
+    const uint16_t* A;
+    const uint16_t* G;
+    const float* clip;     // clipped sum only
+    float* out;            // clipped: slice base [z][M][N] (slice stride `slice`); direct: partial[ex][tiles]
+    int64_t slice;
+    int K;                 // total rows B*T
+    int T;
+    int M, N;
+    int tiles_m, tiles_n;
+    int kchunk;            // clipped: rows per K slice
+    int accumulate;        // clipped with one slice: add to out
+};
+
+// Load an 8(k) x 8(col) block starting at (row0, col0) of X[K, D]; rows >= k_end and
+// columns >= D read as zero.
+__device__ __forceinline__ void load_block(const uint16_t* __restrict__ X, int D, bool vec_ok,
+                                           int row0, int k_end, int col0, uint4 (&r)[8]) {
+    if (vec_ok) {
+        const bool col_ok = col0 < D;     // D % 8 == 0 and col0 % 8 == 0: the piece is all in or all out
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = row0 + i;
+            if (col_ok && row < k_end) r[i] = *reinterpret_cast<const uint4*>(X + (size_t)row * D + col0);
+            else r[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = row0 + i;
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            if (row < k_end) {
+                const uint16_t* p = X + (size_t)row * D;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int col = col0 + j;
+                    const uint32_t v = (col < D) ? (uint32_t)p[col] : 0u;
+                    w[j >> 1] |= v << ((j & 1) * 16);
+                }
+            }
+            r[i] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
+// Repack rows r[0..7] (each 8 columns) into columns c[0..7] (each 8 k values), no scaling.
+__device__ __forceinline__ void transpose8x8(const uint4 (&r)[8], uint4 (&c)[8]) {
+    uint32_t in[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { in[i][0] = r[i].x; in[i][1] = r[i].y; in[i][2] = r[i].z; in[i][3] = r[i].w; }
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t e[4], o[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            e[p] = pack_lo16(in[2 * p][d], in[2 * p + 1][d]);
+            o[p] = pack_hi16(in[2 * p][d], in[2 * p + 1][d]);
+        }
+        c[2 * d] = make_uint4(e[0], e[1], e[2], e[3]);
+        c[2 * d + 1] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+// Same repack with row i multiplied by s[i] in float and rounded to bf16 (nearest even).
+__device__ __forceinline__ void transpose8x8_scaled(const uint4 (&r)[8], const float (&s)[8], uint4 (&c)[8]) {
+    uint32_t in[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { in[i][0] = r[i].x; in[i][1] = r[i].y; in[i][2] = r[i].z; in[i][3] = r[i].w; }
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t e[4], o[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t x = in[2 * p][d], y = in[2 * p + 1][d];
+            e[p] = pack_bf16(bf16_lo(x) * s[2 * p], bf16_lo(y) * s[2 * p + 1]);
+            o[p] = pack_bf16(bf16_hi(x) * s[2 * p], bf16_hi(y) * s[2 * p + 1]);
+        }
+        c[2 * d] = make_uint4(e[0], e[1], e[2], e[3]);
+        c[2 * d + 1] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+// MODE 0: clipped sum (scale A rows, store the tile).  MODE 1: direct squared norm.
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 2) void k_tn_bf16(TnArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BM * 128];   // A^T tile then G^T tile: [col][64 k]
+    __shared__ float red[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = blockIdx.x;
+    const int tm = tile / a.tiles_n, tn = tile % a.tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int z = blockIdx.y;
+    int k_begin, k_end;
+    if (MODE == 0) {
+        k_begin = z * a.kchunk;
+        k_end = min(a.K, k_begin + a.kchunk);
+    } else {
+        k_begin = z * a.T;
+        k_end = k_begin + a.T;
+    }
+
+    // global -> LDS task of this thread: waves 0,1 move A, waves 2,3 move G
+    const int opnd = tid >> 7;
+    const int local = tid & 127;
+    const int cg = local & 15;          // 8-column group inside the 128-column tile
+    const int kc = local >> 4;          // 8-row chunk inside the 64-row stage
+    const uint16_t* X = opnd ? a.G : a.A;
+    const int D = opnd ? a.N : a.M;
+    const int col0 = (opnd ? n0 : m0) + cg * 8;
+    const bool vec_ok = (D & 7) == 0;
+    unsigned char* lds_x = lds + opnd * (BM * 128);
+
+    // MFMA roles: 2 x 2 waves, each owns a 64 x 64 piece made of 2 x 2 MFMA tiles
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    uint4 stage[8];
+    float scl[8];
+    auto fetch = [&](int k0) {
+        const int row0 = k0 + kc * 8;
+        load_block(X, D, vec_ok, row0, k_end, col0, stage);
+        if (MODE == 0 && opnd == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = row0 + i;
+                scl[i] = (row < k_end) ? a.clip[a.T == 1 ? row : row / a.T] : 0.f;
+            }
+        }
+    };
+    auto commit = [&]() {
+        uint4 cols[8];
+        if (MODE == 0 && opnd == 0) transpose8x8_scaled(stage, scl, cols);
+        else transpose8x8(stage, cols);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            *reinterpret_cast<uint4*>(lds_x + lds_off_bytes(cg * 8 + j, kc)) = cols[j];
+    };
+
+    if (k_begin < k_end) fetch(k_begin);
+    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
+        commit();
+        __syncthreads();
+        if (k0 + BK < k_end) fetch(k0 + BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = wm * 64 + i * 32 + lrow;
+                fa[i] = *reinterpret_cast<const bf16x8*>(lds + lds_off_bytes(row, ks * 2 + lhalf));
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int row = wn * 64 + j * 32 + lrow;
+                fb[j] = *reinterpret_cast<const bf16x8*>(lds + BM * 128 + lds_off_bytes(row, ks * 2 + lhalf));
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    if (MODE == 0) {
+        // accumulator element r of lane: row 8*(r/4) + 4*lhalf + r%4, column lrow of the 32 x 32 MFMA tile
+        float* out = a.out + (size_t)z * a.slice;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int n = n0 + wn * 64 + j * 32 + lrow;
+                if (n >= a.N) continue;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                    if (m < a.M) {
+                        float* p = out + (size_t)m * a.N + n;
+                        *p = a.accumulate ? *p + acc[i][j][r] : acc[i][j][r];
+                    }
+                }
+            }
+    } else {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s += acc[i][j][r] * acc[i][j][r];
+        s = block_sum_256(s, red);
+        if (tid == 0) a.out[(size_t)z * (a.tiles_m * a.tiles_n) + tile] = s;
+    }
+}
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+}  // namespace
+
+TnPlan plan_clipped_bf16(int64_t K, int M, int N) {
+    TnPlan p;
+    p.tile_m = BM; p.tile_n = BN;
+    p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    // enough K slices for about two workgroups per compute unit, each at least 4 stages long
+    int64_t want = (512 + tiles - 1) / tiles;
+    int64_t max_splits = (K + 4 * BK - 1) / (4 * BK);
+    if (want > max_splits) want = max_splits;
+    if (want < 1) want = 1;
+    int64_t kchunk = (K + want - 1) / want;
+    kchunk = ((kchunk + BK - 1) / BK) * BK;
+    if (kchunk < BK) kchunk = BK;
+    p.kchunk = (int)kchunk;
+    p.splits = (int)((K + kchunk - 1) / kchunk);
+    if (p.splits < 1) p.splits = 1;
+    return p;
+}
+
+TnPlan plan_direct_bf16(int T, int M, int N) {
+    (void)T;
+    TnPlan p;
+    p.tile_m = BM; p.tile_n = BN;
+    p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
+    p.splits = 1; p.kchunk = 0;
+    return p;
+}
+
+hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
+                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st) {
+    TnArgs a;
+    a.A = A; a.G = G; a.clip = clip;
+    a.K = B * T; a.T = T; a.M = M; a.N = N;
+    a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.kchunk = p.kchunk;
+    const int64_t n = (int64_t)M * N;
+    if (p.splits == 1) {
+        a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0;
+    } else {
+        a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.splits);
+    k_tn_bf16<0><<<grid, kThreads, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.splits == 1) return e;
+    return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
+}
+
+hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
+                              bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+    TnArgs a;
+    a.A = A; a.G = G; a.clip = nullptr;
+    a.K = B * T; a.T = T; a.M = M; a.N = N;
+    a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.kchunk = 0;
+    a.out = partial; a.slice = 0; a.accumulate = 0;
+    const int tiles = p.tiles_m * p.tiles_n;
+    // grid.y is limited to 65535: fold larger batches into several launches
+    for (int b0 = 0; b0 < B; b0 += 65535) {
+        const int nb = (B - b0 < 65535) ? (B - b0) : 65535;
+        TnArgs s = a;
+        s.A = A + (size_t)b0 * T * M;
+        s.G = G + (size_t)b0 * T * N;
+        s.out = partial + (size_t)b0 * tiles;
+        dim3 grid((unsigned)tiles, (unsigned)nb);
+        k_tn_bf16<1><<<grid, kThreads, 0, st>>>(s);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
+}
+
+}  // namespace dpk

@@ -1,0 +1,193 @@
+"""Thin ctypes binding over libdpclip.so (see include/dpclip.h for the contract).
+
+Argument marshalling only: tensors -> device pointers and sizes, the current
+torch stream -> hipStream_t.  Every computation runs in the HIP kernels.  There
+is no CPU fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libdpclip.so")
+
+DP_OK = 0
+DP_ERR_INVALID_ARG, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_HIP = 1, 2, 3, 4
+DP_F32, DP_BF16 = 0, 1
+DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
+DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
+_PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
+
+EXPORTS = ("dp_layer_sqnorm", "dp_clip_factors", "dp_clipped_grad", "dp_add_noise", "dp_workspace_bytes",
+           "dp_choose_path", "dp_status_string", "dp_philox_raw")
+
+_lib = None
+
+
+class DpclipError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (dp_status {status})")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdpclip.so from the package directory; raise if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it first (python -m paper_2009_03106_amd.build); "
+                           "there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, sz, u64, f32, ci = (ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint64,
+                                 ctypes.c_float, ctypes.c_int)
+    lib.dp_layer_sqnorm.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp, sz, vp]
+    lib.dp_layer_sqnorm.restype = ci
+    lib.dp_clip_factors.argtypes = [vp, i64, f32, vp, vp]
+    lib.dp_clip_factors.restype = ci
+    lib.dp_clipped_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
+    lib.dp_clipped_grad.restype = ci
+    lib.dp_add_noise.argtypes = [vp, i64, f32, u64, u64, vp]
+    lib.dp_add_noise.restype = ci
+    lib.dp_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci, ci]
+    lib.dp_workspace_bytes.restype = sz
+    lib.dp_choose_path.argtypes = [i64, i64, i64]
+    lib.dp_choose_path.restype = ci
+    lib.dp_status_string.argtypes = [ci]
+    lib.dp_status_string.restype = ctypes.c_char_p
+    lib.dp_philox_raw.argtypes = [vp, i64, u64, u64, vp]
+    lib.dp_philox_raw.restype = ci
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().dp_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != DP_OK:
+        raise DpclipError(status, where)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DP_F32
+    if t.dtype == torch.bfloat16:
+        return DP_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    return t.data_ptr() if t.numel() > 0 else None
+
+
+def _shape3(A: torch.Tensor, G: torch.Tensor):
+    if A.dim() == 2:
+        A = A.unsqueeze(1)
+    if G.dim() == 2:
+        G = G.unsqueeze(1)
+    if A.dim() != 3 or G.dim() != 3 or A.shape[:2] != G.shape[:2] or A.dtype != G.dtype:
+        raise ValueError("A must be [B,T,d_in] and G [B,T,d_out] of one dtype")
+    B, T, d_in = A.shape
+    return A, G, int(B), int(T), int(d_in), int(G.shape[2])
+
+
+def choose_path(T: int, d_in: int, d_out: int) -> str:
+    code = load_library().dp_choose_path(T, d_in, d_out)
+    return {DP_PATH_GRAM: "gram", DP_PATH_DIRECT: "direct"}[code]
+
+
+def workspace_bytes(op: int, B: int, T: int, d_in: int, d_out: int, dtype: int, path: str = "auto") -> int:
+    return int(load_library().dp_workspace_bytes(op, B, T, d_in, d_out, dtype, _PATHS[path]))
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return workspace
+    if workspace is not None:
+        return workspace
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor] = None, *,
+                 path: str = "auto", accumulate: bool = False, workspace: Optional[torch.Tensor] = None,
+                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """sqnorm[i] (+)= ||A_i^T G_i||_F^2 via dp_layer_sqnorm."""
+    lib = load_library()
+    A, G, B, T, d_in, d_out = _shape3(A, G)
+    dt = _dtype_code(A)
+    if sqnorm is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing sqnorm tensor")
+        sqnorm = torch.empty(B, dtype=torch.float32, device=A.device)
+    ws = _workspace(workspace_bytes(DP_OP_SQNORM, B, T, d_in, d_out, dt, path), A.device, workspace)
+    st = lib.dp_layer_sqnorm(_ptr(A), _ptr(G), B, T, d_in, d_out, dt, _PATHS[path], int(bool(accumulate)),
+                             _ptr(sqnorm), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                             _stream_ptr(stream))
+    _check(st, "dp_layer_sqnorm")
+    return sqnorm
+
+
+def clip_factors(sqnorm: torch.Tensor, C: float, clip: Optional[torch.Tensor] = None, *,
+                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """clip[i] = min(1, C / sqrt(sqnorm[i])) via dp_clip_factors."""
+    lib = load_library()
+    if clip is None:
+        clip = torch.empty_like(sqnorm)
+    st = lib.dp_clip_factors(_ptr(sqnorm), sqnorm.numel(), float(C), _ptr(clip), _stream_ptr(stream))
+    _check(st, "dp_clip_factors")
+    return clip
+
+
+def clipped_grad(A: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, grad: Optional[torch.Tensor] = None, *,
+                 accumulate: bool = False, workspace: Optional[torch.Tensor] = None,
+                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """grad (+)= sum_i clip[i] A_i^T G_i, float32 [d_in, d_out], via dp_clipped_grad."""
+    lib = load_library()
+    A, G, B, T, d_in, d_out = _shape3(A, G)
+    dt = _dtype_code(A)
+    if grad is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing grad tensor")
+        grad = torch.empty((d_in, d_out), dtype=torch.float32, device=A.device)
+    ws = _workspace(workspace_bytes(DP_OP_CLIPPED_GRAD, B, T, d_in, d_out, dt), A.device, workspace)
+    st = lib.dp_clipped_grad(_ptr(A), _ptr(G), _ptr(clip), B, T, d_in, d_out, dt, int(bool(accumulate)),
+                             _ptr(grad), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                             _stream_ptr(stream))
+    _check(st, "dp_clipped_grad")
+    return grad
+
+
+def add_noise(grad: torch.Tensor, stddev: float, seed: int, offset: int = 0, *,
+              stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """grad += stddev * N(0,1)[seed, offset + j] in place via dp_add_noise."""
+    lib = load_library()
+    if grad.dtype != torch.float32:
+        raise TypeError("grad must be float32")
+    st = lib.dp_add_noise(_ptr(grad), grad.numel(), float(stddev), int(seed) & (2 ** 64 - 1), int(offset),
+                          _stream_ptr(stream))
+    _check(st, "dp_add_noise")
+    return grad
+
+
+def philox_raw(n_counters: int, seed: int, first_counter: int, device="cuda") -> torch.Tensor:
+    """Raw Philox4x32-10 words, int32 view of uint32 [n_counters, 4] (test hook)."""
+    lib = load_library()
+    out = torch.empty((n_counters, 4), dtype=torch.int32, device=device)
+    st = lib.dp_philox_raw(_ptr(out), n_counters, int(seed) & (2 ** 64 - 1), int(first_counter), _stream_ptr(None))
+    _check(st, "dp_philox_raw")
+    return out

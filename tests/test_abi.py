@@ -1,0 +1,74 @@
+"""The C-ABI library loads and exports every symbol the header declares; host-only
+entry points (path choice, workspace sizes, status strings) behave as documented.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import dp_oracle as orc
+from paper_2009_03106_amd import dpclip, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dpclip.LIB_PATH):
+        from paper_2009_03106_amd import build
+        build.build_library()
+    return dpclip.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dpclip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dp_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_match_header(lib):
+    syms = declared_symbols()
+    assert set(syms) == set(dpclip.EXPORTS)
+    for s in syms:
+        assert getattr(lib, s) is not None
+
+
+def test_status_strings(lib):
+    seen = {dpclip.status_string(i) for i in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert dpclip.status_string(99)
+
+
+def test_choose_path_matches_flop_model(lib):
+    for w in wl.WORKLOADS.values():
+        for spec in w.layers:
+            if spec.T > 1:
+                assert dpclip.choose_path(spec.T, spec.d_in, spec.d_out) == orc.choose_path(spec.T, spec.d_in, spec.d_out)
+    for T in (2, 3, 8, 63, 64, 65, 500, 4096):
+        for d_in in (1, 7, 64, 577, 4096):
+            for d_out in (1, 10, 128, 3072):
+                assert dpclip.choose_path(T, d_in, d_out) == orc.choose_path(T, d_in, d_out), (T, d_in, d_out)
+    assert dpclip.choose_path(1024, 576, 128) == "direct"
+    assert dpclip.choose_path(512, 768, 768) == "gram"
+
+
+def test_workspace_sizes(lib):
+    f = dpclip.workspace_bytes
+    assert f(dpclip.DP_OP_SQNORM, 256, 1, 784, 512, dpclip.DP_F32) == 0          # T = 1 needs none
+    assert f(dpclip.DP_OP_SQNORM, 0, 64, 256, 256, dpclip.DP_BF16) == 0
+    assert f(dpclip.DP_OP_SQNORM, -1, 64, 256, 256, dpclip.DP_BF16) == 0
+    g = f(dpclip.DP_OP_SQNORM, 64, 512, 768, 768, dpclip.DP_BF16, "gram")
+    d = f(dpclip.DP_OP_SQNORM, 64, 512, 768, 768, dpclip.DP_BF16, "direct")
+    assert g > 0 and d > 0 and g % 4 == 0 and d % 4 == 0
+    assert f(dpclip.DP_OP_SQNORM, 64, 512, 768, 768, dpclip.DP_BF16, "auto") == g
+    c = f(dpclip.DP_OP_CLIPPED_GRAD, 64, 512, 768, 2304, dpclip.DP_BF16)
+    assert c % (768 * 2304 * 4) == 0 and c >= 768 * 2304 * 4
+    assert f(dpclip.DP_OP_CLIPPED_GRAD, 1, 1, 8, 8, dpclip.DP_F32) == 0          # one K slice: no scratch
+
+
+def test_missing_library_raises(monkeypatch):
+    monkeypatch.setattr(dpclip, "_lib", None)
+    monkeypatch.setattr(dpclip, "LIB_PATH", "/nonexistent/libdpclip.so")
+    with pytest.raises(RuntimeError):
+        dpclip.load_library()

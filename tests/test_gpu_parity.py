@@ -1,0 +1,280 @@
+"""Parity of the HIP path (through the C-ABI binding) against the CPU oracle,
+element by element on the same seeded inputs.  Needs a real MI355X.
+
+Tolerances (stated by the task and derived in the design doc):
+  squared norms   rel 1e-5 (fp32 inputs)      2e-2 (bf16 inputs)
+  clipped grad    rel Frobenius 1e-4 (fp32)   2e-2 (bf16)
+  clip factors    as the norms
+  noise           |z_gpu - z_ref| <= 1e-5 (1 + |z_ref|), Philox words bit-exact
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dp_oracle as orc
+from paper_2009_03106_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SQ_TOL = {"f32": 1e-5, "bf16": 2e-2}
+FRO_TOL = {"f32": 1e-4, "bf16": 2e-2}
+# what the kernels are expected to reach in practice (fp32 accumulation of exact bf16 products);
+# looser than this but inside the stated tolerance would point at a real defect
+SQ_TIGHT = {"f32": 1e-5, "bf16": 2e-4}
+
+
+@pytest.fixture(scope="module")
+def dp():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2009_03106_amd import dpclip
+    dpclip.load_library()
+    return dpclip
+
+
+def to_dev(x: np.ndarray) -> torch.Tensor:
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x).cuda()
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    return float(np.max(np.abs(got.astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-300)))
+
+
+def fro_err(got: np.ndarray, ref: np.ndarray) -> float:
+    return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def run_gpu_pipeline(dp, layers_np, C, path="auto", noise_std=0.0, seed=0):
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers_np]
+    s = None
+    for li, (A, G) in enumerate(dev):
+        s = dp.layer_sqnorm(A, G, s, path=path, accumulate=li > 0)
+    c = dp.clip_factors(s, C)
+    grads = []
+    off = 0
+    for A, G in dev:
+        g = dp.clipped_grad(A, G, c)
+        if noise_std > 0:
+            dp.add_noise(g, noise_std, seed, off)
+        off += g.numel()
+        grads.append(g)
+    torch.cuda.synchronize()
+    return s.cpu().numpy(), c.cpu().numpy(), [g.cpu().numpy() for g in grads]
+
+
+def check_pipeline(dp, name, B=None, straddle=False, path="auto", with_noise=False):
+    w, layers = wl.generate(name, B=B, straddle=straddle)
+    std = w.noise_std if with_noise else 0.0
+    s_ref, c_ref, g_ref = orc.run_pipeline(layers, w.C, std, w.noise_seed)
+    s, c, g = run_gpu_pipeline(dp, layers, w.C, path=path, noise_std=std, seed=w.noise_seed)
+    assert rel_err(s, s_ref) <= SQ_TOL[w.dtype], (name, "sqnorm", rel_err(s, s_ref))
+    assert rel_err(s, s_ref) <= SQ_TIGHT[w.dtype], (name, "sqnorm (expected accuracy)", rel_err(s, s_ref))
+    assert rel_err(c, c_ref) <= SQ_TOL[w.dtype], (name, "clip", rel_err(c, c_ref))
+    for li, (gg, gr) in enumerate(zip(g, g_ref)):
+        assert fro_err(gg, gr) <= FRO_TOL[w.dtype], (name, li, "grad", fro_err(gg, gr))
+    # every clipped per-example gradient has norm <= C: nu_i * ||g_i|| with the oracle's norms
+    assert np.all(c.astype(np.float64) * np.sqrt(s_ref) <= w.C * (1 + SQ_TOL[w.dtype]))
+    if straddle:
+        assert (c == 1.0).any() and (c < 1.0).any()
+    return s, c, g
+
+
+# ----------------------------------------------------------------- the five configurations
+@pytest.mark.parametrize("straddle", [False, True])
+def test_config_dense(dp, straddle):
+    check_pipeline(dp, "dense", straddle=straddle)
+
+
+@pytest.mark.parametrize("straddle", [False, True])
+def test_config_mlp(dp, straddle):
+    check_pipeline(dp, "mlp", straddle=straddle)
+
+
+@pytest.mark.parametrize("straddle", [False, True])
+def test_config_rnn_gram_and_direct(dp, straddle):
+    s_gram, _, _ = check_pipeline(dp, "rnn", straddle=straddle, path="gram")
+    s_dir, _, _ = check_pipeline(dp, "rnn", straddle=straddle, path="direct")
+    s_auto, _, _ = check_pipeline(dp, "rnn", straddle=straddle, path="auto")
+    assert rel_err(s_gram, s_dir.astype(np.float64)) <= 2e-2
+    assert rel_err(s_gram, s_dir.astype(np.float64)) <= 1e-4
+    np.testing.assert_array_equal(s_auto, s_gram)       # AUTO resolves to GRAM here
+
+
+def test_config_conv_full(dp):
+    w = wl.WORKLOADS["conv"]
+    spec = w.layers[0]
+    assert dp.choose_path(spec.T, spec.d_in, spec.d_out) == "direct"
+    check_pipeline(dp, "conv")
+
+
+def test_config_conv_straddle_small_batch(dp):
+    check_pipeline(dp, "conv", B=16, straddle=True)
+
+
+def test_config_transformer_full_with_noise(dp):
+    w = wl.WORKLOADS["transformer"]
+    for spec in w.layers:
+        assert dp.choose_path(spec.T, spec.d_in, spec.d_out) == "gram"
+    check_pipeline(dp, "transformer", with_noise=True)
+
+
+def test_config_transformer_straddle_direct_path(dp):
+    check_pipeline(dp, "transformer", B=4, straddle=True, path="direct")
+
+
+def test_fused_qkv_equals_three_projections(dp):
+    """Squared norm of the stacked 768 -> 2304 projection = sum over its three 768-wide blocks (Section 5.6)."""
+    w, layers = wl.generate("transformer", B=4, layers=(0,))
+    A, G = layers[0]
+    Ad, Gd = to_dev(A), to_dev(G)
+    full = dp.layer_sqnorm(Ad, Gd).cpu().numpy()
+    parts = None
+    for j in range(3):
+        Gj = Gd[:, :, 768 * j:768 * (j + 1)].contiguous()
+        parts = dp.layer_sqnorm(Ad, Gj, parts, accumulate=j > 0)
+    assert rel_err(full, parts.cpu().numpy().astype(np.float64)) <= 1e-4
+
+
+# ----------------------------------------------------------------- ragged shapes and edge cases
+RAGGED = [
+    # B, T, d_in, d_out
+    (3, 1, 5, 3), (7, 1, 130, 67), (5, 1, 1024, 8),
+    (2, 3, 8, 8), (3, 17, 72, 40), (2, 70, 136, 264), (3, 129, 200, 24), (2, 257, 64, 320),
+    (1, 64, 7, 9), (2, 33, 129, 65),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,T,d_in,d_out", RAGGED)
+def test_ragged_shapes(dp, dtype, B, T, d_in, d_out):
+    A, G = wl.random_layer(1234 + B + T + d_in, B, T, d_in, d_out, dtype,
+                           g_row_scale=np.exp(np.linspace(-3, 1, B)))
+    C = 0.7
+    s_ref = orc.layer_sqnorm(A, G)
+    c_ref = orc.clip_factors(s_ref, C)
+    g_ref = orc.clipped_grad(A, G, c_ref)
+    Ad, Gd = to_dev(A), to_dev(G)
+    paths = ["auto"] if (T == 1 or dtype == "f32") else ["gram", "direct"]
+    for path in paths:
+        s = dp.layer_sqnorm(Ad, Gd, path=path)
+        assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], (path, rel_err(s.cpu().numpy(), s_ref))
+    c = dp.clip_factors(s, C)
+    assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL[dtype]
+    g = dp.clipped_grad(Ad, Gd, c)
+    assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL[dtype]
+
+
+def test_accumulate_flags(dp):
+    A, G = wl.random_layer(77, 6, 9, 40, 24, "bf16")
+    Ad, Gd = to_dev(A), to_dev(G)
+    s_ref = orc.layer_sqnorm(A, G)
+    s = torch.full((6,), 3.0, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, s, accumulate=True, path="direct")
+    assert rel_err(s.cpu().numpy(), s_ref + 3.0) <= 1e-4
+    s2 = torch.full((6,), 3.0, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, s2, accumulate=True, path="gram")
+    assert rel_err(s2.cpu().numpy(), s_ref + 3.0) <= 1e-4
+    c = torch.linspace(0.1, 1.0, 6, device="cuda")
+    g_ref = orc.clipped_grad(A, G, c.cpu().numpy().astype(np.float64))
+    g = torch.ones((40, 24), device="cuda")
+    dp.clipped_grad(Ad, Gd, c, g, accumulate=True)
+    assert fro_err(g.cpu().numpy(), g_ref + 1.0) <= 2e-2
+    dp.clipped_grad(Ad, Gd, c, g, accumulate=False)
+    assert fro_err(g.cpu().numpy(), g_ref) <= 2e-2
+
+
+def test_clip_factor_edge_values(dp):
+    s = torch.tensor([0.0, 0.25, 1.0, 4.0, 1e30, float("inf")], device="cuda")
+    c = dp.clip_factors(s, 1.0).cpu().numpy()
+    np.testing.assert_array_equal(c[:3], [1.0, 1.0, 1.0])
+    np.testing.assert_allclose(c[3:5], [0.5, 1e-15], rtol=1e-6)
+    assert c[5] == 0.0
+    nan = dp.clip_factors(torch.tensor([float("nan")], device="cuda"), 1.0).cpu().numpy()
+    assert np.isnan(nan[0])          # NaN inputs propagate, as documented
+
+
+def test_empty_problems_and_errors(dp):
+    lib = dp.load_library()
+    s = torch.full((4,), 9.0, device="cuda")
+    A = torch.zeros((4, 0, 8), dtype=torch.bfloat16, device="cuda")
+    G = torch.zeros((4, 0, 8), dtype=torch.bfloat16, device="cuda")
+    dp.layer_sqnorm(A, G, s)                         # T == 0, overwrite -> zeros
+    assert torch.all(s == 0)
+    g = torch.full((8, 8), 5.0, device="cuda")
+    dp.clipped_grad(A, G, torch.ones(4, device="cuda"), g)
+    assert torch.all(g == 0)
+    g.fill_(5.0)
+    dp.clipped_grad(A, G, torch.ones(4, device="cuda"), g, accumulate=True)
+    assert torch.all(g == 5.0)
+    # errors: nothing launched, outputs untouched
+    A2 = torch.zeros((2, 4, 8), dtype=torch.bfloat16, device="cuda")
+    G2 = torch.zeros((2, 4, 8), dtype=torch.bfloat16, device="cuda")
+    s2 = torch.full((2,), 7.0, device="cuda")
+    st = lib.dp_layer_sqnorm(A2.data_ptr(), G2.data_ptr(), 2, 4, 8, 8, dp.DP_BF16, dp.DP_PATH_DIRECT, 0,
+                             s2.data_ptr(), None, 0, None)
+    assert st == dp.DP_ERR_WORKSPACE
+    st = lib.dp_layer_sqnorm(A2.data_ptr(), G2.data_ptr(), -1, 4, 8, 8, dp.DP_BF16, 0, 0, s2.data_ptr(), None, 0, None)
+    assert st == dp.DP_ERR_INVALID_ARG
+    st = lib.dp_layer_sqnorm(A2.data_ptr(), G2.data_ptr(), 2, 4, 8, 8, dp.DP_F32, dp.DP_PATH_GRAM, 0,
+                             s2.data_ptr(), None, 0, None)
+    assert st == dp.DP_ERR_UNSUPPORTED
+    st = lib.dp_clip_factors(s2.data_ptr(), 2, 0.0, s2.data_ptr(), None)
+    assert st == dp.DP_ERR_INVALID_ARG
+    st = lib.dp_add_noise(s2.data_ptr(), 2, -1.0, 0, 0, None)
+    assert st == dp.DP_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.all(s2 == 7.0)
+
+
+def test_reruns_are_bit_identical(dp):
+    w, layers = wl.generate("rnn", B=32)
+    a = run_gpu_pipeline(dp, layers, w.C, path="gram")
+    b = run_gpu_pipeline(dp, layers, w.C, path="gram")
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[2][0], b[2][0])
+    a = run_gpu_pipeline(dp, layers, w.C, path="direct")
+    b = run_gpu_pipeline(dp, layers, w.C, path="direct")
+    np.testing.assert_array_equal(a[0], b[0])
+
+
+# ----------------------------------------------------------------- noise
+def test_philox_words_bit_exact(dp):
+    for seed, first in [(0, 0), (0x0123456789ABCDEF, (1 << 32) - 1000), (20090310, (1 << 40) + 7)]:
+        n = 5000
+        got = dp.philox_raw(n, seed, first).cpu().numpy().view(np.uint32)
+        np.testing.assert_array_equal(got, orc.philox_words(n, seed, first))
+
+
+@pytest.mark.parametrize("offset", [0, 1, 2, 3, 4, 4099, (1 << 34) + 5])
+def test_noise_matches_oracle(dp, offset):
+    n = 100003
+    g = torch.zeros(n, device="cuda")
+    dp.add_noise(g, 1.0, 0xABCDEF0123, offset)
+    z = g.cpu().numpy().astype(np.float64)
+    ref = orc.standard_normals(n, 0xABCDEF0123, offset)
+    assert np.max(np.abs(z - ref) / (1 + np.abs(ref))) <= 1e-5
+    # scaled and added to existing values
+    g2 = torch.full((n,), 2.0, device="cuda")
+    dp.add_noise(g2, 0.5, 0xABCDEF0123, offset)
+    np.testing.assert_allclose(g2.cpu().numpy(), 2.0 + 0.5 * ref, rtol=0, atol=1e-5)
+
+
+def test_noise_offset_continuity_bit_exact(dp):
+    n = 4096 + 3
+    full = torch.zeros(n, device="cuda")
+    dp.add_noise(full, 1.0, 99, 0)
+    for k in (1, 2, 3, 5, 64):
+        part = torch.zeros(n - k, device="cuda")
+        dp.add_noise(part, 1.0, 99, k)
+        assert torch.equal(part, full[k:])
+
+
+def test_noise_moments(dp):
+    n = 7_077_888                      # the transformer configuration's parameter count
+    g = torch.zeros(n, device="cuda")
+    dp.add_noise(g, 1.0, 2009, 0)
+    z = g.double()
+    assert abs(z.mean().item()) < 4.0 / np.sqrt(n)
+    assert abs(z.var().item() - 1.0) < 3e-3
+    assert abs((z ** 4).mean().item() - 3.0) < 2e-2
