@@ -42,8 +42,8 @@ size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dty
 }
 
 size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
-    TnPlan p = (dtype == DP_BF16) ? plan_clipped_bf16(B * T, (int)d_in, (int)d_out)
-                                  : plan_clipped_f32(B * T, (int)d_in, (int)d_out);
+    TnPlan p = (dtype == DP_BF16) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
+                                  : plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
     if (p.splits <= 1) return 0;
     return (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float);
 }
@@ -156,11 +156,11 @@ dp_status dp_clipped_grad(const void* A, const void* G, const float* clip, int64
 
     hipError_t e;
     if (dtype == DP_BF16) {
-        TnPlan p = plan_clipped_bf16(B * T, (int)d_in, (int)d_out);
+        TnPlan p = plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_clipped_bf16(p, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), clip, (int)B, (int)T,
                                 (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream);
     } else {
-        TnPlan p = plan_clipped_f32(B * T, (int)d_in, (int)d_out);
+        TnPlan p = plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_clipped_f32(p, static_cast<const float*>(A), static_cast<const float*>(G), clip, (int)B, (int)T,
                                (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream);
     }

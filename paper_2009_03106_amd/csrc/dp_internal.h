@@ -26,10 +26,12 @@ struct TnPlan {
     int tile_m, tile_n;     // block tile
     int tiles_m, tiles_n;
     int splits;             // clipped grad: number of K slices; direct sqnorm: unused
-    int kchunk;             // rows of K per slice (multiple of the kernel's BK)
+    int kchunk;             // rows of K per slice
+    bool segmented;         // bf16 only: K is walked example by example (slices are whole examples)
+    int epu;                // segmented: examples per K slice
 };
-TnPlan plan_clipped_bf16(int64_t K, int M, int N);
-TnPlan plan_clipped_f32(int64_t K, int M, int N);
+TnPlan plan_clipped_bf16(int B, int T, int M, int N);
+TnPlan plan_clipped_f32(int B, int T, int M, int N);
 TnPlan plan_direct_bf16(int T, int M, int N);
 TnPlan plan_direct_f32(int T, int M, int N);
 

@@ -9,6 +9,14 @@
 // are multiplied by their example's clip factor in the same step (the values
 // are in float registers anyway for the repack), then rounded back to bf16.
 //
+// Two kernels share the repack.  k_tn_bf16_seg (T >= 32) walks K example by
+// example: a per-example accumulator tile is finished when the example's T
+// rows are done and is then either folded into the running clipped sum with
+// one float multiply-add per element (exact clip factor, no re-rounding of A)
+// or squared and reduced.  k_tn_bf16_rows (small T, where an LDS stage would
+// be mostly padding) walks K in plain 64-row stages and scales the rows of A
+// by their clip factors during the repack, rounding them back to bf16.
+//
 // Two uses:
 //   * clipped sum (dp_clipped_grad): grid = tiles x K-slices; every slice's
 //     tile goes to the workspace and is folded in a fixed order afterwards.
@@ -110,7 +118,7 @@ __device__ __forceinline__ void transpose8x8_scaled(const uint4 (&r)[8], const f
 
 // MODE 0: clipped sum (scale A rows, store the tile).  MODE 1: direct squared norm.
 template <int MODE>
-__global__ __launch_bounds__(kThreads, 2) void k_tn_bf16(TnArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_rows(TnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BM * 128];   // A^T tile then G^T tile: [col][64 k]
     __shared__ float red[4];
 
@@ -230,15 +238,185 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16(TnArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Example-segmented kernel (T >= 32).
+// ---------------------------------------------------------------------------
+struct SegArgs {
+    const uint16_t* A;
+    const uint16_t* G;
+    const float* clip;     // clipped sum only
+    float* out;            // clipped: slice base (stride `slice` per unit) or grad; direct: partial[B][tiles]
+    int64_t slice;
+    int B, T, M, N;
+    int tiles_m, tiles_n;
+    int epu;               // examples per unit of work (one unit = one K slice); direct: 1
+    int units;
+    int accumulate;        // clipped with a single unit: add to out
+};
+
+// Workgroup b runs on XCD b % 8 (round-robin dispatch).  Units are dealt to XCDs so that the
+// workgroups resident on one XCD at a time work on the same rows of A and G (same unit,
+// neighbouring tiles) and share them through that XCD's L2.
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][2 * BM * 128];
+    __shared__ float red[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles = a.tiles_m * a.tiles_n;
+    const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+    const int z = xcd + 8 * (jj / tiles);
+    const int tile = jj % tiles;
+    if (z >= a.units) return;
+    const int tm = tile / a.tiles_n, tn = tile % a.tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int ex_begin = z * a.epu;
+    const int ex_end = min(a.B, ex_begin + a.epu);
+    const int spe = (a.T + BK - 1) / BK;                 // stages per example
+    const int n_stages = (ex_end - ex_begin) * spe;
+
+    const int opnd = tid >> 7;
+    const int local = tid & 127;
+    const int cg = local & 15;
+    const int kc = local >> 4;
+    const uint16_t* X = opnd ? a.G : a.A;
+    const int D = opnd ? a.N : a.M;
+    const int col0 = (opnd ? n0 : m0) + cg * 8;
+    const bool vec_ok = (D & 7) == 0;
+    const int lds_x = opnd * (BM * 128);
+
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    f32x16 acc[2][2], tot[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; tot[i][j][r] = 0.f; }
+
+    uint4 stage[8];
+    auto fetch = [&](int st) {
+        const int e = st / spe;
+        const int k0 = (st - e * spe) * BK;
+        const uint16_t* Xi = X + (size_t)(ex_begin + e) * a.T * D;
+        load_block(Xi, D, vec_ok, k0 + kc * 8, a.T, col0, stage);
+    };
+    auto commit = [&](int buf) {
+        uint4 cols[8];
+        transpose8x8(stage, cols);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            *reinterpret_cast<uint4*>(&lds[buf][lds_x + lds_off_bytes(cg * 8 + j, kc)]) = cols[j];
+    };
+    auto kstep = [&](int buf, int ks, bool fresh) {
+        bf16x8 fa[2], fb[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            fa[i] = *reinterpret_cast<const bf16x8*>(&lds[buf][lds_off_bytes(wm * 64 + i * 32 + lrow, ks * 2 + lhalf)]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            fb[j] = *reinterpret_cast<const bf16x8*>(&lds[buf][BM * 128 + lds_off_bytes(wn * 64 + j * 32 + lrow, ks * 2 + lhalf)]);
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], fresh ? zero : acc[i][j], 0, 0, 0);
+    };
+
+    if (n_stages > 0) {
+        fetch(0);
+        commit(0);
+        if (n_stages > 1) fetch(1);
+    }
+    __syncthreads();
+    int sub = 0;                    // stage index inside the current example
+    int ex = ex_begin;
+    for (int st = 0; st < n_stages; ++st) {
+        const int cur = st & 1;
+        if (st + 1 < n_stages) commit(cur ^ 1);
+        if (st + 2 < n_stages) fetch(st + 2);
+        if (sub == 0) kstep(cur, 0, true); else kstep(cur, 0, false);
+#pragma unroll
+        for (int ks = 1; ks < BK / 16; ++ks) kstep(cur, ks, false);
+        if (++sub == spe) {
+            // this example's tile of A_i^T G_i is complete
+            if (MODE == 0) {
+                const float c = a.clip[ex];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) tot[i][j][r] += c * acc[i][j][r];
+            } else {
+                float s = 0.f;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s += acc[i][j][r] * acc[i][j][r];
+                s = block_sum_256(s, red);
+                if (tid == 0) a.out[(size_t)ex * tiles + tile] = s;
+            }
+            sub = 0;
+            ++ex;
+        }
+        __syncthreads();
+    }
+
+    if (MODE == 0) {
+        float* out = a.out + (size_t)z * a.slice;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int n = n0 + wn * 64 + j * 32 + lrow;
+                if (n >= a.N) continue;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                    if (m < a.M) {
+                        float* p = out + (size_t)m * a.N + n;
+                        *p = a.accumulate ? *p + tot[i][j][r] : tot[i][j][r];
+                    }
+                }
+            }
+    }
+}
+
+constexpr int kSegMinT = 32;      // below this an LDS stage would be mostly padding
+
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 }  // namespace
 
-TnPlan plan_clipped_bf16(int64_t K, int M, int N) {
+TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
     TnPlan p;
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    p.segmented = (T >= kSegMinT);
+    if (p.segmented) {
+        // K slices are whole examples.  Aim for a few workgroups per compute unit, in multiples of the
+        // 8 XCDs, without multiplying the fp32 slice traffic more than needed.
+        int64_t units = (768 + tiles - 1) / tiles;
+        units = ((units + 7) / 8) * 8;
+        // every slice costs a write and a read of M*N floats: keep that below a quarter of the input bytes
+        const int64_t in_bytes = (int64_t)B * T * ((int64_t)M + N) * 2;
+        int64_t cap = in_bytes / 4 / ((int64_t)M * N * 8);
+        cap = (cap / 8) * 8;
+        if (cap < 8) cap = 8;
+        if (units > cap) units = cap;
+        if (units > B) units = B;
+        p.epu = ceil_div(B, units);
+        p.splits = ceil_div(B, p.epu);
+        p.kchunk = p.epu * T;
+        return p;
+    }
+    const int64_t K = (int64_t)B * T;
     // enough K slices for about two workgroups per compute unit, each at least 4 stages long
     int64_t want = (512 + tiles - 1) / tiles;
     int64_t max_splits = (K + 4 * BK - 1) / (4 * BK);
@@ -248,34 +426,44 @@ TnPlan plan_clipped_bf16(int64_t K, int M, int N) {
     kchunk = ((kchunk + BK - 1) / BK) * BK;
     if (kchunk < BK) kchunk = BK;
     p.kchunk = (int)kchunk;
+    p.epu = 0;
     p.splits = (int)((K + kchunk - 1) / kchunk);
     if (p.splits < 1) p.splits = 1;
     return p;
 }
 
 TnPlan plan_direct_bf16(int T, int M, int N) {
-    (void)T;
     TnPlan p;
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
-    p.splits = 1; p.kchunk = 0;
+    p.segmented = (T >= kSegMinT);
+    p.splits = 1; p.kchunk = 0; p.epu = 1;
     return p;
 }
 
 hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st) {
-    TnArgs a;
-    a.A = A; a.G = G; a.clip = clip;
-    a.K = B * T; a.T = T; a.M = M; a.N = N;
-    a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.kchunk = p.kchunk;
     const int64_t n = (int64_t)M * N;
-    if (p.splits == 1) {
-        a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0;
+    const int tiles = p.tiles_m * p.tiles_n;
+    if (p.segmented) {
+        SegArgs a;
+        a.A = A; a.G = G; a.clip = clip;
+        a.B = B; a.T = T; a.M = M; a.N = N;
+        a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.epu = p.epu; a.units = p.splits;
+        if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
+        else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
+        const unsigned grid = 8u * (unsigned)ceil_div(p.splits, 8) * (unsigned)tiles;
+        k_tn_bf16_seg<0><<<grid, kThreads, 0, st>>>(a);
     } else {
-        a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0;
+        TnArgs a;
+        a.A = A; a.G = G; a.clip = clip;
+        a.K = B * T; a.T = T; a.M = M; a.N = N;
+        a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.kchunk = p.kchunk;
+        if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
+        else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
+        dim3 grid((unsigned)tiles, (unsigned)p.splits);
+        k_tn_bf16_rows<0><<<grid, kThreads, 0, st>>>(a);
     }
-    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.splits);
-    k_tn_bf16<0><<<grid, kThreads, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
@@ -283,12 +471,29 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
 
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                               bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+    const int tiles = p.tiles_m * p.tiles_n;
+    if (p.segmented) {
+        // one launch covers at most 2^20 examples so that the workgroup count stays far below 2^31
+        for (int b0 = 0; b0 < B; b0 += (1 << 20)) {
+            const int nb = (B - b0 < (1 << 20)) ? (B - b0) : (1 << 20);
+            SegArgs a;
+            a.A = A + (size_t)b0 * T * M; a.G = G + (size_t)b0 * T * N; a.clip = nullptr;
+            a.B = nb; a.T = T; a.M = M; a.N = N;
+            a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.epu = 1; a.units = nb;
+            a.out = partial + (size_t)b0 * tiles; a.slice = 0; a.accumulate = 0;
+            const int64_t grid = 8ll * ceil_div(nb, 8) * tiles;
+            if (grid >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+            k_tn_bf16_seg<1><<<(unsigned)grid, kThreads, 0, st>>>(a);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
+    }
     TnArgs a;
     a.A = A; a.G = G; a.clip = nullptr;
     a.K = B * T; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.kchunk = 0;
     a.out = partial; a.slice = 0; a.accumulate = 0;
-    const int tiles = p.tiles_m * p.tiles_n;
     // grid.y is limited to 65535: fold larger batches into several launches
     for (int b0 = 0; b0 < B; b0 += 65535) {
         const int nb = (B - b0 < 65535) ? (B - b0) : 65535;
@@ -297,7 +502,7 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
         s.G = G + (size_t)b0 * T * N;
         s.out = partial + (size_t)b0 * tiles;
         dim3 grid((unsigned)tiles, (unsigned)nb);
-        k_tn_bf16<1><<<grid, kThreads, 0, st>>>(s);
+        k_tn_bf16_rows<1><<<grid, kThreads, 0, st>>>(s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
