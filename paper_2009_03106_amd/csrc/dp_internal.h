@@ -29,6 +29,7 @@ struct TnPlan {
     int kchunk;             // rows of K per slice
     bool segmented;         // bf16 only: K is walked example by example (slices are whole examples)
     int epu;                // segmented: examples per K slice
+    bool big;               // bf16 clipped sum only: 256 x 256 tiles, one workgroup per compute unit
 };
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
 TnPlan plan_clipped_f32(int B, int T, int M, int N);

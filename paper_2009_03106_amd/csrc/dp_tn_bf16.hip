@@ -32,6 +32,7 @@ namespace dpk {
 namespace {
 
 constexpr int BK = 64;           // k rows per LDS stage
+inline int ceil_div_i(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 constexpr int BM = 128, BN = 128;
 
 struct TnArgs {
@@ -257,7 +258,8 @@ struct SegArgs {
 // Workgroup b runs on XCD b % 8 (round-robin dispatch).  Units are dealt to XCDs so that the
 // workgroups resident on one XCD at a time work on the same rows of A and G (same unit,
 // neighbouring tiles) and share them through that XCD's L2.
-template <int MODE>
+// FAST: d_in, d_out and T are multiples of 8, so every 16-byte piece and every thread's 8 rows are all in or all out.
+template <int MODE, bool FAST>
 __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][2 * BM * 128];
     __shared__ float red[4];
@@ -296,27 +298,50 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
             for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; tot[i][j][r] = 0.f; }
 
     uint4 stage[8];
-    auto fetch = [&](int st) {
-        const int e = st / spe;
-        const int k0 = (st - e * spe) * BK;
-        const uint16_t* Xi = X + (size_t)(ex_begin + e) * a.T * D;
-        load_block(Xi, D, vec_ok, k0 + kc * 8, a.T, col0, stage);
+    // fast path: 16-byte pieces, and a thread's 8 rows are inside the example together (T % 8 == 0)
+    const bool col_ok = col0 < D;
+    const size_t row_bytes = (size_t)D * 2;
+    int f_e = 0, f_sub = 0;         // (example, stage in example) of the next fetch
+    auto fetch = [&]() {
+        const int row0 = f_sub * BK + kc * 8;
+        const uint16_t* Xi = X + (size_t)(ex_begin + f_e) * a.T * D;
+        if (FAST) {
+            if (col_ok && row0 < a.T) {
+                const unsigned char* p = reinterpret_cast<const unsigned char*>(Xi + (size_t)row0 * D + col0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) stage[i] = *reinterpret_cast<const uint4*>(p + i * row_bytes);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) stage[i] = make_uint4(0u, 0u, 0u, 0u);
+            }
+        } else {
+            load_block(Xi, D, vec_ok, row0, a.T, col0, stage);
+        }
+        if (++f_sub == spe) { f_sub = 0; ++f_e; }
     };
+    // LDS addresses are loop invariant: 8 write slots, 4 read rows (the k-step only flips bits 5-6)
+    int wr_off[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) wr_off[j] = lds_x + lds_off_bytes(cg * 8 + j, kc);
+    int rd_a[2], rd_b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        rd_a[i] = lds_off_bytes(wm * 64 + i * 32 + lrow, lhalf);
+        rd_b[i] = BM * 128 + lds_off_bytes(wn * 64 + i * 32 + lrow, lhalf);
+    }
     auto commit = [&](int buf) {
         uint4 cols[8];
         transpose8x8(stage, cols);
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            *reinterpret_cast<uint4*>(&lds[buf][lds_x + lds_off_bytes(cg * 8 + j, kc)]) = cols[j];
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(&lds[buf][wr_off[j]]) = cols[j];
     };
     auto kstep = [&](int buf, int ks, bool fresh) {
         bf16x8 fa[2], fb[2];
+        // chunk (2*ks + lhalf) ^ swz(row) == (lhalf ^ swz(row)) ^ (2*ks): flip bits 5-6 of the byte offset
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            fa[i] = *reinterpret_cast<const bf16x8*>(&lds[buf][lds_off_bytes(wm * 64 + i * 32 + lrow, ks * 2 + lhalf)]);
+        for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&lds[buf][rd_a[i] ^ (ks << 5)]);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-            fb[j] = *reinterpret_cast<const bf16x8*>(&lds[buf][BM * 128 + lds_off_bytes(wn * 64 + j * 32 + lrow, ks * 2 + lhalf)]);
+        for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&lds[buf][rd_b[j] ^ (ks << 5)]);
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -326,9 +351,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
     };
 
     if (n_stages > 0) {
-        fetch(0);
+        fetch();
         commit(0);
-        if (n_stages > 1) fetch(1);
+        if (n_stages > 1) fetch();
     }
     __syncthreads();
     int sub = 0;                    // stage index inside the current example
@@ -336,7 +361,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
     for (int st = 0; st < n_stages; ++st) {
         const int cur = st & 1;
         if (st + 1 < n_stages) commit(cur ^ 1);
-        if (st + 2 < n_stages) fetch(st + 2);
+        if (st + 2 < n_stages) fetch();
         if (sub == 0) kstep(cur, 0, true); else kstep(cur, 0, false);
 #pragma unroll
         for (int ks = 1; ks < BK / 16; ++ks) kstep(cur, ks, false);
@@ -387,6 +412,185 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
     }
 }
 
+inline bool seg_fast(int T, int M, int N) { return ((T | M | N) & 7) == 0; }
+
+// ---------------------------------------------------------------------------
+// Large-tile clipped sum: 256 x 256 output tile per workgroup, one workgroup
+// per compute unit (128 KB of LDS, double buffered), each wave owning a
+// 128 x 128 piece (4 x 4 MFMA tiles, 256 accumulator registers).  Per 64-row
+// stage a workgroup reads 64 KB for 8.4 MFLOP, i.e. 32 bytes per clock and
+// compute unit at full MFMA rate, half of what the 128 x 128 tiles need.
+// Rows of A are scaled by their example's clip factor while they are
+// repacked (all 8 rows of a thread's block belong to one example because
+// T % 8 == 0 here).  K slices are arbitrary multiples of 64 rows.
+// Requires d_in % 8 == 0, d_out % 8 == 0, T % 8 == 0.
+// ---------------------------------------------------------------------------
+constexpr int GM = 256, GN = 256;
+
+struct BigArgs {
+    const uint16_t* A;
+    const uint16_t* G;
+    const float* clip;
+    float* out;            // slice base (stride `slice` per K slice) or grad
+    int64_t slice;
+    int B, T, K, M, N;
+    int tiles_m, tiles_n;
+    int splits, kchunk;
+    int per_xcd;           // workgroups per XCD
+    int accumulate;
+};
+
+// Same repack as transpose8x8_scaled with one factor for all 8 rows.
+__device__ __forceinline__ void transpose8x8_scaled1(const uint4 (&r)[8], float s, uint4 (&c)[8]) {
+    uint32_t in[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { in[i][0] = r[i].x; in[i][1] = r[i].y; in[i][2] = r[i].z; in[i][3] = r[i].w; }
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t e[4], o[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t x = in[2 * p][d], y = in[2 * p + 1][d];
+            e[p] = pack_bf16(bf16_lo(x) * s, bf16_lo(y) * s);
+            o[p] = pack_bf16(bf16_hi(x) * s, bf16_hi(y) * s);
+        }
+        c[2 * d] = make_uint4(e[0], e[1], e[2], e[3]);
+        c[2 * d + 1] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+__global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_big(BigArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][2 * GM * 128];   // [buffer][A^T tile | G^T tile]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles = a.tiles_m * a.tiles_n;
+    // workgroup b runs on XCD b % 8: give each XCD a contiguous run of (slice, tile) pairs so that
+    // its workgroups stream the same rows of A and G through one L2
+    const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
+    if (L >= tiles * a.splits) return;
+    const int z = L / tiles, tile = L - z * tiles;
+    const int tm = tile / a.tiles_n, tn = tile - tm * a.tiles_n;
+    const int m0 = tm * GM, n0 = tn * GN;
+    const int k_begin = z * a.kchunk;
+    const int k_end = min(a.K, k_begin + a.kchunk);
+    const int n_stages = (k_end - k_begin + BK - 1) / BK;
+
+    // global -> LDS: every thread moves one 8 x 8 block of A and one of G per stage
+    const int cg = tid & 31;            // 8-column group in the 256-column tile
+    const int kc = tid >> 5;            // 8-row chunk in the 64-row stage
+    const int colA = m0 + cg * 8, colG = n0 + cg * 8;
+    const bool okA = colA < a.M, okG = colG < a.N;
+    const size_t rbA = (size_t)a.M * 2, rbG = (size_t)a.N * 2;
+    int row = k_begin + kc * 8;         // first row of this thread's block in the next stage to fetch
+    int ex = row / a.T, rem = row - ex * a.T;
+
+    uint4 stA[8], stG[8];
+    float scl = 0.f;
+    auto fetch = [&]() {
+        const bool in = row < k_end;
+        if (in && okA) {
+            const unsigned char* p = reinterpret_cast<const unsigned char*>(a.A + (size_t)row * a.M + colA);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) stA[i] = *reinterpret_cast<const uint4*>(p + i * rbA);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) stA[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        if (in && okG) {
+            const unsigned char* p = reinterpret_cast<const unsigned char*>(a.G + (size_t)row * a.N + colG);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) stG[i] = *reinterpret_cast<const uint4*>(p + i * rbG);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) stG[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        scl = a.clip[min(ex, a.B - 1)];
+        row += BK; rem += BK;
+        while (rem >= a.T) { rem -= a.T; ++ex; }
+    };
+    int wrA[8], wrG[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        wrA[j] = lds_off_bytes(cg * 8 + j, kc);
+        wrG[j] = GM * 128 + wrA[j];
+    }
+    auto commit = [&](int buf) {
+        uint4 cols[8];
+        transpose8x8_scaled1(stA, scl, cols);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(&lds[buf][wrA[j]]) = cols[j];
+        transpose8x8(stG, cols);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(&lds[buf][wrG[j]]) = cols[j];
+    };
+
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    int rdA[4], rdG[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        rdA[i] = lds_off_bytes(wm * 128 + i * 32 + lrow, lhalf);
+        rdG[i] = GM * 128 + lds_off_bytes(wn * 128 + i * 32 + lrow, lhalf);
+    }
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    if (n_stages > 0) {
+        fetch();
+        commit(0);
+        if (n_stages > 1) fetch();
+    }
+    __syncthreads();
+    for (int st = 0; st < n_stages; ++st) {
+        const int cur = st & 1;
+        if (st + 1 < n_stages) commit(cur ^ 1);
+        if (st + 2 < n_stages) fetch();
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[4], fb[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&lds[cur][rdA[i] ^ (ks << 5)]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&lds[cur][rdG[j] ^ (ks << 5)]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    float* out = a.out + (size_t)z * a.slice;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + wn * 128 + j * 32 + lrow;
+            if (n >= a.N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                if (m < a.M) {
+                    float* p = out + (size_t)m * a.N + n;
+                    *p = a.accumulate ? *p + acc[i][j][r] : acc[i][j][r];
+                }
+            }
+        }
+}
+
+// Use the 256 x 256 kernel when the shape is aligned and its padded tiles waste at most a quarter.
+inline bool big_ok(int T, int M, int N) {
+    if (((T | M | N) & 7) != 0) return false;
+    const int64_t padded = (int64_t)ceil_div_i(M, GM) * GM * ceil_div_i(N, GN) * GN;
+    return padded * 4 <= (int64_t)M * N * 5;
+}
+
 constexpr int kSegMinT = 32;      // below this an LDS stage would be mostly padding
 
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
@@ -398,6 +602,24 @@ TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    p.big = big_ok(T, M, N);
+    if (p.big) {
+        p.tile_m = GM; p.tile_n = GN;
+        p.tiles_m = ceil_div(M, GM); p.tiles_n = ceil_div(N, GN);
+        const int64_t bt = (int64_t)p.tiles_m * p.tiles_n;
+        const int64_t K = (int64_t)B * T;
+        // one workgroup per compute unit: as many K slices as fit in 256 workgroups
+        int64_t splits = 256 / bt;
+        if (splits < 1) splits = 1;
+        const int64_t max_splits = (K + 2 * BK - 1) / (2 * BK);
+        if (splits > max_splits) splits = max_splits;
+        int64_t kchunk = (K + splits - 1) / splits;
+        kchunk = ((kchunk + BK - 1) / BK) * BK;
+        p.kchunk = (int)kchunk;
+        p.splits = (int)((K + kchunk - 1) / kchunk);
+        p.segmented = false; p.epu = 0;
+        return p;
+    }
     p.segmented = (T >= kSegMinT);
     if (p.segmented) {
         // K slices are whole examples.  Aim for a few workgroups per compute unit, in multiples of the
@@ -437,6 +659,7 @@ TnPlan plan_direct_bf16(int T, int M, int N) {
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     p.segmented = (T >= kSegMinT);
+    p.big = false;
     p.splits = 1; p.kchunk = 0; p.epu = 1;
     return p;
 }
@@ -445,7 +668,16 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
                                int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st) {
     const int64_t n = (int64_t)M * N;
     const int tiles = p.tiles_m * p.tiles_n;
-    if (p.segmented) {
+    if (p.big) {
+        BigArgs a;
+        a.A = A; a.G = G; a.clip = clip;
+        a.B = B; a.T = T; a.K = B * T; a.M = M; a.N = N;
+        a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.splits = p.splits; a.kchunk = p.kchunk;
+        a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
+        if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
+        else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
+        k_tn_bf16_big<<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+    } else if (p.segmented) {
         SegArgs a;
         a.A = A; a.G = G; a.clip = clip;
         a.B = B; a.T = T; a.M = M; a.N = N;
@@ -453,7 +685,8 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
         if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
         else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
         const unsigned grid = 8u * (unsigned)ceil_div(p.splits, 8) * (unsigned)tiles;
-        k_tn_bf16_seg<0><<<grid, kThreads, 0, st>>>(a);
+        if (seg_fast(T, M, N)) k_tn_bf16_seg<0, true><<<grid, kThreads, 0, st>>>(a);
+        else k_tn_bf16_seg<0, false><<<grid, kThreads, 0, st>>>(a);
     } else {
         TnArgs a;
         a.A = A; a.G = G; a.clip = clip;
@@ -483,7 +716,8 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
             a.out = partial + (size_t)b0 * tiles; a.slice = 0; a.accumulate = 0;
             const int64_t grid = 8ll * ceil_div(nb, 8) * tiles;
             if (grid >= (int64_t(1) << 31)) return hipErrorInvalidValue;
-            k_tn_bf16_seg<1><<<(unsigned)grid, kThreads, 0, st>>>(a);
+            if (seg_fast(T, M, N)) k_tn_bf16_seg<1, true><<<(unsigned)grid, kThreads, 0, st>>>(a);
+            else k_tn_bf16_seg<1, false><<<(unsigned)grid, kThreads, 0, st>>>(a);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
