@@ -30,16 +30,21 @@ struct TnPlan {
     bool segmented;         // bf16 only: K is walked example by example (slices are whole examples)
     int epu;                // segmented: examples per K slice
     bool big;               // bf16 clipped sum only: 256 x 256 tiles, one workgroup per compute unit
+    bool dma;               // bf16 clipped sum only: 256 x 256 tiles fed by direct-to-LDS copies and transposing LDS reads
 };
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
 TnPlan plan_clipped_f32(int B, int T, int M, int N);
 TnPlan plan_direct_bf16(int T, int M, int N);
+bool dma_clipped_ok(int B, int T, int M, int N);
+TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N);
 TnPlan plan_direct_f32(int T, int M, int N);
 
 // out: splits == 1 -> nullptr workspace allowed and the tile goes straight to `grad` (overwrite
 // or accumulate); otherwise slices go to ws[splits][M][N] and a second kernel folds them.
 hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
+hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
+                                   int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 // partial[B][tiles_m*tiles_n] then finalize into sqnorm

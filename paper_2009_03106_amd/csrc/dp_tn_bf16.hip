@@ -598,7 +598,9 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 }  // namespace
 
 TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
+    if (dma_clipped_ok(B, T, M, N)) return plan_clipped_bf16_dma(B, T, M, N);
     TnPlan p;
+    p.dma = false;
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
@@ -659,7 +661,7 @@ TnPlan plan_direct_bf16(int T, int M, int N) {
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     p.segmented = (T >= kSegMinT);
-    p.big = false;
+    p.big = false; p.dma = false;
     p.splits = 1; p.kchunk = 0; p.epu = 1;
     return p;
 }
@@ -668,6 +670,7 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
                                int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st) {
     const int64_t n = (int64_t)M * N;
     const int tiles = p.tiles_m * p.tiles_n;
+    if (p.dma) return launch_clipped_bf16_dma(p, A, G, clip, B, T, M, N, accumulate, grad, ws, st);
     if (p.big) {
         BigArgs a;
         a.A = A; a.G = G; a.clip = clip;

@@ -123,7 +123,7 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 TnPlan plan_clipped_f32(int B, int T, int M, int N) {
     const int64_t K = (int64_t)B * T;
     TnPlan p;
-    p.segmented = false; p.epu = 0; p.big = false;
+    p.segmented = false; p.epu = 0; p.big = false; p.dma = false;
     p.tile_m = FBM; p.tile_n = FBN;
     p.tiles_m = ceil_div(M, FBM); p.tiles_n = ceil_div(N, FBN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
@@ -143,7 +143,7 @@ TnPlan plan_clipped_f32(int B, int T, int M, int N) {
 TnPlan plan_direct_f32(int T, int M, int N) {
     (void)T;
     TnPlan p;
-    p.segmented = false; p.epu = 0; p.big = false;
+    p.segmented = false; p.epu = 0; p.big = false; p.dma = false;
     p.tile_m = FBM; p.tile_n = FBN;
     p.tiles_m = ceil_div(M, FBM); p.tiles_n = ceil_div(N, FBN);
     p.splits = 1; p.kchunk = 0;

@@ -142,6 +142,8 @@ RAGGED = [
     (3, 1, 5, 3), (7, 1, 130, 67), (5, 1, 1024, 8),
     (2, 3, 8, 8), (3, 17, 72, 40), (2, 70, 136, 264), (3, 129, 200, 24), (2, 257, 64, 320),
     (1, 64, 7, 9), (2, 33, 129, 65),
+    # large aligned tiles with ragged edges (256 x 256 clipped-sum kernels), T % 32 == 0 and T % 8 == 0 only
+    (5, 64, 456, 248), (3, 96, 264, 520), (3, 40, 456, 248), (9, 32, 512, 256),
 ]
 
 
