@@ -1,16 +1,17 @@
 // Large-tile bf16 clipped sum  sum_i c_i A_i^T G_i  for big aligned layers.
 //
-// gfx950-specific data path, no VALU work in the main loop:
+// gfx950-specific data path with (almost) no VALU work in the main loop:
 //   * global -> LDS copies go straight into LDS (global_load_lds_dwordx4): a
-//     wave instruction moves two 512-byte rows of a K-major tile, as they lie
-//     in memory, into 1 KB of LDS.  Four 32-row stages are kept in LDS, three
-//     of them in flight while one is consumed.
+//     wave instruction moves 1 KB of a K-major tile, as it lies in memory
+//     (two 512-byte rows of A or four 256-byte rows of G).  Three 32-row
+//     stages are kept in LDS, two of them in flight while one is consumed.
 //   * the 16-bit transpose the MFMA needs (a lane must hold consecutive k for
 //     one column, memory has consecutive columns for one k) is done by the
 //     LDS read itself (ds_read_b64_tr_b16): 16 lanes read a 4(k) x 16(col)
 //     patch and each lane gets the 4 k values of one column.
-//   * 256 x 256 output tile per workgroup, one workgroup per compute unit,
-//     each of the 4 waves owns 128 x 128 (256 accumulator registers).
+//   * 256 x 128 output tile per workgroup (4 waves, 128 x 64 each = 128
+//     accumulator registers), two workgroups per compute unit so that one
+//     can compute while the other waits at its stage barrier.
 //
 // Clip factors are applied to the fp32 accumulators, not to the bf16 inputs:
 // the tile holds  (1 / c_cur) * sum_{j <= cur} c_j g_j ; when the rows of the
@@ -26,16 +27,18 @@ namespace dpk {
 
 namespace {
 
-constexpr int DM = 256, DN = 256;     // output tile
+constexpr int DM = 256, DN = 128;     // output tile
 constexpr int DK = 32;                // rows per stage
-constexpr int NST = 4;                // stages resident in LDS
-constexpr int STAGE_BYTES = 2 * DK * DM * 2;     // A part then G part: 32 KB
-constexpr int OPND_BYTES = DK * DM * 2;          // 16 KB
+constexpr int NST = 3;                // stages resident in LDS
+constexpr int A_BYTES = DK * DM * 2;             // 16 KB, rows of 512 B
+constexpr int G_BYTES = DK * DN * 2;             //  8 KB, rows of 256 B
+constexpr int STAGE_BYTES = A_BYTES + G_BYTES;   // 24 KB
+constexpr int LOADS_PER_STAGE = 6;               // per wave: 4 of A, 2 of G
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
-typedef short v8i16 __attribute__((ext_vector_type(8)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 #define GLB_PTR(T) const __attribute__((address_space(1))) T*
+#define TR_READ(dst, addr, off) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off))
 
 struct DmaArgs {
     const uint16_t* A;
@@ -56,11 +59,13 @@ struct DmaArgs {
 // transposing read touches then fall into four different 32-byte bank windows.
 __device__ __forceinline__ int chunk_swz(int r) { return (r & 3) << 1; }
 
-__global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_dma(DmaArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];   // 128 KB
+__global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_dma(DmaArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];   // 72 KB
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles = a.tiles_m * a.tiles_n;
+    // workgroup b runs on XCD b % 8: give each XCD a contiguous run of (slice, tile) pairs so that
+    // its workgroups stream the same rows of A and G through one L2
     const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
     if (L >= tiles * a.splits) return;
     const int z = L / tiles, tile = L - z * tiles;
@@ -72,37 +77,34 @@ __global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_dma(DmaArgs a) {
     if (n_stages <= 0) return;
     const int spe = a.T / DK;                       // stages per example
 
-    // ---- global -> LDS: wave w copies rows 8w..8w+7 of the A part and of the G part of a stage,
-    //      4 instructions each; instruction u covers rows 8w+2u, 8w+2u+1 (lane / 32 picks the row)
-    const int lr = lane >> 5, cp = lane & 31;
-    int offA[2], offG[2];                           // element offsets of this lane's source chunk for u even / odd
+    // ---- global -> LDS.  Wave w copies rows 8w..8w+7 of a stage.
+    //   A: 4 instructions, instruction u covers rows 8w+2u, 8w+2u+1 (lane / 32 picks the row, lane % 32 the chunk)
+    //   G: 2 instructions, instruction u covers rows 8w+4u .. 8w+4u+3 (lane / 16 picks the row, lane % 16 the chunk)
+    int offA[2];                                    // element offset of this lane's source chunk for u even / odd
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
-        const int r = 2 * par + lr;                 // r & 3 of the row this lane fills
-        const int c = cp ^ chunk_swz(r);
-        int ca = m0 + c * 8, cgn = n0 + c * 8;
+        const int r = 2 * par + (lane >> 5);        // r & 3 of the row this lane fills
+        int ca = m0 + ((lane & 31) ^ chunk_swz(r)) * 8;
         if (ca >= a.M) ca = m0;                     // out-of-range columns only feed output rows that are never stored
-        if (cgn >= a.N) cgn = n0;
         offA[par] = ca;
-        offG[par] = cgn;
     }
-    const uint16_t* pA = a.A + ((size_t)s_begin * DK + wave * 8 + lr) * a.M;    // row of this lane for u = 0
-    const uint16_t* pG = a.G + ((size_t)s_begin * DK + wave * 8 + lr) * a.N;
+    int offG = n0 + ((lane & 15) ^ chunk_swz(lane >> 4)) * 8;
+    if (offG >= a.N) offG = n0;
+    const uint16_t* pA = a.A + ((size_t)s_begin * DK + wave * 8 + (lane >> 5)) * a.M;
+    const uint16_t* pG = a.G + ((size_t)s_begin * DK + wave * 8 + (lane >> 4)) * a.N + offG;
     const size_t stepA = (size_t)DK * a.M, stepG = (size_t)DK * a.N;            // per stage
-    const size_t row2A = (size_t)2 * a.M, row2G = (size_t)2 * a.N;              // per instruction (two rows)
+    const size_t row2A = (size_t)2 * a.M, row4G = (size_t)4 * a.N;              // per instruction
 
     auto issue = [&](int buf) {
-        LDS_PTR(unsigned char) base = (LDS_PTR(unsigned char))lds + buf * STAGE_BYTES + wave * 8 * 512;
+        LDS_PTR(unsigned char) base = (LDS_PTR(unsigned char))lds + buf * STAGE_BYTES;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 4; ++u)
             __builtin_amdgcn_global_load_lds((GLB_PTR(void))(pA + u * row2A + offA[u & 1]),
-                                             (LDS_PTR(void))(base + u * 1024), 16, 0, 0);
-        }
+                                             (LDS_PTR(void))(base + wave * 4096 + u * 1024), 16, 0, 0);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            __builtin_amdgcn_global_load_lds((GLB_PTR(void))(pG + u * row2G + offG[u & 1]),
-                                             (LDS_PTR(void))(base + OPND_BYTES + u * 1024), 16, 0, 0);
-        }
+        for (int u = 0; u < 2; ++u)
+            __builtin_amdgcn_global_load_lds((GLB_PTR(void))(pG + u * row4G),
+                                             (LDS_PTR(void))(base + A_BYTES + wave * 2048 + u * 1024), 16, 0, 0);
         pA += stepA;
         pG += stepG;
     };
@@ -113,83 +115,101 @@ __global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_dma(DmaArgs a) {
     const int g16 = lane >> 4, s16 = lane & 15;
     const int half = g16 >> 1;                      // lanes 32..63 hold k + 8 .. k + 15 of a 16-wide k step
     const int rsrc = 8 * half + (s16 >> 2);         // row inside the k step for the first read (second read: + 4)
-    int rdA[4], rdG[4];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
+    uint32_t rdA[4], rdG[2];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int ma = wm * 128 + i * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);      // column (element) of the 8-byte piece
-        const int na = wn * 128 + i * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
-        rdA[i] = rsrc * 512 + ((((ma >> 3) ^ chunk_swz(rsrc)) << 4) | ((ma & 7) << 1));
-        rdG[i] = OPND_BYTES + rsrc * 512 + ((((na >> 3) ^ chunk_swz(rsrc)) << 4) | ((na & 7) << 1));
+        rdA[i] = lds_base + rsrc * 512 + ((((ma >> 3) ^ chunk_swz(rsrc)) << 4) | ((ma & 7) << 1));
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int na = wn * 64 + j * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
+        rdG[j] = lds_base + A_BYTES + rsrc * 256 + ((((na >> 3) ^ chunk_swz(rsrc)) << 4) | ((na & 7) << 1));
     }
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // prologue: up to NST - 1 stages in flight
+    // prologue: NST - 1 stages in flight
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p)
         if (p < n_stages) issue(p);
 
     int ex = s_begin / spe;
     int sub = s_begin - ex * spe;
-    float c_cur = a.clip[ex];
+    // clip factors are read with scalar loads (constant address space, uniform index): a vector load here
+    // would tie every later vmcnt wait to the copies in flight
+    const __attribute__((address_space(4))) float* clip_s = (const __attribute__((address_space(4))) float*)a.clip;
+    float c_cur = clip_s[ex];
 
-    int st = 0;
-    while (st < n_stages) {
-        // the stages left in the current example: plain copy / read / MFMA loop, no other vector work
-        const int run_end = min(n_stages, st + (spe - sub));
-        for (; st < run_end; ++st) {
-            // stage st must have landed; the copies of later stages may stay in flight (8 per stage and wave)
-            const int ahead = min(n_stages - 1 - st, NST - 2);
-            if (ahead >= 2) __builtin_amdgcn_s_waitcnt(0x4F70);        // vmcnt(16)
-            else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
-            else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
-            __syncthreads();
-            if (st + NST - 1 < n_stages) issue((st + NST - 1) % NST);
+    for (int st = 0; st < n_stages; ++st) {
+        // stage st must have landed; the copies of the next stage may stay in flight
+        if (st + 1 < n_stages) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_STAGE);     // vmcnt(6)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);                                         // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        if (st + NST - 1 < n_stages) issue((st + NST - 1) % NST);
 
-            LDS_PTR(unsigned char) sb = (LDS_PTR(unsigned char))lds + (st % NST) * STAGE_BYTES;
-#pragma unroll
-            for (int ks = 0; ks < DK / 16; ++ks) {
-                bf16x8 fa[4], fb[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(sb + rdA[i] + ks * 16 * 512));
-                    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(sb + rdA[i] + ks * 16 * 512 + 4 * 512));
-                    fa[i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(sb + rdG[j] + ks * 16 * 512));
-                    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(sb + rdG[j] + ks * 16 * 512 + 4 * 512));
-                    fb[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-            }
-        }
-        sub = 0;
-        ++ex;
-        if (st < n_stages) {
-            // the next example starts: rescale the running tile
-            const float c_next = a.clip[ex];
+        if (sub == spe) {
+            // first stage of the next example: rescale the running tile
+            sub = 0;
+            ++ex;
+            const float c_next = clip_s[ex];
             if (c_next != c_cur) {
                 const float ratio = c_cur / c_next;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < 2; ++j)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
             }
             c_cur = c_next;
+        }
+        ++sub;
+
+        const uint32_t sb = (uint32_t)(st % NST) * STAGE_BYTES;
+        uint32_t adA[4], adG[2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) adA[i] = sb + rdA[i];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) adG[j] = sb + rdG[j];
+        // The transposing reads are issued as inline assembly so that they are ordered by the explicit
+        // lgkmcnt waits below and are not tied to the completion of the copies still in flight.
+        // k step ks covers rows 16 ks .. 16 ks + 15 of the stage (A rows are 512 B, G rows 256 B apart).
+        v4i16 lo[2][6], hi[2][6];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { TR_READ(lo[0][i], adA[i], 0); TR_READ(hi[0][i], adA[i], 4 * 512); }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) { TR_READ(lo[0][4 + j], adG[j], 0); TR_READ(hi[0][4 + j], adG[j], 4 * 256); }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { TR_READ(lo[1][i], adA[i], 16 * 512); TR_READ(hi[1][i], adA[i], 20 * 512); }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) { TR_READ(lo[1][4 + j], adG[j], 16 * 256); TR_READ(hi[1][4 + j], adG[j], 20 * 256); }
+        // LDS reads return in order: 24 issued, the first 12 are back once at most 12 are outstanding
+        asm volatile("s_waitcnt lgkmcnt(12)" : "+v"(lo[0][0]), "+v"(hi[0][0]), "+v"(lo[0][1]), "+v"(hi[0][1]),
+                     "+v"(lo[0][2]), "+v"(hi[0][2]), "+v"(lo[0][3]), "+v"(hi[0][3]), "+v"(lo[0][4]), "+v"(hi[0][4]),
+                     "+v"(lo[0][5]), "+v"(hi[0][5]));
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks == 1)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[1][0]), "+v"(hi[1][0]), "+v"(lo[1][1]), "+v"(hi[1][1]),
+                             "+v"(lo[1][2]), "+v"(hi[1][2]), "+v"(lo[1][3]), "+v"(hi[1][3]), "+v"(lo[1][4]), "+v"(hi[1][4]),
+                             "+v"(lo[1][5]), "+v"(hi[1][5]));
+            bf16x8 f[6];
+#pragma unroll
+            for (int x = 0; x < 6; ++x)
+                f[x] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[ks][x], hi[ks][x], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[4 + j], acc[i][j], 0, 0, 0);
         }
     }
 
@@ -199,8 +219,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_dma(DmaArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = n0 + wn * 128 + j * 32 + lrow;
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn * 64 + j * 32 + lrow;
             if (n >= a.N) continue;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -232,8 +252,8 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     const int64_t stages = (int64_t)B * T / DK;
-    // one workgroup per compute unit: as many K slices as fit into 256 workgroups, at least 8 stages each
-    int64_t splits = 256 / tiles;
+    // two workgroups per compute unit: as many K slices as fit into 512 workgroups, at least 8 stages each
+    int64_t splits = 512 / tiles;
     if (splits < 1) splits = 1;
     const int64_t max_splits = (stages + 7) / 8;
     if (splits > max_splits) splits = max_splits;
