@@ -3,15 +3,17 @@
 // gfx950-specific data path with (almost) no VALU work in the main loop:
 //   * global -> LDS copies go straight into LDS (global_load_lds_dwordx4): a
 //     wave instruction moves 1 KB of a K-major tile, as it lies in memory
-//     (two 512-byte rows of A or four 256-byte rows of G).  Three 32-row
-//     stages are kept in LDS, two of them in flight while one is consumed.
+//     (two 512-byte rows).  Four 32-row stages are kept in LDS, three of them
+//     in flight while one is consumed.
 //   * the 16-bit transpose the MFMA needs (a lane must hold consecutive k for
 //     one column, memory has consecutive columns for one k) is done by the
 //     LDS read itself (ds_read_b64_tr_b16): 16 lanes read a 4(k) x 16(col)
 //     patch and each lane gets the 4 k values of one column.
-//   * 256 x 128 output tile per workgroup (4 waves, 128 x 64 each = 128
-//     accumulator registers), two workgroups per compute unit so that one
-//     can compute while the other waits at its stage barrier.
+//   * 256 x 256 output tile per workgroup of 8 waves (128 x 64 each = 128
+//     accumulator registers, two waves per SIMD), one workgroup per compute
+//     unit.  The tile size is set by the L2: at 256 x 128 the kernel ran into
+//     the ~10 TB/s the L2s deliver to the compute units (85 flop per byte);
+//     256 x 256 needs 128 flop per byte.
 //
 // Clip factors are applied to the fp32 accumulators, not to the bf16 inputs:
 // the tile holds  (1 / c_cur) * sum_{j <= cur} c_j g_j ; when the rows of the
@@ -27,18 +29,18 @@ namespace dpk {
 
 namespace {
 
-constexpr int DM = 256, DN = 128;     // output tile
+constexpr int DM = 256, DN = 256;     // output tile
+constexpr int DTHREADS = 512;         // 8 waves: 2 (M) x 4 (N)
 constexpr int DK = 32;                // rows per stage
-constexpr int NST = 3;                // stages resident in LDS
+constexpr int NST = 4;                // stages resident in LDS
 constexpr int A_BYTES = DK * DM * 2;             // 16 KB, rows of 512 B
-constexpr int G_BYTES = DK * DN * 2;             //  8 KB, rows of 256 B
-constexpr int STAGE_BYTES = A_BYTES + G_BYTES;   // 24 KB
-constexpr int LOADS_PER_STAGE = 6;               // per wave: 4 of A, 2 of G
+constexpr int G_BYTES = DK * DN * 2;             // 16 KB, rows of 512 B
+constexpr int STAGE_BYTES = A_BYTES + G_BYTES;   // 32 KB
+constexpr int LOADS_PER_STAGE = 4;               // per wave: 2 of A, 2 of G
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 #define GLB_PTR(T) const __attribute__((address_space(1))) T*
-#define TR_READ(dst, addr, off) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off))
 
 struct DmaArgs {
     const uint16_t* A;
@@ -55,12 +57,14 @@ struct DmaArgs {
     int accumulate;
 };
 
-// 16-byte chunk c of tile row r sits at chunk position c ^ ((r & 3) << 1): the four rows a
-// transposing read touches then fall into four different 32-byte bank windows.
-__device__ __forceinline__ int chunk_swz(int r) { return (r & 3) << 1; }
+// 16-byte chunk c of tile row r sits at chunk position c ^ ((r & 3) << 2).  A transposing read of 32
+// lanes touches 4 rows x two 32-byte pieces (columns m .. m+15 and m+16 .. m+31); rows are 512 B apart, so
+// without the xor all of them would start in the same bank.  With it the 8 pieces cover 256 consecutive
+// bytes modulo the bank period and the read is conflict free.
+__device__ __forceinline__ int chunk_swz(int r) { return (r & 3) << 2; }
 
-__global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_dma(DmaArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];   // 72 KB
+__global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];   // 128 KB
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles = a.tiles_m * a.tiles_n;
@@ -77,55 +81,58 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_dma(DmaArgs a) {
     if (n_stages <= 0) return;
     const int spe = a.T / DK;                       // stages per example
 
-    // ---- global -> LDS.  Wave w copies rows 8w..8w+7 of a stage.
-    //   A: 4 instructions, instruction u covers rows 8w+2u, 8w+2u+1 (lane / 32 picks the row, lane % 32 the chunk)
-    //   G: 2 instructions, instruction u covers rows 8w+4u .. 8w+4u+3 (lane / 16 picks the row, lane % 16 the chunk)
-    int offA[2];                                    // element offset of this lane's source chunk for u even / odd
+    // ---- global -> LDS.  Wave w copies rows 4w..4w+3 of the A part and of the G part of a stage, two
+    //      instructions each; instruction u covers rows 4w+2u, 4w+2u+1 (lane / 32 picks the row, lane % 32 the chunk)
+    int offA[2], offG[2];                           // element offset of this lane's source chunk for u = 0 / 1
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        const int r = 2 * par + (lane >> 5);        // r & 3 of the row this lane fills
-        int ca = m0 + ((lane & 31) ^ chunk_swz(r)) * 8;
-        if (ca >= a.M) ca = m0;                     // out-of-range columns only feed output rows that are never stored
-        offA[par] = ca;
+    for (int u = 0; u < 2; ++u) {
+        const int r = 2 * u + (lane >> 5);          // r & 3 of the row this lane fills
+        const int c = (lane & 31) ^ chunk_swz(r);
+        int ca = m0 + c * 8, cn = n0 + c * 8;
+        if (ca >= a.M) ca = m0;                     // out-of-range columns only feed output rows / columns that are never stored
+        if (cn >= a.N) cn = n0;
+        offA[u] = ca;
+        offG[u] = cn;
     }
-    int offG = n0 + ((lane & 15) ^ chunk_swz(lane >> 4)) * 8;
-    if (offG >= a.N) offG = n0;
-    const uint16_t* pA = a.A + ((size_t)s_begin * DK + wave * 8 + (lane >> 5)) * a.M;
-    const uint16_t* pG = a.G + ((size_t)s_begin * DK + wave * 8 + (lane >> 4)) * a.N + offG;
+    const uint16_t* pA = a.A + ((size_t)s_begin * DK + wave * 4 + (lane >> 5)) * a.M;
+    const uint16_t* pG = a.G + ((size_t)s_begin * DK + wave * 4 + (lane >> 5)) * a.N;
     const size_t stepA = (size_t)DK * a.M, stepG = (size_t)DK * a.N;            // per stage
-    const size_t row2A = (size_t)2 * a.M, row4G = (size_t)4 * a.N;              // per instruction
+    const size_t row2A = (size_t)2 * a.M, row2G = (size_t)2 * a.N;              // per instruction
 
+    // The copies are issued as inline assembly: the compiler then does not know that they write LDS and
+    // does not make every LDS read wait for all copies in flight; the waits for them are the explicit
+    // vmcnt waits in front of the stage barriers below.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
     auto issue = [&](int buf) {
-        LDS_PTR(unsigned char) base = (LDS_PTR(unsigned char))lds + buf * STAGE_BYTES;
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            __builtin_amdgcn_global_load_lds((GLB_PTR(void))(pA + u * row2A + offA[u & 1]),
-                                             (LDS_PTR(void))(base + wave * 4096 + u * 1024), 16, 0, 0);
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + buf * STAGE_BYTES + wave * 2048);
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-            __builtin_amdgcn_global_load_lds((GLB_PTR(void))(pG + u * row4G),
-                                             (LDS_PTR(void))(base + A_BYTES + wave * 2048 + u * 1024), 16, 0, 0);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(base + u * 1024), "v"(pA + u * row2A + offA[u]) : "memory", "m0");
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(base + A_BYTES + u * 1024), "v"(pG + u * row2G + offG[u]) : "memory", "m0");
         pA += stepA;
         pG += stepG;
     };
 
     // ---- LDS -> MFMA operands.  Lane l of a 16-lane group: source row j = (l % 16) / 4, source column
     //      piece q = l % 4; after the transposing read the lane holds 4 k values of column l % 16.
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 2, wn = wave & 3;
     const int g16 = lane >> 4, s16 = lane & 15;
     const int half = g16 >> 1;                      // lanes 32..63 hold k + 8 .. k + 15 of a 16-wide k step
     const int rsrc = 8 * half + (s16 >> 2);         // row inside the k step for the first read (second read: + 4)
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
     uint32_t rdA[4], rdG[2];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int ma = wm * 128 + i * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);      // column (element) of the 8-byte piece
-        rdA[i] = lds_base + rsrc * 512 + ((((ma >> 3) ^ chunk_swz(rsrc)) << 4) | ((ma & 7) << 1));
+        rdA[i] = rsrc * 512 + ((((ma >> 3) ^ chunk_swz(rsrc)) << 4) | ((ma & 7) << 1));
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int na = wn * 64 + j * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
-        rdG[j] = lds_base + A_BYTES + rsrc * 256 + ((((na >> 3) ^ chunk_swz(rsrc)) << 4) | ((na & 7) << 1));
+        rdG[j] = A_BYTES + rsrc * 512 + ((((na >> 3) ^ chunk_swz(rsrc)) << 4) | ((na & 7) << 1));
     }
 
     f32x16 acc[4][2];
@@ -136,30 +143,56 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_dma(DmaArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    int ex = s_begin / spe;
+    int sub = s_begin - ex * spe;
+    // The clip factors of the examples this workgroup walks through are kept one per lane in a register
+    // (loaded before the copies start) and picked with v_readlane: a scalar or vector load inside the loop
+    // would make the compiler wait for every LDS read / copy in flight at each use.
+    const int ex0 = ex;                             // a K slice spans at most 64 examples (see the plan)
+    float vclip = a.clip[min(ex0 + lane, a.B - 1)];
+    float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
+
     // prologue: NST - 1 stages in flight
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p)
         if (p < n_stages) issue(p);
 
-    int ex = s_begin / spe;
-    int sub = s_begin - ex * spe;
-    // clip factors are read with scalar loads (constant address space, uniform index): a vector load here
-    // would tie every later vmcnt wait to the copies in flight
-    const __attribute__((address_space(4))) float* clip_s = (const __attribute__((address_space(4))) float*)a.clip;
-    float c_cur = clip_s[ex];
+    // Software pipeline over k steps (two per stage): while the MFMAs of one k step run, the LDS reads of
+    // the next one are in flight, also across the stage boundary.  The barrier that makes stage st + 1
+    // visible therefore sits in the middle of stage st.
+    auto read_kstep = [&](bf16x8 (&f)[6], uint32_t sb, int row) {
+        LDS_PTR(unsigned char) b = (LDS_PTR(unsigned char))lds + sb + row * 512;
+#pragma unroll
+        for (int x = 0; x < 6; ++x) {
+            const uint32_t off = x < 4 ? rdA[x & 3] : rdG[x & 1];
+            const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off));
+            const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off + 4 * 512));
+            f[x] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    auto mfma_kstep = [&](const bf16x8 (&f)[6]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[4 + j], acc[i][j], 0, 0, 0);
+    };
+
+    // stage 0 must have landed (the copies of stages 1, 2 may stay in flight)
+    if (n_stages >= 3) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS_PER_STAGE));
+    else if (n_stages == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_STAGE);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    bf16x8 f0[6], f1[6];                            // fragments of k step 0 / k step 1: 0..3 of A, 4..5 of G
+    read_kstep(f0, 0u, 0);
 
     for (int st = 0; st < n_stages; ++st) {
-        // stage st must have landed; the copies of the next stage may stay in flight
-        if (st + 1 < n_stages) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_STAGE);     // vmcnt(6)
-        else __builtin_amdgcn_s_waitcnt(0x0F70);                                         // vmcnt(0)
-        __builtin_amdgcn_s_barrier();
-        if (st + NST - 1 < n_stages) issue((st + NST - 1) % NST);
-
+        const uint32_t sb = (uint32_t)(st % NST) * STAGE_BYTES;
         if (sub == spe) {
             // first stage of the next example: rescale the running tile
             sub = 0;
             ++ex;
-            const float c_next = clip_s[ex];
+            const float c_next = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), ex - ex0));
             if (c_next != c_cur) {
                 const float ratio = c_cur / c_next;
 #pragma unroll
@@ -172,45 +205,22 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_dma(DmaArgs a) {
             c_cur = c_next;
         }
         ++sub;
-
-        const uint32_t sb = (uint32_t)(st % NST) * STAGE_BYTES;
-        uint32_t adA[4], adG[2];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) adA[i] = sb + rdA[i];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) adG[j] = sb + rdG[j];
-        // The transposing reads are issued as inline assembly so that they are ordered by the explicit
-        // lgkmcnt waits below and are not tied to the completion of the copies still in flight.
-        // k step ks covers rows 16 ks .. 16 ks + 15 of the stage (A rows are 512 B, G rows 256 B apart).
-        v4i16 lo[2][6], hi[2][6];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { TR_READ(lo[0][i], adA[i], 0); TR_READ(hi[0][i], adA[i], 4 * 512); }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) { TR_READ(lo[0][4 + j], adG[j], 0); TR_READ(hi[0][4 + j], adG[j], 4 * 256); }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { TR_READ(lo[1][i], adA[i], 16 * 512); TR_READ(hi[1][i], adA[i], 20 * 512); }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) { TR_READ(lo[1][4 + j], adG[j], 16 * 256); TR_READ(hi[1][4 + j], adG[j], 20 * 256); }
-        // LDS reads return in order: 24 issued, the first 12 are back once at most 12 are outstanding
-        asm volatile("s_waitcnt lgkmcnt(12)" : "+v"(lo[0][0]), "+v"(hi[0][0]), "+v"(lo[0][1]), "+v"(hi[0][1]),
-                     "+v"(lo[0][2]), "+v"(hi[0][2]), "+v"(lo[0][3]), "+v"(hi[0][3]), "+v"(lo[0][4]), "+v"(hi[0][4]),
-                     "+v"(lo[0][5]), "+v"(hi[0][5]));
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            if (ks == 1)
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[1][0]), "+v"(hi[1][0]), "+v"(lo[1][1]), "+v"(hi[1][1]),
-                             "+v"(lo[1][2]), "+v"(hi[1][2]), "+v"(lo[1][3]), "+v"(hi[1][3]), "+v"(lo[1][4]), "+v"(hi[1][4]),
-                             "+v"(lo[1][5]), "+v"(hi[1][5]));
-            bf16x8 f[6];
-#pragma unroll
-            for (int x = 0; x < 6; ++x)
-                f[x] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[ks][x], hi[ks][x], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[4 + j], acc[i][j], 0, 0, 0);
+        read_kstep(f1, sb, 16);
+        mfma_kstep(f0);
+        // the reads of k step 1 were issued a whole k step ago: retire them before queueing new ones, so
+        // that the MFMAs of k step 1 do not have to wait for the reads issued below (LDS reads return in order)
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);                                              // lgkmcnt(0)
+        if (st + 1 < n_stages) {
+            // stage st + 1 must have landed; the copies of stage st + 2 may stay in flight
+            if (st + 2 < n_stages) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_STAGE);
+            else __builtin_amdgcn_s_waitcnt(0x0F70);
+            __builtin_amdgcn_s_barrier();
+            // every wave is past its reads of stage st - 1: its buffer takes stage st + 3
+            if (st + NST - 1 < n_stages) issue((st + NST - 1) % NST);
+            read_kstep(f0, (uint32_t)((st + 1) % NST) * STAGE_BYTES, 0);
         }
+        mfma_kstep(f1);
     }
 
     // the tile holds (1 / c_cur) * sum: finish with the last example's factor
@@ -252,12 +262,14 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     const int64_t stages = (int64_t)B * T / DK;
-    // two workgroups per compute unit: as many K slices as fit into 512 workgroups, at least 8 stages each
-    int64_t splits = 512 / tiles;
+    // one workgroup per compute unit: as many K slices as fit into 256 workgroups, at least 8 stages each
+    int64_t splits = 256 / tiles;
     if (splits < 1) splits = 1;
     const int64_t max_splits = (stages + 7) / 8;
     if (splits > max_splits) splits = max_splits;
-    const int64_t sps = (stages + splits - 1) / splits;
+    int64_t sps = (stages + splits - 1) / splits;
+    const int64_t spe = T / DK;
+    if (sps > 63 * spe) sps = 63 * spe;               // a slice may touch at most 64 examples (one clip factor per lane)
     p.kchunk = (int)(sps * DK);
     p.splits = (int)((stages + sps - 1) / sps);
     return p;
@@ -276,7 +288,7 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    k_tn_bf16_dma<<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+    k_tn_bf16_dma<<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
