@@ -158,6 +158,7 @@ GramPlan plan_gram_bf16(int T, int d_in, int d_out) {
 
 hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
                             bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+    if (gram_dma_ok(T, d_in, d_out)) return launch_gram_bf16_dma(p, A, G, B, T, d_in, d_out, accumulate, sqnorm, partial, st);
     GramArgs a;
     a.A = A; a.G = G; a.partial = partial;
     a.T = T; a.d_in = d_in; a.d_out = d_out;

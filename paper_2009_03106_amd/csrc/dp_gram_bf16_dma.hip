@@ -1,0 +1,188 @@
+// Gram path of the per-example squared norm for aligned bf16 layers
+// (d_in % 64 == 0, d_out % 64 == 0, T > 64):
+//     ||A_i^T G_i||_F^2 = sum_{t,s} (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}.
+// Same decomposition as the generic Gram kernel (one workgroup per example
+// and upper-triangular pair of 128-row tiles, both Gram tiles kept in MFMA
+// accumulators of identical layout, multiplied lane by lane and reduced), with
+// the gfx950 data path:
+//   * row tiles are copied global -> LDS directly (global_load_lds_dwordx4, a
+//     wave instruction moves 8 rows x 128 B), double buffered; the chunk
+//     permutation that makes the 16-byte LDS reads conflict free is applied to
+//     the source addresses of the copy;
+//   * workgroups of one example are dealt to the same XCD (workgroup b runs on
+//     XCD b % 8), so the up to four re-reads of every row tile hit that XCD's
+//     L2 instead of going out to memory;
+//   * two workgroups per compute unit, so one computes while the other waits
+//     at its stage barrier.
+// Rows t >= T of a ragged last tile are read from a clamped (valid) row and
+// masked out of the final product.
+#include "dp_common.h"
+#include "dp_internal.h"
+
+namespace dpk {
+
+namespace {
+
+constexpr int GT = 128;                 // rows of T per tile
+constexpr int GK = 64;                  // contraction elements per stage (128 B per row)
+constexpr int TILE_BYTES = GT * GK * 2; // 16 KB
+constexpr int GSTAGE = 2 * TILE_BYTES;  // t-tile then s-tile
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+
+struct GramDmaArgs {
+    const uint16_t* A;
+    const uint16_t* G;
+    float* partial;      // [B][npairs]
+    int B, T, d_in, d_out;
+    int nt, npairs;
+    int per_xcd;
+};
+
+// chunk c (16 B) of tile row r sits at chunk position c ^ ((r >> 1) & 7): 16 consecutive rows reading the
+// same logical chunk then cover all 64 banks once (row parity selects the upper or lower 128 bytes)
+__device__ __forceinline__ int gram_swz(int r) { return (r >> 1) & 7; }
+
+__global__ __launch_bounds__(kThreads, 2) void k_gram_bf16_dma(GramDmaArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * GSTAGE];   // 64 KB
+    __shared__ float red[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
+    if (L >= a.B * a.npairs) return;
+    const int ex = L / a.npairs;
+    int pair = L - ex * a.npairs;                       // position in the row-major list of (tt, ss), tt <= ss
+    int tt = 0;
+    while (pair >= a.nt - tt) { pair -= a.nt - tt; ++tt; }
+    const int ss = tt + pair;
+    const bool diag = (tt == ss);
+
+    const int sa = a.d_in / GK, sg = a.d_out / GK;      // stages of the A phase and of the G phase
+    const int n_stages = sa + sg;
+
+    // ---- copies: wave w moves rows 32w .. 32w+31 of the t-tile and of the s-tile, 4 instructions each
+    //      (instruction u: rows 32w + 8u .. + 7; lane / 8 picks the row, lane % 8 the chunk position)
+    const int lrow8 = lane >> 3, cp = lane & 7;
+    int row_t[4], row_s[4], chunk16[4];             // tile rows (clamped to valid rows) and source chunk byte offsets
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int r = wave * 32 + u * 8 + lrow8;                       // row inside the tile
+        chunk16[u] = (cp ^ gram_swz(r)) << 4;                          // source chunk for this LDS slot
+        row_t[u] = min(tt * GT + r, a.T - 1);
+        row_s[u] = min(ss * GT + r, a.T - 1);
+    }
+    const uint16_t* baseA = a.A + (size_t)ex * a.T * a.d_in;          // uniform example bases; lane offsets stay 32-bit
+    const uint16_t* baseG = a.G + (size_t)ex * a.T * a.d_out;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
+    // The copies are inline assembly so that the compiler does not tie every LDS read to them; they are
+    // waited for with the explicit vmcnt wait in front of the stage barrier.
+    auto issue = [&](int st, int buf) {
+        const bool phase_g = st >= sa;
+        const int k0 = (phase_g ? st - sa : st) * GK;
+        const uint16_t* sbase = (phase_g ? baseG : baseA) + k0;
+        const uint32_t rb = (uint32_t)(phase_g ? a.d_out : a.d_in) * 2u;          // row bytes
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + buf * GSTAGE + wave * 4096);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t off = (uint32_t)row_t[u] * rb + (uint32_t)chunk16[u];
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + u * 1024), "v"(off), "s"(sbase) : "memory", "m0");
+        }
+        if (!diag) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t off = (uint32_t)row_s[u] * rb + (uint32_t)chunk16[u];
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + TILE_BYTES + u * 1024), "v"(off), "s"(sbase) : "memory", "m0");
+            }
+        }
+    };
+
+    // ---- MFMA roles: 2 x 2 waves, each owns 64 x 64 of the 128 x 128 tile pair
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    int rd_t[2], rd_s[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int rt = wm * 64 + i * 32 + lrow, rs = wn * 64 + i * 32 + lrow;
+        rd_t[i] = rt * 128 + ((lhalf ^ gram_swz(rt)) << 4);
+        rd_s[i] = (diag ? 0 : TILE_BYTES) + rs * 128 + ((lhalf ^ gram_swz(rs)) << 4);
+    }
+    f32x16 accP[2][2], accQ[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { accP[i][j][r] = 0.f; accQ[i][j][r] = 0.f; }
+
+    auto compute = [&](int buf, f32x16 (&acc)[2][2]) {
+        const unsigned char* sb = lds + buf * GSTAGE;
+#pragma unroll
+        for (int ks = 0; ks < GK / 16; ++ks) {
+            bf16x8 fa[2], fb[2];
+            // chunk (2 ks + lhalf) ^ swz == (lhalf ^ swz) ^ (2 ks): flip bits 5-6 of the byte offset
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sb + (rd_t[i] ^ (ks << 5)));
+#pragma unroll
+            for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(sb + (rd_s[j] ^ (ks << 5)));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    issue(0, 0);
+    for (int st = 0; st < sa; ++st) {                // A A^T tile
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the copies of stage st (the only ones in flight) landed
+        __builtin_amdgcn_s_barrier();                // ... for every wave, and every wave is done reading the other buffer
+        issue(st + 1, (st + 1) & 1);                 // sg >= 1, so a next stage always exists here
+        compute(st & 1, accP);
+    }
+    for (int st = sa; st < n_stages; ++st) {         // G G^T tile
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+        if (st + 1 < n_stages) issue(st + 1, (st + 1) & 1);
+        compute(st & 1, accQ);
+    }
+
+    // ---- sum of the elementwise product; rows / columns beyond T are masked (their tiles hold clamped rows)
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = ss * GT + wn * 64 + j * 32 + lrow;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tt * GT + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                const float v = accP[i][j][r] * accQ[i][j][r];
+                s += (row < a.T && col < a.T) ? v : 0.f;
+            }
+        }
+    __syncthreads();
+    s = block_sum_256(s, red);
+    if (tid == 0) a.partial[L] = diag ? s : 2.0f * s;
+}
+
+}  // namespace
+
+bool gram_dma_ok(int T, int d_in, int d_out) {
+    const int64_t dmax = d_in > d_out ? d_in : d_out;
+    return T > 64 && (d_in % GK) == 0 && (d_out % GK) == 0 && (int64_t)T * dmax * 2 < (int64_t(1) << 31);   // 32-bit lane offsets
+}
+
+hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+    GramDmaArgs a;
+    a.A = A; a.G = G; a.partial = partial;
+    a.B = B; a.T = T; a.d_in = d_in; a.d_out = d_out;
+    a.nt = p.nt; a.npairs = p.npairs;
+    const int64_t total = (int64_t)B * p.npairs;
+    a.per_xcd = (int)((total + 7) / 8);
+    k_gram_bf16_dma<<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);
+}
+
+}  // namespace dpk

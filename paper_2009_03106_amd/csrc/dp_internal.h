@@ -60,6 +60,9 @@ struct GramPlan {
     int npairs;   // nt*(nt+1)/2 upper-triangular tile pairs per example
 };
 GramPlan plan_gram_bf16(int T, int d_in, int d_out);
+bool gram_dma_ok(int T, int d_in, int d_out);
+hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st);
 hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
                             bool accumulate, float* sqnorm, float* partial, hipStream_t st);
 
