@@ -23,6 +23,11 @@ if ROOT not in sys.path:
 
 import numpy as np  # noqa: E402
 
+# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
+# `bench.py --calib-copy`, scaled by what the same counters read for the 1 GiB copy (see profiles/).
+# None until measured for the current kernels.
+MEASURED_TRAFFIC = {}
+
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
@@ -152,6 +157,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the configuration's batch size (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a kernel of known traffic) so that a rocprofv3 "
+                         "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -164,6 +172,13 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     dp.load_library()
+
+    if args.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     w, layers = wl.generate(args.workload, B=args.batch)
     pipe = Pipeline(w, layers, torch, dp, args.path)
@@ -187,7 +202,8 @@ def main():
     else:
         ach = byts / (dur_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
-    roof.update({"traffic": None, "kernel": kname, "launches_per_step": nlayers,
+    traffic = MEASURED_TRAFFIC.get(w.name) if (args.batch is None and args.path == "auto") else None
+    roof.update({"traffic": traffic, "kernel": kname, "launches_per_step": nlayers,
                  "avg_launch_ms": dur_ms / nlayers,
                  "algorithmic_flops_per_step": flops, "algorithmic_bytes_per_step": byts})
 
@@ -229,8 +245,7 @@ def main():
         "roofline": roof, "phases": phases_out, "other_workloads": others,
     }
     if not args.no_cpu_baseline:
-        sample = {"transformer": 32, "conv": 128, "rnn": 128, "mlp": 256, "dense": 32}[w.name]
-        out["cpu_baseline"] = cpu_baseline(w.name, min(sample, B))
+        out["cpu_baseline"] = cpu_baseline(w.name, min(w.B, B))
     print(json.dumps(out))
 
 

@@ -6,7 +6,8 @@
 // accumulators of identical layout, multiplied lane by lane and reduced), with
 // the gfx950 data path:
 //   * row tiles are copied global -> LDS directly (global_load_lds_dwordx4, a
-//     wave instruction moves 8 rows x 128 B), double buffered; the chunk
+//     wave instruction moves 8 rows x 128 B), double buffered and one stage
+//     ahead; the LDS reads run one k step ahead of the MFMAs; the chunk
 //     permutation that makes the 16-byte LDS reads conflict free is applied to
 //     the source addresses of the copy;
 //   * workgroups of one example are dealt to the same XCD (workgroup b runs on
@@ -27,6 +28,8 @@ constexpr int GT = 128;                 // rows of T per tile
 constexpr int GK = 64;                  // contraction elements per stage (128 B per row)
 constexpr int TILE_BYTES = GT * GK * 2; // 16 KB
 constexpr int GSTAGE = 2 * TILE_BYTES;  // t-tile then s-tile
+constexpr int GNST = 2;                 // stages resident in LDS (64 KB: two workgroups per compute unit; a 3-stage
+                                        // ring with one workgroup per compute unit measured ~7 % slower)
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
 struct GramDmaArgs {
@@ -42,8 +45,8 @@ struct GramDmaArgs {
 // same logical chunk then cover all 64 banks once (row parity selects the upper or lower 128 bytes)
 __device__ __forceinline__ int gram_swz(int r) { return (r >> 1) & 7; }
 
-__global__ __launch_bounds__(kThreads, 2) void k_gram_bf16_dma(GramDmaArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * GSTAGE];   // 64 KB
+__global__ __launch_bounds__(kThreads, GNST == 2 ? 2 : 1) void k_gram_bf16_dma(GramDmaArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[GNST * GSTAGE];
     __shared__ float red[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -113,37 +116,58 @@ __global__ __launch_bounds__(kThreads, 2) void k_gram_bf16_dma(GramDmaArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { accP[i][j][r] = 0.f; accQ[i][j][r] = 0.f; }
 
-    auto compute = [&](int buf, f32x16 (&acc)[2][2]) {
+    // Software pipeline over k steps (4 per stage): the LDS reads of the next k step are in flight while the
+    // MFMAs of the current one run, also across the stage boundary; the stage barrier sits in front of the
+    // last k step of a stage, when every wave has retired its reads of that stage.
+    auto read_kstep = [&](bf16x8 (&f)[4], int buf, int ks) {
         const unsigned char* sb = lds + buf * GSTAGE;
+        // chunk (2 ks + lhalf) ^ swz == (lhalf ^ swz) ^ (2 ks): flip bits 5-6 of the byte offset
+#pragma unroll
+        for (int i = 0; i < 2; ++i) f[i] = *reinterpret_cast<const bf16x8*>(sb + (rd_t[i] ^ (ks << 5)));
+#pragma unroll
+        for (int j = 0; j < 2; ++j) f[2 + j] = *reinterpret_cast<const bf16x8*>(sb + (rd_s[j] ^ (ks << 5)));
+    };
+    auto mfma_kstep = [&](const bf16x8 (&f)[4], f32x16 (&acc)[2][2]) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[2 + j], acc[i][j], 0, 0, 0);
+    };
+    bf16x8 f[2][4];
+    // wait until at most `stages` later stages' copies are outstanding (4 per wave and stage on a diagonal pair, else 8)
+    auto wait_copies = [&](int stages) {
+        if (stages <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
+        else if (stages == 1) { if (diag) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F78); }   // 4 / 8
+        else { if (diag) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x4F70); }                  // 8 / 16
+    };
+    auto stage = [&](int st, f32x16 (&acc)[2][2]) {
 #pragma unroll
         for (int ks = 0; ks < GK / 16; ++ks) {
-            bf16x8 fa[2], fb[2];
-            // chunk (2 ks + lhalf) ^ swz == (lhalf ^ swz) ^ (2 ks): flip bits 5-6 of the byte offset
-#pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sb + (rd_t[i] ^ (ks << 5)));
-#pragma unroll
-            for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(sb + (rd_s[j] ^ (ks << 5)));
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): this k step's fragments (requested a k step ago)
+            if (ks + 1 < GK / 16) {
+                read_kstep(f[(ks + 1) & 1], st % GNST, ks + 1);
+            } else if (st + 1 < n_stages) {
+                // the copies of stage st + 1 must have landed; those of stage st + 2 (4 per wave on a diagonal
+                // pair, else 8) may stay in flight
+                wait_copies(min(n_stages - 2 - st, GNST - 2));
+                __builtin_amdgcn_s_barrier();                // ... for every wave, and every wave is done reading stage st
+                if (st + GNST < n_stages) issue(st + GNST, st % GNST);
+                read_kstep(f[0], (st + 1) % GNST, 0);
+            }
+            mfma_kstep(f[ks & 1], acc);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    issue(0, 0);
-    for (int st = 0; st < sa; ++st) {                // A A^T tile
-        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the copies of stage st (the only ones in flight) landed
-        __builtin_amdgcn_s_barrier();                // ... for every wave, and every wave is done reading the other buffer
-        issue(st + 1, (st + 1) & 1);                 // sg >= 1, so a next stage always exists here
-        compute(st & 1, accP);
-    }
-    for (int st = sa; st < n_stages; ++st) {         // G G^T tile
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __builtin_amdgcn_s_barrier();
-        if (st + 1 < n_stages) issue(st + 1, (st + 1) & 1);
-        compute(st & 1, accQ);
-    }
+#pragma unroll
+    for (int p = 0; p < GNST; ++p)
+        if (p < n_stages) issue(p, p);
+    wait_copies(min(n_stages, GNST) - 1);                        // stage 0 must have landed
+    __builtin_amdgcn_s_barrier();
+    read_kstep(f[0], 0, 0);
+    for (int st = 0; st < sa; ++st) stage(st, accP);              // A A^T tile
+    for (int st = sa; st < n_stages; ++st) stage(st, accQ);       // G G^T tile
 
     // ---- sum of the elementwise product; rows / columns beyond T are masked (their tiles hold clamped rows)
     float s = 0.f;

@@ -31,16 +31,10 @@ namespace {
 
 constexpr int DM = 256, DN = 256;     // output tile
 constexpr int DTHREADS = 512;         // 8 waves: 2 (M) x 4 (N)
-constexpr int DK = 32;                // rows per stage
-constexpr int NST = 4;                // stages resident in LDS
-constexpr int A_BYTES = DK * DM * 2;             // 16 KB, rows of 512 B
-constexpr int G_BYTES = DK * DN * 2;             // 16 KB, rows of 512 B
-constexpr int STAGE_BYTES = A_BYTES + G_BYTES;   // 32 KB
-constexpr int LOADS_PER_STAGE = 4;               // per wave: 2 of A, 2 of G
+constexpr int ROW_BYTES = 512;        // one tile row of either operand in LDS
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
-#define GLB_PTR(T) const __attribute__((address_space(1))) T*
 
 struct DmaArgs {
     const uint16_t* A;
@@ -51,7 +45,7 @@ struct DmaArgs {
     int B, T, M, N;
     int tiles_m, tiles_n;
     int splits;
-    int stages_total;      // B*T / 32
+    int stages_total;      // B*T / DK
     int stages_per_split;
     int per_xcd;
     int accumulate;
@@ -63,8 +57,18 @@ struct DmaArgs {
 // bytes modulo the bank period and the read is conflict free.
 __device__ __forceinline__ int chunk_swz(int r) { return (r & 3) << 2; }
 
+template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
+
+// DK rows per stage, NST stages resident in LDS (DK * NST * 1 KB <= 128 KB).
+template <int DK, int NST>
 __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];   // 128 KB
+    constexpr int OPND_BYTES = DK * ROW_BYTES;       // one operand of one stage
+    constexpr int STAGE_BYTES = 2 * OPND_BYTES;      // A part then G part
+    constexpr int KS = DK / 16;                      // k steps per stage
+    constexpr int IPO = DK / 16;                     // copy instructions per operand, stage and wave (2 rows each)
+    constexpr int LPS = 2 * IPO;                     // copies per stage and wave
+    static_assert(KS % 2 == 0 && NST >= 2 && NST * STAGE_BYTES <= 131072, "stage geometry");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles = a.tiles_m * a.tiles_n;
@@ -81,40 +85,44 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     if (n_stages <= 0) return;
     const int spe = a.T / DK;                       // stages per example
 
-    // ---- global -> LDS.  Wave w copies rows 4w..4w+3 of the A part and of the G part of a stage, two
-    //      instructions each; instruction u covers rows 4w+2u, 4w+2u+1 (lane / 32 picks the row, lane % 32 the chunk)
-    int offA[2], offG[2];                           // element offset of this lane's source chunk for u = 0 / 1
+    // ---- global -> LDS.  Wave w copies rows (DK/8) w .. of the A part and of the G part of a stage, two rows
+    //      per instruction (lane / 32 picks the row, lane % 32 the chunk position).  Addresses are a uniform
+    //      64-bit stage base (SGPR) plus a 32-bit per-lane byte offset that never changes.
+    uint32_t offA[IPO], offG[IPO];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int r = 2 * u + (lane >> 5);          // r & 3 of the row this lane fills
+    for (int u = 0; u < IPO; ++u) {
+        const int r = wave * (DK / 8) + 2 * u + (lane >> 5);          // row inside the stage
         const int c = (lane & 31) ^ chunk_swz(r);
         int ca = m0 + c * 8, cn = n0 + c * 8;
         if (ca >= a.M) ca = m0;                     // out-of-range columns only feed output rows / columns that are never stored
         if (cn >= a.N) cn = n0;
-        offA[u] = ca;
-        offG[u] = cn;
+        offA[u] = ((uint32_t)r * (uint32_t)a.M + (uint32_t)ca) * 2u;
+        offG[u] = ((uint32_t)r * (uint32_t)a.N + (uint32_t)cn) * 2u;
     }
-    const uint16_t* pA = a.A + ((size_t)s_begin * DK + wave * 4 + (lane >> 5)) * a.M;
-    const uint16_t* pG = a.G + ((size_t)s_begin * DK + wave * 4 + (lane >> 5)) * a.N;
-    const size_t stepA = (size_t)DK * a.M, stepG = (size_t)DK * a.N;            // per stage
-    const size_t row2A = (size_t)2 * a.M, row2G = (size_t)2 * a.N;              // per instruction
+    const uint16_t* baseA = a.A + (size_t)s_begin * DK * a.M;         // uniform
+    const uint16_t* baseG = a.G + (size_t)s_begin * DK * a.N;
+    const size_t stepA = (size_t)DK * a.M, stepG = (size_t)DK * a.N;  // per stage
 
     // The copies are issued as inline assembly: the compiler then does not know that they write LDS and
     // does not make every LDS read wait for all copies in flight; the waits for them are the explicit
     // vmcnt waits in front of the stage barriers below.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_base + wave * (DK / 8) * ROW_BYTES);
     auto issue = [&](int buf) {
-        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + buf * STAGE_BYTES + wave * 2048);
+#if defined(DPK_EXP) && DPK_EXP == 2
+        (void)buf; return;                          // scratch timing experiment: no copies at all
+#endif
+        const uint32_t base = wave_lds + buf * STAGE_BYTES;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(base + u * 1024), "v"(pA + u * row2A + offA[u]) : "memory", "m0");
+        for (int u = 0; u < IPO; ++u)
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(base + u * 1024), "v"(offA[u]), "s"(baseA) : "memory", "m0");
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(base + A_BYTES + u * 1024), "v"(pG + u * row2G + offG[u]) : "memory", "m0");
-        pA += stepA;
-        pG += stepG;
+        for (int u = 0; u < IPO; ++u)
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(base + OPND_BYTES + u * 1024), "v"(offG[u]), "s"(baseG) : "memory", "m0");
+        baseA += stepA;
+        baseG += stepG;
     };
 
     // ---- LDS -> MFMA operands.  Lane l of a 16-lane group: source row j = (l % 16) / 4, source column
@@ -127,12 +135,12 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int ma = wm * 128 + i * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);      // column (element) of the 8-byte piece
-        rdA[i] = rsrc * 512 + ((((ma >> 3) ^ chunk_swz(rsrc)) << 4) | ((ma & 7) << 1));
+        rdA[i] = rsrc * ROW_BYTES + ((((ma >> 3) ^ chunk_swz(rsrc)) << 4) | ((ma & 7) << 1));
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int na = wn * 64 + j * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
-        rdG[j] = A_BYTES + rsrc * 512 + ((((na >> 3) ^ chunk_swz(rsrc)) << 4) | ((na & 7) << 1));
+        rdG[j] = OPND_BYTES + rsrc * ROW_BYTES + ((((na >> 3) ^ chunk_swz(rsrc)) << 4) | ((na & 7) << 1));
     }
 
     f32x16 acc[4][2];
@@ -152,21 +160,21 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     float vclip = a.clip[min(ex0 + lane, a.B - 1)];
     float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
 
-    // prologue: NST - 1 stages in flight
+    // prologue: all NST buffers are free, fill them
 #pragma unroll
-    for (int p = 0; p < NST - 1; ++p)
+    for (int p = 0; p < NST; ++p)
         if (p < n_stages) issue(p);
 
-    // Software pipeline over k steps (two per stage): while the MFMAs of one k step run, the LDS reads of
-    // the next one are in flight, also across the stage boundary.  The barrier that makes stage st + 1
-    // visible therefore sits in the middle of stage st.
-    auto read_kstep = [&](bf16x8 (&f)[6], uint32_t sb, int row) {
-        LDS_PTR(unsigned char) b = (LDS_PTR(unsigned char))lds + sb + row * 512;
+    // Software pipeline over k steps: while the MFMAs of one k step run, the LDS reads of the next one are
+    // in flight, also across the stage boundary.  The barrier that makes stage st + 1 visible therefore
+    // sits in front of the last k step of stage st.
+    auto read_kstep = [&](bf16x8 (&f)[6], uint32_t sb, int ks) {
+        LDS_PTR(unsigned char) b = (LDS_PTR(unsigned char))lds + sb + ks * 16 * ROW_BYTES;
 #pragma unroll
         for (int x = 0; x < 6; ++x) {
             const uint32_t off = x < 4 ? rdA[x & 3] : rdG[x & 1];
             const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off));
-            const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off + 4 * 512));
+            const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off + 4 * ROW_BYTES));
             f[x] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     };
@@ -177,14 +185,21 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
             for (int j = 0; j < 2; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[4 + j], acc[i][j], 0, 0, 0);
     };
+    // stage s (relative) landed once at most `ahead` later stages' copies are outstanding
+    auto wait_stage = [&](int ahead) {
+#if defined(DPK_EXP) && (DPK_EXP == 1 || DPK_EXP == 2)
+        (void)ahead; return;                        // scratch timing experiment: no waits for the copies
+#endif
+        if (NST >= 4 && ahead >= 3) wait_vmcnt<3 * LPS>();
+        else if (NST >= 3 && ahead == 2) wait_vmcnt<2 * LPS>();
+        else if (ahead == 1) wait_vmcnt<LPS>();
+        else wait_vmcnt<0>();
+    };
 
-    // stage 0 must have landed (the copies of stages 1, 2 may stay in flight)
-    if (n_stages >= 3) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS_PER_STAGE));
-    else if (n_stages == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_STAGE);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    wait_stage(min(n_stages - 1, NST - 1));
     __builtin_amdgcn_s_barrier();
-    bf16x8 f0[6], f1[6];                            // fragments of k step 0 / k step 1: 0..3 of A, 4..5 of G
-    read_kstep(f0, 0u, 0);
+    bf16x8 f[2][6];                                 // fragments of the current / next k step: 0..3 of A, 4..5 of G
+    read_kstep(f[0], 0u, 0);
 
     for (int st = 0; st < n_stages; ++st) {
         const uint32_t sb = (uint32_t)(st % NST) * STAGE_BYTES;
@@ -205,22 +220,24 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
             c_cur = c_next;
         }
         ++sub;
-        read_kstep(f1, sb, 16);
-        mfma_kstep(f0);
-        // the reads of k step 1 were issued a whole k step ago: retire them before queueing new ones, so
-        // that the MFMAs of k step 1 do not have to wait for the reads issued below (LDS reads return in order)
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(0xC07F);                                              // lgkmcnt(0)
-        if (st + 1 < n_stages) {
-            // stage st + 1 must have landed; the copies of stage st + 2 may stay in flight
-            if (st + 2 < n_stages) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_STAGE);
-            else __builtin_amdgcn_s_waitcnt(0x0F70);
-            __builtin_amdgcn_s_barrier();
-            // every wave is past its reads of stage st - 1: its buffer takes stage st + 3
-            if (st + NST - 1 < n_stages) issue((st + NST - 1) % NST);
-            read_kstep(f0, (uint32_t)((st + 1) % NST) * STAGE_BYTES, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            // the fragments of this k step were requested a whole k step ago: retire them before queueing the
+            // next ones, so that the MFMAs below never wait for reads issued here (LDS reads return in order)
+            __builtin_amdgcn_s_waitcnt(0xC07F);                                          // lgkmcnt(0)
+            if (ks + 1 < KS) {
+                read_kstep(f[(ks + 1) & 1], sb, ks + 1);
+            } else if (st + 1 < n_stages) {
+                // stage st + 1 must have landed (later stages may stay in flight), for every wave; every wave
+                // has also retired its last reads of stage st, so that buffer can take stage st + NST
+                wait_stage(min(n_stages - 2 - st, NST - 2));
+                __builtin_amdgcn_s_barrier();
+                if (st + NST < n_stages) issue(st % NST);
+                read_kstep(f[0], (uint32_t)((st + 1) % NST) * STAGE_BYTES, 0);
+            }
+            mfma_kstep(f[ks & 1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        mfma_kstep(f1);
     }
 
     // the tile holds (1 / c_cur) * sum: finish with the last example's factor
@@ -244,13 +261,17 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
         }
 }
 
+// rows per stage: 64 when every example is a whole number of 64-row stages, else 32
+inline int dma_dk(int T) { (void)T; return 32; }
+
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 }  // namespace
 
 bool dma_clipped_ok(int B, int T, int M, int N) {
     (void)B;
-    if ((T % DK) != 0 || ((M | N) & 7) != 0) return false;
+    if ((T % 32) != 0 || ((M | N) & 7) != 0) return false;
+    if ((int64_t)64 * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;     // 32-bit lane offsets inside a stage
     const int64_t padded = (int64_t)ceil_div(M, DM) * DM * ceil_div(N, DN) * DN;
     return padded * 4 <= (int64_t)M * N * 5;          // at most a quarter of the padded tiles is waste
 }
@@ -261,6 +282,7 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
     p.tiles_m = ceil_div(M, DM); p.tiles_n = ceil_div(N, DN);
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int DK = dma_dk(T);
     const int64_t stages = (int64_t)B * T / DK;
     // one workgroup per compute unit: as many K slices as fit into 256 workgroups, at least 8 stages each
     int64_t splits = 256 / tiles;
@@ -281,6 +303,7 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.A = A; a.G = G; a.clip = clip;
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.splits = p.splits;
+    const int DK = dma_dk(T);
     a.stages_total = (int)((int64_t)B * T / DK);
     a.stages_per_split = p.kchunk / DK;
     const int64_t n = (int64_t)M * N;
@@ -288,7 +311,8 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    k_tn_bf16_dma<<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
+    if (DK == 64) k_tn_bf16_dma<64, 2><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
+    else k_tn_bf16_dma<32, 4><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
