@@ -25,11 +25,16 @@ namespace dpk {
 namespace {
 
 constexpr int GT = 128;                 // rows of T per tile
-constexpr int GK = 64;                  // contraction elements per stage (128 B per row)
-constexpr int TILE_BYTES = GT * GK * 2; // 16 KB
+constexpr int GK = 64;                  // contraction elements per stage (128 B per row = one cache line)
+constexpr int ROWB = GK * 2;            // bytes per tile row in LDS
+constexpr int CPR = ROWB / 16;          // 16-byte chunks per row
+constexpr int RPI = 64 / CPR;           // rows per copy instruction (1 KB)
+constexpr int IPT = GT / RPI / 4;       // copy instructions per tile and wave
+constexpr int TILE_BYTES = GT * ROWB;
 constexpr int GSTAGE = 2 * TILE_BYTES;  // t-tile then s-tile
-constexpr int GNST = 2;                 // stages resident in LDS (64 KB: two workgroups per compute unit; a 3-stage
-                                        // ring with one workgroup per compute unit measured ~7 % slower)
+constexpr int GNST = 2;                 // stages resident in LDS (64 KB: two workgroups per compute unit).  Measured
+                                        // alternatives: GK = 32 with a 4-stage ring (half cache lines per row) 14 % slower,
+                                        // 3 stages of GK = 64 with one workgroup per compute unit 7 % slower
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
 struct GramDmaArgs {
@@ -41,11 +46,14 @@ struct GramDmaArgs {
     int per_xcd;
 };
 
-// chunk c (16 B) of tile row r sits at chunk position c ^ ((r >> 1) & 7): 16 consecutive rows reading the
-// same logical chunk then cover all 64 banks once (row parity selects the upper or lower 128 bytes)
-__device__ __forceinline__ int gram_swz(int r) { return (r >> 1) & 7; }
+// chunk c (16 B) of tile row r sits at chunk position c ^ swz(r) so that 16 consecutive rows reading the same
+// logical chunk cover all 64 banks once: with 128-byte rows the row parity selects the upper or lower 128 bytes
+// and (r >> 1) & 7 spreads the rest; with 64-byte rows r & 3 selects a 64-byte window and (r >> 2) & 3 spreads.
+template <int N> __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70); }
 
-__global__ __launch_bounds__(kThreads, GNST == 2 ? 2 : 1) void k_gram_bf16_dma(GramDmaArgs a) {
+__device__ __forceinline__ int gram_swz(int r) { return CPR == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
+
+__global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gram_bf16_dma(GramDmaArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[GNST * GSTAGE];
     __shared__ float red[4];
 
@@ -64,11 +72,11 @@ __global__ __launch_bounds__(kThreads, GNST == 2 ? 2 : 1) void k_gram_bf16_dma(G
 
     // ---- copies: wave w moves rows 32w .. 32w+31 of the t-tile and of the s-tile, 4 instructions each
     //      (instruction u: rows 32w + 8u .. + 7; lane / 8 picks the row, lane % 8 the chunk position)
-    const int lrow8 = lane >> 3, cp = lane & 7;
-    int row_t[4], row_s[4], chunk16[4];             // tile rows (clamped to valid rows) and source chunk byte offsets
+    const int lrow8 = lane / CPR, cp = lane % CPR;
+    int row_t[IPT], row_s[IPT], chunk16[IPT];       // tile rows (clamped to valid rows) and source chunk byte offsets
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int r = wave * 32 + u * 8 + lrow8;                       // row inside the tile
+    for (int u = 0; u < IPT; ++u) {
+        const int r = wave * 32 + u * RPI + lrow8;                     // row inside the tile
         chunk16[u] = (cp ^ gram_swz(r)) << 4;                          // source chunk for this LDS slot
         row_t[u] = min(tt * GT + r, a.T - 1);
         row_s[u] = min(ss * GT + r, a.T - 1);
@@ -79,19 +87,22 @@ __global__ __launch_bounds__(kThreads, GNST == 2 ? 2 : 1) void k_gram_bf16_dma(G
     // The copies are inline assembly so that the compiler does not tie every LDS read to them; they are
     // waited for with the explicit vmcnt wait in front of the stage barrier.
     auto issue = [&](int st, int buf) {
+#if defined(DPK_EXP) && DPK_EXP == 3
+        (void)st; (void)buf; return;               // scratch timing experiment: no copies at all
+#endif
         const bool phase_g = st >= sa;
         const int k0 = (phase_g ? st - sa : st) * GK;
         const uint16_t* sbase = (phase_g ? baseG : baseA) + k0;
         const uint32_t rb = (uint32_t)(phase_g ? a.d_out : a.d_in) * 2u;          // row bytes
-        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + buf * GSTAGE + wave * 4096);
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + buf * GSTAGE + wave * 32 * ROWB);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < IPT; ++u) {
             const uint32_t off = (uint32_t)row_t[u] * rb + (uint32_t)chunk16[u];
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + u * 1024), "v"(off), "s"(sbase) : "memory", "m0");
         }
         if (!diag) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < IPT; ++u) {
                 const uint32_t off = (uint32_t)row_s[u] * rb + (uint32_t)chunk16[u];
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + TILE_BYTES + u * 1024), "v"(off), "s"(sbase) : "memory", "m0");
             }
@@ -105,8 +116,8 @@ __global__ __launch_bounds__(kThreads, GNST == 2 ? 2 : 1) void k_gram_bf16_dma(G
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int rt = wm * 64 + i * 32 + lrow, rs = wn * 64 + i * 32 + lrow;
-        rd_t[i] = rt * 128 + ((lhalf ^ gram_swz(rt)) << 4);
-        rd_s[i] = (diag ? 0 : TILE_BYTES) + rs * 128 + ((lhalf ^ gram_swz(rs)) << 4);
+        rd_t[i] = rt * ROWB + ((lhalf ^ gram_swz(rt)) << 4);
+        rd_s[i] = (diag ? 0 : TILE_BYTES) + rs * ROWB + ((lhalf ^ gram_swz(rs)) << 4);
     }
     f32x16 accP[2][2], accQ[2][2];
 #pragma unroll
@@ -137,9 +148,11 @@ __global__ __launch_bounds__(kThreads, GNST == 2 ? 2 : 1) void k_gram_bf16_dma(G
     bf16x8 f[2][4];
     // wait until at most `stages` later stages' copies are outstanding (4 per wave and stage on a diagonal pair, else 8)
     auto wait_copies = [&](int stages) {
-        if (stages <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
-        else if (stages == 1) { if (diag) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F78); }   // 4 / 8
-        else { if (diag) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x4F70); }                  // 8 / 16
+        // copies per wave and stage: IPT on a diagonal pair, else 2 * IPT
+        if (stages <= 0) wait_vm<0>();
+        else if (stages == 1) { if (diag) wait_vm<IPT>(); else wait_vm<2 * IPT>(); }
+        else if (stages == 2) { if (diag) wait_vm<2 * IPT>(); else wait_vm<4 * IPT>(); }
+        else { if (diag) wait_vm<3 * IPT>(); else wait_vm<6 * IPT>(); }
     };
     auto stage = [&](int st, f32x16 (&acc)[2][2]) {
 #pragma unroll
