@@ -26,7 +26,11 @@ import numpy as np  # noqa: E402
 # HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
 # `bench.py --calib-copy`, scaled by what the same counters read for the 1 GiB copy (see profiles/).
 # None until measured for the current kernels.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # one dp_clipped_grad call (GEMM + split-K reduce), mean of the 4 layers: 286.3 + 65.5 MB read,
+    # 65.5 + 7.1 MB written (profiles/transformer_hbm_traffic.md)
+    "transformer": 424.4e6,
+}
 
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
