@@ -73,40 +73,45 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     // ---- copies: wave w moves rows 32w .. 32w+31 of the t-tile and of the s-tile, 4 instructions each
     //      (instruction u: rows 32w + 8u .. + 7; lane / 8 picks the row, lane % 8 the chunk position)
     const int lrow8 = lane / CPR, cp = lane % CPR;
-    int row_t[IPT], row_s[IPT], chunk16[IPT];       // tile rows (clamped to valid rows) and source chunk byte offsets
+    // per-lane byte offsets inside the example (tile rows clamped to valid rows), fixed for the whole kernel:
+    // [0] = A phase, [1] = G phase
+    uint32_t off_t[2][IPT], off_s[2][IPT];
 #pragma unroll
     for (int u = 0; u < IPT; ++u) {
         const int r = wave * 32 + u * RPI + lrow8;                     // row inside the tile
-        chunk16[u] = (cp ^ gram_swz(r)) << 4;                          // source chunk for this LDS slot
-        row_t[u] = min(tt * GT + r, a.T - 1);
-        row_s[u] = min(ss * GT + r, a.T - 1);
+        const uint32_t c16 = (uint32_t)((cp ^ gram_swz(r)) << 4);      // source chunk for this LDS slot
+        const uint32_t rt = (uint32_t)min(tt * GT + r, a.T - 1), rs = (uint32_t)min(ss * GT + r, a.T - 1);
+        off_t[0][u] = rt * (uint32_t)a.d_in * 2u + c16;  off_s[0][u] = rs * (uint32_t)a.d_in * 2u + c16;
+        off_t[1][u] = rt * (uint32_t)a.d_out * 2u + c16; off_s[1][u] = rs * (uint32_t)a.d_out * 2u + c16;
     }
+#if defined(DPK_EXP) && DPK_EXP == 4
+    const uint16_t* baseA = a.A;                   // scratch timing experiment: every workgroup reads example 0 (L2 resident)
+    const uint16_t* baseG = a.G;
+#else
     const uint16_t* baseA = a.A + (size_t)ex * a.T * a.d_in;          // uniform example bases; lane offsets stay 32-bit
     const uint16_t* baseG = a.G + (size_t)ex * a.T * a.d_out;
+#endif
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_base + wave * 32 * ROWB);
     // The copies are inline assembly so that the compiler does not tie every LDS read to them; they are
     // waited for with the explicit vmcnt wait in front of the stage barrier.
+    auto issue_phase = [&](const uint16_t* sbase, const uint32_t (&ot)[IPT], const uint32_t (&os)[IPT], int buf) {
+        const uint32_t base = wave_lds + buf * GSTAGE;
+#pragma unroll
+        for (int u = 0; u < IPT; ++u)
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + u * 1024), "v"(ot[u]), "s"(sbase) : "memory", "m0");
+        if (!diag) {
+#pragma unroll
+            for (int u = 0; u < IPT; ++u)
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + TILE_BYTES + u * 1024), "v"(os[u]), "s"(sbase) : "memory", "m0");
+        }
+    };
     auto issue = [&](int st, int buf) {
 #if defined(DPK_EXP) && DPK_EXP == 3
         (void)st; (void)buf; return;               // scratch timing experiment: no copies at all
 #endif
-        const bool phase_g = st >= sa;
-        const int k0 = (phase_g ? st - sa : st) * GK;
-        const uint16_t* sbase = (phase_g ? baseG : baseA) + k0;
-        const uint32_t rb = (uint32_t)(phase_g ? a.d_out : a.d_in) * 2u;          // row bytes
-        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + buf * GSTAGE + wave * 32 * ROWB);
-#pragma unroll
-        for (int u = 0; u < IPT; ++u) {
-            const uint32_t off = (uint32_t)row_t[u] * rb + (uint32_t)chunk16[u];
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + u * 1024), "v"(off), "s"(sbase) : "memory", "m0");
-        }
-        if (!diag) {
-#pragma unroll
-            for (int u = 0; u < IPT; ++u) {
-                const uint32_t off = (uint32_t)row_s[u] * rb + (uint32_t)chunk16[u];
-                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + TILE_BYTES + u * 1024), "v"(off), "s"(sbase) : "memory", "m0");
-            }
-        }
+        if (st < sa) issue_phase(baseA + st * GK, off_t[0], off_s[0], buf);
+        else issue_phase(baseG + (st - sa) * GK, off_t[1], off_s[1], buf);
     };
 
     // ---- MFMA roles: 2 x 2 waves, each owns 64 x 64 of the 128 x 128 tile pair
