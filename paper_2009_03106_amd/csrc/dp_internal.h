@@ -45,6 +45,10 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
                                int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
+// direct squared norm with the large-tile copy-pipeline kernel; partial[B][ceil(M/256)*ceil(N/256)]
+bool dma_direct_ok(int T, int M, int N);
+hipError_t launch_direct_bf16_dma(const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
+                                  bool accumulate, float* sqnorm, float* partial, hipStream_t st);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 // partial[B][tiles_m*tiles_n] then finalize into sqnorm

@@ -60,7 +60,10 @@ __device__ __forceinline__ int chunk_swz(int r) { return (r & 3) << 2; }
 template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
 
 // DK rows per stage, NST stages resident in LDS (DK * NST * 1 KB <= 128 KB).
-template <int DK, int NST>
+// MODE 0: clipped sum over a K slice (any range of stages).  MODE 1: direct squared norm: the K slice is one
+// example (stages_per_split = T / DK, splits = B), no scaling, and the finished tile of A_i^T G_i is squared
+// and reduced to one float per (example, tile) instead of being stored (Algorithm 3 / 4 without their output).
+template <int DK, int NST, int MODE>
 __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     constexpr int OPND_BYTES = DK * ROW_BYTES;       // one operand of one stage
     constexpr int STAGE_BYTES = 2 * OPND_BYTES;      // A part then G part
@@ -157,7 +160,8 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     // (loaded before the copies start) and picked with v_readlane: a scalar or vector load inside the loop
     // would make the compiler wait for every LDS read / copy in flight at each use.
     const int ex0 = ex;                             // a K slice spans at most 64 examples (see the plan)
-    float vclip = a.clip[min(ex0 + lane, a.B - 1)];
+    float vclip = 1.0f;
+    if (MODE == 0) vclip = a.clip[min(ex0 + lane, a.B - 1)];
     float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
 
     // prologue: all NST buffers are free, fill them
@@ -203,7 +207,7 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
 
     for (int st = 0; st < n_stages; ++st) {
         const uint32_t sb = (uint32_t)(st % NST) * STAGE_BYTES;
-        if (sub == spe) {
+        if (MODE == 0 && sub == spe) {
             // first stage of the next example: rescale the running tile
             sub = 0;
             ++ex;
@@ -240,9 +244,37 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
         }
     }
 
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    if (MODE == 1) {
+        // sum of squares over the valid part of the tile (columns / rows beyond d_out / d_in hold clamped copies)
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int n = n0 + wn * 64 + j * 32 + lrow;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                    const float v = acc[i][j][r];
+                    sq += (m < a.M && n < a.N) ? v * v : 0.f;
+                }
+            }
+        sq = wave_sum(sq);
+        __syncthreads();                            // every wave is done with the stage buffers: reuse them for the reduction
+        float* red = reinterpret_cast<float*>(lds);
+        if (lane == 0) red[wave] = sq;
+        __syncthreads();
+        if (tid == 0) {
+            float t = 0.f;
+#pragma unroll
+            for (int w = 0; w < DTHREADS / 64; ++w) t += red[w];
+            a.out[(size_t)z * tiles + tile] = t;
+        }
+        return;
+    }
     // the tile holds (1 / c_cur) * sum: finish with the last example's factor
     float* out = a.out + (size_t)z * a.slice;
-    const int lrow = lane & 31, lhalf = lane >> 5;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -273,7 +305,7 @@ bool dma_clipped_ok(int B, int T, int M, int N) {
     if ((T % 32) != 0 || ((M | N) & 7) != 0) return false;
     if ((int64_t)64 * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;     // 32-bit lane offsets inside a stage
     const int64_t padded = (int64_t)ceil_div(M, DM) * DM * ceil_div(N, DN) * DN;
-    return padded * 4 <= (int64_t)M * N * 5;          // at most a quarter of the padded tiles is waste
+    return padded * 4 <= (int64_t)M * N * 5;                              // at most a quarter of the padded tiles is waste
 }
 
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
@@ -311,11 +343,38 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    if (DK == 64) k_tn_bf16_dma<64, 2><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
-    else k_tn_bf16_dma<32, 4><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
+    if (DK == 64) k_tn_bf16_dma<64, 2, 0><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
+    else k_tn_bf16_dma<32, 4, 0><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
+}
+
+bool dma_direct_ok(int T, int M, int N) {
+    if (T < 64 || (T % 32) != 0 || ((M | N) & 7) != 0) return false;
+    if ((int64_t)64 * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;     // 32-bit lane offsets inside a stage
+    const int64_t padded = (int64_t)ceil_div(M, DM) * DM * ceil_div(N, DN) * DN;
+    return padded * 4 <= (int64_t)M * N * 5;                              // at most a quarter of the padded tiles is waste
+}
+
+hipError_t launch_direct_bf16_dma(const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
+                                  bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+    DmaArgs a;
+    a.A = A; a.G = G; a.clip = nullptr;
+    a.B = B; a.T = T; a.M = M; a.N = N;
+    a.tiles_m = ceil_div(M, DM); a.tiles_n = ceil_div(N, DN);
+    a.splits = B;
+    a.stages_total = (int)((int64_t)B * T / 32);
+    a.stages_per_split = T / 32;
+    a.out = partial; a.slice = 0; a.accumulate = 0;
+    const int tiles = a.tiles_m * a.tiles_n;
+    const int64_t total = (int64_t)tiles * B;
+    if (total >= (int64_t(1) << 28)) return hipErrorInvalidValue;
+    a.per_xcd = ceil_div(total, 8);
+    k_tn_bf16_dma<32, 4, 1><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
 }
 
 }  // namespace dpk
