@@ -43,7 +43,7 @@ struct GramDmaArgs {
     float* partial;      // [B][npairs]
     int B, T, d_in, d_out;
     int nt, npairs;
-    int per_xcd;
+    int per_xcd_off, per_xcd_diag;   // queue lengths per XCD: off-diagonal pairs, then diagonal pairs
 };
 
 // chunk c (16 B) of tile row r sits at chunk position c ^ swz(r) so that 16 consecutive rows reading the same
@@ -58,13 +58,29 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     __shared__ float red[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
-    if (L >= a.B * a.npairs) return;
-    const int ex = L / a.npairs;
-    int pair = L - ex * a.npairs;                       // position in the row-major list of (tt, ss), tt <= ss
-    int tt = 0;
-    while (pair >= a.nt - tt) { pair -= a.nt - tt; ++tt; }
-    const int ss = tt + pair;
+    // Work order.  Consecutive workgroup ids go round the 8 XCDs, so id & 7 names the XCD (and its L2) and
+    // id >> 3 the position in that XCD's queue.  Each XCD takes a contiguous eighth of the off-diagonal pairs
+    // (example-major) and then the matching eighth of the diagonal pairs: one example's pairs share an L2, and the
+    // cheaper diagonal pairs (half the copies) run last, where they fill the tail of the launch.
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int noff = a.npairs - a.nt;                   // off-diagonal pairs per example
+    int ex, tt, ss, slot;                               // slot: position of this pair in the example's partial sums
+    if (j < a.per_xcd_off) {
+        const int L = xcd * a.per_xcd_off + j;
+        if (L >= a.B * noff) return;
+        ex = L / noff;
+        int q = L - ex * noff;                          // position in the row-major list of (tt, ss), tt < ss
+        slot = q;
+        tt = 0;
+        while (q >= a.nt - 1 - tt) { q -= a.nt - 1 - tt; ++tt; }
+        ss = tt + 1 + q;
+    } else {
+        const int L = xcd * a.per_xcd_diag + (j - a.per_xcd_off);
+        if (L >= a.B * a.nt) return;
+        ex = L / a.nt;
+        tt = ss = L - ex * a.nt;
+        slot = noff + tt;
+    }
     const bool diag = (tt == ss);
 
     const int sa = a.d_in / GK, sg = a.d_out / GK;      // stages of the A phase and of the G phase
@@ -153,6 +169,9 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     bf16x8 f[2][4];
     // wait until at most `stages` later stages' copies are outstanding (4 per wave and stage on a diagonal pair, else 8)
     auto wait_copies = [&](int stages) {
+#if defined(DPK_EXP) && (DPK_EXP == 5 || DPK_EXP == 6)
+        (void)stages; return;                      // scratch timing experiment: never wait for the copies
+#endif
         // copies per wave and stage: IPT on a diagonal pair, else 2 * IPT
         if (stages <= 0) wait_vm<0>();
         else if (stages == 1) { if (diag) wait_vm<IPT>(); else wait_vm<2 * IPT>(); }
@@ -170,17 +189,39 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
                 // pair, else 8) may stay in flight
                 wait_copies(min(n_stages - 2 - st, GNST - 2));
                 __builtin_amdgcn_s_barrier();                // ... for every wave, and every wave is done reading stage st
+#if !(defined(DPK_EXP) && DPK_EXP == 6)
                 if (st + GNST < n_stages) issue(st + GNST, st % GNST);
+#endif
                 read_kstep(f[0], (st + 1) % GNST, 0);
             }
+#if defined(DPK_EXP) && DPK_EXP == 6
+            {   // scratch timing experiment: copies of the next stage spread between the MFMAs, never waited for
+                const bf16x8 (&ff)[4] = f[ks & 1];
+                const int tg = st + 1;
+                const bool on = tg < n_stages;
+                const uint16_t* sbase = tg < sa ? baseA + tg * GK : baseG + (tg - sa) * GK;
+                const uint32_t base = wave_lds + (tg % GNST) * GSTAGE;
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[0], ff[2], acc[0][0], 0, 0, 0);
+                if (on) asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + ks * 1024), "v"(tg < sa ? off_t[0][ks] : off_t[1][ks]), "s"(sbase) : "memory", "m0");
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[0], ff[3], acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[1], ff[2], acc[1][0], 0, 0, 0);
+                if (on && !diag) asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + TILE_BYTES + ks * 1024), "v"(tg < sa ? off_s[0][ks] : off_s[1][ks]), "s"(sbase) : "memory", "m0");
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[1], ff[3], acc[1][1], 0, 0, 0);
+            }
+#else
             mfma_kstep(f[ks & 1], acc);
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
 #pragma unroll
     for (int p = 0; p < GNST; ++p)
+#if defined(DPK_EXP) && DPK_EXP == 6
+        if (p < 1) issue(p, p);
+#else
         if (p < n_stages) issue(p, p);
+#endif
     wait_copies(min(n_stages, GNST) - 1);                        // stage 0 must have landed
     __builtin_amdgcn_s_barrier();
     read_kstep(f[0], 0, 0);
@@ -203,7 +244,7 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         }
     __syncthreads();
     s = block_sum_256(s, red);
-    if (tid == 0) a.partial[L] = diag ? s : 2.0f * s;
+    if (tid == 0) a.partial[(size_t)ex * a.npairs + slot] = diag ? s : 2.0f * s;
 }
 
 }  // namespace
@@ -219,9 +260,9 @@ hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint
     a.A = A; a.G = G; a.partial = partial;
     a.B = B; a.T = T; a.d_in = d_in; a.d_out = d_out;
     a.nt = p.nt; a.npairs = p.npairs;
-    const int64_t total = (int64_t)B * p.npairs;
-    a.per_xcd = (int)((total + 7) / 8);
-    k_gram_bf16_dma<<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+    a.per_xcd_off = (int)(((int64_t)B * (p.npairs - p.nt) + 7) / 8);
+    a.per_xcd_diag = (int)(((int64_t)B * p.nt + 7) / 8);
+    k_gram_bf16_dma<<<8u * (unsigned)(a.per_xcd_off + a.per_xcd_diag), kThreads, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);

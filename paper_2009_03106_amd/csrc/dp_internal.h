@@ -30,7 +30,7 @@ struct TnPlan {
     bool segmented;         // bf16 only: K is walked example by example (slices are whole examples)
     int epu;                // segmented: examples per K slice
     bool big;               // bf16 clipped sum only: 256 x 256 tiles, one workgroup per compute unit
-    bool dma;               // bf16 clipped sum only: 256 x 256 tiles fed by direct-to-LDS copies and transposing LDS reads
+    bool dma;               // bf16 only: copy-pipeline kernel (direct-to-LDS copies, transposing LDS reads); tile_m x tile_n names its geometry
 };
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
 TnPlan plan_clipped_f32(int B, int T, int M, int N);
@@ -45,9 +45,10 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
                                int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
-// direct squared norm with the large-tile copy-pipeline kernel; partial[B][ceil(M/256)*ceil(N/256)]
+// direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
-hipError_t launch_direct_bf16_dma(const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
+TnPlan plan_direct_bf16_dma(int T, int M, int N);
+hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);

@@ -134,9 +134,52 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
     }
 }
 
+// Same sum for many slices of a small matrix, where one thread per output would leave most of the chip idle and
+// walk its slices one load at a time: 8 threads share an output column group, thread g adds slices g, g + 8, ...
+// in ascending order, and the 8 partial sums are added in the order g = 0 .. 7.  The order is fixed, so the
+// result is reproducible; it differs from the one-thread order only by rounding.
+__global__ __launch_bounds__(256) void k_splitk_reduce_wide(const float* __restrict__ ws, int64_t n4, int64_t slice, int splits,
+                                                            int accumulate, float* __restrict__ grad) {
+    __shared__ float4 part[8][32];
+    const int g = threadIdx.x >> 5, cl = threadIdx.x & 31;
+    const int64_t c = (int64_t)blockIdx.x * 32 + cl;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < n4) {
+        int z = g;
+        for (; z + 24 < splits; z += 32) {
+            const float4 v0 = reinterpret_cast<const float4*>(ws + (size_t)z * slice)[c];
+            const float4 v1 = reinterpret_cast<const float4*>(ws + (size_t)(z + 8) * slice)[c];
+            const float4 v2 = reinterpret_cast<const float4*>(ws + (size_t)(z + 16) * slice)[c];
+            const float4 v3 = reinterpret_cast<const float4*>(ws + (size_t)(z + 24) * slice)[c];
+            acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+            acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+            acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+            acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
+        }
+        for (; z < splits; z += 8) {
+            const float4 v = reinterpret_cast<const float4*>(ws + (size_t)z * slice)[c];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    }
+    part[g][cl] = acc;
+    __syncthreads();
+    if (g == 0 && c < n4) {
+#pragma unroll
+        for (int k = 1; k < 8; ++k) { const float4 v = part[k][cl]; acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w; }
+        float4* o = reinterpret_cast<float4*>(grad) + c;
+        if (accumulate) { const float4 q = *o; acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w; }
+        *o = acc;
+    }
+}
+
 hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st) {
     // slices are spaced splitk_slice_elems(n) apart, a multiple of 4 floats, so each starts 16-byte aligned
-    int64_t blocks = ((n >> 2) + 255) / 256;
+    const int64_t n4 = n >> 2;
+    if (splits >= 16 && (n & 3) == 0 && n4 <= (int64_t)256 * 1024) {
+        k_splitk_reduce_wide<<<(unsigned)((n4 + 31) / 32), 256, 0, st>>>(ws, n4, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad);
+        return hipGetLastError();
+    }
+    int64_t blocks = (n4 + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
     k_splitk_reduce<<<(unsigned)blocks, 256, 0, st>>>(ws, n, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad);

@@ -658,13 +658,7 @@ TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
 
 TnPlan plan_direct_bf16(int T, int M, int N) {
     TnPlan p;
-    if (dma_direct_ok(T, M, N)) {
-        p.tile_m = 256; p.tile_n = 256;
-        p.tiles_m = ceil_div(M, 256); p.tiles_n = ceil_div(N, 256);
-        p.segmented = false; p.big = false; p.dma = true;
-        p.splits = 1; p.kchunk = 0; p.epu = 1;
-        return p;
-    }
+    if (dma_direct_ok(T, M, N)) return plan_direct_bf16_dma(T, M, N);
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     p.segmented = (T >= kSegMinT);
@@ -714,7 +708,7 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
 
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                               bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
-    if (p.dma) return launch_direct_bf16_dma(A, G, B, T, M, N, accumulate, sqnorm, partial, st);
+    if (p.dma) return launch_direct_bf16_dma(p, A, G, B, T, M, N, accumulate, sqnorm, partial, st);
     const int tiles = p.tiles_m * p.tiles_n;
     if (p.segmented) {
         // one launch covers at most 2^20 examples so that the workgroup count stays far below 2^31

@@ -1,4 +1,4 @@
-// Large-tile bf16 clipped sum  sum_i c_i A_i^T G_i  for big aligned layers.
+// Copy-pipeline bf16 kernels for aligned layers: clipped sum  sum_i c_i A_i^T G_i  and direct squared norm.
 //
 // gfx950-specific data path with (almost) no VALU work in the main loop:
 //   * global -> LDS copies go straight into LDS (global_load_lds_dwordx4): a
@@ -29,18 +29,39 @@ namespace dpk {
 
 namespace {
 
-constexpr int DM = 256, DN = 256;     // output tile
-constexpr int DTHREADS = 512;         // 8 waves: 2 (M) x 4 (N)
-constexpr int ROW_BYTES = 512;        // one tile row of either operand in LDS
+constexpr int DK = 32;                // rows of A and of G per stage
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
+
+// Tile geometry: WM x WN waves, each owning FM x FN MFMA tiles of 32 x 32; NST stages resident in LDS; OCC
+// workgroups per compute unit.
+template <int WM_, int WN_, int FM_, int FN_, int NST_, int OCC_>
+struct Geo {
+    static constexpr int WM = WM_, WN = WN_, FM = FM_, FN = FN_, NST = NST_, OCC = OCC_;
+    static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
+    static constexpr int TM = WM * FM * 32, TN = WN * FN * 32;        // output tile
+    static constexpr int RBA = TM * 2, RBG = TN * 2;                  // bytes of one stage row of either operand
+    static constexpr int IPA = RBA / 32 / WAVES, IPG = RBG / 32 / WAVES;   // 1 KB copies per operand, stage and wave
+    static constexpr int LPS = IPA + IPG;                             // copies per stage and wave
+    static constexpr int OPA = DK * RBA, STAGE_BYTES = DK * (RBA + RBG);
+    static_assert(IPA * 32 * WAVES == RBA && IPG * 32 * WAVES == RBG, "a stage must be a whole number of copies per wave");
+    static_assert(NST >= 2 && OCC * NST * STAGE_BYTES <= 160 * 1024, "stages must fit the 160 KB of LDS");
+    static_assert(3 * LPS <= 63, "vmcnt range");
+};
+// MFMA-bound layers: 256 x 256 tile (128 flop per byte copied), 8 waves of 128 x 64, four 32 KB stages, one
+// workgroup per compute unit.  At 256 x 128 the kernel ran into the ~10 TB/s the L2s deliver to the compute units.
+using GeoL = Geo<2, 4, 4, 2, 4, 1>;
+// narrow, HBM-bound layers (e.g. the unfolded 3 x 3 convolution, 576 x 128): 192 x 128 tile, 4 waves of 96 x 64,
+// three 20 KB stages, two workgroups per compute unit: more workgroups to spread over the chip, and as many bytes
+// in flight per compute unit
+using GeoS = Geo<2, 2, 3, 2, 3, 2>;
 
 struct DmaArgs {
     const uint16_t* A;
     const uint16_t* G;
     const float* clip;
-    float* out;            // slice base (stride `slice` per K slice) or grad
+    float* out;            // slice base (stride `slice` per K slice) or grad; direct norm: partial[B][tiles]
     int64_t slice;
     int B, T, M, N;
     int tiles_m, tiles_n;
@@ -51,26 +72,28 @@ struct DmaArgs {
     int accumulate;
 };
 
-// 16-byte chunk c of tile row r sits at chunk position c ^ ((r & 3) << 2).  A transposing read of 32
-// lanes touches 4 rows x two 32-byte pieces (columns m .. m+15 and m+16 .. m+31); rows are 512 B apart, so
-// without the xor all of them would start in the same bank.  With it the 8 pieces cover 256 consecutive
-// bytes modulo the bank period and the read is conflict free.
-__device__ __forceinline__ int chunk_swz(int r) { return (r & 3) << 2; }
+// Rows of RB bytes; the 16-byte chunk c of row r sits at chunk position c ^ chunk_swz<RB>(r).  A transposing read
+// of 32 lanes touches 4 consecutive rows x 64 bytes (two 32-byte pieces side by side).  Banks repeat every 256
+// bytes: when RB is a multiple of 256 the 4 rows start in the same bank and the xor moves them to 4 different
+// 64-byte windows; when RB = 128 mod 256 rows r and r + 2 collide and the xor separates those.
+template <int RB> __device__ __forceinline__ int chunk_swz(int r) {
+    static_assert(RB % 128 == 0, "row bytes");
+    if (RB % 256 == 0) return (r & 3) << 2;         // needs 16 | chunks per row
+    return ((r >> 1) & 1) << 2;                     // needs 8 | chunks per row
+}
 
-template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
+template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14)); }
 
-// DK rows per stage, NST stages resident in LDS (DK * NST * 1 KB <= 128 KB).
 // MODE 0: clipped sum over a K slice (any range of stages).  MODE 1: direct squared norm: the K slice is one
 // example (stages_per_split = T / DK, splits = B), no scaling, and the finished tile of A_i^T G_i is squared
 // and reduced to one float per (example, tile) instead of being stored (Algorithm 3 / 4 without their output).
-template <int DK, int NST, int MODE>
-__global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
-    constexpr int OPND_BYTES = DK * ROW_BYTES;       // one operand of one stage
-    constexpr int STAGE_BYTES = 2 * OPND_BYTES;      // A part then G part
+template <class GEO, int MODE>
+__global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs a) {
+    constexpr int NST = GEO::NST, FM = GEO::FM, FN = GEO::FN, NF = FM + FN;
+    constexpr int RBA = GEO::RBA, RBG = GEO::RBG, IPA = GEO::IPA, IPG = GEO::IPG, LPS = GEO::LPS;
+    constexpr int OPA = GEO::OPA, STAGE_BYTES = GEO::STAGE_BYTES;
     constexpr int KS = DK / 16;                      // k steps per stage
-    constexpr int IPO = DK / 16;                     // copy instructions per operand, stage and wave (2 rows each)
-    constexpr int LPS = 2 * IPO;                     // copies per stage and wave
-    static_assert(KS % 2 == 0 && NST >= 2 && NST * STAGE_BYTES <= 131072, "stage geometry");
+    static_assert((RBA % 256 == 0 ? (RBA / 16) % 16 : (RBA / 16) % 8) == 0 && (RBG % 256 == 0 ? (RBG / 16) % 16 : (RBG / 16) % 8) == 0, "swizzle range");
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -81,26 +104,32 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     if (L >= tiles * a.splits) return;
     const int z = L / tiles, tile = L - z * tiles;
     const int tm = tile / a.tiles_n, tn = tile - tm * a.tiles_n;
-    const int m0 = tm * DM, n0 = tn * DN;
+    const int m0 = tm * GEO::TM, n0 = tn * GEO::TN;
     const int s_begin = z * a.stages_per_split;
     const int s_end = min(a.stages_total, s_begin + a.stages_per_split);
     const int n_stages = s_end - s_begin;
     if (n_stages <= 0) return;
     const int spe = a.T / DK;                       // stages per example
 
-    // ---- global -> LDS.  Wave w copies rows (DK/8) w .. of the A part and of the G part of a stage, two rows
-    //      per instruction (lane / 32 picks the row, lane % 32 the chunk position).  Addresses are a uniform
-    //      64-bit stage base (SGPR) plus a 32-bit per-lane byte offset that never changes.
-    uint32_t offA[IPO], offG[IPO];
+    // ---- global -> LDS.  The A part of a stage (DK rows of RBA bytes) and its G part are each a linear run of
+    //      16-byte chunks; copy u of wave w moves chunks 64 (w IP + u) .. + 63, one per lane.  Addresses are a
+    //      uniform 64-bit stage base (SGPR) plus a 32-bit per-lane byte offset that never changes.
+    uint32_t offA[IPA], offG[IPG];
 #pragma unroll
-    for (int u = 0; u < IPO; ++u) {
-        const int r = wave * (DK / 8) + 2 * u + (lane >> 5);          // row inside the stage
-        const int c = (lane & 31) ^ chunk_swz(r);
-        int ca = m0 + c * 8, cn = n0 + c * 8;
-        if (ca >= a.M) ca = m0;                     // out-of-range columns only feed output rows / columns that are never stored
-        if (cn >= a.N) cn = n0;
-        offA[u] = ((uint32_t)r * (uint32_t)a.M + (uint32_t)ca) * 2u;
-        offG[u] = ((uint32_t)r * (uint32_t)a.N + (uint32_t)cn) * 2u;
+    for (int u = 0; u < IPA; ++u) {
+        const int idx = (wave * IPA + u) * 64 + lane;
+        const int r = idx / (RBA / 16);                               // row inside the stage
+        int col = m0 + (((idx % (RBA / 16)) ^ chunk_swz<RBA>(r)) << 3);
+        if (col >= a.M) col = m0;                   // out-of-range columns only feed output rows that are never stored
+        offA[u] = ((uint32_t)r * (uint32_t)a.M + (uint32_t)col) * 2u;
+    }
+#pragma unroll
+    for (int u = 0; u < IPG; ++u) {
+        const int idx = (wave * IPG + u) * 64 + lane;
+        const int r = idx / (RBG / 16);
+        int col = n0 + (((idx % (RBG / 16)) ^ chunk_swz<RBG>(r)) << 3);
+        if (col >= a.N) col = n0;
+        offG[u] = ((uint32_t)r * (uint32_t)a.N + (uint32_t)col) * 2u;
     }
     const uint16_t* baseA = a.A + (size_t)s_begin * DK * a.M;         // uniform
     const uint16_t* baseG = a.G + (size_t)s_begin * DK * a.N;
@@ -110,47 +139,47 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     // does not make every LDS read wait for all copies in flight; the waits for them are the explicit
     // vmcnt waits in front of the stage barriers below.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
-    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_base + wave * (DK / 8) * ROW_BYTES);
+    const uint32_t wave_ldsA = __builtin_amdgcn_readfirstlane(lds_base + wave * IPA * 1024);
+    const uint32_t wave_ldsG = __builtin_amdgcn_readfirstlane(lds_base + OPA + wave * IPG * 1024);
     auto issue = [&](int buf) {
 #if defined(DPK_EXP) && DPK_EXP == 2
         (void)buf; return;                          // scratch timing experiment: no copies at all
 #endif
-        const uint32_t base = wave_lds + buf * STAGE_BYTES;
 #pragma unroll
-        for (int u = 0; u < IPO; ++u)
+        for (int u = 0; u < IPA; ++u)
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(base + u * 1024), "v"(offA[u]), "s"(baseA) : "memory", "m0");
+                         :: "s"(wave_ldsA + buf * STAGE_BYTES + u * 1024), "v"(offA[u]), "s"(baseA) : "memory", "m0");
 #pragma unroll
-        for (int u = 0; u < IPO; ++u)
+        for (int u = 0; u < IPG; ++u)
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(base + OPND_BYTES + u * 1024), "v"(offG[u]), "s"(baseG) : "memory", "m0");
+                         :: "s"(wave_ldsG + buf * STAGE_BYTES + u * 1024), "v"(offG[u]), "s"(baseG) : "memory", "m0");
         baseA += stepA;
         baseG += stepG;
     };
 
     // ---- LDS -> MFMA operands.  Lane l of a 16-lane group: source row j = (l % 16) / 4, source column
     //      piece q = l % 4; after the transposing read the lane holds 4 k values of column l % 16.
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave / GEO::WN, wn = wave % GEO::WN;
     const int g16 = lane >> 4, s16 = lane & 15;
     const int half = g16 >> 1;                      // lanes 32..63 hold k + 8 .. k + 15 of a 16-wide k step
     const int rsrc = 8 * half + (s16 >> 2);         // row inside the k step for the first read (second read: + 4)
-    uint32_t rdA[4], rdG[2];
+    uint32_t rd[NF];                                // 0 .. FM-1: A fragments, FM ..: G fragments
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int ma = wm * 128 + i * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);      // column (element) of the 8-byte piece
-        rdA[i] = rsrc * ROW_BYTES + ((((ma >> 3) ^ chunk_swz(rsrc)) << 4) | ((ma & 7) << 1));
+    for (int i = 0; i < FM; ++i) {
+        const int ma = (wm * FM + i) * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);     // column (element) of the 8-byte piece
+        rd[i] = rsrc * RBA + ((((ma >> 3) ^ chunk_swz<RBA>(rsrc)) << 4) | ((ma & 7) << 1));
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int na = wn * 64 + j * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
-        rdG[j] = OPND_BYTES + rsrc * ROW_BYTES + ((((na >> 3) ^ chunk_swz(rsrc)) << 4) | ((na & 7) << 1));
+    for (int j = 0; j < FN; ++j) {
+        const int na = (wn * FN + j) * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
+        rd[FM + j] = OPA + rsrc * RBG + ((((na >> 3) ^ chunk_swz<RBG>(rsrc)) << 4) | ((na & 7) << 1));
     }
 
-    f32x16 acc[4][2];
+    f32x16 acc[FM][FN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -172,22 +201,22 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     // Software pipeline over k steps: while the MFMAs of one k step run, the LDS reads of the next one are
     // in flight, also across the stage boundary.  The barrier that makes stage st + 1 visible therefore
     // sits in front of the last k step of stage st.
-    auto read_kstep = [&](bf16x8 (&f)[6], uint32_t sb, int ks) {
-        LDS_PTR(unsigned char) b = (LDS_PTR(unsigned char))lds + sb + ks * 16 * ROW_BYTES;
+    auto read_kstep = [&](bf16x8 (&f)[NF], uint32_t sb, int ks) {
+        LDS_PTR(unsigned char) b = (LDS_PTR(unsigned char))lds + sb;
 #pragma unroll
-        for (int x = 0; x < 6; ++x) {
-            const uint32_t off = x < 4 ? rdA[x & 3] : rdG[x & 1];
+        for (int x = 0; x < NF; ++x) {
+            const uint32_t off = rd[x] + ks * 16 * (x < FM ? RBA : RBG);
             const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off));
-            const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off + 4 * ROW_BYTES));
+            const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + off + 4 * (x < FM ? RBA : RBG)));
             f[x] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     };
-    auto mfma_kstep = [&](const bf16x8 (&f)[6]) {
+    auto mfma_kstep = [&](const bf16x8 (&f)[NF]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[4 + j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[FM + j], acc[i][j], 0, 0, 0);
     };
     // stage s (relative) landed once at most `ahead` later stages' copies are outstanding
     auto wait_stage = [&](int ahead) {
@@ -202,7 +231,7 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
 
     wait_stage(min(n_stages - 1, NST - 1));
     __builtin_amdgcn_s_barrier();
-    bf16x8 f[2][6];                                 // fragments of the current / next k step: 0..3 of A, 4..5 of G
+    bf16x8 f[2][NF];                                // fragments of the current / next k step
     read_kstep(f[0], 0u, 0);
 
     for (int st = 0; st < n_stages; ++st) {
@@ -215,9 +244,9 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
             if (c_next != c_cur) {
                 const float ratio = c_cur / c_next;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < FM; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                    for (int j = 0; j < FN; ++j)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
             }
@@ -249,13 +278,13 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
         // sum of squares over the valid part of the tile (columns / rows beyond d_out / d_in hold clamped copies)
         float sq = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int n = n0 + wn * 64 + j * 32 + lrow;
+            for (int j = 0; j < FN; ++j) {
+                const int n = n0 + (wn * FN + j) * 32 + lrow;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                    const int m = m0 + (wm * FM + i) * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
                     const float v = acc[i][j][r];
                     sq += (m < a.M && n < a.N) ? v * v : 0.f;
                 }
@@ -268,7 +297,7 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
         if (tid == 0) {
             float t = 0.f;
 #pragma unroll
-            for (int w = 0; w < DTHREADS / 64; ++w) t += red[w];
+            for (int w = 0; w < GEO::WAVES; ++w) t += red[w];
             a.out[(size_t)z * tiles + tile] = t;
         }
         return;
@@ -276,14 +305,14 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
     // the tile holds (1 / c_cur) * sum: finish with the last example's factor
     float* out = a.out + (size_t)z * a.slice;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn * 64 + j * 32 + lrow;
+        for (int j = 0; j < FN; ++j) {
+            const int n = n0 + (wn * FN + j) * 32 + lrow;
             if (n >= a.N) continue;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                const int m = m0 + (wm * FM + i) * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
                 if (m < a.M) {
                     float* p = out + (size_t)m * a.N + n;
                     const float v = acc[i][j][r] * c_cur;
@@ -293,31 +322,42 @@ __global__ __launch_bounds__(DTHREADS, 1) void k_tn_bf16_dma(DmaArgs a) {
         }
 }
 
-// rows per stage: 64 when every example is a whole number of 64-row stages, else 32
-inline int dma_dk(int T) { (void)T; return 32; }
-
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// at most a quarter of the padded tiles may be waste
+inline bool tiles_fit(int M, int N, int TM, int TN) {
+    const int64_t padded = (int64_t)ceil_div(M, TM) * TM * ceil_div(N, TN) * TN;
+    return padded * 4 <= (int64_t)M * N * 5;
+}
+
+// 0: not for this kernel; 1: GeoL; 2: GeoS
+int dma_geometry(int T, int M, int N) {
+    if ((T % DK) != 0 || ((M | N) & 7) != 0) return 0;
+    if ((int64_t)DK * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return 0;        // 32-bit lane offsets inside a stage
+    if (tiles_fit(M, N, GeoL::TM, GeoL::TN)) return 1;
+    if (tiles_fit(M, N, GeoS::TM, GeoS::TN)) return 2;
+    return 0;
+}
+
+template <class GEO, int MODE> hipError_t launch_geo(const DmaArgs& a, hipStream_t st) {
+    k_tn_bf16_dma<GEO, MODE><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+    return hipGetLastError();
+}
 
 }  // namespace
 
-bool dma_clipped_ok(int B, int T, int M, int N) {
-    (void)B;
-    if ((T % 32) != 0 || ((M | N) & 7) != 0) return false;
-    if ((int64_t)64 * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;     // 32-bit lane offsets inside a stage
-    const int64_t padded = (int64_t)ceil_div(M, DM) * DM * ceil_div(N, DN) * DN;
-    return padded * 4 <= (int64_t)M * N * 5;                              // at most a quarter of the padded tiles is waste
-}
+bool dma_clipped_ok(int B, int T, int M, int N) { (void)B; return dma_geometry(T, M, N) != 0; }
 
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
+    const bool large = dma_geometry(T, M, N) == 1;
     TnPlan p;
-    p.tile_m = DM; p.tile_n = DN;
-    p.tiles_m = ceil_div(M, DM); p.tiles_n = ceil_div(N, DN);
+    p.tile_m = large ? GeoL::TM : GeoS::TM; p.tile_n = large ? GeoL::TN : GeoS::TN;
+    p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    const int DK = dma_dk(T);
     const int64_t stages = (int64_t)B * T / DK;
-    // one workgroup per compute unit: as many K slices as fit into 256 workgroups, at least 8 stages each
-    int64_t splits = 256 / tiles;
+    // fill the chip once (256 compute units x workgroups per unit) with K slices of at least 8 stages each
+    int64_t splits = 256 * (large ? GeoL::OCC : GeoS::OCC) / tiles;
     if (splits < 1) splits = 1;
     const int64_t max_splits = (stages + 7) / 8;
     if (splits > max_splits) splits = max_splits;
@@ -335,7 +375,6 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.A = A; a.G = G; a.clip = clip;
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.splits = p.splits;
-    const int DK = dma_dk(T);
     a.stages_total = (int)((int64_t)B * T / DK);
     a.stages_per_split = p.kchunk / DK;
     const int64_t n = (int64_t)M * N;
@@ -343,36 +382,38 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    if (DK == 64) k_tn_bf16_dma<64, 2, 0><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
-    else k_tn_bf16_dma<32, 4, 0><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 0>(a, st) : launch_geo<GeoS, 0>(a, st);
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
 }
 
-bool dma_direct_ok(int T, int M, int N) {
-    if (T < 64 || (T % 32) != 0 || ((M | N) & 7) != 0) return false;
-    if ((int64_t)64 * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;     // 32-bit lane offsets inside a stage
-    const int64_t padded = (int64_t)ceil_div(M, DM) * DM * ceil_div(N, DN) * DN;
-    return padded * 4 <= (int64_t)M * N * 5;                              // at most a quarter of the padded tiles is waste
+bool dma_direct_ok(int T, int M, int N) { return T >= 64 && dma_geometry(T, M, N) != 0; }
+
+TnPlan plan_direct_bf16_dma(int T, int M, int N) {
+    const bool large = dma_geometry(T, M, N) == 1;
+    TnPlan p;
+    p.tile_m = large ? GeoL::TM : GeoS::TM; p.tile_n = large ? GeoL::TN : GeoS::TN;
+    p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
+    p.segmented = false; p.big = false; p.dma = true;
+    p.splits = 1; p.kchunk = 0; p.epu = 1;
+    return p;
 }
 
-hipError_t launch_direct_bf16_dma(const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
+hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
     DmaArgs a;
     a.A = A; a.G = G; a.clip = nullptr;
     a.B = B; a.T = T; a.M = M; a.N = N;
-    a.tiles_m = ceil_div(M, DM); a.tiles_n = ceil_div(N, DN);
+    a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n;
     a.splits = B;
-    a.stages_total = (int)((int64_t)B * T / 32);
-    a.stages_per_split = T / 32;
+    a.stages_total = (int)((int64_t)B * T / DK);
+    a.stages_per_split = T / DK;
     a.out = partial; a.slice = 0; a.accumulate = 0;
     const int tiles = a.tiles_m * a.tiles_n;
     const int64_t total = (int64_t)tiles * B;
     if (total >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     a.per_xcd = ceil_div(total, 8);
-    k_tn_bf16_dma<32, 4, 1><<<8u * (unsigned)a.per_xcd, DTHREADS, 0, st>>>(a);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 1>(a, st) : launch_geo<GeoS, 1>(a, st);
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
 }

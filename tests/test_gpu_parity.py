@@ -144,6 +144,8 @@ RAGGED = [
     (1, 64, 7, 9), (2, 33, 129, 65),
     # large aligned tiles with ragged edges (256 x 256 clipped-sum kernels), T % 32 == 0 and T % 8 == 0 only
     (5, 64, 456, 248), (3, 96, 264, 520), (3, 40, 456, 248), (9, 32, 512, 256), (2, 160, 504, 488),
+    # 192 x 128 tiles of the copy-pipeline kernel (narrow layers), with ragged edges
+    (3, 64, 376, 120), (2, 96, 192, 256), (5, 32, 576, 128),
     # aligned Gram kernel (d % 64 == 0, T > 64) with a ragged last row tile and with one or several tiles
     (3, 200, 128, 192), (2, 128, 64, 320), (2, 300, 256, 64), (3, 72, 192, 128),
 ]
