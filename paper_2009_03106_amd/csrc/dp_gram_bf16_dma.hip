@@ -100,13 +100,8 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         off_t[0][u] = rt * (uint32_t)a.d_in * 2u + c16;  off_s[0][u] = rs * (uint32_t)a.d_in * 2u + c16;
         off_t[1][u] = rt * (uint32_t)a.d_out * 2u + c16; off_s[1][u] = rs * (uint32_t)a.d_out * 2u + c16;
     }
-#if defined(DPK_EXP) && DPK_EXP == 4
-    const uint16_t* baseA = a.A;                   // scratch timing experiment: every workgroup reads example 0 (L2 resident)
-    const uint16_t* baseG = a.G;
-#else
     const uint16_t* baseA = a.A + (size_t)ex * a.T * a.d_in;          // uniform example bases; lane offsets stay 32-bit
     const uint16_t* baseG = a.G + (size_t)ex * a.T * a.d_out;
-#endif
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_base + wave * 32 * ROWB);
     // The copies are inline assembly so that the compiler does not tie every LDS read to them; they are
@@ -123,9 +118,6 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         }
     };
     auto issue = [&](int st, int buf) {
-#if defined(DPK_EXP) && DPK_EXP == 3
-        (void)st; (void)buf; return;               // scratch timing experiment: no copies at all
-#endif
         if (st < sa) issue_phase(baseA + st * GK, off_t[0], off_s[0], buf);
         else issue_phase(baseG + (st - sa) * GK, off_t[1], off_s[1], buf);
     };
@@ -169,9 +161,6 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     bf16x8 f[2][4];
     // wait until at most `stages` later stages' copies are outstanding (4 per wave and stage on a diagonal pair, else 8)
     auto wait_copies = [&](int stages) {
-#if defined(DPK_EXP) && (DPK_EXP == 5 || DPK_EXP == 6)
-        (void)stages; return;                      // scratch timing experiment: never wait for the copies
-#endif
         // copies per wave and stage: IPT on a diagonal pair, else 2 * IPT
         if (stages <= 0) wait_vm<0>();
         else if (stages == 1) { if (diag) wait_vm<IPT>(); else wait_vm<2 * IPT>(); }
@@ -189,39 +178,17 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
                 // pair, else 8) may stay in flight
                 wait_copies(min(n_stages - 2 - st, GNST - 2));
                 __builtin_amdgcn_s_barrier();                // ... for every wave, and every wave is done reading stage st
-#if !(defined(DPK_EXP) && DPK_EXP == 6)
                 if (st + GNST < n_stages) issue(st + GNST, st % GNST);
-#endif
                 read_kstep(f[0], (st + 1) % GNST, 0);
             }
-#if defined(DPK_EXP) && DPK_EXP == 6
-            {   // scratch timing experiment: copies of the next stage spread between the MFMAs, never waited for
-                const bf16x8 (&ff)[4] = f[ks & 1];
-                const int tg = st + 1;
-                const bool on = tg < n_stages;
-                const uint16_t* sbase = tg < sa ? baseA + tg * GK : baseG + (tg - sa) * GK;
-                const uint32_t base = wave_lds + (tg % GNST) * GSTAGE;
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[0], ff[2], acc[0][0], 0, 0, 0);
-                if (on) asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + ks * 1024), "v"(tg < sa ? off_t[0][ks] : off_t[1][ks]), "s"(sbase) : "memory", "m0");
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[0], ff[3], acc[0][1], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[1], ff[2], acc[1][0], 0, 0, 0);
-                if (on && !diag) asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(base + TILE_BYTES + ks * 1024), "v"(tg < sa ? off_s[0][ks] : off_s[1][ks]), "s"(sbase) : "memory", "m0");
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[1], ff[3], acc[1][1], 0, 0, 0);
-            }
-#else
             mfma_kstep(f[ks & 1], acc);
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
 #pragma unroll
     for (int p = 0; p < GNST; ++p)
-#if defined(DPK_EXP) && DPK_EXP == 6
-        if (p < 1) issue(p, p);
-#else
         if (p < n_stages) issue(p, p);
-#endif
     wait_copies(min(n_stages, GNST) - 1);                        // stage 0 must have landed
     __builtin_amdgcn_s_barrier();
     read_kstep(f[0], 0, 0);

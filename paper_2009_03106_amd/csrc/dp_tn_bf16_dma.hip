@@ -142,9 +142,6 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     const uint32_t wave_ldsA = __builtin_amdgcn_readfirstlane(lds_base + wave * IPA * 1024);
     const uint32_t wave_ldsG = __builtin_amdgcn_readfirstlane(lds_base + OPA + wave * IPG * 1024);
     auto issue = [&](int buf) {
-#if defined(DPK_EXP) && DPK_EXP == 2
-        (void)buf; return;                          // scratch timing experiment: no copies at all
-#endif
 #pragma unroll
         for (int u = 0; u < IPA; ++u)
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -220,9 +217,6 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     };
     // stage s (relative) landed once at most `ahead` later stages' copies are outstanding
     auto wait_stage = [&](int ahead) {
-#if defined(DPK_EXP) && (DPK_EXP == 1 || DPK_EXP == 2)
-        (void)ahead; return;                        // scratch timing experiment: no waits for the copies
-#endif
         if (NST >= 4 && ahead >= 3) wait_vmcnt<3 * LPS>();
         else if (NST >= 3 && ahead == 2) wait_vmcnt<2 * LPS>();
         else if (ahead == 1) wait_vmcnt<LPS>();
