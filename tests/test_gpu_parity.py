@@ -171,6 +171,26 @@ def test_ragged_shapes(dp, dtype, B, T, d_in, d_out):
     assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL[dtype]
 
 
+# long sequences (many Gram tile pairs, ragged last tile), wide layers (many output tiles, few rows), one example
+LARGE = [(2, 2048, 128, 192), (1, 1056, 64, 64), (3, 64, 2048, 1024), (1, 4096, 64, 128), (11, 96, 768, 384)]
+
+
+@pytest.mark.parametrize("B,T,d_in,d_out", LARGE)
+def test_large_shapes(dp, B, T, d_in, d_out):
+    A, G = wl.random_layer(4321 + T + d_in, B, T, d_in, d_out, "bf16", g_row_scale=np.exp(np.linspace(-2, 2, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    C = float(np.sqrt(np.median(s_ref))) if B > 1 else float(np.sqrt(s_ref[0]) / 3)
+    c_ref = orc.clip_factors(s_ref, C)
+    g_ref = orc.clipped_grad(A, G, c_ref)
+    Ad, Gd = to_dev(A), to_dev(G)
+    for path in ("gram", "direct"):
+        s = dp.layer_sqnorm(Ad, Gd, path=path)
+        assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["bf16"], (path, rel_err(s.cpu().numpy(), s_ref))
+    c = dp.clip_factors(s, C)
+    g = dp.clipped_grad(Ad, Gd, c)
+    assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL["bf16"]
+
+
 def test_accumulate_flags(dp):
     A, G = wl.random_layer(77, 6, 9, 40, 24, "bf16")
     Ad, Gd = to_dev(A), to_dev(G)
