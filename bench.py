@@ -116,16 +116,22 @@ def algorithmic_work(w, B):
 
 
 def time_steps(pipe, torch, steps, warmup):
+    """(ms per step, ms per phase).  The step time is the wall clock around `steps` back-to-back steps between two
+    device synchronisations, with nothing else in the stream; the phase times come from a second pass of the same
+    number of steps with HIP events between the phases (the event records cost a few microseconds each, which is
+    why they stay out of the pass that is timed as a whole)."""
     for _ in range(warmup):
         pipe.step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for k in range(steps):
+        pipe.step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
     for k in range(steps):
         pipe.step(evs[k])
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
     phases = np.zeros(4)
     for k in range(steps):
         for p in range(4):

@@ -265,6 +265,49 @@ def test_reruns_are_bit_identical(dp):
 
 
 # ----------------------------------------------------------------- noise
+def test_pipeline_is_graph_capturable(dp):
+    """The library neither allocates nor synchronises, so a whole step can be captured into a HIP graph; every
+    replay (with eager work in between) must reproduce the eager results bit for bit."""
+    w, layers = wl.generate("rnn")
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    B = dev[0][0].shape[0]
+    s = torch.zeros(B, device="cuda")
+    c = torch.zeros(B, device="cuda")
+    grads = [torch.zeros(A.shape[2], G.shape[2], device="cuda") for A, G in dev]
+    ws = [(torch.empty(max(16, dp.workspace_bytes(dp.DP_OP_SQNORM, B, A.shape[1], A.shape[2], G.shape[2], dp.DP_BF16)),
+                       dtype=torch.uint8, device="cuda"),
+           torch.empty(max(16, dp.workspace_bytes(dp.DP_OP_CLIPPED_GRAD, B, A.shape[1], A.shape[2], G.shape[2], dp.DP_BF16)),
+                       dtype=torch.uint8, device="cuda")) for A, G in dev]
+
+    def step():
+        for li, (A, G) in enumerate(dev):
+            dp.layer_sqnorm(A, G, s, accumulate=li > 0, workspace=ws[li][0])
+        dp.clip_factors(s, w.C, c)
+        for li, (A, G) in enumerate(dev):
+            dp.clipped_grad(A, G, c, grads[li], workspace=ws[li][1])
+            dp.add_noise(grads[li], 0.5, 99, 0)
+
+    step()
+    torch.cuda.synchronize()
+    want = [s.clone(), c.clone()] + [g.clone() for g in grads]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in [s, c] + grads:
+            t.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip([s, c] + grads, want):
+            assert torch.equal(got, ref), rep
+        _ = torch.randn(1 << 18, device="cuda").sum().item()        # eager work and a synchronisation between replays
+
+
 def test_philox_words_bit_exact(dp):
     for seed, first in [(0, 0), (0x0123456789ABCDEF, (1 << 32) - 1000), (20090310, (1 << 40) + 7)]:
         n = 5000
