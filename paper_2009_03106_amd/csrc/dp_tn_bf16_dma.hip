@@ -2,18 +2,17 @@
 //
 // gfx950-specific data path with (almost) no VALU work in the main loop:
 //   * global -> LDS copies go straight into LDS (global_load_lds_dwordx4): a
-//     wave instruction moves 1 KB of a K-major tile, as it lies in memory
-//     (two 512-byte rows).  Four 32-row stages are kept in LDS, three of them
-//     in flight while one is consumed.
+//     wave instruction moves 1 KB of a K-major tile, as it lies in memory.
+//     A ring of 32-row stages is kept in LDS, all but one of them in flight
+//     while one is consumed.
 //   * the 16-bit transpose the MFMA needs (a lane must hold consecutive k for
 //     one column, memory has consecutive columns for one k) is done by the
 //     LDS read itself (ds_read_b64_tr_b16): 16 lanes read a 4(k) x 16(col)
 //     patch and each lane gets the 4 k values of one column.
-//   * 256 x 256 output tile per workgroup of 8 waves (128 x 64 each = 128
-//     accumulator registers, two waves per SIMD), one workgroup per compute
-//     unit.  The tile size is set by the L2: at 256 x 128 the kernel ran into
-//     the ~10 TB/s the L2s deliver to the compute units (85 flop per byte);
-//     256 x 256 needs 128 flop per byte.
+//   * two tile geometries (struct Geo below): 256 x 256 per workgroup of 8
+//     waves, one workgroup per compute unit, for layers whose clipped sum is
+//     bound by the MFMA rate; 192 x 128 per workgroup of 4 waves, two
+//     workgroups per compute unit, for narrow layers bound by HBM.
 //
 // Clip factors are applied to the fp32 accumulators, not to the bf16 inputs:
 // the tile holds  (1 / c_cur) * sum_{j <= cur} c_j g_j ; when the rows of the
