@@ -151,6 +151,38 @@ def clipped_grad_by_clip_function(A, G, C: float, other_sq: np.ndarray | None = 
 
 
 # --------------------------------------------------------------------------
+# bias parameters
+# --------------------------------------------------------------------------
+def bias_rows(G) -> np.ndarray:
+    """Per-example gradient of the layer's bias vector, [B, d_out]: dL/db = dL/dz for a
+    fully-connected layer (Section 5.1) and the sum over positions, sum_t dL/dz^(t), when the
+    bias is shared by T positions (Section 5.3; likewise over the output positions of a
+    convolution)."""
+    G = _as3d(G)
+    out = np.zeros((G.shape[0], G.shape[2]), dtype=np.float64)
+    for i in range(G.shape[0]):
+        for t in range(G.shape[1]):
+            out[i] += G[i, t]
+    return out
+
+
+def bias_sqnorm(G) -> np.ndarray:
+    """s[i] = ||dL_i/db||^2: the bias's share of the squared gradient norm (Section 5,
+    paragraph before 5.1: the norm runs over the weight matrix and the bias of every layer)."""
+    u = bias_rows(G)
+    return np.sum(u * u, axis=1)
+
+
+def clipped_bias_grad(G, clip: np.ndarray) -> np.ndarray:
+    """sum_i nu_i dL_i/db, [d_out] (Eq. weighted_loss applied to the bias)."""
+    u = bias_rows(G)
+    out = np.zeros(u.shape[1], dtype=np.float64)
+    for i in range(u.shape[0]):
+        out += float(clip[i]) * u[i]
+    return out
+
+
+# --------------------------------------------------------------------------
 # path choice (host logic twin for tests)
 # --------------------------------------------------------------------------
 def gram_flops(T: int, d_in: int, d_out: int) -> int:

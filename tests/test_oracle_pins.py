@@ -37,6 +37,10 @@ def test_hand_worked_cases():
         np.testing.assert_array_equal(orc.layer_sqnorm_gram(A, G), s)
         nu = orc.clip_factors(s, c["C"])
         np.testing.assert_allclose(nu, [_eval_expr(e) for e in c["clip"]], rtol=1e-15)
+        np.testing.assert_array_equal(orc.bias_rows(G), np.array(c["bias_rows"], dtype=np.float64))
+        np.testing.assert_array_equal(orc.bias_sqnorm(G), np.array(c["bias_sqnorm"], dtype=np.float64))
+        if "clipped_bias" in c:
+            np.testing.assert_allclose(orc.clipped_bias_grad(G, nu), [_eval_expr(e) for e in c["clipped_bias"]], rtol=1e-15)
         if "clipped_sum" in c:
             np.testing.assert_allclose(orc.clipped_grad(A, G, nu), np.array(c["clipped_sum"], dtype=np.float64),
                                        rtol=1e-15, atol=1e-15)
@@ -140,6 +144,32 @@ def test_additivity_over_output_split_and_layers():
     G2 = _rand(12, 4, 1, 3)
     tot = orc.total_sqnorm([(A, G), (A2, G2)])
     np.testing.assert_allclose(tot, orc.layer_sqnorm(A, G) + orc.layer_sqnorm(A2, G2), rtol=1e-15)
+
+
+def test_bias_equals_ones_column():
+    """A bias is a weight row fed by a constant 1: appending a column of ones to A adds exactly the bias's
+    share to the squared norm and one row, the bias gradient, to the clipped sum (Z = XW + b, Algorithm 1)."""
+    for seed, (B, T, di, do) in enumerate([(3, 1, 5, 4), (4, 7, 3, 6), (2, 12, 8, 2)]):
+        A, G = _rand(100 + seed, B, T, di), _rand(200 + seed, B, T, do)
+        A1 = np.concatenate([A, np.ones((B, T, 1))], axis=2)
+        np.testing.assert_allclose(orc.layer_sqnorm(A1, G) - orc.layer_sqnorm(A, G), orc.bias_sqnorm(G), rtol=1e-11)
+        nu = orc.clip_factors(orc.layer_sqnorm(A1, G), 1.5)
+        full = orc.clipped_grad(A1, G, nu)
+        np.testing.assert_allclose(full[-1], orc.clipped_bias_grad(G, nu), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(full[:-1], orc.clipped_grad(A, G, nu), rtol=1e-12, atol=1e-13)
+
+
+def test_bias_brute_force():
+    B, T, do = 3, 4, 5
+    G = _rand(7, B, T, do)
+    nu = np.array([0.25, 1.0, 0.5])
+    u = [[sum(float(G[i, t, q]) for t in range(T)) for q in range(do)] for i in range(B)]
+    np.testing.assert_allclose(orc.bias_rows(G), u, rtol=1e-14)
+    np.testing.assert_allclose(orc.bias_sqnorm(G), [sum(x * x for x in row) for row in u], rtol=1e-14)
+    np.testing.assert_allclose(orc.clipped_bias_grad(G, nu), [sum(nu[i] * u[i][q] for i in range(B)) for q in range(do)], rtol=1e-14)
+    # T = 1: the bias gradient is dL/dz itself (Section 5.1)
+    G1 = _rand(8, 4, 1, 6)
+    np.testing.assert_array_equal(orc.bias_rows(G1), G1[:, 0, :])
 
 
 def test_per_example_grad_orientation():
