@@ -243,6 +243,30 @@ def main():
     if noise_ms > 0 and work["noise_bytes"]:
         phases_out["noise_gbs"] = work["noise_bytes"] / (noise_ms * 1e-3) / 1e9
 
+    # bias parameters (the first of the "next" rows): per-example bias gradients + their squared norms for every
+    # layer, then the clipped bias sums; timed on their own, not part of `value`
+    es = 2 if w.dtype == "bf16" else 4
+    rows = [torch.empty((B, spec.d_out), dtype=torch.float32, device="cuda") for spec in w.layers]
+    gbs = [torch.empty(spec.d_out, dtype=torch.float32, device="cuda") for spec in w.layers]
+    evb = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    tb = np.zeros(2)
+    for rep in range(5 + 2):
+        evb[0].record()
+        for (A, G), u in zip(pipe.dev, rows):
+            dp.bias_sqnorm(G, pipe.s, u, accumulate=True)
+        evb[1].record()
+        for u, gb in zip(rows, gbs):
+            dp.clipped_bias_grad(u, pipe.c, gb)
+        evb[2].record()
+        torch.cuda.synchronize()
+        if rep >= 2:
+            tb += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
+    tb /= 5
+    bias_bytes = sum(B * spec.T * spec.d_out * es + 4 * B * spec.d_out for spec in w.layers)
+    bias_out = {"bias_sqnorm_ms": tb[0], "clipped_bias_grad_ms": tb[1], "bias_sqnorm_gbs": bias_bytes / (tb[0] * 1e-3) / 1e9,
+                "algorithmic_bytes": bias_bytes}
+    del rows, gbs
+
     others = {}
     if not args.no_others and args.batch is None:
         flush = torch.zeros(1 << 27, dtype=torch.float32, device="cuda")
@@ -275,7 +299,7 @@ def main():
         "config": {"workload": f"{w.name}: B={B}, " + ", ".join(f"{s.name} T={s.T} {s.d_in}->{s.d_out}" for s in w.layers)
                    + f", C={w.C}" + (f", noise std={w.noise_std}" if w.noise_std > 0 else ""),
                    "path": args.path, "parallelism": "single GPU"},
-        "roofline": roof, "phases": phases_out, "other_workloads": others,
+        "roofline": roof, "phases": phases_out, "bias_terms": bias_out, "other_workloads": others,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w.name, min(w.B, B))

@@ -101,13 +101,40 @@ dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C,
  *   clip       device float32[B]
  *   workspace  device scratch of at least
  *              dp_workspace_bytes(DP_OP_CLIPPED_GRAD, ...) bytes
- * With bf16 inputs clip[i]*A is rounded back to bf16 before the matrix
- * multiply (relative error 2^-9 per element, unbiased). */
+ * With bf16 inputs the factor is applied either to the fp32 accumulators (one
+ * fp32 rounding per example) or, in the kernels for unaligned shapes, to the
+ * rows of A, which are then rounded back to bf16 (relative error 2^-9 per
+ * element, unbiased). */
 dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
                           int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                           dp_dtype dtype, int accumulate, float* grad,
                           void* workspace, size_t workspace_bytes,
                           void* hip_stream);
+
+/* Bias parameters.  The per-example gradient of a layer's bias vector is
+ * dL/dz itself for a fully-connected layer (Section 5.1) and its sum over the
+ * T positions that share the bias otherwise (Section 5.3; the output positions
+ * of a convolution likewise):
+ *     bias_rows[i, :] = sum_t G_i[t, :]
+ *     sqnorm[i]       = (accumulate ? sqnorm[i] : 0) + ||bias_rows[i, :]||^2
+ * (the norm of the whole parameter gradient runs over weights and biases,
+ * Section 5, paragraph before 5.1: call this with accumulate = 1 on the array
+ * that dp_layer_sqnorm fills).
+ *   G          device, [B,T,d_out] of `dtype`, read only
+ *   bias_rows  device, float32[B, d_out], written; keep it for dp_clipped_bias_grad
+ *   sqnorm     device, float32[B]
+ * B must be < 65536 (DP_ERR_UNSUPPORTED otherwise).  No workspace. */
+dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
+                         dp_dtype dtype, int accumulate, float* sqnorm,
+                         float* bias_rows, void* hip_stream);
+
+/* Clipped batch gradient of the bias (Eq. weighted_loss applied to b):
+ *     grad_b[q] = (accumulate ? grad_b[q] : 0) + sum_i clip[i] * bias_rows[i, q]
+ *   bias_rows  device float32[B, d_out] from dp_bias_sqnorm, read only
+ *   clip       device float32[B];  grad_b  device float32[d_out] */
+dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
+                               int64_t B, int64_t d_out, int accumulate,
+                               float* grad_b, void* hip_stream);
 
 /* Gaussian mechanism (Section 2, Gaussian-mechanism lemma; Algorithm 1, the
  * update line): grad[j] += stddev * z[offset + j], j in [0, n), with z an

@@ -167,6 +167,47 @@ dp_status dp_clipped_grad(const void* A, const void* G, const float* clip, int64
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 
+dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_dtype dtype, int accumulate,
+                         float* sqnorm, float* bias_rows, void* hip_stream) {
+    dp_status st = check_dims(B, T, 1, d_out);
+    if (st != DP_OK) return st;
+    if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
+    if (B >= 65536) return DP_ERR_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (B == 0) return DP_OK;
+    if (!sqnorm) return DP_ERR_INVALID_ARG;
+    if (d_out == 0) {
+        if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (!bias_rows) return DP_ERR_INVALID_ARG;
+    if (T == 0) {
+        if (launch_fill_zero(bias_rows, B * d_out, stream) != hipSuccess) return DP_ERR_HIP;
+        if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (!G || !aligned16(G)) return DP_ERR_INVALID_ARG;
+    hipError_t e = launch_bias_rows(G, (int)B, (int)T, (int)d_out, dtype == DP_BF16, bias_rows, stream);
+    if (e == hipSuccess) e = launch_rows_sqnorm(bias_rows, (int)B, (int)d_out, accumulate != 0, sqnorm, stream);
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip, int64_t B, int64_t d_out, int accumulate,
+                               float* grad_b, void* hip_stream) {
+    dp_status st = check_dims(B, 1, 1, d_out);
+    if (st != DP_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (d_out == 0) return DP_OK;
+    if (!grad_b) return DP_ERR_INVALID_ARG;
+    if (B == 0) {
+        if (!accumulate && launch_fill_zero(grad_b, d_out, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (!bias_rows || !clip) return DP_ERR_INVALID_ARG;
+    hipError_t e = launch_clipped_bias(bias_rows, clip, (int)B, (int)d_out, accumulate != 0, grad_b, stream);
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
 dp_status dp_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, void* hip_stream) {
     if (n < 0 || !(stddev >= 0.0f)) return DP_ERR_INVALID_ARG;
     if (n == 0) return DP_OK;

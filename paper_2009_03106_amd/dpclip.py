@@ -22,8 +22,8 @@ DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
-EXPORTS = ("dp_layer_sqnorm", "dp_clip_factors", "dp_clipped_grad", "dp_add_noise", "dp_workspace_bytes",
-           "dp_choose_path", "dp_status_string", "dp_philox_raw")
+EXPORTS = ("dp_layer_sqnorm", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad",
+           "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
 
 _lib = None
 
@@ -51,6 +51,10 @@ def load_library() -> ctypes.CDLL:
     lib.dp_clip_factors.restype = ci
     lib.dp_clipped_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
     lib.dp_clipped_grad.restype = ci
+    lib.dp_bias_sqnorm.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp]
+    lib.dp_bias_sqnorm.restype = ci
+    lib.dp_clipped_bias_grad.argtypes = [vp, vp, i64, i64, ci, vp, vp]
+    lib.dp_clipped_bias_grad.restype = ci
     lib.dp_add_noise.argtypes = [vp, i64, f32, u64, u64, vp]
     lib.dp_add_noise.restype = ci
     lib.dp_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci, ci]
@@ -170,6 +174,45 @@ def clipped_grad(A: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, grad: Opt
                              _stream_ptr(stream))
     _check(st, "dp_clipped_grad")
     return grad
+
+
+def bias_sqnorm(G: torch.Tensor, sqnorm: Optional[torch.Tensor] = None, bias_rows: Optional[torch.Tensor] = None, *,
+                accumulate: bool = False, stream: Optional[torch.cuda.Stream] = None):
+    """bias_rows[i] = sum_t G_i[t]; sqnorm[i] (+)= ||bias_rows[i]||^2 via dp_bias_sqnorm.  Returns (sqnorm, bias_rows)."""
+    lib = load_library()
+    if G.dim() == 2:
+        G = G.unsqueeze(1)
+    if G.dim() != 3:
+        raise ValueError("G must be [B, d_out] or [B, T, d_out]")
+    G = G.contiguous()
+    B, T, d_out = G.shape
+    if sqnorm is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing sqnorm tensor")
+        sqnorm = torch.empty(B, dtype=torch.float32, device=G.device)
+    if bias_rows is None:
+        bias_rows = torch.empty((B, d_out), dtype=torch.float32, device=G.device)
+    st = lib.dp_bias_sqnorm(_ptr(G), B, T, d_out, _dtype_code(G), int(bool(accumulate)), _ptr(sqnorm), _ptr(bias_rows),
+                            _stream_ptr(stream))
+    _check(st, "dp_bias_sqnorm")
+    return sqnorm, bias_rows
+
+
+def clipped_bias_grad(bias_rows: torch.Tensor, clip: torch.Tensor, grad_b: Optional[torch.Tensor] = None, *,
+                      accumulate: bool = False, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """grad_b (+)= sum_i clip[i] bias_rows[i], float32 [d_out], via dp_clipped_bias_grad."""
+    lib = load_library()
+    if bias_rows.dtype != torch.float32 or bias_rows.dim() != 2 or not bias_rows.is_contiguous():
+        raise TypeError("bias_rows must be a contiguous float32 [B, d_out] tensor")
+    B, d_out = bias_rows.shape
+    if grad_b is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing grad_b tensor")
+        grad_b = torch.empty(d_out, dtype=torch.float32, device=bias_rows.device)
+    st = lib.dp_clipped_bias_grad(_ptr(bias_rows), _ptr(clip), B, d_out, int(bool(accumulate)), _ptr(grad_b),
+                                  _stream_ptr(stream))
+    _check(st, "dp_clipped_bias_grad")
+    return grad_b
 
 
 def add_noise(grad: torch.Tensor, stddev: float, seed: int, offset: int = 0, *,

@@ -265,6 +265,86 @@ def test_reruns_are_bit_identical(dp):
 
 
 # ----------------------------------------------------------------- noise
+# ----------------------------------------------------------------- bias parameters
+BIAS_SHAPES = [(3, 1, 3), (7, 1, 67), (5, 1, 1024), (2, 3, 8), (3, 17, 40), (2, 70, 264), (3, 129, 24), (2, 257, 320),
+               (1, 64, 9), (2, 33, 65), (4, 300, 2304), (9, 5, 4100)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,T,d_out", BIAS_SHAPES)
+def test_bias_shapes(dp, dtype, B, T, d_out):
+    _, G = wl.random_layer(900 + B + T + d_out, B, T, 8, d_out, dtype, g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    u_ref = orc.bias_rows(G)
+    s_ref = orc.bias_sqnorm(G)
+    c_ref = orc.clip_factors(s_ref, 0.8 * float(np.sqrt(np.median(s_ref))))
+    b_ref = orc.clipped_bias_grad(G, c_ref)
+    Gd = to_dev(G)
+    s, u = dp.bias_sqnorm(Gd)
+    # fp32 sums of at most T terms: relative to the largest term's magnitude
+    scale = np.abs(orc.widen(G)).sum(axis=1) if G.ndim == 3 else np.abs(orc.widen(G))
+    assert np.all(np.abs(u.cpu().numpy() - u_ref) <= 1e-6 * np.maximum(scale.reshape(u_ref.shape), 1e-30))
+    assert rel_err(s.cpu().numpy(), s_ref) <= 1e-5
+    s2 = torch.full((B,), 2.5, device="cuda")
+    dp.bias_sqnorm(Gd, s2, accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 2.5) <= 1e-5
+    c = to_dev(c_ref.astype(np.float32))
+    gb = dp.clipped_bias_grad(u, c)
+    ref_scale = np.abs(u_ref * c_ref[:, None]).sum(axis=0)
+    assert np.all(np.abs(gb.cpu().numpy() - b_ref) <= 1e-5 * np.maximum(ref_scale, 1e-30))
+    gb2 = torch.full((d_out,), -1.0, device="cuda")
+    dp.clipped_bias_grad(u, c, gb2, accumulate=True)
+    np.testing.assert_allclose(gb2.cpu().numpy(), gb.cpu().numpy() - 1.0, rtol=1e-6, atol=1e-6)
+
+
+@pytest.mark.parametrize("name", ["mlp", "rnn", "conv", "transformer"])
+def test_bias_on_configurations(dp, name):
+    """Weights and biases together: the squared norm gains the bias share, and the clipped bias gradient
+    uses the factors of the whole parameter gradient (Section 5, paragraph before 5.1)."""
+    B = {"conv": 16, "transformer": 8}.get(name)
+    w, layers = wl.generate(name, B=B)
+    s_ref = orc.total_sqnorm(layers)
+    for _, G in layers:
+        s_ref = s_ref + orc.bias_sqnorm(G)
+    c_ref = orc.clip_factors(s_ref, w.C)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    s, rows = None, []
+    for li, (A, G) in enumerate(dev):
+        s = dp.layer_sqnorm(A, G, s, accumulate=li > 0)
+        _, u = dp.bias_sqnorm(G, s, accumulate=True)
+        rows.append(u)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[w.dtype]
+    c = dp.clip_factors(s, w.C)
+    assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL[w.dtype]
+    for (A, G), u in zip(layers, rows):
+        gb = dp.clipped_bias_grad(u, c).cpu().numpy()
+        assert fro_err(gb, orc.clipped_bias_grad(G, c_ref)) <= 1e-4
+
+
+def test_bias_empty_and_errors(dp):
+    lib = dp.load_library()
+    s = torch.full((4,), 7.0, device="cuda")
+    u = torch.full((4, 6), 7.0, device="cuda")
+    G = torch.zeros((4, 0, 6), device="cuda")
+    # T == 0: rows are zero, the norm is zero
+    assert lib.dp_bias_sqnorm(G.data_ptr() or u.data_ptr(), 4, 0, 6, dp.DP_F32, 0, s.data_ptr(), u.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert float(s.abs().sum()) == 0.0 and float(u.abs().sum()) == 0.0
+    # B == 0 in the clipped sum zero-fills unless accumulating
+    gb = torch.full((6,), 3.0, device="cuda")
+    assert lib.dp_clipped_bias_grad(u.data_ptr(), s.data_ptr(), 0, 6, 1, gb.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert float(gb[0]) == 3.0
+    assert lib.dp_clipped_bias_grad(u.data_ptr(), s.data_ptr(), 0, 6, 0, gb.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert float(gb.abs().sum()) == 0.0
+    # errors: negative sizes, null pointers, unknown dtype, too many examples
+    assert lib.dp_bias_sqnorm(u.data_ptr(), -1, 1, 6, dp.DP_F32, 0, s.data_ptr(), u.data_ptr(), None) == 1
+    assert lib.dp_bias_sqnorm(None, 4, 1, 6, dp.DP_F32, 0, s.data_ptr(), u.data_ptr(), None) == 1
+    assert lib.dp_bias_sqnorm(u.data_ptr(), 4, 1, 6, 7, 0, s.data_ptr(), u.data_ptr(), None) == 1
+    assert lib.dp_bias_sqnorm(u.data_ptr(), 70000, 1, 6, dp.DP_F32, 0, s.data_ptr(), u.data_ptr(), None) == 2
+    assert lib.dp_clipped_bias_grad(u.data_ptr(), None, 4, 6, 0, gb.data_ptr(), None) == 1
+
+
 def test_pipeline_is_graph_capturable(dp):
     """The library neither allocates nor synchronises, so a whole step can be captured into a HIP graph; every
     replay (with eager work in between) must reproduce the eager results bit for bit."""
