@@ -183,6 +183,29 @@ def clipped_bias_grad(G, clip: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# convolution layers given by their input image
+# --------------------------------------------------------------------------
+def conv_unfold(X, KH: int, KW: int, pad: int) -> np.ndarray:
+    """Patch matrix of a stride-1 convolution (the unfolding step of Algorithm 3):
+    X[B, H, W, C] (channels last, zero padding `pad` on every side) ->
+    A[B, H_out*W_out, KH*KW*C] with A[b, y*W_out + x, (kh*KW + kw)*C + c] = Xpad[b, y+kh, x+kw, c].
+    With it the layer is the sequence layer of Eq. recurrent_gradient over the output positions
+    (Section 5.2); the column order only fixes how the [KH*KW*C, d_out] gradient is read."""
+    X = widen(np.asarray(X)) if np.asarray(X).dtype == np.uint16 else np.asarray(X, dtype=np.float64)
+    B, H, W, C = X.shape
+    Xp = np.zeros((B, H + 2 * pad, W + 2 * pad, C), dtype=np.float64)
+    Xp[:, pad:pad + H, pad:pad + W, :] = X
+    ho, wo = H + 2 * pad - KH + 1, W + 2 * pad - KW + 1
+    A = np.zeros((B, ho * wo, KH * KW * C), dtype=np.float64)
+    for y in range(ho):
+        for x in range(wo):
+            for kh in range(KH):
+                for kw in range(KW):
+                    A[:, y * wo + x, (kh * KW + kw) * C:(kh * KW + kw + 1) * C] = Xp[:, y + kh, x + kw, :]
+    return A
+
+
+# --------------------------------------------------------------------------
 # path choice (host logic twin for tests)
 # --------------------------------------------------------------------------
 def gram_flops(T: int, d_in: int, d_out: int) -> int:

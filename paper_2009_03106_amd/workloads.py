@@ -145,3 +145,27 @@ def random_layer(seed: int, B: int, T: int, d_in: int, d_out: int, dtype: str,
     """Free-form shapes for edge-case tests (ragged tiles, tiny sizes)."""
     rng = np.random.default_rng(seed)
     return make_layer(rng, B, LayerSpec("adhoc", T, d_in, d_out), dtype, a_dist, g_std, g_row_scale)
+
+
+# The convolution configuration as an image: the same layer (3 x 3 kernel, padding 1, 64 -> 128 channels on
+# 32 x 32 inputs) given by its input X[B, H, W, C] (channels last) instead of the unfolded patch matrix.
+CONV_IMAGE = {"B": 128, "H": 32, "W": 32, "C": 64, "KH": 3, "KW": 3, "pad": 1, "d_out": 128,
+              "dtype": "bf16", "C_clip": 1.0, "g_std": 1e-3}
+
+
+def generate_conv_image(B: int | None = None, H: int | None = None, W: int | None = None, C: int | None = None,
+                        KH: int | None = None, KW: int | None = None, pad: int | None = None,
+                        d_out: int | None = None, seed: int = BASE_SEED + 40, g_row_scale: np.ndarray | None = None):
+    """(spec, X, G): X[B,H,W,C] = max(0, N(0,1)), G[B, H_out*W_out, d_out] = N(0, g_std^2), both bf16 bit patterns.
+    Any geometry argument overrides the configuration's value."""
+    spec = dict(CONV_IMAGE)
+    for k, v in (("B", B), ("H", H), ("W", W), ("C", C), ("KH", KH), ("KW", KW), ("pad", pad), ("d_out", d_out)):
+        if v is not None:
+            spec[k] = int(v)
+    rng = np.random.default_rng(seed)
+    ho, wo = spec["H"] + 2 * spec["pad"] - spec["KH"] + 1, spec["W"] + 2 * spec["pad"] - spec["KW"] + 1
+    X = _draw(rng, (spec["B"], spec["H"], spec["W"], spec["C"]), "relu")
+    G = _draw(rng, (spec["B"], ho * wo, spec["d_out"]), "normal", spec["g_std"])
+    if g_row_scale is not None:
+        G *= g_row_scale.astype(np.float32)[:, None, None]
+    return spec, _store(X, "bf16"), _store(G, "bf16")

@@ -172,6 +172,33 @@ def test_bias_brute_force():
     np.testing.assert_array_equal(orc.bias_rows(G1), G1[:, 0, :])
 
 
+def test_conv_unfold_against_the_definition():
+    """dL/dW[kh,kw,c,o] = sum_{y,x} dL/dZ[y,x,o] * Xpad[y+kh, x+kw, c] (Section 5.2, the derivative of the
+    pre-activation with respect to a kernel entry), written as scalar loops, against the oracle's
+    unfold-then-multiply; and the degenerate 1 x 1 kernel, which is a plain reshape."""
+    for seed, (H, W, C, KH, KW, pad, O) in enumerate([(4, 5, 2, 3, 3, 1, 3), (5, 4, 3, 2, 3, 0, 2), (3, 3, 1, 3, 3, 2, 2)]):
+        X = _rand(300 + seed, 2, H, W, C)
+        ho, wo = H + 2 * pad - KH + 1, W + 2 * pad - KW + 1
+        G = _rand(400 + seed, 2, ho * wo, O)
+        A = orc.conv_unfold(X, KH, KW, pad)
+        assert A.shape == (2, ho * wo, KH * KW * C)
+        for b in range(2):
+            got = orc.per_example_grad(A[b], G[b]).reshape(KH, KW, C, O)
+            for kh in range(KH):
+                for kw in range(KW):
+                    for c in range(C):
+                        for o in range(O):
+                            ref = 0.0
+                            for y in range(ho):
+                                for x in range(wo):
+                                    yy, xx = y + kh - pad, x + kw - pad
+                                    if 0 <= yy < H and 0 <= xx < W:
+                                        ref += G[b, y * wo + x, o] * X[b, yy, xx, c]
+                            assert abs(got[kh, kw, c, o] - ref) <= 1e-12 * (1 + abs(ref))
+    X = _rand(9, 3, 4, 6, 5)
+    np.testing.assert_array_equal(orc.conv_unfold(X, 1, 1, 0), X.reshape(3, 24, 5))
+
+
 def test_per_example_grad_orientation():
     """g is [d_in, d_out]: entry (p, q) pairs input p with output q."""
     A = np.zeros((1, 2, 3))
