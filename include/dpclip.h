@@ -136,6 +136,37 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
                                int64_t B, int64_t d_out, int accumulate,
                                float* grad_b, void* hip_stream);
 
+/* Convolution layers given by their input image instead of the unfolded patch
+ * matrix (Section 5.2; Algorithm 3 unfolds the image first, here the patches
+ * are formed on the fly, so the kh*kw-fold larger matrix never exists in
+ * memory).  Stride 1, zero padding `pad` on every side:
+ *   X  device, [B, H, W, C] of bf16, channels last
+ *   G  device, [B, T, d_out] of bf16, T = H_out * W_out output positions in
+ *      row-major (y, x) order, H_out = H + 2 pad - KH + 1, W_out likewise
+ * The layer's weight gradient is [d_in, d_out] with d_in = KH*KW*C and row
+ * index (kh*KW + kw)*C + c:  g_i[(kh,kw,c), o] = sum_{y,x} Xpad_i[y+kh, x+kw, c] * G_i[y*W_out + x, o].
+ * dp_conv_sqnorm and dp_conv_clipped_grad compute exactly what
+ * dp_layer_sqnorm (direct path) and dp_clipped_grad compute on the unfolded
+ * A[B, T, d_in]; arguments not listed here mean the same as there.
+ * Supported: DP_BF16, C % 8 == 0, d_out % 8 == 0, T % 32 == 0 and T >= 64, and a
+ * [d_in, d_out] that tiles into 256 x 256 or 192 x 128 blocks with at most a
+ * quarter of padding; anything else is DP_ERR_UNSUPPORTED (unfold and use the
+ * general entry points).  workspace: at least dp_conv_workspace_bytes(...). */
+dp_status dp_conv_sqnorm(const void* X, const void* G,
+                         int64_t B, int64_t H, int64_t W, int64_t C,
+                         int64_t KH, int64_t KW, int64_t pad, int64_t d_out,
+                         dp_dtype dtype, int accumulate, float* sqnorm,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip,
+                               int64_t B, int64_t H, int64_t W, int64_t C,
+                               int64_t KH, int64_t KW, int64_t pad, int64_t d_out,
+                               dp_dtype dtype, int accumulate, float* grad,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+/* Scratch bytes for the two calls above (op as in dp_workspace_bytes); 0 for
+ * invalid or unsupported arguments. */
+size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_t C,
+                               int64_t KH, int64_t KW, int64_t pad, int64_t d_out, dp_dtype dtype);
+
 /* Gaussian mechanism (Section 2, Gaussian-mechanism lemma; Algorithm 1, the
  * update line): grad[j] += stddev * z[offset + j], j in [0, n), with z an
  * i.i.d. N(0,1) stream that is a pure function of (seed, element index):

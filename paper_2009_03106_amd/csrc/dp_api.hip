@@ -48,6 +48,24 @@ size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dt
     return (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float);
 }
 
+constexpr size_t kConvZeroBytes = 256;                // head of the conv workspace: a line of zeros for the padding
+
+// geometry check shared by the conv entry points; fills T and d_in
+dp_status conv_geometry(int64_t B, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW, int64_t pad, int64_t d_out,
+                        dp_dtype dtype, ConvGeom* g, int64_t* T, int64_t* d_in) {
+    if (B < 0 || H < 0 || W < 0 || C < 0 || KH < 1 || KW < 1 || pad < 0 || d_out < 0) return DP_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
+    if (H >= kMaxDim || W >= kMaxDim || C >= kMaxDim || KH >= 4096 || KW >= 4096 || pad >= 4096) return DP_ERR_UNSUPPORTED;
+    const int64_t Hout = H + 2 * pad - KH + 1, Wout = W + 2 * pad - KW + 1;
+    if (Hout < 1 || Wout < 1) return DP_ERR_INVALID_ARG;
+    *T = Hout * Wout;
+    *d_in = KH * KW * C;
+    const dp_status st = check_dims(B, *T, *d_in, d_out);
+    if (st != DP_OK) return st;
+    g->H = (int)H; g->W = (int)W; g->C = (int)C; g->KH = (int)KH; g->KW = (int)KW; g->pad = (int)pad;
+    return DP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -205,6 +223,78 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip, int64_
     }
     if (!bias_rows || !clip) return DP_ERR_INVALID_ARG;
     hipError_t e = launch_clipped_bias(bias_rows, clip, (int)B, (int)d_out, accumulate != 0, grad_b, stream);
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW, int64_t pad,
+                               int64_t d_out, dp_dtype dtype) {
+    ConvGeom g; int64_t T, d_in;
+    if (conv_geometry(B, H, W, C, KH, KW, pad, d_out, dtype, &g, &T, &d_in) != DP_OK) return 0;
+    if (B == 0 || C == 0 || d_out == 0 || H == 0 || W == 0) return 0;
+    if (dtype != DP_BF16 || !dma_conv_ok(g, (int)d_out)) return 0;
+    if (op == DP_OP_SQNORM) {
+        const TnPlan p = plan_direct_bf16_dma((int)T, (int)d_in, (int)d_out);
+        return kConvZeroBytes + (size_t)B * p.tiles_m * p.tiles_n * sizeof(float);
+    }
+    if (op == DP_OP_CLIPPED_GRAD) {
+        const TnPlan p = plan_clipped_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
+        return kConvZeroBytes + (p.splits <= 1 ? 0 : (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float));
+    }
+    return 0;
+}
+
+dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW,
+                         int64_t pad, int64_t d_out, dp_dtype dtype, int accumulate, float* sqnorm,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ConvGeom g; int64_t T, d_in;
+    dp_status st = conv_geometry(B, H, W, C, KH, KW, pad, d_out, dtype, &g, &T, &d_in);
+    if (st != DP_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (B == 0) return DP_OK;
+    if (!sqnorm) return DP_ERR_INVALID_ARG;
+    if (d_in == 0 || d_out == 0 || H == 0 || W == 0) {
+        if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (dtype != DP_BF16 || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    if (!X || !G || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
+    const size_t need = dp_conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dtype);
+    if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
+    float* zero = static_cast<float*>(workspace);
+    float* partial = zero + kConvZeroBytes / sizeof(float);
+    if (launch_fill_zero(zero, kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+    const TnPlan p = plan_direct_bf16_dma((int)T, (int)d_in, (int)d_out);
+    const hipError_t e = launch_direct_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), (int)B, (int)T,
+                                                (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, &g,
+                                                reinterpret_cast<const uint16_t*>(zero));
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, int64_t B, int64_t H, int64_t W, int64_t C,
+                               int64_t KH, int64_t KW, int64_t pad, int64_t d_out, dp_dtype dtype, int accumulate,
+                               float* grad, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ConvGeom g; int64_t T, d_in;
+    dp_status st = conv_geometry(B, H, W, C, KH, KW, pad, d_out, dtype, &g, &T, &d_in);
+    if (st != DP_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (d_in == 0 || d_out == 0) return DP_OK;
+    if (!grad || !aligned16(grad)) return DP_ERR_INVALID_ARG;
+    if (B == 0 || H == 0 || W == 0) {
+        if (!accumulate && launch_fill_zero(grad, d_in * d_out, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (dtype != DP_BF16 || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    if (!X || !G || !clip || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
+    const size_t need = dp_conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dtype);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
+    float* zero = static_cast<float*>(workspace);
+    float* ws = zero + kConvZeroBytes / sizeof(float);
+    if (launch_fill_zero(zero, kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+    const TnPlan p = plan_clipped_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
+    const hipError_t e = launch_clipped_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), clip, (int)B,
+                                                 (int)T, (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, &g,
+                                                 reinterpret_cast<const uint16_t*>(zero));
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 

@@ -39,6 +39,9 @@ struct TnPlan {
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
 TnPlan plan_clipped_f32(int B, int T, int M, int N);
 TnPlan plan_direct_bf16(int T, int M, int N);
+// stride-1 convolution given by its channels-last input image (implicit unfolding in the copy-pipeline kernel)
+struct ConvGeom { int H, W, C, KH, KW, pad; };
+bool dma_conv_ok(const ConvGeom& g, int d_out);
 bool dma_clipped_ok(int B, int T, int M, int N);
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N);
 TnPlan plan_direct_f32(int T, int M, int N);
@@ -48,12 +51,14 @@ TnPlan plan_direct_f32(int T, int M, int N);
 hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
-                                   int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
+                                   int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
+                                   const ConvGeom* cg = nullptr, const uint16_t* zero = nullptr);
 // direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
 TnPlan plan_direct_bf16_dma(int T, int M, int N);
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
-                                  bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+                                  bool accumulate, float* sqnorm, float* partial, hipStream_t st,
+                                  const ConvGeom* cg = nullptr, const uint16_t* zero = nullptr);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 // partial[B][tiles_m*tiles_n] then finalize into sqnorm

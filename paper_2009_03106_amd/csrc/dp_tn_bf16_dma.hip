@@ -69,6 +69,10 @@ struct DmaArgs {
     int stages_per_split;
     int per_xcd;
     int accumulate;
+    // CONV only: A is the image X[B, H, W, C] (channels last); column (kh * KW + kw) * C + c of the patch matrix at
+    // output position (y, x) is X[y + kh - pad, x + kw - pad, c], zero outside the image; T = Hout * Wout.
+    const uint16_t* zero;  // at least 16 bytes of zeros
+    int H, W, C, KW, pad, Wout;
 };
 
 // Rows of RB bytes; the 16-byte chunk c of row r sits at chunk position c ^ chunk_swz<RB>(r).  A transposing read
@@ -86,7 +90,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn
 // MODE 0: clipped sum over a K slice (any range of stages).  MODE 1: direct squared norm: the K slice is one
 // example (stages_per_split = T / DK, splits = B), no scaling, and the finished tile of A_i^T G_i is squared
 // and reduced to one float per (example, tile) instead of being stored (Algorithm 3 / 4 without their output).
-template <class GEO, int MODE>
+// CONV: the A operand is never unfolded in memory (implicit unfolding of Algorithm 3's patch matrix): every lane of
+// a copy instruction computes the address of its 16-byte piece of the image, or points at a line of zeros where
+// the patch reaches into the padding; the LDS tile, the MFMA loop and the epilogues are the same.
+template <class GEO, int MODE, bool CONV>
 __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs a) {
     constexpr int NST = GEO::NST, FM = GEO::FM, FN = GEO::FN, NF = FM + FN;
     constexpr int RBA = GEO::RBA, RBG = GEO::RBG, IPA = GEO::IPA, IPG = GEO::IPG, LPS = GEO::LPS;
@@ -114,13 +121,24 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     //      16-byte chunks; copy u of wave w moves chunks 64 (w IP + u) .. + 63, one per lane.  Addresses are a
     //      uniform 64-bit stage base (SGPR) plus a 32-bit per-lane byte offset that never changes.
     uint32_t offA[IPA], offG[IPG];
+    int cdy[IPA], cdx[IPA], cy0[IPA], cx0[IPA], cy[IPA], cx[IPA];    // CONV: tap offsets, position at an example's start, current position
+    const int sub_begin = s_begin - (s_begin / spe) * spe;
 #pragma unroll
     for (int u = 0; u < IPA; ++u) {
         const int idx = (wave * IPA + u) * 64 + lane;
         const int r = idx / (RBA / 16);                               // row inside the stage
         int col = m0 + (((idx % (RBA / 16)) ^ chunk_swz<RBA>(r)) << 3);
         if (col >= a.M) col = m0;                   // out-of-range columns only feed output rows that are never stored
-        offA[u] = ((uint32_t)r * (uint32_t)a.M + (uint32_t)col) * 2u;
+        if (CONV) {
+            const int tap = col / a.C, kh = tap / a.KW;
+            offA[u] = (uint32_t)(col - tap * a.C) * 2u;               // channel offset inside the pixel, bytes
+            cdy[u] = kh - a.pad; cdx[u] = tap - kh * a.KW - a.pad;
+            cy0[u] = r / a.Wout; cx0[u] = r - cy0[u] * a.Wout;
+            const int t = sub_begin * DK + r;
+            cy[u] = t / a.Wout; cx[u] = t - cy[u] * a.Wout;
+        } else {
+            offA[u] = ((uint32_t)r * (uint32_t)a.M + (uint32_t)col) * 2u;
+        }
     }
 #pragma unroll
     for (int u = 0; u < IPG; ++u) {
@@ -130,7 +148,9 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
         if (col >= a.N) col = n0;
         offG[u] = ((uint32_t)r * (uint32_t)a.N + (uint32_t)col) * 2u;
     }
-    const uint16_t* baseA = a.A + (size_t)s_begin * DK * a.M;         // uniform
+    const uint16_t* baseA = CONV ? a.A + (size_t)(s_begin / spe) * a.H * a.W * a.C       // the example's image
+                                 : a.A + (size_t)s_begin * DK * a.M;                     // uniform
+    int conv_sub = sub_begin;                                          // CONV: stage inside the example of the next copy
     const uint16_t* baseG = a.G + (size_t)s_begin * DK * a.N;
     const size_t stepA = (size_t)DK * a.M, stepG = (size_t)DK * a.N;  // per stage
 
@@ -141,15 +161,40 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     const uint32_t wave_ldsA = __builtin_amdgcn_readfirstlane(lds_base + wave * IPA * 1024);
     const uint32_t wave_ldsG = __builtin_amdgcn_readfirstlane(lds_base + OPA + wave * IPG * 1024);
     auto issue = [&](int buf) {
+        if (CONV) {
 #pragma unroll
-        for (int u = 0; u < IPA; ++u)
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(wave_ldsA + buf * STAGE_BYTES + u * 1024), "v"(offA[u]), "s"(baseA) : "memory", "m0");
+            for (int u = 0; u < IPA; ++u) {
+                const int py = cy[u] + cdy[u], px = cx[u] + cdx[u];
+                const bool inside = (unsigned)py < (unsigned)a.H && (unsigned)px < (unsigned)a.W;
+                const uint64_t addr = inside ? (uint64_t)(uintptr_t)baseA + ((uint32_t)(py * a.W + px) * (uint32_t)a.C * 2u + offA[u])
+                                             : (uint64_t)(uintptr_t)a.zero;
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(wave_ldsA + buf * STAGE_BYTES + u * 1024), "v"(addr) : "memory", "m0");
+            }
+            // the next stage: 32 positions further, or the start of the next example's image
+            if (++conv_sub == spe) {
+                conv_sub = 0;
+                baseA += (size_t)a.H * a.W * a.C;
+#pragma unroll
+                for (int u = 0; u < IPA; ++u) { cy[u] = cy0[u]; cx[u] = cx0[u]; }
+            } else {
+#pragma unroll
+                for (int u = 0; u < IPA; ++u) {
+                    cx[u] += DK;
+                    while (cx[u] >= a.Wout) { cx[u] -= a.Wout; ++cy[u]; }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < IPA; ++u)
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                             :: "s"(wave_ldsA + buf * STAGE_BYTES + u * 1024), "v"(offA[u]), "s"(baseA) : "memory", "m0");
+            baseA += stepA;
+        }
 #pragma unroll
         for (int u = 0; u < IPG; ++u)
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :: "s"(wave_ldsG + buf * STAGE_BYTES + u * 1024), "v"(offG[u]), "s"(baseG) : "memory", "m0");
-        baseA += stepA;
         baseG += stepG;
     };
 
@@ -332,9 +377,16 @@ int dma_geometry(int T, int M, int N) {
     return 0;
 }
 
-template <class GEO, int MODE> hipError_t launch_geo(const DmaArgs& a, hipStream_t st) {
-    k_tn_bf16_dma<GEO, MODE><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+template <class GEO, int MODE> hipError_t launch_geo(const DmaArgs& a, bool conv, hipStream_t st) {
+    if (conv) k_tn_bf16_dma<GEO, MODE, true><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+    else      k_tn_bf16_dma<GEO, MODE, false><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
     return hipGetLastError();
+}
+
+void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
+    a.zero = zero;
+    if (cg) { a.H = cg->H; a.W = cg->W; a.C = cg->C; a.KW = cg->KW; a.pad = cg->pad; a.Wout = cg->W + 2 * cg->pad - cg->KW + 1; }
+    else { a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0; }
 }
 
 }  // namespace
@@ -363,8 +415,10 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
 }
 
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
-                                   int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st) {
+                                   int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
+                                   const ConvGeom* cg, const uint16_t* zero) {
     DmaArgs a;
+    set_conv(a, cg, zero);
     a.A = A; a.G = G; a.clip = clip;
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.splits = p.splits;
@@ -375,9 +429,19 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 0>(a, st) : launch_geo<GeoS, 0>(a, st);
+    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 0>(a, cg != nullptr, st) : launch_geo<GeoS, 0>(a, cg != nullptr, st);
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
+}
+
+// implicit unfolding: whole 16-byte pieces must stay inside one pixel's channels, image offsets must fit 32 bits
+bool dma_conv_ok(const ConvGeom& g, int N) {
+    const int64_t Hout = (int64_t)g.H + 2 * g.pad - g.KH + 1, Wout = (int64_t)g.W + 2 * g.pad - g.KW + 1;
+    if (Hout < 1 || Wout < 1 || (g.C & 7) != 0) return false;
+    if ((int64_t)g.H * g.W * g.C * 2 >= (int64_t(1) << 31)) return false;
+    const int64_t T = Hout * Wout, M = (int64_t)g.KH * g.KW * g.C;
+    if (T >= (int64_t(1) << 31) || M >= (int64_t(1) << 24)) return false;
+    return dma_direct_ok((int)T, (int)M, N);
 }
 
 bool dma_direct_ok(int T, int M, int N) { return T >= 64 && dma_geometry(T, M, N) != 0; }
@@ -393,8 +457,10 @@ TnPlan plan_direct_bf16_dma(int T, int M, int N) {
 }
 
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
-                                  bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+                                  bool accumulate, float* sqnorm, float* partial, hipStream_t st,
+                                  const ConvGeom* cg, const uint16_t* zero) {
     DmaArgs a;
+    set_conv(a, cg, zero);
     a.A = A; a.G = G; a.clip = nullptr;
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n;
@@ -406,7 +472,7 @@ hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint
     const int64_t total = (int64_t)tiles * B;
     if (total >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     a.per_xcd = ceil_div(total, 8);
-    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 1>(a, st) : launch_geo<GeoS, 1>(a, st);
+    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 1>(a, cg != nullptr, st) : launch_geo<GeoS, 1>(a, cg != nullptr, st);
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
 }

@@ -23,7 +23,7 @@ DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
 EXPORTS = ("dp_layer_sqnorm", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad",
-           "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
+           "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
 
 _lib = None
 
@@ -55,6 +55,12 @@ def load_library() -> ctypes.CDLL:
     lib.dp_bias_sqnorm.restype = ci
     lib.dp_clipped_bias_grad.argtypes = [vp, vp, i64, i64, ci, vp, vp]
     lib.dp_clipped_bias_grad.restype = ci
+    lib.dp_conv_sqnorm.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
+    lib.dp_conv_sqnorm.restype = ci
+    lib.dp_conv_clipped_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
+    lib.dp_conv_clipped_grad.restype = ci
+    lib.dp_conv_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, i64, i64, i64, i64, ci]
+    lib.dp_conv_workspace_bytes.restype = sz
     lib.dp_add_noise.argtypes = [vp, i64, f32, u64, u64, vp]
     lib.dp_add_noise.restype = ci
     lib.dp_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci, ci]
@@ -213,6 +219,58 @@ def clipped_bias_grad(bias_rows: torch.Tensor, clip: torch.Tensor, grad_b: Optio
                                   _stream_ptr(stream))
     _check(st, "dp_clipped_bias_grad")
     return grad_b
+
+
+def _conv_args(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int):
+    if X.dim() != 4 or G.dim() != 3 or X.shape[0] != G.shape[0]:
+        raise ValueError("X must be [B, H, W, C] (channels last) and G [B, H_out*W_out, d_out]")
+    X, G = X.contiguous(), G.contiguous()
+    B, H, W, C = X.shape
+    T = (H + 2 * pad - KH + 1) * (W + 2 * pad - KW + 1)
+    if G.shape[1] != T or X.dtype != G.dtype:
+        raise ValueError("G does not match the convolution's output positions / dtype")
+    return X, G, B, H, W, C, G.shape[2]
+
+
+def conv_workspace_bytes(op: int, B: int, H: int, W: int, C: int, KH: int, KW: int, pad: int, d_out: int, dtype: int) -> int:
+    return int(load_library().dp_conv_workspace_bytes(op, B, H, W, C, KH, KW, pad, d_out, dtype))
+
+
+def conv_sqnorm(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int, sqnorm: Optional[torch.Tensor] = None, *,
+                accumulate: bool = False, workspace: Optional[torch.Tensor] = None,
+                stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """sqnorm[i] (+)= squared norm of example i's kernel gradient, from the image X, via dp_conv_sqnorm."""
+    lib = load_library()
+    X, G, B, H, W, C, d_out = _conv_args(X, G, KH, KW, pad)
+    dt = _dtype_code(X)
+    if sqnorm is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing sqnorm tensor")
+        sqnorm = torch.empty(B, dtype=torch.float32, device=X.device)
+    ws = _workspace(conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
+    st = lib.dp_conv_sqnorm(_ptr(X), _ptr(G), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)), _ptr(sqnorm),
+                            _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
+    _check(st, "dp_conv_sqnorm")
+    return sqnorm
+
+
+def conv_clipped_grad(X: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, KH: int, KW: int, pad: int,
+                      grad: Optional[torch.Tensor] = None, *, accumulate: bool = False,
+                      workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """grad (+)= sum_i clip[i] * (kernel gradient of example i), float32 [KH*KW*C, d_out], via dp_conv_clipped_grad."""
+    lib = load_library()
+    X, G, B, H, W, C, d_out = _conv_args(X, G, KH, KW, pad)
+    dt = _dtype_code(X)
+    if grad is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing grad tensor")
+        grad = torch.empty((KH * KW * C, d_out), dtype=torch.float32, device=X.device)
+    ws = _workspace(conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
+    st = lib.dp_conv_clipped_grad(_ptr(X), _ptr(G), _ptr(clip), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)),
+                                  _ptr(grad), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                  _stream_ptr(stream))
+    _check(st, "dp_conv_clipped_grad")
+    return grad
 
 
 def add_noise(grad: torch.Tensor, stddev: float, seed: int, offset: int = 0, *,

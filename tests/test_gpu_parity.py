@@ -345,6 +345,54 @@ def test_bias_empty_and_errors(dp):
     assert lib.dp_clipped_bias_grad(u.data_ptr(), None, 4, 6, 0, gb.data_ptr(), None) == 1
 
 
+# ----------------------------------------------------------------- convolution layers from their input image
+CONV_GEOMS = [
+    # B, H, W, C, KH, KW, pad, d_out
+    (3, 32, 32, 64, 3, 3, 1, 128),      # the convolution configuration's layer (192 x 128 tiles)
+    (2, 8, 8, 128, 3, 3, 1, 256),       # 256 x 256 tiles, one 64-position example = two stages
+    (2, 10, 10, 64, 3, 3, 0, 128),      # no padding
+    (2, 8, 16, 64, 5, 5, 2, 120),       # 5 x 5 kernel, ragged d_out and d_in (1600 = 8.33 x 192)
+    (5, 4, 24, 64, 3, 3, 1, 128),       # W_out = 24 does not divide a 32-position stage
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,KH,KW,pad,d_out", CONV_GEOMS)
+def test_conv_from_image(dp, B, H, W, C, KH, KW, pad, d_out):
+    spec, X, G = wl.generate_conv_image(B=B, H=H, W=W, C=C, KH=KH, KW=KW, pad=pad, d_out=d_out,
+                                        g_row_scale=np.exp(np.linspace(-1, 2, B)))
+    A = orc.conv_unfold(X, KH, KW, pad)
+    s_ref = orc.layer_sqnorm(A, G)
+    Cc = float(np.sqrt(np.median(s_ref)))
+    c_ref = orc.clip_factors(s_ref, Cc)
+    g_ref = orc.clipped_grad(A, G, c_ref)
+    Xd, Gd = to_dev(X), to_dev(G)
+    s = dp.conv_sqnorm(Xd, Gd, KH, KW, pad)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["bf16"], rel_err(s.cpu().numpy(), s_ref)
+    s2 = torch.full((B,), 1.5, device="cuda")
+    dp.conv_sqnorm(Xd, Gd, KH, KW, pad, s2, accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 1.5) <= SQ_TIGHT["bf16"]
+    c = dp.clip_factors(s, Cc)
+    g = dp.conv_clipped_grad(Xd, Gd, c, KH, KW, pad)
+    assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL["bf16"], fro_err(g.cpu().numpy(), g_ref)
+    g2 = torch.ones_like(g)
+    dp.conv_clipped_grad(Xd, Gd, c, KH, KW, pad, g2, accumulate=True)
+    assert fro_err(g2.cpu().numpy() - 1.0, g_ref) <= FRO_TOL["bf16"]
+    # the same layer through the general entry points on the unfolded patch matrix (same kernels, same order)
+    Ad = to_dev(wl.f32_to_bf16_bits(A.astype(np.float32)))
+    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
+    np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
+
+
+def test_conv_unsupported_geometries_fail_loudly(dp):
+    spec, X, G = wl.generate_conv_image(B=2, H=8, W=8, C=12, KH=3, KW=3, pad=1, d_out=64)     # C % 8 != 0
+    with pytest.raises(dp.DpclipError):
+        dp.conv_sqnorm(to_dev(X), to_dev(G), 3, 3, 1)
+    spec, X, G = wl.generate_conv_image(B=2, H=6, W=6, C=64, KH=3, KW=3, pad=1, d_out=128)    # T = 36
+    with pytest.raises(dp.DpclipError):
+        dp.conv_sqnorm(to_dev(X), to_dev(G), 3, 3, 1)
+    assert dp.conv_workspace_bytes(dp.DP_OP_SQNORM, 2, 6, 6, 64, 3, 3, 1, 128, dp.DP_BF16) == 0
+
+
 def test_pipeline_is_graph_capturable(dp):
     """The library neither allocates nor synchronises, so a whole step can be captured into a HIP graph; every
     replay (with eager work in between) must reproduce the eager results bit for bit."""
