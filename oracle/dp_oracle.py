@@ -183,6 +183,39 @@ def clipped_bias_grad(G, clip: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# LayerNorm parameters
+# --------------------------------------------------------------------------
+def layernorm_rows(G, Hbar):
+    """Per-example gradients of a LayerNorm layer's scale and shift (Section 5.5, Algorithm 5):
+    dL/dgamma = dL/dh (*) hbar (elementwise) and dL/dbeta = dL/dh, each summed over the T positions
+    that share the two vectors.  G = dL/dh and Hbar = the normalised input, both [B, T, d].
+    Returns (gamma_rows, beta_rows), each [B, d]."""
+    G = _as3d(G)
+    Hbar = _as3d(Hbar)
+    gam = np.zeros((G.shape[0], G.shape[2]), dtype=np.float64)
+    bet = np.zeros_like(gam)
+    for i in range(G.shape[0]):
+        for t in range(G.shape[1]):
+            gam[i] += G[i, t] * Hbar[i, t]
+            bet[i] += G[i, t]
+    return gam, bet
+
+
+def layernorm_sqnorm(G, Hbar) -> np.ndarray:
+    """The layer's share of the squared gradient norm: ||dL_i/dgamma||^2 + ||dL_i/dbeta||^2."""
+    gam, bet = layernorm_rows(G, Hbar)
+    return np.sum(gam * gam, axis=1) + np.sum(bet * bet, axis=1)
+
+
+def clipped_rows_sum(rows: np.ndarray, clip: np.ndarray) -> np.ndarray:
+    """sum_i nu_i rows[i] for per-example gradient rows [B, d] (Eq. weighted_loss)."""
+    out = np.zeros(rows.shape[1], dtype=np.float64)
+    for i in range(rows.shape[0]):
+        out += float(clip[i]) * rows[i]
+    return out
+
+
+# --------------------------------------------------------------------------
 # convolution layers given by their input image
 # --------------------------------------------------------------------------
 def conv_unfold(X, KH: int, KW: int, pad: int) -> np.ndarray:

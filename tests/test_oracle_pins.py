@@ -172,6 +172,29 @@ def test_bias_brute_force():
     np.testing.assert_array_equal(orc.bias_rows(G1), G1[:, 0, :])
 
 
+def test_layernorm_rows():
+    """dL/dgamma[j] = sum_t dL/dh[t, j] * hbar[t, j] is the diagonal of hbar^T (dL/dh), i.e. of the (already
+    pinned) per-example gradient of a linear layer fed with hbar; dL/dbeta is the bias gradient; both also as
+    scalar loops (Section 5.5)."""
+    B, T, d = 3, 5, 4
+    G, Hb = _rand(31, B, T, d), _rand(32, B, T, d)
+    gam, bet = orc.layernorm_rows(G, Hb)
+    for i in range(B):
+        np.testing.assert_allclose(gam[i], np.diag(orc.per_example_grad(Hb[i], G[i])), rtol=1e-13)
+        for j in range(d):
+            assert abs(gam[i, j] - sum(float(G[i, t, j]) * float(Hb[i, t, j]) for t in range(T))) <= 1e-13
+    np.testing.assert_array_equal(bet, orc.bias_rows(G))
+    np.testing.assert_allclose(orc.layernorm_sqnorm(G, Hb), (gam ** 2).sum(1) + orc.bias_sqnorm(G), rtol=1e-14)
+    # hand case: one example, T = 2, d = 2: G = [[1,2],[3,4]], hbar = [[1,-1],[2,0]] -> gamma = [1+6, -2+0], beta = [4, 6]
+    gam, bet = orc.layernorm_rows(np.array([[[1., 2.], [3., 4.]]]), np.array([[[1., -1.], [2., 0.]]]))
+    np.testing.assert_array_equal(gam, [[7., -2.]])
+    np.testing.assert_array_equal(bet, [[4., 6.]])
+    np.testing.assert_array_equal(orc.layernorm_sqnorm(np.array([[[1., 2.], [3., 4.]]]), np.array([[[1., -1.], [2., 0.]]])), [49 + 4 + 16 + 36])
+    nu = np.array([0.5, 1.0, 0.25])
+    rows = _rand(33, 3, 6)
+    np.testing.assert_allclose(orc.clipped_rows_sum(rows, nu), (nu[:, None] * rows).sum(0), rtol=1e-14)
+
+
 def test_conv_unfold_against_the_definition():
     """dL/dW[kh,kw,c,o] = sum_{y,x} dL/dZ[y,x,o] * Xpad[y+kh, x+kw, c] (Section 5.2, the derivative of the
     pre-activation with respect to a kernel entry), written as scalar loops, against the oracle's
