@@ -128,7 +128,20 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
                          dp_dtype dtype, int accumulate, float* sqnorm,
                          float* bias_rows, void* hip_stream);
 
-/* Clipped batch gradient of the bias (Eq. weighted_loss applied to b):
+/* LayerNorm scale and shift (Section 5.5, Algorithm 5): with G = dL/dh, the
+ * gradient with respect to the layer's output, and Hbar the normalised input,
+ * both [B, T, d] of `dtype`,
+ *     gamma_rows[i, :] = sum_t G_i[t, :] * Hbar_i[t, :]   (elementwise product)
+ *     beta_rows[i, :]  = sum_t G_i[t, :]
+ *     sqnorm[i] = (accumulate ? sqnorm[i] : 0) + ||gamma_rows[i]||^2 + ||beta_rows[i]||^2
+ * gamma_rows, beta_rows: device float32[B, d], written; their clipped sums
+ * are two calls of dp_clipped_bias_grad.  B must be < 65536.  No workspace. */
+dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_t T, int64_t d,
+                              dp_dtype dtype, int accumulate, float* sqnorm,
+                              float* gamma_rows, float* beta_rows, void* hip_stream);
+
+/* Clipped batch gradient of the bias (Eq. weighted_loss applied to b; the same
+ * call serves any per-example gradient rows [B, d_out], e.g. LayerNorm's):
  *     grad_b[q] = (accumulate ? grad_b[q] : 0) + sum_i clip[i] * bias_rows[i, q]
  *   bias_rows  device float32[B, d_out] from dp_bias_sqnorm, read only
  *   clip       device float32[B];  grad_b  device float32[d_out] */

@@ -205,8 +205,35 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_
         return DP_OK;
     }
     if (!G || !aligned16(G)) return DP_ERR_INVALID_ARG;
-    hipError_t e = launch_bias_rows(G, (int)B, (int)T, (int)d_out, dtype == DP_BF16, bias_rows, stream);
+    hipError_t e = launch_bias_rows(G, nullptr, (int)B, (int)T, (int)d_out, dtype == DP_BF16, bias_rows, nullptr, stream);
     if (e == hipSuccess) e = launch_rows_sqnorm(bias_rows, (int)B, (int)d_out, accumulate != 0, sqnorm, stream);
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_t T, int64_t d, dp_dtype dtype, int accumulate,
+                              float* sqnorm, float* gamma_rows, float* beta_rows, void* hip_stream) {
+    dp_status st = check_dims(B, T, 1, d);
+    if (st != DP_OK) return st;
+    if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
+    if (B >= 65536) return DP_ERR_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (B == 0) return DP_OK;
+    if (!sqnorm) return DP_ERR_INVALID_ARG;
+    if (d == 0) {
+        if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (!gamma_rows || !beta_rows) return DP_ERR_INVALID_ARG;
+    if (T == 0) {
+        if (launch_fill_zero(gamma_rows, B * d, stream) != hipSuccess) return DP_ERR_HIP;
+        if (launch_fill_zero(beta_rows, B * d, stream) != hipSuccess) return DP_ERR_HIP;
+        if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+        return DP_OK;
+    }
+    if (!G || !Hbar || !aligned16(G) || !aligned16(Hbar)) return DP_ERR_INVALID_ARG;
+    hipError_t e = launch_bias_rows(G, Hbar, (int)B, (int)T, (int)d, dtype == DP_BF16, gamma_rows, beta_rows, stream);
+    if (e == hipSuccess) e = launch_rows_sqnorm(gamma_rows, (int)B, (int)d, accumulate != 0, sqnorm, stream);
+    if (e == hipSuccess) e = launch_rows_sqnorm(beta_rows, (int)B, (int)d, true, sqnorm, stream);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 

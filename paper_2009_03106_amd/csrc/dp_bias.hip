@@ -1,7 +1,9 @@
-// Bias parameters: per-example bias gradients u_i = sum_t G_i[t, :] (dL/db = dL/dz for a
-// fully-connected layer, Section 5.1; summed over the positions that share the bias,
-// Section 5.3), their squared norms, and the clipped sum  sum_i nu_i u_i.
-// All three are bandwidth-bound; every sum runs in a fixed order (no atomics).
+// Parameters whose per-example gradients are column sums, small enough ([B, d] floats) to
+// materialise: bias vectors, u_i = sum_t G_i[t, :] (dL/db = dL/dz for a fully-connected
+// layer, Section 5.1; summed over the positions that share the bias, Section 5.3), and
+// LayerNorm scale / shift, sum_t G_i[t, :] (*) Hbar_i[t, :] and sum_t G_i[t, :] (Section 5.5,
+// Algorithm 5); their squared norms; and the clipped sum  sum_i nu_i u_i.
+// All of it is bandwidth-bound; every sum runs in a fixed order (no atomics).
 #include "dp_common.h"
 #include "dp_internal.h"
 
@@ -13,69 +15,109 @@ namespace {
 // threads (ct = 1 << ctl); a thread owns VEC consecutive columns (one 16-byte load per row) and
 // adds rows rgid, rgid + rg, ... in ascending order; the rg partial sums are then added in the
 // order 0 .. rg-1.  Needs D % VEC == 0 (with the 16-byte aligned base every load is aligned).
-template <bool BF16>
-__global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__ G, int T, int D, int ctl,
-                                                        float* __restrict__ u) {
+// PROD: a second input Hb of the same shape; u2 gets the plain column sums and u the sums of G (*) Hb.
+template <bool BF16, bool PROD>
+__global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__ G, const void* __restrict__ Hb, int T, int D, int ctl,
+                                                        float* __restrict__ u, float* __restrict__ u2) {
     constexpr int VEC = BF16 ? 8 : 4;
-    __shared__ float part[kThreads][VEC];
+    __shared__ float part[kThreads][PROD ? 2 * VEC : VEC];
     const int tid = threadIdx.x, ct = 1 << ctl, rg = kThreads >> ctl;
     const int ctid = tid & (ct - 1), rgid = tid >> ctl;
     const int ex = blockIdx.y;
     const int col0 = (blockIdx.x * ct + ctid) * VEC;
-    float acc[VEC];
+    float acc[VEC], acc2[VEC];                        // acc2 (PROD only): plain sums
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-    auto add = [&](const uint4& w) {
+    for (int v = 0; v < VEC; ++v) { acc[v] = 0.f; acc2[v] = 0.f; }
+    auto widen = [&](const uint4& w, float (&x)[VEC]) {
         if (BF16) {
             const uint32_t d[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { acc[2 * j] += bf16_lo(d[j]); acc[2 * j + 1] += bf16_hi(d[j]); }
+            for (int j = 0; j < 4; ++j) { x[2 * j] = bf16_lo(d[j]); x[2 * j + 1] = bf16_hi(d[j]); }
         } else {
-            acc[0] += __uint_as_float(w.x); acc[1] += __uint_as_float(w.y);
-            acc[2] += __uint_as_float(w.z); acc[3] += __uint_as_float(w.w);
+            x[0] = __uint_as_float(w.x); x[1] = __uint_as_float(w.y); x[2] = __uint_as_float(w.z); x[3] = __uint_as_float(w.w);
         }
+    };
+    auto add = [&](const uint4& w) {
+        float x[VEC];
+        widen(w, x);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += x[v];
+    };
+    auto add_prod = [&](const uint4& w, const uint4& h) {
+        float x[VEC], y[VEC];
+        widen(w, x);
+        widen(h, y);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) { acc[v] += x[v] * y[v]; acc2[v] += x[v]; }
     };
     if (col0 < D) {
         const size_t row_bytes = (size_t)D * (BF16 ? 2 : 4);
         const unsigned char* p = static_cast<const unsigned char*>(G) + ((size_t)ex * T) * row_bytes + (size_t)col0 * (BF16 ? 2 : 4);
         int t = rgid;
-        for (; t + 7 * rg < T; t += 8 * rg) {          // eight loads in flight, added in row order
-            uint4 w[8];
+        if (PROD) {
+            const unsigned char* q = static_cast<const unsigned char*>(Hb) + ((size_t)ex * T) * row_bytes + (size_t)col0 * (BF16 ? 2 : 4);
+            for (; t + 3 * rg < T; t += 4 * rg) {      // eight loads in flight, added in row order
+                uint4 w[4], h[4];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) w[k] = *reinterpret_cast<const uint4*>(p + (size_t)(t + k * rg) * row_bytes);
+                for (int k = 0; k < 4; ++k) {
+                    w[k] = *reinterpret_cast<const uint4*>(p + (size_t)(t + k * rg) * row_bytes);
+                    h[k] = *reinterpret_cast<const uint4*>(q + (size_t)(t + k * rg) * row_bytes);
+                }
 #pragma unroll
-            for (int k = 0; k < 8; ++k) add(w[k]);
+                for (int k = 0; k < 4; ++k) add_prod(w[k], h[k]);
+            }
+            for (; t < T; t += rg)
+                add_prod(*reinterpret_cast<const uint4*>(p + (size_t)t * row_bytes), *reinterpret_cast<const uint4*>(q + (size_t)t * row_bytes));
+        } else {
+            for (; t + 7 * rg < T; t += 8 * rg) {      // eight loads in flight, added in row order
+                uint4 w[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) w[k] = *reinterpret_cast<const uint4*>(p + (size_t)(t + k * rg) * row_bytes);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) add(w[k]);
+            }
+            for (; t < T; t += rg) add(*reinterpret_cast<const uint4*>(p + (size_t)t * row_bytes));
         }
-        for (; t < T; t += rg) add(*reinterpret_cast<const uint4*>(p + (size_t)t * row_bytes));
     }
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) part[tid][v] = acc[v];
+    for (int v = 0; v < VEC; ++v) { part[tid][v] = acc[v]; if (PROD) part[tid][VEC + v] = acc2[v]; }
     __syncthreads();
     if (rgid == 0 && col0 < D) {
         for (int r = 1; r < rg; ++r)
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[v] += part[r * ct + ctid][v];
+            for (int v = 0; v < VEC; ++v) { acc[v] += part[r * ct + ctid][v]; if (PROD) acc2[v] += part[r * ct + ctid][VEC + v]; }
         float* o = u + (size_t)ex * D + col0;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) o[v] = acc[v];
+        if (PROD) {
+            float* o2 = u2 + (size_t)ex * D + col0;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) o2[v] = acc2[v];
+        }
     }
 }
 
 // Any D: one thread per column, rows in ascending order.
-template <bool BF16>
-__global__ __launch_bounds__(kThreads) void k_bias_rows_scalar(const void* __restrict__ G, int T, int D, float* __restrict__ u) {
+template <bool BF16, bool PROD>
+__global__ __launch_bounds__(kThreads) void k_bias_rows_scalar(const void* __restrict__ G, const void* __restrict__ Hb, int T, int D,
+                                                               float* __restrict__ u, float* __restrict__ u2) {
     const int q = blockIdx.x * kThreads + threadIdx.x;
     const int ex = blockIdx.y;
     if (q >= D) return;
-    float acc = 0.f;
-    if (BF16) {
-        const uint16_t* p = static_cast<const uint16_t*>(G) + (size_t)ex * T * D + q;
-        for (int t = 0; t < T; ++t) acc += bf16_to_f32(p[(size_t)t * D]);
-    } else {
-        const float* p = static_cast<const float*>(G) + (size_t)ex * T * D + q;
-        for (int t = 0; t < T; ++t) acc += p[(size_t)t * D];
+    float acc = 0.f, acc2 = 0.f;
+    const size_t base = (size_t)ex * T * D + q;
+    for (int t = 0; t < T; ++t) {
+        const size_t k = base + (size_t)t * D;
+        const float g = BF16 ? bf16_to_f32(static_cast<const uint16_t*>(G)[k]) : static_cast<const float*>(G)[k];
+        if (PROD) {
+            const float h = BF16 ? bf16_to_f32(static_cast<const uint16_t*>(Hb)[k]) : static_cast<const float*>(Hb)[k];
+            acc += g * h; acc2 += g;
+        } else {
+            acc += g;
+        }
     }
     u[(size_t)ex * D + q] = acc;
+    if (PROD) u2[(size_t)ex * D + q] = acc2;
 }
 
 // s_i (+)= sum_q u[i, q]^2: one wave per example, lane l adds columns l, l + 64, ..., then a shuffle tree.
@@ -106,8 +148,10 @@ __global__ __launch_bounds__(kThreads) void k_clipped_bias(const float* __restri
 
 }  // namespace
 
-hipError_t launch_bias_rows(const void* G, int B, int T, int D, bool bf16, float* u, hipStream_t st) {
+// Hb == nullptr: u = column sums of G.  Otherwise u = column sums of G (*) Hb and u2 = column sums of G.
+hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, bool bf16, float* u, float* u2, hipStream_t st) {
     const int vec = bf16 ? 8 : 4;
+    const bool prod = Hb != nullptr;
     if (B > 65535) return hipErrorInvalidValue;          // grid.y
     if (D % vec == 0) {
         const int nvec = D / vec;
@@ -117,12 +161,16 @@ hipError_t launch_bias_rows(const void* G, int B, int T, int D, bool bf16, float
         // to keep enough loads in flight for HBM
         while (ctl > 4 && (int64_t)((nvec + (1 << ctl) - 1) >> ctl) * B < 1024) --ctl;
         const dim3 grid((unsigned)((nvec + (1 << ctl) - 1) >> ctl), (unsigned)B);
-        if (bf16) k_bias_rows<true><<<grid, kThreads, 0, st>>>(G, T, D, ctl, u);
-        else      k_bias_rows<false><<<grid, kThreads, 0, st>>>(G, T, D, ctl, u);
+        if (bf16) { if (prod) k_bias_rows<true, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
+                    else      k_bias_rows<true, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2); }
+        else      { if (prod) k_bias_rows<false, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
+                    else      k_bias_rows<false, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2); }
     } else {
         const dim3 grid((unsigned)((D + kThreads - 1) / kThreads), (unsigned)B);
-        if (bf16) k_bias_rows_scalar<true><<<grid, kThreads, 0, st>>>(G, T, D, u);
-        else      k_bias_rows_scalar<false><<<grid, kThreads, 0, st>>>(G, T, D, u);
+        if (bf16) { if (prod) k_bias_rows_scalar<true, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
+                    else      k_bias_rows_scalar<true, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2); }
+        else      { if (prod) k_bias_rows_scalar<false, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
+                    else      k_bias_rows_scalar<false, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2); }
     }
     return hipGetLastError();
 }

@@ -20,7 +20,7 @@ hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool acc
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st);
 // ---- bias parameters (dp_bias.hip)
-hipError_t launch_bias_rows(const void* G, int B, int T, int D, bool bf16, float* u, hipStream_t st);
+hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, bool bf16, float* u, float* u2, hipStream_t st);
 hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st);
 hipError_t launch_clipped_bias(const float* u, const float* clip, int B, int D, bool accumulate, float* grad_b, hipStream_t st);
 hipError_t launch_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64_t first, hipStream_t st);

@@ -22,7 +22,7 @@ DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
-EXPORTS = ("dp_layer_sqnorm", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad",
+EXPORTS = ("dp_layer_sqnorm", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
 
 _lib = None
@@ -53,6 +53,8 @@ def load_library() -> ctypes.CDLL:
     lib.dp_clipped_grad.restype = ci
     lib.dp_bias_sqnorm.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp]
     lib.dp_bias_sqnorm.restype = ci
+    lib.dp_layernorm_sqnorm.argtypes = [vp, vp, i64, i64, i64, ci, ci, vp, vp, vp, vp]
+    lib.dp_layernorm_sqnorm.restype = ci
     lib.dp_clipped_bias_grad.argtypes = [vp, vp, i64, i64, ci, vp, vp]
     lib.dp_clipped_bias_grad.restype = ci
     lib.dp_conv_sqnorm.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
@@ -202,6 +204,29 @@ def bias_sqnorm(G: torch.Tensor, sqnorm: Optional[torch.Tensor] = None, bias_row
                             _stream_ptr(stream))
     _check(st, "dp_bias_sqnorm")
     return sqnorm, bias_rows
+
+
+def layernorm_sqnorm(G: torch.Tensor, Hbar: torch.Tensor, sqnorm: Optional[torch.Tensor] = None, *,
+                     accumulate: bool = False, stream: Optional[torch.cuda.Stream] = None):
+    """gamma_rows[i] = sum_t G_i[t] * Hbar_i[t], beta_rows[i] = sum_t G_i[t], sqnorm[i] (+)= their squared norms,
+    via dp_layernorm_sqnorm.  Returns (sqnorm, gamma_rows, beta_rows)."""
+    lib = load_library()
+    if G.dim() == 2:
+        G, Hbar = G.unsqueeze(1), Hbar.unsqueeze(1)
+    if G.dim() != 3 or G.shape != Hbar.shape or G.dtype != Hbar.dtype:
+        raise ValueError("G and Hbar must have the same [B, T, d] shape and dtype")
+    G, Hbar = G.contiguous(), Hbar.contiguous()
+    B, T, d = G.shape
+    if sqnorm is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing sqnorm tensor")
+        sqnorm = torch.empty(B, dtype=torch.float32, device=G.device)
+    gam = torch.empty((B, d), dtype=torch.float32, device=G.device)
+    bet = torch.empty((B, d), dtype=torch.float32, device=G.device)
+    st = lib.dp_layernorm_sqnorm(_ptr(G), _ptr(Hbar), B, T, d, _dtype_code(G), int(bool(accumulate)), _ptr(sqnorm),
+                                 _ptr(gam), _ptr(bet), _stream_ptr(stream))
+    _check(st, "dp_layernorm_sqnorm")
+    return sqnorm, gam, bet
 
 
 def clipped_bias_grad(bias_rows: torch.Tensor, clip: torch.Tensor, grad_b: Optional[torch.Tensor] = None, *,

@@ -320,6 +320,47 @@ def test_bias_on_configurations(dp, name):
         assert fro_err(gb, orc.clipped_bias_grad(G, c_ref)) <= 1e-4
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,T,d", [(3, 1, 8), (4, 7, 67), (2, 130, 264), (5, 64, 768), (2, 512, 768), (3, 33, 4100)])
+def test_layernorm_rows_and_norms(dp, dtype, B, T, d):
+    Hb, G = wl.random_layer(700 + B + T + d, B, T, d, d, dtype, g_row_scale=np.exp(np.linspace(-1, 1, B)))
+    gam_ref, bet_ref = orc.layernorm_rows(G, Hb)
+    s_ref = orc.layernorm_sqnorm(G, Hb)
+    s, gam, bet = dp.layernorm_sqnorm(to_dev(G), to_dev(Hb))
+    Gw, Hw = orc.widen(G).reshape(B, T, d), orc.widen(Hb).reshape(B, T, d)
+    assert np.all(np.abs(gam.cpu().numpy() - gam_ref) <= 2e-6 * np.maximum(np.abs(Gw * Hw).sum(1), 1e-30))
+    assert np.all(np.abs(bet.cpu().numpy() - bet_ref) <= 1e-6 * np.maximum(np.abs(Gw).sum(1), 1e-30))
+    assert rel_err(s.cpu().numpy(), s_ref) <= 1e-5
+    s2 = torch.full((B,), 0.75, device="cuda")
+    dp.layernorm_sqnorm(to_dev(G), to_dev(Hb), s2, accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.75) <= 1e-5
+    c_ref = orc.clip_factors(s_ref, float(np.sqrt(np.median(s_ref))))
+    c = to_dev(c_ref.astype(np.float32))
+    for rows, rows_ref in ((gam, gam_ref), (bet, bet_ref)):
+        got = dp.clipped_bias_grad(rows, c).cpu().numpy()
+        ref = orc.clipped_rows_sum(rows_ref, c_ref)
+        assert np.all(np.abs(got - ref) <= 1e-5 * np.maximum(np.abs(rows_ref * c_ref[:, None]).sum(0), 1e-30))
+
+
+def test_per_layer_clipping_is_a_composition(dp):
+    """Clipping every layer on its own to C / sqrt(m) (the per-layer variant discussed with the related work)
+    needs no kernel of its own: squared norms without accumulation, one clip-factor call per layer."""
+    w, layers = wl.generate("rnn")
+    two = [layers[0], wl.random_layer(5, w.B, 64, 256, 128, "bf16")]
+    C = 0.5 / np.sqrt(2.0)
+    for A, G in two:
+        s_ref = orc.layer_sqnorm(A, G)
+        c_ref = orc.clip_factors(s_ref, C)
+        g_ref = orc.clipped_grad(A, G, c_ref)
+        Ad, Gd = to_dev(A), to_dev(G)
+        s = dp.layer_sqnorm(Ad, Gd)
+        c = dp.clip_factors(s, float(C))
+        g = dp.clipped_grad(Ad, Gd, c)
+        assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL["bf16"]
+        assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL["bf16"]
+        assert np.all(c.cpu().numpy().astype(np.float64) * np.sqrt(s_ref) <= C * (1 + SQ_TOL["bf16"]))
+
+
 def test_bias_empty_and_errors(dp):
     lib = dp.load_library()
     s = torch.full((4,), 7.0, device="cuda")
