@@ -68,7 +68,10 @@ class Pipeline:
         self.dp.clip_factors(self.s, self.w.C, self.c)
 
     def phase_grad(self):
-        for li, (A, G) in enumerate(self.dev):
+        # last layer first, as a backward pass would: the inputs that the norm phase read last are the likeliest
+        # to be still in the Infinity Cache
+        for li in reversed(range(len(self.dev))):
+            A, G = self.dev[li]
             self.dp.clipped_grad(A, G, self.c, self.grads[li], workspace=self.ws_cg[li])
 
     def phase_noise(self):
