@@ -9,10 +9,11 @@
 //     one column, memory has consecutive columns for one k) is done by the
 //     LDS read itself (ds_read_b64_tr_b16): 16 lanes read a 4(k) x 16(col)
 //     patch and each lane gets the 4 k values of one column.
-//   * two tile geometries (struct Geo below): 256 x 256 per workgroup of 8
+//   * three tile geometries (struct Geo below): 256 x 256 per workgroup of 8
 //     waves, one workgroup per compute unit, for layers whose clipped sum is
 //     bound by the MFMA rate; 192 x 128 per workgroup of 4 waves, two
-//     workgroups per compute unit, for narrow layers bound by HBM.
+//     workgroups per compute unit, for narrow layers bound by HBM; 128 x 128
+//     for the mid-size layers that neither tiles without much padding.
 //
 // Clip factors are applied to the fp32 accumulators, not to the bf16 inputs:
 // the tile holds  (1 / c_cur) * sum_{j <= cur} c_j g_j ; when the rows of the
@@ -55,6 +56,9 @@ using GeoL = Geo<2, 4, 4, 2, 4, 1>;
 // three 20 KB stages, two workgroups per compute unit: more workgroups to spread over the chip, and as many bytes
 // in flight per compute unit
 using GeoS = Geo<2, 2, 3, 2, 3, 2>;
+// layers of a few hundred columns that neither of the above tiles without much padding (256 x 128, 128 x 128,
+// 640 x 384, ...): 128 x 128 tile, 4 waves of 64 x 64, four 16 KB stages, two workgroups per compute unit
+using GeoT = Geo<2, 2, 2, 2, 4, 2>;
 
 struct DmaArgs {
     const uint16_t* A;
@@ -368,19 +372,34 @@ inline bool tiles_fit(int M, int N, int TM, int TN) {
     return padded * 4 <= (int64_t)M * N * 5;
 }
 
-// 0: not for this kernel; 1: GeoL; 2: GeoS
+// 0: not for this kernel; 1: GeoL; 2: GeoS; 3: GeoT (the first that fits, in the order of flop per copied byte)
 int dma_geometry(int T, int M, int N) {
     if ((T % DK) != 0 || ((M | N) & 7) != 0) return 0;
     if ((int64_t)DK * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return 0;        // 32-bit lane offsets inside a stage
     if (tiles_fit(M, N, GeoL::TM, GeoL::TN)) return 1;
     if (tiles_fit(M, N, GeoS::TM, GeoS::TN)) return 2;
+    if (tiles_fit(M, N, GeoT::TM, GeoT::TN)) return 3;
     return 0;
 }
+
+struct GeoDims { int tm, tn, occ; };
+GeoDims geo_dims(int id) {
+    if (id == 1) return {GeoL::TM, GeoL::TN, GeoL::OCC};
+    if (id == 2) return {GeoS::TM, GeoS::TN, GeoS::OCC};
+    return {GeoT::TM, GeoT::TN, GeoT::OCC};
+}
+// the plan names its geometry by the tile shape
+int geo_of_plan(const TnPlan& p) { return p.tile_m == GeoL::TM ? 1 : (p.tile_m == GeoS::TM ? 2 : 3); }
 
 template <class GEO, int MODE> hipError_t launch_geo(const DmaArgs& a, bool conv, hipStream_t st) {
     if (conv) k_tn_bf16_dma<GEO, MODE, true><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
     else      k_tn_bf16_dma<GEO, MODE, false><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
     return hipGetLastError();
+}
+template <int MODE> hipError_t launch_any(int geo, const DmaArgs& a, bool conv, hipStream_t st) {
+    if (geo == 1) return launch_geo<GeoL, MODE>(a, conv, st);
+    if (geo == 2) return launch_geo<GeoS, MODE>(a, conv, st);
+    return launch_geo<GeoT, MODE>(a, conv, st);
 }
 
 void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
@@ -394,15 +413,15 @@ void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
 bool dma_clipped_ok(int B, int T, int M, int N) { (void)B; return dma_geometry(T, M, N) != 0; }
 
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
-    const bool large = dma_geometry(T, M, N) == 1;
+    const GeoDims gd = geo_dims(dma_geometry(T, M, N));
     TnPlan p;
-    p.tile_m = large ? GeoL::TM : GeoS::TM; p.tile_n = large ? GeoL::TN : GeoS::TN;
+    p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     const int64_t stages = (int64_t)B * T / DK;
     // fill the chip once (256 compute units x workgroups per unit) with K slices of at least 8 stages each
-    int64_t splits = 256 * (large ? GeoL::OCC : GeoS::OCC) / tiles;
+    int64_t splits = 256 * gd.occ / tiles;
     if (splits < 1) splits = 1;
     const int64_t max_splits = (stages + 7) / 8;
     if (splits > max_splits) splits = max_splits;
@@ -429,7 +448,7 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 0>(a, cg != nullptr, st) : launch_geo<GeoS, 0>(a, cg != nullptr, st);
+    const hipError_t e = launch_any<0>(geo_of_plan(p), a, cg != nullptr, st);
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
 }
@@ -447,9 +466,9 @@ bool dma_conv_ok(const ConvGeom& g, int N) {
 bool dma_direct_ok(int T, int M, int N) { return T >= 64 && dma_geometry(T, M, N) != 0; }
 
 TnPlan plan_direct_bf16_dma(int T, int M, int N) {
-    const bool large = dma_geometry(T, M, N) == 1;
+    const GeoDims gd = geo_dims(dma_geometry(T, M, N));
     TnPlan p;
-    p.tile_m = large ? GeoL::TM : GeoS::TM; p.tile_n = large ? GeoL::TN : GeoS::TN;
+    p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.big = false; p.dma = true;
     p.splits = 1; p.kchunk = 0; p.epu = 1;
@@ -472,7 +491,7 @@ hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint
     const int64_t total = (int64_t)tiles * B;
     if (total >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     a.per_xcd = ceil_div(total, 8);
-    const hipError_t e = p.tile_m == GeoL::TM ? launch_geo<GeoL, 1>(a, cg != nullptr, st) : launch_geo<GeoS, 1>(a, cg != nullptr, st);
+    const hipError_t e = launch_any<1>(geo_of_plan(p), a, cg != nullptr, st);
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
 }

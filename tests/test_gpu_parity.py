@@ -147,6 +147,8 @@ RAGGED = [
     (5, 64, 456, 248), (3, 96, 264, 520), (3, 40, 456, 248), (9, 32, 512, 256), (2, 160, 504, 488),
     # 192 x 128 tiles of the copy-pipeline kernel (narrow layers), with ragged edges
     (3, 64, 376, 120), (2, 96, 192, 256), (5, 32, 576, 128),
+    # 128 x 128 tiles of the copy-pipeline kernel
+    (4, 64, 256, 128), (3, 96, 128, 128), (2, 64, 256, 376),
     # aligned Gram kernel (d % 64 == 0, T > 64) with a ragged last row tile and with one or several tiles
     (3, 200, 128, 192), (2, 128, 64, 320), (2, 300, 256, 64), (3, 72, 192, 128),
 ]
@@ -395,6 +397,7 @@ CONV_GEOMS = [
     (2, 10, 10, 64, 3, 3, 0, 128),      # no padding
     (2, 8, 16, 64, 5, 5, 2, 120),       # 5 x 5 kernel, ragged d_out and d_in (1600 = 8.33 x 192)
     (5, 4, 24, 64, 3, 3, 1, 128),       # W_out = 24 does not divide a 32-position stage
+    (2, 9, 9, 32, 2, 2, 0, 128),        # 2 x 2 kernel, d_in = 128 (128 x 128 tiles)
 ]
 
 
