@@ -382,12 +382,33 @@ int dma_geometry(int T, int M, int N) {
     return 0;
 }
 
+// Among the geometries that fit, the first one (largest tile) unless it leaves most of the chip idle: a launch
+// of fewer than 128 workgroups gives way to the geometry with the most workgroups.  `units` = what multiplies
+// the tile count: K slices available (clipped sum) or examples (direct norm).
 struct GeoDims { int tm, tn, occ; };
 GeoDims geo_dims(int id) {
     if (id == 1) return {GeoL::TM, GeoL::TN, GeoL::OCC};
     if (id == 2) return {GeoS::TM, GeoS::TN, GeoS::OCC};
     return {GeoT::TM, GeoT::TN, GeoT::OCC};
 }
+int pick_geometry(int T, int M, int N, int64_t units) {
+    const int first = dma_geometry(T, M, N);
+    if (first == 0) return 0;
+    int best = first;
+    int64_t best_blocks = -1;
+    for (int id = first; id <= 3; ++id) {
+        const GeoDims g = geo_dims(id);
+        if (!tiles_fit(M, N, g.tm, g.tn)) continue;
+        const int64_t tiles = (int64_t)ceil_div(M, g.tm) * ceil_div(N, g.tn);
+        int64_t per_tile = 256 * g.occ / tiles;
+        if (per_tile < 1) per_tile = 1;
+        const int64_t blocks = tiles * (units < per_tile ? units : per_tile);
+        if (id == first && blocks >= 128) return first;
+        if (blocks > best_blocks) { best_blocks = blocks; best = id; }
+    }
+    return best;
+}
+
 // the plan names its geometry by the tile shape
 int geo_of_plan(const TnPlan& p) { return p.tile_m == GeoL::TM ? 1 : (p.tile_m == GeoS::TM ? 2 : 3); }
 
@@ -413,13 +434,13 @@ void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
 bool dma_clipped_ok(int B, int T, int M, int N) { (void)B; return dma_geometry(T, M, N) != 0; }
 
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
-    const GeoDims gd = geo_dims(dma_geometry(T, M, N));
+    const int64_t stages = (int64_t)B * T / DK;
+    const GeoDims gd = geo_dims(pick_geometry(T, M, N, (stages + 7) / 8));
     TnPlan p;
     p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    const int64_t stages = (int64_t)B * T / DK;
     // fill the chip once (256 compute units x workgroups per unit) with K slices of at least 8 stages each
     int64_t splits = 256 * gd.occ / tiles;
     if (splits < 1) splits = 1;
