@@ -38,14 +38,15 @@ size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dty
     }
     TnPlan p = (dtype == DP_BF16) ? plan_direct_bf16((int)T, (int)d_in, (int)d_out)
                                   : plan_direct_f32((int)T, (int)d_in, (int)d_out);
-    return (size_t)B * p.tiles_m * p.tiles_n * sizeof(float);
+    return (size_t)B * p.tiles_m * p.tiles_n * sizeof(float) + (p.zero_head ? kZeroHeadFloats * sizeof(float) : 0);
 }
 
 size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
     TnPlan p = (dtype == DP_BF16) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
                                   : plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
-    if (p.splits <= 1) return 0;
-    return (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float);
+    const size_t head = p.zero_head ? kZeroHeadFloats * sizeof(float) : 0;
+    if (p.splits <= 1) return head;
+    return head + (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float);
 }
 
 constexpr size_t kConvZeroBytes = 256;                // head of the conv workspace: a line of zeros for the padding

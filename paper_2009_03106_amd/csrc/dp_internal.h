@@ -34,8 +34,10 @@ struct TnPlan {
     bool segmented;         // bf16 only: K is walked example by example (slices are whole examples)
     int epu;                // segmented: examples per K slice
     bool big;               // bf16 clipped sum only: 256 x 256 tiles, one workgroup per compute unit
+    bool zero_head = false; // the kernel needs a line of zeros: the first kZeroHeadFloats floats of the workspace are set aside for it
     bool dma;               // bf16 only: copy-pipeline kernel (direct-to-LDS copies, transposing LDS reads); tile_m x tile_n names its geometry
 };
+constexpr int kZeroHeadFloats = 64;   // 256 bytes
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
 TnPlan plan_clipped_f32(int B, int T, int M, int N);
 TnPlan plan_direct_bf16(int T, int M, int N);

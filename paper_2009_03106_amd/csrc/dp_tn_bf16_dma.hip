@@ -69,7 +69,7 @@ struct DmaArgs {
     int B, T, M, N;
     int tiles_m, tiles_n;
     int splits;
-    int stages_total;      // B*T / DK
+    int stages_total;      // B * ceil(T / DK)
     int stages_per_split;
     int per_xcd;
     int accumulate;
@@ -92,13 +92,17 @@ template <int RB> __device__ __forceinline__ int chunk_swz(int r) {
 template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14)); }
 
 // MODE 0: clipped sum over a K slice (any range of stages).  MODE 1: direct squared norm: the K slice is one
-// example (stages_per_split = T / DK, splits = B), no scaling, and the finished tile of A_i^T G_i is squared
+// example (stages_per_split = ceil(T / DK), splits = B), no scaling, and the finished tile of A_i^T G_i is squared
 // and reduced to one float per (example, tile) instead of being stored (Algorithm 3 / 4 without their output).
 // CONV: the A operand is never unfolded in memory (implicit unfolding of Algorithm 3's patch matrix): every lane of
 // a copy instruction computes the address of its 16-byte piece of the image, or points at a line of zeros where
 // the patch reaches into the padding; the LDS tile, the MFMA loop and the epilogues are the same.
-template <class GEO, int MODE, bool CONV>
+// AM = 2 (ragged): T is not a multiple of the 32-row stage.  Every example then takes ceil(T / 32) stages, and
+// the rows past its end in the last one are copied from the line of zeros (rows of zeros add nothing to the
+// product); the per-lane addresses are 64-bit as in the convolution mode.
+template <class GEO, int MODE, int AM>
 __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs a) {
+    constexpr bool CONV = AM == 1, RAG = AM == 2;
     constexpr int NST = GEO::NST, FM = GEO::FM, FN = GEO::FN, NF = FM + FN;
     constexpr int RBA = GEO::RBA, RBG = GEO::RBG, IPA = GEO::IPA, IPG = GEO::IPG, LPS = GEO::LPS;
     constexpr int OPA = GEO::OPA, STAGE_BYTES = GEO::STAGE_BYTES;
@@ -119,12 +123,13 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     const int s_end = min(a.stages_total, s_begin + a.stages_per_split);
     const int n_stages = s_end - s_begin;
     if (n_stages <= 0) return;
-    const int spe = a.T / DK;                       // stages per example
+    const int spe = (a.T + DK - 1) / DK;            // stages per example (T % 32 != 0 only in the ragged mode)
 
     // ---- global -> LDS.  The A part of a stage (DK rows of RBA bytes) and its G part are each a linear run of
     //      16-byte chunks; copy u of wave w moves chunks 64 (w IP + u) .. + 63, one per lane.  Addresses are a
     //      uniform 64-bit stage base (SGPR) plus a 32-bit per-lane byte offset that never changes.
     uint32_t offA[IPA], offG[IPG];
+    int rowA[IPA], rowG[IPG];                        // RAG: row inside the stage of each copy's lane
     int cdy[IPA], cdx[IPA], cy0[IPA], cx0[IPA], cy[IPA], cx[IPA];    // CONV: tap offsets, position at an example's start, current position
     const int sub_begin = s_begin - (s_begin / spe) * spe;
 #pragma unroll
@@ -133,6 +138,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
         const int r = idx / (RBA / 16);                               // row inside the stage
         int col = m0 + (((idx % (RBA / 16)) ^ chunk_swz<RBA>(r)) << 3);
         if (col >= a.M) col = m0;                   // out-of-range columns only feed output rows that are never stored
+        rowA[u] = r;
         if (CONV) {
             const int tap = col / a.C, kh = tap / a.KW;
             offA[u] = (uint32_t)(col - tap * a.C) * 2u;               // channel offset inside the pixel, bytes
@@ -150,13 +156,16 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
         const int r = idx / (RBG / 16);
         int col = n0 + (((idx % (RBG / 16)) ^ chunk_swz<RBG>(r)) << 3);
         if (col >= a.N) col = n0;
+        rowG[u] = r;
         offG[u] = ((uint32_t)r * (uint32_t)a.N + (uint32_t)col) * 2u;
     }
-    const uint16_t* baseA = CONV ? a.A + (size_t)(s_begin / spe) * a.H * a.W * a.C       // the example's image
-                                 : a.A + (size_t)s_begin * DK * a.M;                     // uniform
-    int conv_sub = sub_begin;                                          // CONV: stage inside the example of the next copy
-    const uint16_t* baseG = a.G + (size_t)s_begin * DK * a.N;
     const size_t stepA = (size_t)DK * a.M, stepG = (size_t)DK * a.N;  // per stage
+    const uint16_t* baseA = CONV ? a.A + (size_t)(s_begin / spe) * a.H * a.W * a.C       // the example's image
+                          : RAG  ? a.A + (size_t)(s_begin / spe) * a.T * a.M + (size_t)sub_begin * stepA
+                                 : a.A + (size_t)s_begin * stepA;                        // uniform
+    const uint16_t* baseG = RAG ? a.G + (size_t)(s_begin / spe) * a.T * a.N + (size_t)sub_begin * stepG
+                                : a.G + (size_t)s_begin * stepG;
+    int conv_sub = sub_begin;                                          // CONV, RAG: stage inside the example of the next copy
 
     // The copies are issued as inline assembly: the compiler then does not know that they write LDS and
     // does not make every LDS read wait for all copies in flight; the waits for them are the explicit
@@ -188,6 +197,30 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
                     while (cx[u] >= a.Wout) { cx[u] -= a.Wout; ++cy[u]; }
                 }
             }
+        } else if (RAG) {
+            const int rows_valid = a.T - conv_sub * DK;               // rows of this stage inside the example (may exceed 32)
+#pragma unroll
+            for (int u = 0; u < IPA; ++u) {
+                const uint64_t addr = rowA[u] < rows_valid ? (uint64_t)(uintptr_t)baseA + offA[u] : (uint64_t)(uintptr_t)a.zero;
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(wave_ldsA + buf * STAGE_BYTES + u * 1024), "v"(addr) : "memory", "m0");
+            }
+#pragma unroll
+            for (int u = 0; u < IPG; ++u) {
+                const uint64_t addr = rowG[u] < rows_valid ? (uint64_t)(uintptr_t)baseG + offG[u] : (uint64_t)(uintptr_t)a.zero;
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(wave_ldsG + buf * STAGE_BYTES + u * 1024), "v"(addr) : "memory", "m0");
+            }
+            // the next stage: 32 rows further, or the first rows of the next example (which start T rows after this one's)
+            if (++conv_sub == spe) {
+                baseA += (size_t)(a.T - (spe - 1) * DK) * a.M;
+                baseG += (size_t)(a.T - (spe - 1) * DK) * a.N;
+                conv_sub = 0;
+            } else {
+                baseA += stepA;
+                baseG += stepG;
+            }
+            return;
         } else {
 #pragma unroll
             for (int u = 0; u < IPA; ++u)
@@ -374,7 +407,8 @@ inline bool tiles_fit(int M, int N, int TM, int TN) {
 
 // 0: not for this kernel; 1: GeoL; 2: GeoS; 3: GeoT (the first that fits, in the order of flop per copied byte)
 int dma_geometry(int T, int M, int N) {
-    if ((T % DK) != 0 || ((M | N) & 7) != 0) return 0;
+    if (((M | N) & 7) != 0) return 0;
+    if ((T % DK) != 0 && (int64_t)ceil_div(T, DK) * DK * 4 > (int64_t)T * 5) return 0;   // ragged T: at most a quarter of zero rows
     if ((int64_t)DK * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return 0;        // 32-bit lane offsets inside a stage
     if (tiles_fit(M, N, GeoL::TM, GeoL::TN)) return 1;
     if (tiles_fit(M, N, GeoS::TM, GeoS::TN)) return 2;
@@ -412,15 +446,17 @@ int pick_geometry(int T, int M, int N, int64_t units) {
 // the plan names its geometry by the tile shape
 int geo_of_plan(const TnPlan& p) { return p.tile_m == GeoL::TM ? 1 : (p.tile_m == GeoS::TM ? 2 : 3); }
 
-template <class GEO, int MODE> hipError_t launch_geo(const DmaArgs& a, bool conv, hipStream_t st) {
-    if (conv) k_tn_bf16_dma<GEO, MODE, true><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
-    else      k_tn_bf16_dma<GEO, MODE, false><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+// am: 0 = rows of A as they lie in memory, 1 = implicit unfolding of an image, 2 = ragged T
+template <class GEO, int MODE> hipError_t launch_geo(const DmaArgs& a, int am, hipStream_t st) {
+    if (am == 1)      k_tn_bf16_dma<GEO, MODE, 1><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+    else if (am == 2) k_tn_bf16_dma<GEO, MODE, 2><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+    else              k_tn_bf16_dma<GEO, MODE, 0><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
     return hipGetLastError();
 }
-template <int MODE> hipError_t launch_any(int geo, const DmaArgs& a, bool conv, hipStream_t st) {
-    if (geo == 1) return launch_geo<GeoL, MODE>(a, conv, st);
-    if (geo == 2) return launch_geo<GeoS, MODE>(a, conv, st);
-    return launch_geo<GeoT, MODE>(a, conv, st);
+template <int MODE> hipError_t launch_any(int geo, const DmaArgs& a, int am, hipStream_t st) {
+    if (geo == 1) return launch_geo<GeoL, MODE>(a, am, st);
+    if (geo == 2) return launch_geo<GeoS, MODE>(a, am, st);
+    return launch_geo<GeoT, MODE>(a, am, st);
 }
 
 void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
@@ -434,12 +470,14 @@ void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
 bool dma_clipped_ok(int B, int T, int M, int N) { (void)B; return dma_geometry(T, M, N) != 0; }
 
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
-    const int64_t stages = (int64_t)B * T / DK;
+    const int64_t spe = ceil_div(T, DK);
+    const int64_t stages = (int64_t)B * spe;
     const GeoDims gd = geo_dims(pick_geometry(T, M, N, (stages + 7) / 8));
     TnPlan p;
     p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
+    p.zero_head = (T % DK) != 0;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     // fill the chip once (256 compute units x workgroups per unit) with K slices of at least 8 stages each
     int64_t splits = 256 * gd.occ / tiles;
@@ -447,7 +485,6 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
     const int64_t max_splits = (stages + 7) / 8;
     if (splits > max_splits) splits = max_splits;
     int64_t sps = (stages + splits - 1) / splits;
-    const int64_t spe = T / DK;
     if (sps > 63 * spe) sps = 63 * spe;               // a slice may touch at most 64 examples (one clip factor per lane)
     p.kchunk = (int)(sps * DK);
     p.splits = (int)((stages + sps - 1) / sps);
@@ -457,19 +494,28 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
                                    const ConvGeom* cg, const uint16_t* zero) {
+    int am = cg ? 1 : 0;
+    if (!cg && p.zero_head) {
+        // ragged T: the head of the workspace is the line of zeros
+        const hipError_t ez = launch_fill_zero(ws, kZeroHeadFloats, st);
+        if (ez != hipSuccess) return ez;
+        zero = reinterpret_cast<const uint16_t*>(ws);
+        ws += kZeroHeadFloats;
+        am = 2;
+    }
     DmaArgs a;
     set_conv(a, cg, zero);
     a.A = A; a.G = G; a.clip = clip;
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.splits = p.splits;
-    a.stages_total = (int)((int64_t)B * T / DK);
+    a.stages_total = (int)((int64_t)B * ceil_div(T, DK));
     a.stages_per_split = p.kchunk / DK;
     const int64_t n = (int64_t)M * N;
     const int tiles = p.tiles_m * p.tiles_n;
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    const hipError_t e = launch_any<0>(geo_of_plan(p), a, cg != nullptr, st);
+    const hipError_t e = launch_any<0>(geo_of_plan(p), a, am, st);
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
 }
@@ -480,7 +526,7 @@ bool dma_conv_ok(const ConvGeom& g, int N) {
     if (Hout < 1 || Wout < 1 || (g.C & 7) != 0) return false;
     if ((int64_t)g.H * g.W * g.C * 2 >= (int64_t(1) << 31)) return false;
     const int64_t T = Hout * Wout, M = (int64_t)g.KH * g.KW * g.C;
-    if (T >= (int64_t(1) << 31) || M >= (int64_t(1) << 24)) return false;
+    if (T >= (int64_t(1) << 31) || M >= (int64_t(1) << 24) || (T % DK) != 0) return false;
     return dma_direct_ok((int)T, (int)M, N);
 }
 
@@ -492,6 +538,7 @@ TnPlan plan_direct_bf16_dma(int T, int M, int N) {
     p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.big = false; p.dma = true;
+    p.zero_head = (T % DK) != 0;
     p.splits = 1; p.kchunk = 0; p.epu = 1;
     return p;
 }
@@ -499,20 +546,28 @@ TnPlan plan_direct_bf16_dma(int T, int M, int N) {
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
                                   const ConvGeom* cg, const uint16_t* zero) {
+    int am = cg ? 1 : 0;
+    if (!cg && p.zero_head) {
+        const hipError_t ez = launch_fill_zero(partial, kZeroHeadFloats, st);
+        if (ez != hipSuccess) return ez;
+        zero = reinterpret_cast<const uint16_t*>(partial);
+        partial += kZeroHeadFloats;
+        am = 2;
+    }
     DmaArgs a;
     set_conv(a, cg, zero);
     a.A = A; a.G = G; a.clip = nullptr;
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n;
     a.splits = B;
-    a.stages_total = (int)((int64_t)B * T / DK);
-    a.stages_per_split = T / DK;
+    a.stages_total = (int)((int64_t)B * ceil_div(T, DK));
+    a.stages_per_split = ceil_div(T, DK);
     a.out = partial; a.slice = 0; a.accumulate = 0;
     const int tiles = a.tiles_m * a.tiles_n;
     const int64_t total = (int64_t)tiles * B;
     if (total >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     a.per_xcd = ceil_div(total, 8);
-    const hipError_t e = launch_any<1>(geo_of_plan(p), a, cg != nullptr, st);
+    const hipError_t e = launch_any<1>(geo_of_plan(p), a, am, st);
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
 }

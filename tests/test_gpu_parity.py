@@ -147,6 +147,8 @@ RAGGED = [
     (5, 64, 456, 248), (3, 96, 264, 520), (3, 40, 456, 248), (9, 32, 512, 256), (2, 160, 504, 488),
     # 192 x 128 tiles of the copy-pipeline kernel (narrow layers), with ragged edges
     (3, 64, 376, 120), (2, 96, 192, 256), (5, 32, 576, 128),
+    # T not a multiple of the 32-row stage in the copy-pipeline kernels (zero rows appended to every example)
+    (3, 197, 768, 384), (2, 200, 256, 256), (4, 1000, 128, 128), (2, 130, 512, 256), (5, 161, 192, 128),
     # 128 x 128 tiles of the copy-pipeline kernel
     (4, 64, 256, 128), (3, 96, 128, 128), (2, 64, 256, 376),
     # aligned Gram kernel (d % 64 == 0, T > 64) with a ragged last row tile and with one or several tiles
