@@ -21,7 +21,8 @@
 // accumulator register per example, skipped when the two factors are equal),
 // and by the last example's factor at the end.  This is exact up to one fp32
 // rounding per example.  It needs every 32-row stage to lie inside one
-// example, hence T % 32 == 0.  K slices are arbitrary ranges of stages.
+// example: T % 32 == 0, or the ragged mode below, which pads every example
+// with rows of zeros.  K slices are arbitrary ranges of stages.
 #include "dp_common.h"
 #include "dp_internal.h"
 
@@ -73,10 +74,10 @@ struct DmaArgs {
     int stages_per_split;
     int per_xcd;
     int accumulate;
-    // CONV only: A is the image X[B, H, W, C] (channels last); column (kh * KW + kw) * C + c of the patch matrix at
+    // AM = 1: A is the image X[B, H, W, C] (channels last); column (kh * KW + kw) * C + c of the patch matrix at
     // output position (y, x) is X[y + kh - pad, x + kw - pad, c], zero outside the image; T = Hout * Wout.
-    const uint16_t* zero;  // at least 16 bytes of zeros
     int H, W, C, KW, pad, Wout;
+    const uint16_t* zero;  // AM = 1, 2: at least 16 bytes of zeros
 };
 
 // Rows of RB bytes; the 16-byte chunk c of row r sits at chunk position c ^ chunk_swz<RB>(r).  A transposing read
@@ -94,7 +95,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn
 // MODE 0: clipped sum over a K slice (any range of stages).  MODE 1: direct squared norm: the K slice is one
 // example (stages_per_split = ceil(T / DK), splits = B), no scaling, and the finished tile of A_i^T G_i is squared
 // and reduced to one float per (example, tile) instead of being stored (Algorithm 3 / 4 without their output).
-// CONV: the A operand is never unfolded in memory (implicit unfolding of Algorithm 3's patch matrix): every lane of
+// AM = 1 (CONV): the A operand is never unfolded in memory (implicit unfolding of Algorithm 3's patch matrix): every lane of
 // a copy instruction computes the address of its 16-byte piece of the image, or points at a line of zeros where
 // the patch reaches into the padding; the LDS tile, the MFMA loop and the epilogues are the same.
 // AM = 2 (ragged): T is not a multiple of the 32-row stage.  Every example then takes ceil(T / 32) stages, and
