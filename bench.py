@@ -286,6 +286,29 @@ def main():
                             "sqnorm_tflops": wk2["norm_flops"] / (ph2[0] * 1e-3) / 1e12,
                             "clipped_grad_tflops": wk2["gemm_flops"] / (ph2[2] * 1e-3) / 1e12,
                             "clipped_grad_gbs": wk2["gemm_bytes"] / (ph2[2] * 1e-3) / 1e9}
+            # the same step captured once into a HIP graph and replayed (the library neither allocates nor
+            # synchronises, so a step is capturable): takes the host's launch rate out of the small configurations
+            try:
+                side = torch.cuda.Stream()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.stream(side):
+                    p2.step()
+                    side.synchronize()
+                    with torch.cuda.graph(graph, stream=side):
+                        p2.step()
+                torch.cuda.synchronize()
+                for _ in range(5):
+                    graph.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(50):
+                    graph.replay()
+                torch.cuda.synchronize()
+                others[name]["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / 50
+                del graph
+            except Exception as exc:          # reported, never fatal for the benchmark line
+                others[name]["ms_per_step_graph"] = None
+                others[name]["graph_error"] = str(exc)[:200]
             # the same with cold caches (the timings above are back-to-back steps over inputs that fit the caches)
             pc = time_steps_cold(p2, torch, 10, flush)
             others[name]["cold"] = {"sqnorm_ms": pc[0], "clipped_grad_ms": pc[2],
