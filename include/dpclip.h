@@ -161,9 +161,10 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
  * dp_conv_sqnorm and dp_conv_clipped_grad compute exactly what
  * dp_layer_sqnorm (direct path) and dp_clipped_grad compute on the unfolded
  * A[B, T, d_in]; arguments not listed here mean the same as there.
- * Supported: DP_BF16, C % 8 == 0, d_out % 8 == 0, T % 32 == 0 and T >= 64, and a
- * [d_in, d_out] that tiles into 256 x 256 or 192 x 128 blocks with at most a
- * quarter of padding; anything else is DP_ERR_UNSUPPORTED (unfold and use the
+ * Supported: DP_BF16, C % 8 == 0, d_out % 8 == 0, T >= 64 with at most a quarter
+ * of padding up to the next multiple of 32 (e.g. 784, 196, 1024), and a
+ * [d_in, d_out] that tiles into 256 x 256, 192 x 128 or 128 x 128 blocks with at
+ * most a quarter of padding; anything else is DP_ERR_UNSUPPORTED (unfold and use the
  * general entry points).  workspace: at least dp_conv_workspace_bytes(...). */
 dp_status dp_conv_sqnorm(const void* X, const void* G,
                          int64_t B, int64_t H, int64_t W, int64_t C,

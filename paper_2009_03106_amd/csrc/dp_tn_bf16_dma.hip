@@ -164,7 +164,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     const uint16_t* baseA = CONV ? a.A + (size_t)(s_begin / spe) * a.H * a.W * a.C       // the example's image
                           : RAG  ? a.A + (size_t)(s_begin / spe) * a.T * a.M + (size_t)sub_begin * stepA
                                  : a.A + (size_t)s_begin * stepA;                        // uniform
-    const uint16_t* baseG = RAG ? a.G + (size_t)(s_begin / spe) * a.T * a.N + (size_t)sub_begin * stepG
+    const uint16_t* baseG = (RAG || CONV) ? a.G + (size_t)(s_begin / spe) * a.T * a.N + (size_t)sub_begin * stepG
                                 : a.G + (size_t)s_begin * stepG;
     int conv_sub = sub_begin;                                          // CONV, RAG: stage inside the example of the next copy
 
@@ -176,28 +176,40 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     const uint32_t wave_ldsG = __builtin_amdgcn_readfirstlane(lds_base + OPA + wave * IPG * 1024);
     auto issue = [&](int buf) {
         if (CONV) {
+            const int hout = a.T / a.Wout;
 #pragma unroll
             for (int u = 0; u < IPA; ++u) {
                 const int py = cy[u] + cdy[u], px = cx[u] + cdx[u];
-                const bool inside = (unsigned)py < (unsigned)a.H && (unsigned)px < (unsigned)a.W;
+                // inside the image, and an output position of this example (the last stage may run past T)
+                const bool inside = (unsigned)py < (unsigned)a.H && (unsigned)px < (unsigned)a.W && cy[u] < hout;
                 const uint64_t addr = inside ? (uint64_t)(uintptr_t)baseA + ((uint32_t)(py * a.W + px) * (uint32_t)a.C * 2u + offA[u])
                                              : (uint64_t)(uintptr_t)a.zero;
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                              :: "s"(wave_ldsA + buf * STAGE_BYTES + u * 1024), "v"(addr) : "memory", "m0");
             }
+            const int rows_valid = a.T - conv_sub * DK;
+#pragma unroll
+            for (int u = 0; u < IPG; ++u) {
+                const uint64_t addr = rowG[u] < rows_valid ? (uint64_t)(uintptr_t)baseG + offG[u] : (uint64_t)(uintptr_t)a.zero;
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(wave_ldsG + buf * STAGE_BYTES + u * 1024), "v"(addr) : "memory", "m0");
+            }
             // the next stage: 32 positions further, or the start of the next example's image
             if (++conv_sub == spe) {
                 conv_sub = 0;
                 baseA += (size_t)a.H * a.W * a.C;
+                baseG += (size_t)(a.T - (spe - 1) * DK) * a.N;
 #pragma unroll
                 for (int u = 0; u < IPA; ++u) { cy[u] = cy0[u]; cx[u] = cx0[u]; }
             } else {
+                baseG += stepG;
 #pragma unroll
                 for (int u = 0; u < IPA; ++u) {
                     cx[u] += DK;
                     while (cx[u] >= a.Wout) { cx[u] -= a.Wout; ++cy[u]; }
                 }
             }
+            return;
         } else if (RAG) {
             const int rows_valid = a.T - conv_sub * DK;               // rows of this stage inside the example (may exceed 32)
 #pragma unroll
@@ -527,7 +539,7 @@ bool dma_conv_ok(const ConvGeom& g, int N) {
     if (Hout < 1 || Wout < 1 || (g.C & 7) != 0) return false;
     if ((int64_t)g.H * g.W * g.C * 2 >= (int64_t(1) << 31)) return false;
     const int64_t T = Hout * Wout, M = (int64_t)g.KH * g.KW * g.C;
-    if (T >= (int64_t(1) << 31) || M >= (int64_t(1) << 24) || (T % DK) != 0) return false;
+    if (T >= (int64_t(1) << 31) || M >= (int64_t(1) << 24)) return false;
     return dma_direct_ok((int)T, (int)M, N);
 }
 

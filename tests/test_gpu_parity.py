@@ -400,6 +400,8 @@ CONV_GEOMS = [
     (2, 8, 16, 64, 5, 5, 2, 120),       # 5 x 5 kernel, ragged d_out and d_in (1600 = 8.33 x 192)
     (5, 4, 24, 64, 3, 3, 1, 128),       # W_out = 24 does not divide a 32-position stage
     (2, 9, 9, 32, 2, 2, 0, 128),        # 2 x 2 kernel, d_in = 128 (128 x 128 tiles)
+    (3, 28, 28, 64, 3, 3, 1, 128),      # 784 output positions: not a multiple of the 32-position stage
+    (2, 14, 14, 64, 3, 3, 1, 128),      # 196 positions
 ]
 
 
