@@ -36,7 +36,7 @@ size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dty
         GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
         return (size_t)B * g.npairs * sizeof(float);
     }
-    TnPlan p = (dtype == DP_BF16) ? plan_direct_bf16((int)T, (int)d_in, (int)d_out)
+    TnPlan p = (dtype == DP_BF16) ? plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out)
                                   : plan_direct_f32((int)T, (int)d_in, (int)d_out);
     return (size_t)B * p.tiles_m * p.tiles_n * sizeof(float) + (p.zero_head ? kZeroHeadFloats * sizeof(float) : 0);
 }
@@ -135,7 +135,7 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
         e = launch_gram_bf16(g, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
                              (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
     } else if (dtype == DP_BF16) {
-        TnPlan t = plan_direct_bf16((int)T, (int)d_in, (int)d_out);
+        TnPlan t = plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_direct_bf16(t, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
                                (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
     } else {
@@ -261,7 +261,7 @@ size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_
     if (B == 0 || C == 0 || d_out == 0 || H == 0 || W == 0) return 0;
     if (dtype != DP_BF16 || !dma_conv_ok(g, (int)d_out)) return 0;
     if (op == DP_OP_SQNORM) {
-        const TnPlan p = plan_direct_bf16_dma((int)T, (int)d_in, (int)d_out);
+        const TnPlan p = plan_direct_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
         return kConvZeroBytes + (size_t)B * p.tiles_m * p.tiles_n * sizeof(float);
     }
     if (op == DP_OP_CLIPPED_GRAD) {
@@ -292,7 +292,7 @@ dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int
     float* zero = static_cast<float*>(workspace);
     float* partial = zero + kConvZeroBytes / sizeof(float);
     if (launch_fill_zero(zero, kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
-    const TnPlan p = plan_direct_bf16_dma((int)T, (int)d_in, (int)d_out);
+    const TnPlan p = plan_direct_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
     const hipError_t e = launch_direct_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), (int)B, (int)T,
                                                 (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, &g,
                                                 reinterpret_cast<const uint16_t*>(zero));

@@ -40,7 +40,7 @@ struct TnPlan {
 constexpr int kZeroHeadFloats = 64;   // 256 bytes
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
 TnPlan plan_clipped_f32(int B, int T, int M, int N);
-TnPlan plan_direct_bf16(int T, int M, int N);
+TnPlan plan_direct_bf16(int B, int T, int M, int N);
 // stride-1 convolution given by its channels-last input image (implicit unfolding in the copy-pipeline kernel)
 struct ConvGeom { int H, W, C, KH, KW, pad; };
 bool dma_conv_ok(const ConvGeom& g, int d_out);
@@ -57,7 +57,7 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
                                    const ConvGeom* cg = nullptr, const uint16_t* zero = nullptr);
 // direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
-TnPlan plan_direct_bf16_dma(int T, int M, int N);
+TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
                                   const ConvGeom* cg = nullptr, const uint16_t* zero = nullptr);

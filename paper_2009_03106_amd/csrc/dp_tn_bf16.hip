@@ -656,9 +656,9 @@ TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
     return p;
 }
 
-TnPlan plan_direct_bf16(int T, int M, int N) {
+TnPlan plan_direct_bf16(int B, int T, int M, int N) {
     TnPlan p;
-    if (dma_direct_ok(T, M, N)) return plan_direct_bf16_dma(T, M, N);
+    if (dma_direct_ok(T, M, N)) return plan_direct_bf16_dma(B, T, M, N);
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     p.segmented = (T >= kSegMinT);

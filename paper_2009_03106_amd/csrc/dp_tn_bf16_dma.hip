@@ -545,8 +545,8 @@ bool dma_conv_ok(const ConvGeom& g, int N) {
 
 bool dma_direct_ok(int T, int M, int N) { return T >= 64 && dma_geometry(T, M, N) != 0; }
 
-TnPlan plan_direct_bf16_dma(int T, int M, int N) {
-    const GeoDims gd = geo_dims(dma_geometry(T, M, N));
+TnPlan plan_direct_bf16_dma(int B, int T, int M, int N) {
+    const GeoDims gd = geo_dims(pick_geometry(T, M, N, B));      // one workgroup per (example, tile)
     TnPlan p;
     p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
