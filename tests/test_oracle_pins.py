@@ -437,3 +437,29 @@ def test_straddle_variant_clips_about_half():
         c = orc.clip_factors(s, w.C)
         frac = (c < 1).mean()
         assert 0.2 < frac < 0.8, (name, frac)
+
+
+# ---------------------------------------------------------------- randomised identities (hypothesis)
+from hypothesis import given, settings, strategies as st
+
+
+@settings(max_examples=40, deadline=None)
+@given(B=st.integers(1, 4), T=st.integers(1, 9), di=st.integers(1, 7), do=st.integers(1, 7), seed=st.integers(0, 10 ** 6))
+def test_random_shapes_identities(B, T, di, do, seed):
+    """On arbitrary small shapes: Gram form == materialised form; the squared norm is invariant under transposing
+    the roles of A and G (||A^T G|| = ||G^T A||); clipping never increases a norm and leaves short gradients alone;
+    the clipped sum is linear in the clip factors."""
+    rng = np.random.default_rng(seed)
+    A, G = rng.standard_normal((B, T, di)), rng.standard_normal((B, T, do))
+    s = orc.layer_sqnorm(A, G)
+    np.testing.assert_allclose(orc.layer_sqnorm_gram(A, G), s, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(orc.layer_sqnorm(G, A), s, rtol=1e-12, atol=1e-14)
+    C = float(np.sqrt(np.median(s))) + 1e-9
+    nu = orc.clip_factors(s, C)
+    assert np.all(nu <= 1.0) and np.all(nu > 0.0)
+    assert np.all(nu * np.sqrt(s) <= C * (1 + 1e-12))
+    assert np.all(nu[np.sqrt(s) <= C] == 1.0)
+    g1 = orc.clipped_grad(A, G, nu)
+    g2 = orc.clipped_grad(A, G, 0.5 * nu)
+    np.testing.assert_allclose(g2, 0.5 * g1, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(g1, orc.clipped_grad_by_clip_function(A, G, C), rtol=1e-10, atol=1e-12)
