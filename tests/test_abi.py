@@ -67,6 +67,36 @@ def test_workspace_sizes(lib):
     assert f(dpclip.DP_OP_CLIPPED_GRAD, 1, 1, 8, 8, dpclip.DP_F32) == 0          # one K slice: no scratch
 
 
+def test_workspace_sizes_over_many_shapes(lib):
+    """Host logic only: the size queries answer for every shape class without crashing, are multiples of 4, hold at
+    least one float per example for the norm scratch, and reject what the entry points reject."""
+    f = dpclip.workspace_bytes
+    shapes = [(1, 1, 1, 1), (3, 17, 72, 40), (64, 197, 768, 3072), (64, 200, 256, 256), (128, 64, 256, 256),
+              (128, 1024, 576, 128), (2, 4096, 64, 128), (1, 100000, 64, 64), (1 << 16, 8, 8, 8), (7, 33, 129, 65),
+              (4, 64, 4096, 4096), (2, 96, 192, 256), (5, 161, 192, 128)]
+    for B, T, di, do in shapes:
+        for dt in (dpclip.DP_F32, dpclip.DP_BF16):
+            for path in ("auto", "gram", "direct"):
+                n = f(dpclip.DP_OP_SQNORM, B, T, di, do, dt, path)
+                assert n >= 0 and n % 4 == 0 and n < (1 << 40), (B, T, di, do, dt, path, n)
+                if T > 1 and not (path == "gram" and dt == dpclip.DP_F32):
+                    assert n >= 4 * B, (B, T, di, do, dt, path, n)
+            n = f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dt)
+            assert n >= 0 and n % 4 == 0 and n < (1 << 40)
+    # a ragged sequence length on the copy-pipeline kernels sets aside a line of zeros even without K slices
+    assert f(dpclip.DP_OP_CLIPPED_GRAD, 1, 197, 768, 768, dpclip.DP_BF16) >= 256
+    # too large: B * T must stay below 2^31, layer widths below 2^24
+    assert f(dpclip.DP_OP_SQNORM, 1 << 20, 1 << 12, 64, 64, dpclip.DP_BF16) == 0
+    assert f(dpclip.DP_OP_CLIPPED_GRAD, 2, 64, 1 << 24, 64, dpclip.DP_BF16) == 0
+    g = dpclip.conv_workspace_bytes
+    assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_BF16) >= 256 + 4 * 128
+    assert g(dpclip.DP_OP_CLIPPED_GRAD, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_BF16) >= 256
+    assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F32) == 0        # bf16 only
+    assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 60, 3, 3, 1, 128, dpclip.DP_BF16) == 0       # C % 8 != 0
+    assert g(dpclip.DP_OP_SQNORM, 128, 2, 2, 64, 3, 3, 0, 128, dpclip.DP_BF16) == 0         # kernel larger than the image
+    assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 0, 3, 1, 128, dpclip.DP_BF16) == 0
+
+
 def test_missing_library_raises(monkeypatch):
     monkeypatch.setattr(dpclip, "_lib", None)
     monkeypatch.setattr(dpclip, "LIB_PATH", "/nonexistent/libdpclip.so")
