@@ -12,6 +12,7 @@ supported: --gpus above 1 exits with a message.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -49,7 +50,7 @@ class Pipeline:
         self.w, self.torch, self.dp, self.path = w, torch, dp, path
         self.dev = [(to_dev(A, torch), to_dev(G, torch)) for A, G in layers_np]
         self.B = self.dev[0][0].shape[0]
-        dt = dp.DP_BF16 if w.dtype == "bf16" else dp.DP_F32
+        dt = {"f32": dp.DP_F32, "bf16": dp.DP_BF16, "f16": dp.DP_F16}[w.dtype]
         self.s = torch.zeros(self.B, dtype=torch.float32, device="cuda")
         self.c = torch.zeros(self.B, dtype=torch.float32, device="cuda")
         self.grads, self.ws_sq, self.ws_cg = [], [], []
@@ -100,7 +101,7 @@ class Pipeline:
 
 def algorithmic_work(w, B):
     """Flops and HBM bytes per step that the method itself needs (no re-reads, no scratch)."""
-    es = 2 if w.dtype == "bf16" else 4
+    es = 2 if w.dtype in ("bf16", "f16") else 4
     out = {"norm_flops": 0, "gemm_flops": 0, "norm_bytes": 0, "gemm_bytes": 0, "noise_bytes": 0}
     for spec in w.layers:
         T, di, do = spec.T, spec.d_in, spec.d_out
@@ -315,6 +316,18 @@ def main():
                                     "sqnorm_gbs": wk2["norm_bytes"] / (pc[0] * 1e-3) / 1e9,
                                     "clipped_grad_gbs": wk2["gemm_bytes"] / (pc[2] * 1e-3) / 1e9}
             del p2, l2
+        # the transformer configuration with fp16 inputs (G and C carry a loss scale of 1024): the same kernels with
+        # the fp16 matrix instruction
+        w16, l16 = wl.generate("transformer", dtype="f16", g_scale=1024.0)
+        w16 = dataclasses.replace(w16, dtype="f16", C=w16.C * 1024.0, noise_std=w16.noise_std * 1024.0)
+        p16 = Pipeline(w16, l16, torch, dp, "auto")
+        ms16, ph16 = time_steps(p16, torch, 20, 3)
+        wk16 = algorithmic_work(w16, p16.B)
+        others["transformer_f16"] = {"examples_per_s": p16.B / (ms16 * 1e-3), "ms_per_step": ms16,
+                                     "sqnorm_ms": ph16[0], "clipped_grad_ms": ph16[2],
+                                     "sqnorm_tflops": wk16["norm_flops"] / (ph16[0] * 1e-3) / 1e12,
+                                     "clipped_grad_tflops": wk16["gemm_flops"] / (ph16[2] * 1e-3) / 1e12}
+        del p16, l16
         # the convolution configuration again, given by its input image (implicit unfolding: 16.8 MB of X instead of
         # the 151 MB patch matrix); same flops, same outputs as "conv"
         spec, Xn, Gn = wl.generate_conv_image()

@@ -31,8 +31,11 @@
  *  - NaN / Inf inputs are not detected; they propagate into the outputs.
  *  - Results are bit-reproducible for fixed inputs, sizes and build: all
  *    reductions run in a fixed order and no floating-point atomics are used.
- *  - bf16 inputs are the upper 16 bits of an IEEE float32; all accumulation
- *    and all outputs are float32.
+ *  - bf16 inputs are the upper 16 bits of an IEEE float32, fp16 inputs are
+ *    IEEE binary16; both run through the same kernels (the matrix
+ *    instruction for the format is the only difference) and multiply exactly
+ *    into float32.  All accumulation and all outputs are float32.  fp16
+ *    subnormals (values below 6.1e-5) take part with their exact value.
  */
 #ifndef DPCLIP_H
 #define DPCLIP_H
@@ -52,7 +55,9 @@ typedef enum {
     DP_ERR_HIP = 4          /* a kernel launch failed; hipGetLastError() has the cause */
 } dp_status;
 
-typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
+/* DP_F16 widens the library beyond what the paper ran (it used float32); it
+ * is accepted wherever DP_BF16 is. */
+typedef enum { DP_F32 = 0, DP_BF16 = 1, DP_F16 = 2 } dp_dtype;
 
 /* How dp_layer_sqnorm evaluates ||A_i^T G_i||_F^2 when T > 1.
  *   DIRECT: a tile of g_i = sum_t outer(A_i[t], G_i[t]) is accumulated in
@@ -101,10 +106,10 @@ dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C,
  *   clip       device float32[B]
  *   workspace  device scratch of at least
  *              dp_workspace_bytes(DP_OP_CLIPPED_GRAD, ...) bytes
- * With bf16 inputs the factor is applied either to the fp32 accumulators (one
- * fp32 rounding per example) or, in the kernels for unaligned shapes, to the
- * rows of A, which are then rounded back to bf16 (relative error 2^-9 per
- * element, unbiased). */
+ * With 16-bit inputs the factor is applied either to the fp32 accumulators
+ * (one fp32 rounding per example) or, in the kernels for unaligned shapes, to
+ * the rows of A, which are then rounded back to the input format (relative
+ * error 2^-9 per element for bf16, 2^-12 for fp16, unbiased). */
 dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
                           int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                           dp_dtype dtype, int accumulate, float* grad,
@@ -153,15 +158,15 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
  * matrix (Section 5.2; Algorithm 3 unfolds the image first, here the patches
  * are formed on the fly, so the kh*kw-fold larger matrix never exists in
  * memory).  Stride 1, zero padding `pad` on every side:
- *   X  device, [B, H, W, C] of bf16, channels last
- *   G  device, [B, T, d_out] of bf16, T = H_out * W_out output positions in
+ *   X  device, [B, H, W, C] of bf16 or fp16, channels last
+ *   G  device, [B, T, d_out] of the same type, T = H_out * W_out output positions in
  *      row-major (y, x) order, H_out = H + 2 pad - KH + 1, W_out likewise
  * The layer's weight gradient is [d_in, d_out] with d_in = KH*KW*C and row
  * index (kh*KW + kw)*C + c:  g_i[(kh,kw,c), o] = sum_{y,x} Xpad_i[y+kh, x+kw, c] * G_i[y*W_out + x, o].
  * dp_conv_sqnorm and dp_conv_clipped_grad compute exactly what
  * dp_layer_sqnorm (direct path) and dp_clipped_grad compute on the unfolded
  * A[B, T, d_in]; arguments not listed here mean the same as there.
- * Supported: DP_BF16, C % 8 == 0, d_out % 8 == 0, T >= 64 with at most a quarter
+ * Supported: DP_BF16 and DP_F16, C % 8 == 0, d_out % 8 == 0, T >= 64 with at most a quarter
  * of padding up to the next multiple of 32 (e.g. 784, 196, 1024), and a
  * [d_in, d_out] that tiles into 256 x 256, 192 x 128 or 128 x 128 blocks with at
  * most a quarter of padding; anything else is DP_ERR_UNSUPPORTED (unfold and use the

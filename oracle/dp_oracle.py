@@ -42,11 +42,11 @@ _MASK32 = 0xFFFFFFFF
 # --------------------------------------------------------------------------
 def widen(x: np.ndarray) -> np.ndarray:
     """Stored bits -> float64, exactly.  uint16 arrays are bf16 bit patterns
-    (upper half of a float32); float32 arrays are taken as they are."""
+    (upper half of a float32); float16 / float32 arrays are taken as they are."""
     x = np.asarray(x)
     if x.dtype == np.uint16:
         return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
-    if x.dtype == np.float32 or x.dtype == np.float64:
+    if x.dtype == np.float16 or x.dtype == np.float32 or x.dtype == np.float64:
         return x.astype(np.float64)
     raise TypeError(f"unsupported storage dtype {x.dtype}")
 
@@ -224,7 +224,7 @@ def conv_unfold(X, KH: int, KW: int, pad: int) -> np.ndarray:
     A[B, H_out*W_out, KH*KW*C] with A[b, y*W_out + x, (kh*KW + kw)*C + c] = Xpad[b, y+kh, x+kw, c].
     With it the layer is the sequence layer of Eq. recurrent_gradient over the output positions
     (Section 5.2); the column order only fixes how the [KH*KW*C, d_out] gradient is read."""
-    X = widen(np.asarray(X)) if np.asarray(X).dtype == np.uint16 else np.asarray(X, dtype=np.float64)
+    X = widen(np.asarray(X))
     B, H, W, C = X.shape
     Xp = np.zeros((B, H + 2 * pad, W + 2 * pad, C), dtype=np.float64)
     Xp[:, pad:pad + H, pad:pad + W, :] = X

@@ -11,7 +11,8 @@ namespace {
 constexpr int64_t kMaxRows = (int64_t(1) << 31) - 1;   // B*T
 constexpr int64_t kMaxDim = int64_t(1) << 24;          // d_in, d_out
 
-bool valid_dtype(dp_dtype d) { return d == DP_F32 || d == DP_BF16; }
+bool valid_dtype(dp_dtype d) { return d == DP_F32 || d == DP_BF16 || d == DP_F16; }
+bool is16(dp_dtype d) { return d == DP_BF16 || d == DP_F16; }
 bool valid_path(dp_path p) { return p == DP_PATH_AUTO || p == DP_PATH_GRAM || p == DP_PATH_DIRECT; }
 
 dp_status check_dims(int64_t B, int64_t T, int64_t d_in, int64_t d_out) {
@@ -36,13 +37,13 @@ size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dty
         GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
         return (size_t)B * g.npairs * sizeof(float);
     }
-    TnPlan p = (dtype == DP_BF16) ? plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out)
+    TnPlan p = is16(dtype) ? plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out)
                                   : plan_direct_f32((int)T, (int)d_in, (int)d_out);
     return (size_t)B * p.tiles_m * p.tiles_n * sizeof(float) + (p.zero_head ? kZeroHeadFloats * sizeof(float) : 0);
 }
 
 size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
-    TnPlan p = (dtype == DP_BF16) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
+    TnPlan p = is16(dtype) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
                                   : plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
     const size_t head = p.zero_head ? kZeroHeadFloats * sizeof(float) : 0;
     if (p.splits <= 1) return head;
@@ -96,7 +97,7 @@ size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t 
     if (op == DP_OP_SQNORM) {
         if (T == 1) return 0;
         const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
-        if (p == DP_PATH_GRAM && dtype != DP_BF16) return 0;
+        if (p == DP_PATH_GRAM && !is16(dtype)) return 0;
         return sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
     }
     if (op == DP_OP_CLIPPED_GRAD) return clipped_ws_bytes(B, T, d_in, d_out, dtype);
@@ -120,11 +121,11 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
 
     hipError_t e;
     if (T == 1) {
-        e = launch_sqnorm_dense(A, G, (int)B, (int)d_in, (int)d_out, dtype == DP_BF16, accumulate != 0, sqnorm, stream);
+        e = launch_sqnorm_dense(A, G, (int)B, (int)d_in, (int)d_out, (int)dtype, accumulate != 0, sqnorm, stream);
         return e == hipSuccess ? DP_OK : DP_ERR_HIP;
     }
     const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
-    if (p == DP_PATH_GRAM && dtype != DP_BF16) return DP_ERR_UNSUPPORTED;
+    if (p == DP_PATH_GRAM && !is16(dtype)) return DP_ERR_UNSUPPORTED;
     const size_t need = sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;           // > 2^31 partial sums
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
@@ -133,11 +134,11 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
     if (p == DP_PATH_GRAM) {
         GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
         e = launch_gram_bf16(g, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
-                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
-    } else if (dtype == DP_BF16) {
+                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16);
+    } else if (is16(dtype)) {
         TnPlan t = plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_direct_bf16(t, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
-                               (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
+                               (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16);
     } else {
         TnPlan t = plan_direct_f32((int)T, (int)d_in, (int)d_out);
         e = launch_direct_f32(t, static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
@@ -174,10 +175,10 @@ dp_status dp_clipped_grad(const void* A, const void* G, const float* clip, int64
     float* ws = static_cast<float*>(workspace);
 
     hipError_t e;
-    if (dtype == DP_BF16) {
+    if (is16(dtype)) {
         TnPlan p = plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_clipped_bf16(p, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), clip, (int)B, (int)T,
-                                (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream);
+                                (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, dtype == DP_F16);
     } else {
         TnPlan p = plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_clipped_f32(p, static_cast<const float*>(A), static_cast<const float*>(G), clip, (int)B, (int)T,
@@ -206,7 +207,7 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_
         return DP_OK;
     }
     if (!G || !aligned16(G)) return DP_ERR_INVALID_ARG;
-    hipError_t e = launch_bias_rows(G, nullptr, (int)B, (int)T, (int)d_out, dtype == DP_BF16, bias_rows, nullptr, stream);
+    hipError_t e = launch_bias_rows(G, nullptr, (int)B, (int)T, (int)d_out, (int)dtype, bias_rows, nullptr, stream);
     if (e == hipSuccess) e = launch_rows_sqnorm(bias_rows, (int)B, (int)d_out, accumulate != 0, sqnorm, stream);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
@@ -232,7 +233,7 @@ dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_
         return DP_OK;
     }
     if (!G || !Hbar || !aligned16(G) || !aligned16(Hbar)) return DP_ERR_INVALID_ARG;
-    hipError_t e = launch_bias_rows(G, Hbar, (int)B, (int)T, (int)d, dtype == DP_BF16, gamma_rows, beta_rows, stream);
+    hipError_t e = launch_bias_rows(G, Hbar, (int)B, (int)T, (int)d, (int)dtype, gamma_rows, beta_rows, stream);
     if (e == hipSuccess) e = launch_rows_sqnorm(gamma_rows, (int)B, (int)d, accumulate != 0, sqnorm, stream);
     if (e == hipSuccess) e = launch_rows_sqnorm(beta_rows, (int)B, (int)d, true, sqnorm, stream);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
@@ -259,7 +260,7 @@ size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_
     ConvGeom g; int64_t T, d_in;
     if (conv_geometry(B, H, W, C, KH, KW, pad, d_out, dtype, &g, &T, &d_in) != DP_OK) return 0;
     if (B == 0 || C == 0 || d_out == 0 || H == 0 || W == 0) return 0;
-    if (dtype != DP_BF16 || !dma_conv_ok(g, (int)d_out)) return 0;
+    if (!is16(dtype) || !dma_conv_ok(g, (int)d_out)) return 0;
     if (op == DP_OP_SQNORM) {
         const TnPlan p = plan_direct_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
         return kConvZeroBytes + (size_t)B * p.tiles_m * p.tiles_n * sizeof(float);
@@ -284,7 +285,7 @@ dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int
         if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
         return DP_OK;
     }
-    if (dtype != DP_BF16 || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    if (!is16(dtype) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
     if (!X || !G || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
     const size_t need = dp_conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dtype);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;
@@ -295,7 +296,7 @@ dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int
     const TnPlan p = plan_direct_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
     const hipError_t e = launch_direct_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), (int)B, (int)T,
                                                 (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, &g,
-                                                reinterpret_cast<const uint16_t*>(zero));
+                                                reinterpret_cast<const uint16_t*>(zero), dtype == DP_F16);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 
@@ -312,7 +313,7 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, 
         if (!accumulate && launch_fill_zero(grad, d_in * d_out, stream) != hipSuccess) return DP_ERR_HIP;
         return DP_OK;
     }
-    if (dtype != DP_BF16 || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    if (!is16(dtype) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
     if (!X || !G || !clip || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
     const size_t need = dp_conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dtype);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
@@ -322,7 +323,7 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, 
     const TnPlan p = plan_clipped_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
     const hipError_t e = launch_clipped_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), clip, (int)B,
                                                  (int)T, (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, &g,
-                                                 reinterpret_cast<const uint16_t*>(zero));
+                                                 reinterpret_cast<const uint16_t*>(zero), dtype == DP_F16);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 

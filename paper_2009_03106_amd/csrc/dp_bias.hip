@@ -16,9 +16,11 @@ namespace {
 // adds rows rgid, rgid + rg, ... in ascending order; the rg partial sums are then added in the
 // order 0 .. rg-1.  Needs D % VEC == 0 (with the 16-byte aligned base every load is aligned).
 // PROD: a second input Hb of the same shape; u2 gets the plain column sums and u the sums of G (*) Hb.
-template <bool BF16, bool PROD>
+// DT: 0 = float32, 1 = bf16, 2 = fp16
+template <int DT, bool PROD>
 __global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__ G, const void* __restrict__ Hb, int T, int D, int ctl,
                                                         float* __restrict__ u, float* __restrict__ u2) {
+    constexpr bool BF16 = DT != 0;                    // 16-bit elements
     constexpr int VEC = BF16 ? 8 : 4;
     __shared__ float part[kThreads][PROD ? 2 * VEC : VEC];
     const int tid = threadIdx.x, ct = 1 << ctl, rg = kThreads >> ctl;
@@ -32,7 +34,7 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__
         if (BF16) {
             const uint32_t d[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { x[2 * j] = bf16_lo(d[j]); x[2 * j + 1] = bf16_hi(d[j]); }
+            for (int j = 0; j < 4; ++j) { x[2 * j] = In16<DT == 2>::lo(d[j]); x[2 * j + 1] = In16<DT == 2>::hi(d[j]); }
         } else {
             x[0] = __uint_as_float(w.x); x[1] = __uint_as_float(w.y); x[2] = __uint_as_float(w.z); x[3] = __uint_as_float(w.w);
         }
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__
 }
 
 // Any D: one thread per column, rows in ascending order.
-template <bool BF16, bool PROD>
+template <int DT, bool PROD>
 __global__ __launch_bounds__(kThreads) void k_bias_rows_scalar(const void* __restrict__ G, const void* __restrict__ Hb, int T, int D,
                                                                float* __restrict__ u, float* __restrict__ u2) {
     const int q = blockIdx.x * kThreads + threadIdx.x;
@@ -108,9 +110,9 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows_scalar(const void* __res
     const size_t base = (size_t)ex * T * D + q;
     for (int t = 0; t < T; ++t) {
         const size_t k = base + (size_t)t * D;
-        const float g = BF16 ? bf16_to_f32(static_cast<const uint16_t*>(G)[k]) : static_cast<const float*>(G)[k];
+        const float g = DT != 0 ? In16<DT == 2>::lo(static_cast<const uint16_t*>(G)[k]) : static_cast<const float*>(G)[k];
         if (PROD) {
-            const float h = BF16 ? bf16_to_f32(static_cast<const uint16_t*>(Hb)[k]) : static_cast<const float*>(Hb)[k];
+            const float h = DT != 0 ? In16<DT == 2>::lo(static_cast<const uint16_t*>(Hb)[k]) : static_cast<const float*>(Hb)[k];
             acc += g * h; acc2 += g;
         } else {
             acc += g;
@@ -146,13 +148,9 @@ __global__ __launch_bounds__(kThreads) void k_clipped_bias(const float* __restri
     grad_b[q] = accumulate ? grad_b[q] + acc : acc;
 }
 
-}  // namespace
-
-// Hb == nullptr: u = column sums of G.  Otherwise u = column sums of G (*) Hb and u2 = column sums of G.
-hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, bool bf16, float* u, float* u2, hipStream_t st) {
-    const int vec = bf16 ? 8 : 4;
+template <int DT> void launch_bias_rows_dt(const void* G, const void* Hb, int B, int T, int D, float* u, float* u2, hipStream_t st) {
+    constexpr int vec = DT != 0 ? 8 : 4;
     const bool prod = Hb != nullptr;
-    if (B > 65535) return hipErrorInvalidValue;          // grid.y
     if (D % vec == 0) {
         const int nvec = D / vec;
         int ctl = 0;
@@ -161,17 +159,23 @@ hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, 
         // to keep enough loads in flight for HBM
         while (ctl > 4 && (int64_t)((nvec + (1 << ctl) - 1) >> ctl) * B < 1024) --ctl;
         const dim3 grid((unsigned)((nvec + (1 << ctl) - 1) >> ctl), (unsigned)B);
-        if (bf16) { if (prod) k_bias_rows<true, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
-                    else      k_bias_rows<true, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2); }
-        else      { if (prod) k_bias_rows<false, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
-                    else      k_bias_rows<false, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2); }
+        if (prod) k_bias_rows<DT, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
+        else      k_bias_rows<DT, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
     } else {
         const dim3 grid((unsigned)((D + kThreads - 1) / kThreads), (unsigned)B);
-        if (bf16) { if (prod) k_bias_rows_scalar<true, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
-                    else      k_bias_rows_scalar<true, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2); }
-        else      { if (prod) k_bias_rows_scalar<false, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
-                    else      k_bias_rows_scalar<false, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2); }
+        if (prod) k_bias_rows_scalar<DT, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
+        else      k_bias_rows_scalar<DT, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
     }
+}
+
+}  // namespace
+
+// Hb == nullptr: u = column sums of G.  Otherwise u = column sums of G (*) Hb and u2 = column sums of G.
+hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, int dt, float* u, float* u2, hipStream_t st) {
+    if (B > 65535) return hipErrorInvalidValue;          // grid.y
+    if (dt == 2)      launch_bias_rows_dt<2>(G, Hb, B, T, D, u, u2, st);
+    else if (dt == 1) launch_bias_rows_dt<1>(G, Hb, B, T, D, u, u2, st);
+    else              launch_bias_rows_dt<0>(G, Hb, B, T, D, u, u2, st);
     return hipGetLastError();
 }
 

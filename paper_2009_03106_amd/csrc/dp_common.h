@@ -24,6 +24,33 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// The two 16-bit input formats of the MFMA kernels.  The kernels move the 16-bit values as bits (typed bf16x8
+// whatever the format); only these four operations look inside them.
+template <bool F16> struct In16;
+template <> struct In16<false> {                   // bfloat16
+    static __device__ __forceinline__ float lo(uint32_t d) { return bf16_lo(d); }
+    static __device__ __forceinline__ float hi(uint32_t d) { return bf16_hi(d); }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return pack_bf16(lo, hi); }
+    static __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct In16<true> {                    // IEEE half
+    static __device__ __forceinline__ float lo(uint32_t d) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(d & 0xffffu)); }
+    static __device__ __forceinline__ float hi(uint32_t d) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(d >> 16)); }
+    // round to nearest even, lo in bits 15:0
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) {
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
+    static __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
+
 // (a.lo16, b.lo16) and (a.hi16, b.hi16) packs, a in the low half of the result.
 __device__ __forceinline__ uint32_t pack_lo16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
 __device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }

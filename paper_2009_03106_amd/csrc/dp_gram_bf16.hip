@@ -1,4 +1,4 @@
-// Gram path for the per-example squared norm (bf16 inputs):
+// Gram path for the per-example squared norm (16-bit inputs: bf16 or fp16):
 //     ||A_i^T G_i||_F^2 = sum_{t,s} (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}.
 // One workgroup owns one (example, t-tile, s-tile) with t-tile <= s-tile.  It
 // forms the tile of A_i A_i^T (contraction over d_in) and then the tile of
@@ -67,7 +67,7 @@ __device__ __forceinline__ void gram_commit(unsigned char* lds_tile, int tid, co
 }
 
 // One Gram product tile: acc[i][j] += X[t-tile rows] . X[s-tile rows]^T over D.
-template <int TT>
+template <int TT, bool F16>
 __device__ __forceinline__ void gram_product(const uint16_t* __restrict__ Xi, int T, int D, int t0, int s0, bool diag,
                                              unsigned char* lds, f32x16 (&acc)[TT / 64][TT / 64]) {
     constexpr int WT = TT / 2;       // rows (and columns) per wave
@@ -103,13 +103,13 @@ __device__ __forceinline__ void gram_product(const uint16_t* __restrict__ Xi, in
             for (int i = 0; i < NF; ++i)
 #pragma unroll
                 for (int j = 0; j < NF; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = In16<F16>::mfma(fa[i], fb[j], acc[i][j]);
         }
         __syncthreads();
     }
 }
 
-template <int TT>
+template <int TT, bool F16>
 __global__ __launch_bounds__(kThreads, 2) void k_gram_bf16(GramArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TT * 128];
     __shared__ float red[4];
@@ -131,8 +131,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_gram_bf16(GramArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { accP[i][j][r] = 0.f; accQ[i][j][r] = 0.f; }
 
-    gram_product<TT>(a.A + (size_t)ex * a.T * a.d_in, a.T, a.d_in, tt * TT, ss * TT, diag, lds, accP);
-    gram_product<TT>(a.G + (size_t)ex * a.T * a.d_out, a.T, a.d_out, tt * TT, ss * TT, diag, lds, accQ);
+    gram_product<TT, F16>(a.A + (size_t)ex * a.T * a.d_in, a.T, a.d_in, tt * TT, ss * TT, diag, lds, accP);
+    gram_product<TT, F16>(a.G + (size_t)ex * a.T * a.d_out, a.T, a.d_out, tt * TT, ss * TT, diag, lds, accQ);
 
     float s = 0.f;
 #pragma unroll
@@ -157,15 +157,15 @@ GramPlan plan_gram_bf16(int T, int d_in, int d_out) {
 }
 
 hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                            bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
-    if (gram_dma_ok(T, d_in, d_out)) return launch_gram_bf16_dma(p, A, G, B, T, d_in, d_out, accumulate, sqnorm, partial, st);
+                            bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
+    if (gram_dma_ok(T, d_in, d_out)) return launch_gram_bf16_dma(p, A, G, B, T, d_in, d_out, accumulate, sqnorm, partial, st, f16);
     GramArgs a;
     a.A = A; a.G = G; a.partial = partial;
     a.T = T; a.d_in = d_in; a.d_out = d_out;
     a.nt = p.nt; a.npairs = p.npairs;
     const unsigned grid = (unsigned)((int64_t)B * p.npairs);
-    if (p.tile == 64) k_gram_bf16<64><<<grid, kThreads, 0, st>>>(a);
-    else              k_gram_bf16<128><<<grid, kThreads, 0, st>>>(a);
+    if (p.tile == 64) { if (f16) k_gram_bf16<64, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16<64, false><<<grid, kThreads, 0, st>>>(a); }
+    else              { if (f16) k_gram_bf16<128, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16<128, false><<<grid, kThreads, 0, st>>>(a); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);

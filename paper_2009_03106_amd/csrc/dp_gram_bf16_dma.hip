@@ -1,4 +1,4 @@
-// Gram path of the per-example squared norm for aligned bf16 layers
+// Gram path of the per-example squared norm for aligned 16-bit (bf16 or fp16) layers
 // (d_in % 64 == 0, d_out % 64 == 0, T > 64):
 //     ||A_i^T G_i||_F^2 = sum_{t,s} (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}.
 // Same decomposition as the generic Gram kernel (one workgroup per example
@@ -53,6 +53,7 @@ template <int N> __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_
 
 __device__ __forceinline__ int gram_swz(int r) { return CPR == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
 
+template <bool F16>
 __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gram_bf16_dma(GramDmaArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[GNST * GSTAGE];
     __shared__ float red[4];
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[2 + j], acc[i][j], 0, 0, 0);
+                acc[i][j] = In16<F16>::mfma(f[i], f[2 + j], acc[i][j]);
     };
     bf16x8 f[2][4];
     // wait until at most `stages` later stages' copies are outstanding (4 per wave and stage on a diagonal pair, else 8)
@@ -211,13 +212,14 @@ bool gram_dma_ok(int T, int d_in, int d_out) {
 }
 
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
     GramDmaArgs a;
     a.A = A; a.G = G; a.partial = partial;
     a.B = B; a.T = T; a.d_in = d_in; a.d_out = d_out;
     a.nt = p.nt; a.npairs = p.npairs;
     a.per_xcd = (int)(((int64_t)B * p.npairs + 7) / 8);
-    k_gram_bf16_dma<<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+    if (f16) k_gram_bf16_dma<true><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+    else     k_gram_bf16_dma<false><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);

@@ -9,7 +9,8 @@
 namespace dpk {
 
 // ---- small elementwise / reduction kernels (dp_small_kernels.hip)
-hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, bool bf16,
+// dt: 0 = float32, 1 = bf16, 2 = fp16 (the values of dp_dtype)
+hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
                                bool accumulate, float* sqnorm, hipStream_t st);
 hipError_t launch_finalize_partials(const float* partial, int B, int n_per_example, bool accumulate,
                                     float* sqnorm, hipStream_t st);
@@ -20,7 +21,7 @@ hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool acc
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st);
 // ---- bias parameters (dp_bias.hip)
-hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, bool bf16, float* u, float* u2, hipStream_t st);
+hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, int dt, float* u, float* u2, hipStream_t st);
 hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st);
 hipError_t launch_clipped_bias(const float* u, const float* clip, int B, int D, bool accumulate, float* grad_b, hipStream_t st);
 hipError_t launch_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64_t first, hipStream_t st);
@@ -48,24 +49,25 @@ bool dma_clipped_ok(int B, int T, int M, int N);
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N);
 TnPlan plan_direct_f32(int T, int M, int N);
 
+// The 16-bit launchers below take bf16 bits, or fp16 bits when f16 is set.
 // out: splits == 1 -> nullptr workspace allowed and the tile goes straight to `grad` (overwrite
 // or accumulate); otherwise slices go to ws[splits][M][N] and a second kernel folds them.
 hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
-                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
+                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st, bool f16);
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
-                                   const ConvGeom* cg = nullptr, const uint16_t* zero = nullptr);
+                                   const ConvGeom* cg, const uint16_t* zero, bool f16);
 // direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
-                                  const ConvGeom* cg = nullptr, const uint16_t* zero = nullptr);
+                                  const ConvGeom* cg, const uint16_t* zero, bool f16);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
 // partial[B][tiles_m*tiles_n] then finalize into sqnorm
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
-                              bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+                              bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
 hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, int B, int T, int M, int N,
                              bool accumulate, float* sqnorm, float* partial, hipStream_t st);
 
@@ -78,8 +80,8 @@ struct GramPlan {
 GramPlan plan_gram_bf16(int T, int d_in, int d_out);
 bool gram_dma_ok(int T, int d_in, int d_out);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
 hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                            bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+                            bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
 
 }  // namespace dpk

@@ -25,7 +25,8 @@ __device__ __forceinline__ float row_sumsq_f32(const float* __restrict__ row, in
     return wave_sum(acc);
 }
 
-__device__ __forceinline__ float row_sumsq_bf16(const uint16_t* __restrict__ row, int d, int lane) {
+template <bool F16>
+__device__ __forceinline__ float row_sumsq_16(const uint16_t* __restrict__ row, int d, int lane) {
     float acc = 0.f;
     if ((d & 7) == 0) {
         const uint4* r8 = reinterpret_cast<const uint4*>(row);
@@ -34,17 +35,18 @@ __device__ __forceinline__ float row_sumsq_bf16(const uint16_t* __restrict__ row
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float lo = bf16_lo(w[j]), hi = bf16_hi(w[j]);
+                float lo = In16<F16>::lo(w[j]), hi = In16<F16>::hi(w[j]);
                 acc += lo * lo + hi * hi;
             }
         }
     } else {
-        for (int c = lane; c < d; c += kWave) { float v = bf16_to_f32(row[c]); acc += v * v; }
+        for (int c = lane; c < d; c += kWave) { float v = In16<F16>::lo(row[c]); acc += v * v; }
     }
     return wave_sum(acc);
 }
 
-template <bool BF16>
+// DT: 0 = float32, 1 = bf16, 2 = fp16
+template <int DT>
 __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restrict__ A, const void* __restrict__ G,
                                                            int B, int d_in, int d_out, int accumulate,
                                                            float* __restrict__ sqnorm) {
@@ -52,9 +54,9 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restric
     const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
     if (ex >= B) return;
     float sa, sg;
-    if (BF16) {
-        sa = row_sumsq_bf16(static_cast<const uint16_t*>(A) + (size_t)ex * d_in, d_in, lane);
-        sg = row_sumsq_bf16(static_cast<const uint16_t*>(G) + (size_t)ex * d_out, d_out, lane);
+    if (DT != 0) {
+        sa = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(A) + (size_t)ex * d_in, d_in, lane);
+        sg = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(G) + (size_t)ex * d_out, d_out, lane);
     } else {
         sa = row_sumsq_f32(static_cast<const float*>(A) + (size_t)ex * d_in, d_in, lane);
         sg = row_sumsq_f32(static_cast<const float*>(G) + (size_t)ex * d_out, d_out, lane);
@@ -65,12 +67,13 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restric
     }
 }
 
-hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, bool bf16,
+hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
                                bool accumulate, float* sqnorm, hipStream_t st) {
     const int per_block = kThreads / kWave;
     dim3 grid((B + per_block - 1) / per_block);
-    if (bf16) k_sqnorm_dense<true><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
-    else      k_sqnorm_dense<false><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
+    if (dt == 2)      k_sqnorm_dense<2><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
+    else if (dt == 1) k_sqnorm_dense<1><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
+    else              k_sqnorm_dense<0><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
     return hipGetLastError();
 }
 

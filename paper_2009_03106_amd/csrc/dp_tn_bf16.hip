@@ -1,4 +1,4 @@
-// bf16 K-major products  P = sum_k A[k, m-tile]^T G[k, n-tile]  on MFMA.
+// K-major products  P = sum_k A[k, m-tile]^T G[k, n-tile]  of 16-bit inputs (bf16 or fp16) on MFMA.
 //
 // Both operands are stored with the contraction index k (example-major rows
 // of the flattened [B*T, d] matrices) as the slow axis, while the MFMA wants
@@ -7,7 +7,7 @@
 // 8(k) x 8(col) block as eight 16-byte row pieces, repacks it into eight
 // 16-byte column pieces and stores those.  For the clipped sum the rows of A
 // are multiplied by their example's clip factor in the same step (the values
-// are in float registers anyway for the repack), then rounded back to bf16.
+// are in float registers anyway for the repack), then rounded back to 16 bits.
 //
 // Two kernels share the repack.  k_tn_bf16_seg (T >= 32) walks K example by
 // example: a per-example accumulator tile is finished when the example's T
@@ -15,7 +15,7 @@
 // one float multiply-add per element (exact clip factor, no re-rounding of A)
 // or squared and reduced.  k_tn_bf16_rows (small T, where an LDS stage would
 // be mostly padding) walks K in plain 64-row stages and scales the rows of A
-// by their clip factors during the repack, rounding them back to bf16.
+// by their clip factors during the repack, rounding them back to the input format.
 //
 // Two uses:
 //   * clipped sum (dp_clipped_grad): grid = tiles x K-slices; every slice's
@@ -98,7 +98,8 @@ __device__ __forceinline__ void transpose8x8(const uint4 (&r)[8], uint4 (&c)[8])
     }
 }
 
-// Same repack with row i multiplied by s[i] in float and rounded to bf16 (nearest even).
+// Same repack with row i multiplied by s[i] in float and rounded back to the input format (nearest even).
+template <bool F16>
 __device__ __forceinline__ void transpose8x8_scaled(const uint4 (&r)[8], const float (&s)[8], uint4 (&c)[8]) {
     uint32_t in[8][4];
 #pragma unroll
@@ -109,8 +110,8 @@ __device__ __forceinline__ void transpose8x8_scaled(const uint4 (&r)[8], const f
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const uint32_t x = in[2 * p][d], y = in[2 * p + 1][d];
-            e[p] = pack_bf16(bf16_lo(x) * s[2 * p], bf16_lo(y) * s[2 * p + 1]);
-            o[p] = pack_bf16(bf16_hi(x) * s[2 * p], bf16_hi(y) * s[2 * p + 1]);
+            e[p] = In16<F16>::pack(In16<F16>::lo(x) * s[2 * p], In16<F16>::lo(y) * s[2 * p + 1]);
+            o[p] = In16<F16>::pack(In16<F16>::hi(x) * s[2 * p], In16<F16>::hi(y) * s[2 * p + 1]);
         }
         c[2 * d] = make_uint4(e[0], e[1], e[2], e[3]);
         c[2 * d + 1] = make_uint4(o[0], o[1], o[2], o[3]);
@@ -118,7 +119,7 @@ __device__ __forceinline__ void transpose8x8_scaled(const uint4 (&r)[8], const f
 }
 
 // MODE 0: clipped sum (scale A rows, store the tile).  MODE 1: direct squared norm.
-template <int MODE>
+template <int MODE, bool F16>
 __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_rows(TnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BM * 128];   // A^T tile then G^T tile: [col][64 k]
     __shared__ float red[4];
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_rows(TnArgs a) {
     };
     auto commit = [&]() {
         uint4 cols[8];
-        if (MODE == 0 && opnd == 0) transpose8x8_scaled(stage, scl, cols);
+        if (MODE == 0 && opnd == 0) transpose8x8_scaled<F16>(stage, scl, cols);
         else transpose8x8(stage, cols);
 #pragma unroll
         for (int j = 0; j < 8; ++j)
@@ -203,7 +204,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_rows(TnArgs a) {
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = In16<F16>::mfma(fa[i], fb[j], acc[i][j]);
         }
         __syncthreads();
     }
@@ -259,7 +260,7 @@ struct SegArgs {
 // workgroups resident on one XCD at a time work on the same rows of A and G (same unit,
 // neighbouring tiles) and share them through that XCD's L2.
 // FAST: d_in, d_out and T are multiples of 8, so every 16-byte piece and every thread's 8 rows are all in or all out.
-template <int MODE, bool FAST>
+template <int MODE, bool FAST, bool F16>
 __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][2 * BM * 128];
     __shared__ float red[4];
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], fresh ? zero : acc[i][j], 0, 0, 0);
+                acc[i][j] = In16<F16>::mfma(fa[i], fb[j], fresh ? zero : acc[i][j]);
     };
 
     if (n_stages > 0) {
@@ -414,6 +415,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_seg(SegArgs a) {
 
 inline bool seg_fast(int T, int M, int N) { return ((T | M | N) & 7) == 0; }
 
+template <int MODE> void launch_seg(bool fast, bool f16, unsigned grid, const SegArgs& a, hipStream_t st) {
+    if (fast) { if (f16) k_tn_bf16_seg<MODE, true, true><<<grid, kThreads, 0, st>>>(a); else k_tn_bf16_seg<MODE, true, false><<<grid, kThreads, 0, st>>>(a); }
+    else      { if (f16) k_tn_bf16_seg<MODE, false, true><<<grid, kThreads, 0, st>>>(a); else k_tn_bf16_seg<MODE, false, false><<<grid, kThreads, 0, st>>>(a); }
+}
+
 // ---------------------------------------------------------------------------
 // Large-tile clipped sum: 256 x 256 output tile per workgroup, one workgroup
 // per compute unit (128 KB of LDS, double buffered), each wave owning a
@@ -441,6 +447,7 @@ struct BigArgs {
 };
 
 // Same repack as transpose8x8_scaled with one factor for all 8 rows.
+template <bool F16>
 __device__ __forceinline__ void transpose8x8_scaled1(const uint4 (&r)[8], float s, uint4 (&c)[8]) {
     uint32_t in[8][4];
 #pragma unroll
@@ -451,14 +458,15 @@ __device__ __forceinline__ void transpose8x8_scaled1(const uint4 (&r)[8], float 
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const uint32_t x = in[2 * p][d], y = in[2 * p + 1][d];
-            e[p] = pack_bf16(bf16_lo(x) * s, bf16_lo(y) * s);
-            o[p] = pack_bf16(bf16_hi(x) * s, bf16_hi(y) * s);
+            e[p] = In16<F16>::pack(In16<F16>::lo(x) * s, In16<F16>::lo(y) * s);
+            o[p] = In16<F16>::pack(In16<F16>::hi(x) * s, In16<F16>::hi(y) * s);
         }
         c[2 * d] = make_uint4(e[0], e[1], e[2], e[3]);
         c[2 * d + 1] = make_uint4(o[0], o[1], o[2], o[3]);
     }
 }
 
+template <bool F16>
 __global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_big(BigArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][2 * GM * 128];   // [buffer][A^T tile | G^T tile]
 
@@ -516,7 +524,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_big(BigArgs a) {
     }
     auto commit = [&](int buf) {
         uint4 cols[8];
-        transpose8x8_scaled1(stA, scl, cols);
+        transpose8x8_scaled1<F16>(stA, scl, cols);
 #pragma unroll
         for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(&lds[buf][wrA[j]]) = cols[j];
         transpose8x8(stG, cols);
@@ -561,7 +569,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_big(BigArgs a) {
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = In16<F16>::mfma(fa[i], fb[j], acc[i][j]);
         }
         __syncthreads();
     }
@@ -668,10 +676,10 @@ TnPlan plan_direct_bf16(int B, int T, int M, int N) {
 }
 
 hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
-                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st) {
+                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st, bool f16) {
     const int64_t n = (int64_t)M * N;
     const int tiles = p.tiles_m * p.tiles_n;
-    if (p.dma) return launch_clipped_bf16_dma(p, A, G, clip, B, T, M, N, accumulate, grad, ws, st);
+    if (p.dma) return launch_clipped_bf16_dma(p, A, G, clip, B, T, M, N, accumulate, grad, ws, st, nullptr, nullptr, f16);
     if (p.big) {
         BigArgs a;
         a.A = A; a.G = G; a.clip = clip;
@@ -680,7 +688,8 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
         a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
         if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
         else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-        k_tn_bf16_big<<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+        if (f16) k_tn_bf16_big<true><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+        else     k_tn_bf16_big<false><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
     } else if (p.segmented) {
         SegArgs a;
         a.A = A; a.G = G; a.clip = clip;
@@ -689,8 +698,7 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
         if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
         else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
         const unsigned grid = 8u * (unsigned)ceil_div(p.splits, 8) * (unsigned)tiles;
-        if (seg_fast(T, M, N)) k_tn_bf16_seg<0, true><<<grid, kThreads, 0, st>>>(a);
-        else k_tn_bf16_seg<0, false><<<grid, kThreads, 0, st>>>(a);
+        launch_seg<0>(seg_fast(T, M, N), f16, grid, a, st);
     } else {
         TnArgs a;
         a.A = A; a.G = G; a.clip = clip;
@@ -699,7 +707,8 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
         if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
         else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
         dim3 grid((unsigned)tiles, (unsigned)p.splits);
-        k_tn_bf16_rows<0><<<grid, kThreads, 0, st>>>(a);
+        if (f16) k_tn_bf16_rows<0, true><<<grid, kThreads, 0, st>>>(a);
+        else     k_tn_bf16_rows<0, false><<<grid, kThreads, 0, st>>>(a);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
@@ -707,8 +716,8 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
 }
 
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
-                              bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
-    if (p.dma) return launch_direct_bf16_dma(p, A, G, B, T, M, N, accumulate, sqnorm, partial, st);
+                              bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
+    if (p.dma) return launch_direct_bf16_dma(p, A, G, B, T, M, N, accumulate, sqnorm, partial, st, nullptr, nullptr, f16);
     const int tiles = p.tiles_m * p.tiles_n;
     if (p.segmented) {
         // one launch covers at most 2^20 examples so that the workgroup count stays far below 2^31
@@ -721,8 +730,7 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
             a.out = partial + (size_t)b0 * tiles; a.slice = 0; a.accumulate = 0;
             const int64_t grid = 8ll * ceil_div(nb, 8) * tiles;
             if (grid >= (int64_t(1) << 31)) return hipErrorInvalidValue;
-            if (seg_fast(T, M, N)) k_tn_bf16_seg<1, true><<<(unsigned)grid, kThreads, 0, st>>>(a);
-            else k_tn_bf16_seg<1, false><<<(unsigned)grid, kThreads, 0, st>>>(a);
+            launch_seg<1>(seg_fast(T, M, N), f16, (unsigned)grid, a, st);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
@@ -741,7 +749,8 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
         s.G = G + (size_t)b0 * T * N;
         s.out = partial + (size_t)b0 * tiles;
         dim3 grid((unsigned)tiles, (unsigned)nb);
-        k_tn_bf16_rows<1><<<grid, kThreads, 0, st>>>(s);
+        if (f16) k_tn_bf16_rows<1, true><<<grid, kThreads, 0, st>>>(s);
+        else     k_tn_bf16_rows<1, false><<<grid, kThreads, 0, st>>>(s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -1,4 +1,5 @@
-// Copy-pipeline bf16 kernels for aligned layers: clipped sum  sum_i c_i A_i^T G_i  and direct squared norm.
+// Copy-pipeline kernels for aligned layers with 16-bit inputs (bf16 or fp16; the kernels only move the bits, the
+// format decides which MFMA instruction consumes them): clipped sum  sum_i c_i A_i^T G_i  and direct squared norm.
 //
 // gfx950-specific data path with (almost) no VALU work in the main loop:
 //   * global -> LDS copies go straight into LDS (global_load_lds_dwordx4): a
@@ -15,7 +16,7 @@
 //     workgroups per compute unit, for narrow layers bound by HBM; 128 x 128
 //     for the mid-size layers that neither tiles without much padding.
 //
-// Clip factors are applied to the fp32 accumulators, not to the bf16 inputs:
+// Clip factors are applied to the fp32 accumulators, not to the 16-bit inputs:
 // the tile holds  (1 / c_cur) * sum_{j <= cur} c_j g_j ; when the rows of the
 // next example start it is multiplied by c_cur / c_next (one multiply per
 // accumulator register per example, skipped when the two factors are equal),
@@ -101,7 +102,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn
 // AM = 2 (ragged): T is not a multiple of the 32-row stage.  Every example then takes ceil(T / 32) stages, and
 // the rows past its end in the last one are copied from the line of zeros (rows of zeros add nothing to the
 // product); the per-lane addresses are 64-bit as in the convolution mode.
-template <class GEO, int MODE, int AM>
+template <class GEO, int MODE, int AM, bool F16>
 __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs a) {
     constexpr bool CONV = AM == 1, RAG = AM == 2;
     constexpr int NST = GEO::NST, FM = GEO::FM, FN = GEO::FN, NF = FM + FN;
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
         for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[FM + j], acc[i][j], 0, 0, 0);
+                acc[i][j] = In16<F16>::mfma(f[i], f[FM + j], acc[i][j]);
     };
     // stage s (relative) landed once at most `ahead` later stages' copies are outstanding
     auto wait_stage = [&](int ahead) {
@@ -460,16 +461,19 @@ int pick_geometry(int T, int M, int N, int64_t units) {
 int geo_of_plan(const TnPlan& p) { return p.tile_m == GeoL::TM ? 1 : (p.tile_m == GeoS::TM ? 2 : 3); }
 
 // am: 0 = rows of A as they lie in memory, 1 = implicit unfolding of an image, 2 = ragged T
-template <class GEO, int MODE> hipError_t launch_geo(const DmaArgs& a, int am, hipStream_t st) {
-    if (am == 1)      k_tn_bf16_dma<GEO, MODE, 1><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
-    else if (am == 2) k_tn_bf16_dma<GEO, MODE, 2><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
-    else              k_tn_bf16_dma<GEO, MODE, 0><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+template <class GEO, int MODE, bool F16> hipError_t launch_geo(const DmaArgs& a, int am, hipStream_t st) {
+    if (am == 1)      k_tn_bf16_dma<GEO, MODE, 1, F16><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+    else if (am == 2) k_tn_bf16_dma<GEO, MODE, 2, F16><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
+    else              k_tn_bf16_dma<GEO, MODE, 0, F16><<<8u * (unsigned)a.per_xcd, GEO::THREADS, 0, st>>>(a);
     return hipGetLastError();
 }
-template <int MODE> hipError_t launch_any(int geo, const DmaArgs& a, int am, hipStream_t st) {
-    if (geo == 1) return launch_geo<GeoL, MODE>(a, am, st);
-    if (geo == 2) return launch_geo<GeoS, MODE>(a, am, st);
-    return launch_geo<GeoT, MODE>(a, am, st);
+template <int MODE, bool F16> hipError_t launch_fmt(int geo, const DmaArgs& a, int am, hipStream_t st) {
+    if (geo == 1) return launch_geo<GeoL, MODE, F16>(a, am, st);
+    if (geo == 2) return launch_geo<GeoS, MODE, F16>(a, am, st);
+    return launch_geo<GeoT, MODE, F16>(a, am, st);
+}
+template <int MODE> hipError_t launch_any(int geo, const DmaArgs& a, int am, bool f16, hipStream_t st) {
+    return f16 ? launch_fmt<MODE, true>(geo, a, am, st) : launch_fmt<MODE, false>(geo, a, am, st);
 }
 
 void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
@@ -506,7 +510,7 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
 
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
-                                   const ConvGeom* cg, const uint16_t* zero) {
+                                   const ConvGeom* cg, const uint16_t* zero, bool f16) {
     int am = cg ? 1 : 0;
     if (!cg && p.zero_head) {
         // ragged T: the head of the workspace is the line of zeros
@@ -528,7 +532,7 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    const hipError_t e = launch_any<0>(geo_of_plan(p), a, am, st);
+    const hipError_t e = launch_any<0>(geo_of_plan(p), a, am, f16, st);
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
 }
@@ -558,7 +562,7 @@ TnPlan plan_direct_bf16_dma(int B, int T, int M, int N) {
 
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
-                                  const ConvGeom* cg, const uint16_t* zero) {
+                                  const ConvGeom* cg, const uint16_t* zero, bool f16) {
     int am = cg ? 1 : 0;
     if (!cg && p.zero_head) {
         const hipError_t ez = launch_fill_zero(partial, kZeroHeadFloats, st);
@@ -580,7 +584,7 @@ hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint
     const int64_t total = (int64_t)tiles * B;
     if (total >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     a.per_xcd = ceil_div(total, 8);
-    const hipError_t e = launch_any<1>(geo_of_plan(p), a, am, st);
+    const hipError_t e = launch_any<1>(geo_of_plan(p), a, am, f16, st);
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
 }

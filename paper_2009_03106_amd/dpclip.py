@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libdpclip.so")
 
 DP_OK = 0
 DP_ERR_INVALID_ARG, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_HIP = 1, 2, 3, 4
-DP_F32, DP_BF16 = 0, 1
+DP_F32, DP_BF16, DP_F16 = 0, 1, 2
 DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
@@ -91,6 +91,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return DP_F32
     if t.dtype == torch.bfloat16:
         return DP_BF16
+    if t.dtype == torch.float16:
+        return DP_F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 

@@ -14,7 +14,8 @@ activations, tanh activations, small Gaussian output gradients).
 
 Layouts: A is [B, T, d_in], G is [B, T, d_out], row-major, example-major.
 fp32 tensors are numpy float32.  bf16 tensors are numpy uint16 holding the
-upper 16 bits of the float32 value after round-to-nearest-even.
+upper 16 bits of the float32 value after round-to-nearest-even.  fp16 tensors
+(dtype "f16", an override of a configuration's own type) are numpy float16.
 """
 from __future__ import annotations
 
@@ -99,6 +100,8 @@ def _store(x: np.ndarray, dtype: str) -> np.ndarray:
         return x
     if dtype == "bf16":
         return f32_to_bf16_bits(x)
+    if dtype == "f16":
+        return x.astype(np.float16)           # numpy rounds to nearest even
     raise ValueError(dtype)
 
 
@@ -113,7 +116,7 @@ def make_layer(rng: np.random.Generator, B: int, spec: LayerSpec, dtype: str,
 
 
 def generate(name: str, B: int | None = None, straddle: bool = False,
-             layers: Tuple[int, ...] | None = None):
+             layers: Tuple[int, ...] | None = None, dtype: str | None = None, g_scale: float = 1.0):
     """Return (workload, [(A, G), ...]) for the named configuration.
 
     B overrides the batch size (used for bounded CPU samples and scaled sweeps).
@@ -123,6 +126,8 @@ def generate(name: str, B: int | None = None, straddle: bool = False,
     exercised.
     layers selects a subset of layer indices (all layers are still drawn so
     the random stream of the remaining ones does not change).
+    dtype stores the same draws in another format; g_scale multiplies G (a loss
+    scale, as mixed-precision training uses to keep fp16 gradients in range).
     """
     w = WORKLOADS[name]
     B = w.B if B is None else int(B)
@@ -132,7 +137,7 @@ def generate(name: str, B: int | None = None, straddle: bool = False,
         scale = (w.C / w.typical_norm) * np.exp(rng.uniform(np.log(0.1), np.log(10.0), size=B))
     out = []
     for li, spec in enumerate(w.layers):
-        pair = make_layer(rng, B, spec, w.dtype, w.a_dist, w.g_std, scale)
+        pair = make_layer(rng, B, spec, dtype or w.dtype, w.a_dist, w.g_std * g_scale, scale)
         if layers is None or li in layers:
             out.append(pair)
         else:
@@ -155,9 +160,10 @@ CONV_IMAGE = {"B": 128, "H": 32, "W": 32, "C": 64, "KH": 3, "KW": 3, "pad": 1, "
 
 def generate_conv_image(B: int | None = None, H: int | None = None, W: int | None = None, C: int | None = None,
                         KH: int | None = None, KW: int | None = None, pad: int | None = None,
-                        d_out: int | None = None, seed: int = BASE_SEED + 40, g_row_scale: np.ndarray | None = None):
-    """(spec, X, G): X[B,H,W,C] = max(0, N(0,1)), G[B, H_out*W_out, d_out] = N(0, g_std^2), both bf16 bit patterns.
-    Any geometry argument overrides the configuration's value."""
+                        d_out: int | None = None, seed: int = BASE_SEED + 40, g_row_scale: np.ndarray | None = None,
+                        dtype: str = "bf16"):
+    """(spec, X, G): X[B,H,W,C] = max(0, N(0,1)), G[B, H_out*W_out, d_out] = N(0, g_std^2), both stored as `dtype`
+    (bf16 bit patterns by default).  Any geometry argument overrides the configuration's value."""
     spec = dict(CONV_IMAGE)
     for k, v in (("B", B), ("H", H), ("W", W), ("C", C), ("KH", KH), ("KW", KW), ("pad", pad), ("d_out", d_out)):
         if v is not None:
@@ -168,4 +174,4 @@ def generate_conv_image(B: int | None = None, H: int | None = None, W: int | Non
     G = _draw(rng, (spec["B"], ho * wo, spec["d_out"]), "normal", spec["g_std"])
     if g_row_scale is not None:
         G *= g_row_scale.astype(np.float32)[:, None, None]
-    return spec, _store(X, "bf16"), _store(G, "bf16")
+    return spec, _store(X, dtype), _store(G, dtype)

@@ -83,6 +83,11 @@ def test_workspace_sizes_over_many_shapes(lib):
                     assert n >= 4 * B, (B, T, di, do, dt, path, n)
             n = f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dt)
             assert n >= 0 and n % 4 == 0 and n < (1 << 40)
+        # fp16 runs through the bf16 plans: the same scratch for every operation and path
+        for path in ("auto", "gram", "direct"):
+            assert f(dpclip.DP_OP_SQNORM, B, T, di, do, dpclip.DP_F16, path) == f(dpclip.DP_OP_SQNORM, B, T, di, do, dpclip.DP_BF16, path)
+        assert f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dpclip.DP_F16) == f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dpclip.DP_BF16)
+    assert f(dpclip.DP_OP_SQNORM, 4, 64, 64, 64, 3) == 0                                       # unknown dtype
     # a ragged sequence length on the copy-pipeline kernels sets aside a line of zeros even without K slices
     assert f(dpclip.DP_OP_CLIPPED_GRAD, 1, 197, 768, 768, dpclip.DP_BF16) >= 256
     # too large: B * T must stay below 2^31, layer widths below 2^24
@@ -91,7 +96,8 @@ def test_workspace_sizes_over_many_shapes(lib):
     g = dpclip.conv_workspace_bytes
     assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_BF16) >= 256 + 4 * 128
     assert g(dpclip.DP_OP_CLIPPED_GRAD, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_BF16) >= 256
-    assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F32) == 0        # bf16 only
+    assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F16) == g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_BF16)
+    assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F32) == 0        # 16-bit inputs only
     assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 60, 3, 3, 1, 128, dpclip.DP_BF16) == 0       # C % 8 != 0
     assert g(dpclip.DP_OP_SQNORM, 128, 2, 2, 64, 3, 3, 0, 128, dpclip.DP_BF16) == 0         # kernel larger than the image
     assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 0, 3, 1, 128, dpclip.DP_BF16) == 0

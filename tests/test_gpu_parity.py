@@ -2,12 +2,14 @@
 element by element on the same seeded inputs.  Needs a real MI355X.
 
 Tolerances (the inputs are the stored bits widened exactly, so they cover only accumulation order, fp32
-accumulation and, for some bf16 clipped-sum kernels, the re-rounding of nu_i * A to bf16):
-  squared norms   rel 1e-5 (fp32 inputs)      2e-2 (bf16 inputs)
-  clipped grad    rel Frobenius 1e-4 (fp32)   2e-2 (bf16)
+accumulation and, for some 16-bit clipped-sum kernels, the re-rounding of nu_i * A to the input format):
+  squared norms   rel 1e-5 (fp32 inputs)      2e-2 (bf16 inputs)   2e-3 (fp16 inputs)
+  clipped grad    rel Frobenius 1e-4 (fp32)   2e-2 (bf16)          2e-3 (fp16)
   clip factors    as the norms
   noise           |z_gpu - z_ref| <= 1e-5 (1 + |z_ref|), Philox words bit-exact
 """
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -17,11 +19,11 @@ from paper_2009_03106_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-SQ_TOL = {"f32": 1e-5, "bf16": 2e-2}
-FRO_TOL = {"f32": 1e-4, "bf16": 2e-2}
+SQ_TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-3}
+FRO_TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-3}
 # what the kernels are expected to reach in practice (fp32 accumulation of exact bf16 products);
 # looser than this but inside the stated tolerance would point at a real defect
-SQ_TIGHT = {"f32": 1e-5, "bf16": 2e-4}
+SQ_TIGHT = {"f32": 1e-5, "bf16": 2e-4, "f16": 2e-4}
 
 
 @pytest.fixture(scope="module")
@@ -64,8 +66,10 @@ def run_gpu_pipeline(dp, layers_np, C, path="auto", noise_std=0.0, seed=0):
     return s.cpu().numpy(), c.cpu().numpy(), [g.cpu().numpy() for g in grads]
 
 
-def check_pipeline(dp, name, B=None, straddle=False, path="auto", with_noise=False):
-    w, layers = wl.generate(name, B=B, straddle=straddle)
+def check_pipeline(dp, name, B=None, straddle=False, path="auto", with_noise=False, dtype=None, g_scale=1.0):
+    w, layers = wl.generate(name, B=B, straddle=straddle, dtype=dtype, g_scale=g_scale)
+    if dtype is not None or g_scale != 1.0:
+        w = dataclasses.replace(w, dtype=dtype or w.dtype, C=w.C * g_scale)
     std = w.noise_std if with_noise else 0.0
     s_ref, c_ref, g_ref = orc.run_pipeline(layers, w.C, std, w.noise_seed)
     s, c, g = run_gpu_pipeline(dp, layers, w.C, path=path, noise_std=std, seed=w.noise_seed)
@@ -124,6 +128,36 @@ def test_config_transformer_straddle_direct_path(dp):
     check_pipeline(dp, "transformer", B=4, straddle=True, path="direct")
 
 
+# fp16 inputs: the same kernels with the fp16 matrix instruction.  With a loss scale of 1024 on G (and on the
+# threshold C) the configurations' 1e-3-sized gradients sit in fp16's normal range; without it some 6 % of the
+# transformer's and 13 % of the convolution's values are fp16 subnormals, which must count with their exact value.
+@pytest.mark.parametrize("name,B,path,g_scale", [("rnn", None, "gram", 1024.0), ("rnn", None, "direct", 1024.0),
+                                                 ("conv", 16, "auto", 1024.0), ("conv", 16, "auto", 1.0),
+                                                 ("transformer", 8, "auto", 1024.0), ("transformer", 8, "auto", 1.0),
+                                                 ("transformer", 4, "direct", 1.0)])
+def test_configs_fp16(dp, name, B, path, g_scale):
+    check_pipeline(dp, name, B=B, path=path, dtype="f16", g_scale=g_scale)
+    check_pipeline(dp, name, B=B, path=path, straddle=True, dtype="f16", g_scale=g_scale)
+
+
+@pytest.mark.parametrize("B,T,d_in,d_out", [(4, 128, 256, 256), (3, 96, 72, 40), (5, 1, 256, 64), (2, 200, 128, 192)])
+def test_fp16_subnormal_gradients(dp, B, T, d_in, d_out):
+    """G entirely below fp16's normal range (|g| ~ 1e-6, a few units of its 6e-8 spacing): every kernel family
+    must still agree with the oracle, which takes the stored values exactly."""
+    rng = np.random.default_rng(31 + T)
+    A = rng.standard_normal((B, T, d_in)).astype(np.float16)
+    G = (rng.standard_normal((B, T, d_out)) * 1e-6).astype(np.float16)
+    assert np.all(np.abs(G.astype(np.float64)) < 6.1e-5) and np.count_nonzero(G) > G.size // 2
+    s_ref = orc.layer_sqnorm(A, G)
+    Ad, Gd = to_dev(A), to_dev(G)
+    for path in (("gram", "direct") if T > 1 else ("auto",)):
+        s = dp.layer_sqnorm(Ad, Gd, path=path).cpu().numpy()
+        assert rel_err(s, s_ref) <= SQ_TIGHT["f16"], (path, rel_err(s, s_ref))
+    c_ref = np.linspace(0.25, 1.0, B)
+    g = dp.clipped_grad(Ad, Gd, to_dev(c_ref.astype(np.float32))).cpu().numpy()
+    assert fro_err(g, orc.clipped_grad(A, G, c_ref)) <= FRO_TOL["f16"]
+
+
 def test_fused_qkv_equals_three_projections(dp):
     """Squared norm of the stacked 768 -> 2304 projection = sum over its three 768-wide blocks (Section 5.6)."""
     w, layers = wl.generate("transformer", B=4, layers=(0,))
@@ -156,7 +190,7 @@ RAGGED = [
 ]
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("B,T,d_in,d_out", RAGGED)
 def test_ragged_shapes(dp, dtype, B, T, d_in, d_out):
     A, G = wl.random_layer(1234 + B + T + d_in, B, T, d_in, d_out, dtype,
@@ -275,7 +309,7 @@ BIAS_SHAPES = [(3, 1, 3), (7, 1, 67), (5, 1, 1024), (2, 3, 8), (3, 17, 40), (2, 
                (1, 64, 9), (2, 33, 65), (4, 300, 2304), (9, 5, 4100)]
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("B,T,d_out", BIAS_SHAPES)
 def test_bias_shapes(dp, dtype, B, T, d_out):
     _, G = wl.random_layer(900 + B + T + d_out, B, T, 8, d_out, dtype, g_row_scale=np.exp(np.linspace(-2, 1, B)))
@@ -325,7 +359,7 @@ def test_bias_on_configurations(dp, name):
         assert fro_err(gb, orc.clipped_bias_grad(G, c_ref)) <= 1e-4
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("B,T,d", [(3, 1, 8), (4, 7, 67), (2, 130, 264), (5, 64, 768), (2, 512, 768), (3, 33, 4100)])
 def test_layernorm_rows_and_norms(dp, dtype, B, T, d):
     Hb, G = wl.random_layer(700 + B + T + d, B, T, d, d, dtype, g_row_scale=np.exp(np.linspace(-1, 1, B)))
@@ -428,6 +462,27 @@ def test_conv_from_image(dp, B, H, W, C, KH, KW, pad, d_out):
     assert fro_err(g2.cpu().numpy() - 1.0, g_ref) <= FRO_TOL["bf16"]
     # the same layer through the general entry points on the unfolded patch matrix (same kernels, same order)
     Ad = to_dev(wl.f32_to_bf16_bits(A.astype(np.float32)))
+    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
+    np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
+
+
+@pytest.mark.parametrize("B,H,W,C,KH,KW,pad,d_out", [CONV_GEOMS[0], CONV_GEOMS[1], CONV_GEOMS[3], CONV_GEOMS[6]])
+def test_conv_from_image_fp16(dp, B, H, W, C, KH, KW, pad, d_out):
+    """fp16 images and gradients (G carries a loss scale of 1024) through the implicit unfolding."""
+    spec, X, G = wl.generate_conv_image(B=B, H=H, W=W, C=C, KH=KH, KW=KW, pad=pad, d_out=d_out,
+                                        g_row_scale=1024.0 * np.exp(np.linspace(-1, 2, B)), dtype="f16")
+    A = orc.conv_unfold(X, KH, KW, pad)
+    s_ref = orc.layer_sqnorm(A, G)
+    Cc = float(np.sqrt(np.median(s_ref)))
+    c_ref = orc.clip_factors(s_ref, Cc)
+    g_ref = orc.clipped_grad(A, G, c_ref)
+    Xd, Gd = to_dev(X), to_dev(G)
+    s = dp.conv_sqnorm(Xd, Gd, KH, KW, pad)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["f16"], rel_err(s.cpu().numpy(), s_ref)
+    c = dp.clip_factors(s, Cc)
+    g = dp.conv_clipped_grad(Xd, Gd, c, KH, KW, pad)
+    assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL["f16"], fro_err(g.cpu().numpy(), g_ref)
+    Ad = to_dev(A.astype(np.float16))                 # exact: the patches are copies of fp16 values
     np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
     np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
 

@@ -307,6 +307,19 @@ def test_bf16_widening_exact():
     np.testing.assert_array_equal(back, wl.bf16_bits_to_f32(bits).astype(np.float64))
 
 
+def test_fp16_storage_is_taken_exactly():
+    # binary16 values, subnormals included, reach the oracle's float64 arithmetic unchanged
+    x = np.array([1.0, -2.5, 2.0 ** -14, 2.0 ** -24, 3 * 2.0 ** -24, 65504.0], dtype=np.float16)
+    np.testing.assert_array_equal(orc.widen(x), [1.0, -2.5, 2.0 ** -14, 2.0 ** -24, 3 * 2.0 ** -24, 65504.0])
+    A = np.array([[[1.0, 2.0 ** -24]]], dtype=np.float16)          # B = T = 1, d_in = 2
+    G = np.array([[[3.0, 2.0 ** -20]]], dtype=np.float16)
+    # ||a g^T||_F^2 = ||a||^2 ||g||^2
+    assert orc.layer_sqnorm(A, G)[0] == (1.0 + 2.0 ** -48) * (9.0 + 2.0 ** -40)
+    # the generator's fp16 store rounds to nearest even: 1 + 2^-11 lies between 1 and 1 + 2^-10
+    y = wl._store(np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11], dtype=np.float32), "f16")
+    assert y.dtype == np.float16 and y[0] == 1.0 and y[1] == np.float16(1.0 + 2.0 ** -9)
+
+
 def test_bf16_rounding_ties_to_even():
     # 1 + 2^-8 lies exactly between bf16 neighbours 1.0 and 1 + 2^-7 -> even mantissa (1.0)
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8], dtype=np.float32)
