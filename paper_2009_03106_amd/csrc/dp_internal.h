@@ -32,11 +32,11 @@ struct TnPlan {
     int tiles_m, tiles_n;
     int splits;             // clipped grad: number of K slices; direct sqnorm: unused
     int kchunk;             // rows of K per slice
-    bool segmented;         // bf16 only: K is walked example by example (slices are whole examples)
+    bool segmented;         // 16-bit inputs only: K is walked example by example (slices are whole examples)
     int epu;                // segmented: examples per K slice
-    bool big;               // bf16 clipped sum only: 256 x 256 tiles, one workgroup per compute unit
+    bool big;               // 16-bit clipped sum only: 256 x 256 tiles, one workgroup per compute unit
     bool zero_head = false; // the kernel needs a line of zeros: the first kZeroHeadFloats floats of the workspace are set aside for it
-    bool dma;               // bf16 only: copy-pipeline kernel (direct-to-LDS copies, transposing LDS reads); tile_m x tile_n names its geometry
+    bool dma;               // 16-bit inputs only: copy-pipeline kernel (direct-to-LDS copies, transposing LDS reads); tile_m x tile_n names its geometry
 };
 constexpr int kZeroHeadFloats = 64;   // 256 bytes
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
@@ -71,7 +71,7 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
 hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, int B, int T, int M, int N,
                              bool accumulate, float* sqnorm, float* partial, hipStream_t st);
 
-// ---- Gram path (dp_gram_bf16.hip)
+// ---- Gram path, 16-bit inputs (dp_gram_bf16.hip, dp_gram_bf16_dma.hip)
 struct GramPlan {
     int tile;     // rows of T per tile
     int nt;       // tiles along T

@@ -210,6 +210,43 @@ def test_ragged_shapes(dp, dtype, B, T, d_in, d_out):
     assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL[dtype]
 
 
+def _drawn_shapes(n, seed):
+    """Seeded shapes around the dispatch thresholds: sequence lengths at and next to multiples of the 32-row stage
+    and of the 128-row Gram tile, widths that are multiples of 64, of 8 only, or odd, tiles that just fit or just
+    miss the quarter-of-padding rule."""
+    rng = np.random.default_rng(seed)
+    t_pool = [1, 2, 7, 8, 24, 31, 32, 33, 40, 63, 64, 65, 96, 100, 127, 128, 129, 160, 161, 192, 197, 255, 256, 257, 300]
+    d_pool = [8, 24, 40, 64, 72, 104, 120, 128, 136, 192, 200, 256, 264, 320, 376, 384, 392, 512, 520, 576, 640,
+              5, 33, 67, 129, 250]
+    out = []
+    for _ in range(n):
+        out.append((int(rng.integers(1, 6)), int(rng.choice(t_pool)), int(rng.choice(d_pool)), int(rng.choice(d_pool)),
+                    str(rng.choice(["f32", "bf16", "f16"]))))
+    return out
+
+
+@pytest.mark.parametrize("B,T,d_in,d_out,dtype", _drawn_shapes(48, 20090310))
+def test_drawn_shapes(dp, B, T, d_in, d_out, dtype):
+    A, G = wl.random_layer(B * 7 + T * 3 + d_in + 11 * d_out, B, T, d_in, d_out, dtype,
+                           g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    C = float(np.sqrt(np.median(s_ref)))
+    c_ref = orc.clip_factors(s_ref, C)
+    g_ref = orc.clipped_grad(A, G, c_ref)
+    Ad, Gd = to_dev(A), to_dev(G)
+    paths = ["auto"] if (T == 1 or dtype == "f32") else ["gram", "direct", "auto"]
+    for path in paths:
+        s = dp.layer_sqnorm(Ad, Gd, path=path)
+        assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], (path, rel_err(s.cpu().numpy(), s_ref))
+    c = dp.clip_factors(s, C)
+    assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL[dtype]
+    g = dp.clipped_grad(Ad, Gd, c)
+    assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL[dtype]
+    g2 = torch.full_like(g, 0.5)
+    dp.clipped_grad(Ad, Gd, c, g2, accumulate=True)
+    assert fro_err(g2.cpu().numpy() - 0.5, g_ref) <= FRO_TOL[dtype] + 1e-6 * 0.5 * np.sqrt(g_ref.size) / max(np.linalg.norm(g_ref), 1e-30)
+
+
 # long sequences (many Gram tile pairs, ragged last tile), wide layers (many output tiles, few rows), one example
 LARGE = [(2, 2048, 128, 192), (1, 1056, 64, 64), (3, 64, 2048, 1024), (1, 4096, 64, 128), (11, 96, 768, 384)]
 
