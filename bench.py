@@ -60,8 +60,14 @@ class Pipeline:
             n2 = dp.workspace_bytes(dp.DP_OP_CLIPPED_GRAD, self.B, spec.T, spec.d_in, spec.d_out, dt)
             self.ws_sq.append(torch.empty(max(n1, 16), dtype=torch.uint8, device="cuda"))
             self.ws_cg.append(torch.empty(max(n2, 16), dtype=torch.uint8, device="cuda"))
+        self.descs = dp.layer_descs(self.dev)
+        self.ws_layers = torch.empty(max(16, dp.layers_workspace_bytes(self.descs[0], self.B, dt, path)), dtype=torch.uint8, device="cuda")
 
     def phase_sqnorm(self):
+        if len(self.dev) > 1:
+            # all layers in one call: the copy-pipeline Gram layers share a launch
+            self.dp.layers_sqnorm(self.dev, self.s, path=self.path, workspace=self.ws_layers, descs=self.descs)
+            return
         for li, (A, G) in enumerate(self.dev):
             self.dp.layer_sqnorm(A, G, self.s, path=self.path, accumulate=li > 0, workspace=self.ws_sq[li])
 
@@ -69,9 +75,11 @@ class Pipeline:
         self.dp.clip_factors(self.s, self.w.C, self.c)
 
     def phase_grad(self):
-        # last layer first, as a backward pass would: the inputs that the norm phase read last are the likeliest
-        # to be still in the Infinity Cache
-        for li in reversed(range(len(self.dev))):
+        # the layers that the norm phase read last first: their inputs are the likeliest to be still in the
+        # Infinity Cache (the several-layers call runs the widest layers first, a single call per layer runs them
+        # in the order given)
+        order = sorted(range(len(self.dev)), key=lambda li: self.dev[li][0].shape[2] + self.dev[li][1].shape[2])
+        for li in order:
             A, G = self.dev[li]
             self.dp.clipped_grad(A, G, self.c, self.grads[li], workspace=self.ws_cg[li])
 

@@ -89,6 +89,35 @@ dp_status dp_layer_sqnorm(const void* A, const void* G,
                           float* sqnorm, void* workspace, size_t workspace_bytes,
                           void* hip_stream);
 
+/* The same for several layers of one model in one call (the whole-model norm
+ * is the sum over the layers; Section 5, paragraph before 5.1):
+ *     sqnorm[i] = (accumulate ? sqnorm[i] : 0) + sum_l ||A_l,i^T G_l,i||_F^2.
+ * Layers on the Gram path whose widths are multiples of 64 (16-bit inputs,
+ * T > 64) share kernel launches, up to 16 layers each: the workgroups of one
+ * layer then fill the idle tail of another's, which a per-layer launch leaves
+ * empty.  Every other layer is handled exactly as dp_layer_sqnorm handles it.
+ * The result equals per-layer calls up to the order of the float32 additions
+ * over layers (those other layers first, in the order given; then the shared
+ * launches, widest layer first).
+ *   layers     HOST array of n_layers descriptors, read during the call only;
+ *              A and G are device pointers as in dp_layer_sqnorm; all layers
+ *              share B, dtype and path
+ *   workspace  device scratch of at least dp_layers_workspace_bytes(...) bytes
+ * n_layers == 0 (or only empty layers) zero-fills sqnorm unless accumulating. */
+typedef struct {
+    const void* A;              /* device, [B, T, d_in] */
+    const void* G;              /* device, [B, T, d_out] */
+    int64_t T, d_in, d_out;
+} dp_layer_desc;
+
+dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
+                           dp_dtype dtype, dp_path path, int accumulate,
+                           float* sqnorm, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+size_t dp_layers_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
+                                 dp_dtype dtype, dp_path path);
+
 /* Clip factors (Algorithm 1, the line defining nu_i; Eq. per_example_weight;
  * clip function of Section 3.2):
  *     clip[i] = 1 / max(1, sqrt(sqnorm[i]) / C)  =  min(1, C / ||g_i||),

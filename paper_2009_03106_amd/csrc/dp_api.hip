@@ -50,6 +50,15 @@ size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dt
     return head + (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float);
 }
 
+// a layer that the batched Gram launch of dp_layers_sqnorm takes (everything else goes through dp_layer_sqnorm)
+bool gram_batchable(int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
+    if (T <= 1 || d_in == 0 || d_out == 0 || !is16(dtype)) return false;
+    if (resolve_path(path, dtype, T, d_in, d_out) != DP_PATH_GRAM) return false;
+    return gram_dma_ok((int)T, (int)d_in, (int)d_out);
+}
+
+size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
+
 constexpr size_t kConvZeroBytes = 256;                // head of the conv workspace: a line of zeros for the padding
 
 // geometry check shared by the conv entry points; fills T and d_in
@@ -343,6 +352,107 @@ dp_status dp_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64
     if (!out) return DP_ERR_INVALID_ARG;
     hipError_t e = launch_philox_raw(out, n_counters, seed, first_counter, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+}  // extern "C"
+
+namespace {
+
+// checks shared by dp_layers_sqnorm and its size query; *any_work: some layer is not empty
+dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path, bool pointers) {
+    if (n_layers < 0 || B < 0 || (n_layers > 0 && !layers)) return DP_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype) || !valid_path(path)) return DP_ERR_INVALID_ARG;
+    if (n_layers > 4096) return DP_ERR_UNSUPPORTED;
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        const dp_status st = check_dims(B, y.T, y.d_in, y.d_out);
+        if (st != DP_OK) return st;
+        if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (pointers && (!y.A || !y.G || !aligned16(y.A) || !aligned16(y.G))) return DP_ERR_INVALID_ARG;
+        if (y.T > 1 && !is16(dtype) && resolve_path(path, dtype, y.T, y.d_in, y.d_out) == DP_PATH_GRAM) return DP_ERR_UNSUPPORTED;
+    }
+    return DP_OK;
+}
+
+// scratch: the layers that run one by one reuse one region, and so do the batched launches
+size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path) {
+    size_t single = 0, batch = 0, batch_max = 0;
+    int in_batch = 0;
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) {
+            if (in_batch == kGramBatch) { in_batch = 0; batch = 0; }
+            const GramPlan g = plan_gram_bf16((int)y.T, (int)y.d_in, (int)y.d_out);
+            batch += (size_t)B * g.npairs * sizeof(float);
+            ++in_batch;
+            if (batch > batch_max) batch_max = batch;
+        } else {
+            const size_t n = dp_workspace_bytes(DP_OP_SQNORM, B, y.T, y.d_in, y.d_out, dtype, path);
+            if (n > single) single = n;
+        }
+    }
+    return round16(single > batch_max ? single : batch_max);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dp_layers_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path) {
+    if (check_layers(layers, n_layers, B, dtype, path, false) != DP_OK) return 0;
+    return layers_ws_bytes(layers, n_layers, B, dtype, path);
+}
+
+dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path,
+                           int accumulate, float* sqnorm, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const dp_status st = check_layers(layers, n_layers, B, dtype, path, true);
+    if (st != DP_OK) return st;
+    if (B == 0) return DP_OK;
+    if (!sqnorm) return DP_ERR_INVALID_ARG;
+    const size_t need = layers_ws_bytes(layers, n_layers, B, dtype, path);
+    if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    int acc = accumulate != 0;
+    bool launched = false;
+    // layers outside the batched Gram launch, in the order given
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;                 // adds nothing
+        if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
+        const dp_status s1 = dp_layer_sqnorm(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes, hip_stream);
+        if (s1 != DP_OK) return s1;
+        acc = 1; launched = true;
+    }
+    // the others, up to kGramBatch per launch, heaviest first inside a launch (the light ones fill its tail)
+    GramLayerDesc batch[kGramBatch];
+    int nb = 0;
+    auto flush = [&]() -> hipError_t {
+        if (nb == 0) return hipSuccess;
+        for (int i = 1; i < nb; ++i) {                                          // stable insertion sort, descending work
+            const GramLayerDesc v = batch[i];
+            const int64_t wv = (int64_t)(v.d_in + v.d_out);
+            int j = i;
+            while (j > 0 && (int64_t)(batch[j - 1].d_in + batch[j - 1].d_out) < wv) { batch[j] = batch[j - 1]; --j; }
+            batch[j] = v;
+        }
+        const hipError_t e = launch_gram_bf16_dma_layers(batch, nb, (int)B, acc != 0, sqnorm, static_cast<float*>(workspace),
+                                                         stream, dtype == DP_F16);
+        nb = 0; acc = 1; launched = true;
+        return e;
+    };
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (!gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
+        batch[nb++] = GramLayerDesc{static_cast<const uint16_t*>(y.A), static_cast<const uint16_t*>(y.G), (int)y.T, (int)y.d_in, (int)y.d_out};
+        if (nb == kGramBatch && flush() != hipSuccess) return DP_ERR_HIP;
+    }
+    if (flush() != hipSuccess) return DP_ERR_HIP;
+    if (!launched && !accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+    return DP_OK;
 }
 
 }  // extern "C"

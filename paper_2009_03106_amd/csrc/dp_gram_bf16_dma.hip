@@ -37,13 +37,22 @@ constexpr int GNST = 2;                 // stages resident in LDS (64 KB: two wo
                                         // 3 stages of GK = 64 with one workgroup per compute unit 7 % slower
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
-struct GramDmaArgs {
+// One launch covers up to kGramBatch layers: their (example, pair) work items form one list, so that the tail of
+// one layer's work (10 items per example at T = 512 against 512 resident workgroups) is filled by the next layer's.
+struct GramDmaLayer {
     const uint16_t* A;
     const uint16_t* G;
-    float* partial;      // [B][npairs]
-    int B, T, d_in, d_out;
+    int T, d_in, d_out;
     int nt, npairs;
-    int per_xcd;
+    int first;           // index of the layer's first item in partial[]; its items are partial[first + ex * npairs + slot]
+    int per_xcd;         // items of this layer per XCD queue: ceil(B * npairs / 8)
+};
+struct GramDmaArgs {
+    GramDmaLayer layer[kGramBatch];
+    int n_layers;
+    float* partial;
+    int B;
+    int per_xcd;         // length of one XCD's queue: sum of the layers' per_xcd
 };
 
 // chunk c (16 B) of tile row r sits at chunk position c ^ swz(r) so that 16 consecutive rows reading the same
@@ -60,20 +69,26 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // Work order.  Consecutive workgroup ids go round the 8 XCDs, so id & 7 names the XCD (and its L2) and
-    // id >> 3 the position in that XCD's queue.  Each XCD takes a contiguous eighth of the (example, pair) list,
-    // example-major: the pairs of one example run on one XCD at about the same time and share its L2 (measured:
-    // 1.09x the algorithmic bytes from HBM; with the diagonal pairs moved to the end of the queue, to fill the tail
-    // of the launch, 1.5x for the same run time).
-    const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
-    if (L >= a.B * a.npairs) return;
-    const int ex = L / a.npairs;
-    const int slot = L - ex * a.npairs;                 // position in the row-major list of (tt, ss), tt <= ss
+    // id >> 3 the position in that XCD's queue.  Each XCD takes a contiguous eighth of every layer's
+    // (example, pair) list, example-major, one layer after the other: the pairs of one example run on one XCD at
+    // about the same time and share its L2 (measured: 1.09x the algorithmic bytes from HBM; with the diagonal
+    // pairs moved to the end of the queue 1.5x for the same run time), and every XCD gets the same mix of layers.
+    const int xcd = blockIdx.x & 7;
+    int q = blockIdx.x >> 3;
+    int li = 0;
+    while (li < a.n_layers && q >= a.layer[li].per_xcd) { q -= a.layer[li].per_xcd; ++li; }
+    if (li >= a.n_layers) return;
+    const GramDmaLayer ly = a.layer[li];
+    const int L = xcd * ly.per_xcd + q;                 // item of this layer
+    if (L >= a.B * ly.npairs) return;
+    const int ex = L / ly.npairs;
+    const int slot = L - ex * ly.npairs;                // position in the row-major list of (tt, ss), tt <= ss
     int pair = slot, tt = 0;
-    while (pair >= a.nt - tt) { pair -= a.nt - tt; ++tt; }
+    while (pair >= ly.nt - tt) { pair -= ly.nt - tt; ++tt; }
     const int ss = tt + pair;
     const bool diag = (tt == ss);
 
-    const int sa = a.d_in / GK, sg = a.d_out / GK;      // stages of the A phase and of the G phase
+    const int sa = ly.d_in / GK, sg = ly.d_out / GK;      // stages of the A phase and of the G phase
     const int n_stages = sa + sg;
 
     // ---- copies: wave w moves rows 32w .. 32w+31 of the t-tile and of the s-tile, 4 instructions each
@@ -86,12 +101,12 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     for (int u = 0; u < IPT; ++u) {
         const int r = wave * 32 + u * RPI + lrow8;                     // row inside the tile
         const uint32_t c16 = (uint32_t)((cp ^ gram_swz(r)) << 4);      // source chunk for this LDS slot
-        const uint32_t rt = (uint32_t)min(tt * GT + r, a.T - 1), rs = (uint32_t)min(ss * GT + r, a.T - 1);
-        off_t[0][u] = rt * (uint32_t)a.d_in * 2u + c16;  off_s[0][u] = rs * (uint32_t)a.d_in * 2u + c16;
-        off_t[1][u] = rt * (uint32_t)a.d_out * 2u + c16; off_s[1][u] = rs * (uint32_t)a.d_out * 2u + c16;
+        const uint32_t rt = (uint32_t)min(tt * GT + r, ly.T - 1), rs = (uint32_t)min(ss * GT + r, ly.T - 1);
+        off_t[0][u] = rt * (uint32_t)ly.d_in * 2u + c16;  off_s[0][u] = rs * (uint32_t)ly.d_in * 2u + c16;
+        off_t[1][u] = rt * (uint32_t)ly.d_out * 2u + c16; off_s[1][u] = rs * (uint32_t)ly.d_out * 2u + c16;
     }
-    const uint16_t* baseA = a.A + (size_t)ex * a.T * a.d_in;          // uniform example bases; lane offsets stay 32-bit
-    const uint16_t* baseG = a.G + (size_t)ex * a.T * a.d_out;
+    const uint16_t* baseA = ly.A + (size_t)ex * ly.T * ly.d_in;          // uniform example bases; lane offsets stay 32-bit
+    const uint16_t* baseG = ly.G + (size_t)ex * ly.T * ly.d_out;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_base + wave * 32 * ROWB);
     // The copies are inline assembly so that the compiler does not tie every LDS read to them; they are
@@ -196,12 +211,12 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
             for (int r = 0; r < 16; ++r) {
                 const int row = tt * GT + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
                 const float v = accP[i][j][r] * accQ[i][j][r];
-                s += (row < a.T && col < a.T) ? v : 0.f;
+                s += (row < ly.T && col < ly.T) ? v : 0.f;
             }
         }
     __syncthreads();
     s = block_sum_256(s, red);
-    if (tid == 0) a.partial[(size_t)ex * a.npairs + slot] = diag ? s : 2.0f * s;
+    if (tid == 0) a.partial[(size_t)ly.first + (size_t)ex * ly.npairs + slot] = diag ? s : 2.0f * s;
 }
 
 }  // namespace
@@ -211,18 +226,45 @@ bool gram_dma_ok(int T, int d_in, int d_out) {
     return T > 64 && (d_in % GK) == 0 && (d_out % GK) == 0 && (int64_t)T * dmax * 2 < (int64_t(1) << 31);   // 32-bit lane offsets
 }
 
-hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
+// Several layers in one launch (at most kGramBatch, every one passing gram_dma_ok); partial gets the layers' item
+// lists one after the other, in the order given, and the sums go to sqnorm in that order.
+hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
+                                       float* partial, hipStream_t st, bool f16) {
+    if (n_layers < 1 || n_layers > kGramBatch) return hipErrorInvalidValue;
     GramDmaArgs a;
-    a.A = A; a.G = G; a.partial = partial;
-    a.B = B; a.T = T; a.d_in = d_in; a.d_out = d_out;
-    a.nt = p.nt; a.npairs = p.npairs;
-    a.per_xcd = (int)(((int64_t)B * p.npairs + 7) / 8);
+    FinalizeLayers fin;
+    a.n_layers = n_layers; a.partial = partial; a.B = B;
+    fin.n_layers = n_layers;
+    int64_t first = 0, queue = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const GramPlan p = plan_gram_bf16(layers[l].T, layers[l].d_in, layers[l].d_out);
+        GramDmaLayer& y = a.layer[l];
+        y.A = layers[l].A; y.G = layers[l].G;
+        y.T = layers[l].T; y.d_in = layers[l].d_in; y.d_out = layers[l].d_out;
+        y.nt = p.nt; y.npairs = p.npairs;
+        const int64_t items = (int64_t)B * p.npairs;
+        if (first + items >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+        y.first = (int)first;
+        y.per_xcd = (int)((items + 7) / 8);
+        fin.first[l] = (int)first; fin.n[l] = p.npairs;
+        first += items;
+        queue += y.per_xcd;
+    }
+    for (int l = n_layers; l < kGramBatch; ++l) a.layer[l] = GramDmaLayer{nullptr, nullptr, 0, 0, 0, 0, 0, 0, 0};
+    if (queue * 8 >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    a.per_xcd = (int)queue;
     if (f16) k_gram_bf16_dma<true><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
     else     k_gram_bf16_dma<false><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);
+    return launch_finalize_layers(partial, fin, B, accumulate, sqnorm, st);
+}
+
+hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
+    (void)p;
+    const GramLayerDesc one{A, G, T, d_in, d_out};
+    return launch_gram_bf16_dma_layers(&one, 1, B, accumulate, sqnorm, partial, st, f16);
 }
 
 }  // namespace dpk

@@ -96,6 +96,26 @@ hipError_t launch_finalize_partials(const float* partial, int B, int n, bool acc
     return hipGetLastError();
 }
 
+// The same over the item lists of several layers (batched Gram launch), layer after layer.
+__global__ void k_finalize_layers(const float* __restrict__ partial, FinalizeLayers f, int B, int accumulate,
+                                  float* __restrict__ sqnorm) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    float s = accumulate ? sqnorm[i] : 0.f;
+    for (int l = 0; l < f.n_layers; ++l) {
+        const float* p = partial + (size_t)f.first[l] + (size_t)i * f.n[l];
+        float t = 0.f;
+        for (int j = 0; j < f.n[l]; ++j) t += p[j];
+        s += t;
+    }
+    sqnorm[i] = s;
+}
+
+hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f, int B, bool accumulate, float* sqnorm, hipStream_t st) {
+    k_finalize_layers<<<(B + 63) / 64, 64, 0, st>>>(partial, f, B, accumulate ? 1 : 0, sqnorm);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // nu_i = 1 / max(1, sqrt(s_i) / C)   (clip function of Section 3.2)
 // ---------------------------------------------------------------------------

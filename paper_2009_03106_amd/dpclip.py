@@ -22,10 +22,16 @@ DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
-EXPORTS = ("dp_layer_sqnorm", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
+EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
 
 _lib = None
+
+
+class LayerDesc(ctypes.Structure):
+    """dp_layer_desc of the header."""
+    _fields_ = [("A", ctypes.c_void_p), ("G", ctypes.c_void_p), ("T", ctypes.c_int64), ("d_in", ctypes.c_int64),
+                ("d_out", ctypes.c_int64)]
 
 
 class DpclipError(RuntimeError):
@@ -47,6 +53,10 @@ def load_library() -> ctypes.CDLL:
                                  ctypes.c_float, ctypes.c_int)
     lib.dp_layer_sqnorm.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp, sz, vp]
     lib.dp_layer_sqnorm.restype = ci
+    lib.dp_layers_sqnorm.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci, ci, vp, vp, sz, vp]
+    lib.dp_layers_sqnorm.restype = ci
+    lib.dp_layers_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci]
+    lib.dp_layers_workspace_bytes.restype = sz
     lib.dp_clip_factors.argtypes = [vp, i64, f32, vp, vp]
     lib.dp_clip_factors.restype = ci
     lib.dp_clipped_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
@@ -153,6 +163,49 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
                              _ptr(sqnorm), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                              _stream_ptr(stream))
     _check(st, "dp_layer_sqnorm")
+    return sqnorm
+
+
+def layer_descs(layers):
+    """(ctypes array of dp_layer_desc, B, dtype code) for a list of (A, G) tensor pairs sharing B and dtype.
+    The tensors must stay alive (and contiguous: the pointers are taken here) while the array is used."""
+    if len(layers) == 0:
+        raise ValueError("no layers")
+    arr = (LayerDesc * len(layers))()
+    B0, dt0 = None, None
+    for i, (A, G) in enumerate(layers):
+        if not (A.is_contiguous() and G.is_contiguous()):
+            raise ValueError("layer tensors must be contiguous")
+        A, G, B, T, d_in, d_out = _shape3(A, G)
+        dt = _dtype_code(A)
+        if B0 is None:
+            B0, dt0 = B, dt
+        elif (B, dt) != (B0, dt0):
+            raise ValueError("all layers must share the batch size and the dtype")
+        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out)
+    return arr, B0, dt0
+
+
+def layers_workspace_bytes(descs, B: int, dtype: int, path: str = "auto") -> int:
+    return int(load_library().dp_layers_workspace_bytes(descs, len(descs), B, dtype, _PATHS[path]))
+
+
+def layers_sqnorm(layers, sqnorm: Optional[torch.Tensor] = None, *, path: str = "auto", accumulate: bool = False,
+                  workspace: Optional[torch.Tensor] = None, descs=None,
+                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """sqnorm[i] (+)= sum over the (A, G) pairs of ||A_i^T G_i||_F^2 via dp_layers_sqnorm.
+    descs: the result of layer_descs(layers), to skip rebuilding it on every call."""
+    lib = load_library()
+    arr, B, dt = descs if descs is not None else layer_descs(layers)
+    dev = layers[0][0].device
+    if sqnorm is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing sqnorm tensor")
+        sqnorm = torch.empty(B, dtype=torch.float32, device=dev)
+    ws = _workspace(layers_workspace_bytes(arr, B, dt, path), dev, workspace)
+    st = lib.dp_layers_sqnorm(arr, len(arr), B, dt, _PATHS[path], int(bool(accumulate)), _ptr(sqnorm), _ptr(ws),
+                              0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
+    _check(st, "dp_layers_sqnorm")
     return sqnorm
 
 

@@ -103,6 +103,29 @@ def test_workspace_sizes_over_many_shapes(lib):
     assert g(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 0, 3, 1, 128, dpclip.DP_BF16) == 0
 
 
+def test_layers_workspace_sizes(lib):
+    """Host logic of the several-layers call: the copy-pipeline Gram layers of one launch (at most 16) have their partial
+    sums side by side, every other layer needs what dp_layer_sqnorm needs, and the two groups share the space."""
+    import ctypes
+    def descs(shapes):
+        arr = (dpclip.LayerDesc * len(shapes))()
+        for i, (T, di, do) in enumerate(shapes):
+            arr[i] = dpclip.LayerDesc(None, None, T, di, do)
+        return arr
+    f = dpclip.layers_workspace_bytes
+    tr = descs([(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)])
+    assert f(tr, 64, dpclip.DP_BF16) == 4 * 64 * 10 * 4                  # 10 pairs of 128-row tiles per example and layer
+    assert f(tr, 64, dpclip.DP_F16) == f(tr, 64, dpclip.DP_BF16)
+    assert f(tr, 64, dpclip.DP_F32) == max(dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 64, *sh, dpclip.DP_F32)
+                                            for sh in [(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)])
+    assert f(tr, 64, dpclip.DP_F32, "gram") == 0                         # unsupported combination
+    many = descs([(128, 64, 64)] * 20)
+    assert f(many, 8, dpclip.DP_BF16, "gram") == 16 * 8 * 1 * 4           # launches of 16 and 4 layers reuse the space
+    mixed = descs([(1, 64, 32), (1024, 576, 128), (0, 8, 8)])
+    assert f(mixed, 128, dpclip.DP_BF16) == (dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 128, 1024, 576, 128, dpclip.DP_BF16) + 15) // 16 * 16
+    assert f(descs([(512, 1 << 24, 64)]), 2, dpclip.DP_BF16) == 0         # width out of range
+
+
 def test_missing_library_raises(monkeypatch):
     monkeypatch.setattr(dpclip, "_lib", None)
     monkeypatch.setattr(dpclip, "LIB_PATH", "/nonexistent/libdpclip.so")

@@ -171,6 +171,78 @@ def test_fused_qkv_equals_three_projections(dp):
     assert rel_err(full, parts.cpu().numpy().astype(np.float64)) <= 1e-4
 
 
+# ----------------------------------------------------------------- several layers in one call
+def test_layers_call_on_the_transformer_configuration(dp):
+    w, layers = wl.generate("transformer")
+    s_ref = orc.total_sqnorm(layers)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    s = dp.layers_sqnorm(dev)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["bf16"]
+    one_by_one = None
+    for li, (A, G) in enumerate(dev):
+        one_by_one = dp.layer_sqnorm(A, G, one_by_one, accumulate=li > 0)
+    assert rel_err(s.cpu().numpy(), one_by_one.cpu().numpy().astype(np.float64)) <= 1e-6    # fp32 order of the layer sums
+    s2 = torch.full_like(s, 3.0)
+    dp.layers_sqnorm(dev, s2, accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 3.0) <= SQ_TIGHT["bf16"]
+    np.testing.assert_array_equal(dp.layers_sqnorm(dev).cpu().numpy(), s.cpu().numpy())      # reruns are bit-identical
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_layers_call_mixed_kinds(dp, dtype):
+    """Layers of every kind in one call: dense (T = 1), direct path, Gram path off the copy-pipeline kernel (width not a
+    multiple of 64), copy-pipeline Gram layers of different lengths and widths, and an empty layer."""
+    B = 5
+    shapes = [(1, 130, 67), (64, 576, 128), (200, 72, 264), (200, 128, 192), (128, 64, 320), (300, 256, 64), (0, 8, 8),
+              (72, 192, 128)]
+    layers = [wl.random_layer(50 + i, B, T, di, do, dtype, g_row_scale=np.exp(np.linspace(-1, 1, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    s_ref = sum(orc.layer_sqnorm(A, G) for (A, G), sh in zip(layers, shapes) if sh[0] > 0)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    s = dp.layers_sqnorm(dev)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], rel_err(s.cpu().numpy(), s_ref)
+    s2 = torch.full_like(s, 0.25)
+    dp.layers_sqnorm(dev, s2, accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.25) <= SQ_TIGHT[dtype]
+    if dtype != "f32":
+        sd = dp.layers_sqnorm(dev, path="direct")
+        assert rel_err(sd.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype]
+
+
+def test_layers_call_more_layers_than_one_launch_takes(dp):
+    B = 3
+    layers = [wl.random_layer(300 + i, B, 96 + 32 * (i % 3), 64 * (1 + i % 2), 64 * (1 + (i // 2) % 3), "bf16",
+                              g_row_scale=np.exp(np.linspace(-1, 1, B))) for i in range(19)]
+    s_ref = sum(orc.layer_sqnorm(A, G) for A, G in layers)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    s = dp.layers_sqnorm(dev, path="gram")
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["bf16"]
+
+
+def test_layers_call_empty_and_errors(dp):
+    lib = dp.load_library()
+    B = 4
+    A, G = wl.random_layer(1, B, 128, 64, 64, "bf16")
+    Ad, Gd = to_dev(A), to_dev(G)
+    s = torch.full((B,), 7.0, device="cuda")
+    empty = [(torch.zeros((B, 0, 8), dtype=torch.bfloat16, device="cuda"), torch.zeros((B, 0, 8), dtype=torch.bfloat16, device="cuda"))]
+    dp.layers_sqnorm(empty, s)                              # only empty layers: zero-filled
+    assert torch.all(s == 0)
+    s.fill_(7.0)
+    dp.layers_sqnorm(empty, s, accumulate=True)
+    assert torch.all(s == 7.0)
+    descs, _, dt = dp.layer_descs([(Ad, Gd)])
+    need = dp.layers_workspace_bytes(descs, B, dt, "gram")
+    assert need >= 4 * B
+    assert lib.dp_layers_sqnorm(descs, 1, B, dt, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_WORKSPACE
+    assert lib.dp_layers_sqnorm(descs, -1, B, dt, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_INVALID_ARG
+    assert lib.dp_layers_sqnorm(None, 1, B, dt, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_INVALID_ARG
+    assert lib.dp_layers_sqnorm(descs, 1, B, dp.DP_F32, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_UNSUPPORTED
+    assert lib.dp_layers_sqnorm(descs, 0, B, dt, dp.DP_PATH_AUTO, 0, s.data_ptr(), None, 0, None) == dp.DP_OK   # no layers: zeros
+    torch.cuda.synchronize()
+    assert torch.all(s == 0)
+
+
 # ----------------------------------------------------------------- ragged shapes and edge cases
 RAGGED = [
     # B, T, d_in, d_out
