@@ -54,8 +54,13 @@ class Pipeline:
         self.s = torch.zeros(self.B, dtype=torch.float32, device="cuda")
         self.c = torch.zeros(self.B, dtype=torch.float32, device="cuda")
         self.grads, self.ws_sq, self.ws_cg = [], [], []
-        for spec in w.layers:
-            self.grads.append(torch.zeros((spec.d_in, spec.d_out), dtype=torch.float32, device="cuda"))
+        # the layers' gradients lie one after the other in one flat buffer (the model's flat parameter gradient):
+        # the noise is then one call over the whole buffer, whose offsets are the per-layer calls' running offsets
+        sizes = [spec.d_in * spec.d_out for spec in w.layers]
+        self.flat_grad = torch.zeros(sum(sizes), dtype=torch.float32, device="cuda")
+        starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+        for li, spec in enumerate(w.layers):
+            self.grads.append(self.flat_grad[starts[li]:starts[li + 1]].view(spec.d_in, spec.d_out))
             n1 = dp.workspace_bytes(dp.DP_OP_SQNORM, self.B, spec.T, spec.d_in, spec.d_out, dt, path)
             n2 = dp.workspace_bytes(dp.DP_OP_CLIPPED_GRAD, self.B, spec.T, spec.d_in, spec.d_out, dt)
             self.ws_sq.append(torch.empty(max(n1, 16), dtype=torch.uint8, device="cuda"))
@@ -85,10 +90,7 @@ class Pipeline:
 
     def phase_noise(self):
         if self.w.noise_std > 0:
-            off = 0
-            for g in self.grads:
-                self.dp.add_noise(g, self.w.noise_std, self.w.noise_seed, off)
-                off += g.numel()
+            self.dp.add_noise(self.flat_grad, self.w.noise_std, self.w.noise_seed, 0)
 
     def step(self, events=None):
         if events is not None:

@@ -649,6 +649,26 @@ def test_pipeline_is_graph_capturable(dp):
         _ = torch.randn(1 << 18, device="cuda").sum().item()        # eager work and a synchronisation between replays
 
 
+def test_noise_over_a_flat_buffer_equals_per_layer_calls(dp):
+    """One call over the layers' gradients laid out back to back = one call per layer with running offsets
+    (the stream is indexed by offset + position), bit for bit, whatever the alignment of the pieces."""
+    sizes = [768 * 2304, 10, 3, 784 * 512 + 1, 7]
+    flat = torch.linspace(-1, 1, sum(sizes), device="cuda")
+    parts = flat.clone()
+    dp.add_noise(flat, 0.75, 20090310, 5)
+    off = 0
+    for n in sizes:
+        piece = parts[off:off + n]
+        if piece.data_ptr() % 16 == 0:
+            dp.add_noise(piece, 0.75, 20090310, 5 + off)
+        else:                                   # the entry point wants 16-byte aligned pointers: go through a copy
+            tmp = piece.clone()
+            dp.add_noise(tmp, 0.75, 20090310, 5 + off)
+            piece.copy_(tmp)
+        off += n
+    assert torch.equal(flat, parts)
+
+
 def test_philox_words_bit_exact(dp):
     for seed, first in [(0, 0), (0x0123456789ABCDEF, (1 << 32) - 1000), (20090310, (1 << 40) + 7)]:
         n = 5000
