@@ -95,10 +95,11 @@ dp_status dp_layer_sqnorm(const void* A, const void* G,
  * Layers on the Gram path whose widths are multiples of 64 (16-bit inputs,
  * T > 64) share kernel launches, up to 16 layers each: the workgroups of one
  * layer then fill the idle tail of another's, which a per-layer launch leaves
- * empty.  Every other layer is handled exactly as dp_layer_sqnorm handles it.
- * The result equals per-layer calls up to the order of the float32 additions
- * over layers (those other layers first, in the order given; then the shared
- * launches, widest layer first).
+ * empty.  Dense layers (T == 1) share launches too, 16 each.  Every other
+ * layer is handled exactly as dp_layer_sqnorm handles it.  The result equals
+ * per-layer calls up to the order of the float32 additions over layers (dense
+ * layers first, then those other layers, both in the order given; then the
+ * shared Gram launches, widest layer first).
  *   layers     HOST array of n_layers descriptors, read during the call only;
  *              A and G are device pointers as in dp_layer_sqnorm; all layers
  *              share B, dtype and path

@@ -417,10 +417,27 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
 
     int acc = accumulate != 0;
     bool launched = false;
-    // layers outside the batched Gram launch, in the order given
+    // dense layers (T = 1, closed form): up to kDenseBatch per launch, in the order given
+    DenseLayers dense;
+    dense.n_layers = 0;
+    auto flush_dense = [&]() -> hipError_t {
+        if (dense.n_layers == 0) return hipSuccess;
+        const hipError_t e = launch_sqnorm_dense_layers(dense, (int)B, (int)dtype, acc != 0, sqnorm, stream);
+        dense.n_layers = 0; acc = 1; launched = true;
+        return e;
+    };
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
-        if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;                 // adds nothing
+        if (y.T != 1 || y.d_in == 0 || y.d_out == 0) continue;
+        const int k = dense.n_layers++;
+        dense.A[k] = y.A; dense.G[k] = y.G; dense.d_in[k] = (int)y.d_in; dense.d_out[k] = (int)y.d_out;
+        if (dense.n_layers == kDenseBatch && flush_dense() != hipSuccess) return DP_ERR_HIP;
+    }
+    if (flush_dense() != hipSuccess) return DP_ERR_HIP;
+    // layers outside the batched launches, in the order given
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.T <= 1 || y.d_in == 0 || y.d_out == 0) continue;                 // empty layers add nothing
         if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
         const dp_status s1 = dp_layer_sqnorm(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes, hip_stream);
         if (s1 != DP_OK) return s1;

@@ -12,6 +12,9 @@ namespace dpk {
 // dt: 0 = float32, 1 = bf16, 2 = fp16 (the values of dp_dtype)
 hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
                                bool accumulate, float* sqnorm, hipStream_t st);
+constexpr int kDenseBatch = 16;        // dense (T = 1) layers per launch of the several-layers call
+struct DenseLayers { int n_layers; const void* A[kDenseBatch]; const void* G[kDenseBatch]; int d_in[kDenseBatch]; int d_out[kDenseBatch]; };
+hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool accumulate, float* sqnorm, hipStream_t st);
 hipError_t launch_finalize_partials(const float* partial, int B, int n_per_example, bool accumulate,
                                     float* sqnorm, hipStream_t st);
 // s_i (+)= sum over the layers l, then over j < n[l], of partial[first[l] + i * n[l] + j], in that order

@@ -67,6 +67,38 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restric
     }
 }
 
+// The same for several dense layers at once: s_i (+)= sum over the layers, in the order given, of
+// ||a_l,i||^2 ||g_l,i||^2  (one launch instead of one per layer: these layers are a few microseconds each).
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_sqnorm_dense_layers(DenseLayers t, int B, int accumulate, float* __restrict__ sqnorm) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    if (ex >= B) return;
+    float s = 0.f;
+    for (int l = 0; l < t.n_layers; ++l) {
+        const int d_in = t.d_in[l], d_out = t.d_out[l];
+        float sa, sg;
+        if (DT != 0) {
+            sa = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(t.A[l]) + (size_t)ex * d_in, d_in, lane);
+            sg = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(t.G[l]) + (size_t)ex * d_out, d_out, lane);
+        } else {
+            sa = row_sumsq_f32(static_cast<const float*>(t.A[l]) + (size_t)ex * d_in, d_in, lane);
+            sg = row_sumsq_f32(static_cast<const float*>(t.G[l]) + (size_t)ex * d_out, d_out, lane);
+        }
+        s += sa * sg;
+    }
+    if (lane == 0) sqnorm[ex] = accumulate ? sqnorm[ex] + s : s;
+}
+
+hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool accumulate, float* sqnorm, hipStream_t st) {
+    const int per_block = kThreads / kWave;
+    dim3 grid((B + per_block - 1) / per_block);
+    if (dt == 2)      k_sqnorm_dense_layers<2><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm);
+    else if (dt == 1) k_sqnorm_dense_layers<1><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm);
+    else              k_sqnorm_dense_layers<0><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm);
+    return hipGetLastError();
+}
+
 hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
                                bool accumulate, float* sqnorm, hipStream_t st) {
     const int per_block = kThreads / kWave;

@@ -11,7 +11,10 @@ namespace dpk {
 
 namespace {
 
-constexpr int FBK = 16;               // k rows per stage
+// k rows per stage: 64 where the contraction is long enough (a stage costs a global-load latency and two barriers
+// whatever its size, so short stages make the loop latency-bound), 16 for short ones (direct norm of short sequences,
+// where a 64-row stage would be mostly zero padding)
+inline int stage_rows(int64_t k) { return k >= 128 ? 64 : 16; }
 constexpr int FBM = 64, FBN = 64;     // block tile; 2 x 2 waves, one 32 x 32 MFMA tile each
 
 struct TnArgsF {
@@ -26,24 +29,13 @@ struct TnArgsF {
     int accumulate;
 };
 
-__device__ __forceinline__ float4 load4_guarded(const float* __restrict__ X, int D, bool vec_ok,
-                                                int row, int k_end, int col0) {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row >= k_end) return v;
-    const float* p = X + (size_t)row * D;
-    if (vec_ok) {
-        if (col0 < D) v = *reinterpret_cast<const float4*>(p + col0);
-    } else {
-        if (col0 + 0 < D) v.x = p[col0 + 0];
-        if (col0 + 1 < D) v.y = p[col0 + 1];
-        if (col0 + 2 < D) v.z = p[col0 + 2];
-        if (col0 + 3 < D) v.w = p[col0 + 3];
-    }
-    return v;
-}
-
-template <int MODE>
+// The loads of a stage are issued unconditionally from clamped (valid) addresses and zeroed afterwards: no branch
+// sits between them, so they are all in flight together (a guarded load costs one memory round trip each).
+// VEC: d_in and d_out are multiples of 4, so every 16-byte piece is all inside or all outside a row and is one
+// load; otherwise a piece is four 4-byte loads.
+template <int MODE, int FBK, bool VEC>
 __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
+    constexpr int NV = FBK / 16;        // float4 pieces of either operand per thread and stage
     __shared__ __attribute__((aligned(16))) float sA[FBK][FBM];
     __shared__ __attribute__((aligned(16))) float sG[FBK][FBN];
     __shared__ float red[4];
@@ -57,10 +49,16 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
     if (MODE == 0) { k_begin = z * a.kchunk; k_end = min(a.K, k_begin + a.kchunk); }
     else { k_begin = z * a.T; k_end = k_begin + a.T; }
 
-    // each thread moves one float4 of A and one of G per stage
-    const int lr = tid >> 4;            // row in stage, 0..15
-    const int lc = (tid & 15) * 4;      // column in tile
-    const bool vecA = (a.M & 3) == 0, vecG = (a.N & 3) == 0;
+    // each thread moves NV float4 of A and of G per stage: rows lr, lr + 16, ..., columns lc .. lc + 3 of the tile
+    const int lr = tid >> 4;            // 0..15
+    const int lc = (tid & 15) * 4;
+    bool okA[4], okG[4];                // the column lies inside the matrix
+    int colA[4], colG[4];               // a valid column to load from
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        okA[j] = m0 + lc + j < a.M; okG[j] = n0 + lc + j < a.N;
+        colA[j] = okA[j] ? m0 + lc + j : 0; colG[j] = okG[j] ? n0 + lc + j : 0;
+    }
 
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lhalf = lane >> 5;
@@ -68,28 +66,61 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
-    float4 va, vg;
+    float xa[NV][4], xg[NV][4];         // what fetch() loaded; scaled and zeroed in commit(), one stage of MFMAs
+    float cl[NV];                       // later, so that the loads stay in flight behind them
+    bool inr[NV];                       // the row lies inside the slice
     auto fetch = [&](int k0) {
-        const int row = k0 + lr;
-        va = load4_guarded(a.A, a.M, vecA, row, k_end, m0 + lc);
-        vg = load4_guarded(a.G, a.N, vecG, row, k_end, n0 + lc);
-        if (MODE == 0 && row < k_end) {
-            const float c = a.clip[a.T == 1 ? row : row / a.T];
-            va.x *= c; va.y *= c; va.z *= c; va.w *= c;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int row = k0 + lr + 16 * v;
+            inr[v] = row < k_end;
+            const int rc = inr[v] ? row : k_end - 1;                    // k_begin < k_end whenever a stage is fetched
+            const float* pa = a.A + (size_t)rc * a.M;
+            const float* pg = a.G + (size_t)rc * a.N;
+            if (VEC) {
+                const float4 qa = *reinterpret_cast<const float4*>(pa + colA[0]);
+                const float4 qg = *reinterpret_cast<const float4*>(pg + colG[0]);
+                xa[v][0] = qa.x; xa[v][1] = qa.y; xa[v][2] = qa.z; xa[v][3] = qa.w;
+                xg[v][0] = qg.x; xg[v][1] = qg.y; xg[v][2] = qg.z; xg[v][3] = qg.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { xa[v][j] = pa[colA[j]]; xg[v][j] = pg[colG[j]]; }
+            }
+            cl[v] = (MODE == 0) ? a.clip[a.T == 1 ? rc : rc / a.T] : 1.0f;
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            float ya[4], yg[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ya[j] = (inr[v] && okA[j]) ? xa[v][j] * cl[v] : 0.f;
+                yg[j] = (inr[v] && okG[j]) ? xg[v][j] : 0.f;
+            }
+            *reinterpret_cast<float4*>(&sA[lr + 16 * v][lc]) = make_float4(ya[0], ya[1], ya[2], ya[3]);
+            *reinterpret_cast<float4*>(&sG[lr + 16 * v][lc]) = make_float4(yg[0], yg[1], yg[2], yg[3]);
         }
     };
 
     if (k_begin < k_end) fetch(k_begin);
     for (int k0 = k_begin; k0 < k_end; k0 += FBK) {
-        *reinterpret_cast<float4*>(&sA[lr][lc]) = va;
-        *reinterpret_cast<float4*>(&sG[lr][lc]) = vg;
+        commit();
         __syncthreads();
         if (k0 + FBK < k_end) fetch(k0 + FBK);
+        // the operands of 8 MFMAs are read together, so that their LDS latency is paid once per group
 #pragma unroll
-        for (int ks = 0; ks < FBK / 2; ++ks) {
-            const float fa = sA[ks * 2 + lhalf][wm * 32 + lrow];
-            const float fb = sG[ks * 2 + lhalf][wn * 32 + lrow];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb, acc, 0, 0, 0);
+        for (int k8 = 0; k8 < FBK / 2; k8 += 8) {
+            float fa[8], fb[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                fa[j] = sA[(k8 + j) * 2 + lhalf][wm * 32 + lrow];
+                fb[j] = sG[(k8 + j) * 2 + lhalf][wn * 32 + lrow];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
     }
@@ -118,6 +149,11 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
 
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
+template <int MODE> void launch_f32(bool deep, bool vec, dim3 grid, const TnArgsF& a, hipStream_t st) {
+    if (deep) { if (vec) k_tn_f32<MODE, 64, true><<<grid, kThreads, 0, st>>>(a); else k_tn_f32<MODE, 64, false><<<grid, kThreads, 0, st>>>(a); }
+    else      { if (vec) k_tn_f32<MODE, 16, true><<<grid, kThreads, 0, st>>>(a); else k_tn_f32<MODE, 16, false><<<grid, kThreads, 0, st>>>(a); }
+}
+
 }  // namespace
 
 TnPlan plan_clipped_f32(int B, int T, int M, int N) {
@@ -127,8 +163,9 @@ TnPlan plan_clipped_f32(int B, int T, int M, int N) {
     p.tile_m = FBM; p.tile_n = FBN;
     p.tiles_m = ceil_div(M, FBM); p.tiles_n = ceil_div(N, FBN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int FBK = stage_rows(K);
     int64_t want = (512 + tiles - 1) / tiles;
-    int64_t max_splits = (K + 4 * FBK - 1) / (4 * FBK);
+    int64_t max_splits = (K + 4 * FBK - 1) / (4 * FBK);      // at least 4 stages per slice
     if (want > max_splits) want = max_splits;
     if (want < 1) want = 1;
     int64_t kchunk = (K + want - 1) / want;
@@ -160,7 +197,7 @@ hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, c
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.splits);
-    k_tn_f32<0><<<grid, kThreads, 0, st>>>(a);
+    launch_f32<0>(stage_rows(a.K) == 64, ((M | N) & 3) == 0, grid, a, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
@@ -180,7 +217,7 @@ hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, in
         a.G = G + (size_t)b0 * T * N;
         a.out = partial + (size_t)b0 * tiles;
         dim3 grid((unsigned)tiles, (unsigned)nb);
-        k_tn_f32<1><<<grid, kThreads, 0, st>>>(a);
+        launch_f32<1>(stage_rows(T) == 64, ((M | N) & 3) == 0, grid, a, st);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -209,6 +209,21 @@ def test_layers_call_mixed_kinds(dp, dtype):
         assert rel_err(sd.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_layers_call_dense_layers(dp, dtype):
+    """Dense layers share a launch: the MLP configuration's three layers, and 19 layers (two launches)."""
+    w, layers = wl.generate("mlp", dtype=dtype)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    s = dp.layers_sqnorm(dev)
+    assert rel_err(s.cpu().numpy(), orc.total_sqnorm(layers)) <= SQ_TIGHT[dtype]
+    B = 7
+    many = [wl.random_layer(800 + i, B, 1, 8 + 13 * i, 5 + 7 * (i % 4), dtype, g_row_scale=np.exp(np.linspace(-1, 1, B))) for i in range(19)]
+    s_ref = sum(orc.layer_sqnorm(A, G) for A, G in many)
+    s2 = torch.full((B,), 0.5, device="cuda")
+    dp.layers_sqnorm([(to_dev(A), to_dev(G)) for A, G in many], s2, accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
+
+
 def test_layers_call_more_layers_than_one_launch_takes(dp):
     B = 3
     layers = [wl.random_layer(300 + i, B, 96 + 32 * (i % 3), 64 * (1 + i % 2), 64 * (1 + (i // 2) % 3), "bf16",
