@@ -106,9 +106,17 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
+# torch's raw handle of the current stream: building a torch.cuda.Stream object for it costs about 3 us per call,
+# as much as the library call itself
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
-    s = torch.cuda.current_stream() if stream is None else stream
-    return int(s.cuda_stream)
+    if stream is not None:
+        return int(stream.cuda_stream)
+    if _raw_stream is not None:
+        return int(_raw_stream(torch.cuda.current_device()))
+    return int(torch.cuda.current_stream().cuda_stream)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
@@ -139,12 +147,14 @@ def workspace_bytes(op: int, B: int, T: int, d_in: int, d_out: int, dtype: int, 
     return int(load_library().dp_workspace_bytes(op, B, T, d_in, d_out, dtype, _PATHS[path]))
 
 
-def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
-    if nbytes == 0:
-        return workspace
+def _workspace(nbytes, device, workspace: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    """The caller's workspace if there is one (the library checks its size), else a fresh one of nbytes() bytes."""
     if workspace is not None:
         return workspace
-    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    n = nbytes()
+    if n == 0:
+        return None
+    return torch.empty(n, dtype=torch.uint8, device=device)
 
 
 def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor] = None, *,
@@ -158,7 +168,7 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
         if accumulate:
             raise ValueError("accumulate needs an existing sqnorm tensor")
         sqnorm = torch.empty(B, dtype=torch.float32, device=A.device)
-    ws = _workspace(workspace_bytes(DP_OP_SQNORM, B, T, d_in, d_out, dt, path), A.device, workspace)
+    ws = _workspace(lambda: workspace_bytes(DP_OP_SQNORM, B, T, d_in, d_out, dt, path), A.device, workspace)
     st = lib.dp_layer_sqnorm(_ptr(A), _ptr(G), B, T, d_in, d_out, dt, _PATHS[path], int(bool(accumulate)),
                              _ptr(sqnorm), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                              _stream_ptr(stream))
@@ -202,7 +212,7 @@ def layers_sqnorm(layers, sqnorm: Optional[torch.Tensor] = None, *, path: str = 
         if accumulate:
             raise ValueError("accumulate needs an existing sqnorm tensor")
         sqnorm = torch.empty(B, dtype=torch.float32, device=dev)
-    ws = _workspace(layers_workspace_bytes(arr, B, dt, path), dev, workspace)
+    ws = _workspace(lambda: layers_workspace_bytes(arr, B, dt, path), dev, workspace)
     st = lib.dp_layers_sqnorm(arr, len(arr), B, dt, _PATHS[path], int(bool(accumulate)), _ptr(sqnorm), _ptr(ws),
                               0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
     _check(st, "dp_layers_sqnorm")
@@ -231,7 +241,7 @@ def clipped_grad(A: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, grad: Opt
         if accumulate:
             raise ValueError("accumulate needs an existing grad tensor")
         grad = torch.empty((d_in, d_out), dtype=torch.float32, device=A.device)
-    ws = _workspace(workspace_bytes(DP_OP_CLIPPED_GRAD, B, T, d_in, d_out, dt), A.device, workspace)
+    ws = _workspace(lambda: workspace_bytes(DP_OP_CLIPPED_GRAD, B, T, d_in, d_out, dt), A.device, workspace)
     st = lib.dp_clipped_grad(_ptr(A), _ptr(G), _ptr(clip), B, T, d_in, d_out, dt, int(bool(accumulate)),
                              _ptr(grad), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                              _stream_ptr(stream))
@@ -327,7 +337,7 @@ def conv_sqnorm(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int, sq
         if accumulate:
             raise ValueError("accumulate needs an existing sqnorm tensor")
         sqnorm = torch.empty(B, dtype=torch.float32, device=X.device)
-    ws = _workspace(conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
+    ws = _workspace(lambda: conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
     st = lib.dp_conv_sqnorm(_ptr(X), _ptr(G), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)), _ptr(sqnorm),
                             _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
     _check(st, "dp_conv_sqnorm")
@@ -345,7 +355,7 @@ def conv_clipped_grad(X: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, KH: 
         if accumulate:
             raise ValueError("accumulate needs an existing grad tensor")
         grad = torch.empty((KH * KW * C, d_out), dtype=torch.float32, device=X.device)
-    ws = _workspace(conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
+    ws = _workspace(lambda: conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
     st = lib.dp_conv_clipped_grad(_ptr(X), _ptr(G), _ptr(clip), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)),
                                   _ptr(grad), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                   _stream_ptr(stream))
