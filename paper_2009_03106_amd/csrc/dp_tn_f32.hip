@@ -147,7 +147,115 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
     }
 }
 
+// Clipped sum over a short contraction (dense layers: K = B, a few hundred rows): 32 x 32 output tile per workgroup,
+// the four waves split the rows of every 64-row stage between them (wave w: rows 16 w .. 16 w + 15) and their four
+// partial tiles are added through LDS in the order w = 0 .. 3.  The fp32 MFMA is a chain of dependent 64-cycle
+// instructions per wave, so the 64 x 64 kernel above, one wave per 32 x 32 tile, needs K / 2 of them in a row and
+// fills only (d_in / 64)(d_out / 64) compute units; here a wave runs K / 8 and there are four times as many
+// workgroups.  No K slices: the whole sum is finished in the kernel.
+constexpr int SBK = 64, STM = 32, STN = 32;
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) {
+    constexpr int NV = 2;               // float4 pieces of either operand per thread and stage
+    __shared__ __attribute__((aligned(16))) float sA[SBK][STM];
+    __shared__ __attribute__((aligned(16))) float sG[SBK][STN];
+    __shared__ __attribute__((aligned(16))) float part[4][STM][STN + 1];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = blockIdx.x;
+    const int tm = tile / a.tiles_n, tn = tile % a.tiles_n;
+    const int m0 = tm * STM, n0 = tn * STN;
+    const int k_end = a.K;
+
+    // each thread moves NV float4 of A and of G per stage: rows lr, lr + 32, columns lc .. lc + 3 of the tile
+    const int lr = tid >> 3;            // 0..31
+    const int lc = (tid & 7) * 4;
+    bool okA[4], okG[4];
+    int colA[4], colG[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        okA[j] = m0 + lc + j < a.M; okG[j] = n0 + lc + j < a.N;
+        colA[j] = okA[j] ? m0 + lc + j : 0; colG[j] = okG[j] ? n0 + lc + j : 0;
+    }
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    float xa[NV][4], xg[NV][4], cl[NV];
+    bool inr[NV];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int row = k0 + lr + 32 * v;
+            inr[v] = row < k_end;
+            const int rc = inr[v] ? row : k_end - 1;
+            const float* pa = a.A + (size_t)rc * a.M;
+            const float* pg = a.G + (size_t)rc * a.N;
+            if (VEC) {
+                const float4 qa = *reinterpret_cast<const float4*>(pa + colA[0]);
+                const float4 qg = *reinterpret_cast<const float4*>(pg + colG[0]);
+                xa[v][0] = qa.x; xa[v][1] = qa.y; xa[v][2] = qa.z; xa[v][3] = qa.w;
+                xg[v][0] = qg.x; xg[v][1] = qg.y; xg[v][2] = qg.z; xg[v][3] = qg.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { xa[v][j] = pa[colA[j]]; xg[v][j] = pg[colG[j]]; }
+            }
+            cl[v] = a.clip[a.T == 1 ? rc : rc / a.T];
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            float ya[4], yg[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ya[j] = (inr[v] && okA[j]) ? xa[v][j] * cl[v] : 0.f;
+                yg[j] = (inr[v] && okG[j]) ? xg[v][j] : 0.f;
+            }
+            *reinterpret_cast<float4*>(&sA[lr + 32 * v][lc]) = make_float4(ya[0], ya[1], ya[2], ya[3]);
+            *reinterpret_cast<float4*>(&sG[lr + 32 * v][lc]) = make_float4(yg[0], yg[1], yg[2], yg[3]);
+        }
+    };
+
+    if (k_end > 0) fetch(0);
+    for (int k0 = 0; k0 < k_end; k0 += SBK) {
+        commit();
+        __syncthreads();
+        if (k0 + SBK < k_end) fetch(k0 + SBK);
+        float fa[8], fb[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            fa[j] = sA[wave * 16 + j * 2 + lhalf][lrow];
+            fb[j] = sG[wave * 16 + j * 2 + lhalf][lrow];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], acc, 0, 0, 0);
+        __syncthreads();
+    }
+
+    // accumulator element r of a lane: row 8 (r / 4) + 4 lhalf + r % 4, column lrow of the 32 x 32 tile
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave][8 * (r >> 2) + 4 * lhalf + (r & 3)][lrow] = acc[r];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int idx = tid + 256 * e;              // 1024 outputs, 4 per thread; consecutive threads: consecutive columns
+        const int mr = idx >> 5, nc = idx & 31;
+        const int m = m0 + mr, n = n0 + nc;
+        if (m < a.M && n < a.N) {
+            const float v = ((part[0][mr][nc] + part[1][mr][nc]) + part[2][mr][nc]) + part[3][mr][nc];
+            float* p = a.out + (size_t)m * a.N + n;
+            *p = a.accumulate ? *p + v : v;
+        }
+    }
+}
+
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// the short-contraction kernel takes K up to this many rows
+constexpr int kShortK = 512;
 
 template <int MODE> void launch_f32(bool deep, bool vec, dim3 grid, const TnArgsF& a, hipStream_t st) {
     if (deep) { if (vec) k_tn_f32<MODE, 64, true><<<grid, kThreads, 0, st>>>(a); else k_tn_f32<MODE, 64, false><<<grid, kThreads, 0, st>>>(a); }
@@ -160,6 +268,12 @@ TnPlan plan_clipped_f32(int B, int T, int M, int N) {
     const int64_t K = (int64_t)B * T;
     TnPlan p;
     p.segmented = false; p.epu = 0; p.big = false; p.dma = false;
+    if (K <= kShortK) {
+        p.tile_m = STM; p.tile_n = STN;
+        p.tiles_m = ceil_div(M, STM); p.tiles_n = ceil_div(N, STN);
+        p.splits = 1; p.kchunk = (int)K;
+        return p;
+    }
     p.tile_m = FBM; p.tile_n = FBN;
     p.tiles_m = ceil_div(M, FBM); p.tiles_n = ceil_div(N, FBN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
@@ -196,6 +310,13 @@ hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, c
     const int64_t n = (int64_t)M * N;
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
+    if (p.tile_m == STM) {
+        a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0;
+        const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n);
+        if (((M | N) & 3) == 0) k_tn_f32_short<true><<<tiles, kThreads, 0, st>>>(a);
+        else                    k_tn_f32_short<false><<<tiles, kThreads, 0, st>>>(a);
+        return hipGetLastError();
+    }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.splits);
     launch_f32<0>(stage_rows(a.K) == 64, ((M | N) & 3) == 0, grid, a, st);
     hipError_t e = hipGetLastError();
