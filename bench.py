@@ -66,6 +66,10 @@ class Pipeline:
             self.ws_sq.append(torch.empty(max(n1, 16), dtype=torch.uint8, device="cuda"))
             self.ws_cg.append(torch.empty(max(n2, 16), dtype=torch.uint8, device="cuda"))
         self.descs = dp.layer_descs(self.dev)
+        order = sorted(range(len(self.dev)), key=lambda li: self.dev[li][0].shape[2] + self.dev[li][1].shape[2])
+        self.dev_cg = [self.dev[li] for li in order]
+        self.descs_cg = dp.layer_descs(self.dev_cg, [self.grads[li] for li in order])
+        self.ws_cg_all = torch.empty(max(16, dp.layers_clipped_workspace_bytes(self.descs_cg[0], self.B, dt)), dtype=torch.uint8, device="cuda")
         self.ws_layers = torch.empty(max(16, dp.layers_workspace_bytes(self.descs[0], self.B, dt, path)), dtype=torch.uint8, device="cuda")
 
     def phase_sqnorm(self):
@@ -83,8 +87,10 @@ class Pipeline:
         # the layers that the norm phase read last first: their inputs are the likeliest to be still in the
         # Infinity Cache (the several-layers call runs the widest layers first, a single call per layer runs them
         # in the order given)
-        order = sorted(range(len(self.dev)), key=lambda li: self.dev[li][0].shape[2] + self.dev[li][1].shape[2])
-        for li in order:
+        if len(self.dev) > 1:
+            self.dp.layers_clipped_grad(self.dev_cg, self.c, workspace=self.ws_cg_all, descs=self.descs_cg)
+            return
+        for li in range(len(self.dev)):
             A, G = self.dev[li]
             self.dp.clipped_grad(A, G, self.c, self.grads[li], workspace=self.ws_cg[li])
 

@@ -109,6 +109,7 @@ typedef struct {
     const void* A;              /* device, [B, T, d_in] */
     const void* G;              /* device, [B, T, d_out] */
     int64_t T, d_in, d_out;
+    float* grad;                /* device, float32[d_in, d_out]: dp_layers_clipped_grad only */
 } dp_layer_desc;
 
 dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
@@ -118,6 +119,21 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
 
 size_t dp_layers_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
                                  dp_dtype dtype, dp_path path);
+
+/* dp_clipped_grad for several layers in one call, in the order given:
+ *     layers[l].grad = (accumulate ? layers[l].grad : 0) + sum_i clip[i] * A_l,i^T G_l,i.
+ * Same kernels and same results, bit for bit, as one dp_clipped_grad call per
+ * layer; what it saves is the caller's per-call cost, which is what bounds
+ * models made of many small layers.  The layers run one after the other on
+ * the stream and share the workspace:
+ *   workspace  device scratch of at least dp_layers_clipped_workspace_bytes(...)
+ *              bytes (the largest single layer's need). */
+dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
+                                 const float* clip, dp_dtype dtype, int accumulate,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
+                                         dp_dtype dtype);
 
 /* Clip factors (Algorithm 1, the line defining nu_i; Eq. per_example_weight;
  * clip function of Section 3.2):

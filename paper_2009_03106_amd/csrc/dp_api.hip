@@ -472,4 +472,37 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
     return DP_OK;
 }
 
+size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype) {
+    if (check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, false) != DP_OK) return 0;
+    size_t need = 0;
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, layers[l].T, layers[l].d_in, layers[l].d_out, dtype, DP_PATH_AUTO);
+        if (n > need) need = n;
+    }
+    return round16(need);
+}
+
+dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, int64_t B, const float* clip, dp_dtype dtype,
+                                 int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    // everything is checked before the first launch: an error leaves every output untouched
+    const dp_status st = check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, true);
+    if (st != DP_OK) return st;
+    size_t need = 0;
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.d_in > 0 && y.d_out > 0 && (!y.grad || !aligned16(y.grad))) return DP_ERR_INVALID_ARG;
+        const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
+        if (n > need) need = n;
+    }
+    if (B > 0 && n_layers > 0 && !clip) return DP_ERR_INVALID_ARG;
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        const dp_status s1 = dp_clipped_grad(y.A, y.G, clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
+                                             workspace_bytes, hip_stream);
+        if (s1 != DP_OK) return s1;
+    }
+    return DP_OK;
+}
+
 }  // extern "C"

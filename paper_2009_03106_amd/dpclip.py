@@ -22,7 +22,8 @@ DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
-EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
+EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
+           "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
 
 _lib = None
@@ -31,7 +32,7 @@ _lib = None
 class LayerDesc(ctypes.Structure):
     """dp_layer_desc of the header."""
     _fields_ = [("A", ctypes.c_void_p), ("G", ctypes.c_void_p), ("T", ctypes.c_int64), ("d_in", ctypes.c_int64),
-                ("d_out", ctypes.c_int64)]
+                ("d_out", ctypes.c_int64), ("grad", ctypes.c_void_p)]
 
 
 class DpclipError(RuntimeError):
@@ -57,6 +58,10 @@ def load_library() -> ctypes.CDLL:
     lib.dp_layers_sqnorm.restype = ci
     lib.dp_layers_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci]
     lib.dp_layers_workspace_bytes.restype = sz
+    lib.dp_layers_clipped_grad.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, vp, ci, ci, vp, sz, vp]
+    lib.dp_layers_clipped_grad.restype = ci
+    lib.dp_layers_clipped_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci]
+    lib.dp_layers_clipped_workspace_bytes.restype = sz
     lib.dp_clip_factors.argtypes = [vp, i64, f32, vp, vp]
     lib.dp_clip_factors.restype = ci
     lib.dp_clipped_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
@@ -176,11 +181,14 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
     return sqnorm
 
 
-def layer_descs(layers):
-    """(ctypes array of dp_layer_desc, B, dtype code) for a list of (A, G) tensor pairs sharing B and dtype.
+def layer_descs(layers, grads=None):
+    """(ctypes array of dp_layer_desc, B, dtype code) for a list of (A, G) tensor pairs sharing B and dtype, with
+    the float32 [d_in, d_out] output of each layer if grads is given (layers_clipped_grad needs them).
     The tensors must stay alive (and contiguous: the pointers are taken here) while the array is used."""
     if len(layers) == 0:
         raise ValueError("no layers")
+    if grads is not None and len(grads) != len(layers):
+        raise ValueError("one gradient tensor per layer")
     arr = (LayerDesc * len(layers))()
     B0, dt0 = None, None
     for i, (A, G) in enumerate(layers):
@@ -192,7 +200,13 @@ def layer_descs(layers):
             B0, dt0 = B, dt
         elif (B, dt) != (B0, dt0):
             raise ValueError("all layers must share the batch size and the dtype")
-        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out)
+        gp = None
+        if grads is not None:
+            g = grads[i]
+            if g.dtype != torch.float32 or tuple(g.shape) != (d_in, d_out):
+                raise ValueError("gradients must be float32 [d_in, d_out]")
+            gp = _ptr(g)
+        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp)
     return arr, B0, dt0
 
 
@@ -217,6 +231,30 @@ def layers_sqnorm(layers, sqnorm: Optional[torch.Tensor] = None, *, path: str = 
                               0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
     _check(st, "dp_layers_sqnorm")
     return sqnorm
+
+
+def layers_clipped_workspace_bytes(descs, B: int, dtype: int) -> int:
+    return int(load_library().dp_layers_clipped_workspace_bytes(descs, len(descs), B, dtype))
+
+
+def layers_clipped_grad(layers, clip: torch.Tensor, grads=None, *, accumulate: bool = False,
+                        workspace: Optional[torch.Tensor] = None, descs=None,
+                        stream: Optional[torch.cuda.Stream] = None):
+    """grads[l] (+)= sum_i clip[i] A_l,i^T G_l,i for every (A, G) pair via dp_layers_clipped_grad; returns grads.
+    descs: the result of layer_descs(layers, grads), to skip rebuilding it on every call."""
+    lib = load_library()
+    if descs is None:
+        if grads is None:
+            if accumulate:
+                raise ValueError("accumulate needs existing gradient tensors")
+            grads = [torch.empty((A.shape[-1], G.shape[-1]), dtype=torch.float32, device=A.device) for A, G in layers]
+        descs = layer_descs(layers, grads)
+    arr, B, dt = descs
+    ws = _workspace(lambda: layers_clipped_workspace_bytes(arr, B, dt), layers[0][0].device, workspace)
+    st = lib.dp_layers_clipped_grad(arr, len(arr), B, _ptr(clip), dt, int(bool(accumulate)), _ptr(ws),
+                                    0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
+    _check(st, "dp_layers_clipped_grad")
+    return grads
 
 
 def clip_factors(sqnorm: torch.Tensor, C: float, clip: Optional[torch.Tensor] = None, *,

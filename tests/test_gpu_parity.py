@@ -224,6 +224,35 @@ def test_layers_call_dense_layers(dp, dtype):
     assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
 
 
+@pytest.mark.parametrize("name,B", [("mlp", None), ("transformer", 6), ("rnn", None)])
+def test_layers_clipped_grad_equals_per_layer_calls(dp, name, B):
+    w, layers = wl.generate(name, B=B, straddle=True)
+    s_ref = orc.total_sqnorm(layers)
+    c_ref = orc.clip_factors(s_ref, w.C)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    c = to_dev(c_ref.astype(np.float32))
+    grads = dp.layers_clipped_grad(dev, c)
+    for (A, G), (An, Gn), g in zip(dev, layers, grads):
+        np.testing.assert_array_equal(g.cpu().numpy(), dp.clipped_grad(A, G, c).cpu().numpy())      # same kernels, same order
+        assert fro_err(g.cpu().numpy(), orc.clipped_grad(An, Gn, c_ref)) <= FRO_TOL[w.dtype]
+    again = [torch.full_like(g, 2.0) for g in grads]
+    dp.layers_clipped_grad(dev, c, again, accumulate=True)
+    for g, h in zip(grads, again):
+        np.testing.assert_array_equal(h.cpu().numpy(), g.cpu().numpy() + np.float32(2.0))     # one fp32 addition per element
+    # errors: checked for all layers before anything is launched
+    lib = dp.load_library()
+    keep = [torch.full_like(g, 5.0) for g in grads]
+    descs, Bn, dt = dp.layer_descs(dev, keep)
+    need = dp.layers_clipped_workspace_bytes(descs, Bn, dt)
+    if need > 0:
+        assert lib.dp_layers_clipped_grad(descs, len(descs), Bn, c.data_ptr(), dt, 0, None, 0, None) == dp.DP_ERR_WORKSPACE
+    descs[len(descs) - 1].grad = None
+    ws = torch.empty(max(16, need), dtype=torch.uint8, device="cuda")
+    assert lib.dp_layers_clipped_grad(descs, len(descs), Bn, c.data_ptr(), dt, 0, ws.data_ptr(), ws.numel(), None) == dp.DP_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert all(torch.all(k == 5.0) for k in keep)
+
+
 def test_layers_call_more_layers_than_one_launch_takes(dp):
     B = 3
     layers = [wl.random_layer(300 + i, B, 96 + 32 * (i % 3), 64 * (1 + i % 2), 64 * (1 + (i // 2) % 3), "bf16",
