@@ -693,6 +693,51 @@ def test_pipeline_is_graph_capturable(dp):
         _ = torch.randn(1 << 18, device="cuda").sum().item()        # eager work and a synchronisation between replays
 
 
+@pytest.mark.parametrize("name,B", [("transformer", 3), ("mlp", None)])
+def test_several_layers_calls_are_graph_capturable(dp, name, B):
+    """The same for a step made of the several-layers calls (their host-side descriptor arrays are read during the
+    call only, and the per-layer tables travel as kernel arguments) and one noise call over the flat gradient."""
+    w, layers = wl.generate(name, B=B)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    Bn = dev[0][0].shape[0]
+    s = torch.zeros(Bn, device="cuda")
+    c = torch.zeros(Bn, device="cuda")
+    sizes = [A.shape[-1] * G.shape[-1] for A, G in dev]
+    flat = torch.zeros(sum(sizes), device="cuda")
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    grads = [flat[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)]
+    d1 = dp.layer_descs(dev)
+    d2 = dp.layer_descs(dev, grads)
+    ws1 = torch.empty(max(16, dp.layers_workspace_bytes(d1[0], Bn, d1[2])), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(max(16, dp.layers_clipped_workspace_bytes(d2[0], Bn, d2[2])), dtype=torch.uint8, device="cuda")
+
+    def step():
+        dp.layers_sqnorm(dev, s, workspace=ws1, descs=d1)
+        dp.clip_factors(s, w.C, c)
+        dp.layers_clipped_grad(dev, c, workspace=ws2, descs=d2)
+        dp.add_noise(flat, 0.5, 99, 0)
+
+    step()
+    torch.cuda.synchronize()
+    want = [s.clone(), c.clone(), flat.clone()]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (s, c, flat):
+            t.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((s, c, flat), want):
+            assert torch.equal(got, ref), rep
+        _ = torch.randn(1 << 18, device="cuda").sum().item()
+
+
 def test_noise_over_a_flat_buffer_equals_per_layer_calls(dp):
     """One call over the layers' gradients laid out back to back = one call per layer with running offsets
     (the stream is indexed by offset + position), bit for bit, whatever the alignment of the pieces."""
