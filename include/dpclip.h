@@ -82,7 +82,7 @@ typedef enum { DP_OP_SQNORM = 0, DP_OP_CLIPPED_GRAD = 1 } dp_op;
  *   sqnorm     device, float32[B], written (read first if accumulate)
  *   workspace  device scratch of at least dp_workspace_bytes(DP_OP_SQNORM, ...)
  *              bytes; may be NULL when that size is 0 (T == 1)
- * DP_PATH_GRAM with DP_F32 inputs is DP_ERR_UNSUPPORTED (AUTO then takes DIRECT). */
+ * Both paths exist for every input type. */
 dp_status dp_layer_sqnorm(const void* A, const void* G,
                           int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                           dp_dtype dtype, dp_path path, int accumulate,

@@ -26,15 +26,15 @@ dp_status check_dims(int64_t B, int64_t T, int64_t d_in, int64_t d_out) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 dp_path resolve_path(dp_path path, dp_dtype dtype, int64_t T, int64_t d_in, int64_t d_out) {
+    (void)dtype;
     if (path != DP_PATH_AUTO) return path;
-    if (dtype == DP_F32) return DP_PATH_DIRECT;
     return dp_choose_path(T, d_in, d_out);
 }
 
 // bytes of scratch for the squared-norm call on an already resolved path (T > 1)
 size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
     if (path == DP_PATH_GRAM) {
-        GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
+        GramPlan g = is16(dtype) ? plan_gram_bf16((int)T, (int)d_in, (int)d_out) : plan_gram_f32((int)T);
         return (size_t)B * g.npairs * sizeof(float);
     }
     TnPlan p = is16(dtype) ? plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out)
@@ -106,7 +106,6 @@ size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t 
     if (op == DP_OP_SQNORM) {
         if (T == 1) return 0;
         const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
-        if (p == DP_PATH_GRAM && !is16(dtype)) return 0;
         return sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
     }
     if (op == DP_OP_CLIPPED_GRAD) return clipped_ws_bytes(B, T, d_in, d_out, dtype);
@@ -134,13 +133,15 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
         return e == hipSuccess ? DP_OK : DP_ERR_HIP;
     }
     const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
-    if (p == DP_PATH_GRAM && !is16(dtype)) return DP_ERR_UNSUPPORTED;
     const size_t need = sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;           // > 2^31 partial sums
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
     float* partial = static_cast<float*>(workspace);
 
-    if (p == DP_PATH_GRAM) {
+    if (p == DP_PATH_GRAM && !is16(dtype)) {
+        e = launch_gram_f32(plan_gram_f32((int)T), static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
+                            (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
+    } else if (p == DP_PATH_GRAM) {
         GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
         e = launch_gram_bf16(g, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
                              (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16);
@@ -369,7 +370,6 @@ dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
         if (st != DP_OK) return st;
         if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (pointers && (!y.A || !y.G || !aligned16(y.A) || !aligned16(y.G))) return DP_ERR_INVALID_ARG;
-        if (y.T > 1 && !is16(dtype) && resolve_path(path, dtype, y.T, y.d_in, y.d_out) == DP_PATH_GRAM) return DP_ERR_UNSUPPORTED;
     }
     return DP_OK;
 }

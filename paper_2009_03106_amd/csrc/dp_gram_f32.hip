@@ -1,0 +1,157 @@
+// Gram path of the per-example squared norm for float32 inputs:
+//     ||A_i^T G_i||_F^2 = sum_{t,s} (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}.
+// Same decomposition as the 16-bit Gram kernels: one workgroup per example and
+// pair of row tiles (t-tile <= s-tile, 64 rows each), the tile of A_i A_i^T
+// (contraction over d_in) and then the tile of G_i G_i^T (contraction over
+// d_out) kept in MFMA accumulators of identical layout, multiplied lane by lane
+// and reduced; off-diagonal pairs count twice.  The matrix instruction is the
+// fp32 one (v_mfma_f32_32x32x2_f32: one k per lane and instruction, lanes 0-31
+// take k, lanes 32-63 take k + 1), so a lane reads its operands straight from the
+// row-major LDS tiles; the rows are padded to 33 floats, which puts the 32 rows
+// that one read touches into 32 different banks.
+#include "dp_common.h"
+#include "dp_internal.h"
+
+namespace dpk {
+
+namespace {
+
+constexpr int FT = 64;        // rows of T per tile
+constexpr int FK = 32;        // contraction elements per LDS stage
+constexpr int FP = FK + 1;    // padded row length in LDS
+
+struct GramArgsF {
+    const float* A;
+    const float* G;
+    float* partial;      // [B][npairs]
+    int T, d_in, d_out;
+    int nt, npairs;
+};
+
+// One Gram product tile: acc += X[t-tile rows] . X[s-tile rows]^T over the D columns of X_i[T, D].
+// VEC: D % 4 == 0 (every 16-byte piece lies inside a row or outside it).
+template <bool VEC>
+__device__ __forceinline__ void gram_product_f32(const float* __restrict__ Xi, int T, int D, int t0, int s0, bool diag,
+                                                 float (*sT)[FP], float (*sS)[FP], f32x16& acc) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    // global -> LDS: a thread moves two 4-column pieces of either tile per stage (rows lr and lr + 32)
+    const int lr = tid >> 3, lc = (tid & 7) * 4;
+    float xt[2][4], xs[2][4];
+    bool in_t[2], in_s[2];
+    // loads are issued from clamped (valid) addresses and zeroed when they are committed, one stage of MFMAs
+    // later, so that nothing waits for them in between
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            const int rt = t0 + lr + 32 * v, rs = s0 + lr + 32 * v;
+            in_t[v] = rt < T; in_s[v] = rs < T;
+            const float* pt = Xi + (size_t)(in_t[v] ? rt : T - 1) * D;
+            const float* ps = Xi + (size_t)(in_s[v] ? rs : T - 1) * D;
+            if (VEC) {
+                const int c = (k0 + lc < D) ? k0 + lc : 0;
+                const float4 q = *reinterpret_cast<const float4*>(pt + c);
+                xt[v][0] = q.x; xt[v][1] = q.y; xt[v][2] = q.z; xt[v][3] = q.w;
+                if (!diag) {
+                    const float4 r = *reinterpret_cast<const float4*>(ps + c);
+                    xs[v][0] = r.x; xs[v][1] = r.y; xs[v][2] = r.z; xs[v][3] = r.w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = (k0 + lc + j < D) ? k0 + lc + j : 0;
+                    xt[v][j] = pt[c];
+                    if (!diag) xs[v][j] = ps[c];
+                }
+            }
+        }
+    };
+    auto commit = [&](int k0) {
+#pragma unroll
+        for (int v = 0; v < 2; ++v)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool col_ok = k0 + lc + j < D;
+                sT[lr + 32 * v][lc + j] = (in_t[v] && col_ok) ? xt[v][j] : 0.f;
+                if (!diag) sS[lr + 32 * v][lc + j] = (in_s[v] && col_ok) ? xs[v][j] : 0.f;
+            }
+    };
+    float (*sB)[FP] = diag ? sT : sS;
+    if (D > 0) fetch(0);
+    for (int k0 = 0; k0 < D; k0 += FK) {
+        commit(k0);
+        __syncthreads();
+        if (k0 + FK < D) fetch(k0 + FK);
+        // the operands of 8 MFMAs are read together, so that their LDS latency is paid once per group
+#pragma unroll
+        for (int k8 = 0; k8 < FK / 2; k8 += 8) {
+            float fa[8], fb[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                fa[j] = sT[wm * 32 + lrow][(k8 + j) * 2 + lhalf];
+                fb[j] = sB[wn * 32 + lrow][(k8 + j) * 2 + lhalf];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+    }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void k_gram_f32(GramArgsF a) {
+    __shared__ float sT[FT][FP];
+    __shared__ float sS[FT][FP];
+    __shared__ float red[4];
+
+    const int ex = blockIdx.x / a.npairs;
+    int pair = blockIdx.x - ex * a.npairs;
+    // pair -> (tt, ss), tt <= ss, rows of the upper triangle in order
+    int tt = 0;
+    while (pair >= a.nt - tt) { pair -= a.nt - tt; ++tt; }
+    const int ss = tt + pair;
+    const bool diag = (tt == ss);
+
+    f32x16 accP, accQ;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { accP[r] = 0.f; accQ[r] = 0.f; }
+    gram_product_f32<VEC>(a.A + (size_t)ex * a.T * a.d_in, a.T, a.d_in, tt * FT, ss * FT, diag, sT, sS, accP);
+    gram_product_f32<VEC>(a.G + (size_t)ex * a.T * a.d_out, a.T, a.d_out, tt * FT, ss * FT, diag, sT, sS, accQ);
+
+    // rows beyond T were stored as zeros, so their entries of both tiles are zero
+    float s = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += accP[r] * accQ[r];
+    s = block_sum_256(s, red);
+    if (threadIdx.x == 0) a.partial[blockIdx.x] = diag ? s : 2.0f * s;
+}
+
+}  // namespace
+
+GramPlan plan_gram_f32(int T) {
+    GramPlan p;
+    p.tile = FT;
+    p.nt = (T + FT - 1) / FT;
+    p.npairs = p.nt * (p.nt + 1) / 2;
+    return p;
+}
+
+hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, int B, int T, int d_in, int d_out,
+                           bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+    GramArgsF a;
+    a.A = A; a.G = G; a.partial = partial;
+    a.T = T; a.d_in = d_in; a.d_out = d_out;
+    a.nt = p.nt; a.npairs = p.npairs;
+    const int64_t grid = (int64_t)B * p.npairs;
+    if (grid >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    if (((d_in | d_out) & 3) == 0) k_gram_f32<true><<<(unsigned)grid, kThreads, 0, st>>>(a);
+    else                           k_gram_f32<false><<<(unsigned)grid, kThreads, 0, st>>>(a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);
+}
+
+}  // namespace dpk

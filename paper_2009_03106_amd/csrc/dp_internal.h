@@ -91,6 +91,10 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
                                        float* partial, hipStream_t st, bool f16);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
                                 bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
+// float32 inputs (dp_gram_f32.hip): 64-row tiles
+GramPlan plan_gram_f32(int T);
+hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, int B, int T, int d_in, int d_out,
+                           bool accumulate, float* sqnorm, float* partial, hipStream_t st);
 hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
                             bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
 

@@ -79,7 +79,7 @@ def test_workspace_sizes_over_many_shapes(lib):
             for path in ("auto", "gram", "direct"):
                 n = f(dpclip.DP_OP_SQNORM, B, T, di, do, dt, path)
                 assert n >= 0 and n % 4 == 0 and n < (1 << 40), (B, T, di, do, dt, path, n)
-                if T > 1 and not (path == "gram" and dt == dpclip.DP_F32):
+                if T > 1:
                     assert n >= 4 * B, (B, T, di, do, dt, path, n)
             n = f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dt)
             assert n >= 0 and n % 4 == 0 and n < (1 << 40)
@@ -116,9 +116,10 @@ def test_layers_workspace_sizes(lib):
     tr = descs([(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)])
     assert f(tr, 64, dpclip.DP_BF16) == 4 * 64 * 10 * 4                  # 10 pairs of 128-row tiles per example and layer
     assert f(tr, 64, dpclip.DP_F16) == f(tr, 64, dpclip.DP_BF16)
-    assert f(tr, 64, dpclip.DP_F32) == max(dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 64, *sh, dpclip.DP_F32)
+    assert f(tr, 64, dpclip.DP_F32) == 64 * 36 * 4                        # fp32 Gram: 8 tiles of 64 rows, 36 pairs, one layer at a time
+    assert f(tr, 64, dpclip.DP_F32, "direct") == max(dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 64, *sh, dpclip.DP_F32, "direct")
                                             for sh in [(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)])
-    assert f(tr, 64, dpclip.DP_F32, "gram") == 0                         # unsupported combination
+    assert f(tr, 64, dpclip.DP_F32, "gram") == 64 * 36 * 4
     many = descs([(128, 64, 64)] * 20)
     assert f(many, 8, dpclip.DP_BF16, "gram") == 16 * 8 * 1 * 4           # launches of 16 and 4 layers reuse the space
     mixed = descs([(1, 64, 32), (1024, 576, 128), (0, 8, 8)])

@@ -158,6 +158,24 @@ def test_fp16_subnormal_gradients(dp, B, T, d_in, d_out):
     assert fro_err(g, orc.clipped_grad(A, G, c_ref)) <= FRO_TOL["f16"]
 
 
+def test_fp32_transformer_shapes_take_the_gram_path(dp):
+    """float32 inputs (the paper's precision) on transformer-shaped layers: AUTO resolves to the Gram path, which agrees
+    with the direct path and the oracle."""
+    w, layers = wl.generate("transformer", B=3, dtype="f32", layers=(1,))
+    A, G = layers[1]
+    assert dp.choose_path(A.shape[1], A.shape[2], G.shape[2]) == "gram"
+    s_ref = orc.layer_sqnorm(A, G)
+    Ad, Gd = to_dev(A), to_dev(G)
+    s_gram = dp.layer_sqnorm(Ad, Gd, path="gram").cpu().numpy()
+    s_auto = dp.layer_sqnorm(Ad, Gd).cpu().numpy()
+    s_dir = dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy()
+    np.testing.assert_array_equal(s_auto, s_gram)
+    assert rel_err(s_gram, s_ref) <= SQ_TOL["f32"] and rel_err(s_dir, s_ref) <= SQ_TOL["f32"]
+    s2 = torch.full((3,), 1.25, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, s2, path="gram", accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 1.25) <= SQ_TOL["f32"]
+
+
 def test_fused_qkv_equals_three_projections(dp):
     """Squared norm of the stacked 768 -> 2304 projection = sum over its three 768-wide blocks (Section 5.6)."""
     w, layers = wl.generate("transformer", B=4, layers=(0,))
@@ -281,7 +299,7 @@ def test_layers_call_empty_and_errors(dp):
     assert lib.dp_layers_sqnorm(descs, 1, B, dt, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_WORKSPACE
     assert lib.dp_layers_sqnorm(descs, -1, B, dt, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_INVALID_ARG
     assert lib.dp_layers_sqnorm(None, 1, B, dt, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_INVALID_ARG
-    assert lib.dp_layers_sqnorm(descs, 1, B, dp.DP_F32, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_UNSUPPORTED
+    assert lib.dp_layers_sqnorm(descs, 1, B, 9, dp.DP_PATH_GRAM, 0, s.data_ptr(), None, 0, None) == dp.DP_ERR_INVALID_ARG   # unknown dtype
     assert lib.dp_layers_sqnorm(descs, 0, B, dt, dp.DP_PATH_AUTO, 0, s.data_ptr(), None, 0, None) == dp.DP_OK   # no layers: zeros
     torch.cuda.synchronize()
     assert torch.all(s == 0)
@@ -316,7 +334,7 @@ def test_ragged_shapes(dp, dtype, B, T, d_in, d_out):
     c_ref = orc.clip_factors(s_ref, C)
     g_ref = orc.clipped_grad(A, G, c_ref)
     Ad, Gd = to_dev(A), to_dev(G)
-    paths = ["auto"] if (T == 1 or dtype == "f32") else ["gram", "direct"]
+    paths = ["auto"] if T == 1 else ["gram", "direct"]
     for path in paths:
         s = dp.layer_sqnorm(Ad, Gd, path=path)
         assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], (path, rel_err(s.cpu().numpy(), s_ref))
@@ -350,7 +368,7 @@ def test_drawn_shapes(dp, B, T, d_in, d_out, dtype):
     c_ref = orc.clip_factors(s_ref, C)
     g_ref = orc.clipped_grad(A, G, c_ref)
     Ad, Gd = to_dev(A), to_dev(G)
-    paths = ["auto"] if (T == 1 or dtype == "f32") else ["gram", "direct", "auto"]
+    paths = ["auto"] if T == 1 else ["gram", "direct", "auto"]
     for path in paths:
         s = dp.layer_sqnorm(Ad, Gd, path=path)
         assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], (path, rel_err(s.cpu().numpy(), s_ref))
@@ -434,9 +452,10 @@ def test_empty_problems_and_errors(dp):
     assert st == dp.DP_ERR_WORKSPACE
     st = lib.dp_layer_sqnorm(A2.data_ptr(), G2.data_ptr(), -1, 4, 8, 8, dp.DP_BF16, 0, 0, s2.data_ptr(), None, 0, None)
     assert st == dp.DP_ERR_INVALID_ARG
-    st = lib.dp_layer_sqnorm(A2.data_ptr(), G2.data_ptr(), 2, 4, 8, 8, dp.DP_F32, dp.DP_PATH_GRAM, 0,
-                             s2.data_ptr(), None, 0, None)
-    assert st == dp.DP_ERR_UNSUPPORTED
+    st = lib.dp_layer_sqnorm(A2.data_ptr(), G2.data_ptr(), 2, 4, 8, 8, dp.DP_BF16, 3, 0, s2.data_ptr(), None, 0, None)
+    assert st == dp.DP_ERR_INVALID_ARG                     # unknown path
+    st = lib.dp_layer_sqnorm(A2.data_ptr(), G2.data_ptr(), 1 << 20, 1 << 12, 8, 8, dp.DP_BF16, 0, 0, s2.data_ptr(), None, 0, None)
+    assert st == dp.DP_ERR_UNSUPPORTED                     # B * T >= 2^31
     st = lib.dp_clip_factors(s2.data_ptr(), 2, 0.0, s2.data_ptr(), None)
     assert st == dp.DP_ERR_INVALID_ARG
     st = lib.dp_add_noise(s2.data_ptr(), 2, -1.0, 0, 0, None)
