@@ -69,7 +69,7 @@ class Pipeline:
         self.descs = dp.layer_descs(self.dev)
         order = sorted(range(len(self.dev)), key=lambda li: self.dev[li][0].shape[2] + self.dev[li][1].shape[2])
         self.dev_cg = [self.dev[li] for li in order]
-        self.descs_cg = dp.layer_descs(self.dev_cg, [self.grads[li] for li in order])
+        self.descs_cg = dp.layer_descs(self.dev_cg, [self.grads[li] for li in order], [starts[li] for li in order])
         self.ws_cg_all = torch.empty(max(16, dp.layers_clipped_workspace_bytes(self.descs_cg[0], self.B, dt)), dtype=torch.uint8, device="cuda")
         self.ws_layers = torch.empty(max(16, dp.layers_workspace_bytes(self.descs[0], self.B, dt, path)), dtype=torch.uint8, device="cuda")
 
@@ -89,14 +89,16 @@ class Pipeline:
         # Infinity Cache (the several-layers call runs the widest layers first, a single call per layer runs them
         # in the order given)
         if len(self.dev) > 1:
-            self.dp.layers_clipped_grad(self.dev_cg, self.c, workspace=self.ws_cg_all, descs=self.descs_cg)
+            # with the noise of the flat gradient buffer added by the kernels that fold the K slices
+            self.dp.layers_clipped_grad(self.dev_cg, self.c, workspace=self.ws_cg_all, descs=self.descs_cg,
+                                        noise_std=self.w.noise_std, seed=self.w.noise_seed)
             return
         for li in range(len(self.dev)):
             A, G = self.dev[li]
             self.dp.clipped_grad(A, G, self.c, self.grads[li], workspace=self.ws_cg[li])
 
     def phase_noise(self):
-        if self.w.noise_std > 0:
+        if self.w.noise_std > 0 and len(self.dev) == 1:       # several layers: added in phase_grad
             self.dp.add_noise(self.flat_grad, self.w.noise_std, self.w.noise_seed, 0)
 
     def step(self, events=None):
@@ -270,7 +272,12 @@ def main():
         "clipped_grad_tflops": work["gemm_flops"] / (grad_ms * 1e-3) / 1e12,
         "clipped_grad_gbs": work["gemm_bytes"] / (grad_ms * 1e-3) / 1e9,
     }
-    if noise_ms > 0 and work["noise_bytes"]:
+    noise_fused = w.noise_std > 0 and len(w.layers) > 1
+    if noise_fused:
+        # the noise is added inside the clipped-sum phase (by the kernels that fold the K slices): no pass of its own
+        phases_out["noise_ms"] = 0.0
+        phases_out["noise"] = "added by the split-K reduce kernels, inside clipped_grad_ms"
+    elif noise_ms > 0 and work["noise_bytes"]:
         phases_out["noise_gbs"] = work["noise_bytes"] / (noise_ms * 1e-3) / 1e9
 
     # bias parameters (the first of the "next" rows): per-example bias gradients + their squared norms for every

@@ -109,7 +109,8 @@ typedef struct {
     const void* A;              /* device, [B, T, d_in] */
     const void* G;              /* device, [B, T, d_out] */
     int64_t T, d_in, d_out;
-    float* grad;                /* device, float32[d_in, d_out]: dp_layers_clipped_grad only */
+    float* grad;                /* device, float32[d_in, d_out]: dp_layers_clipped_grad(_noise) only */
+    uint64_t noise_offset;      /* position of grad[0] in the noise stream: dp_layers_clipped_grad_noise only */
 } dp_layer_desc;
 
 dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
@@ -134,6 +135,22 @@ dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, 
 
 size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
                                          dp_dtype dtype);
+
+/* dp_layers_clipped_grad followed by the Gaussian mechanism's noise (Algorithm 1,
+ * the line that adds N(0, sigma^2 C^2 I)) on every layer's result:
+ *     layers[l].grad[j] += stddev * z[layers[l].noise_offset + j],
+ * z = the stream of dp_add_noise for `seed`.  Bit-identical to
+ * dp_layers_clipped_grad followed by dp_add_noise(grad, d_in*d_out, stddev, seed,
+ * noise_offset) per layer; where a layer's clipped sum ends in the kernel that
+ * folds its K slices (and d_in*d_out and noise_offset are multiples of 4), that
+ * kernel adds the noise while it holds the sums, which saves the extra pass over
+ * the gradient.  With the layers' noise_offset set to the positions of their
+ * gradients in the model's flat parameter vector, the noise is the same as one
+ * dp_add_noise call over that vector.  stddev == 0 adds nothing. */
+dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
+                                       const float* clip, dp_dtype dtype, int accumulate,
+                                       float stddev, uint64_t seed,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Clip factors (Algorithm 1, the line defining nu_i; Eq. per_example_weight;
  * clip function of Section 3.2):

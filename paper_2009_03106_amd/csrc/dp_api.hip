@@ -166,17 +166,41 @@ dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C, float* clip, 
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 
-dp_status dp_clipped_grad(const void* A, const void* G, const float* clip, int64_t B, int64_t T, int64_t d_in,
-                          int64_t d_out, dp_dtype dtype, int accumulate, float* grad, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// dp_clipped_grad, optionally followed by  grad[j] += stddev * N(0,1)[seed, offset + j].  The noise is added by the
+// split-K reduce kernel when there is one and the offsets are multiples of 4, else by the noise kernel.
+dp_status clipped_grad_noise(const void* A, const void* G, const float* clip, int64_t B, int64_t T, int64_t d_in,
+                             int64_t d_out, dp_dtype dtype, int accumulate, float* grad, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, float stddev, uint64_t seed, uint64_t offset);
+
+}  // namespace
+
+extern "C" dp_status dp_clipped_grad(const void* A, const void* G, const float* clip, int64_t B, int64_t T, int64_t d_in,
+                                     int64_t d_out, dp_dtype dtype, int accumulate, float* grad, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+    return clipped_grad_noise(A, G, clip, B, T, d_in, d_out, dtype, accumulate, grad, workspace, workspace_bytes, hip_stream,
+                              0.0f, 0, 0);
+}
+
+namespace {
+
+dp_status clipped_grad_noise(const void* A, const void* G, const float* clip, int64_t B, int64_t T, int64_t d_in,
+                             int64_t d_out, dp_dtype dtype, int accumulate, float* grad, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, float stddev, uint64_t seed, uint64_t offset) {
     dp_status st = check_dims(B, T, d_in, d_out);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (d_in == 0 || d_out == 0) return DP_OK;
     if (!grad || !aligned16(grad)) return DP_ERR_INVALID_ARG;
+    const int64_t n = d_in * d_out;
+    const bool noisy = stddev != 0.0f;
     if (B == 0 || T == 0) {
-        if (!accumulate && launch_fill_zero(grad, d_in * d_out, stream) != hipSuccess) return DP_ERR_HIP;
+        if (!accumulate && launch_fill_zero(grad, n, stream) != hipSuccess) return DP_ERR_HIP;
+        if (noisy && launch_add_noise(grad, n, stddev, seed, offset, stream) != hipSuccess) return DP_ERR_HIP;
         return DP_OK;
     }
     if (!A || !G || !clip || !aligned16(A) || !aligned16(G)) return DP_ERR_INVALID_ARG;
@@ -184,18 +208,25 @@ dp_status dp_clipped_grad(const void* A, const void* G, const float* clip, int64
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
     float* ws = static_cast<float*>(workspace);
 
+    const TnPlan p = is16(dtype) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
+                                 : plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
+    const NoiseArgs nz{stddev, (uint32_t)seed, (uint32_t)(seed >> 32), offset};
+    const bool fused = noisy && p.splits > 1 && splitk_noise_ok(n, offset);
     hipError_t e;
     if (is16(dtype)) {
-        TnPlan p = plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_clipped_bf16(p, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), clip, (int)B, (int)T,
-                                (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, dtype == DP_F16);
+                                (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, dtype == DP_F16, fused ? &nz : nullptr);
     } else {
-        TnPlan p = plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_clipped_f32(p, static_cast<const float*>(A), static_cast<const float*>(G), clip, (int)B, (int)T,
-                               (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream);
+                               (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, fused ? &nz : nullptr);
     }
+    if (e == hipSuccess && noisy && !fused) e = launch_add_noise(grad, n, stddev, seed, offset, stream);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
+
+}  // namespace
+
+extern "C" {
 
 dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_dtype dtype, int accumulate,
                          float* sqnorm, float* bias_rows, void* hip_stream) {
@@ -333,7 +364,7 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, 
     const TnPlan p = plan_clipped_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
     const hipError_t e = launch_clipped_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), clip, (int)B,
                                                  (int)T, (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, &g,
-                                                 reinterpret_cast<const uint16_t*>(zero), dtype == DP_F16);
+                                                 reinterpret_cast<const uint16_t*>(zero), dtype == DP_F16, nullptr);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 
@@ -484,13 +515,21 @@ size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_
 
 dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, int64_t B, const float* clip, dp_dtype dtype,
                                  int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return dp_layers_clipped_grad_noise(layers, n_layers, B, clip, dtype, accumulate, 0.0f, 0, workspace, workspace_bytes, hip_stream);
+}
+
+dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_layers, int64_t B, const float* clip, dp_dtype dtype,
+                                       int accumulate, float stddev, uint64_t seed, void* workspace, size_t workspace_bytes,
+                                       void* hip_stream) {
     // everything is checked before the first launch: an error leaves every output untouched
+    if (!(stddev >= 0.0f)) return DP_ERR_INVALID_ARG;
     const dp_status st = check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, true);
     if (st != DP_OK) return st;
     size_t need = 0;
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
         if (y.d_in > 0 && y.d_out > 0 && (!y.grad || !aligned16(y.grad))) return DP_ERR_INVALID_ARG;
+        if (stddev > 0.0f && y.noise_offset > ~uint64_t(0) - (uint64_t)(y.d_in * y.d_out)) return DP_ERR_INVALID_ARG;   // offset + n must not wrap
         const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
         if (n > need) need = n;
     }
@@ -498,8 +537,8 @@ dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, 
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
-        const dp_status s1 = dp_clipped_grad(y.A, y.G, clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
-                                             workspace_bytes, hip_stream);
+        const dp_status s1 = clipped_grad_noise(y.A, y.G, clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
+                                                workspace_bytes, hip_stream, stddev, seed, y.noise_offset);
         if (s1 != DP_OK) return s1;
     }
     return DP_OK;

@@ -24,7 +24,11 @@ hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f,
 hipError_t launch_clip_factors(const float* sqnorm, int B, float C, float* clip, hipStream_t st);
 // distance in floats between consecutive split-K slices of an n-element output
 inline int64_t splitk_slice_elems(int64_t n) { return (n + 3) & ~(int64_t)3; }
-hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st);
+// Gaussian noise that the split-K reduce can add while it holds the sums (stddev == 0: none)
+struct NoiseArgs { float stddev; uint32_t k0, k1; uint64_t offset; };
+bool splitk_noise_ok(int64_t n, uint64_t offset);       // n and offset multiples of 4
+hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st,
+                                const NoiseArgs* noise);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st);
 // ---- bias parameters (dp_bias.hip)
@@ -60,10 +64,11 @@ TnPlan plan_direct_f32(int T, int M, int N);
 // out: splits == 1 -> nullptr workspace allowed and the tile goes straight to `grad` (overwrite
 // or accumulate); otherwise slices go to ws[splits][M][N] and a second kernel folds them.
 hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
-                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st, bool f16);
+                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st, bool f16,
+                               const NoiseArgs* noise);
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
-                                   const ConvGeom* cg, const uint16_t* zero, bool f16);
+                                   const ConvGeom* cg, const uint16_t* zero, bool f16, const NoiseArgs* noise);
 // direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);
@@ -71,7 +76,8 @@ hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
                                   const ConvGeom* cg, const uint16_t* zero, bool f16);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
-                              int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st);
+                              int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
+                              const NoiseArgs* noise);
 // partial[B][tiles_m*tiles_n] then finalize into sqnorm
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                               bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);

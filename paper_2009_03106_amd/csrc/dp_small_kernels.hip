@@ -165,10 +165,52 @@ hipError_t launch_clip_factors(const float* sqnorm, int B, float C, float* clip,
 }
 
 // ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11) and Box-Muller normals.
+// ---------------------------------------------------------------------------
+struct U4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += W0; k1 += W1;
+    }
+    return U4{c0, c1, c2, c3};
+}
+
+// u = ((w >> 9) + 1/2) / 2^23, exact in float32 and strictly inside (0, 1)
+__device__ __forceinline__ float uniform23(uint32_t w) { return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f; }
+
+__device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float& z_even, float& z_odd) {
+    const float r = sqrtf(-2.0f * logf(uniform23(wa)));
+    float s, c;
+    sincospif(2.0f * uniform23(wb), &s, &c);
+    z_even = r * c;
+    z_odd = r * s;
+}
+
+// The four normals of Philox block q = (offset + j) / 4, scaled: what k_add_noise adds to grad[j .. j + 3] when
+// offset + j is a multiple of 4.  Used by the split-K reduce kernels to add the noise while the sums are in
+// registers (same values, same single multiply-add per element as the stand-alone kernel).
+__device__ __forceinline__ void add_noise4(float4& g, uint64_t q, const NoiseArgs& nz) {
+    const U4 w = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), 0u, 0u, nz.k0, nz.k1);
+    float z[4];
+    box_muller(w.x, w.y, z[0], z[1]);
+    box_muller(w.z, w.w, z[2], z[3]);
+    g.x += nz.stddev * z[0]; g.y += nz.stddev * z[1]; g.z += nz.stddev * z[2]; g.w += nz.stddev * z[3];
+}
+
+// ---------------------------------------------------------------------------
 // grad[j] (+)= sum_z ws[z][j], z ascending: second stage of the split-K GEMM.
 // ---------------------------------------------------------------------------
+// NOISE: n and nz.offset are multiples of 4; element j gets stddev * N(0,1)[seed, offset + j] on top.
+template <bool NOISE>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__ ws, int64_t n, int64_t slice, int splits,
-                                                       int accumulate, float* __restrict__ grad) {
+                                                       int accumulate, float* __restrict__ grad, NoiseArgs nz) {
     const int64_t n4 = n >> 2;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < n4; c += stride) {
@@ -179,6 +221,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
         }
         float4* o = reinterpret_cast<float4*>(grad) + c;
         if (accumulate) { float4 g = *o; acc.x += g.x; acc.y += g.y; acc.z += g.z; acc.w += g.w; }
+        if (NOISE) add_noise4(acc, (nz.offset >> 2) + (uint64_t)c, nz);
         *o = acc;
     }
     // tail (n not a multiple of 4)
@@ -193,8 +236,9 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 // walk its slices one load at a time: 8 threads share an output column group, thread g adds slices g, g + 8, ...
 // in ascending order, and the 8 partial sums are added in the order g = 0 .. 7.  The order is fixed, so the
 // result is reproducible; it differs from the one-thread order only by rounding.
+template <bool NOISE>
 __global__ __launch_bounds__(256) void k_splitk_reduce_wide(const float* __restrict__ ws, int64_t n4, int64_t slice, int splits,
-                                                            int accumulate, float* __restrict__ grad) {
+                                                            int accumulate, float* __restrict__ grad, NoiseArgs nz) {
     __shared__ float4 part[8][32];
     const int g = threadIdx.x >> 5, cl = threadIdx.x & 31;
     const int64_t c = (int64_t)blockIdx.x * 32 + cl;
@@ -223,21 +267,32 @@ __global__ __launch_bounds__(256) void k_splitk_reduce_wide(const float* __restr
         for (int k = 1; k < 8; ++k) { const float4 v = part[k][cl]; acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w; }
         float4* o = reinterpret_cast<float4*>(grad) + c;
         if (accumulate) { const float4 q = *o; acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w; }
+        if (NOISE) add_noise4(acc, (nz.offset >> 2) + (uint64_t)c, nz);
         *o = acc;
     }
 }
 
-hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st) {
+bool splitk_noise_ok(int64_t n, uint64_t offset) { return (n & 3) == 0 && (offset & 3) == 0; }
+
+// noise: nullptr or stddev == 0 for none; otherwise splitk_noise_ok(n, noise->offset) must hold
+hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st,
+                                const NoiseArgs* noise) {
     // slices are spaced splitk_slice_elems(n) apart, a multiple of 4 floats, so each starts 16-byte aligned
     const int64_t n4 = n >> 2;
+    const bool nz = noise != nullptr && noise->stddev != 0.0f;
+    if (nz && !splitk_noise_ok(n, noise->offset)) return hipErrorInvalidValue;
+    const NoiseArgs na = nz ? *noise : NoiseArgs{0.f, 0u, 0u, 0u};
     if (splits >= 16 && (n & 3) == 0 && n4 <= (int64_t)256 * 1024) {
-        k_splitk_reduce_wide<<<(unsigned)((n4 + 31) / 32), 256, 0, st>>>(ws, n4, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad);
+        const unsigned grid = (unsigned)((n4 + 31) / 32);
+        if (nz) k_splitk_reduce_wide<true><<<grid, 256, 0, st>>>(ws, n4, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad, na);
+        else    k_splitk_reduce_wide<false><<<grid, 256, 0, st>>>(ws, n4, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad, na);
         return hipGetLastError();
     }
     int64_t blocks = (n4 + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
-    k_splitk_reduce<<<(unsigned)blocks, 256, 0, st>>>(ws, n, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad);
+    if (nz) k_splitk_reduce<true><<<(unsigned)blocks, 256, 0, st>>>(ws, n, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad, na);
+    else    k_splitk_reduce<false><<<(unsigned)blocks, 256, 0, st>>>(ws, n, splitk_slice_elems(n), splits, accumulate ? 1 : 0, grad, na);
     return hipGetLastError();
 }
 
@@ -252,35 +307,6 @@ hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
     if (blocks > 4096) blocks = 4096;
     k_fill_zero<<<(unsigned)blocks, 256, 0, st>>>(p, n);
     return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
-// Philox4x32-10 (Salmon et al., SC'11) and Box-Muller normals.
-// ---------------------------------------------------------------------------
-struct U4 { uint32_t x, y, z, w; };
-
-__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
-    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
-        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
-        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
-        k0 += W0; k1 += W1;
-    }
-    return U4{c0, c1, c2, c3};
-}
-
-// u = ((w >> 9) + 1/2) / 2^23, exact in float32 and strictly inside (0, 1)
-__device__ __forceinline__ float uniform23(uint32_t w) { return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f; }
-
-__device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float& z_even, float& z_odd) {
-    const float r = sqrtf(-2.0f * logf(uniform23(wa)));
-    float s, c;
-    sincospif(2.0f * uniform23(wb), &s, &c);
-    z_even = r * c;
-    z_odd = r * s;
 }
 
 __global__ __launch_bounds__(256) void k_add_noise(float* __restrict__ grad, int64_t n, float stddev,

@@ -676,10 +676,11 @@ TnPlan plan_direct_bf16(int B, int T, int M, int N) {
 }
 
 hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
-                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st, bool f16) {
+                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st, bool f16,
+                               const NoiseArgs* noise) {
     const int64_t n = (int64_t)M * N;
     const int tiles = p.tiles_m * p.tiles_n;
-    if (p.dma) return launch_clipped_bf16_dma(p, A, G, clip, B, T, M, N, accumulate, grad, ws, st, nullptr, nullptr, f16);
+    if (p.dma) return launch_clipped_bf16_dma(p, A, G, clip, B, T, M, N, accumulate, grad, ws, st, nullptr, nullptr, f16, noise);
     if (p.big) {
         BigArgs a;
         a.A = A; a.G = G; a.clip = clip;
@@ -712,7 +713,7 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
-    return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
+    return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
 }
 
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,

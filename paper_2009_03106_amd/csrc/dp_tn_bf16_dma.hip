@@ -510,7 +510,7 @@ TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
 
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
-                                   const ConvGeom* cg, const uint16_t* zero, bool f16) {
+                                   const ConvGeom* cg, const uint16_t* zero, bool f16, const NoiseArgs* noise) {
     int am = cg ? 1 : 0;
     if (!cg && p.zero_head) {
         // ragged T: the head of the workspace is the line of zeros
@@ -534,7 +534,7 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
     const hipError_t e = launch_any<0>(geo_of_plan(p), a, am, f16, st);
     if (e != hipSuccess || p.splits == 1) return e;
-    return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
+    return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
 }
 
 // implicit unfolding: whole 16-byte pieces must stay inside one pixel's channels, image offsets must fit 32 bits

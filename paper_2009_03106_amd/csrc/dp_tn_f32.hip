@@ -302,7 +302,8 @@ TnPlan plan_direct_f32(int T, int M, int N) {
 }
 
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
-                              int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st) {
+                              int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
+                              const NoiseArgs* noise) {
     TnArgsF a;
     a.A = A; a.G = G; a.clip = clip;
     a.K = B * T; a.T = T; a.M = M; a.N = N;
@@ -321,7 +322,7 @@ hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, c
     launch_f32<0>(stage_rows(a.K) == 64, ((M | N) & 3) == 0, grid, a, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
-    return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st);
+    return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
 }
 
 hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, int B, int T, int M, int N,

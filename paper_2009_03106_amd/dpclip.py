@@ -23,7 +23,7 @@ DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
 EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
-           "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
+           "dp_layers_clipped_grad_noise", "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
 
 _lib = None
@@ -32,7 +32,7 @@ _lib = None
 class LayerDesc(ctypes.Structure):
     """dp_layer_desc of the header."""
     _fields_ = [("A", ctypes.c_void_p), ("G", ctypes.c_void_p), ("T", ctypes.c_int64), ("d_in", ctypes.c_int64),
-                ("d_out", ctypes.c_int64), ("grad", ctypes.c_void_p)]
+                ("d_out", ctypes.c_int64), ("grad", ctypes.c_void_p), ("noise_offset", ctypes.c_uint64)]
 
 
 class DpclipError(RuntimeError):
@@ -60,6 +60,8 @@ def load_library() -> ctypes.CDLL:
     lib.dp_layers_workspace_bytes.restype = sz
     lib.dp_layers_clipped_grad.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, vp, ci, ci, vp, sz, vp]
     lib.dp_layers_clipped_grad.restype = ci
+    lib.dp_layers_clipped_grad_noise.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, vp, ci, ci, f32, u64, vp, sz, vp]
+    lib.dp_layers_clipped_grad_noise.restype = ci
     lib.dp_layers_clipped_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci]
     lib.dp_layers_clipped_workspace_bytes.restype = sz
     lib.dp_clip_factors.argtypes = [vp, i64, f32, vp, vp]
@@ -181,9 +183,11 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
     return sqnorm
 
 
-def layer_descs(layers, grads=None):
+def layer_descs(layers, grads=None, noise_offsets=None):
     """(ctypes array of dp_layer_desc, B, dtype code) for a list of (A, G) tensor pairs sharing B and dtype, with
-    the float32 [d_in, d_out] output of each layer if grads is given (layers_clipped_grad needs them).
+    the float32 [d_in, d_out] output of each layer if grads is given (layers_clipped_grad needs them) and the position of
+    each gradient in the noise stream if noise_offsets is given (default: the gradients laid out back to back in the order
+    of the list).
     The tensors must stay alive (and contiguous: the pointers are taken here) while the array is used."""
     if len(layers) == 0:
         raise ValueError("no layers")
@@ -191,6 +195,7 @@ def layer_descs(layers, grads=None):
         raise ValueError("one gradient tensor per layer")
     arr = (LayerDesc * len(layers))()
     B0, dt0 = None, None
+    running = 0
     for i, (A, G) in enumerate(layers):
         if not (A.is_contiguous() and G.is_contiguous()):
             raise ValueError("layer tensors must be contiguous")
@@ -206,7 +211,8 @@ def layer_descs(layers, grads=None):
             if g.dtype != torch.float32 or tuple(g.shape) != (d_in, d_out):
                 raise ValueError("gradients must be float32 [d_in, d_out]")
             gp = _ptr(g)
-        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp)
+        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, running if noise_offsets is None else int(noise_offsets[i]))
+        running += d_in * d_out
     return arr, B0, dt0
 
 
@@ -238,9 +244,10 @@ def layers_clipped_workspace_bytes(descs, B: int, dtype: int) -> int:
 
 
 def layers_clipped_grad(layers, clip: torch.Tensor, grads=None, *, accumulate: bool = False,
-                        workspace: Optional[torch.Tensor] = None, descs=None,
+                        workspace: Optional[torch.Tensor] = None, descs=None, noise_std: float = 0.0, seed: int = 0,
                         stream: Optional[torch.cuda.Stream] = None):
-    """grads[l] (+)= sum_i clip[i] A_l,i^T G_l,i for every (A, G) pair via dp_layers_clipped_grad; returns grads.
+    """grads[l] (+)= sum_i clip[i] A_l,i^T G_l,i for every (A, G) pair via dp_layers_clipped_grad(_noise); returns grads.
+    noise_std > 0 also adds noise_std * N(0,1)[seed, noise_offset_l + j] to every grads[l][j] (see layer_descs).
     descs: the result of layer_descs(layers, grads), to skip rebuilding it on every call."""
     lib = load_library()
     if descs is None:
@@ -251,9 +258,10 @@ def layers_clipped_grad(layers, clip: torch.Tensor, grads=None, *, accumulate: b
         descs = layer_descs(layers, grads)
     arr, B, dt = descs
     ws = _workspace(lambda: layers_clipped_workspace_bytes(arr, B, dt), layers[0][0].device, workspace)
-    st = lib.dp_layers_clipped_grad(arr, len(arr), B, _ptr(clip), dt, int(bool(accumulate)), _ptr(ws),
-                                    0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
-    _check(st, "dp_layers_clipped_grad")
+    st = lib.dp_layers_clipped_grad_noise(arr, len(arr), B, _ptr(clip), dt, int(bool(accumulate)), float(noise_std),
+                                          int(seed) & (2 ** 64 - 1), _ptr(ws),
+                                          0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
+    _check(st, "dp_layers_clipped_grad_noise")
     return grads
 
 

@@ -271,6 +271,33 @@ def test_layers_clipped_grad_equals_per_layer_calls(dp, name, B):
     assert all(torch.all(k == 5.0) for k in keep)
 
 
+@pytest.mark.parametrize("name,B,base", [("transformer", 6, 0), ("transformer", 3, 4096), ("mlp", None, 0), ("rnn", None, 7),
+                                         ("conv", 8, 12)])
+def test_layers_clipped_grad_with_noise_equals_separate_calls(dp, name, B, base):
+    """The noise that dp_layers_clipped_grad_noise adds (inside the kernels that fold the K slices where it can, by
+    the noise kernel otherwise: one K slice, offsets that are not multiples of 4) is bit for bit what dp_add_noise
+    adds afterwards, and with back-to-back offsets it is one dp_add_noise call over the flat gradient."""
+    w, layers = wl.generate(name, B=B, straddle=True)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    c = torch.rand(dev[0][0].shape[0], device="cuda") * 0.9 + 0.1
+    sizes = [A.shape[-1] * G.shape[-1] for A, G in dev]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.zeros(sum(sizes), device="cuda")
+    grads = [flat[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)]
+    descs = dp.layer_descs(dev, grads, [base + st for st in starts[:-1]])
+    dp.layers_clipped_grad(dev, c, descs=descs, noise_std=0.75, seed=20090310)
+    ref = torch.zeros_like(flat)
+    ref_grads = [ref[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)]
+    dp.layers_clipped_grad(dev, c, ref_grads)
+    dp.add_noise(ref, 0.75, 20090310, base)
+    assert torch.equal(flat, ref)
+    # accumulate: the noise goes on top of (old + sum)
+    dp.layers_clipped_grad(dev, c, descs=descs, noise_std=0.75, seed=5, accumulate=True)
+    dp.layers_clipped_grad(dev, c, ref_grads, accumulate=True)
+    dp.add_noise(ref, 0.75, 5, base)
+    assert torch.equal(flat, ref)
+
+
 def test_layers_call_more_layers_than_one_launch_takes(dp):
     B = 3
     layers = [wl.random_layer(300 + i, B, 96 + 32 * (i % 3), 64 * (1 + i % 2), 64 * (1 + (i // 2) % 3), "bf16",
