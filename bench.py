@@ -76,13 +76,16 @@ class Pipeline:
     def phase_sqnorm(self):
         if len(self.dev) > 1:
             # all layers in one call: the copy-pipeline Gram layers share a launch
-            self.dp.layers_sqnorm(self.dev, self.s, path=self.path, workspace=self.ws_layers, descs=self.descs)
+            # ... and the launch that completes the norms writes the clip factors
+            self.dp.layers_sqnorm(self.dev, self.s, path=self.path, workspace=self.ws_layers, descs=self.descs,
+                                  C=self.w.C, clip=self.c)
             return
         for li, (A, G) in enumerate(self.dev):
             self.dp.layer_sqnorm(A, G, self.s, path=self.path, accumulate=li > 0, workspace=self.ws_sq[li])
 
     def phase_clip(self):
-        self.dp.clip_factors(self.s, self.w.C, self.c)
+        if len(self.dev) == 1:                                 # several layers: done by phase_sqnorm
+            self.dp.clip_factors(self.s, self.w.C, self.c)
 
     def phase_grad(self):
         # the layers that the norm phase read last first: their inputs are the likeliest to be still in the

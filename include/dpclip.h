@@ -121,6 +121,16 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
 size_t dp_layers_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
                                  dp_dtype dtype, dp_path path);
 
+/* dp_layers_sqnorm followed by dp_clip_factors(sqnorm, B, C, clip) (Algorithm 1,
+ * the line defining nu_i), for the case that the layers given are the whole
+ * model: the launch that completes the norms writes the clip factors too where it
+ * can, else a clip-factor launch follows; the values are the same either way.
+ * clip == NULL: exactly dp_layers_sqnorm.  C must be > 0 when clip is given. */
+dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
+                                dp_dtype dtype, dp_path path, int accumulate,
+                                float* sqnorm, float C, float* clip,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* dp_clipped_grad for several layers in one call, in the order given:
  *     layers[l].grad = (accumulate ? layers[l].grad : 0) + sum_i clip[i] * A_l,i^T G_l,i.
  * Same kernels and same results, bit for bit, as one dp_clipped_grad call per

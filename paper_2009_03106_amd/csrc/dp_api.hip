@@ -437,8 +437,16 @@ size_t dp_layers_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, 
 
 dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path,
                            int accumulate, float* sqnorm, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return dp_layers_sqnorm_clip(layers, n_layers, B, dtype, path, accumulate, sqnorm, 0.0f, nullptr, workspace, workspace_bytes,
+                                 hip_stream);
+}
+
+dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path,
+                                int accumulate, float* sqnorm, float C, float* clip, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
     const dp_status st = check_layers(layers, n_layers, B, dtype, path, true);
     if (st != DP_OK) return st;
+    if (clip && !(C > 0.0f)) return DP_ERR_INVALID_ARG;
     if (B == 0) return DP_OK;
     if (!sqnorm) return DP_ERR_INVALID_ARG;
     const size_t need = layers_ws_bytes(layers, n_layers, B, dtype, path);
@@ -477,7 +485,8 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
     // the others, up to kGramBatch per launch, heaviest first inside a launch (the light ones fill its tail)
     GramLayerDesc batch[kGramBatch];
     int nb = 0;
-    auto flush = [&]() -> hipError_t {
+    // last: the launch that completes the norms also writes the clip factors
+    auto flush = [&](bool last) -> hipError_t {
         if (nb == 0) return hipSuccess;
         for (int i = 1; i < nb; ++i) {                                          // stable insertion sort, descending work
             const GramLayerDesc v = batch[i];
@@ -487,7 +496,7 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
             batch[j] = v;
         }
         const hipError_t e = launch_gram_bf16_dma_layers(batch, nb, (int)B, acc != 0, sqnorm, static_cast<float*>(workspace),
-                                                         stream, dtype == DP_F16);
+                                                         stream, dtype == DP_F16, C, last ? clip : nullptr);
         nb = 0; acc = 1; launched = true;
         return e;
     };
@@ -495,11 +504,13 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
         const dp_layer_desc& y = layers[l];
         if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (!gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
+        if (nb == kGramBatch && flush(false) != hipSuccess) return DP_ERR_HIP;       // full, and another layer follows
         batch[nb++] = GramLayerDesc{static_cast<const uint16_t*>(y.A), static_cast<const uint16_t*>(y.G), (int)y.T, (int)y.d_in, (int)y.d_out};
-        if (nb == kGramBatch && flush() != hipSuccess) return DP_ERR_HIP;
     }
-    if (flush() != hipSuccess) return DP_ERR_HIP;
+    const bool clip_in_finalize = clip != nullptr && nb > 0;
+    if (flush(true) != hipSuccess) return DP_ERR_HIP;
     if (!launched && !accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
+    if (clip && !clip_in_finalize && launch_clip_factors(sqnorm, (int)B, C, clip, stream) != hipSuccess) return DP_ERR_HIP;
     return DP_OK;
 }
 

@@ -229,7 +229,7 @@ bool gram_dma_ok(int T, int d_in, int d_out) {
 // Several layers in one launch (at most kGramBatch, every one passing gram_dma_ok); partial gets the layers' item
 // lists one after the other, in the order given, and the sums go to sqnorm in that order.
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
-                                       float* partial, hipStream_t st, bool f16) {
+                                       float* partial, hipStream_t st, bool f16, float C, float* clip) {
     if (n_layers < 1 || n_layers > kGramBatch) return hipErrorInvalidValue;
     GramDmaArgs a;
     FinalizeLayers fin;
@@ -257,7 +257,7 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
     else     k_gram_bf16_dma<false><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_finalize_layers(partial, fin, B, accumulate, sqnorm, st);
+    return launch_finalize_layers(partial, fin, B, accumulate, sqnorm, st, C, clip);
 }
 
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,

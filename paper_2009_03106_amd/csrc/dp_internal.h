@@ -20,7 +20,9 @@ hipError_t launch_finalize_partials(const float* partial, int B, int n_per_examp
 // s_i (+)= sum over the layers l, then over j < n[l], of partial[first[l] + i * n[l] + j], in that order
 constexpr int kGramBatch = 16;         // layers per batched Gram launch
 struct FinalizeLayers { int n_layers; int first[kGramBatch]; int n[kGramBatch]; };
-hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f, int B, bool accumulate, float* sqnorm, hipStream_t st);
+// clip != nullptr: also clip[i] = 1 / max(1, sqrt(s_i) / C) of the finished sums
+hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f, int B, bool accumulate, float* sqnorm, hipStream_t st,
+                                  float C, float* clip);
 hipError_t launch_clip_factors(const float* sqnorm, int B, float C, float* clip, hipStream_t st);
 // distance in floats between consecutive split-K slices of an n-element output
 inline int64_t splitk_slice_elems(int64_t n) { return (n + 3) & ~(int64_t)3; }
@@ -94,7 +96,7 @@ GramPlan plan_gram_bf16(int T, int d_in, int d_out);
 bool gram_dma_ok(int T, int d_in, int d_out);
 struct GramLayerDesc { const uint16_t* A; const uint16_t* G; int T, d_in, d_out; };
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
-                                       float* partial, hipStream_t st, bool f16);
+                                       float* partial, hipStream_t st, bool f16, float C = 0.f, float* clip = nullptr);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
                                 bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
 // float32 inputs (dp_gram_f32.hip): 64-row tiles

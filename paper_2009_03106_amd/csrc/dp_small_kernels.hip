@@ -128,9 +128,16 @@ hipError_t launch_finalize_partials(const float* partial, int B, int n, bool acc
     return hipGetLastError();
 }
 
-// The same over the item lists of several layers (batched Gram launch), layer after layer.
+// nu = 1 / max(1, sqrt(s) / C)   (clip function of Section 3.2); the max lets a NaN norm through
+__device__ __forceinline__ float clip_factor_of(float s, float C) {
+    const float m = sqrtf(s) / C;
+    return 1.0f / (!(m <= 1.0f) ? m : 1.0f);
+}
+
+// The same over the item lists of several layers (batched Gram launch), layer after layer.  clip != nullptr: the
+// finished norms are the whole model's, and their clip factors for threshold C are written too.
 __global__ void k_finalize_layers(const float* __restrict__ partial, FinalizeLayers f, int B, int accumulate,
-                                  float* __restrict__ sqnorm) {
+                                  float* __restrict__ sqnorm, float C, float* __restrict__ clip) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B) return;
     float s = accumulate ? sqnorm[i] : 0.f;
@@ -141,10 +148,12 @@ __global__ void k_finalize_layers(const float* __restrict__ partial, FinalizeLay
         s += t;
     }
     sqnorm[i] = s;
+    if (clip) clip[i] = clip_factor_of(s, C);
 }
 
-hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f, int B, bool accumulate, float* sqnorm, hipStream_t st) {
-    k_finalize_layers<<<(B + 63) / 64, 64, 0, st>>>(partial, f, B, accumulate ? 1 : 0, sqnorm);
+hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f, int B, bool accumulate, float* sqnorm, hipStream_t st,
+                                  float C, float* clip) {
+    k_finalize_layers<<<(B + 63) / 64, 64, 0, st>>>(partial, f, B, accumulate ? 1 : 0, sqnorm, C, clip);
     return hipGetLastError();
 }
 
@@ -154,9 +163,7 @@ hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f,
 __global__ void k_clip_factors(const float* __restrict__ sqnorm, int B, float C, float* __restrict__ clip) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B) return;
-    const float n = sqrtf(sqnorm[i]);
-    const float m = n / C;
-    clip[i] = 1.0f / (!(m <= 1.0f) ? m : 1.0f);     // max(1, m) that lets a NaN norm through
+    clip[i] = clip_factor_of(sqnorm[i], C);
 }
 
 hipError_t launch_clip_factors(const float* sqnorm, int B, float C, float* clip, hipStream_t st) {

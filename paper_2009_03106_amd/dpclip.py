@@ -22,7 +22,7 @@ DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
-EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
+EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_sqnorm_clip", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
            "dp_layers_clipped_grad_noise", "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
 
@@ -56,6 +56,8 @@ def load_library() -> ctypes.CDLL:
     lib.dp_layer_sqnorm.restype = ci
     lib.dp_layers_sqnorm.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci, ci, vp, vp, sz, vp]
     lib.dp_layers_sqnorm.restype = ci
+    lib.dp_layers_sqnorm_clip.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci, ci, vp, f32, vp, vp, sz, vp]
+    lib.dp_layers_sqnorm_clip.restype = ci
     lib.dp_layers_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci]
     lib.dp_layers_workspace_bytes.restype = sz
     lib.dp_layers_clipped_grad.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, vp, ci, ci, vp, sz, vp]
@@ -221,9 +223,10 @@ def layers_workspace_bytes(descs, B: int, dtype: int, path: str = "auto") -> int
 
 
 def layers_sqnorm(layers, sqnorm: Optional[torch.Tensor] = None, *, path: str = "auto", accumulate: bool = False,
-                  workspace: Optional[torch.Tensor] = None, descs=None,
-                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
-    """sqnorm[i] (+)= sum over the (A, G) pairs of ||A_i^T G_i||_F^2 via dp_layers_sqnorm.
+                  workspace: Optional[torch.Tensor] = None, descs=None, C: Optional[float] = None,
+                  clip: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """sqnorm[i] (+)= sum over the (A, G) pairs of ||A_i^T G_i||_F^2 via dp_layers_sqnorm(_clip).
+    With C and clip given, clip[i] = min(1, C / sqrt(sqnorm[i])) is written as well.
     descs: the result of layer_descs(layers), to skip rebuilding it on every call."""
     lib = load_library()
     arr, B, dt = descs if descs is not None else layer_descs(layers)
@@ -233,9 +236,12 @@ def layers_sqnorm(layers, sqnorm: Optional[torch.Tensor] = None, *, path: str = 
             raise ValueError("accumulate needs an existing sqnorm tensor")
         sqnorm = torch.empty(B, dtype=torch.float32, device=dev)
     ws = _workspace(lambda: layers_workspace_bytes(arr, B, dt, path), dev, workspace)
-    st = lib.dp_layers_sqnorm(arr, len(arr), B, dt, _PATHS[path], int(bool(accumulate)), _ptr(sqnorm), _ptr(ws),
-                              0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
-    _check(st, "dp_layers_sqnorm")
+    if (C is None) != (clip is None):
+        raise ValueError("C and clip go together")
+    st = lib.dp_layers_sqnorm_clip(arr, len(arr), B, dt, _PATHS[path], int(bool(accumulate)), _ptr(sqnorm),
+                                   0.0 if C is None else float(C), _ptr(clip), _ptr(ws),
+                                   0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
+    _check(st, "dp_layers_sqnorm_clip")
     return sqnorm
 
 

@@ -298,6 +298,26 @@ def test_layers_clipped_grad_with_noise_equals_separate_calls(dp, name, B, base)
     assert torch.equal(flat, ref)
 
 
+@pytest.mark.parametrize("name,B", [("transformer", 5), ("mlp", None), ("rnn", None)])
+def test_layers_sqnorm_with_clip_factors(dp, name, B):
+    """Clip factors written by the call that sums the norms = dp_clip_factors on its result, bit for bit, and agree
+    with the oracle; straddling inputs so that both branches of the clip function occur."""
+    w, layers = wl.generate(name, B=B, straddle=True)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    Bn = dev[0][0].shape[0]
+    c = torch.full((Bn,), -1.0, device="cuda")
+    s = dp.layers_sqnorm(dev, C=w.C, clip=c)
+    np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s, w.C).cpu().numpy())
+    np.testing.assert_array_equal(s.cpu().numpy(), dp.layers_sqnorm(dev).cpu().numpy())
+    c_ref = orc.clip_factors(orc.total_sqnorm(layers), w.C)
+    assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL[w.dtype]
+    assert (c == 1.0).any() and (c < 1.0).any()
+    lib = dp.load_library()
+    descs, _, dt = dp.layer_descs(dev)
+    ws = torch.empty(max(16, dp.layers_workspace_bytes(descs, Bn, dt)), dtype=torch.uint8, device="cuda")
+    assert lib.dp_layers_sqnorm_clip(descs, len(descs), Bn, dt, 0, 0, s.data_ptr(), 0.0, c.data_ptr(), ws.data_ptr(), ws.numel(), None) == dp.DP_ERR_INVALID_ARG
+
+
 def test_layers_call_more_layers_than_one_launch_takes(dp):
     B = 3
     layers = [wl.random_layer(300 + i, B, 96 + 32 * (i % 3), 64 * (1 + i % 2), 64 * (1 + (i // 2) % 3), "bf16",
