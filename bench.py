@@ -252,7 +252,7 @@ def main():
     norm_ms, clip_ms, grad_ms, noise_ms = phases
     nlayers = len(w.layers)
     if grad_ms >= norm_ms:
-        flops, byts, dur_ms, kname = work["gemm_flops"], work["gemm_bytes"], grad_ms, "clipped-sum GEMM (dp_clipped_grad)"
+        flops, byts, dur_ms, kname = work["gemm_flops"], work["gemm_bytes"], grad_ms, "clipped-sum GEMM with its split-K reduce (and the noise that the reduce adds, where the configuration has noise)"
     else:
         flops, byts, dur_ms, kname = work["norm_flops"], work["norm_bytes"], norm_ms, "squared-norm kernel (dp_layer_sqnorm)"
     peak_tf = PEAK_MFMA_TFLOPS[w.dtype]
