@@ -104,13 +104,22 @@ dp_status dp_layer_sqnorm(const void* A, const void* G,
  *              A and G are device pointers as in dp_layer_sqnorm; all layers
  *              share B, dtype and path
  *   workspace  device scratch of at least dp_layers_workspace_bytes(...) bytes
- * n_layers == 0 (or only empty layers) zero-fills sqnorm unless accumulating. */
+ * n_layers == 0 (or only empty layers) zero-fills sqnorm unless accumulating.
+ * A layer with bias_rows set also gets its bias term (Section 5.1, the bias
+ * gradient; summed over the positions that share the bias as in Eq.
+ * recurrent_gradient): bias_rows[i, :] = sum_t G_i[t, :] and ||bias_rows[i]||^2
+ * joins sqnorm[i].  For the layers that share Gram launches the sums are taken by
+ * the Gram kernel while G is on chip (no second pass over G); for the others
+ * dp_bias_sqnorm is run.  dp_clipped_bias_grad then folds the rows. */
 typedef struct {
     const void* A;              /* device, [B, T, d_in] */
     const void* G;              /* device, [B, T, d_out] */
     int64_t T, d_in, d_out;
     float* grad;                /* device, float32[d_in, d_out]: dp_layers_clipped_grad(_noise) only */
     uint64_t noise_offset;      /* position of grad[0] in the noise stream: dp_layers_clipped_grad_noise only */
+    float* bias_rows;           /* NULL, or device float32[B, d_out]: dp_layers_sqnorm(_clip) also writes the layer's
+                                   per-example bias gradients sum_t G_i[t, :] there and adds their squared norms (what
+                                   dp_bias_sqnorm does), for layers that have a bias */
 } dp_layer_desc;
 
 dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B,

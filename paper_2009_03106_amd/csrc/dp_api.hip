@@ -401,6 +401,7 @@ dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
         if (st != DP_OK) return st;
         if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (pointers && (!y.A || !y.G || !aligned16(y.A) || !aligned16(y.G))) return DP_ERR_INVALID_ARG;
+        if (pointers && y.bias_rows && B > 65535) return DP_ERR_UNSUPPORTED;                      // as dp_bias_sqnorm
     }
     return DP_OK;
 }
@@ -416,6 +417,7 @@ size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
             if (in_batch == kGramBatch) { in_batch = 0; batch = 0; }
             const GramPlan g = plan_gram_bf16((int)y.T, (int)y.d_in, (int)y.d_out);
             batch += (size_t)B * g.npairs * sizeof(float);
+            if (y.bias_rows) batch += (size_t)B * g.nt * (size_t)y.d_out * sizeof(float);      // column sums per row tile
             ++in_batch;
             if (batch > batch_max) batch_max = batch;
         } else {
@@ -482,6 +484,15 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (s1 != DP_OK) return s1;
         acc = 1; launched = true;
     }
+    // bias terms of the layers above (dense ones included): their own pass over G
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (!y.bias_rows || y.d_out == 0) continue;
+        if (y.T > 1 && y.d_in > 0 && gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;     // taken by the Gram kernel
+        const dp_status s1 = dp_bias_sqnorm(y.G, B, y.T, y.d_out, dtype, acc, sqnorm, y.bias_rows, hip_stream);
+        if (s1 != DP_OK) return s1;
+        acc = 1; launched = true;
+    }
     // the others, up to kGramBatch per launch, heaviest first inside a launch (the light ones fill its tail)
     GramLayerDesc batch[kGramBatch];
     int nb = 0;
@@ -495,7 +506,16 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
             while (j > 0 && (int64_t)(batch[j - 1].d_in + batch[j - 1].d_out) < wv) { batch[j] = batch[j - 1]; --j; }
             batch[j] = v;
         }
-        const hipError_t e = launch_gram_bf16_dma_layers(batch, nb, (int)B, acc != 0, sqnorm, static_cast<float*>(workspace),
+        // workspace: the launch's partial sums, then the column-sum scratch of its layers that have a bias
+        float* ws = static_cast<float*>(workspace);
+        size_t used = 0;
+        for (int i = 0; i < nb; ++i) used += (size_t)B * plan_gram_bf16(batch[i].T, batch[i].d_in, batch[i].d_out).npairs;
+        for (int i = 0; i < nb; ++i) {
+            if (!batch[i].bias_rows) continue;
+            batch[i].upart = ws + used;
+            used += (size_t)B * plan_gram_bf16(batch[i].T, batch[i].d_in, batch[i].d_out).nt * (size_t)batch[i].d_out;
+        }
+        const hipError_t e = launch_gram_bf16_dma_layers(batch, nb, (int)B, acc != 0, sqnorm, ws,
                                                          stream, dtype == DP_F16, C, last ? clip : nullptr);
         nb = 0; acc = 1; launched = true;
         return e;
@@ -505,7 +525,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (!gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
         if (nb == kGramBatch && flush(false) != hipSuccess) return DP_ERR_HIP;       // full, and another layer follows
-        batch[nb++] = GramLayerDesc{static_cast<const uint16_t*>(y.A), static_cast<const uint16_t*>(y.G), (int)y.T, (int)y.d_in, (int)y.d_out};
+        batch[nb++] = GramLayerDesc{static_cast<const uint16_t*>(y.A), static_cast<const uint16_t*>(y.G), (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, y.bias_rows};
     }
     const bool clip_in_finalize = clip != nullptr && nb > 0;
     if (flush(true) != hipSuccess) return DP_ERR_HIP;

@@ -191,6 +191,46 @@ hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, 
     return hipGetLastError();
 }
 
+// Bias rows from the per-row-tile column sums that the Gram kernel leaves behind:
+//     u[i, q] = sum_tt upart[i, tt, q]  (tt ascending),   s_i (+)= sum_q u[i, q]^2.
+// One workgroup of 1024 threads per example; thread t takes columns t, t + 1024, ... (the loads of a column's
+// tiles are independent, four in flight); the squares are added per thread in column order, then over each wave
+// and over the 16 waves in a fixed order.
+constexpr int kFoldThreads = 1024;
+__global__ __launch_bounds__(kFoldThreads) void k_bias_fold(const float* __restrict__ upart, int nt, int D, int accumulate,
+                                                            float* __restrict__ u, float* __restrict__ sqnorm) {
+    __shared__ float red[kFoldThreads / kWave];
+    const int ex = blockIdx.x, tid = threadIdx.x;
+    const float* p = upart + (size_t)ex * nt * D;
+    float acc = 0.f;
+    for (int q = tid; q < D; q += kFoldThreads) {
+        float v = 0.f;
+        int tt = 0;
+        for (; tt + 3 < nt; tt += 4) {
+            const float v0 = p[(size_t)tt * D + q], v1 = p[(size_t)(tt + 1) * D + q];
+            const float v2 = p[(size_t)(tt + 2) * D + q], v3 = p[(size_t)(tt + 3) * D + q];
+            v += v0; v += v1; v += v2; v += v3;
+        }
+        for (; tt < nt; ++tt) v += p[(size_t)tt * D + q];
+        u[(size_t)ex * D + q] = v;
+        acc += v * v;
+    }
+    acc = wave_sum(acc);
+    if ((tid & (kWave - 1)) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < kFoldThreads / kWave; ++w) t += red[w];
+        sqnorm[ex] = accumulate ? sqnorm[ex] + t : t;
+    }
+}
+
+hipError_t launch_bias_fold(const float* upart, int B, int nt, int D, bool accumulate, float* u, float* sqnorm, hipStream_t st) {
+    k_bias_fold<<<(unsigned)B, kFoldThreads, 0, st>>>(upart, nt, D, accumulate ? 1 : 0, u, sqnorm);
+    return hipGetLastError();
+}
+
 hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st) {
     k_rows_sqnorm<<<(unsigned)B, kWave, 0, st>>>(u, D, accumulate ? 1 : 0, sqnorm);
     return hipGetLastError();

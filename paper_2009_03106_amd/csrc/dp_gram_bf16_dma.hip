@@ -46,6 +46,7 @@ struct GramDmaLayer {
     int nt, npairs;
     int first;           // index of the layer's first item in partial[]; its items are partial[first + ex * npairs + slot]
     int per_xcd;         // items of this layer per XCD queue: ceil(B * npairs / 8)
+    float* upart;        // BIAS kernels: [B][nt][d_out] column sums of G over each row tile (nullptr: not wanted)
 };
 struct GramDmaArgs {
     GramDmaLayer layer[kGramBatch];
@@ -62,10 +63,20 @@ template <int N> __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_
 
 __device__ __forceinline__ int gram_swz(int r) { return CPR == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
 
-template <bool F16>
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+
+// BIAS: the diagonal pairs (every row tile belongs to exactly one) also take the column sums of their 128 rows of
+// G, sum_t G_i[t, :] over the tile, which is the tile's share of the example's bias gradient (Section 5.1: the
+// bias gradient is dLoss/dz, summed over the positions that share the bias): while a 64-column stage of G sits in
+// LDS, each wave multiplies a row of ones (zeros for rows beyond T) with the transpose of its 32 rows -- read with
+// the transposing LDS load -- on the matrix unit, 4 extra MFMAs next to the 16 of the stage; the four partial sums
+// meet in LDS and wave 0 writes the stage's 64 sums to upart.  The pass over G that a separate bias kernel needs
+// is saved.
+template <bool F16, bool BIAS>
 __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gram_bf16_dma(GramDmaArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[GNST * GSTAGE];
     __shared__ float red[4];
+    __shared__ float ub[BIAS ? 2 * 4 * GK : 1];          // [stage parity][wave][column of the stage]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // Work order.  Consecutive workgroup ids go round the 8 XCDs, so id & 7 names the XCD (and its L2) and
@@ -145,6 +156,52 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
 #pragma unroll
             for (int r = 0; r < 16; ++r) { accP[i][j][r] = 0.f; accQ[i][j][r] = 0.f; }
 
+    // ---- BIAS: operands of the column sums.  Wave w takes rows 32 w .. 32 w + 31 of the t-tile as two 16-row k steps.
+    const bool do_bias = BIAS && diag && ly.upart != nullptr;
+    bf16x8 ones[2];
+    int rdu[2];                                       // byte offset in the t-tile of this lane's piece: rows +0 / +4 of the first
+                                                      // k step, columns 0-31; second k step: + 16 rows, columns 32-63: ^ 64
+    f32x16 au[2];
+    bf16x8 fu[2];
+    if (BIAS) {
+        const int g16 = lane >> 4, s16 = lane & 15, half = g16 >> 1;
+        const uint32_t one = F16 ? 0x3C00u : 0x3F80u;
+#pragma unroll
+        for (int kl = 0; kl < 2; ++kl) {
+            const int k0 = (2 * wave + kl) * 16 + 8 * half;          // first of this lane's 8 rows
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = (tt * GT + k0 + 2 * e < ly.T) ? one : 0u, hi = (tt * GT + k0 + 2 * e + 1 < ly.T) ? one : 0u;
+                w[e] = lo | (hi << 16);
+            }
+            ones[kl] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+        }
+        const int na = 16 * (g16 & 1) + 4 * (s16 & 3);               // column (element) of the 8-byte piece
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int r = 2 * wave * 16 + 8 * half + (s16 >> 2) + 4 * h;
+            rdu[h] = r * ROWB + ((((na >> 3) ^ gram_swz(r)) << 4) | ((na & 7) << 1));
+        }
+    }
+    // this wave's 16 rows of k step kl, transposed: 8 rows x 32 columns per lane half, both 32-column blocks.
+    // Rows + 16 keep their chunk permutation ((r >> 1) & 7), columns + 32 flip bit 2 of the chunk index.
+    auto read_u = [&](int buf, int kl) {
+        LDS_PTR(unsigned char) b = (LDS_PTR(unsigned char))lds + buf * GSTAGE + kl * 16 * ROWB;
+#pragma unroll
+        for (int nf = 0; nf < 2; ++nf) {
+            const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + (rdu[0] ^ (nf << 6))));
+            const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(v4i16))(b + (rdu[1] ^ (nf << 6))));
+            fu[nf] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    // sums of stage `st` (written to ub by the four waves before the barrier that ended it) -> upart; wave 0 only
+    auto flush_u = [&](int st) {
+        const float* p = ub + (st & 1) * 4 * GK;
+        const float v = ((p[lane] + p[GK + lane]) + p[2 * GK + lane]) + p[3 * GK + lane];
+        ly.upart[((size_t)ex * ly.nt + tt) * ly.d_out + (size_t)(st - sa) * GK + lane] = v;
+    };
+
     // Software pipeline over k steps (4 per stage): the LDS reads of the next k step are in flight while the
     // MFMAs of the current one run, also across the stage boundary; the stage barrier sits in front of the
     // last k step of a stage, when every wave has retired its reads of that stage.
@@ -175,6 +232,14 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     auto stage = [&](int st, f32x16 (&acc)[2][2]) {
 #pragma unroll
         for (int ks = 0; ks < GK / 16; ++ks) {
+            if (BIAS && ks == GK / 16 - 1 && do_bias && st >= sa) {
+                // hand the stage's 64 column sums over, in front of the barrier that ends the stage (the MFMAs that
+                // made them were issued a k step ago).  Every row of the 32 x 32 result is the same; element 0 of
+                // lanes 0-31 is row 0, column lane.
+#pragma unroll
+                for (int nf = 0; nf < 2; ++nf)
+                    if (lane < 32) ub[(st & 1) * 4 * GK + wave * GK + nf * 32 + lane] = au[nf][0];
+            }
             __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): this k step's fragments (requested a k step ago)
             if (ks + 1 < GK / 16) {
                 read_kstep(f[(ks + 1) & 1], st % GNST, ks + 1);
@@ -187,6 +252,26 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
                 read_kstep(f[0], (st + 1) % GNST, 0);
             }
             mfma_kstep(f[ks & 1], acc);
+            if (BIAS && do_bias && st >= sa) {
+                // k step 0: request this wave's first 16 rows of the stage (transposed); 1 and 2: one 16-row step each
+                // on the matrix unit (1 also requests the second 16 rows).  All before the barrier in k step 3 that
+                // frees the buffer.
+                if (ks == 0) {
+                    if (wave == 0 && st > sa) flush_u(st - 1);
+                    read_u(st % GNST, 0);
+                } else if (ks == 1) {
+#pragma unroll
+                    for (int nf = 0; nf < 2; ++nf) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) au[nf][r] = 0.f;
+                        au[nf] = In16<F16>::mfma(ones[0], fu[nf], au[nf]);
+                    }
+                    read_u(st % GNST, 1);
+                } else if (ks == 2) {
+#pragma unroll
+                    for (int nf = 0; nf < 2; ++nf) au[nf] = In16<F16>::mfma(ones[1], fu[nf], au[nf]);
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -215,6 +300,7 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
             }
         }
     __syncthreads();
+    if (BIAS && do_bias && wave == 0) flush_u(n_stages - 1);
     s = block_sum_256(s, red);
     if (tid == 0) a.partial[(size_t)ly.first + (size_t)ex * ly.npairs + slot] = diag ? s : 2.0f * s;
 }
@@ -236,6 +322,7 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
     a.n_layers = n_layers; a.partial = partial; a.B = B;
     fin.n_layers = n_layers;
     int64_t first = 0, queue = 0;
+    bool any_bias = false;
     for (int l = 0; l < n_layers; ++l) {
         const GramPlan p = plan_gram_bf16(layers[l].T, layers[l].d_in, layers[l].d_out);
         GramDmaLayer& y = a.layer[l];
@@ -246,24 +333,35 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
         if (first + items >= (int64_t(1) << 31)) return hipErrorInvalidValue;
         y.first = (int)first;
         y.per_xcd = (int)((items + 7) / 8);
+        y.upart = layers[l].upart;
+        any_bias = any_bias || y.upart != nullptr;
         fin.first[l] = (int)first; fin.n[l] = p.npairs;
         first += items;
         queue += y.per_xcd;
     }
-    for (int l = n_layers; l < kGramBatch; ++l) a.layer[l] = GramDmaLayer{nullptr, nullptr, 0, 0, 0, 0, 0, 0, 0};
+    for (int l = n_layers; l < kGramBatch; ++l) a.layer[l] = GramDmaLayer{nullptr, nullptr, 0, 0, 0, 0, 0, 0, 0, nullptr};
     if (queue * 8 >= (int64_t(1) << 31)) return hipErrorInvalidValue;
     a.per_xcd = (int)queue;
-    if (f16) k_gram_bf16_dma<true><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
-    else     k_gram_bf16_dma<false><<<8u * (unsigned)a.per_xcd, kThreads, 0, st>>>(a);
+    const unsigned grid = 8u * (unsigned)a.per_xcd;
+    if (any_bias) { if (f16) k_gram_bf16_dma<true, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16_dma<false, true><<<grid, kThreads, 0, st>>>(a); }
+    else          { if (f16) k_gram_bf16_dma<true, false><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16_dma<false, false><<<grid, kThreads, 0, st>>>(a); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    // bias rows and their share of the norms first, so that the finalize kernel below (which may write the clip
+    // factors) sees complete sums
+    for (int l = 0; l < n_layers; ++l) {
+        if (!layers[l].upart) continue;
+        e = launch_bias_fold(layers[l].upart, B, a.layer[l].nt, layers[l].d_out, accumulate, layers[l].bias_rows, sqnorm, st);
+        if (e != hipSuccess) return e;
+        accumulate = true;
+    }
     return launch_finalize_layers(partial, fin, B, accumulate, sqnorm, st, C, clip);
 }
 
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
                                 bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
     (void)p;
-    const GramLayerDesc one{A, G, T, d_in, d_out};
+    const GramLayerDesc one{A, G, T, d_in, d_out, nullptr, nullptr};
     return launch_gram_bf16_dma_layers(&one, 1, B, accumulate, sqnorm, partial, st, f16);
 }
 

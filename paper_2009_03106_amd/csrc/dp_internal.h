@@ -35,6 +35,8 @@ hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st);
 // ---- bias parameters (dp_bias.hip)
 hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, int dt, float* u, float* u2, hipStream_t st);
+// u[i, :] = sum over nt row tiles of upart[i, tt, :];  s_i (+)= ||u[i, :]||^2
+hipError_t launch_bias_fold(const float* upart, int B, int nt, int D, bool accumulate, float* u, float* sqnorm, hipStream_t st);
 hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st);
 hipError_t launch_clipped_bias(const float* u, const float* clip, int B, int D, bool accumulate, float* grad_b, hipStream_t st);
 hipError_t launch_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64_t first, hipStream_t st);
@@ -94,7 +96,9 @@ struct GramPlan {
 };
 GramPlan plan_gram_bf16(int T, int d_in, int d_out);
 bool gram_dma_ok(int T, int d_in, int d_out);
-struct GramLayerDesc { const uint16_t* A; const uint16_t* G; int T, d_in, d_out; };
+// upart: nullptr, or [B][ceil(T / 128)][d_out] floats that receive the column sums of G over each 128-row tile
+// bias_rows: nullptr, or float32[B, d_out] that receives sum_t G_i[t, :] (then upart is its scratch and ||bias_rows_i||^2 joins the norm)
+struct GramLayerDesc { const uint16_t* A; const uint16_t* G; int T, d_in, d_out; float* upart; float* bias_rows; };
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
                                        float* partial, hipStream_t st, bool f16, float C = 0.f, float* clip = nullptr);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,

@@ -32,7 +32,8 @@ _lib = None
 class LayerDesc(ctypes.Structure):
     """dp_layer_desc of the header."""
     _fields_ = [("A", ctypes.c_void_p), ("G", ctypes.c_void_p), ("T", ctypes.c_int64), ("d_in", ctypes.c_int64),
-                ("d_out", ctypes.c_int64), ("grad", ctypes.c_void_p), ("noise_offset", ctypes.c_uint64)]
+                ("d_out", ctypes.c_int64), ("grad", ctypes.c_void_p), ("noise_offset", ctypes.c_uint64),
+                ("bias_rows", ctypes.c_void_p)]
 
 
 class DpclipError(RuntimeError):
@@ -185,11 +186,12 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
     return sqnorm
 
 
-def layer_descs(layers, grads=None, noise_offsets=None):
+def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None):
     """(ctypes array of dp_layer_desc, B, dtype code) for a list of (A, G) tensor pairs sharing B and dtype, with
     the float32 [d_in, d_out] output of each layer if grads is given (layers_clipped_grad needs them) and the position of
     each gradient in the noise stream if noise_offsets is given (default: the gradients laid out back to back in the order
-    of the list).
+    of the list).  bias_rows: one float32 [B, d_out] tensor (or None) per layer: layers_sqnorm then also writes the
+    per-example bias gradients there and counts their norms.
     The tensors must stay alive (and contiguous: the pointers are taken here) while the array is used."""
     if len(layers) == 0:
         raise ValueError("no layers")
@@ -213,7 +215,12 @@ def layer_descs(layers, grads=None, noise_offsets=None):
             if g.dtype != torch.float32 or tuple(g.shape) != (d_in, d_out):
                 raise ValueError("gradients must be float32 [d_in, d_out]")
             gp = _ptr(g)
-        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, running if noise_offsets is None else int(noise_offsets[i]))
+        bp = None
+        if bias_rows is not None and bias_rows[i] is not None:
+            if bias_rows[i].dtype != torch.float32 or tuple(bias_rows[i].shape) != (B, d_out):
+                raise ValueError("bias rows must be float32 [B, d_out]")
+            bp = _ptr(bias_rows[i])
+        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, running if noise_offsets is None else int(noise_offsets[i]), bp)
         running += d_in * d_out
     return arr, B0, dt0
 

@@ -120,6 +120,9 @@ def test_layers_workspace_sizes(lib):
     assert f(tr, 64, dpclip.DP_F32, "direct") == max(dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 64, *sh, dpclip.DP_F32, "direct")
                                             for sh in [(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)])
     assert f(tr, 64, dpclip.DP_F32, "gram") == 64 * 36 * 4
+    wb = descs([(512, 768, 2304), (512, 768, 768)])
+    wb[0].bias_rows = 16                    # any non-null value: only the sizes are looked at
+    assert f(wb, 64, dpclip.DP_BF16) == 2 * 64 * 10 * 4 + 64 * 4 * 2304 * 4     # + column sums per 128-row tile
     many = descs([(128, 64, 64)] * 20)
     assert f(many, 8, dpclip.DP_BF16, "gram") == 16 * 8 * 1 * 4           # launches of 16 and 4 layers reuse the space
     mixed = descs([(1, 64, 32), (1024, 576, 128), (0, 8, 8)])

@@ -318,6 +318,53 @@ def test_layers_sqnorm_with_clip_factors(dp, name, B):
     assert lib.dp_layers_sqnorm_clip(descs, len(descs), Bn, dt, 0, 0, s.data_ptr(), 0.0, c.data_ptr(), ws.data_ptr(), ws.numel(), None) == dp.DP_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_layers_sqnorm_with_bias_rows(dp, dtype):
+    """Weights and biases in one call: the layers that share Gram launches get their bias rows from the Gram kernel
+    (column sums of G taken per row tile on the matrix unit, ragged last tile masked), the others from the bias kernels;
+    both must match the oracle's rows, and the norms must contain the bias share."""
+    B = 5
+    shapes = [(1, 130, 67), (64, 576, 128), (200, 72, 264), (200, 128, 192), (128, 64, 320), (300, 256, 64), (0, 8, 8),
+              (72, 192, 128), (512, 768, 768)]
+    layers = [wl.random_layer(60 + i, B, T, di, do, dtype, g_row_scale=np.exp(np.linspace(-1, 1, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    s_ref = sum(orc.layer_sqnorm(A, G) + orc.bias_sqnorm(G) for (A, G), sh in zip(layers, shapes) if sh[0] > 0)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    rows = [torch.full((B, sh[2]), -7.0, device="cuda") for sh in shapes]
+    descs = dp.layer_descs(dev, bias_rows=rows)
+    c = torch.zeros(B, device="cuda")
+    Cc = float(np.sqrt(np.median(s_ref)))
+    s = dp.layers_sqnorm(dev, descs=descs, C=Cc, clip=c)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], rel_err(s.cpu().numpy(), s_ref)
+    assert rel_err(c.cpu().numpy(), orc.clip_factors(s_ref, Cc)) <= SQ_TOL[dtype]
+    for (A, G), sh, u in zip(layers, shapes, rows):
+        u_ref = orc.bias_rows(G) if sh[0] > 0 else np.zeros((B, sh[2]))
+        scale = np.abs(orc.widen(G)).reshape(B, -1, sh[2]).sum(axis=1) if sh[0] > 0 else np.ones((B, sh[2]))
+        assert np.all(np.abs(u.cpu().numpy() - u_ref) <= 2e-6 * np.maximum(scale, 1e-30)), sh
+    # only some layers with a bias, and accumulation onto existing norms
+    some = [r if i % 2 == 0 else None for i, r in enumerate(rows)]
+    s2 = torch.full((B,), 0.5, device="cuda")
+    dp.layers_sqnorm(dev, s2, accumulate=True, descs=dp.layer_descs(dev, bias_rows=some))
+    s2_ref = 0.5 + sum(orc.layer_sqnorm(A, G) + (orc.bias_sqnorm(G) if i % 2 == 0 else 0.0)
+                       for i, ((A, G), sh) in enumerate(zip(layers, shapes)) if sh[0] > 0)
+    assert rel_err(s2.cpu().numpy(), s2_ref) <= SQ_TIGHT[dtype]
+
+
+def test_bias_rows_from_the_gram_kernel_on_the_transformer_configuration(dp):
+    w, layers = wl.generate("transformer", B=8)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    rows = [torch.empty((8, G.shape[2]), device="cuda") for _, G in dev]
+    s = dp.layers_sqnorm(dev, descs=dp.layer_descs(dev, bias_rows=rows))
+    s_ref = orc.total_sqnorm(layers)
+    for (A, G), u in zip(layers, rows):
+        s_ref = s_ref + orc.bias_sqnorm(G)
+        u_sep = dp.bias_sqnorm(to_dev(G))[1]
+        scale = np.abs(orc.widen(G)).sum(axis=1)
+        assert np.all(np.abs(u.cpu().numpy() - orc.bias_rows(G)) <= 2e-6 * scale)
+        assert np.all(np.abs(u.cpu().numpy() - u_sep.cpu().numpy()) <= 2e-6 * scale)       # the stand-alone bias kernel
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["bf16"]
+
+
 def test_layers_call_more_layers_than_one_launch_takes(dp):
     B = 3
     layers = [wl.random_layer(300 + i, B, 96 + 32 * (i % 3), 64 * (1 + i % 2), 64 * (1 + (i // 2) % 3), "bf16",
