@@ -390,7 +390,7 @@ dp_status dp_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64
 
 namespace {
 
-// checks shared by dp_layers_sqnorm and its size query; *any_work: some layer is not empty
+// checks shared by the several-layers calls and their size queries
 dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path, bool pointers) {
     if (n_layers < 0 || B < 0 || (n_layers > 0 && !layers)) return DP_ERR_INVALID_ARG;
     if (!valid_dtype(dtype) || !valid_path(path)) return DP_ERR_INVALID_ARG;
