@@ -56,8 +56,26 @@ typedef enum {
 } dp_status;
 
 /* DP_F16 widens the library beyond what the paper ran (it used float32); it
- * is accepted wherever DP_BF16 is. */
-typedef enum { DP_F32 = 0, DP_BF16 = 1, DP_F16 = 2 } dp_dtype;
+ * is accepted wherever DP_BF16 is.
+ * The 8-bit types (one byte per element, the OCP 8-bit floating-point formats:
+ * e4m3 with bias 7, no infinities and the single NaN code S.1111.111; e5m2 with
+ * bias 15 and IEEE-style infinities and NaNs; subnormals in both) run on the
+ * 64-deep 8-bit matrix instruction, at twice the 16-bit rate:
+ *   DP_F8_E4M3       A and G e4m3
+ *   DP_F8_E5M2       A and G e5m2
+ *   DP_F8_E4M3_E5M2  A e4m3 (activations), G e5m2 (backpropagated gradients)
+ * Products of 8-bit values are exact in the fp32 accumulators' inputs, so the
+ * results differ from exact arithmetic on the stored values only by fp32
+ * summation.  They are taken by dp_layer_sqnorm (T > 64; GRAM: d_in and d_out
+ * multiples of 128; DIRECT: d_in and d_out multiples of 16 that tile into
+ * 256 x 256 or 128 x 128 blocks with at most a quarter of padding; AUTO takes the
+ * other path where only that one fits), by dp_clipped_grad and its noise variant
+ * (the DIRECT shapes; T a multiple of 64, or at most a quarter of padding up to
+ * the next one) and by the several-layers calls under the same limits and
+ * without bias_rows.  Every other entry point, and every other shape, returns
+ * DP_ERR_UNSUPPORTED for them (widen to DP_F16, which holds both formats
+ * exactly). */
+typedef enum { DP_F32 = 0, DP_BF16 = 1, DP_F16 = 2, DP_F8_E4M3 = 3, DP_F8_E5M2 = 4, DP_F8_E4M3_E5M2 = 5 } dp_dtype;
 
 /* How dp_layer_sqnorm evaluates ||A_i^T G_i||_F^2 when T > 1.
  *   DIRECT: a tile of g_i = sum_t outer(A_i[t], G_i[t]) is accumulated in

@@ -51,6 +51,39 @@ def widen(x: np.ndarray) -> np.ndarray:
     raise TypeError(f"unsupported storage dtype {x.dtype}")
 
 
+def f8_to_f64(bits: np.ndarray, fmt: str) -> np.ndarray:
+    """Bit patterns of an OCP 8-bit floating-point format -> float64, exactly,
+    from the formats' definition (OCP 8-bit Floating Point Specification): a
+    sign bit, E exponent bits with a bias and M mantissa bits;
+        exponent field 0:      (-1)^s * 2^(1 - bias) * (m / 2^M)        (zero and subnormals)
+        otherwise:             (-1)^s * 2^(e - bias) * (1 + m / 2^M)
+    "e4m3": E = 4, M = 3, bias 7; no infinities, and only the code with every
+            exponent and mantissa bit set is a NaN (so 1.75 * 2^8 = 448 is the largest value);
+    "e5m2": E = 5, M = 2, bias 15; exponent field 31 is infinity (m = 0) or NaN.
+    uint8 arrays carry no format of their own, so 8-bit inputs are widened with
+    this function before they are handed to the functions below."""
+    if fmt == "e4m3":
+        E, M, bias = 4, 3, 7
+    elif fmt == "e5m2":
+        E, M, bias = 5, 2, 15
+    else:
+        raise ValueError(fmt)
+    b = np.asarray(bits)
+    if b.dtype != np.uint8:
+        raise TypeError("8-bit patterns are uint8")
+    b = b.astype(np.int64)
+    s = b >> 7
+    e = (b >> M) & ((1 << E) - 1)
+    m = b & ((1 << M) - 1)
+    frac = m.astype(np.float64) / float(1 << M)
+    mag = np.where(e == 0, np.ldexp(frac, 1 - bias), np.ldexp(1.0 + frac, e - bias))
+    if fmt == "e4m3":
+        mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    else:
+        mag = np.where(e == 31, np.where(m == 0, np.inf, np.nan), mag)
+    return np.where(s == 1, -mag, mag)
+
+
 def _as3d(x: np.ndarray) -> np.ndarray:
     x = widen(x)
     if x.ndim == 2:              # dense layer given as [B, d]

@@ -11,8 +11,11 @@ namespace {
 constexpr int64_t kMaxRows = (int64_t(1) << 31) - 1;   // B*T
 constexpr int64_t kMaxDim = int64_t(1) << 24;          // d_in, d_out
 
-bool valid_dtype(dp_dtype d) { return d == DP_F32 || d == DP_BF16 || d == DP_F16; }
 bool is16(dp_dtype d) { return d == DP_BF16 || d == DP_F16; }
+bool is8(dp_dtype d) { return d == DP_F8_E4M3 || d == DP_F8_E5M2 || d == DP_F8_E4M3_E5M2; }
+bool valid_dtype(dp_dtype d) { return d == DP_F32 || is16(d) || is8(d); }
+// format code of the copy-pipeline launchers (16-bit and 8-bit types)
+int fmt_of(dp_dtype d) { return d == DP_BF16 ? 0 : d == DP_F16 ? 1 : d == DP_F8_E4M3 ? 2 : d == DP_F8_E5M2 ? 3 : 4; }
 bool valid_path(dp_path p) { return p == DP_PATH_AUTO || p == DP_PATH_GRAM || p == DP_PATH_DIRECT; }
 
 dp_status check_dims(int64_t B, int64_t T, int64_t d_in, int64_t d_out) {
@@ -25,26 +28,42 @@ dp_status check_dims(int64_t B, int64_t T, int64_t d_in, int64_t d_out) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// 8-bit types: the shapes that a path's kernels take (T > 1)
+bool f8_path_ok(dp_path p, dp_dtype dtype, int64_t T, int64_t d_in, int64_t d_out) {
+    if (T <= 1) return false;
+    if (p == DP_PATH_GRAM) return gram_dma_ok((int)T, (int)d_in, (int)d_out, fmt_of(dtype));
+    return dma8_direct_ok((int)T, (int)d_in, (int)d_out);
+}
+
 dp_path resolve_path(dp_path path, dp_dtype dtype, int64_t T, int64_t d_in, int64_t d_out) {
-    (void)dtype;
     if (path != DP_PATH_AUTO) return path;
-    return dp_choose_path(T, d_in, d_out);
+    const dp_path p = dp_choose_path(T, d_in, d_out);
+    if (is8(dtype) && !f8_path_ok(p, dtype, T, d_in, d_out)) {
+        // both paths give the same number: take the other one where only its kernels fit the shape
+        const dp_path other = p == DP_PATH_GRAM ? DP_PATH_DIRECT : DP_PATH_GRAM;
+        if (f8_path_ok(other, dtype, T, d_in, d_out)) return other;
+    }
+    return p;
 }
 
 // bytes of scratch for the squared-norm call on an already resolved path (T > 1)
 size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
+    if (is8(dtype) && !f8_path_ok(path, dtype, T, d_in, d_out)) return 0;
     if (path == DP_PATH_GRAM) {
-        GramPlan g = is16(dtype) ? plan_gram_bf16((int)T, (int)d_in, (int)d_out) : plan_gram_f32((int)T);
+        GramPlan g = (is16(dtype) || is8(dtype)) ? plan_gram_bf16((int)T, (int)d_in, (int)d_out) : plan_gram_f32((int)T);
         return (size_t)B * g.npairs * sizeof(float);
     }
-    TnPlan p = is16(dtype) ? plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out)
-                                  : plan_direct_f32((int)T, (int)d_in, (int)d_out);
+    TnPlan p = is8(dtype)  ? plan_direct_f8_dma((int)B, (int)T, (int)d_in, (int)d_out)
+             : is16(dtype) ? plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out)
+                           : plan_direct_f32((int)T, (int)d_in, (int)d_out);
     return (size_t)B * p.tiles_m * p.tiles_n * sizeof(float) + (p.zero_head ? kZeroHeadFloats * sizeof(float) : 0);
 }
 
 size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
-    TnPlan p = is16(dtype) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
-                                  : plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
+    if (is8(dtype) && !dma8_clipped_ok((int)T, (int)d_in, (int)d_out)) return 0;
+    TnPlan p = is8(dtype)  ? plan_clipped_f8_dma((int)B, (int)T, (int)d_in, (int)d_out)
+             : is16(dtype) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
+                           : plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
     const size_t head = p.zero_head ? kZeroHeadFloats * sizeof(float) : 0;
     if (p.splits <= 1) return head;
     return head + (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float);
@@ -52,9 +71,9 @@ size_t clipped_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dt
 
 // a layer that the batched Gram launch of dp_layers_sqnorm takes (everything else goes through dp_layer_sqnorm)
 bool gram_batchable(int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
-    if (T <= 1 || d_in == 0 || d_out == 0 || !is16(dtype)) return false;
+    if (T <= 1 || d_in == 0 || d_out == 0 || !(is16(dtype) || is8(dtype))) return false;
     if (resolve_path(path, dtype, T, d_in, d_out) != DP_PATH_GRAM) return false;
-    return gram_dma_ok((int)T, (int)d_in, (int)d_out);
+    return gram_dma_ok((int)T, (int)d_in, (int)d_out, fmt_of(dtype));
 }
 
 size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
@@ -129,16 +148,25 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
 
     hipError_t e;
     if (T == 1) {
+        if (is8(dtype)) return DP_ERR_UNSUPPORTED;
         e = launch_sqnorm_dense(A, G, (int)B, (int)d_in, (int)d_out, (int)dtype, accumulate != 0, sqnorm, stream);
         return e == hipSuccess ? DP_OK : DP_ERR_HIP;
     }
     const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
+    if (is8(dtype) && !f8_path_ok(p, dtype, T, d_in, d_out)) return DP_ERR_UNSUPPORTED;
     const size_t need = sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;           // > 2^31 partial sums
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
     float* partial = static_cast<float*>(workspace);
 
-    if (p == DP_PATH_GRAM && !is16(dtype)) {
+    if (is8(dtype)) {
+        if (p == DP_PATH_GRAM)
+            e = launch_gram_bf16_dma(plan_gram_bf16((int)T, (int)d_in, (int)d_out), A, G, (int)B, (int)T, (int)d_in, (int)d_out,
+                                     accumulate != 0, sqnorm, partial, stream, fmt_of(dtype));
+        else
+            e = launch_direct_f8_dma(plan_direct_f8_dma((int)B, (int)T, (int)d_in, (int)d_out), A, G, (int)B, (int)T, (int)d_in,
+                                     (int)d_out, accumulate != 0, sqnorm, partial, stream, fmt_of(dtype));
+    } else if (p == DP_PATH_GRAM && !is16(dtype)) {
         e = launch_gram_f32(plan_gram_f32((int)T), static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
     } else if (p == DP_PATH_GRAM) {
@@ -204,16 +232,21 @@ dp_status clipped_grad_noise(const void* A, const void* G, const float* clip, in
         return DP_OK;
     }
     if (!A || !G || !clip || !aligned16(A) || !aligned16(G)) return DP_ERR_INVALID_ARG;
+    if (is8(dtype) && !dma8_clipped_ok((int)T, (int)d_in, (int)d_out)) return DP_ERR_UNSUPPORTED;
     const size_t need = clipped_ws_bytes(B, T, d_in, d_out, dtype);
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
     float* ws = static_cast<float*>(workspace);
 
-    const TnPlan p = is16(dtype) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
+    const TnPlan p = is8(dtype)  ? plan_clipped_f8_dma((int)B, (int)T, (int)d_in, (int)d_out)
+                   : is16(dtype) ? plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out)
                                  : plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
     const NoiseArgs nz{stddev, (uint32_t)seed, (uint32_t)(seed >> 32), offset};
     const bool fused = noisy && p.splits > 1 && splitk_noise_ok(n, offset);
     hipError_t e;
-    if (is16(dtype)) {
+    if (is8(dtype)) {
+        e = launch_clipped_f8_dma(p, A, G, clip, (int)B, (int)T, (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream,
+                                  fmt_of(dtype), fused ? &nz : nullptr);
+    } else if (is16(dtype)) {
         e = launch_clipped_bf16(p, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), clip, (int)B, (int)T,
                                 (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, dtype == DP_F16, fused ? &nz : nullptr);
     } else {
@@ -233,7 +266,7 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_
     dp_status st = check_dims(B, T, 1, d_out);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
-    if (B >= 65536) return DP_ERR_UNSUPPORTED;
+    if (B >= 65536 || is8(dtype)) return DP_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (B == 0) return DP_OK;
     if (!sqnorm) return DP_ERR_INVALID_ARG;
@@ -258,7 +291,7 @@ dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_
     dp_status st = check_dims(B, T, 1, d);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
-    if (B >= 65536) return DP_ERR_UNSUPPORTED;
+    if (B >= 65536 || is8(dtype)) return DP_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (B == 0) return DP_OK;
     if (!sqnorm) return DP_ERR_INVALID_ARG;
@@ -391,7 +424,9 @@ dp_status dp_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64
 namespace {
 
 // checks shared by the several-layers calls and their size queries
-dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path, bool pointers) {
+// op: which call asks (the 8-bit types take only the shapes of their copy-pipeline kernels, and no bias rows)
+dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path, bool pointers,
+                       dp_op op) {
     if (n_layers < 0 || B < 0 || (n_layers > 0 && !layers)) return DP_ERR_INVALID_ARG;
     if (!valid_dtype(dtype) || !valid_path(path)) return DP_ERR_INVALID_ARG;
     if (n_layers > 4096) return DP_ERR_UNSUPPORTED;
@@ -400,6 +435,11 @@ dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
         const dp_status st = check_dims(B, y.T, y.d_in, y.d_out);
         if (st != DP_OK) return st;
         if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (is8(dtype)) {
+            if (op == DP_OP_SQNORM && (y.bias_rows || !f8_path_ok(resolve_path(path, dtype, y.T, y.d_in, y.d_out), dtype, y.T, y.d_in, y.d_out)))
+                return DP_ERR_UNSUPPORTED;
+            if (op == DP_OP_CLIPPED_GRAD && !dma8_clipped_ok((int)y.T, (int)y.d_in, (int)y.d_out)) return DP_ERR_UNSUPPORTED;
+        }
         if (pointers && (!y.A || !y.G || !aligned16(y.A) || !aligned16(y.G))) return DP_ERR_INVALID_ARG;
         if (pointers && y.bias_rows && B > 65535) return DP_ERR_UNSUPPORTED;                      // as dp_bias_sqnorm
     }
@@ -433,7 +473,7 @@ size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
 extern "C" {
 
 size_t dp_layers_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path) {
-    if (check_layers(layers, n_layers, B, dtype, path, false) != DP_OK) return 0;
+    if (check_layers(layers, n_layers, B, dtype, path, false, DP_OP_SQNORM) != DP_OK) return 0;
     return layers_ws_bytes(layers, n_layers, B, dtype, path);
 }
 
@@ -446,7 +486,7 @@ dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_
 dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path,
                                 int accumulate, float* sqnorm, float C, float* clip, void* workspace, size_t workspace_bytes,
                                 void* hip_stream) {
-    const dp_status st = check_layers(layers, n_layers, B, dtype, path, true);
+    const dp_status st = check_layers(layers, n_layers, B, dtype, path, true, DP_OP_SQNORM);
     if (st != DP_OK) return st;
     if (clip && !(C > 0.0f)) return DP_ERR_INVALID_ARG;
     if (B == 0) return DP_OK;
@@ -516,7 +556,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
             used += (size_t)B * plan_gram_bf16(batch[i].T, batch[i].d_in, batch[i].d_out).nt * (size_t)batch[i].d_out;
         }
         const hipError_t e = launch_gram_bf16_dma_layers(batch, nb, (int)B, acc != 0, sqnorm, ws,
-                                                         stream, dtype == DP_F16, C, last ? clip : nullptr);
+                                                         stream, fmt_of(dtype), C, last ? clip : nullptr);
         nb = 0; acc = 1; launched = true;
         return e;
     };
@@ -525,7 +565,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (!gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
         if (nb == kGramBatch && flush(false) != hipSuccess) return DP_ERR_HIP;       // full, and another layer follows
-        batch[nb++] = GramLayerDesc{static_cast<const uint16_t*>(y.A), static_cast<const uint16_t*>(y.G), (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, y.bias_rows};
+        batch[nb++] = GramLayerDesc{y.A, y.G, (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, y.bias_rows};
     }
     const bool clip_in_finalize = clip != nullptr && nb > 0;
     if (flush(true) != hipSuccess) return DP_ERR_HIP;
@@ -535,7 +575,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
 }
 
 size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype) {
-    if (check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, false) != DP_OK) return 0;
+    if (check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, false, DP_OP_CLIPPED_GRAD) != DP_OK) return 0;
     size_t need = 0;
     for (int64_t l = 0; l < n_layers; ++l) {
         const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, layers[l].T, layers[l].d_in, layers[l].d_out, dtype, DP_PATH_AUTO);
@@ -554,7 +594,7 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
                                        void* hip_stream) {
     // everything is checked before the first launch: an error leaves every output untouched
     if (!(stddev >= 0.0f)) return DP_ERR_INVALID_ARG;
-    const dp_status st = check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, true);
+    const dp_status st = check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, true, DP_OP_CLIPPED_GRAD);
     if (st != DP_OK) return st;
     size_t need = 0;
     for (int64_t l = 0; l < n_layers; ++l) {

@@ -1,5 +1,5 @@
-// Gram path of the per-example squared norm for aligned 16-bit (bf16 or fp16) layers
-// (d_in % 64 == 0, d_out % 64 == 0, T > 64):
+// Gram path of the per-example squared norm for aligned 16-bit (bf16 or fp16) and 8-bit (OCP e4m3 / e5m2) layers
+// (d_in and d_out multiples of 128 bytes of elements: 64 for the 16-bit types, 128 for the 8-bit ones; T > 64):
 //     ||A_i^T G_i||_F^2 = sum_{t,s} (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}.
 // Same decomposition as the generic Gram kernel (one workgroup per example
 // and upper-triangular pair of 128-row tiles, both Gram tiles kept in MFMA
@@ -19,13 +19,15 @@
 // masked out of the final product.
 #include "dp_common.h"
 #include "dp_internal.h"
+#include <type_traits>
 
 namespace dpk {
 
 namespace {
 
 constexpr int GT = 128;                 // rows of T per tile
-constexpr int GK = 64;                  // contraction elements per stage (128 B per row = one cache line)
+constexpr int GK = 64;                  // contraction elements per stage, 16-bit types (128 B per row = one cache line)
+constexpr int GK8 = 128;                // ... 8-bit types: the same 128 B
 constexpr int ROWB = GK * 2;            // bytes per tile row in LDS
 constexpr int CPR = ROWB / 16;          // 16-byte chunks per row
 constexpr int RPI = 64 / CPR;           // rows per copy instruction (1 KB)
@@ -40,8 +42,8 @@ constexpr int GNST = 2;                 // stages resident in LDS (64 KB: two wo
 // One launch covers up to kGramBatch layers: their (example, pair) work items form one list, so that the tail of
 // one layer's work (10 items per example at T = 512 against 512 resident workgroups) is filled by the next layer's.
 struct GramDmaLayer {
-    const uint16_t* A;
-    const uint16_t* G;
+    const unsigned char* A;
+    const unsigned char* G;
     int T, d_in, d_out;
     int nt, npairs;
     int first;           // index of the layer's first item in partial[]; its items are partial[first + ex * npairs + slot]
@@ -64,6 +66,17 @@ template <int N> __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_
 __device__ __forceinline__ int gram_swz(int r) { return CPR == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef int v8i32 __attribute__((ext_vector_type(8)));
+
+// Input formats.  0: bf16, 1: fp16 (v_mfma_f32_32x32x16_{bf16,f16}); 2: A and G e4m3, 3: A and G e5m2, 4: A e4m3 and
+// G e5m2 (v_mfma_f32_32x32x64_f8f6f4, whose format fields take 0 for e4m3 and 1 for e5m2).  Both operands of a Gram
+// product come from the same matrix, so one field value per phase serves both.
+__host__ __device__ constexpr bool fmt_is8(int fmt) { return fmt >= 2; }
+__host__ __device__ constexpr int fmt8_of_A(int fmt) { return fmt == 3 ? 1 : 0; }
+__host__ __device__ constexpr int fmt8_of_G(int fmt) { return fmt >= 3 ? 1 : 0; }
+template <int F8> __device__ __forceinline__ f32x16 mfma8(v8i32 x, v8i32 y, f32x16 c) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(x, y, c, F8, F8, 0, 0, 0, 0);
+}
 
 // BIAS: the diagonal pairs (every row tile belongs to exactly one) also take the column sums of their 128 rows of
 // G, sum_t G_i[t, :] over the tile, which is the tile's share of the example's bias gradient (Section 5.1: the
@@ -72,8 +85,12 @@ typedef short v4i16 __attribute__((ext_vector_type(4)));
 // the transposing LDS load -- on the matrix unit, 4 extra MFMAs next to the 16 of the stage; the four partial sums
 // meet in LDS and wave 0 writes the stage's 64 sums to upart.  The pass over G that a separate bias kernel needs
 // is saved.
-template <bool F16, bool BIAS>
+template <int FMT, bool BIAS>
 __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gram_bf16_dma(GramDmaArgs a) {
+    constexpr bool F16 = FMT == 1, F8 = fmt_is8(FMT);
+    constexpr int ES = F8 ? 1 : 2;                       // bytes per element
+    constexpr int GKE = ROWB / ES;                       // elements per stage
+    static_assert(!(F8 && BIAS), "the column sums are built for the 16-bit types");
     __shared__ __attribute__((aligned(1024))) unsigned char lds[GNST * GSTAGE];
     __shared__ float red[4];
     __shared__ float ub[BIAS ? 2 * 4 * GK : 1];          // [stage parity][wave][column of the stage]
@@ -99,7 +116,7 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     const int ss = tt + pair;
     const bool diag = (tt == ss);
 
-    const int sa = ly.d_in / GK, sg = ly.d_out / GK;      // stages of the A phase and of the G phase
+    const int sa = ly.d_in / GKE, sg = ly.d_out / GKE;    // stages of the A phase and of the G phase
     const int n_stages = sa + sg;
 
     // ---- copies: wave w moves rows 32w .. 32w+31 of the t-tile and of the s-tile, 4 instructions each
@@ -113,16 +130,16 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         const int r = wave * 32 + u * RPI + lrow8;                     // row inside the tile
         const uint32_t c16 = (uint32_t)((cp ^ gram_swz(r)) << 4);      // source chunk for this LDS slot
         const uint32_t rt = (uint32_t)min(tt * GT + r, ly.T - 1), rs = (uint32_t)min(ss * GT + r, ly.T - 1);
-        off_t[0][u] = rt * (uint32_t)ly.d_in * 2u + c16;  off_s[0][u] = rs * (uint32_t)ly.d_in * 2u + c16;
-        off_t[1][u] = rt * (uint32_t)ly.d_out * 2u + c16; off_s[1][u] = rs * (uint32_t)ly.d_out * 2u + c16;
+        off_t[0][u] = rt * (uint32_t)ly.d_in * ES + c16;  off_s[0][u] = rs * (uint32_t)ly.d_in * ES + c16;
+        off_t[1][u] = rt * (uint32_t)ly.d_out * ES + c16; off_s[1][u] = rs * (uint32_t)ly.d_out * ES + c16;
     }
-    const uint16_t* baseA = ly.A + (size_t)ex * ly.T * ly.d_in;          // uniform example bases; lane offsets stay 32-bit
-    const uint16_t* baseG = ly.G + (size_t)ex * ly.T * ly.d_out;
+    const unsigned char* baseA = ly.A + (size_t)ex * ly.T * ly.d_in * ES;    // uniform example bases; lane offsets stay 32-bit
+    const unsigned char* baseG = ly.G + (size_t)ex * ly.T * ly.d_out * ES;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_base + wave * 32 * ROWB);
     // The copies are inline assembly so that the compiler does not tie every LDS read to them; they are
     // waited for with the explicit vmcnt wait in front of the stage barrier.
-    auto issue_phase = [&](const uint16_t* sbase, const uint32_t (&ot)[IPT], const uint32_t (&os)[IPT], int buf) {
+    auto issue_phase = [&](const unsigned char* sbase, const uint32_t (&ot)[IPT], const uint32_t (&os)[IPT], int buf) {
         const uint32_t base = wave_lds + buf * GSTAGE;
 #pragma unroll
         for (int u = 0; u < IPT; ++u)
@@ -134,8 +151,8 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         }
     };
     auto issue = [&](int st, int buf) {
-        if (st < sa) issue_phase(baseA + st * GK, off_t[0], off_s[0], buf);
-        else issue_phase(baseG + (st - sa) * GK, off_t[1], off_s[1], buf);
+        if (st < sa) issue_phase(baseA + st * ROWB, off_t[0], off_s[0], buf);
+        else issue_phase(baseG + (st - sa) * ROWB, off_t[1], off_s[1], buf);
     };
 
     // ---- MFMA roles: 2 x 2 waves, each owns 64 x 64 of the 128 x 128 tile pair
@@ -276,14 +293,56 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         }
     };
 
+    // 8-bit types: a stage row holds 128 elements = two k steps of the 64-deep MFMA.  A lane's 32 bytes of a k step
+    // are the two 16-byte pieces that the 16-bit path reads in its k steps 2 K and 2 K + 1 (elements 16 h .. 16 h + 15
+    // and 32 + 16 h .. of the 64, h = lane / 32): which k a byte position stands for does not matter as long as both
+    // operands agree, and they are read the same way.
+    v8i32 f8[2][4];
+    auto read_k8 = [&](v8i32 (&g)[4], int buf, int K) {
+        const unsigned char* sb = lds + buf * GSTAGE;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int o = x < 2 ? rd_t[x] : rd_s[x - 2];
+            const uint4 lo = *reinterpret_cast<const uint4*>(sb + (o ^ ((2 * K) << 5)));
+            const uint4 hi = *reinterpret_cast<const uint4*>(sb + (o ^ ((2 * K + 1) << 5)));
+            g[x] = v8i32{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+        }
+    };
+    auto stage8 = [&](int st, f32x16 (&acc)[2][2], auto tag) {
+        constexpr int F = decltype(tag)::value;
+#pragma unroll
+        for (int K = 0; K < 2; ++K) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): this k step's fragments (requested a k step ago)
+            if (K == 0) {
+                read_k8(f8[1], st % GNST, 1);
+            } else if (st + 1 < n_stages) {
+                wait_copies(min(n_stages - 2 - st, GNST - 2));
+                __builtin_amdgcn_s_barrier();
+                if (st + GNST < n_stages) issue(st + GNST, st % GNST);
+                read_k8(f8[0], (st + 1) % GNST, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma8<F>(f8[K][i], f8[K][2 + j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
 #pragma unroll
     for (int p = 0; p < GNST; ++p)
         if (p < n_stages) issue(p, p);
     wait_copies(min(n_stages, GNST) - 1);                        // stage 0 must have landed
     __builtin_amdgcn_s_barrier();
-    read_kstep(f[0], 0, 0);
-    for (int st = 0; st < sa; ++st) stage(st, accP);              // A A^T tile
-    for (int st = sa; st < n_stages; ++st) stage(st, accQ);       // G G^T tile
+    if constexpr (F8) {
+        read_k8(f8[0], 0, 0);
+        for (int st = 0; st < sa; ++st) stage8(st, accP, std::integral_constant<int, fmt8_of_A(FMT)>{});
+        for (int st = sa; st < n_stages; ++st) stage8(st, accQ, std::integral_constant<int, fmt8_of_G(FMT)>{});
+    } else {
+        read_kstep(f[0], 0, 0);
+        for (int st = 0; st < sa; ++st) stage(st, accP);              // A A^T tile
+        for (int st = sa; st < n_stages; ++st) stage(st, accQ);       // G G^T tile
+    }
 
     // ---- sum of the elementwise product; rows / columns beyond T are masked (their tiles hold clamped rows)
     float s = 0.f;
@@ -307,16 +366,17 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
 
 }  // namespace
 
-bool gram_dma_ok(int T, int d_in, int d_out) {
+bool gram_dma_ok(int T, int d_in, int d_out, int fmt) {
     const int64_t dmax = d_in > d_out ? d_in : d_out;
-    return T > 64 && (d_in % GK) == 0 && (d_out % GK) == 0 && (int64_t)T * dmax * 2 < (int64_t(1) << 31);   // 32-bit lane offsets
+    const int es = fmt_is8(fmt) ? 1 : 2, gke = ROWB / es;
+    return T > 64 && (d_in % gke) == 0 && (d_out % gke) == 0 && (int64_t)T * dmax * es < (int64_t(1) << 31);   // 32-bit lane offsets
 }
 
 // Several layers in one launch (at most kGramBatch, every one passing gram_dma_ok); partial gets the layers' item
 // lists one after the other, in the order given, and the sums go to sqnorm in that order.
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
-                                       float* partial, hipStream_t st, bool f16, float C, float* clip) {
-    if (n_layers < 1 || n_layers > kGramBatch) return hipErrorInvalidValue;
+                                       float* partial, hipStream_t st, int fmt, float C, float* clip) {
+    if (n_layers < 1 || n_layers > kGramBatch || fmt < 0 || fmt > 4) return hipErrorInvalidValue;
     GramDmaArgs a;
     FinalizeLayers fin;
     a.n_layers = n_layers; a.partial = partial; a.B = B;
@@ -326,7 +386,7 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
     for (int l = 0; l < n_layers; ++l) {
         const GramPlan p = plan_gram_bf16(layers[l].T, layers[l].d_in, layers[l].d_out);
         GramDmaLayer& y = a.layer[l];
-        y.A = layers[l].A; y.G = layers[l].G;
+        y.A = static_cast<const unsigned char*>(layers[l].A); y.G = static_cast<const unsigned char*>(layers[l].G);
         y.T = layers[l].T; y.d_in = layers[l].d_in; y.d_out = layers[l].d_out;
         y.nt = p.nt; y.npairs = p.npairs;
         const int64_t items = (int64_t)B * p.npairs;
@@ -343,8 +403,15 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
     if (queue * 8 >= (int64_t(1) << 31)) return hipErrorInvalidValue;
     a.per_xcd = (int)queue;
     const unsigned grid = 8u * (unsigned)a.per_xcd;
-    if (any_bias) { if (f16) k_gram_bf16_dma<true, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16_dma<false, true><<<grid, kThreads, 0, st>>>(a); }
-    else          { if (f16) k_gram_bf16_dma<true, false><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16_dma<false, false><<<grid, kThreads, 0, st>>>(a); }
+    if (any_bias) {
+        if (fmt == 0) k_gram_bf16_dma<0, true><<<grid, kThreads, 0, st>>>(a);
+        else if (fmt == 1) k_gram_bf16_dma<1, true><<<grid, kThreads, 0, st>>>(a);
+        else return hipErrorInvalidValue;                     // 8-bit types: the caller takes the bias rows in a pass of their own
+    } else if (fmt == 0) k_gram_bf16_dma<0, false><<<grid, kThreads, 0, st>>>(a);
+    else if (fmt == 1) k_gram_bf16_dma<1, false><<<grid, kThreads, 0, st>>>(a);
+    else if (fmt == 2) k_gram_bf16_dma<2, false><<<grid, kThreads, 0, st>>>(a);
+    else if (fmt == 3) k_gram_bf16_dma<3, false><<<grid, kThreads, 0, st>>>(a);
+    else               k_gram_bf16_dma<4, false><<<grid, kThreads, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // bias rows and their share of the norms first, so that the finalize kernel below (which may write the clip
@@ -358,11 +425,11 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
     return launch_finalize_layers(partial, fin, B, accumulate, sqnorm, st, C, clip);
 }
 
-hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
+hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt) {
     (void)p;
     const GramLayerDesc one{A, G, T, d_in, d_out, nullptr, nullptr};
-    return launch_gram_bf16_dma_layers(&one, 1, B, accumulate, sqnorm, partial, st, f16);
+    return launch_gram_bf16_dma_layers(&one, 1, B, accumulate, sqnorm, partial, st, fmt);
 }
 
 }  // namespace dpk

@@ -79,6 +79,16 @@ TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
                                   const ConvGeom* cg, const uint16_t* zero, bool f16);
+// 8-bit inputs (dp_tn_f8_dma.hip); fmt: 2 = A and G e4m3, 3 = A and G e5m2, 4 = A e4m3 and G e5m2
+bool dma8_clipped_ok(int T, int M, int N);
+bool dma8_direct_ok(int T, int M, int N);
+TnPlan plan_clipped_f8_dma(int B, int T, int M, int N);
+TnPlan plan_direct_f8_dma(int B, int T, int M, int N);
+hipError_t launch_clipped_f8_dma(const TnPlan& p, const void* A, const void* G, const float* clip,
+                                 int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
+                                 int fmt, const NoiseArgs* noise);
+hipError_t launch_direct_f8_dma(const TnPlan& p, const void* A, const void* G, int B, int T, int M, int N,
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
                               const NoiseArgs* noise);
@@ -95,14 +105,15 @@ struct GramPlan {
     int npairs;   // nt*(nt+1)/2 upper-triangular tile pairs per example
 };
 GramPlan plan_gram_bf16(int T, int d_in, int d_out);
-bool gram_dma_ok(int T, int d_in, int d_out);
+// fmt (copy-pipeline launchers): 0 = bf16, 1 = fp16, 2 = A and G e4m3, 3 = A and G e5m2, 4 = A e4m3 and G e5m2
+bool gram_dma_ok(int T, int d_in, int d_out, int fmt = 0);
 // upart: nullptr, or [B][ceil(T / 128)][d_out] floats that receive the column sums of G over each 128-row tile
 // bias_rows: nullptr, or float32[B, d_out] that receives sum_t G_i[t, :] (then upart is its scratch and ||bias_rows_i||^2 joins the norm)
-struct GramLayerDesc { const uint16_t* A; const uint16_t* G; int T, d_in, d_out; float* upart; float* bias_rows; };
+struct GramLayerDesc { const void* A; const void* G; int T, d_in, d_out; float* upart; float* bias_rows; };
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
-                                       float* partial, hipStream_t st, bool f16, float C = 0.f, float* clip = nullptr);
-hipError_t launch_gram_bf16_dma(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
+                                       float* partial, hipStream_t st, int fmt, float C = 0.f, float* clip = nullptr);
+hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt);
 // float32 inputs (dp_gram_f32.hip): 64-row tiles
 GramPlan plan_gram_f32(int T);
 hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, int B, int T, int d_in, int d_out,

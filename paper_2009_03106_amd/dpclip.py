@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libdpclip.so")
 
 DP_OK = 0
 DP_ERR_INVALID_ARG, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_HIP = 1, 2, 3, 4
-DP_F32, DP_BF16, DP_F16 = 0, 1, 2
+DP_F32, DP_BF16, DP_F16, DP_F8_E4M3, DP_F8_E5M2, DP_F8_E4M3_E5M2 = 0, 1, 2, 3, 4, 5
 DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
@@ -106,13 +106,22 @@ def _check(status: int, where: str) -> None:
         raise DpclipError(status, where)
 
 
-def _dtype_code(t: torch.Tensor) -> int:
+def _dtype_code(t: torch.Tensor, G: Optional[torch.Tensor] = None) -> int:
+    """Library code of a tensor's type; with G, of the (A, G) pair: both of one type, or A e4m3 with G e5m2."""
+    if G is not None and G.dtype != t.dtype:
+        if t.dtype == torch.float8_e4m3fn and G.dtype == torch.float8_e5m2:
+            return DP_F8_E4M3_E5M2
+        raise TypeError(f"unsupported pair of dtypes {t.dtype}, {G.dtype}")
     if t.dtype == torch.float32:
         return DP_F32
     if t.dtype == torch.bfloat16:
         return DP_BF16
     if t.dtype == torch.float16:
         return DP_F16
+    if t.dtype == torch.float8_e4m3fn:
+        return DP_F8_E4M3
+    if t.dtype == torch.float8_e5m2:
+        return DP_F8_E5M2
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
@@ -142,8 +151,9 @@ def _shape3(A: torch.Tensor, G: torch.Tensor):
         A = A.unsqueeze(1)
     if G.dim() == 2:
         G = G.unsqueeze(1)
-    if A.dim() != 3 or G.dim() != 3 or A.shape[:2] != G.shape[:2] or A.dtype != G.dtype:
-        raise ValueError("A must be [B,T,d_in] and G [B,T,d_out] of one dtype")
+    if A.dim() != 3 or G.dim() != 3 or A.shape[:2] != G.shape[:2]:
+        raise ValueError("A must be [B,T,d_in] and G [B,T,d_out]")
+    _dtype_code(A, G)                       # one dtype, or the e4m3 / e5m2 pair
     B, T, d_in = A.shape
     return A, G, int(B), int(T), int(d_in), int(G.shape[2])
 
@@ -173,7 +183,7 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
     """sqnorm[i] (+)= ||A_i^T G_i||_F^2 via dp_layer_sqnorm."""
     lib = load_library()
     A, G, B, T, d_in, d_out = _shape3(A, G)
-    dt = _dtype_code(A)
+    dt = _dtype_code(A, G)
     if sqnorm is None:
         if accumulate:
             raise ValueError("accumulate needs an existing sqnorm tensor")
@@ -204,7 +214,7 @@ def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None):
         if not (A.is_contiguous() and G.is_contiguous()):
             raise ValueError("layer tensors must be contiguous")
         A, G, B, T, d_in, d_out = _shape3(A, G)
-        dt = _dtype_code(A)
+        dt = _dtype_code(A, G)
         if B0 is None:
             B0, dt0 = B, dt
         elif (B, dt) != (B0, dt0):
@@ -295,7 +305,7 @@ def clipped_grad(A: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, grad: Opt
     """grad (+)= sum_i clip[i] A_i^T G_i, float32 [d_in, d_out], via dp_clipped_grad."""
     lib = load_library()
     A, G, B, T, d_in, d_out = _shape3(A, G)
-    dt = _dtype_code(A)
+    dt = _dtype_code(A, G)
     if grad is None:
         if accumulate:
             raise ValueError("accumulate needs an existing grad tensor")

@@ -16,6 +16,8 @@ Layouts: A is [B, T, d_in], G is [B, T, d_out], row-major, example-major.
 fp32 tensors are numpy float32.  bf16 tensors are numpy uint16 holding the
 upper 16 bits of the float32 value after round-to-nearest-even.  fp16 tensors
 (dtype "f16", an override of a configuration's own type) are numpy float16.
+8-bit tensors (dtypes "f8e4m3", "f8e5m2", and "f8" = A e4m3 with G e5m2; also
+overrides) are numpy uint8 holding the bit patterns of the OCP 8-bit formats.
 """
 from __future__ import annotations
 
@@ -95,6 +97,28 @@ def _draw(rng: np.random.Generator, shape, dist: str, std: float = 1.0) -> np.nd
     return x
 
 
+F8_MAX = {"e4m3": 448.0, "e5m2": 57344.0}   # largest finite values of the two OCP 8-bit formats
+
+
+def f32_to_f8_bits(x: np.ndarray, fmt: str) -> np.ndarray:
+    """Round float32 to an OCP 8-bit float ("e4m3": torch.float8_e4m3fn, "e5m2": torch.float8_e5m2; nearest, ties to
+    even, magnitudes beyond the largest finite value saturate to it); returns the uint8 bit patterns."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).clamp(-F8_MAX[fmt], F8_MAX[fmt])
+    t8 = t.to(torch.float8_e4m3fn if fmt == "e4m3" else torch.float8_e5m2)
+    return t8.view(torch.uint8).numpy().copy()
+
+
+def f8_formats(dtype: str) -> Tuple[str, str]:
+    """Storage types of (A, G) for the 8-bit dtype names: "f8e4m3" and "f8e5m2" store both alike, "f8" stores the
+    activations A as e4m3 and the backpropagated gradients G as e5m2."""
+    if dtype == "f8":
+        return "f8e4m3", "f8e5m2"
+    if dtype in ("f8e4m3", "f8e5m2"):
+        return dtype, dtype
+    raise ValueError(dtype)
+
+
 def _store(x: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "f32":
         return x
@@ -102,6 +126,8 @@ def _store(x: np.ndarray, dtype: str) -> np.ndarray:
         return f32_to_bf16_bits(x)
     if dtype == "f16":
         return x.astype(np.float16)           # numpy rounds to nearest even
+    if dtype in ("f8e4m3", "f8e5m2"):
+        return f32_to_f8_bits(x, dtype[2:])
     raise ValueError(dtype)
 
 
@@ -112,7 +138,8 @@ def make_layer(rng: np.random.Generator, B: int, spec: LayerSpec, dtype: str,
     G = _draw(rng, (B, spec.T, spec.d_out), "normal", g_std)
     if g_row_scale is not None:
         G *= g_row_scale.astype(np.float32)[:, None, None]
-    return _store(A, dtype), _store(G, dtype)
+    da, dg = f8_formats(dtype) if dtype.startswith("f8") else (dtype, dtype)
+    return _store(A, da), _store(G, dg)
 
 
 def generate(name: str, B: int | None = None, straddle: bool = False,

@@ -1,0 +1,200 @@
+"""Parity of the 8-bit (OCP e4m3 / e5m2) inputs of the HIP path against the CPU oracle.  Needs a real MI355X.
+
+The oracle works on the stored bytes widened exactly to float64 (oracle f8_to_f64).  A product of two 8-bit values
+has at most 8 significant bits, so it enters the fp32 accumulation exactly; what remains is the fp32 summation
+(order and rounding) of the matrix unit and of the partial sums:
+  squared norms   rel 2e-4
+  clipped grad    rel Frobenius 2e-4
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dp_oracle as orc
+from paper_2009_03106_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SQ_TOL8 = 2e-4
+FRO_TOL8 = 2e-4
+TORCH8 = {"f8e4m3": torch.float8_e4m3fn, "f8e5m2": torch.float8_e5m2}
+# G is drawn with a standard deviation of 1e-3: in e4m3 that lies below the normal range (2^-6), so it gets a
+# loss scale; e5m2 reaches down to 2^-14
+G_SCALE = {"f8e4m3": 256.0, "f8e5m2": 1.0, "f8": 1.0}
+DTYPES = ["f8e4m3", "f8e5m2", "f8"]
+
+
+@pytest.fixture(scope="module")
+def dp():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2009_03106_amd import dpclip
+    dpclip.load_library()
+    return dpclip
+
+
+def to_dev8(bits: np.ndarray, store: str) -> torch.Tensor:
+    assert bits.dtype == np.uint8
+    return torch.from_numpy(bits).cuda().view(TORCH8[store])
+
+
+def wide(bits: np.ndarray, store: str) -> np.ndarray:
+    return orc.f8_to_f64(bits, store[2:])
+
+
+def rel_err(got, ref) -> float:
+    return float(np.max(np.abs(got.astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-300)))
+
+
+def fro_err(got, ref) -> float:
+    return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def draw(seed, B, T, d_in, d_out, dtype, g_std=1e-3):
+    """One layer: A half zeros (post-ReLU), G Gaussian with per-example scales; stored bits, widened copies, device tensors."""
+    rng = np.random.default_rng(seed)
+    A = np.maximum(rng.standard_normal((B, T, d_in), dtype=np.float32), 0)
+    G = rng.standard_normal((B, T, d_out), dtype=np.float32) * np.float32(g_std * G_SCALE[dtype])
+    G *= (0.25 + 2.0 * rng.random((B, 1, 1), dtype=np.float32))
+    sa, sg = wl.f8_formats(dtype)
+    Ab, Gb = wl.f32_to_f8_bits(A, sa[2:]), wl.f32_to_f8_bits(G, sg[2:])
+    return (wide(Ab, sa), wide(Gb, sg)), (to_dev8(Ab, sa), to_dev8(Gb, sg))
+
+
+GRAM_SHAPES = [(3, 256, 256, 384), (2, 200, 128, 256), (2, 512, 768, 768), (4, 65, 128, 128), (5, 129, 384, 128)]
+DIRECT_SHAPES = [(3, 128, 256, 256), (2, 192, 128, 384), (2, 112, 256, 128), (3, 64, 512, 256), (2, 168, 240, 256),
+                 (9, 64, 1024, 768), (2, 320, 240, 128)]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", GRAM_SHAPES)
+def test_f8_gram_sqnorm(dp, dtype, shape):
+    B, T, d_in, d_out = shape
+    (A, G), (Ad, Gd) = draw(11, B, T, d_in, d_out, dtype)
+    ref = orc.layer_sqnorm(A, G)
+    s = dp.layer_sqnorm(Ad, Gd, path="gram").cpu().numpy()
+    assert rel_err(s, ref) <= SQ_TOL8, rel_err(s, ref)
+    # accumulate on top of an earlier value
+    base = torch.full((B,), 3.0, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, base, path="gram", accumulate=True)
+    assert rel_err(base.cpu().numpy(), ref + 3.0) <= SQ_TOL8
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", DIRECT_SHAPES)
+def test_f8_direct_sqnorm(dp, dtype, shape):
+    B, T, d_in, d_out = shape
+    (A, G), (Ad, Gd) = draw(12, B, T, d_in, d_out, dtype)
+    ref = orc.layer_sqnorm(A, G)
+    s = dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy()
+    assert rel_err(s, ref) <= SQ_TOL8, rel_err(s, ref)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", DIRECT_SHAPES + [(40, 256, 256, 256), (70, 64, 128, 128)])
+def test_f8_clipped_grad(dp, dtype, shape):
+    B, T, d_in, d_out = shape
+    (A, G), (Ad, Gd) = draw(13, B, T, d_in, d_out, dtype)
+    rng = np.random.default_rng(5)
+    clip = np.where(rng.random(B) < 0.4, 1.0, 0.05 + 0.9 * rng.random(B)).astype(np.float32)
+    ref = orc.clipped_grad(A, G, clip.astype(np.float64))
+    c = torch.from_numpy(clip).cuda()
+    g = dp.clipped_grad(Ad, Gd, c)
+    assert fro_err(g.cpu().numpy(), ref) <= FRO_TOL8, fro_err(g.cpu().numpy(), ref)
+    h = torch.full_like(g, 2.0)
+    dp.clipped_grad(Ad, Gd, c, h, accumulate=True)
+    np.testing.assert_array_equal(h.cpu().numpy(), g.cpu().numpy() + np.float32(2.0))
+
+
+def test_f8_all_ones_clip_is_the_plain_sum(dp):
+    """c_i = 1: the clipped sum is A^T G over all B T rows, whatever the example boundaries."""
+    (A, G), (Ad, Gd) = draw(14, 6, 128, 256, 256, "f8")
+    g = dp.clipped_grad(Ad, Gd, torch.ones(6, device="cuda")).cpu().numpy()
+    ref = A.reshape(-1, 256).T @ G.reshape(-1, 256)
+    assert fro_err(g, ref) <= FRO_TOL8
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_f8_transformer_pipeline(dp, dtype):
+    """The transformer configuration's four layers with 8-bit inputs through the several-layers calls: norms, clip
+    factors, clipped sums and noise against the oracle's pipeline on the widened bytes."""
+    w, layers = wl.generate("transformer", B=6, straddle=True, dtype=dtype, g_scale=G_SCALE[dtype])
+    C = w.C * G_SCALE[dtype]
+    sa, sg = wl.f8_formats(dtype)
+    layers64 = [(wide(A, sa), wide(G, sg)) for A, G in layers]
+    s_ref, c_ref, g_ref = orc.run_pipeline(layers64, C, w.noise_std, w.noise_seed)
+    dev = [(to_dev8(A, sa), to_dev8(G, sg)) for A, G in layers]
+    c = torch.empty(6, device="cuda")
+    s = dp.layers_sqnorm(dev, C=C, clip=c)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TOL8
+    assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL8
+    assert (c == 1.0).any() and (c < 1.0).any()
+    sizes = [A.shape[-1] * G.shape[-1] for A, G in dev]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.zeros(sum(sizes), device="cuda")
+    grads = [flat[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)]
+    descs = dp.layer_descs(dev, grads, starts[:-1])
+    dp.layers_clipped_grad(dev, c, descs=descs, noise_std=w.noise_std, seed=w.noise_seed)
+    for g, gr in zip(grads, g_ref):
+        assert fro_err(g.cpu().numpy(), gr) <= FRO_TOL8
+    # the layer-by-layer calls give the same numbers
+    s1 = None
+    for li, (A, G) in enumerate(dev):
+        s1 = dp.layer_sqnorm(A, G, s1, accumulate=li > 0)
+    assert rel_err(s1.cpu().numpy(), s_ref) <= SQ_TOL8
+
+
+def test_f8_auto_takes_the_path_whose_kernels_fit(dp):
+    """T = 128, 240 x 256: the flop rule says Gram, whose 8-bit kernel needs widths that are multiples of 128; the
+    direct kernel takes multiples of 16.  T = 256, 128 x 128: the rule says direct and both fit."""
+    (A, G), (Ad, Gd) = draw(15, 3, 128, 240, 256, "f8")
+    assert dp.choose_path(128, 240, 256) == "gram"
+    s_auto = dp.layer_sqnorm(Ad, Gd).cpu().numpy()
+    s_dir = dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy()
+    np.testing.assert_array_equal(s_auto, s_dir)
+    assert rel_err(s_auto, orc.layer_sqnorm(A, G)) <= SQ_TOL8
+    with pytest.raises(dp.DpclipError) as ei:
+        dp.layer_sqnorm(Ad, Gd, path="gram")
+    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+
+
+def test_f8_extreme_values(dp):
+    """Largest finite values, subnormals and signed zeros of both formats go through the matrix unit exactly."""
+    B, T, d = 2, 128, 128
+    rng = np.random.default_rng(3)
+    # e4m3 activations from the whole finite code range (NaN codes 0x7f / 0xff left out), scaled-down e5m2 gradients
+    # from the subnormal and lowest normal codes
+    Ab = rng.integers(0, 0x7F, size=(B, T, d), dtype=np.uint8) | (rng.integers(0, 2, size=(B, T, d), dtype=np.uint8) << 7)
+    Gb = rng.integers(0, 0x10, size=(B, T, d), dtype=np.uint8) | (rng.integers(0, 2, size=(B, T, d), dtype=np.uint8) << 7)
+    A, G = wide(Ab, "f8e4m3"), wide(Gb, "f8e5m2")
+    assert np.isfinite(A).all() and np.abs(A).max() == 448.0 and 0 < np.abs(G[G != 0]).min() == 2.0 ** -16
+    Ad, Gd = to_dev8(Ab, "f8e4m3"), to_dev8(Gb, "f8e5m2")
+    ref = orc.layer_sqnorm(A, G)
+    for path in ("gram", "direct"):
+        s = dp.layer_sqnorm(Ad, Gd, path=path).cpu().numpy()
+        assert rel_err(s, ref) <= SQ_TOL8, (path, rel_err(s, ref))
+    g = dp.clipped_grad(Ad, Gd, torch.ones(B, device="cuda")).cpu().numpy()
+    assert fro_err(g, orc.clipped_grad(A, G, np.ones(B))) <= FRO_TOL8
+
+
+def test_f8_unsupported_is_reported(dp):
+    """What the 8-bit kernels do not take comes back as DP_ERR_UNSUPPORTED, before anything is launched."""
+    (_, _), (Ad, Gd) = draw(16, 4, 1, 128, 128, "f8")                      # dense layer
+    with pytest.raises(dp.DpclipError) as ei:
+        dp.layer_sqnorm(Ad, Gd)
+    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    (_, _), (Ad, Gd) = draw(16, 2, 128, 136, 128, "f8")                    # width not a multiple of 16
+    for call in (lambda: dp.layer_sqnorm(Ad, Gd), lambda: dp.clipped_grad(Ad, Gd, torch.ones(2, device="cuda"))):
+        with pytest.raises(dp.DpclipError) as ei:
+            call()
+        assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    with pytest.raises(dp.DpclipError) as ei:
+        dp.bias_sqnorm(Gd)
+    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    # a several-layers call with one unsupported layer leaves its outputs alone
+    (_, _), good = draw(17, 2, 128, 128, 128, "f8")
+    s = torch.full((2,), 7.0, device="cuda")
+    with pytest.raises(dp.DpclipError) as ei:
+        dp.layers_sqnorm([good, (Ad, Gd)], s)
+    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert torch.all(s == 7.0)

@@ -476,3 +476,52 @@ def test_random_shapes_identities(B, T, di, do, seed):
     g2 = orc.clipped_grad(A, G, 0.5 * nu)
     np.testing.assert_allclose(g2, 0.5 * g1, rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(g1, orc.clipped_grad_by_clip_function(A, G, C), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- 8-bit storage formats
+def test_f8_decoding_matches_the_library_conversion_on_every_code():
+    """All 256 codes of both OCP 8-bit formats against torch's conversion (a table-driven implementation that shares
+    nothing with the oracle's formula), NaN codes included."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    for fmt, td in (("e4m3", torch.float8_e4m3fn), ("e5m2", torch.float8_e5m2)):
+        ref = torch.from_numpy(codes.copy()).view(td).to(torch.float64).numpy()
+        got = orc.f8_to_f64(codes, fmt)
+        np.testing.assert_array_equal(np.isnan(got), np.isnan(ref))
+        np.testing.assert_array_equal(got[~np.isnan(ref)], ref[~np.isnan(ref)])
+
+
+def test_f8_decoding_landmarks():
+    """Values that the format definitions fix: one, the largest finite value, the smallest subnormal, the largest
+    subnormal, the smallest normal, signed zero, the special codes."""
+    e4 = lambda c: float(orc.f8_to_f64(np.array([c], dtype=np.uint8), "e4m3")[0])
+    e5 = lambda c: float(orc.f8_to_f64(np.array([c], dtype=np.uint8), "e5m2")[0])
+    assert e4(0x38) == 1.0 and e4(0x7E) == 448.0 and e4(0x01) == 2.0 ** -9 and e4(0x07) == 7 * 2.0 ** -9 and e4(0x08) == 2.0 ** -6
+    assert e4(0xB8) == -1.0 and e4(0x00) == 0.0 and np.signbit(e4(0x80)) and np.isnan(e4(0x7F)) and np.isnan(e4(0xFF))
+    assert e4(0x78) == 256.0                                    # exponent field 15 is an ordinary binade in e4m3
+    assert e5(0x3C) == 1.0 and e5(0x7B) == 57344.0 and e5(0x01) == 2.0 ** -16 and e5(0x03) == 3 * 2.0 ** -16 and e5(0x04) == 2.0 ** -14
+    assert e5(0x7C) == np.inf and e5(0xFC) == -np.inf and np.isnan(e5(0x7D)) and np.isnan(e5(0xFF))
+    with pytest.raises(TypeError):
+        orc.f8_to_f64(np.zeros(3, dtype=np.int32), "e4m3")
+
+
+def test_f8_generator_rounds_to_the_nearest_code():
+    """The input generator's 8-bit storage: every stored value is a nearest representable one (brute force over the
+    finite codes with the oracle's decoding), ties go to the even code, and out-of-range magnitudes saturate."""
+    from paper_2009_03106_amd import workloads as wl
+    rng = np.random.default_rng(8)
+    x = np.concatenate([rng.standard_normal(4000).astype(np.float32) * s for s in (1e-3, 0.05, 1.0, 60.0)] +
+                       [np.array([0.0, 1e9, -1e9, 2.0 ** -10, 3 * 2.0 ** -10, 17.0, 19.0], dtype=np.float32)])
+    for fmt in ("e4m3", "e5m2"):
+        codes = np.arange(256, dtype=np.uint8)
+        vals = orc.f8_to_f64(codes, fmt)
+        finite = np.isfinite(vals)
+        bits = wl.f32_to_f8_bits(x, fmt)
+        got = orc.f8_to_f64(bits, fmt)
+        assert np.isfinite(got).all()
+        best = np.min(np.abs(x.astype(np.float64)[:, None] - vals[finite][None, :]), axis=1)
+        np.testing.assert_array_equal(np.abs(got - x.astype(np.float64)), best)
+        assert float(orc.f8_to_f64(wl.f32_to_f8_bits(np.array([1e9], dtype=np.float32), fmt), fmt)[0]) == wl.F8_MAX[fmt]
+    # ties: 17 lies midway between the e4m3 neighbours 16 (mantissa 000) and 18 (001), 19 between 18 and 20 (010)
+    t = orc.f8_to_f64(wl.f32_to_f8_bits(np.array([17.0, 19.0], dtype=np.float32), "e4m3"), "e4m3")
+    np.testing.assert_array_equal(t, [16.0, 20.0])
