@@ -38,10 +38,20 @@ PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 SPINUP_S = 0.04          # untimed busy time in front of every timed loop (see time_steps)
 
 
-def to_dev(x, torch):
+def to_dev(x, torch, f8=None):
+    """f8: torch dtype of uint8 bit patterns (the two 8-bit formats are told apart by the workload's dtype name)."""
     if x.dtype == np.uint16:
         return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    if x.dtype == np.uint8:
+        return torch.from_numpy(x).cuda().view(f8)
     return torch.from_numpy(x).cuda()
+
+
+def f8_torch_types(dtype, torch):
+    from paper_2009_03106_amd import workloads as wl
+    t = {"f8e4m3": torch.float8_e4m3fn, "f8e5m2": torch.float8_e5m2}
+    sa, sg = wl.f8_formats(dtype)
+    return t[sa], t[sg]
 
 
 class Pipeline:
@@ -49,9 +59,11 @@ class Pipeline:
 
     def __init__(self, w, layers_np, torch, dp, path="auto"):
         self.w, self.torch, self.dp, self.path = w, torch, dp, path
-        self.dev = [(to_dev(A, torch), to_dev(G, torch)) for A, G in layers_np]
+        ta, tg = f8_torch_types(w.dtype, torch) if w.dtype.startswith("f8") else (None, None)
+        self.dev = [(to_dev(A, torch, ta), to_dev(G, torch, tg)) for A, G in layers_np]
         self.B = self.dev[0][0].shape[0]
-        dt = {"f32": dp.DP_F32, "bf16": dp.DP_BF16, "f16": dp.DP_F16}[w.dtype]
+        dt = {"f32": dp.DP_F32, "bf16": dp.DP_BF16, "f16": dp.DP_F16, "f8e4m3": dp.DP_F8_E4M3, "f8e5m2": dp.DP_F8_E5M2,
+              "f8": dp.DP_F8_E4M3_E5M2}[w.dtype]
         self.s = torch.zeros(self.B, dtype=torch.float32, device="cuda")
         self.c = torch.zeros(self.B, dtype=torch.float32, device="cuda")
         self.grads, self.ws_sq, self.ws_cg = [], [], []
@@ -123,7 +135,7 @@ class Pipeline:
 
 def algorithmic_work(w, B):
     """Flops and HBM bytes per step that the method itself needs (no re-reads, no scratch)."""
-    es = 2 if w.dtype in ("bf16", "f16") else 4
+    es = 2 if w.dtype in ("bf16", "f16") else (1 if w.dtype.startswith("f8") else 4)
     out = {"norm_flops": 0, "gemm_flops": 0, "norm_bytes": 0, "gemm_bytes": 0, "noise_bytes": 0}
     for spec in w.layers:
         T, di, do = spec.T, spec.d_in, spec.d_out
@@ -383,6 +395,18 @@ def main():
                                      "sqnorm_tflops": wk16["norm_flops"] / (ph16[0] * 1e-3) / 1e12,
                                      "clipped_grad_tflops": wk16["gemm_flops"] / (ph16[2] * 1e-3) / 1e12}
         del p16, l16
+        # ... and with 8-bit inputs, activations e4m3 and backpropagated gradients e5m2: the 64-deep 8-bit matrix
+        # instruction, twice the rate for half the bytes
+        w8, l8 = wl.generate("transformer", dtype="f8")
+        w8 = dataclasses.replace(w8, dtype="f8")
+        p8 = Pipeline(w8, l8, torch, dp, "auto")
+        ms8, ph8 = time_steps(p8, torch, 20, 3)
+        wk8 = algorithmic_work(w8, p8.B)
+        others["transformer_f8"] = {"examples_per_s": p8.B / (ms8 * 1e-3), "ms_per_step": ms8, "storage": "A e4m3, G e5m2",
+                                    "sqnorm_ms": ph8[0], "clipped_grad_ms": ph8[2],
+                                    "sqnorm_tflops": wk8["norm_flops"] / (ph8[0] * 1e-3) / 1e12,
+                                    "clipped_grad_tflops": wk8["gemm_flops"] / (ph8[2] * 1e-3) / 1e12}
+        del p8, l8
         # the convolution configuration again, given by its input image (implicit unfolding: 16.8 MB of X instead of
         # the 151 MB patch matrix); same flops, same outputs as "conv"
         spec, Xn, Gn = wl.generate_conv_image()
