@@ -64,17 +64,21 @@ typedef enum {
  *   DP_F8_E4M3       A and G e4m3
  *   DP_F8_E5M2       A and G e5m2
  *   DP_F8_E4M3_E5M2  A e4m3 (activations), G e5m2 (backpropagated gradients)
- * Products of 8-bit values are exact in the fp32 accumulators' inputs, so the
- * results differ from exact arithmetic on the stored values only by fp32
- * summation.  They are taken by dp_layer_sqnorm (T > 64; GRAM: d_in and d_out
- * multiples of 128; DIRECT: d_in and d_out multiples of 16 that tile into
- * 256 x 256 or 128 x 128 blocks with at most a quarter of padding; AUTO takes the
- * other path where only that one fits), by dp_clipped_grad and its noise variant
- * (the DIRECT shapes; T a multiple of 64, or at most a quarter of padding up to
- * the next one) and by the several-layers calls under the same limits and
- * without bias_rows.  Every other entry point, and every other shape, returns
- * DP_ERR_UNSUPPORTED for them (widen to DP_F16, which holds both formats
- * exactly). */
+ * Products of 8-bit values are exact in fp32, so the results differ from exact
+ * arithmetic on the stored values only by the fp32 summation.
+ * dp_layer_sqnorm, dp_clipped_grad(_noise) and the several-layers calls take
+ * them for every shape.  The 8-bit kernels run: GRAM for T > 64 with d_in and
+ * d_out multiples of 128; DIRECT and the clipped sum for d_in and d_out multiples
+ * of 16 that tile into 256 x 256 or 128 x 128 blocks with at most a quarter of
+ * padding and T >= 64 a multiple of 64 (or at most a quarter of padding up to the
+ * next one); under DP_PATH_AUTO a layer goes to the other path where only that
+ * one's kernel fits.  Every other shape (dense layers, other widths, short T) is
+ * widened to fp16 -- which holds both formats exactly -- at the head of the
+ * workspace and runs through the fp16 kernels: same result as the DP_F16 call on
+ * the widened values, 2 bytes per input element more workspace (the size queries
+ * include it).  Not taken (DP_ERR_UNSUPPORTED): dp_bias_sqnorm,
+ * dp_layernorm_sqnorm, the convolution-from-image calls and bias_rows in
+ * dp_layers_sqnorm: 8-bit training keeps the inputs of those in 16 bits. */
 typedef enum { DP_F32 = 0, DP_BF16 = 1, DP_F16 = 2, DP_F8_E4M3 = 3, DP_F8_E5M2 = 4, DP_F8_E4M3_E5M2 = 5 } dp_dtype;
 
 /* How dp_layer_sqnorm evaluates ||A_i^T G_i||_F^2 when T > 1.

@@ -46,6 +46,15 @@ dp_path resolve_path(dp_path path, dp_dtype dtype, int64_t T, int64_t d_in, int6
     return p;
 }
 
+// 8-bit inputs outside the shapes of their own kernels are widened to fp16 (exact for both formats) at the head of
+// the workspace and run through the fp16 kernels
+size_t widen_bytes(int64_t n) { return (size_t)((n * 2 + 255) & ~int64_t(255)); }
+bool f8_fast_sqnorm(dp_dtype dtype, dp_path path, int64_t T, int64_t d_in, int64_t d_out) {
+    return T > 1 && f8_path_ok(resolve_path(path, dtype, T, d_in, d_out), dtype, T, d_in, d_out);
+}
+bool a_is_e5m2(dp_dtype d) { return d == DP_F8_E5M2; }
+bool g_is_e5m2(dp_dtype d) { return d != DP_F8_E4M3; }
+
 // bytes of scratch for the squared-norm call on an already resolved path (T > 1)
 size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
     if (is8(dtype) && !f8_path_ok(path, dtype, T, d_in, d_out)) return 0;
@@ -122,6 +131,10 @@ dp_path dp_choose_path(int64_t T, int64_t d_in, int64_t d_out) {
 size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
     if (check_dims(B, T, d_in, d_out) != DP_OK || !valid_dtype(dtype) || !valid_path(path)) return 0;
     if (B == 0 || T == 0 || d_in == 0 || d_out == 0) return 0;
+    if (is8(dtype) && (op == DP_OP_SQNORM || op == DP_OP_CLIPPED_GRAD)) {
+        const bool fast = op == DP_OP_SQNORM ? f8_fast_sqnorm(dtype, path, T, d_in, d_out) : dma8_clipped_ok((int)T, (int)d_in, (int)d_out);
+        if (!fast) return widen_bytes(B * T * d_in) + widen_bytes(B * T * d_out) + dp_workspace_bytes(op, B, T, d_in, d_out, DP_F16, path);
+    }
     if (op == DP_OP_SQNORM) {
         if (T == 1) return 0;
         const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
@@ -147,13 +160,21 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
     if (!A || !G || !aligned16(A) || !aligned16(G)) return DP_ERR_INVALID_ARG;
 
     hipError_t e;
+    if (is8(dtype) && !f8_fast_sqnorm(dtype, path, T, d_in, d_out)) {
+        const size_t na = widen_bytes(B * T * d_in), ng = widen_bytes(B * T * d_out);
+        const size_t inner = dp_workspace_bytes(DP_OP_SQNORM, B, T, d_in, d_out, DP_F16, path);
+        if (!workspace || workspace_bytes < na + ng + inner || !aligned16(workspace)) return DP_ERR_WORKSPACE;
+        unsigned char* w = static_cast<unsigned char*>(workspace);
+        if (launch_widen_f8(A, reinterpret_cast<uint16_t*>(w), B * T * d_in, a_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        if (launch_widen_f8(G, reinterpret_cast<uint16_t*>(w + na), B * T * d_out, g_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        return dp_layer_sqnorm(w, w + na, B, T, d_in, d_out, DP_F16, path, accumulate, sqnorm, w + na + ng,
+                               workspace_bytes - na - ng, hip_stream);
+    }
     if (T == 1) {
-        if (is8(dtype)) return DP_ERR_UNSUPPORTED;
         e = launch_sqnorm_dense(A, G, (int)B, (int)d_in, (int)d_out, (int)dtype, accumulate != 0, sqnorm, stream);
         return e == hipSuccess ? DP_OK : DP_ERR_HIP;
     }
     const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
-    if (is8(dtype) && !f8_path_ok(p, dtype, T, d_in, d_out)) return DP_ERR_UNSUPPORTED;
     const size_t need = sqnorm_ws_bytes(B, T, d_in, d_out, dtype, p);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;           // > 2^31 partial sums
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
@@ -232,7 +253,16 @@ dp_status clipped_grad_noise(const void* A, const void* G, const float* clip, in
         return DP_OK;
     }
     if (!A || !G || !clip || !aligned16(A) || !aligned16(G)) return DP_ERR_INVALID_ARG;
-    if (is8(dtype) && !dma8_clipped_ok((int)T, (int)d_in, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    if (is8(dtype) && !dma8_clipped_ok((int)T, (int)d_in, (int)d_out)) {
+        const size_t na = widen_bytes(B * T * d_in), ng = widen_bytes(B * T * d_out);
+        const size_t inner = clipped_ws_bytes(B, T, d_in, d_out, DP_F16);
+        if (!workspace || workspace_bytes < na + ng + inner || !aligned16(workspace)) return DP_ERR_WORKSPACE;
+        unsigned char* w = static_cast<unsigned char*>(workspace);
+        if (launch_widen_f8(A, reinterpret_cast<uint16_t*>(w), B * T * d_in, a_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        if (launch_widen_f8(G, reinterpret_cast<uint16_t*>(w + na), B * T * d_out, g_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        return clipped_grad_noise(w, w + na, clip, B, T, d_in, d_out, DP_F16, accumulate, grad, w + na + ng,
+                                  workspace_bytes - na - ng, hip_stream, stddev, seed, offset);
+    }
     const size_t need = clipped_ws_bytes(B, T, d_in, d_out, dtype);
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
     float* ws = static_cast<float*>(workspace);
@@ -424,7 +454,7 @@ dp_status dp_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64
 namespace {
 
 // checks shared by the several-layers calls and their size queries
-// op: which call asks (the 8-bit types take only the shapes of their copy-pipeline kernels, and no bias rows)
+// op: which call asks (the 8-bit types take no bias rows)
 dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path, bool pointers,
                        dp_op op) {
     if (n_layers < 0 || B < 0 || (n_layers > 0 && !layers)) return DP_ERR_INVALID_ARG;
@@ -435,11 +465,7 @@ dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
         const dp_status st = check_dims(B, y.T, y.d_in, y.d_out);
         if (st != DP_OK) return st;
         if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
-        if (is8(dtype)) {
-            if (op == DP_OP_SQNORM && (y.bias_rows || !f8_path_ok(resolve_path(path, dtype, y.T, y.d_in, y.d_out), dtype, y.T, y.d_in, y.d_out)))
-                return DP_ERR_UNSUPPORTED;
-            if (op == DP_OP_CLIPPED_GRAD && !dma8_clipped_ok((int)y.T, (int)y.d_in, (int)y.d_out)) return DP_ERR_UNSUPPORTED;
-        }
+        if (is8(dtype) && op == DP_OP_SQNORM && y.bias_rows) return DP_ERR_UNSUPPORTED;
         if (pointers && (!y.A || !y.G || !aligned16(y.A) || !aligned16(y.G))) return DP_ERR_INVALID_ARG;
         if (pointers && y.bias_rows && B > 65535) return DP_ERR_UNSUPPORTED;                      // as dp_bias_sqnorm
     }
@@ -509,7 +535,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
     };
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
-        if (y.T != 1 || y.d_in == 0 || y.d_out == 0) continue;
+        if (y.T != 1 || y.d_in == 0 || y.d_out == 0 || is8(dtype)) continue;      // 8-bit dense layers: one by one below
         const int k = dense.n_layers++;
         dense.A[k] = y.A; dense.G[k] = y.G; dense.d_in[k] = (int)y.d_in; dense.d_out[k] = (int)y.d_out;
         if (dense.n_layers == kDenseBatch && flush_dense() != hipSuccess) return DP_ERR_HIP;
@@ -518,7 +544,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
     // layers outside the batched launches, in the order given
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
-        if (y.T <= 1 || y.d_in == 0 || y.d_out == 0) continue;                 // empty layers add nothing
+        if (y.T == 0 || (y.T == 1 && !is8(dtype)) || y.d_in == 0 || y.d_out == 0) continue;     // empty layers add nothing
         if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
         const dp_status s1 = dp_layer_sqnorm(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes, hip_stream);
         if (s1 != DP_OK) return s1;

@@ -32,6 +32,8 @@ bool splitk_noise_ok(int64_t n, uint64_t offset);       // n and offset multiple
 hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st,
                                 const NoiseArgs* noise);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+// dst[j] = fp16 bits of the 8-bit float src[j] (e4m3, or e5m2 when e5m2 is set), exact
+hipError_t launch_widen_f8(const void* src, uint16_t* dst, int64_t n, bool e5m2, hipStream_t st);
 hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st);
 // ---- bias parameters (dp_bias.hip)
 hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, int dt, float* u, float* u2, hipStream_t st);

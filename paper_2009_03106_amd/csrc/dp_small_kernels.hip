@@ -308,6 +308,43 @@ __global__ void k_fill_zero(float* __restrict__ p, int64_t n) {
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) p[j] = 0.f;
 }
 
+// 8-bit floats -> fp16, exactly: e5m2 is the upper byte of an fp16, and e4m3's values (2^-9 .. 448) lie inside
+// fp16's normal range.  NaN codes become fp16 NaNs.  16 elements per thread and step while whole 16-byte pieces
+// remain (src and dst 16-byte aligned), then single elements.
+template <bool E5M2> __device__ __forceinline__ uint32_t widen2_f8(uint32_t w, int pair) {
+    if (E5M2) {
+        const uint32_t two = pair ? (w >> 16) : (w & 0xffffu);
+        return ((two & 0xffu) << 8) | ((two & 0xff00u) << 16);
+    }
+    const float lo = pair ? __builtin_amdgcn_cvt_f32_fp8((int)w, 2) : __builtin_amdgcn_cvt_f32_fp8((int)w, 0);
+    const float hi = pair ? __builtin_amdgcn_cvt_f32_fp8((int)w, 3) : __builtin_amdgcn_cvt_f32_fp8((int)w, 1);
+    return In16<true>::pack(lo, hi);
+}
+template <bool E5M2>
+__global__ __launch_bounds__(256) void k_widen_f8(const unsigned char* __restrict__ src, uint16_t* __restrict__ dst, int64_t n) {
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x, stride = (int64_t)gridDim.x * 256;
+    const int64_t nv = n >> 4;
+    for (int64_t i = tid; i < nv; i += stride) {
+        const uint4 w = reinterpret_cast<const uint4*>(src)[i];
+        uint4 o0, o1;
+        o0.x = widen2_f8<E5M2>(w.x, 0); o0.y = widen2_f8<E5M2>(w.x, 1); o0.z = widen2_f8<E5M2>(w.y, 0); o0.w = widen2_f8<E5M2>(w.y, 1);
+        o1.x = widen2_f8<E5M2>(w.z, 0); o1.y = widen2_f8<E5M2>(w.z, 1); o1.z = widen2_f8<E5M2>(w.w, 0); o1.w = widen2_f8<E5M2>(w.w, 1);
+        reinterpret_cast<uint4*>(dst)[2 * i] = o0;
+        reinterpret_cast<uint4*>(dst)[2 * i + 1] = o1;
+    }
+    for (int64_t i = (nv << 4) + tid; i < n; i += stride) dst[i] = (uint16_t)(widen2_f8<E5M2>(src[i], 0) & 0xffffu);
+}
+
+hipError_t launch_widen_f8(const void* src, uint16_t* dst, int64_t n, bool e5m2, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n / 16 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    if (e5m2) k_widen_f8<true><<<(unsigned)blocks, 256, 0, st>>>(static_cast<const unsigned char*>(src), dst, n);
+    else      k_widen_f8<false><<<(unsigned)blocks, 256, 0, st>>>(static_cast<const unsigned char*>(src), dst, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     int64_t blocks = (n + 255) / 256;

@@ -87,7 +87,19 @@ def test_workspace_sizes_over_many_shapes(lib):
         for path in ("auto", "gram", "direct"):
             assert f(dpclip.DP_OP_SQNORM, B, T, di, do, dpclip.DP_F16, path) == f(dpclip.DP_OP_SQNORM, B, T, di, do, dpclip.DP_BF16, path)
         assert f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dpclip.DP_F16) == f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dpclip.DP_BF16)
-    assert f(dpclip.DP_OP_SQNORM, 4, 64, 64, 64, 3) == 0                                       # unknown dtype
+        # 8-bit inputs: either the 8-bit kernels' own scratch, or the fp16 scratch behind the two widened inputs
+        r256 = lambda n: (n + 255) // 256 * 256
+        for dt8 in (dpclip.DP_F8_E4M3, dpclip.DP_F8_E5M2, dpclip.DP_F8_E4M3_E5M2):
+            widened = r256(2 * B * T * di) + r256(2 * B * T * do)
+            for path in ("auto", "gram", "direct"):
+                n = f(dpclip.DP_OP_SQNORM, B, T, di, do, dt8, path)
+                assert n % 4 == 0 and (n >= 4 * B or T == 1)
+                assert n <= widened or n == widened + f(dpclip.DP_OP_SQNORM, B, T, di, do, dpclip.DP_F16, path), (B, T, di, do, path)
+            n = f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dt8)
+            assert n % 4 == 0 and (n <= widened or n == widened + f(dpclip.DP_OP_CLIPPED_GRAD, B, T, di, do, dpclip.DP_F16))
+    assert f(dpclip.DP_OP_SQNORM, 64, 512, 768, 768, dpclip.DP_F8_E4M3_E5M2, "gram") == f(dpclip.DP_OP_SQNORM, 64, 512, 768, 768, dpclip.DP_BF16, "gram")
+    assert f(dpclip.DP_OP_SQNORM, 3, 17, 72, 40, dpclip.DP_F8_E4M3) == 7424 + 4096 + f(dpclip.DP_OP_SQNORM, 3, 17, 72, 40, dpclip.DP_F16)
+    assert f(dpclip.DP_OP_SQNORM, 4, 64, 64, 64, 6) == 0                                       # unknown dtype
     # a ragged sequence length on the copy-pipeline kernels sets aside a line of zeros even without K slices
     assert f(dpclip.DP_OP_CLIPPED_GRAD, 1, 197, 768, 768, dpclip.DP_BF16) >= 256
     # too large: B * T must stay below 2^31, layer widths below 2^24

@@ -152,9 +152,9 @@ def test_f8_auto_takes_the_path_whose_kernels_fit(dp):
     s_dir = dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy()
     np.testing.assert_array_equal(s_auto, s_dir)
     assert rel_err(s_auto, orc.layer_sqnorm(A, G)) <= SQ_TOL8
-    with pytest.raises(dp.DpclipError) as ei:
-        dp.layer_sqnorm(Ad, Gd, path="gram")
-    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    # an explicit request for the Gram path is honoured through the fp16 kernels
+    s_gram = dp.layer_sqnorm(Ad, Gd, path="gram").cpu().numpy()
+    assert rel_err(s_gram, orc.layer_sqnorm(A, G)) <= SQ_TOL8
 
 
 def test_f8_extreme_values(dp):
@@ -176,25 +176,84 @@ def test_f8_extreme_values(dp):
     assert fro_err(g, orc.clipped_grad(A, G, np.ones(B))) <= FRO_TOL8
 
 
+# shapes outside the 8-bit kernels: dense layers, widths that are not multiples of 16, short or very ragged T
+WIDENED_SHAPES = [(32, 1, 64, 32), (7, 1, 784, 512), (3, 128, 136, 128), (5, 32, 256, 256), (2, 70, 100, 60), (4, 20, 48, 33)]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", WIDENED_SHAPES)
+def test_f8_other_shapes_run_widened(dp, dtype, shape):
+    """Shapes that the 8-bit kernels do not take are widened to fp16 (exactly) inside the workspace and run through
+    the fp16 kernels: same results against the oracle, a larger workspace."""
+    B, T, d_in, d_out = shape
+    (A, G), (Ad, Gd) = draw(21, B, T, d_in, d_out, dtype)
+    code = dp._dtype_code(Ad, Gd)
+    for path in ("auto", "gram", "direct"):
+        s = dp.layer_sqnorm(Ad, Gd, path=path).cpu().numpy()
+        assert rel_err(s, orc.layer_sqnorm(A, G)) <= SQ_TOL8, (path, rel_err(s, orc.layer_sqnorm(A, G)))
+    need = dp.workspace_bytes(dp.DP_OP_SQNORM, B, T, d_in, d_out, code)
+    assert need >= 2 * B * T * (d_in + d_out) + dp.workspace_bytes(dp.DP_OP_SQNORM, B, T, d_in, d_out, dp.DP_F16)
+    rng = np.random.default_rng(6)
+    clip = (0.1 + 0.9 * rng.random(B)).astype(np.float32)
+    g = dp.clipped_grad(Ad, Gd, torch.from_numpy(clip).cuda()).cpu().numpy()
+    # the fp16 kernels for these shapes re-round c_i * a to fp16: 2^-12 relative per element
+    assert fro_err(g, orc.clipped_grad(A, G, clip.astype(np.float64))) <= 2e-3
+    # bit for bit what the fp16 entry points give on the widened values
+    A16 = torch.from_numpy(A.astype(np.float16)).cuda()
+    G16 = torch.from_numpy(G.astype(np.float16)).cuda()
+    assert np.array_equal(A16.cpu().numpy().astype(np.float64), A) and np.array_equal(G16.cpu().numpy().astype(np.float64), G)
+    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd).cpu().numpy(), dp.layer_sqnorm(A16, G16).cpu().numpy())
+    np.testing.assert_array_equal(g, dp.clipped_grad(A16, G16, torch.from_numpy(clip).cuda()).cpu().numpy())
+    # too small a workspace is refused
+    lib = dp.load_library()
+    ws = torch.empty(max(16, need - 16), dtype=torch.uint8, device="cuda")
+    sq = torch.zeros(B, device="cuda")
+    assert lib.dp_layer_sqnorm(Ad.data_ptr(), Gd.data_ptr(), B, T, d_in, d_out, code, 0, 0, sq.data_ptr(), ws.data_ptr(),
+                               need - 16, None) == dp.DP_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_f8_mixed_layers_call(dp, dtype):
+    """A model with dense layers, an aligned and an unaligned sequence layer in one several-layers call."""
+    shapes = [(1, 784, 512), (256, 256, 384), (1, 512, 10), (100, 72, 40), (128, 512, 128)]
+    B = 5
+    wides, devs = [], []
+    for k, (T, di, do) in enumerate(shapes):
+        w, d = draw(30 + k, B, T, di, do, dtype)
+        wides.append(w); devs.append(d)
+    s_ref = orc.total_sqnorm(wides)
+    C = float(np.sqrt(np.median(s_ref)))
+    c = torch.empty(B, device="cuda")
+    s = dp.layers_sqnorm(devs, C=C, clip=c)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TOL8
+    c_ref = orc.clip_factors(s_ref, C)
+    assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL8
+    grads = dp.layers_clipped_grad(devs, c)
+    for (A, G), g in zip(wides, grads):
+        assert fro_err(g.cpu().numpy(), orc.clipped_grad(A, G, c.cpu().numpy().astype(np.float64))) <= 2e-3
+
+
 def test_f8_unsupported_is_reported(dp):
-    """What the 8-bit kernels do not take comes back as DP_ERR_UNSUPPORTED, before anything is launched."""
-    (_, _), (Ad, Gd) = draw(16, 4, 1, 128, 128, "f8")                      # dense layer
-    with pytest.raises(dp.DpclipError) as ei:
-        dp.layer_sqnorm(Ad, Gd)
-    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
-    (_, _), (Ad, Gd) = draw(16, 2, 128, 136, 128, "f8")                    # width not a multiple of 16
-    for call in (lambda: dp.layer_sqnorm(Ad, Gd), lambda: dp.clipped_grad(Ad, Gd, torch.ones(2, device="cuda"))):
-        with pytest.raises(dp.DpclipError) as ei:
-            call()
-        assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    """Bias rows, LayerNorm rows and the convolution from the image do not take 8-bit inputs: DP_ERR_UNSUPPORTED,
+    before anything is launched."""
+    (_, _), (Ad, Gd) = draw(16, 2, 128, 128, 128, "f8")
     with pytest.raises(dp.DpclipError) as ei:
         dp.bias_sqnorm(Gd)
     assert ei.value.status == dp.DP_ERR_UNSUPPORTED
-    # a several-layers call with one unsupported layer leaves its outputs alone
-    (_, _), good = draw(17, 2, 128, 128, 128, "f8")
-    s = torch.full((2,), 7.0, device="cuda")
     with pytest.raises(dp.DpclipError) as ei:
-        dp.layers_sqnorm([good, (Ad, Gd)], s)
+        dp.layernorm_sqnorm(Gd, Gd)
+    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    X = torch.zeros((2, 16, 16, 16), dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
+    Gc = torch.zeros((2, 256, 128), dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
+    with pytest.raises(dp.DpclipError) as ei:
+        dp.conv_sqnorm(X, Gc, 3, 3, 1)
+    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    # a several-layers call that asks for bias rows leaves its outputs alone
+    s = torch.full((2,), 7.0, device="cuda")
+    rows = torch.full((2, 128), 7.0, device="cuda")
+    descs = dp.layer_descs([(Ad, Gd)], bias_rows=[rows])
+    with pytest.raises(dp.DpclipError) as ei:
+        dp.layers_sqnorm([(Ad, Gd)], s, descs=descs)
     assert ei.value.status == dp.DP_ERR_UNSUPPORTED
     torch.cuda.synchronize()
-    assert torch.all(s == 7.0)
+    assert torch.all(s == 7.0) and torch.all(rows == 7.0)
