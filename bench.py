@@ -34,7 +34,7 @@ MEASURED_TRAFFIC = {
 }
 
 PEAK_HBM_GBS = 8000.0
-PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3, "f8": 5000.0, "f8e4m3": 5000.0, "f8e5m2": 5000.0}
 SPINUP_S = 0.04          # untimed busy time in front of every timed loop (see time_steps)
 
 
@@ -227,6 +227,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="transformer")
     ap.add_argument("--path", default="auto", choices=["auto", "gram", "direct"])
+    ap.add_argument("--dtype", default=None, choices=["f16", "f8", "f8e4m3", "f8e5m2"],
+                    help="store the configuration's inputs in another type (not the headline run: profiles of the variants)")
     ap.add_argument("--batch", type=int, default=None, help="override the configuration's batch size (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
@@ -253,7 +255,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    w, layers = wl.generate(args.workload, B=args.batch)
+    w, layers = wl.generate(args.workload, B=args.batch, dtype=args.dtype)
+    if args.dtype is not None:
+        w = dataclasses.replace(w, dtype=args.dtype)
     pipe = Pipeline(w, layers, torch, dp, args.path)
     del layers
     B = pipe.B
@@ -275,7 +279,7 @@ def main():
     else:
         ach = byts / (dur_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
-    traffic = MEASURED_TRAFFIC.get(w.name) if (args.batch is None and args.path == "auto") else None
+    traffic = MEASURED_TRAFFIC.get(w.name) if (args.batch is None and args.path == "auto" and args.dtype is None) else None
     roof.update({"traffic": traffic, "kernel": kname, "launches_per_step": nlayers,
                  "avg_launch_ms": dur_ms / nlayers,
                  "algorithmic_flops_per_step": flops, "algorithmic_bytes_per_step": byts})
@@ -297,46 +301,48 @@ def main():
 
     # bias parameters (the first of the "next" rows): per-example bias gradients + their squared norms for every
     # layer, then the clipped bias sums; timed on their own, not part of `value`
-    es = 2 if w.dtype == "bf16" else 4
-    rows = [torch.empty((B, spec.d_out), dtype=torch.float32, device="cuda") for spec in w.layers]
-    gbs = [torch.empty(spec.d_out, dtype=torch.float32, device="cuda") for spec in w.layers]
-    evb = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    tb = np.zeros(2)
-    for rep in range(5 + 2):
-        evb[0].record()
-        for (A, G), u in zip(pipe.dev, rows):
-            dp.bias_sqnorm(G, pipe.s, u, accumulate=True)
-        evb[1].record()
-        for u, gb in zip(rows, gbs):
-            dp.clipped_bias_grad(u, pipe.c, gb)
-        evb[2].record()
-        torch.cuda.synchronize()
-        if rep >= 2:
-            tb += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
-    tb /= 5
-    bias_bytes = sum(B * spec.T * spec.d_out * es + 4 * B * spec.d_out for spec in w.layers)
-    bias_out = {"bias_sqnorm_ms": tb[0], "clipped_bias_grad_ms": tb[1], "bias_sqnorm_gbs": bias_bytes / (tb[0] * 1e-3) / 1e9,
-                "algorithmic_bytes": bias_bytes}
-    if len(w.layers) > 1:
-        # the same bias rows and norms taken inside the several-layers norm call (by the Gram kernel where the
-        # layers share its launch): the norm phase with and without them
-        d_wb = dp.layer_descs(pipe.dev, bias_rows=rows)
-        ws_wb = torch.empty(max(16, dp.layers_workspace_bytes(d_wb[0], B, d_wb[2], args.path)), dtype=torch.uint8, device="cuda")
-        tf = np.zeros(2)
-        for rep in range(10 + 3):
+    bias_out = None                     # the bias kernels take 16- and 32-bit inputs
+    if not w.dtype.startswith("f8"):
+        es = 2 if w.dtype in ("bf16", "f16") else 4
+        rows = [torch.empty((B, spec.d_out), dtype=torch.float32, device="cuda") for spec in w.layers]
+        gbs = [torch.empty(spec.d_out, dtype=torch.float32, device="cuda") for spec in w.layers]
+        evb = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        tb = np.zeros(2)
+        for rep in range(5 + 2):
             evb[0].record()
-            dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=ws_wb, descs=d_wb, C=w.C, clip=pipe.c)
+            for (A, G), u in zip(pipe.dev, rows):
+                dp.bias_sqnorm(G, pipe.s, u, accumulate=True)
             evb[1].record()
-            dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=pipe.ws_layers, descs=pipe.descs, C=w.C, clip=pipe.c)
+            for u, gb in zip(rows, gbs):
+                dp.clipped_bias_grad(u, pipe.c, gb)
             evb[2].record()
             torch.cuda.synchronize()
-            if rep >= 3:
-                tf += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
-        tf /= 10
-        bias_out["sqnorm_with_bias_rows_ms"] = tf[0]
-        bias_out["sqnorm_without_ms"] = tf[1]
-        del ws_wb
-    del rows, gbs
+            if rep >= 2:
+                tb += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
+        tb /= 5
+        bias_bytes = sum(B * spec.T * spec.d_out * es + 4 * B * spec.d_out for spec in w.layers)
+        bias_out = {"bias_sqnorm_ms": tb[0], "clipped_bias_grad_ms": tb[1], "bias_sqnorm_gbs": bias_bytes / (tb[0] * 1e-3) / 1e9,
+                    "algorithmic_bytes": bias_bytes}
+        if len(w.layers) > 1:
+            # the same bias rows and norms taken inside the several-layers norm call (by the Gram kernel where the
+            # layers share its launch): the norm phase with and without them
+            d_wb = dp.layer_descs(pipe.dev, bias_rows=rows)
+            ws_wb = torch.empty(max(16, dp.layers_workspace_bytes(d_wb[0], B, d_wb[2], args.path)), dtype=torch.uint8, device="cuda")
+            tf = np.zeros(2)
+            for rep in range(10 + 3):
+                evb[0].record()
+                dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=ws_wb, descs=d_wb, C=w.C, clip=pipe.c)
+                evb[1].record()
+                dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=pipe.ws_layers, descs=pipe.descs, C=w.C, clip=pipe.c)
+                evb[2].record()
+                torch.cuda.synchronize()
+                if rep >= 3:
+                    tf += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
+            tf /= 10
+            bias_out["sqnorm_with_bias_rows_ms"] = tf[0]
+            bias_out["sqnorm_without_ms"] = tf[1]
+            del ws_wb
+        del rows, gbs
 
     others = {}
     if not args.no_others and args.batch is None:
@@ -458,7 +464,8 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={B}, " + ", ".join(f"{s.name} T={s.T} {s.d_in}->{s.d_out}" for s in w.layers)
-                   + f", C={w.C}" + (f", noise std={w.noise_std}" if w.noise_std > 0 else ""),
+                   + f", C={w.C}" + (f", noise std={w.noise_std}" if w.noise_std > 0 else "")
+                   + (f", inputs stored as {args.dtype}" if args.dtype else ""),
                    "path": args.path, "parallelism": "single GPU", "untimed_spinup_s": SPINUP_S},
         "roofline": roof, "phases": phases_out, "bias_terms": bias_out, "other_workloads": others,
     }
