@@ -36,6 +36,7 @@
  *    instruction for the format is the only difference) and multiply exactly
  *    into float32.  All accumulation and all outputs are float32.  fp16
  *    subnormals (values below 6.1e-5) take part with their exact value.
+ *    The 8-bit types are described at dp_dtype below.
  */
 #ifndef DPCLIP_H
 #define DPCLIP_H
@@ -114,8 +115,8 @@ dp_status dp_layer_sqnorm(const void* A, const void* G,
 /* The same for several layers of one model in one call (the whole-model norm
  * is the sum over the layers; Section 5, paragraph before 5.1):
  *     sqnorm[i] = (accumulate ? sqnorm[i] : 0) + sum_l ||A_l,i^T G_l,i||_F^2.
- * Layers on the Gram path whose widths are multiples of 64 (16-bit inputs,
- * T > 64) share kernel launches, up to 16 layers each: the workgroups of one
+ * Layers on the Gram path whose widths are multiples of 64 (16-bit inputs;
+ * multiples of 128 for 8-bit inputs) with T > 64 share kernel launches, up to 16 layers each: the workgroups of one
  * layer then fill the idle tail of another's, which a per-layer launch leaves
  * empty.  Dense layers (T == 1) share launches too, 16 each.  Every other
  * layer is handled exactly as dp_layer_sqnorm handles it.  The result equals
@@ -232,7 +233,8 @@ dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
  *   G          device, [B,T,d_out] of `dtype`, read only
  *   bias_rows  device, float32[B, d_out], written; keep it for dp_clipped_bias_grad
  *   sqnorm     device, float32[B]
- * B must be < 65536 (DP_ERR_UNSUPPORTED otherwise).  No workspace. */
+ * B must be < 65536 and dtype float32 or a 16-bit type (DP_ERR_UNSUPPORTED
+ * otherwise).  No workspace. */
 dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
                          dp_dtype dtype, int accumulate, float* sqnorm,
                          float* bias_rows, void* hip_stream);
@@ -244,7 +246,8 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
  *     beta_rows[i, :]  = sum_t G_i[t, :]
  *     sqnorm[i] = (accumulate ? sqnorm[i] : 0) + ||gamma_rows[i]||^2 + ||beta_rows[i]||^2
  * gamma_rows, beta_rows: device float32[B, d], written; their clipped sums
- * are two calls of dp_clipped_bias_grad.  B must be < 65536.  No workspace. */
+ * are two calls of dp_clipped_bias_grad.  B must be < 65536 and dtype float32
+ * or a 16-bit type.  No workspace. */
 dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_t T, int64_t d,
                               dp_dtype dtype, int accumulate, float* sqnorm,
                               float* gamma_rows, float* beta_rows, void* hip_stream);
