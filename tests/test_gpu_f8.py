@@ -257,3 +257,39 @@ def test_f8_unsupported_is_reported(dp):
     assert ei.value.status == dp.DP_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert torch.all(s == 7.0) and torch.all(rows == 7.0)
+
+
+def test_f8_empty_problems_and_argument_errors(dp):
+    """Empty sizes are valid and zero-fill; misaligned inputs and a short workspace are refused before any launch."""
+    lib = dp.load_library()
+    code = dp.DP_F8_E4M3_E5M2
+    e4, e5 = torch.float8_e4m3fn, torch.float8_e5m2
+    z = lambda *shape: torch.zeros(shape, dtype=torch.uint8, device="cuda")
+    # T = 0 and d_in = 0: zero norms, zero gradient
+    s = dp.layer_sqnorm(z(3, 0, 128).view(e4), z(3, 0, 128).view(e5))
+    assert torch.all(s == 0)
+    s = torch.full((3,), 5.0, device="cuda")
+    dp.layer_sqnorm(z(3, 128, 0).view(e4), z(3, 128, 128).view(e5), s)
+    assert torch.all(s == 0)
+    g = dp.clipped_grad(z(3, 0, 128).view(e4), z(3, 0, 256).view(e5), torch.ones(3, device="cuda"))
+    assert g.shape == (128, 256) and torch.all(g == 0)
+    # B = 0: nothing to do
+    assert lib.dp_layer_sqnorm(None, None, 0, 128, 128, 128, code, 0, 0, None, None, 0, None) == dp.DP_OK
+    # zeros in, zeros out through the 8-bit kernels (negative zeros included)
+    A = torch.full((2, 128, 128), 0x80, dtype=torch.uint8, device="cuda").view(e4)
+    G = z(2, 128, 128).view(e5)
+    assert torch.all(dp.layer_sqnorm(A, G, path="gram") == 0) and torch.all(dp.layer_sqnorm(A, G, path="direct") == 0)
+    assert torch.all(dp.clipped_grad(A, G, torch.ones(2, device="cuda")) == 0)
+    # misaligned A
+    buf = z(2 * 128 * 128 + 16)
+    need = dp.workspace_bytes(dp.DP_OP_SQNORM, 2, 128, 128, 128, code)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    sq = torch.full((2,), 9.0, device="cuda")
+    assert lib.dp_layer_sqnorm(buf.data_ptr() + 8, G.data_ptr(), 2, 128, 128, 128, code, 0, 0, sq.data_ptr(), ws.data_ptr(), ws.numel(),
+                               None) == dp.DP_ERR_INVALID_ARG
+    # the 8-bit kernels' own scratch: one float per example and tile pair, refused when short
+    assert need == 2 * 1 * 4
+    assert lib.dp_layer_sqnorm(A.data_ptr(), G.data_ptr(), 2, 128, 128, 128, code, 0, 0, sq.data_ptr(), ws.data_ptr(), need - 4,
+                               None) == dp.DP_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.all(sq == 9.0)
