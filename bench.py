@@ -301,48 +301,46 @@ def main():
 
     # bias parameters (the first of the "next" rows): per-example bias gradients + their squared norms for every
     # layer, then the clipped bias sums; timed on their own, not part of `value`
-    bias_out = None                     # the bias kernels take 16- and 32-bit inputs
-    if not w.dtype.startswith("f8"):
-        es = 2 if w.dtype in ("bf16", "f16") else 4
-        rows = [torch.empty((B, spec.d_out), dtype=torch.float32, device="cuda") for spec in w.layers]
-        gbs = [torch.empty(spec.d_out, dtype=torch.float32, device="cuda") for spec in w.layers]
-        evb = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        tb = np.zeros(2)
-        for rep in range(5 + 2):
+    es = 2 if w.dtype in ("bf16", "f16") else (1 if w.dtype.startswith("f8") else 4)
+    rows = [torch.empty((B, spec.d_out), dtype=torch.float32, device="cuda") for spec in w.layers]
+    gbs = [torch.empty(spec.d_out, dtype=torch.float32, device="cuda") for spec in w.layers]
+    evb = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    tb = np.zeros(2)
+    for rep in range(5 + 2):
+        evb[0].record()
+        for (A, G), u in zip(pipe.dev, rows):
+            dp.bias_sqnorm(G, pipe.s, u, accumulate=True)
+        evb[1].record()
+        for u, gb in zip(rows, gbs):
+            dp.clipped_bias_grad(u, pipe.c, gb)
+        evb[2].record()
+        torch.cuda.synchronize()
+        if rep >= 2:
+            tb += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
+    tb /= 5
+    bias_bytes = sum(B * spec.T * spec.d_out * es + 4 * B * spec.d_out for spec in w.layers)
+    bias_out = {"bias_sqnorm_ms": tb[0], "clipped_bias_grad_ms": tb[1], "bias_sqnorm_gbs": bias_bytes / (tb[0] * 1e-3) / 1e9,
+                "algorithmic_bytes": bias_bytes}
+    if len(w.layers) > 1:
+        # the same bias rows and norms taken inside the several-layers norm call (by the Gram kernel where the
+        # layers share its launch): the norm phase with and without them
+        d_wb = dp.layer_descs(pipe.dev, bias_rows=rows)
+        ws_wb = torch.empty(max(16, dp.layers_workspace_bytes(d_wb[0], B, d_wb[2], args.path)), dtype=torch.uint8, device="cuda")
+        tf = np.zeros(2)
+        for rep in range(10 + 3):
             evb[0].record()
-            for (A, G), u in zip(pipe.dev, rows):
-                dp.bias_sqnorm(G, pipe.s, u, accumulate=True)
+            dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=ws_wb, descs=d_wb, C=w.C, clip=pipe.c)
             evb[1].record()
-            for u, gb in zip(rows, gbs):
-                dp.clipped_bias_grad(u, pipe.c, gb)
+            dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=pipe.ws_layers, descs=pipe.descs, C=w.C, clip=pipe.c)
             evb[2].record()
             torch.cuda.synchronize()
-            if rep >= 2:
-                tb += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
-        tb /= 5
-        bias_bytes = sum(B * spec.T * spec.d_out * es + 4 * B * spec.d_out for spec in w.layers)
-        bias_out = {"bias_sqnorm_ms": tb[0], "clipped_bias_grad_ms": tb[1], "bias_sqnorm_gbs": bias_bytes / (tb[0] * 1e-3) / 1e9,
-                    "algorithmic_bytes": bias_bytes}
-        if len(w.layers) > 1:
-            # the same bias rows and norms taken inside the several-layers norm call (by the Gram kernel where the
-            # layers share its launch): the norm phase with and without them
-            d_wb = dp.layer_descs(pipe.dev, bias_rows=rows)
-            ws_wb = torch.empty(max(16, dp.layers_workspace_bytes(d_wb[0], B, d_wb[2], args.path)), dtype=torch.uint8, device="cuda")
-            tf = np.zeros(2)
-            for rep in range(10 + 3):
-                evb[0].record()
-                dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=ws_wb, descs=d_wb, C=w.C, clip=pipe.c)
-                evb[1].record()
-                dp.layers_sqnorm(pipe.dev, pipe.s, path=args.path, workspace=pipe.ws_layers, descs=pipe.descs, C=w.C, clip=pipe.c)
-                evb[2].record()
-                torch.cuda.synchronize()
-                if rep >= 3:
-                    tf += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
-            tf /= 10
-            bias_out["sqnorm_with_bias_rows_ms"] = tf[0]
-            bias_out["sqnorm_without_ms"] = tf[1]
-            del ws_wb
-        del rows, gbs
+            if rep >= 3:
+                tf += [evb[0].elapsed_time(evb[1]), evb[1].elapsed_time(evb[2])]
+        tf /= 10
+        bias_out["sqnorm_with_bias_rows_ms"] = tf[0]
+        bias_out["sqnorm_without_ms"] = tf[1]
+        del ws_wb
+    del rows, gbs
 
     others = {}
     if not args.no_others and args.batch is None:

@@ -77,9 +77,10 @@ typedef enum {
  * widened to fp16 -- which holds both formats exactly -- at the head of the
  * workspace and runs through the fp16 kernels: same result as the DP_F16 call on
  * the widened values, 2 bytes per input element more workspace (the size queries
- * include it).  Not taken (DP_ERR_UNSUPPORTED): dp_bias_sqnorm,
- * dp_layernorm_sqnorm, the convolution-from-image calls and bias_rows in
- * dp_layers_sqnorm: 8-bit training keeps the inputs of those in 16 bits. */
+ * include it).  dp_bias_sqnorm and dp_layernorm_sqnorm read 8-bit G (and
+ * Hbar, stored like A) directly; bias_rows of dp_layers_sqnorm are then taken
+ * in a pass of their own.  Not taken (DP_ERR_UNSUPPORTED): the
+ * convolution-from-image calls. */
 typedef enum { DP_F32 = 0, DP_BF16 = 1, DP_F16 = 2, DP_F8_E4M3 = 3, DP_F8_E5M2 = 4, DP_F8_E4M3_E5M2 = 5 } dp_dtype;
 
 /* How dp_layer_sqnorm evaluates ||A_i^T G_i||_F^2 when T > 1.
@@ -233,8 +234,7 @@ dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
  *   G          device, [B,T,d_out] of `dtype`, read only
  *   bias_rows  device, float32[B, d_out], written; keep it for dp_clipped_bias_grad
  *   sqnorm     device, float32[B]
- * B must be < 65536 and dtype float32 or a 16-bit type (DP_ERR_UNSUPPORTED
- * otherwise).  No workspace. */
+ * B must be < 65536 (DP_ERR_UNSUPPORTED otherwise).  No workspace. */
 dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
                          dp_dtype dtype, int accumulate, float* sqnorm,
                          float* bias_rows, void* hip_stream);
@@ -246,8 +246,8 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
  *     beta_rows[i, :]  = sum_t G_i[t, :]
  *     sqnorm[i] = (accumulate ? sqnorm[i] : 0) + ||gamma_rows[i]||^2 + ||beta_rows[i]||^2
  * gamma_rows, beta_rows: device float32[B, d], written; their clipped sums
- * are two calls of dp_clipped_bias_grad.  B must be < 65536 and dtype float32
- * or a 16-bit type.  No workspace. */
+ * are two calls of dp_clipped_bias_grad.  B must be < 65536.  No workspace.
+ * With the 8-bit pair type DP_F8_E4M3_E5M2, G is e5m2 and Hbar e4m3. */
 dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_t T, int64_t d,
                               dp_dtype dtype, int accumulate, float* sqnorm,
                               float* gamma_rows, float* beta_rows, void* hip_stream);

@@ -296,7 +296,7 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_
     dp_status st = check_dims(B, T, 1, d_out);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
-    if (B >= 65536 || is8(dtype)) return DP_ERR_UNSUPPORTED;
+    if (B >= 65536) return DP_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (B == 0) return DP_OK;
     if (!sqnorm) return DP_ERR_INVALID_ARG;
@@ -311,7 +311,9 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_
         return DP_OK;
     }
     if (!G || !aligned16(G)) return DP_ERR_INVALID_ARG;
-    hipError_t e = launch_bias_rows(G, nullptr, (int)B, (int)T, (int)d_out, (int)dtype, bias_rows, nullptr, stream);
+    // element type of G for the row kernels: the 8-bit pair types store G as e5m2 unless both are e4m3
+    const int gdt = is8(dtype) ? (g_is_e5m2(dtype) ? 4 : 3) : (int)dtype;
+    hipError_t e = launch_bias_rows(G, nullptr, (int)B, (int)T, (int)d_out, gdt, bias_rows, nullptr, stream);
     if (e == hipSuccess) e = launch_rows_sqnorm(bias_rows, (int)B, (int)d_out, accumulate != 0, sqnorm, stream);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
@@ -321,7 +323,7 @@ dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_
     dp_status st = check_dims(B, T, 1, d);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
-    if (B >= 65536 || is8(dtype)) return DP_ERR_UNSUPPORTED;
+    if (B >= 65536) return DP_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (B == 0) return DP_OK;
     if (!sqnorm) return DP_ERR_INVALID_ARG;
@@ -337,7 +339,9 @@ dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_
         return DP_OK;
     }
     if (!G || !Hbar || !aligned16(G) || !aligned16(Hbar)) return DP_ERR_INVALID_ARG;
-    hipError_t e = launch_bias_rows(G, Hbar, (int)B, (int)T, (int)d, (int)dtype, gamma_rows, beta_rows, stream);
+    // 8-bit types: Hbar is an activation (stored like A), G a backpropagated gradient
+    const int gdt = dtype == DP_F8_E4M3 ? 3 : dtype == DP_F8_E5M2 ? 4 : dtype == DP_F8_E4M3_E5M2 ? 5 : (int)dtype;
+    hipError_t e = launch_bias_rows(G, Hbar, (int)B, (int)T, (int)d, gdt, gamma_rows, beta_rows, stream);
     if (e == hipSuccess) e = launch_rows_sqnorm(gamma_rows, (int)B, (int)d, accumulate != 0, sqnorm, stream);
     if (e == hipSuccess) e = launch_rows_sqnorm(beta_rows, (int)B, (int)d, true, sqnorm, stream);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
@@ -454,9 +458,10 @@ dp_status dp_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64
 namespace {
 
 // checks shared by the several-layers calls and their size queries
-// op: which call asks (the 8-bit types take no bias rows)
+// op: which call asks
 dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path, bool pointers,
                        dp_op op) {
+    (void)op;
     if (n_layers < 0 || B < 0 || (n_layers > 0 && !layers)) return DP_ERR_INVALID_ARG;
     if (!valid_dtype(dtype) || !valid_path(path)) return DP_ERR_INVALID_ARG;
     if (n_layers > 4096) return DP_ERR_UNSUPPORTED;
@@ -465,7 +470,6 @@ dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
         const dp_status st = check_dims(B, y.T, y.d_in, y.d_out);
         if (st != DP_OK) return st;
         if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
-        if (is8(dtype) && op == DP_OP_SQNORM && y.bias_rows) return DP_ERR_UNSUPPORTED;
         if (pointers && (!y.A || !y.G || !aligned16(y.A) || !aligned16(y.G))) return DP_ERR_INVALID_ARG;
         if (pointers && y.bias_rows && B > 65535) return DP_ERR_UNSUPPORTED;                      // as dp_bias_sqnorm
     }
@@ -483,7 +487,7 @@ size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
             if (in_batch == kGramBatch) { in_batch = 0; batch = 0; }
             const GramPlan g = plan_gram_bf16((int)y.T, (int)y.d_in, (int)y.d_out);
             batch += (size_t)B * g.npairs * sizeof(float);
-            if (y.bias_rows) batch += (size_t)B * g.nt * (size_t)y.d_out * sizeof(float);      // column sums per row tile
+            if (y.bias_rows && !is8(dtype)) batch += (size_t)B * g.nt * (size_t)y.d_out * sizeof(float);      // column sums per row tile
             ++in_batch;
             if (batch > batch_max) batch_max = batch;
         } else {
@@ -554,7 +558,8 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
         if (!y.bias_rows || y.d_out == 0) continue;
-        if (y.T > 1 && y.d_in > 0 && gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;     // taken by the Gram kernel
+        // taken by the Gram kernel (16-bit types: the 8-bit Gram kernel has no column sums)
+        if (!is8(dtype) && y.T > 1 && y.d_in > 0 && gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
         const dp_status s1 = dp_bias_sqnorm(y.G, B, y.T, y.d_out, dtype, acc, sqnorm, y.bias_rows, hip_stream);
         if (s1 != DP_OK) return s1;
         acc = 1; launched = true;
@@ -591,7 +596,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (!gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
         if (nb == kGramBatch && flush(false) != hipSuccess) return DP_ERR_HIP;       // full, and another layer follows
-        batch[nb++] = GramLayerDesc{y.A, y.G, (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, y.bias_rows};
+        batch[nb++] = GramLayerDesc{y.A, y.G, (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, is8(dtype) ? nullptr : y.bias_rows};
     }
     const bool clip_in_finalize = clip != nullptr && nb > 0;
     if (flush(true) != hipSuccess) return DP_ERR_HIP;

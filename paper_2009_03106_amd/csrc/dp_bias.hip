@@ -6,6 +6,7 @@
 // All of it is bandwidth-bound; every sum runs in a fixed order (no atomics).
 #include "dp_common.h"
 #include "dp_internal.h"
+#include <type_traits>
 
 namespace dpk {
 
@@ -16,12 +17,20 @@ namespace {
 // adds rows rgid, rgid + rg, ... in ascending order; the rg partial sums are then added in the
 // order 0 .. rg-1.  Needs D % VEC == 0 (with the 16-byte aligned base every load is aligned).
 // PROD: a second input Hb of the same shape; u2 gets the plain column sums and u the sums of G (*) Hb.
-// DT: 0 = float32, 1 = bf16, 2 = fp16
-template <int DT, bool PROD>
+// DT (type of G), DTH (type of Hb): 0 = float32, 1 = bf16, 2 = fp16, 3 = e4m3, 4 = e5m2; both of the same width
+template <int DT> struct ElemBytes { static constexpr int value = DT == 0 ? 4 : (DT >= 3 ? 1 : 2); };
+// one 8-bit float -> float32 (e5m2 is the upper byte of an fp16)
+template <int DT> __device__ __forceinline__ float f8_byte(uint32_t word, int which) {
+    if (DT == 4) return (float)__builtin_bit_cast(_Float16, (uint16_t)(((word >> (8 * which)) & 0xffu) << 8));
+    return which == 0 ? __builtin_amdgcn_cvt_f32_fp8((int)word, 0) : which == 1 ? __builtin_amdgcn_cvt_f32_fp8((int)word, 1)
+         : which == 2 ? __builtin_amdgcn_cvt_f32_fp8((int)word, 2) : __builtin_amdgcn_cvt_f32_fp8((int)word, 3);
+}
+template <int DT, bool PROD, int DTH = DT>
 __global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__ G, const void* __restrict__ Hb, int T, int D, int ctl,
                                                         float* __restrict__ u, float* __restrict__ u2) {
-    constexpr bool BF16 = DT != 0;                    // 16-bit elements
-    constexpr int VEC = BF16 ? 8 : 4;
+    constexpr int ES = ElemBytes<DT>::value;          // bytes per element
+    static_assert(ElemBytes<DTH>::value == ES, "G and Hb of one width");
+    constexpr int VEC = 16 / ES;
     __shared__ float part[kThreads][PROD ? 2 * VEC : VEC];
     const int tid = threadIdx.x, ct = 1 << ctl, rg = kThreads >> ctl;
     const int ctid = tid & (ct - 1), rgid = tid >> ctl;
@@ -30,34 +39,40 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__
     float acc[VEC], acc2[VEC];                        // acc2 (PROD only): plain sums
 #pragma unroll
     for (int v = 0; v < VEC; ++v) { acc[v] = 0.f; acc2[v] = 0.f; }
-    auto widen = [&](const uint4& w, float (&x)[VEC]) {
-        if (BF16) {
-            const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+    auto widen = [&](const uint4& w, float (&x)[VEC], auto tag) {
+        constexpr int E = decltype(tag)::value;
+        const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+        if constexpr (E >= 3) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { x[2 * j] = In16<DT == 2>::lo(d[j]); x[2 * j + 1] = In16<DT == 2>::hi(d[j]); }
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) x[4 * j + k] = f8_byte<E>(d[j], k);
+        } else if constexpr (E != 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { x[2 * j] = In16<E == 2>::lo(d[j]); x[2 * j + 1] = In16<E == 2>::hi(d[j]); }
         } else {
             x[0] = __uint_as_float(w.x); x[1] = __uint_as_float(w.y); x[2] = __uint_as_float(w.z); x[3] = __uint_as_float(w.w);
         }
     };
     auto add = [&](const uint4& w) {
         float x[VEC];
-        widen(w, x);
+        widen(w, x, std::integral_constant<int, DT>{});
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] += x[v];
     };
     auto add_prod = [&](const uint4& w, const uint4& h) {
         float x[VEC], y[VEC];
-        widen(w, x);
-        widen(h, y);
+        widen(w, x, std::integral_constant<int, DT>{});
+        widen(h, y, std::integral_constant<int, DTH>{});
 #pragma unroll
         for (int v = 0; v < VEC; ++v) { acc[v] += x[v] * y[v]; acc2[v] += x[v]; }
     };
     if (col0 < D) {
-        const size_t row_bytes = (size_t)D * (BF16 ? 2 : 4);
-        const unsigned char* p = static_cast<const unsigned char*>(G) + ((size_t)ex * T) * row_bytes + (size_t)col0 * (BF16 ? 2 : 4);
+        const size_t row_bytes = (size_t)D * ES;
+        const unsigned char* p = static_cast<const unsigned char*>(G) + ((size_t)ex * T) * row_bytes + (size_t)col0 * ES;
         int t = rgid;
         if (PROD) {
-            const unsigned char* q = static_cast<const unsigned char*>(Hb) + ((size_t)ex * T) * row_bytes + (size_t)col0 * (BF16 ? 2 : 4);
+            const unsigned char* q = static_cast<const unsigned char*>(Hb) + ((size_t)ex * T) * row_bytes + (size_t)col0 * ES;
             for (; t + 3 * rg < T; t += 4 * rg) {      // eight loads in flight, added in row order
                 uint4 w[4], h[4];
 #pragma unroll
@@ -100,7 +115,12 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__
 }
 
 // Any D: one thread per column, rows in ascending order.
-template <int DT, bool PROD>
+template <int DT> __device__ __forceinline__ float load_elem(const void* p, size_t k) {
+    if (DT >= 3) return f8_byte<DT>(static_cast<const unsigned char*>(p)[k], 0);
+    if (DT != 0) return In16<DT == 2>::lo(static_cast<const uint16_t*>(p)[k]);
+    return static_cast<const float*>(p)[k];
+}
+template <int DT, bool PROD, int DTH = DT>
 __global__ __launch_bounds__(kThreads) void k_bias_rows_scalar(const void* __restrict__ G, const void* __restrict__ Hb, int T, int D,
                                                                float* __restrict__ u, float* __restrict__ u2) {
     const int q = blockIdx.x * kThreads + threadIdx.x;
@@ -110,9 +130,9 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows_scalar(const void* __res
     const size_t base = (size_t)ex * T * D + q;
     for (int t = 0; t < T; ++t) {
         const size_t k = base + (size_t)t * D;
-        const float g = DT != 0 ? In16<DT == 2>::lo(static_cast<const uint16_t*>(G)[k]) : static_cast<const float*>(G)[k];
+        const float g = load_elem<DT>(G, k);
         if (PROD) {
-            const float h = DT != 0 ? In16<DT == 2>::lo(static_cast<const uint16_t*>(Hb)[k]) : static_cast<const float*>(Hb)[k];
+            const float h = load_elem<DTH>(Hb, k);
             acc += g * h; acc2 += g;
         } else {
             acc += g;
@@ -160,8 +180,8 @@ __global__ __launch_bounds__(kThreads) void k_clipped_bias(const float* __restri
     }
 }
 
-template <int DT> void launch_bias_rows_dt(const void* G, const void* Hb, int B, int T, int D, float* u, float* u2, hipStream_t st) {
-    constexpr int vec = DT != 0 ? 8 : 4;
+template <int DT, int DTH = DT> void launch_bias_rows_dt(const void* G, const void* Hb, int B, int T, int D, float* u, float* u2, hipStream_t st) {
+    constexpr int vec = 16 / ElemBytes<DT>::value;
     const bool prod = Hb != nullptr;
     if (D % vec == 0) {
         const int nvec = D / vec;
@@ -171,11 +191,11 @@ template <int DT> void launch_bias_rows_dt(const void* G, const void* Hb, int B,
         // to keep enough loads in flight for HBM
         while (ctl > 4 && (int64_t)((nvec + (1 << ctl) - 1) >> ctl) * B < 1024) --ctl;
         const dim3 grid((unsigned)((nvec + (1 << ctl) - 1) >> ctl), (unsigned)B);
-        if (prod) k_bias_rows<DT, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
+        if (prod) k_bias_rows<DT, true, DTH><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
         else      k_bias_rows<DT, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, ctl, u, u2);
     } else {
         const dim3 grid((unsigned)((D + kThreads - 1) / kThreads), (unsigned)B);
-        if (prod) k_bias_rows_scalar<DT, true><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
+        if (prod) k_bias_rows_scalar<DT, true, DTH><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
         else      k_bias_rows_scalar<DT, false><<<grid, kThreads, 0, st>>>(G, Hb, T, D, u, u2);
     }
 }
@@ -183,9 +203,13 @@ template <int DT> void launch_bias_rows_dt(const void* G, const void* Hb, int B,
 }  // namespace
 
 // Hb == nullptr: u = column sums of G.  Otherwise u = column sums of G (*) Hb and u2 = column sums of G.
+// dt: type of G and Hb as above; 5: G e5m2 with Hb e4m3.
 hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, int dt, float* u, float* u2, hipStream_t st) {
     if (B > 65535) return hipErrorInvalidValue;          // grid.y
-    if (dt == 2)      launch_bias_rows_dt<2>(G, Hb, B, T, D, u, u2, st);
+    if (dt == 5)      launch_bias_rows_dt<4, 3>(G, Hb, B, T, D, u, u2, st);
+    else if (dt == 4) launch_bias_rows_dt<4>(G, Hb, B, T, D, u, u2, st);
+    else if (dt == 3) launch_bias_rows_dt<3>(G, Hb, B, T, D, u, u2, st);
+    else if (dt == 2) launch_bias_rows_dt<2>(G, Hb, B, T, D, u, u2, st);
     else if (dt == 1) launch_bias_rows_dt<1>(G, Hb, B, T, D, u, u2, st);
     else              launch_bias_rows_dt<0>(G, Hb, B, T, D, u, u2, st);
     return hipGetLastError();

@@ -347,8 +347,9 @@ def layernorm_sqnorm(G: torch.Tensor, Hbar: torch.Tensor, sqnorm: Optional[torch
     lib = load_library()
     if G.dim() == 2:
         G, Hbar = G.unsqueeze(1), Hbar.unsqueeze(1)
-    if G.dim() != 3 or G.shape != Hbar.shape or G.dtype != Hbar.dtype:
-        raise ValueError("G and Hbar must have the same [B, T, d] shape and dtype")
+    if G.dim() != 3 or G.shape != Hbar.shape:
+        raise ValueError("G and Hbar must have the same [B, T, d] shape")
+    dt = _dtype_code(Hbar, G)               # one dtype, or Hbar e4m3 (an activation) with G e5m2
     G, Hbar = G.contiguous(), Hbar.contiguous()
     B, T, d = G.shape
     if sqnorm is None:
@@ -357,7 +358,7 @@ def layernorm_sqnorm(G: torch.Tensor, Hbar: torch.Tensor, sqnorm: Optional[torch
         sqnorm = torch.empty(B, dtype=torch.float32, device=G.device)
     gam = torch.empty((B, d), dtype=torch.float32, device=G.device)
     bet = torch.empty((B, d), dtype=torch.float32, device=G.device)
-    st = lib.dp_layernorm_sqnorm(_ptr(G), _ptr(Hbar), B, T, d, _dtype_code(G), int(bool(accumulate)), _ptr(sqnorm),
+    st = lib.dp_layernorm_sqnorm(_ptr(G), _ptr(Hbar), B, T, d, dt, int(bool(accumulate)), _ptr(sqnorm),
                                  _ptr(gam), _ptr(bet), _stream_ptr(stream))
     _check(st, "dp_layernorm_sqnorm")
     return sqnorm, gam, bet

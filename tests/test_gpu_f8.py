@@ -233,30 +233,63 @@ def test_f8_mixed_layers_call(dp, dtype):
         assert fro_err(g.cpu().numpy(), orc.clipped_grad(A, G, c.cpu().numpy().astype(np.float64))) <= 2e-3
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(3, 256, 384), (2, 100, 136), (5, 1, 512), (4, 513, 48), (2, 37, 33)])
+def test_f8_bias_and_layernorm_rows(dp, dtype, shape):
+    """Bias rows sum_t G_i[t] and LayerNorm rows sum_t G_i[t] * Hbar_i[t] from 8-bit inputs (Hbar stored like A),
+    their squared norms, and the clipped bias sum, for widths with and without whole 16-byte pieces."""
+    B, T, d = shape
+    (H, G), (Hd, Gd) = draw(41, B, T, d, d, dtype)
+    u_ref = orc.bias_rows(G)
+    rows = torch.empty((B, d), device="cuda")
+    s, _ = dp.bias_sqnorm(Gd, None, rows)
+    assert np.max(np.abs(rows.cpu().numpy() - u_ref)) <= 1e-6 * np.max(np.sum(np.abs(G), axis=1))
+    assert rel_err(s.cpu().numpy(), orc.bias_sqnorm(G)) <= 1e-5 or np.all(np.abs(s.cpu().numpy() - orc.bias_sqnorm(G)) <= 1e-12)
+    gam_ref, bet_ref = orc.layernorm_rows(G, H)
+    out = dp.layernorm_sqnorm(Gd, Hd)
+    s2, gam, bet = out
+    scale = np.max(np.sum(np.abs(G * H), axis=1)) + 1e-300
+    assert np.max(np.abs(gam.cpu().numpy() - gam_ref)) <= 1e-6 * scale
+    assert np.max(np.abs(bet.cpu().numpy() - bet_ref)) <= 1e-6 * np.max(np.sum(np.abs(G), axis=1))
+    ref2 = orc.layernorm_sqnorm(G, H)
+    assert np.all(np.abs(s2.cpu().numpy() - ref2) <= 1e-5 * ref2 + 1e-12)
+    clip = torch.rand(B, device="cuda")
+    gb = dp.clipped_bias_grad(rows, clip).cpu().numpy()
+    assert np.max(np.abs(gb - orc.clipped_bias_grad(G, clip.cpu().numpy().astype(np.float64)))) <= 1e-5 * np.max(np.abs(u_ref)) * B
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_f8_layers_call_with_bias_rows(dp, dtype):
+    """Weights and biases of several 8-bit layers clipped together in one norm call (the bias rows of 8-bit layers
+    are taken in a pass of their own)."""
+    shapes = [(256, 256, 384), (1, 512, 64), (100, 72, 40)]
+    B = 4
+    wides, devs = [], []
+    for k, (T, di, do) in enumerate(shapes):
+        w, d = draw(50 + k, B, T, di, do, dtype)
+        wides.append(w); devs.append(d)
+    rows = [torch.empty((B, do), device="cuda") for _, _, do in shapes]
+    descs = dp.layer_descs(devs, bias_rows=rows)
+    s = dp.layers_sqnorm(devs, descs=descs)
+    ref = orc.total_sqnorm(wides) + sum(orc.bias_sqnorm(G) for _, G in wides)
+    assert rel_err(s.cpu().numpy(), ref) <= SQ_TOL8
+    for (_, G), u in zip(wides, rows):
+        assert np.max(np.abs(u.cpu().numpy() - orc.bias_rows(G))) <= 1e-6 * np.max(np.sum(np.abs(G), axis=1))
+
+
 def test_f8_unsupported_is_reported(dp):
-    """Bias rows, LayerNorm rows and the convolution from the image do not take 8-bit inputs: DP_ERR_UNSUPPORTED,
-    before anything is launched."""
-    (_, _), (Ad, Gd) = draw(16, 2, 128, 128, 128, "f8")
-    with pytest.raises(dp.DpclipError) as ei:
-        dp.bias_sqnorm(Gd)
-    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
-    with pytest.raises(dp.DpclipError) as ei:
-        dp.layernorm_sqnorm(Gd, Gd)
-    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    """The convolution from the image does not take 8-bit inputs: DP_ERR_UNSUPPORTED, before anything is launched."""
     X = torch.zeros((2, 16, 16, 16), dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
     Gc = torch.zeros((2, 256, 128), dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
-    with pytest.raises(dp.DpclipError) as ei:
-        dp.conv_sqnorm(X, Gc, 3, 3, 1)
-    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
-    # a several-layers call that asks for bias rows leaves its outputs alone
     s = torch.full((2,), 7.0, device="cuda")
-    rows = torch.full((2, 128), 7.0, device="cuda")
-    descs = dp.layer_descs([(Ad, Gd)], bias_rows=[rows])
     with pytest.raises(dp.DpclipError) as ei:
-        dp.layers_sqnorm([(Ad, Gd)], s, descs=descs)
+        dp.conv_sqnorm(X, Gc, 3, 3, 1, s)
+    assert ei.value.status == dp.DP_ERR_UNSUPPORTED
+    with pytest.raises(dp.DpclipError) as ei:
+        dp.conv_clipped_grad(X, Gc, torch.ones(2, device="cuda"), 3, 3, 1)
     assert ei.value.status == dp.DP_ERR_UNSUPPORTED
     torch.cuda.synchronize()
-    assert torch.all(s == 7.0) and torch.all(rows == 7.0)
+    assert torch.all(s == 7.0)
 
 
 def test_f8_empty_problems_and_argument_errors(dp):
