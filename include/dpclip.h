@@ -79,8 +79,8 @@ typedef enum {
  * the widened values, 2 bytes per input element more workspace (the size queries
  * include it).  dp_bias_sqnorm and dp_layernorm_sqnorm read 8-bit G (and
  * Hbar, stored like A) directly; bias_rows of dp_layers_sqnorm are then taken
- * in a pass of their own.  Not taken (DP_ERR_UNSUPPORTED): the
- * convolution-from-image calls. */
+ * in a pass of their own.  The convolution-from-image calls widen X and G to
+ * fp16 in their workspace. */
 typedef enum { DP_F32 = 0, DP_BF16 = 1, DP_F16 = 2, DP_F8_E4M3 = 3, DP_F8_E5M2 = 4, DP_F8_E4M3_E5M2 = 5 } dp_dtype;
 
 /* How dp_layer_sqnorm evaluates ||A_i^T G_i||_F^2 when T > 1.
@@ -265,7 +265,7 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
  * matrix (Section 5.2; Algorithm 3 unfolds the image first, here the patches
  * are formed on the fly, so the kh*kw-fold larger matrix never exists in
  * memory).  Stride 1, zero padding `pad` on every side:
- *   X  device, [B, H, W, C] of bf16 or fp16, channels last
+ *   X  device, [B, H, W, C] of bf16, fp16 or an 8-bit type, channels last
  *   G  device, [B, T, d_out] of the same type, T = H_out * W_out output positions in
  *      row-major (y, x) order, H_out = H + 2 pad - KH + 1, W_out likewise
  * The layer's weight gradient is [d_in, d_out] with d_in = KH*KW*C and row
@@ -273,7 +273,7 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
  * dp_conv_sqnorm and dp_conv_clipped_grad compute exactly what
  * dp_layer_sqnorm (direct path) and dp_clipped_grad compute on the unfolded
  * A[B, T, d_in]; arguments not listed here mean the same as there.
- * Supported: DP_BF16 and DP_F16, C % 8 == 0, d_out % 8 == 0, T >= 64 with at most a quarter
+ * Supported: DP_BF16, DP_F16 and the 8-bit types (widened to fp16), C % 8 == 0, d_out % 8 == 0, T >= 64 with at most a quarter
  * of padding up to the next multiple of 32 (e.g. 784, 196, 1024), and a
  * [d_in, d_out] that tiles into 256 x 256, 192 x 128 or 128 x 128 blocks with at
  * most a quarter of padding; anything else is DP_ERR_UNSUPPORTED (unfold and use the

@@ -368,6 +368,11 @@ size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_
     ConvGeom g; int64_t T, d_in;
     if (conv_geometry(B, H, W, C, KH, KW, pad, d_out, dtype, &g, &T, &d_in) != DP_OK) return 0;
     if (B == 0 || C == 0 || d_out == 0 || H == 0 || W == 0) return 0;
+    if (is8(dtype)) {
+        // widened to fp16 at the head of the workspace
+        const size_t inner = dp_conv_workspace_bytes(op, B, H, W, C, KH, KW, pad, d_out, DP_F16);
+        return inner == 0 ? 0 : widen_bytes(B * H * W * C) + widen_bytes(B * T * d_out) + inner;
+    }
     if (!is16(dtype) || !dma_conv_ok(g, (int)d_out)) return 0;
     if (op == DP_OP_SQNORM) {
         const TnPlan p = plan_direct_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
@@ -393,8 +398,18 @@ dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int
         if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
         return DP_OK;
     }
-    if (!is16(dtype) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    if (!(is16(dtype) || is8(dtype)) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
     if (!X || !G || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
+    if (is8(dtype)) {
+        const size_t nx = widen_bytes(B * H * W * C), ng = widen_bytes(B * T * d_out);
+        const size_t inner = dp_conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, DP_F16);
+        if (!workspace || workspace_bytes < nx + ng + inner || !aligned16(workspace)) return DP_ERR_WORKSPACE;
+        unsigned char* w = static_cast<unsigned char*>(workspace);
+        if (launch_widen_f8(X, reinterpret_cast<uint16_t*>(w), B * H * W * C, a_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        if (launch_widen_f8(G, reinterpret_cast<uint16_t*>(w + nx), B * T * d_out, g_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        return dp_conv_sqnorm(w, w + nx, B, H, W, C, KH, KW, pad, d_out, DP_F16, accumulate, sqnorm, w + nx + ng,
+                              workspace_bytes - nx - ng, hip_stream);
+    }
     const size_t need = dp_conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dtype);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
@@ -421,8 +436,18 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, 
         if (!accumulate && launch_fill_zero(grad, d_in * d_out, stream) != hipSuccess) return DP_ERR_HIP;
         return DP_OK;
     }
-    if (!is16(dtype) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    if (!(is16(dtype) || is8(dtype)) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
     if (!X || !G || !clip || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
+    if (is8(dtype)) {
+        const size_t nx = widen_bytes(B * H * W * C), ng = widen_bytes(B * T * d_out);
+        const size_t inner = dp_conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, DP_F16);
+        if (!workspace || workspace_bytes < nx + ng + inner || !aligned16(workspace)) return DP_ERR_WORKSPACE;
+        unsigned char* w = static_cast<unsigned char*>(workspace);
+        if (launch_widen_f8(X, reinterpret_cast<uint16_t*>(w), B * H * W * C, a_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        if (launch_widen_f8(G, reinterpret_cast<uint16_t*>(w + nx), B * T * d_out, g_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
+        return dp_conv_clipped_grad(w, w + nx, clip, B, H, W, C, KH, KW, pad, d_out, DP_F16, accumulate, grad, w + nx + ng,
+                                    workspace_bytes - nx - ng, hip_stream);
+    }
     const size_t need = dp_conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dtype);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
     float* zero = static_cast<float*>(workspace);

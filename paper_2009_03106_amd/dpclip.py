@@ -387,8 +387,9 @@ def _conv_args(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int):
     X, G = X.contiguous(), G.contiguous()
     B, H, W, C = X.shape
     T = (H + 2 * pad - KH + 1) * (W + 2 * pad - KW + 1)
-    if G.shape[1] != T or X.dtype != G.dtype:
-        raise ValueError("G does not match the convolution's output positions / dtype")
+    if G.shape[1] != T:
+        raise ValueError("G does not match the convolution's output positions")
+    _dtype_code(X, G)                       # one dtype, or the e4m3 / e5m2 pair
     return X, G, B, H, W, C, G.shape[2]
 
 
@@ -402,7 +403,7 @@ def conv_sqnorm(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int, sq
     """sqnorm[i] (+)= squared norm of example i's kernel gradient, from the image X, via dp_conv_sqnorm."""
     lib = load_library()
     X, G, B, H, W, C, d_out = _conv_args(X, G, KH, KW, pad)
-    dt = _dtype_code(X)
+    dt = _dtype_code(X, G)
     if sqnorm is None:
         if accumulate:
             raise ValueError("accumulate needs an existing sqnorm tensor")
@@ -420,7 +421,7 @@ def conv_clipped_grad(X: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, KH: 
     """grad (+)= sum_i clip[i] * (kernel gradient of example i), float32 [KH*KW*C, d_out], via dp_conv_clipped_grad."""
     lib = load_library()
     X, G, B, H, W, C, d_out = _conv_args(X, G, KH, KW, pad)
-    dt = _dtype_code(X)
+    dt = _dtype_code(X, G)
     if grad is None:
         if accumulate:
             raise ValueError("accumulate needs an existing grad tensor")

@@ -277,9 +277,33 @@ def test_f8_layers_call_with_bias_rows(dp, dtype):
         assert np.max(np.abs(u.cpu().numpy() - orc.bias_rows(G))) <= 1e-6 * np.max(np.sum(np.abs(G), axis=1))
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_f8_conv_from_image_runs_widened(dp, dtype):
+    """The convolution given by its image takes 8-bit inputs by widening them to fp16 in the workspace: results
+    against the oracle's unfolding, and bit for bit the DP_F16 call on the widened values."""
+    B, H, W, C, d_out, KH, KW, pad = 3, 16, 16, 64, 128, 3, 3, 1
+    rng = np.random.default_rng(61)
+    X = np.maximum(rng.standard_normal((B, H, W, C), dtype=np.float32), 0)
+    G = rng.standard_normal((B, H * W, d_out), dtype=np.float32) * np.float32(1e-3 * G_SCALE[dtype])
+    sa, sg = wl.f8_formats(dtype)
+    Xb, Gb = wl.f32_to_f8_bits(X, sa[2:]), wl.f32_to_f8_bits(G, sg[2:])
+    Xw, Gw = wide(Xb, sa), wide(Gb, sg)
+    Xd, Gd = to_dev8(Xb, sa), to_dev8(Gb, sg)
+    A = orc.conv_unfold(Xw, KH, KW, pad)
+    s = dp.conv_sqnorm(Xd, Gd, KH, KW, pad)
+    assert rel_err(s.cpu().numpy(), orc.layer_sqnorm(A, Gw)) <= SQ_TOL8
+    clip = torch.tensor([1.0, 0.3, 0.7], device="cuda")
+    g = dp.conv_clipped_grad(Xd, Gd, clip, KH, KW, pad)
+    assert fro_err(g.cpu().numpy(), orc.clipped_grad(A, Gw, clip.cpu().numpy().astype(np.float64))) <= FRO_TOL8
+    X16, G16 = torch.from_numpy(Xw.astype(np.float16)).cuda(), torch.from_numpy(Gw.astype(np.float16)).cuda()
+    np.testing.assert_array_equal(s.cpu().numpy(), dp.conv_sqnorm(X16, G16, KH, KW, pad).cpu().numpy())
+    np.testing.assert_array_equal(g.cpu().numpy(), dp.conv_clipped_grad(X16, G16, clip, KH, KW, pad).cpu().numpy())
+
+
 def test_f8_unsupported_is_reported(dp):
-    """The convolution from the image does not take 8-bit inputs: DP_ERR_UNSUPPORTED, before anything is launched."""
-    X = torch.zeros((2, 16, 16, 16), dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
+    """A convolution geometry that the image kernels do not take stays DP_ERR_UNSUPPORTED for 8-bit inputs too
+    (here 12 channels: whole 16-byte pieces must stay inside one pixel), before anything is launched."""
+    X = torch.zeros((2, 16, 16, 12), dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
     Gc = torch.zeros((2, 256, 128), dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
     s = torch.full((2,), 7.0, device="cuda")
     with pytest.raises(dp.DpclipError) as ei:
