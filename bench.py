@@ -66,7 +66,7 @@ class Pipeline:
               "f8": dp.DP_F8_E4M3_E5M2}[w.dtype]
         self.s = torch.zeros(self.B, dtype=torch.float32, device="cuda")
         self.c = torch.zeros(self.B, dtype=torch.float32, device="cuda")
-        self.grads, self.ws_sq, self.ws_cg = [], [], []
+        self.grads = []
         # the layers' gradients lie one after the other in one flat buffer (the model's flat parameter gradient):
         # the noise is then one call over the whole buffer, whose offsets are the per-layer calls' running offsets
         sizes = [spec.d_in * spec.d_out for spec in w.layers]
@@ -74,10 +74,6 @@ class Pipeline:
         starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
         for li, spec in enumerate(w.layers):
             self.grads.append(self.flat_grad[starts[li]:starts[li + 1]].view(spec.d_in, spec.d_out))
-            n1 = dp.workspace_bytes(dp.DP_OP_SQNORM, self.B, spec.T, spec.d_in, spec.d_out, dt, path)
-            n2 = dp.workspace_bytes(dp.DP_OP_CLIPPED_GRAD, self.B, spec.T, spec.d_in, spec.d_out, dt)
-            self.ws_sq.append(torch.empty(max(n1, 16), dtype=torch.uint8, device="cuda"))
-            self.ws_cg.append(torch.empty(max(n2, 16), dtype=torch.uint8, device="cuda"))
         self.descs = dp.layer_descs(self.dev)
         order = sorted(range(len(self.dev)), key=lambda li: self.dev[li][0].shape[2] + self.dev[li][1].shape[2])
         self.dev_cg = [self.dev[li] for li in order]
@@ -86,35 +82,23 @@ class Pipeline:
         self.ws_layers = torch.empty(max(16, dp.layers_workspace_bytes(self.descs[0], self.B, dt, path)), dtype=torch.uint8, device="cuda")
 
     def phase_sqnorm(self):
-        if len(self.dev) > 1:
-            # all layers in one call: the copy-pipeline Gram layers share a launch
-            # ... and the launch that completes the norms writes the clip factors
-            self.dp.layers_sqnorm(self.dev, self.s, path=self.path, workspace=self.ws_layers, descs=self.descs,
-                                  C=self.w.C, clip=self.c)
-            return
-        for li, (A, G) in enumerate(self.dev):
-            self.dp.layer_sqnorm(A, G, self.s, path=self.path, accumulate=li > 0, workspace=self.ws_sq[li])
+        # all layers in one call: the copy-pipeline Gram layers share a launch, dense layers share one, and the
+        # launch that completes the norms writes the clip factors (a kernel of its own where no Gram launch does)
+        self.dp.layers_sqnorm(self.dev, self.s, path=self.path, workspace=self.ws_layers, descs=self.descs,
+                              C=self.w.C, clip=self.c)
 
     def phase_clip(self):
-        if len(self.dev) == 1:                                 # several layers: done by phase_sqnorm
-            self.dp.clip_factors(self.s, self.w.C, self.c)
+        pass                                                   # done by phase_sqnorm
 
     def phase_grad(self):
         # the layers that the norm phase read last first: their inputs are the likeliest to be still in the
-        # Infinity Cache (the several-layers call runs the widest layers first, a single call per layer runs them
-        # in the order given)
-        if len(self.dev) > 1:
-            # with the noise of the flat gradient buffer added by the kernels that fold the K slices
-            self.dp.layers_clipped_grad(self.dev_cg, self.c, workspace=self.ws_cg_all, descs=self.descs_cg,
-                                        noise_std=self.w.noise_std, seed=self.w.noise_seed)
-            return
-        for li in range(len(self.dev)):
-            A, G = self.dev[li]
-            self.dp.clipped_grad(A, G, self.c, self.grads[li], workspace=self.ws_cg[li])
+        # Infinity Cache (the several-layers call runs the widest layers first); the noise of the flat gradient
+        # buffer is added by the kernels that fold the K slices (by the noise kernel where there is one slice)
+        self.dp.layers_clipped_grad(self.dev_cg, self.c, workspace=self.ws_cg_all, descs=self.descs_cg,
+                                    noise_std=self.w.noise_std, seed=self.w.noise_seed)
 
     def phase_noise(self):
-        if self.w.noise_std > 0 and len(self.dev) == 1:       # several layers: added in phase_grad
-            self.dp.add_noise(self.flat_grad, self.w.noise_std, self.w.noise_seed, 0)
+        pass                                                   # added in phase_grad
 
     def step(self, events=None):
         if events is not None:
@@ -291,7 +275,7 @@ def main():
         "clipped_grad_tflops": work["gemm_flops"] / (grad_ms * 1e-3) / 1e12,
         "clipped_grad_gbs": work["gemm_bytes"] / (grad_ms * 1e-3) / 1e9,
     }
-    noise_fused = w.noise_std > 0 and len(w.layers) > 1
+    noise_fused = w.noise_std > 0
     if noise_fused:
         # the noise is added inside the clipped-sum phase (by the kernels that fold the K slices): no pass of its own
         phases_out["noise_ms"] = 0.0
