@@ -105,6 +105,10 @@ dp_status conv_geometry(int64_t B, int64_t H, int64_t W, int64_t C, int64_t KH, 
     return DP_OK;
 }
 
+dp_status layer_sqnorm_clip(const void* A, const void* G, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                            dp_dtype dtype, dp_path path, int accumulate, float* sqnorm,
+                            void* workspace, size_t workspace_bytes, void* hip_stream, const ClipOut* co);
+
 }  // namespace
 
 extern "C" {
@@ -147,6 +151,17 @@ size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t 
 dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                           dp_dtype dtype, dp_path path, int accumulate, float* sqnorm,
                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return layer_sqnorm_clip(A, G, B, T, d_in, d_out, dtype, path, accumulate, sqnorm, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+}  // extern "C"
+
+namespace {
+
+// dp_layer_sqnorm; co != nullptr (non-empty problems only): the kernel that completes sqnorm also writes the clip factors
+dp_status layer_sqnorm_clip(const void* A, const void* G, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                            dp_dtype dtype, dp_path path, int accumulate, float* sqnorm,
+                            void* workspace, size_t workspace_bytes, void* hip_stream, const ClipOut* co) {
     dp_status st = check_dims(B, T, d_in, d_out);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype) || !valid_path(path)) return DP_ERR_INVALID_ARG;
@@ -167,11 +182,11 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
         unsigned char* w = static_cast<unsigned char*>(workspace);
         if (launch_widen_f8(A, reinterpret_cast<uint16_t*>(w), B * T * d_in, a_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
         if (launch_widen_f8(G, reinterpret_cast<uint16_t*>(w + na), B * T * d_out, g_is_e5m2(dtype), stream) != hipSuccess) return DP_ERR_HIP;
-        return dp_layer_sqnorm(w, w + na, B, T, d_in, d_out, DP_F16, path, accumulate, sqnorm, w + na + ng,
-                               workspace_bytes - na - ng, hip_stream);
+        return layer_sqnorm_clip(w, w + na, B, T, d_in, d_out, DP_F16, path, accumulate, sqnorm, w + na + ng,
+                                 workspace_bytes - na - ng, hip_stream, co);
     }
     if (T == 1) {
-        e = launch_sqnorm_dense(A, G, (int)B, (int)d_in, (int)d_out, (int)dtype, accumulate != 0, sqnorm, stream);
+        e = launch_sqnorm_dense(A, G, (int)B, (int)d_in, (int)d_out, (int)dtype, accumulate != 0, sqnorm, stream, co);
         return e == hipSuccess ? DP_OK : DP_ERR_HIP;
     }
     const dp_path p = resolve_path(path, dtype, T, d_in, d_out);
@@ -183,28 +198,32 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
     if (is8(dtype)) {
         if (p == DP_PATH_GRAM)
             e = launch_gram_bf16_dma(plan_gram_bf16((int)T, (int)d_in, (int)d_out), A, G, (int)B, (int)T, (int)d_in, (int)d_out,
-                                     accumulate != 0, sqnorm, partial, stream, fmt_of(dtype));
+                                     accumulate != 0, sqnorm, partial, stream, fmt_of(dtype), co);
         else
             e = launch_direct_f8_dma(plan_direct_f8_dma((int)B, (int)T, (int)d_in, (int)d_out), A, G, (int)B, (int)T, (int)d_in,
-                                     (int)d_out, accumulate != 0, sqnorm, partial, stream, fmt_of(dtype));
+                                     (int)d_out, accumulate != 0, sqnorm, partial, stream, fmt_of(dtype), co);
     } else if (p == DP_PATH_GRAM && !is16(dtype)) {
         e = launch_gram_f32(plan_gram_f32((int)T), static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
-                            (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
+                            (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, co);
     } else if (p == DP_PATH_GRAM) {
         GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
         e = launch_gram_bf16(g, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
-                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16);
+                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16, co);
     } else if (is16(dtype)) {
         TnPlan t = plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_direct_bf16(t, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
-                               (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16);
+                               (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16, co);
     } else {
         TnPlan t = plan_direct_f32((int)T, (int)d_in, (int)d_out);
         e = launch_direct_f32(t, static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
-                              (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream);
+                              (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, co);
     }
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
+
+}  // namespace
+
+extern "C" {
 
 dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C, float* clip, void* hip_stream) {
     if (B < 0 || !(C > 0.0f)) return DP_ERR_INVALID_ARG;
@@ -553,12 +572,32 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
 
     int acc = accumulate != 0;
     bool launched = false;
+    // Which kernel completes the norms and can write the clip factors with them: the last shared Gram launch if
+    // there is one; else, unless a bias pass follows, the last layer that runs on its own; else the last launch
+    // of dense layers.  Otherwise (bias passes at the end, or nothing to launch) the clip kernel runs.
+    int64_t n_dense = 0, last_single = -1;
+    bool any_gram = false, any_bias_pass = false;
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.bias_rows && y.d_out != 0 &&
+            !(!is8(dtype) && y.T > 1 && y.d_in > 0 && gram_batchable(y.T, y.d_in, y.d_out, dtype, path))) any_bias_pass = true;
+        if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (y.T == 1 && !is8(dtype)) ++n_dense;
+        else if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) any_gram = true;
+        else last_single = l;
+    }
+    const ClipOut clip_out{C, clip};
+    const bool clip_with_single = clip && !any_gram && !any_bias_pass && last_single >= 0;
+    const bool clip_with_dense = clip && !any_gram && !any_bias_pass && last_single < 0 && n_dense > 0;
     // dense layers (T = 1, closed form): up to kDenseBatch per launch, in the order given
     DenseLayers dense;
     dense.n_layers = 0;
+    int64_t dense_done = 0;
     auto flush_dense = [&]() -> hipError_t {
         if (dense.n_layers == 0) return hipSuccess;
-        const hipError_t e = launch_sqnorm_dense_layers(dense, (int)B, (int)dtype, acc != 0, sqnorm, stream);
+        dense_done += dense.n_layers;
+        const hipError_t e = launch_sqnorm_dense_layers(dense, (int)B, (int)dtype, acc != 0, sqnorm, stream,
+                                                        (clip_with_dense && dense_done == n_dense) ? &clip_out : nullptr);
         dense.n_layers = 0; acc = 1; launched = true;
         return e;
     };
@@ -575,7 +614,8 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         const dp_layer_desc& y = layers[l];
         if (y.T == 0 || (y.T == 1 && !is8(dtype)) || y.d_in == 0 || y.d_out == 0) continue;     // empty layers add nothing
         if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
-        const dp_status s1 = dp_layer_sqnorm(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes, hip_stream);
+        const dp_status s1 = layer_sqnorm_clip(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes,
+                                               hip_stream, (clip_with_single && l == last_single) ? &clip_out : nullptr);
         if (s1 != DP_OK) return s1;
         acc = 1; launched = true;
     }
@@ -623,10 +663,10 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (nb == kGramBatch && flush(false) != hipSuccess) return DP_ERR_HIP;       // full, and another layer follows
         batch[nb++] = GramLayerDesc{y.A, y.G, (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, is8(dtype) ? nullptr : y.bias_rows};
     }
-    const bool clip_in_finalize = clip != nullptr && nb > 0;
+    const bool clip_done = clip != nullptr && (nb > 0 || clip_with_single || clip_with_dense);
     if (flush(true) != hipSuccess) return DP_ERR_HIP;
     if (!launched && !accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
-    if (clip && !clip_in_finalize && launch_clip_factors(sqnorm, (int)B, C, clip, stream) != hipSuccess) return DP_ERR_HIP;
+    if (clip && !clip_done && launch_clip_factors(sqnorm, (int)B, C, clip, stream) != hipSuccess) return DP_ERR_HIP;
     return DP_OK;
 }
 

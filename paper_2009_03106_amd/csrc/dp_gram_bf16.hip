@@ -157,8 +157,8 @@ GramPlan plan_gram_bf16(int T, int d_in, int d_out) {
 }
 
 hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                            bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
-    if (gram_dma_ok(T, d_in, d_out)) return launch_gram_bf16_dma(p, A, G, B, T, d_in, d_out, accumulate, sqnorm, partial, st, f16);
+                            bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16, const ClipOut* co) {
+    if (gram_dma_ok(T, d_in, d_out)) return launch_gram_bf16_dma(p, A, G, B, T, d_in, d_out, accumulate, sqnorm, partial, st, f16, co);
     GramArgs a;
     a.A = A; a.G = G; a.partial = partial;
     a.T = T; a.d_in = d_in; a.d_out = d_out;
@@ -168,7 +168,7 @@ hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t
     else              { if (f16) k_gram_bf16<128, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16<128, false><<<grid, kThreads, 0, st>>>(a); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);
+    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st, co);
 }
 
 }  // namespace dpk

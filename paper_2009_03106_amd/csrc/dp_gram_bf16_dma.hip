@@ -426,10 +426,10 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
 }
 
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt) {
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co) {
     (void)p;
     const GramLayerDesc one{A, G, T, d_in, d_out, nullptr, nullptr};
-    return launch_gram_bf16_dma_layers(&one, 1, B, accumulate, sqnorm, partial, st, fmt);
+    return launch_gram_bf16_dma_layers(&one, 1, B, accumulate, sqnorm, partial, st, fmt, co ? co->C : 0.f, co ? co->clip : nullptr);
 }
 
 }  // namespace dpk

@@ -140,7 +140,7 @@ GramPlan plan_gram_f32(int T) {
 }
 
 hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, int B, int T, int d_in, int d_out,
-                           bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+                           bool accumulate, float* sqnorm, float* partial, hipStream_t st, const ClipOut* co) {
     GramArgsF a;
     a.A = A; a.G = G; a.partial = partial;
     a.T = T; a.d_in = d_in; a.d_out = d_out;
@@ -151,7 +151,7 @@ hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, in
     else                           k_gram_f32<false><<<(unsigned)grid, kThreads, 0, st>>>(a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st);
+    return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st, co);
 }
 
 }  // namespace dpk

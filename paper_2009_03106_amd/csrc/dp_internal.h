@@ -10,13 +10,17 @@ namespace dpk {
 
 // ---- small elementwise / reduction kernels (dp_small_kernels.hip)
 // dt: 0 = float32, 1 = bf16, 2 = fp16 (the values of dp_dtype)
+// Where a norm launcher's last kernel completes the norms of the whole model, it can write the clip factors
+// clip[i] = 1 / max(1, sqrt(s_i) / C) too (co != nullptr), which saves the launch of their own kernel.
+struct ClipOut { float C; float* clip; };
 hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
-                               bool accumulate, float* sqnorm, hipStream_t st);
+                               bool accumulate, float* sqnorm, hipStream_t st, const ClipOut* co = nullptr);
 constexpr int kDenseBatch = 16;        // dense (T = 1) layers per launch of the several-layers call
 struct DenseLayers { int n_layers; const void* A[kDenseBatch]; const void* G[kDenseBatch]; int d_in[kDenseBatch]; int d_out[kDenseBatch]; };
-hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool accumulate, float* sqnorm, hipStream_t st);
+hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool accumulate, float* sqnorm, hipStream_t st,
+                                      const ClipOut* co = nullptr);
 hipError_t launch_finalize_partials(const float* partial, int B, int n_per_example, bool accumulate,
-                                    float* sqnorm, hipStream_t st);
+                                    float* sqnorm, hipStream_t st, const ClipOut* co = nullptr);
 // s_i (+)= sum over the layers l, then over j < n[l], of partial[first[l] + i * n[l] + j], in that order
 constexpr int kGramBatch = 16;         // layers per batched Gram launch
 struct FinalizeLayers { int n_layers; int first[kGramBatch]; int n[kGramBatch]; };
@@ -80,7 +84,7 @@ bool dma_direct_ok(int T, int M, int N);
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
-                                  const ConvGeom* cg, const uint16_t* zero, bool f16);
+                                  const ConvGeom* cg, const uint16_t* zero, bool f16, const ClipOut* co = nullptr);
 // 8-bit inputs (dp_tn_f8_dma.hip); fmt: 2 = A and G e4m3, 3 = A and G e5m2, 4 = A e4m3 and G e5m2
 bool dma8_clipped_ok(int T, int M, int N);
 bool dma8_direct_ok(int T, int M, int N);
@@ -90,15 +94,15 @@ hipError_t launch_clipped_f8_dma(const TnPlan& p, const void* A, const void* G, 
                                  int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
                                  int fmt, const NoiseArgs* noise);
 hipError_t launch_direct_f8_dma(const TnPlan& p, const void* A, const void* G, int B, int T, int M, int N,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt);
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co = nullptr);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
                               const NoiseArgs* noise);
 // partial[B][tiles_m*tiles_n] then finalize into sqnorm
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
-                              bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
+                              bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16, const ClipOut* co = nullptr);
 hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, int B, int T, int M, int N,
-                             bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+                             bool accumulate, float* sqnorm, float* partial, hipStream_t st, const ClipOut* co = nullptr);
 
 // ---- Gram path, 16-bit inputs (dp_gram_bf16.hip, dp_gram_bf16_dma.hip)
 struct GramPlan {
@@ -115,12 +119,12 @@ struct GramLayerDesc { const void* A; const void* G; int T, d_in, d_out; float* 
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
                                        float* partial, hipStream_t st, int fmt, float C = 0.f, float* clip = nullptr);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt);
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co = nullptr);
 // float32 inputs (dp_gram_f32.hip): 64-row tiles
 GramPlan plan_gram_f32(int T);
 hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, int B, int T, int d_in, int d_out,
-                           bool accumulate, float* sqnorm, float* partial, hipStream_t st);
+                           bool accumulate, float* sqnorm, float* partial, hipStream_t st, const ClipOut* co = nullptr);
 hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                            bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16);
+                            bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16, const ClipOut* co = nullptr);
 
 }  // namespace dpk

@@ -11,6 +11,12 @@ namespace dpk {
 // reduction.  Rows whose length is not a multiple of the vector width (or
 // whose start is therefore unaligned) take the scalar loop.
 // ---------------------------------------------------------------------------
+// nu = 1 / max(1, sqrt(s) / C)   (clip function of Section 3.2); the max lets a NaN norm through
+__device__ __forceinline__ float clip_factor_of(float s, float C) {
+    const float m = sqrtf(s) / C;
+    return 1.0f / (!(m <= 1.0f) ? m : 1.0f);
+}
+
 __device__ __forceinline__ float row_sumsq_f32(const float* __restrict__ row, int d, int lane) {
     float acc = 0.f;
     if ((d & 3) == 0) {
@@ -49,7 +55,7 @@ __device__ __forceinline__ float row_sumsq_16(const uint16_t* __restrict__ row, 
 template <int DT>
 __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restrict__ A, const void* __restrict__ G,
                                                            int B, int d_in, int d_out, int accumulate,
-                                                           float* __restrict__ sqnorm) {
+                                                           float* __restrict__ sqnorm, float C, float* __restrict__ clip) {
     const int lane = threadIdx.x & (kWave - 1);
     const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
     if (ex >= B) return;
@@ -63,14 +69,17 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restric
     }
     if (lane == 0) {
         float s = sa * sg;
-        sqnorm[ex] = accumulate ? sqnorm[ex] + s : s;
+        s = accumulate ? sqnorm[ex] + s : s;
+        sqnorm[ex] = s;
+        if (clip) clip[ex] = clip_factor_of(s, C);
     }
 }
 
 // The same for several dense layers at once: s_i (+)= sum over the layers, in the order given, of
 // ||a_l,i||^2 ||g_l,i||^2  (one launch instead of one per layer: these layers are a few microseconds each).
 template <int DT>
-__global__ __launch_bounds__(kThreads) void k_sqnorm_dense_layers(DenseLayers t, int B, int accumulate, float* __restrict__ sqnorm) {
+__global__ __launch_bounds__(kThreads) void k_sqnorm_dense_layers(DenseLayers t, int B, int accumulate, float* __restrict__ sqnorm,
+                                                                  float C, float* __restrict__ clip) {
     const int lane = threadIdx.x & (kWave - 1);
     const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
     if (ex >= B) return;
@@ -87,25 +96,34 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense_layers(DenseLayers t,
         }
         s += sa * sg;
     }
-    if (lane == 0) sqnorm[ex] = accumulate ? sqnorm[ex] + s : s;
+    if (lane == 0) {
+        s = accumulate ? sqnorm[ex] + s : s;
+        sqnorm[ex] = s;
+        if (clip) clip[ex] = clip_factor_of(s, C);
+    }
 }
 
-hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool accumulate, float* sqnorm, hipStream_t st) {
+hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool accumulate, float* sqnorm, hipStream_t st,
+                                      const ClipOut* co) {
     const int per_block = kThreads / kWave;
     dim3 grid((B + per_block - 1) / per_block);
-    if (dt == 2)      k_sqnorm_dense_layers<2><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm);
-    else if (dt == 1) k_sqnorm_dense_layers<1><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm);
-    else              k_sqnorm_dense_layers<0><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm);
+    const float C = co ? co->C : 0.f;
+    float* clip = co ? co->clip : nullptr;
+    if (dt == 2)      k_sqnorm_dense_layers<2><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip);
+    else if (dt == 1) k_sqnorm_dense_layers<1><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip);
+    else              k_sqnorm_dense_layers<0><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip);
     return hipGetLastError();
 }
 
 hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
-                               bool accumulate, float* sqnorm, hipStream_t st) {
+                               bool accumulate, float* sqnorm, hipStream_t st, const ClipOut* co) {
     const int per_block = kThreads / kWave;
     dim3 grid((B + per_block - 1) / per_block);
-    if (dt == 2)      k_sqnorm_dense<2><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
-    else if (dt == 1) k_sqnorm_dense<1><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
-    else              k_sqnorm_dense<0><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm);
+    const float C = co ? co->C : 0.f;
+    float* clip = co ? co->clip : nullptr;
+    if (dt == 2)      k_sqnorm_dense<2><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip);
+    else if (dt == 1) k_sqnorm_dense<1><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip);
+    else              k_sqnorm_dense<0><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip);
     return hipGetLastError();
 }
 
@@ -114,24 +132,21 @@ hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, in
 // the tiled norm kernels.  One thread per example (n is tens at most).
 // ---------------------------------------------------------------------------
 __global__ void k_finalize_partials(const float* __restrict__ partial, int B, int n, int accumulate,
-                                    float* __restrict__ sqnorm) {
+                                    float* __restrict__ sqnorm, float C, float* __restrict__ clip) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B) return;
     const float* p = partial + (size_t)i * n;
     float s = 0.f;
     for (int j = 0; j < n; ++j) s += p[j];
-    sqnorm[i] = accumulate ? sqnorm[i] + s : s;
+    s = accumulate ? sqnorm[i] + s : s;
+    sqnorm[i] = s;
+    if (clip) clip[i] = clip_factor_of(s, C);
 }
 
-hipError_t launch_finalize_partials(const float* partial, int B, int n, bool accumulate, float* sqnorm, hipStream_t st) {
-    k_finalize_partials<<<(B + 63) / 64, 64, 0, st>>>(partial, B, n, accumulate ? 1 : 0, sqnorm);
+hipError_t launch_finalize_partials(const float* partial, int B, int n, bool accumulate, float* sqnorm, hipStream_t st,
+                                    const ClipOut* co) {
+    k_finalize_partials<<<(B + 63) / 64, 64, 0, st>>>(partial, B, n, accumulate ? 1 : 0, sqnorm, co ? co->C : 0.f, co ? co->clip : nullptr);
     return hipGetLastError();
-}
-
-// nu = 1 / max(1, sqrt(s) / C)   (clip function of Section 3.2); the max lets a NaN norm through
-__device__ __forceinline__ float clip_factor_of(float s, float C) {
-    const float m = sqrtf(s) / C;
-    return 1.0f / (!(m <= 1.0f) ? m : 1.0f);
 }
 
 // The same over the item lists of several layers (batched Gram launch), layer after layer.  clip != nullptr: the

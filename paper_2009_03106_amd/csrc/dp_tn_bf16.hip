@@ -717,8 +717,8 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
 }
 
 hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
-                              bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16) {
-    if (p.dma) return launch_direct_bf16_dma(p, A, G, B, T, M, N, accumulate, sqnorm, partial, st, nullptr, nullptr, f16);
+                              bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16, const ClipOut* co) {
+    if (p.dma) return launch_direct_bf16_dma(p, A, G, B, T, M, N, accumulate, sqnorm, partial, st, nullptr, nullptr, f16, co);
     const int tiles = p.tiles_m * p.tiles_n;
     if (p.segmented) {
         // one launch covers at most 2^20 examples so that the workgroup count stays far below 2^31
@@ -735,7 +735,7 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
-        return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
+        return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
     }
     TnArgs a;
     a.A = A; a.G = G; a.clip = nullptr;
@@ -755,7 +755,7 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
+    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
 }
 
 }  // namespace dpk

@@ -562,7 +562,7 @@ TnPlan plan_direct_bf16_dma(int B, int T, int M, int N) {
 
 hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int M, int N,
                                   bool accumulate, float* sqnorm, float* partial, hipStream_t st,
-                                  const ConvGeom* cg, const uint16_t* zero, bool f16) {
+                                  const ConvGeom* cg, const uint16_t* zero, bool f16, const ClipOut* co) {
     int am = cg ? 1 : 0;
     if (!cg && p.zero_head) {
         const hipError_t ez = launch_fill_zero(partial, kZeroHeadFloats, st);
@@ -586,7 +586,7 @@ hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint
     a.per_xcd = ceil_div(total, 8);
     const hipError_t e = launch_any<1>(geo_of_plan(p), a, am, f16, st);
     if (e != hipSuccess) return e;
-    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
+    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
 }
 
 }  // namespace dpk

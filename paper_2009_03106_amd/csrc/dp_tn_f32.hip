@@ -326,7 +326,7 @@ hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, c
 }
 
 hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, int B, int T, int M, int N,
-                             bool accumulate, float* sqnorm, float* partial, hipStream_t st) {
+                             bool accumulate, float* sqnorm, float* partial, hipStream_t st, const ClipOut* co) {
     TnArgsF a;
     a.clip = nullptr;
     a.K = B * T; a.T = T; a.M = M; a.N = N;
@@ -343,7 +343,7 @@ hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, in
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
+    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
 }
 
 }  // namespace dpk

@@ -463,7 +463,7 @@ TnPlan plan_direct_f8_dma(int B, int T, int M, int N) {
 }
 
 hipError_t launch_direct_f8_dma(const TnPlan& p, const void* A, const void* G, int B, int T, int M, int N,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt) {
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co) {
     Dma8Args a;
     a.zero = nullptr;
     if (p.zero_head) {
@@ -485,7 +485,7 @@ hipError_t launch_direct_f8_dma(const TnPlan& p, const void* A, const void* G, i
     a.per_xcd = ceil_div8(total, 8);
     const hipError_t e = launch_any8<1>(p.big, a, p.zero_head, fmt, st);
     if (e != hipSuccess) return e;
-    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st);
+    return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
 }
 
 }  // namespace dpk
