@@ -228,6 +228,44 @@ def test_layers_call_mixed_kinds(dp, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("kinds", ["dense", "dense16", "single", "dense+single", "gram", "single+gram", "bias_last", "empty"])
+def test_layers_call_clip_factors_whatever_kernel_writes_them(dp, dtype, kinds):
+    """dp_layers_sqnorm_clip lets the kernel that completes the norms write the clip factors: the last launch of dense
+    layers, the last layer that runs on its own, the last shared Gram launch, or a clip kernel after a bias pass or
+    when nothing ran.  In every case: bit for bit dp_clip_factors of the norms the same call returns, and both
+    against the oracle; with accumulate on top of an earlier value too."""
+    B = 6
+    shapes = {"dense": [(1, 40, 24), (1, 24, 10)], "dense16": [(1, 8 + i, 5 + i) for i in range(16)],
+              "single": [(48, 72, 40), (64, 256, 256)], "dense+single": [(1, 40, 24), (70, 136, 72), (1, 24, 10)],
+              "gram": [(200, 128, 192), (300, 256, 64)], "single+gram": [(48, 72, 40), (200, 128, 192), (1, 16, 16)],
+              "bias_last": [(1, 40, 24), (64, 72, 40)], "empty": [(0, 8, 8)]}[kinds]
+    layers = [wl.random_layer(900 + i, B, T, di, do, dtype, g_row_scale=np.exp(np.linspace(-1.5, 1.5, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    rows = [torch.empty((B, do), device="cuda") for _, _, do in shapes] if kinds == "bias_last" else None
+    descs = dp.layer_descs(dev, bias_rows=rows)
+    s_ref = sum((orc.layer_sqnorm(A, G) for (A, G), sh in zip(layers, shapes) if sh[0] > 0), np.zeros(B))
+    if rows is not None:
+        s_ref = s_ref + sum(orc.bias_sqnorm(G) for _, G in layers)
+    C = float(np.sqrt(np.median(s_ref))) if kinds != "empty" else 1.0
+    c = torch.full((B,), -1.0, device="cuda")
+    s = dp.layers_sqnorm(dev, descs=descs, C=C, clip=c)
+    if kinds != "empty":
+        assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype]
+        assert (c == 1.0).any() and (c < 1.0).any()
+    else:
+        assert torch.all(s == 0) and torch.all(c == 1.0)
+    np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s, C).cpu().numpy())
+    np.testing.assert_array_equal(s.cpu().numpy(), dp.layers_sqnorm(dev, descs=descs).cpu().numpy())
+    assert rel_err(c.cpu().numpy(), orc.clip_factors(np.maximum(s_ref, 1e-300), C)) <= SQ_TOL[dtype]
+    s2 = torch.full((B,), 0.5, device="cuda")
+    c2 = torch.full((B,), -1.0, device="cuda")
+    dp.layers_sqnorm(dev, s2, descs=descs, C=C, clip=c2, accumulate=True)
+    np.testing.assert_array_equal(c2.cpu().numpy(), dp.clip_factors(s2, C).cpu().numpy())
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_layers_call_dense_layers(dp, dtype):
     """Dense layers share a launch: the MLP configuration's three layers, and 19 layers (two launches)."""
     w, layers = wl.generate("mlp", dtype=dtype)
