@@ -14,6 +14,7 @@ from __future__ import annotations
 import argparse
 import dataclasses
 import json
+import math
 import os
 import sys
 import time
@@ -383,6 +384,25 @@ def main():
                                      "sqnorm_tflops": wk16["norm_flops"] / (ph16[0] * 1e-3) / 1e12,
                                      "clipped_grad_tflops": wk16["gemm_flops"] / (ph16[2] * 1e-3) / 1e12}
         del p16, l16
+        # per-layer clipping (threshold C / sqrt(m) per layer): every layer names its own norm and clip arrays in the
+        # same two calls; the Gram launch stays shared
+        wp, lp = wl.generate("transformer")
+        pp = Pipeline(wp, lp, torch, dp, "auto")
+        m = len(pp.dev)
+        sq_l = [torch.zeros(pp.B, dtype=torch.float32, device="cuda") for _ in range(m)]
+        cl_l = [torch.zeros(pp.B, dtype=torch.float32, device="cuda") for _ in range(m)]
+        Cl = wp.C / math.sqrt(m)
+        pp.descs = dp.layer_descs(pp.dev, groups=[(sq_l[l], cl_l[l], Cl) for l in range(m)])
+        order = sorted(range(m), key=lambda li: pp.dev[li][0].shape[2] + pp.dev[li][1].shape[2])
+        sizes = [spec.d_in * spec.d_out for spec in wp.layers]
+        starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+        pp.descs_cg = dp.layer_descs(pp.dev_cg, [pp.grads[li] for li in order], [starts[li] for li in order],
+                                     groups=[(sq_l[li], cl_l[li], Cl) for li in order])
+        msp, php = time_steps(pp, torch, 20, 3)
+        others["transformer_per_layer_clipping"] = {"examples_per_s": pp.B / (msp * 1e-3), "ms_per_step": msp,
+                                                    "sqnorm_ms": php[0], "clipped_grad_ms": php[2],
+                                                    "threshold_per_layer": Cl}
+        del pp, lp, sq_l, cl_l
         # ... and with 8-bit inputs, activations e4m3 and backpropagated gradients e5m2: the 64-deep 8-bit matrix
         # instruction, twice the rate for half the bytes
         w8, l8 = wl.generate("transformer", dtype="f8")

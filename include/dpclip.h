@@ -144,6 +144,16 @@ typedef struct {
     float* bias_rows;           /* NULL, or device float32[B, d_out]: dp_layers_sqnorm(_clip) also writes the layer's
                                    per-example bias gradients sum_t G_i[t, :] there and adds their squared norms (what
                                    dp_bias_sqnorm does), for layers that have a bias */
+    /* Per-layer and grouped clipping (a threshold per layer, e.g. c / sqrt(m) for m layers, or per group of layers;
+     * Section 2).  A layer that names an array of its own is added to that array instead of the call's sqnorm:
+     * layers naming the same array form a group.  All NULL / 0: the layer belongs to the call's own array. */
+    float* sqnorm;              /* NULL, or device float32[B]: dp_layers_sqnorm(_clip) adds this layer's squared norm
+                                   (bias share included) here; `accumulate` applies to these arrays too */
+    float* clip;                /* NULL, or device float32[B].  dp_layers_sqnorm_clip (with `sqnorm` set): receives
+                                   min(1, clip_C / sqrt(.)) of the finished array; every layer of a group names the same
+                                   clip and clip_C.  dp_layers_clipped_grad(_noise): the clip factors for this layer,
+                                   in place of the call's */
+    float clip_C;               /* threshold of this layer's group; > 0 when clip is set */
 } dp_layer_desc;
 
 dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
@@ -158,7 +168,10 @@ size_t dp_layers_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, 
  * the line defining nu_i), for the case that the layers given are the whole
  * model: the launch that completes the norms writes the clip factors too where it
  * can, else a clip-factor launch follows; the values are the same either way.
- * clip == NULL: exactly dp_layers_sqnorm.  C must be > 0 when clip is given. */
+ * clip == NULL: exactly dp_layers_sqnorm.  C must be > 0 when clip is given.
+ * Layers that name arrays of their own (dp_layer_desc.sqnorm / clip / clip_C) are
+ * added to those instead, group by group, in the same launches; sqnorm and clip
+ * of the call may then be NULL if no layer is left for them. */
 dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
                                 dp_dtype dtype, dp_path path, int accumulate,
                                 float* sqnorm, float C, float* clip,

@@ -1,8 +1,9 @@
 // C-ABI entry points declared in include/dpclip.h: argument checks, path
-// choice, workspace carving and kernel launches.  No allocation, no
+// choice, workspace carving and kernel launches.  No device allocation, no
 // synchronisation, no host reads of device memory.
 #include "../../include/dpclip.h"
 #include "dp_internal.h"
+#include <vector>
 
 using namespace dpk;
 
@@ -520,6 +521,10 @@ dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
     return DP_OK;
 }
 
+dp_status layers_sqnorm_grouped(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path,
+                                int accumulate, float* sqnorm, float C, float* clip, void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
 // scratch: the layers that run one by one reuse one region, and so do the batched launches
 size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path) {
     size_t single = 0, batch = 0, batch_max = 0;
@@ -564,6 +569,9 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
     if (st != DP_OK) return st;
     if (clip && !(C > 0.0f)) return DP_ERR_INVALID_ARG;
     if (B == 0) return DP_OK;
+    for (int64_t l = 0; l < n_layers; ++l)
+        if (layers[l].sqnorm)
+            return layers_sqnorm_grouped(layers, n_layers, B, dtype, path, accumulate, sqnorm, C, clip, workspace, workspace_bytes, hip_stream);
     if (!sqnorm) return DP_ERR_INVALID_ARG;
     const size_t need = layers_ws_bytes(layers, n_layers, B, dtype, path);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;
@@ -670,6 +678,121 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
     return DP_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// dp_layers_sqnorm_clip when layers name output arrays of their own (per-layer or grouped clipping, Section 2: a
+// threshold per layer or per group of layers).  A group is an output array: the layers' `sqnorm` pointers, and the
+// call's own array for the layers that name none.  Every group's norms are complete when its last layer (and bias
+// pass) has been added; the kernel that adds it writes the group's clip factors where it can, else a clip-factor
+// launch follows.  The shared Gram launches take layers of all groups together.
+dp_status layers_sqnorm_grouped(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path,
+                                int accumulate, float* sqnorm, float C, float* clip, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+    struct Group { float* out; float C; float* clip; bool holds; int64_t ops; };
+    std::vector<Group> groups;
+    std::vector<int> group_of((size_t)n_layers, -1);
+    auto bias_pass = [&](const dp_layer_desc& y) {     // the layer's bias rows need a pass of their own
+        return y.bias_rows && y.d_out != 0 &&
+               !(!is8(dtype) && y.T > 1 && y.d_in > 0 && gram_batchable(y.T, y.d_in, y.d_out, dtype, path));
+    };
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        Group g{y.sqnorm ? y.sqnorm : sqnorm, y.sqnorm ? y.clip_C : C, y.sqnorm ? y.clip : clip, accumulate != 0, 0};
+        if (!g.out) return DP_ERR_INVALID_ARG;                         // no array of its own and none given to the call
+        if (g.clip && !(g.C > 0.0f)) return DP_ERR_INVALID_ARG;
+        int gi = -1;
+        for (size_t k = 0; k < groups.size(); ++k)
+            if (groups[k].out == g.out) { gi = (int)k; break; }
+        if (gi < 0) { gi = (int)groups.size(); groups.push_back(g); }
+        else if (groups[gi].clip != g.clip || (g.clip && groups[gi].C != g.C)) return DP_ERR_INVALID_ARG;   // one threshold per array
+        group_of[l] = gi;
+        const bool empty = y.T == 0 || y.d_in == 0 || y.d_out == 0;
+        groups[gi].ops += (empty ? 0 : 1) + (bias_pass(y) ? 1 : 0);
+    }
+    const size_t need = layers_ws_bytes(layers, n_layers, B, dtype, path);
+    if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    // groups without any work: zero (unless accumulating) and, from that, their clip factors
+    for (Group& g : groups) {
+        if (g.ops > 0) continue;
+        if (!g.holds && launch_fill_zero(g.out, B, stream) != hipSuccess) return DP_ERR_HIP;
+        if (g.clip && launch_clip_factors(g.out, (int)B, g.C, g.clip, stream) != hipSuccess) return DP_ERR_HIP;
+    }
+    // dense layers and the layers outside the shared launches, one by one in the order given
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
+        Group& g = groups[group_of[l]];
+        const ClipOut co{g.C, g.clip};
+        const dp_status s1 = layer_sqnorm_clip(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, g.holds ? 1 : 0, g.out, workspace,
+                                               workspace_bytes, hip_stream, (g.clip && g.ops == 1) ? &co : nullptr);
+        if (s1 != DP_OK) return s1;
+        g.holds = true; --g.ops;
+    }
+    // bias terms that need their own pass over G
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (!bias_pass(y)) continue;
+        Group& g = groups[group_of[l]];
+        const dp_status s1 = dp_bias_sqnorm(y.G, B, y.T, y.d_out, dtype, g.holds ? 1 : 0, g.out, y.bias_rows, hip_stream);
+        if (s1 != DP_OK) return s1;
+        g.holds = true; --g.ops;
+        if (g.ops == 0 && g.clip && launch_clip_factors(g.out, (int)B, g.C, g.clip, stream) != hipSuccess) return DP_ERR_HIP;
+    }
+    // the shared Gram launches, up to kGramBatch layers each, heaviest first inside a launch
+    GramLayerDesc batch[kGramBatch];
+    int batch_group[kGramBatch];
+    int nb = 0;
+    auto flush = [&]() -> hipError_t {
+        if (nb == 0) return hipSuccess;
+        for (int i = 1; i < nb; ++i) {                                          // stable insertion sort, descending work
+            const GramLayerDesc v = batch[i];
+            const int gv = batch_group[i];
+            const int64_t wv = (int64_t)(v.d_in + v.d_out);
+            int j = i;
+            while (j > 0 && (int64_t)(batch[j - 1].d_in + batch[j - 1].d_out) < wv) { batch[j] = batch[j - 1]; batch_group[j] = batch_group[j - 1]; --j; }
+            batch[j] = v; batch_group[j] = gv;
+        }
+        float* ws = static_cast<float*>(workspace);
+        size_t used = 0;
+        for (int i = 0; i < nb; ++i) used += (size_t)B * plan_gram_bf16(batch[i].T, batch[i].d_in, batch[i].d_out).npairs;
+        for (int i = 0; i < nb; ++i) {
+            if (batch[i].bias_rows) {
+                batch[i].upart = ws + used;
+                used += (size_t)B * plan_gram_bf16(batch[i].T, batch[i].d_in, batch[i].d_out).nt * (size_t)batch[i].d_out;
+            }
+            int64_t here = 0;                                                   // this group's layers in this launch
+            for (int j = 0; j < nb; ++j) here += batch_group[j] == batch_group[i] ? 1 : 0;
+            const Group& g = groups[batch_group[i]];
+            batch[i].out = g.out; batch[i].out_acc = g.holds; batch[i].out_C = g.C;
+            batch[i].out_clip = (g.ops == here) ? g.clip : nullptr;              // the group is complete after this launch
+        }
+        const hipError_t e = launch_gram_bf16_dma_layers(batch, nb, (int)B, false, nullptr, ws, stream, fmt_of(dtype), 0.f, nullptr);
+        for (int i = 0; i < nb; ++i) { groups[batch_group[i]].holds = true; --groups[batch_group[i]].ops; }
+        nb = 0;
+        return e;
+    };
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (!gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
+        if (nb == kGramBatch && flush() != hipSuccess) return DP_ERR_HIP;
+        batch_group[nb] = group_of[l];
+        batch[nb++] = GramLayerDesc{y.A, y.G, (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, is8(dtype) ? nullptr : y.bias_rows};
+    }
+    if (flush() != hipSuccess) return DP_ERR_HIP;
+    return DP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype) {
     if (check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, false, DP_OP_CLIPPED_GRAD) != DP_OK) return 0;
     size_t need = 0;
@@ -700,11 +823,12 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
         const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
         if (n > need) need = n;
     }
-    if (B > 0 && n_layers > 0 && !clip) return DP_ERR_INVALID_ARG;
+    for (int64_t l = 0; l < n_layers; ++l)
+        if (B > 0 && !clip && !layers[l].clip) return DP_ERR_INVALID_ARG;          // neither the layer's own factors nor the call's
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
-        const dp_status s1 = clipped_grad_noise(y.A, y.G, clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
+        const dp_status s1 = clipped_grad_noise(y.A, y.G, y.clip ? y.clip : clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
                                                 workspace_bytes, hip_stream, stddev, seed, y.noise_offset);
         if (s1 != DP_OK) return s1;
     }

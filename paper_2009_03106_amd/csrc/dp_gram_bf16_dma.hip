@@ -414,6 +414,39 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
     else               k_gram_bf16_dma<4, false><<<grid, kThreads, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (layers[0].out) {
+        // an output array per layer (groups share one): the bias folds first, then the layers' sums, each adding to
+        // its array if the array holds a value by then; a group's clip factors go with its last layer
+        int canon[kGramBatch];
+        bool holds[kGramBatch];
+        for (int l = 0; l < n_layers; ++l) {
+            if (!layers[l].out) return hipErrorInvalidValue;
+            canon[l] = l;
+            for (int j = 0; j < l; ++j)
+                if (layers[j].out == layers[l].out) { canon[l] = canon[j]; break; }
+            holds[l] = layers[l].out_acc;
+        }
+        for (int l = 0; l < n_layers; ++l) {
+            if (!layers[l].upart) continue;
+            e = launch_bias_fold(layers[l].upart, B, a.layer[l].nt, layers[l].d_out, holds[canon[l]], layers[l].bias_rows, layers[l].out, st);
+            if (e != hipSuccess) return e;
+            holds[canon[l]] = true;
+        }
+        FinalizeEach fe;
+        fe.n_layers = n_layers;
+        for (int l = 0; l < kGramBatch; ++l) { fe.first[l] = 0; fe.n[l] = 0; fe.acc[l] = 0; fe.C[l] = 0.f; fe.out[l] = nullptr; fe.clip[l] = nullptr; }
+        for (int l = 0; l < n_layers; ++l) {
+            fe.first[l] = fin.first[l]; fe.n[l] = fin.n[l];
+            fe.out[l] = layers[l].out;
+            fe.acc[l] = holds[canon[l]] ? 1 : 0;
+            holds[canon[l]] = true;
+            bool last = true;
+            for (int j = l + 1; j < n_layers; ++j) last = last && layers[j].out != layers[l].out;
+            fe.C[l] = layers[l].out_C;
+            fe.clip[l] = last ? layers[l].out_clip : nullptr;
+        }
+        return launch_finalize_each(partial, fe, B, st);
+    }
     // bias rows and their share of the norms first, so that the finalize kernel below (which may write the clip
     // factors) sees complete sums
     for (int l = 0; l < n_layers; ++l) {

@@ -27,6 +27,12 @@ struct FinalizeLayers { int n_layers; int first[kGramBatch]; int n[kGramBatch]; 
 // clip != nullptr: also clip[i] = 1 / max(1, sqrt(s_i) / C) of the finished sums
 hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f, int B, bool accumulate, float* sqnorm, hipStream_t st,
                                   float C, float* clip);
+// The same with an output array of its own per layer (per-layer or grouped norms; layers of one group name the same
+// array and are added in the order given):  out[l][i] = (acc[l] ? out[l][i] : 0) + sum_j partial[first[l] + i n[l] + j],
+// then clip[l][i] = 1 / max(1, sqrt(out[l][i]) / C[l]) where clip[l] != nullptr.
+struct FinalizeEach { int n_layers; int first[kGramBatch]; int n[kGramBatch]; int acc[kGramBatch]; float C[kGramBatch];
+                      float* out[kGramBatch]; float* clip[kGramBatch]; };
+hipError_t launch_finalize_each(const float* partial, const FinalizeEach& f, int B, hipStream_t st);
 hipError_t launch_clip_factors(const float* sqnorm, int B, float C, float* clip, hipStream_t st);
 // distance in floats between consecutive split-K slices of an n-element output
 inline int64_t splitk_slice_elems(int64_t n) { return (n + 3) & ~(int64_t)3; }
@@ -115,7 +121,11 @@ GramPlan plan_gram_bf16(int T, int d_in, int d_out);
 bool gram_dma_ok(int T, int d_in, int d_out, int fmt = 0);
 // upart: nullptr, or [B][ceil(T / 128)][d_out] floats that receive the column sums of G over each 128-row tile
 // bias_rows: nullptr, or float32[B, d_out] that receives sum_t G_i[t, :] (then upart is its scratch and ||bias_rows_i||^2 joins the norm)
-struct GramLayerDesc { const void* A; const void* G; int T, d_in, d_out; float* upart; float* bias_rows; };
+// out: nullptr, or this layer's own output array (then every layer of the launch has one): out_acc = whether the array
+// already holds a value to add to (the same for all layers naming the array), out_clip / out_C = nullptr, or where the
+// array's clip factors go once the launch's last layer naming it has been added
+struct GramLayerDesc { const void* A; const void* G; int T, d_in, d_out; float* upart; float* bias_rows;
+                       float* out = nullptr; bool out_acc = false; float out_C = 0.f; float* out_clip = nullptr; };
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
                                        float* partial, hipStream_t st, int fmt, float C = 0.f, float* clip = nullptr);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,

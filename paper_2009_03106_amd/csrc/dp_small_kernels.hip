@@ -172,6 +172,27 @@ hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f,
     return hipGetLastError();
 }
 
+// One output array per layer; arrays may repeat (layers of one group), so they are read and written layer after
+// layer by the example's one thread and are not declared restrict.
+__global__ void k_finalize_each(const float* __restrict__ partial, FinalizeEach f, int B) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    for (int l = 0; l < f.n_layers; ++l) {
+        const float* p = partial + (size_t)f.first[l] + (size_t)i * f.n[l];
+        float t = 0.f;
+        for (int j = 0; j < f.n[l]; ++j) t += p[j];
+        float* out = f.out[l];
+        const float s = f.acc[l] ? out[i] + t : t;
+        out[i] = s;
+        if (f.clip[l]) f.clip[l][i] = clip_factor_of(s, f.C[l]);
+    }
+}
+
+hipError_t launch_finalize_each(const float* partial, const FinalizeEach& f, int B, hipStream_t st) {
+    k_finalize_each<<<(B + 63) / 64, 64, 0, st>>>(partial, f, B);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // nu_i = 1 / max(1, sqrt(s_i) / C)   (clip function of Section 3.2)
 // ---------------------------------------------------------------------------

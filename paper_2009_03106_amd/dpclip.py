@@ -33,7 +33,8 @@ class LayerDesc(ctypes.Structure):
     """dp_layer_desc of the header."""
     _fields_ = [("A", ctypes.c_void_p), ("G", ctypes.c_void_p), ("T", ctypes.c_int64), ("d_in", ctypes.c_int64),
                 ("d_out", ctypes.c_int64), ("grad", ctypes.c_void_p), ("noise_offset", ctypes.c_uint64),
-                ("bias_rows", ctypes.c_void_p)]
+                ("bias_rows", ctypes.c_void_p), ("sqnorm", ctypes.c_void_p), ("clip", ctypes.c_void_p),
+                ("clip_C", ctypes.c_float)]
 
 
 class DpclipError(RuntimeError):
@@ -196,12 +197,16 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
     return sqnorm
 
 
-def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None):
+def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=None):
     """(ctypes array of dp_layer_desc, B, dtype code) for a list of (A, G) tensor pairs sharing B and dtype, with
     the float32 [d_in, d_out] output of each layer if grads is given (layers_clipped_grad needs them) and the position of
     each gradient in the noise stream if noise_offsets is given (default: the gradients laid out back to back in the order
     of the list).  bias_rows: one float32 [B, d_out] tensor (or None) per layer: layers_sqnorm then also writes the
     per-example bias gradients there and counts their norms.
+    groups: per-layer or grouped clipping: one (sqnorm, clip, C) triple (or None) per layer, float32 [B] tensors (clip
+    may be None) and the group's threshold; layers that give the same sqnorm tensor form a group, whose norms
+    layers_sqnorm adds up in that tensor (and whose clip factors it writes to clip), and whose clip factors
+    layers_clipped_grad uses for these layers.
     The tensors must stay alive (and contiguous: the pointers are taken here) while the array is used."""
     if len(layers) == 0:
         raise ValueError("no layers")
@@ -230,7 +235,15 @@ def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None):
             if bias_rows[i].dtype != torch.float32 or tuple(bias_rows[i].shape) != (B, d_out):
                 raise ValueError("bias rows must be float32 [B, d_out]")
             bp = _ptr(bias_rows[i])
-        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, running if noise_offsets is None else int(noise_offsets[i]), bp)
+        sp, cp, cC = None, None, 0.0
+        if groups is not None and groups[i] is not None:
+            gs, gc, cC = groups[i]
+            for t in (gs, gc):
+                if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != (B,)):
+                    raise ValueError("group arrays must be float32 [B]")
+            sp, cp = _ptr(gs), _ptr(gc)
+        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, running if noise_offsets is None else int(noise_offsets[i]), bp,
+                           sp, cp, float(cC))
         running += d_in * d_out
     return arr, B0, dt0
 

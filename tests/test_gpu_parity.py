@@ -265,6 +265,103 @@ def test_layers_call_clip_factors_whatever_kernel_writes_them(dp, dtype, kinds):
     assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
 
 
+def test_per_layer_clipping_in_the_layers_calls(dp):
+    """Per-layer clipping (threshold c / sqrt(m) for each of the m layers, Section 2) through the several-layers calls:
+    every layer names its own norm and clip arrays, the Gram launch is still shared, and the clipped sums take each
+    layer's own factors.  Norms are bit for bit those of the per-layer entry point."""
+    w, layers = wl.generate("transformer", B=5, straddle=True)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    m, B = len(dev), 5
+    s_l = [orc.layer_sqnorm(A, G) for A, G in layers]
+    Cl = float(np.sqrt(np.median(np.concatenate(s_l))))
+    sq = [torch.full((B,), 9.0, device="cuda") for _ in range(m)]
+    cl = [torch.full((B,), -1.0, device="cuda") for _ in range(m)]
+    descs = dp.layer_descs(dev, groups=[(sq[l], cl[l], Cl) for l in range(m)])
+    dp.layers_sqnorm(dev, descs=descs)
+    for l, (A, G) in enumerate(dev):
+        assert rel_err(sq[l].cpu().numpy(), s_l[l]) <= SQ_TIGHT["bf16"]
+        np.testing.assert_array_equal(sq[l].cpu().numpy(), dp.layer_sqnorm(A, G).cpu().numpy())
+        np.testing.assert_array_equal(cl[l].cpu().numpy(), dp.clip_factors(sq[l], Cl).cpu().numpy())
+        assert rel_err(cl[l].cpu().numpy(), orc.clip_factors(s_l[l], Cl)) <= SQ_TOL["bf16"]
+    assert any((c == 1.0).any() for c in cl) and any((c < 1.0).any() for c in cl)
+    grads = [torch.empty((A.shape[-1], G.shape[-1]), device="cuda") for A, G in dev]
+    descs_g = dp.layer_descs(dev, grads, groups=[(sq[l], cl[l], Cl) for l in range(m)])
+    dp.layers_clipped_grad(dev, None, descs=descs_g)
+    for l, ((A, G), g) in enumerate(zip(layers, grads)):
+        assert fro_err(g.cpu().numpy(), orc.clipped_grad(A, G, orc.clip_factors(s_l[l], Cl))) <= FRO_TOL["bf16"]
+        np.testing.assert_array_equal(g.cpu().numpy(), dp.clipped_grad(dev[l][0], dev[l][1], cl[l]).cpu().numpy())
+    # every per-layer clipped gradient has norm <= C / sqrt(m) * sqrt(m) = C overall: sum over layers of (nu_l ||g_l||)^2 <= m Cl^2
+    tot = sum((cl[l].cpu().numpy().astype(np.float64) ** 2) * s_l[l] for l in range(m))
+    assert np.all(tot <= m * Cl * Cl * (1 + 1e-3))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_grouped_clipping_mixed_kinds(dp, dtype, accumulate):
+    """Groups of layers with a threshold each (Section 2: a different amount of clipping for each group): dense, direct,
+    shared-Gram and empty layers, with and without bias rows, spread over four groups, one of them the call's own
+    array.  Against the oracle's sums over each group's layers."""
+    B = 6
+    shapes = [(1, 40, 24), (200, 128, 192), (48, 72, 40), (300, 256, 64), (1, 24, 10), (0, 8, 8), (200, 192, 128)]
+    group = [0, 0, 1, 1, 2, 3, 1]
+    with_bias = [False, True, True, True, False, False, False]
+    layers = [wl.random_layer(950 + i, B, T, di, do, dtype, g_row_scale=np.exp(np.linspace(-1.5, 1.5, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    ref = [np.zeros(B) for _ in range(4)]
+    for (A, G), sh, g, wb in zip(layers, shapes, group, with_bias):
+        if sh[0] > 0:
+            ref[g] = ref[g] + orc.layer_sqnorm(A, G)
+        if wb:
+            ref[g] = ref[g] + orc.bias_sqnorm(G)
+    Cg = [float(np.sqrt(np.median(r))) if r.any() else 1.0 for r in ref]
+    base = 0.5 if accumulate else 0.0
+    sq = [torch.full((B,), base if accumulate else 7.0, device="cuda") for _ in range(4)]
+    cl = [torch.full((B,), -1.0, device="cuda") for _ in range(4)]
+    rows = [torch.empty((B, do), device="cuda") if wb else None for (_, _, do), wb in zip(shapes, with_bias)]
+    # group 0 is the call's own array; the others are named by their layers
+    groups = [None if g == 0 else (sq[g], cl[g], Cg[g]) for g in group]
+    descs = dp.layer_descs(dev, bias_rows=rows, groups=groups)
+    dp.layers_sqnorm(dev, sq[0], descs=descs, C=Cg[0], clip=cl[0], accumulate=accumulate)
+    for g in range(4):
+        got = sq[g].cpu().numpy()
+        if ref[g].any() or accumulate:
+            assert rel_err(got, ref[g] + base) <= SQ_TIGHT[dtype], (g, rel_err(got, ref[g] + base))
+        else:
+            assert np.all(got == 0)
+        np.testing.assert_array_equal(cl[g].cpu().numpy(), dp.clip_factors(sq[g], Cg[g]).cpu().numpy())
+    for (A, G), u, wb in zip(layers, rows, with_bias):
+        if wb:
+            assert np.max(np.abs(u.cpu().numpy() - orc.bias_rows(G))) <= 1e-5 * np.max(np.sum(np.abs(orc.widen(G)), axis=1))
+    # clipped sums with each group's factors
+    grads = [torch.empty((di, do), device="cuda") for _, di, do in shapes]
+    descs_g = dp.layer_descs(dev, grads, groups=groups)
+    dp.layers_clipped_grad(dev, cl[0], descs=descs_g)
+    for (A, G), sh, g, gr in zip(layers, shapes, group, grads):
+        want = orc.clipped_grad(A, G, cl[g].cpu().numpy().astype(np.float64)) if sh[0] > 0 else np.zeros((sh[1], sh[2]))
+        assert fro_err(gr.cpu().numpy(), want) <= FRO_TOL[dtype] or (sh[0] == 0 and np.all(gr.cpu().numpy() == 0))
+
+
+def test_grouped_clipping_argument_errors(dp):
+    B = 3
+    layers = [wl.random_layer(990 + i, B, 64, 72, 40, "bf16") for i in range(2)]
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    own, c1, c2 = (torch.full((B,), 5.0, device="cuda") for _ in range(3))
+    lib = dp.load_library()
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    # two layers name one array with different thresholds
+    arr, Bn, dt = dp.layer_descs(dev, groups=[(own, c1, 1.0), (own, c1, 2.0)])
+    assert lib.dp_layers_sqnorm_clip(arr, 2, Bn, dt, 0, 0, None, 0.0, None, ws.data_ptr(), ws.numel(), None) == dp.DP_ERR_INVALID_ARG
+    # a layer without an array of its own and no array given to the call
+    arr, Bn, dt = dp.layer_descs(dev, groups=[(own, c1, 1.0), None])
+    assert lib.dp_layers_sqnorm_clip(arr, 2, Bn, dt, 0, 0, None, 0.0, None, ws.data_ptr(), ws.numel(), None) == dp.DP_ERR_INVALID_ARG
+    # clip factors wanted, threshold missing
+    arr, Bn, dt = dp.layer_descs(dev, groups=[(own, c1, 0.0), (own, c1, 0.0)])
+    assert lib.dp_layers_sqnorm_clip(arr, 2, Bn, dt, 0, 0, None, 0.0, None, ws.data_ptr(), ws.numel(), None) == dp.DP_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.all(own == 5.0) and torch.all(c1 == 5.0)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_layers_call_dense_layers(dp, dtype):
     """Dense layers share a launch: the MLP configuration's three layers, and 19 layers (two launches)."""
