@@ -154,6 +154,10 @@ typedef struct {
                                    clip and clip_C.  dp_layers_clipped_grad(_noise): the clip factors for this layer,
                                    in place of the call's */
     float clip_C;               /* threshold of this layer's group; > 0 when clip is set */
+    float* grad_b;              /* NULL, or device float32[d_out]: dp_layers_clipped_grad(_noise) also writes the clipped
+                                   sum of the layer's bias gradients, sum_i clip[i] bias_rows[i, :] (what
+                                   dp_clipped_bias_grad does; bias_rows as dp_layers_sqnorm left them) */
+    uint64_t bias_noise_offset; /* position of grad_b[0] in the noise stream: dp_layers_clipped_grad_noise only */
 } dp_layer_desc;
 
 dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B,

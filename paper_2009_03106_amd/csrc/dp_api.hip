@@ -820,6 +820,10 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
         const dp_layer_desc& y = layers[l];
         if (y.d_in > 0 && y.d_out > 0 && (!y.grad || !aligned16(y.grad))) return DP_ERR_INVALID_ARG;
         if (stddev > 0.0f && y.noise_offset > ~uint64_t(0) - (uint64_t)(y.d_in * y.d_out)) return DP_ERR_INVALID_ARG;   // offset + n must not wrap
+        if (y.grad_b && y.d_out > 0) {
+            if (B > 0 && !y.bias_rows) return DP_ERR_INVALID_ARG;                  // the rows that dp_layers_sqnorm left
+            if (stddev > 0.0f && y.bias_noise_offset > ~uint64_t(0) - (uint64_t)y.d_out) return DP_ERR_INVALID_ARG;
+        }
         const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
         if (n > need) need = n;
     }
@@ -831,6 +835,15 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
         const dp_status s1 = clipped_grad_noise(y.A, y.G, y.clip ? y.clip : clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
                                                 workspace_bytes, hip_stream, stddev, seed, y.noise_offset);
         if (s1 != DP_OK) return s1;
+        if (y.grad_b && y.d_out > 0) {
+            // the layer's bias: sum_i nu_i bias_rows[i, :], with its own stretch of the noise stream
+            hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+            hipError_t e = hipSuccess;
+            if (B == 0) { if (!accumulate) e = launch_fill_zero(y.grad_b, y.d_out, stream); }
+            else e = launch_clipped_bias(y.bias_rows, y.clip ? y.clip : clip, (int)B, (int)y.d_out, accumulate != 0, y.grad_b, stream);
+            if (e == hipSuccess && stddev > 0.0f) e = launch_add_noise(y.grad_b, y.d_out, stddev, seed, y.bias_noise_offset, stream);
+            if (e != hipSuccess) return DP_ERR_HIP;
+        }
     }
     return DP_OK;
 }

@@ -34,7 +34,7 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [("A", ctypes.c_void_p), ("G", ctypes.c_void_p), ("T", ctypes.c_int64), ("d_in", ctypes.c_int64),
                 ("d_out", ctypes.c_int64), ("grad", ctypes.c_void_p), ("noise_offset", ctypes.c_uint64),
                 ("bias_rows", ctypes.c_void_p), ("sqnorm", ctypes.c_void_p), ("clip", ctypes.c_void_p),
-                ("clip_C", ctypes.c_float)]
+                ("clip_C", ctypes.c_float), ("grad_b", ctypes.c_void_p), ("bias_noise_offset", ctypes.c_uint64)]
 
 
 class DpclipError(RuntimeError):
@@ -197,7 +197,7 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
     return sqnorm
 
 
-def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=None):
+def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=None, grad_bs=None, bias_noise_offsets=None):
     """(ctypes array of dp_layer_desc, B, dtype code) for a list of (A, G) tensor pairs sharing B and dtype, with
     the float32 [d_in, d_out] output of each layer if grads is given (layers_clipped_grad needs them) and the position of
     each gradient in the noise stream if noise_offsets is given (default: the gradients laid out back to back in the order
@@ -207,6 +207,8 @@ def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=N
     may be None) and the group's threshold; layers that give the same sqnorm tensor form a group, whose norms
     layers_sqnorm adds up in that tensor (and whose clip factors it writes to clip), and whose clip factors
     layers_clipped_grad uses for these layers.
+    grad_bs: one float32 [d_out] tensor (or None) per layer: layers_clipped_grad then also writes the clipped sum of the
+    layer's bias rows there (bias_noise_offsets: their positions in the noise stream, default 0).
     The tensors must stay alive (and contiguous: the pointers are taken here) while the array is used."""
     if len(layers) == 0:
         raise ValueError("no layers")
@@ -242,8 +244,13 @@ def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=N
                 if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != (B,)):
                     raise ValueError("group arrays must be float32 [B]")
             sp, cp = _ptr(gs), _ptr(gc)
+        gbp = None
+        if grad_bs is not None and grad_bs[i] is not None:
+            if grad_bs[i].dtype != torch.float32 or tuple(grad_bs[i].shape) != (d_out,):
+                raise ValueError("bias gradients must be float32 [d_out]")
+            gbp = _ptr(grad_bs[i])
         arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, running if noise_offsets is None else int(noise_offsets[i]), bp,
-                           sp, cp, float(cC))
+                           sp, cp, float(cC), gbp, 0 if bias_noise_offsets is None else int(bias_noise_offsets[i]))
         running += d_in * d_out
     return arr, B0, dt0
 

@@ -295,6 +295,56 @@ def test_per_layer_clipping_in_the_layers_calls(dp):
     assert np.all(tot <= m * Cl * Cl * (1 + 1e-3))
 
 
+@pytest.mark.parametrize("name,B", [("transformer", 5), ("mlp", None), ("rnn", None)])
+def test_layers_calls_with_weights_and_biases(dp, name, B):
+    """A whole step for layers with biases in the two several-layers calls: norms over weights and biases, clip
+    factors, clipped sums of the weight gradients and of the bias gradients, noise over the flat parameter gradient
+    (each layer's weights followed by its bias)."""
+    w, layers = wl.generate(name, B=B, straddle=True)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    Bn = dev[0][0].shape[0]
+    s_ref = orc.total_sqnorm(layers) + sum(orc.bias_sqnorm(G) for _, G in layers)
+    c_ref = orc.clip_factors(s_ref, w.C)
+    rows = [torch.empty((Bn, G.shape[-1]), device="cuda") for _, G in dev]
+    c = torch.empty(Bn, device="cuda")
+    s = dp.layers_sqnorm(dev, descs=dp.layer_descs(dev, bias_rows=rows), C=w.C, clip=c)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[w.dtype]
+    assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL[w.dtype]
+    sizes = [A.shape[-1] * G.shape[-1] + G.shape[-1] for A, G in dev]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.full((sum(sizes),), 3.0, device="cuda")
+    grads, gbs, offs_b = [], [], []
+    for i, (A, G) in enumerate(dev):
+        nw = A.shape[-1] * G.shape[-1]
+        grads.append(flat[starts[i]:starts[i] + nw].view(A.shape[-1], G.shape[-1]))
+        gbs.append(flat[starts[i] + nw:starts[i + 1]])
+        offs_b.append(starts[i] + nw)
+    descs = dp.layer_descs(dev, grads, starts[:-1], bias_rows=rows, grad_bs=gbs, bias_noise_offsets=offs_b)
+    dp.layers_clipped_grad(dev, c, descs=descs, noise_std=0.5, seed=77)
+    # the same from the single-purpose calls
+    ref = torch.zeros_like(flat)
+    for i, (A, G) in enumerate(dev):
+        nw = A.shape[-1] * G.shape[-1]
+        dp.clipped_grad(A, G, c, ref[starts[i]:starts[i] + nw].view(A.shape[-1], G.shape[-1]))
+        dp.clipped_bias_grad(rows[i], c, ref[starts[i] + nw:starts[i + 1]])
+    dp.add_noise(ref, 0.5, 77, 0)
+    assert torch.equal(flat, ref)
+    # ... and against the oracle, noise included
+    cn = c.cpu().numpy().astype(np.float64)
+    want = np.concatenate([np.concatenate([orc.clipped_grad(A, G, cn).ravel(), orc.clipped_bias_grad(G, cn)]) for A, G in layers])
+    want = orc.add_noise(want, 0.5, 77, 0)
+    got = flat.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - want)) <= 1e-4 * (1 + np.max(np.abs(want)))
+    # a bias gradient asked for without the rows is refused before anything is written
+    keep = flat.clone()
+    arr, Bd, dt = dp.layer_descs(dev, grads, starts[:-1], grad_bs=gbs)
+    ws = torch.empty(max(16, dp.layers_clipped_workspace_bytes(arr, Bd, dt)), dtype=torch.uint8, device="cuda")
+    lib = dp.load_library()
+    assert lib.dp_layers_clipped_grad(arr, len(arr), Bd, c.data_ptr(), dt, 0, ws.data_ptr(), ws.numel(), None) == dp.DP_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.equal(flat, keep)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("accumulate", [False, True])
 def test_grouped_clipping_mixed_kinds(dp, dtype, accumulate):
