@@ -147,6 +147,45 @@ def test_layers_workspace_sizes(lib):
     assert h(descs([(1, 784, 512), (1, 512, 256), (1, 256, 10)]), 256, dpclip.DP_F32) == 0    # short contractions: no K slices
 
 
+def test_layer_descriptor_layout_and_argument_checks(lib):
+    """Host logic only: every field of dp_layer_desc is read where the header says (the checks below fail before any
+    launch, so the pointers are never touched; they are made-up, 16-byte aligned addresses)."""
+    B, T, di, do = 4, 64, 72, 40
+    fake = lambda k: 0x10000000 + 0x100000 * k
+
+    def descs(**over):
+        arr = (dpclip.LayerDesc * 2)()
+        for l in range(2):
+            d = dict(A=fake(1 + l), G=fake(3 + l), T=T, d_in=di, d_out=do, grad=fake(5 + l), noise_offset=0, bias_rows=None,
+                     sqnorm=None, clip=None, clip_C=0.0, grad_b=None, bias_noise_offset=0)
+            d.update({k: (v[l] if isinstance(v, (list, tuple)) else v) for k, v in over.items()})
+            arr[l] = dpclip.LayerDesc(**d)
+        return arr
+
+    dt, auto = dpclip.DP_BF16, 0
+    sq = lib.dp_layers_sqnorm_clip
+    assert dpclip.layers_workspace_bytes(descs(), B, dt) > 0       # every valid call below stops at the missing workspace
+    # plain call: everything valid, so the first complaint is the missing workspace
+    assert sq(descs(), 2, B, dt, auto, 0, fake(9), 0.0, None, None, 0, None) == dpclip.DP_ERR_WORKSPACE
+    # sqnorm / clip / clip_C: one array with two thresholds is refused, with one threshold it gets as far as the workspace
+    assert sq(descs(sqnorm=fake(10), clip=fake(11), clip_C=[1.0, 2.0]), 2, B, dt, auto, 0, None, 0.0, None, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+    assert sq(descs(sqnorm=fake(10), clip=fake(11), clip_C=[1.5, 1.5]), 2, B, dt, auto, 0, None, 0.0, None, None, 0, None) == dpclip.DP_ERR_WORKSPACE
+    assert sq(descs(sqnorm=fake(10), clip=fake(11), clip_C=[0.0, 0.0]), 2, B, dt, auto, 0, None, 0.0, None, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+    # a layer without an array of its own needs the call's
+    assert sq(descs(sqnorm=[fake(10), None]), 2, B, dt, auto, 0, None, 0.0, None, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+    cg = lib.dp_layers_clipped_grad_noise
+    need = dpclip.layers_clipped_workspace_bytes(descs(), B, dt)
+    # clip: the layers' own factors stand in for the call's
+    assert cg(descs(), 2, B, None, dt, 0, 0.0, 0, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+    assert need > 0                                   # else the next call would go on to launch kernels on made-up pointers
+    assert cg(descs(clip=fake(11)), 2, B, None, dt, 0, 0.0, 0, None, 0, None) == dpclip.DP_ERR_WORKSPACE
+    # grad_b needs bias_rows; bias_noise_offset + d_out must not wrap
+    assert cg(descs(grad_b=fake(12)), 2, B, fake(13), dt, 0, 0.0, 0, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+    assert cg(descs(grad_b=fake(12), bias_rows=fake(14), bias_noise_offset=2 ** 64 - 8), 2, B, fake(13), dt, 0, 1.0, 0, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+    assert cg(descs(noise_offset=2 ** 64 - 8), 2, B, fake(13), dt, 0, 1.0, 0, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+    assert cg(descs(grad=[fake(5), None]), 2, B, fake(13), dt, 0, 0.0, 0, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
+
+
 def test_missing_library_raises(monkeypatch):
     monkeypatch.setattr(dpclip, "_lib", None)
     monkeypatch.setattr(dpclip, "LIB_PATH", "/nonexistent/libdpclip.so")
