@@ -525,3 +525,22 @@ def test_f8_generator_rounds_to_the_nearest_code():
     # ties: 17 lies midway between the e4m3 neighbours 16 (mantissa 000) and 18 (001), 19 between 18 and 20 (010)
     t = orc.f8_to_f64(wl.f32_to_f8_bits(np.array([17.0, 19.0], dtype=np.float32), "e4m3"), "e4m3")
     np.testing.assert_array_equal(t, [16.0, 20.0])
+
+
+def test_f8_workloads_store_the_same_draws():
+    """generate(dtype=...) stores the configuration's own draws in the other type: the 8-bit bytes decode to a nearest
+    code of the float32 draw (A e4m3 and G e5m2 under "f8"), the fp16 values are its numpy rounding."""
+    from paper_2009_03106_amd import workloads as wl
+    _, l32 = wl.generate("rnn", B=3, dtype="f32")
+    _, l8 = wl.generate("rnn", B=3, dtype="f8")
+    _, l16 = wl.generate("rnn", B=3, dtype="f16")
+    (A32, G32), (A8, G8), (A16, G16) = l32[0], l8[0], l16[0]
+    assert A8.dtype == np.uint8 and G8.dtype == np.uint8 and A8.shape == A32.shape and G8.shape == G32.shape
+    np.testing.assert_array_equal(A16, A32.astype(np.float16))
+    for bits, x, fmt in ((A8, A32, "e4m3"), (G8, G32, "e5m2")):
+        vals = orc.f8_to_f64(np.arange(256, dtype=np.uint8), fmt)
+        vals = vals[np.isfinite(vals)]
+        sample = np.random.default_rng(0).choice(x.size, 2000, replace=False)
+        xs = x.ravel()[sample].astype(np.float64)
+        best = np.min(np.abs(xs[:, None] - vals[None, :]), axis=1)
+        np.testing.assert_array_equal(np.abs(orc.f8_to_f64(bits.ravel()[sample], fmt) - xs), best)
