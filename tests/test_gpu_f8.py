@@ -113,17 +113,18 @@ def test_f8_all_ones_clip_is_the_plain_sum(dp):
     assert fro_err(g, ref) <= FRO_TOL8
 
 
-@pytest.mark.parametrize("dtype", DTYPES)
-def test_f8_transformer_pipeline(dp, dtype):
+@pytest.mark.parametrize("dtype,B", [("f8e4m3", 6), ("f8e5m2", 6), ("f8", 6), ("f8", 64)])
+def test_f8_transformer_pipeline(dp, dtype, B):
     """The transformer configuration's four layers with 8-bit inputs through the several-layers calls: norms, clip
-    factors, clipped sums and noise against the oracle's pipeline on the widened bytes."""
-    w, layers = wl.generate("transformer", B=6, straddle=True, dtype=dtype, g_scale=G_SCALE[dtype])
+    factors, clipped sums and noise against the oracle's pipeline on the widened bytes; B = 64 is the configuration's
+    full size, in the launch shapes that bench.py times."""
+    w, layers = wl.generate("transformer", B=B, straddle=True, dtype=dtype, g_scale=G_SCALE[dtype])
     C = w.C * G_SCALE[dtype]
     sa, sg = wl.f8_formats(dtype)
     layers64 = [(wide(A, sa), wide(G, sg)) for A, G in layers]
     s_ref, c_ref, g_ref = orc.run_pipeline(layers64, C, w.noise_std, w.noise_seed)
     dev = [(to_dev8(A, sa), to_dev8(G, sg)) for A, G in layers]
-    c = torch.empty(6, device="cuda")
+    c = torch.empty(B, device="cuda")
     s = dp.layers_sqnorm(dev, C=C, clip=c)
     assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TOL8
     assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL8
