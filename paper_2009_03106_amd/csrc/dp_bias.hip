@@ -43,10 +43,14 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows(const void* __restrict__
         constexpr int E = decltype(tag)::value;
         const uint32_t d[4] = {w.x, w.y, w.z, w.w};
         if constexpr (E >= 3) {
+            // two conversions per instruction (v_cvt_pk_f32_fp8 / _bf8: the low or the high 16 bits of the word)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int k = 0; k < 4; ++k) x[4 * j + k] = f8_byte<E>(d[j], k);
+            for (int j = 0; j < 4; ++j) {
+                f32x2 lo, hi;
+                if constexpr (E == 3) { lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)d[j], false); hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)d[j], true); }
+                else                  { lo = __builtin_amdgcn_cvt_pk_f32_bf8((int)d[j], false); hi = __builtin_amdgcn_cvt_pk_f32_bf8((int)d[j], true); }
+                x[4 * j] = lo[0]; x[4 * j + 1] = lo[1]; x[4 * j + 2] = hi[0]; x[4 * j + 3] = hi[1];
+            }
         } else if constexpr (E != 0) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) { x[2 * j] = In16<E == 2>::lo(d[j]); x[2 * j + 1] = In16<E == 2>::hi(d[j]); }
