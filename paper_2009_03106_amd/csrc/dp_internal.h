@@ -8,6 +8,13 @@
 
 namespace dpk {
 
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+// an M x N output tiles into TM x TN blocks with at most a quarter of the padded area wasted
+inline bool tiles_fit(int M, int N, int TM, int TN) {
+    const int64_t padded = (int64_t)ceil_div(M, TM) * TM * ceil_div(N, TN) * TN;
+    return padded * 4 <= (int64_t)M * N * 5;
+}
+
 // ---- small elementwise / reduction kernels (dp_small_kernels.hip)
 // dt: 0 = float32, 1 = bf16, 2 = fp16 (the values of dp_dtype)
 // Where a norm launcher's last kernel completes the norms of the whole model, it can write the clip factors

@@ -32,7 +32,6 @@ namespace dpk {
 namespace {
 
 constexpr int BK = 64;           // k rows per LDS stage
-inline int ceil_div_i(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 constexpr int BM = 128, BN = 128;
 
 struct TnArgs {
@@ -595,13 +594,12 @@ __global__ __launch_bounds__(kThreads, 1) void k_tn_bf16_big(BigArgs a) {
 // Use the 256 x 256 kernel when the shape is aligned and its padded tiles waste at most a quarter.
 inline bool big_ok(int T, int M, int N) {
     if (((T | M | N) & 7) != 0) return false;
-    const int64_t padded = (int64_t)ceil_div_i(M, GM) * GM * ceil_div_i(N, GN) * GN;
+    const int64_t padded = (int64_t)ceil_div(M, GM) * GM * ceil_div(N, GN) * GN;
     return padded * 4 <= (int64_t)M * N * 5;
 }
 
 constexpr int kSegMinT = 32;      // below this an LDS stage would be mostly padding
 
-inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 }  // namespace
 

@@ -411,13 +411,6 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
         }
 }
 
-inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
-
-// at most a quarter of the padded tiles may be waste
-inline bool tiles_fit(int M, int N, int TM, int TN) {
-    const int64_t padded = (int64_t)ceil_div(M, TM) * TM * ceil_div(N, TN) * TN;
-    return padded * 4 <= (int64_t)M * N * 5;
-}
 
 // 0: not for this kernel; 1: GeoL; 2: GeoS; 3: GeoT (the first that fits, in the order of flop per copied byte)
 int dma_geometry(int T, int M, int N) {

@@ -252,7 +252,6 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) {
     }
 }
 
-inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // the short-contraction kernel takes K up to this many rows
 constexpr int kShortK = 512;

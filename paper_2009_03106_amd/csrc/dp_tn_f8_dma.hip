@@ -338,21 +338,14 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
         }
 }
 
-inline int ceil_div8(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
-
-// at most a quarter of the padded tiles may be waste
-inline bool tiles_fit8(int M, int N, int TM, int TN) {
-    const int64_t padded = (int64_t)ceil_div8(M, TM) * TM * ceil_div8(N, TN) * TN;
-    return padded * 4 <= (int64_t)M * N * 5;
-}
 
 // 0: not for this kernel; 1: Geo8L; 2: Geo8T
 int dma8_geometry(int T, int M, int N) {
     if (((M | N) & 15) != 0) return 0;
-    if ((T % DK8) != 0 && (int64_t)ceil_div8(T, DK8) * DK8 * 4 > (int64_t)T * 5) return 0;   // ragged T: at most a quarter of zero rows
+    if ((T % DK8) != 0 && (int64_t)ceil_div(T, DK8) * DK8 * 4 > (int64_t)T * 5) return 0;   // ragged T: at most a quarter of zero rows
     if ((int64_t)DK8 * (M > N ? M : N) >= (int64_t(1) << 31)) return 0;           // 32-bit lane offsets inside a stage
-    if (tiles_fit8(M, N, Geo8L::TM, Geo8L::TN)) return 1;
-    if (tiles_fit8(M, N, Geo8T::TM, Geo8T::TN)) return 2;
+    if (tiles_fit(M, N, Geo8L::TM, Geo8L::TN)) return 1;
+    if (tiles_fit(M, N, Geo8T::TM, Geo8T::TN)) return 2;
     return 0;
 }
 
@@ -371,8 +364,8 @@ int pick_geometry8(int T, int M, int N, int64_t units) {
     int64_t best_blocks = -1;
     for (int id = first; id <= 2; ++id) {
         const Geo8Dims g = geo8_dims(id);
-        if (!tiles_fit8(M, N, g.tm, g.tn)) continue;
-        const int64_t tiles = (int64_t)ceil_div8(M, g.tm) * ceil_div8(N, g.tn);
+        if (!tiles_fit(M, N, g.tm, g.tn)) continue;
+        const int64_t tiles = (int64_t)ceil_div(M, g.tm) * ceil_div(N, g.tn);
         int64_t per_tile = 256 * g.occ / tiles;
         if (per_tile < 1) per_tile = 1;
         const int64_t blocks = tiles * (units < per_tile ? units : per_tile);
@@ -403,12 +396,12 @@ bool dma8_clipped_ok(int T, int M, int N) { return dma8_geometry(T, M, N) != 0; 
 bool dma8_direct_ok(int T, int M, int N) { return T >= 64 && dma8_geometry(T, M, N) != 0; }
 
 TnPlan plan_clipped_f8_dma(int B, int T, int M, int N) {
-    const int64_t spe = ceil_div8(T, DK8);
+    const int64_t spe = ceil_div(T, DK8);
     const int64_t stages = (int64_t)B * spe;
     const Geo8Dims gd = geo8_dims(pick_geometry8(T, M, N, (stages + 3) / 4));
     TnPlan p;
     p.tile_m = gd.tm; p.tile_n = gd.tn;
-    p.tiles_m = ceil_div8(M, p.tile_m); p.tiles_n = ceil_div8(N, p.tile_n);
+    p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.epu = 0; p.big = gd.tm == Geo8L::TM; p.dma = true;
     p.zero_head = (T % DK8) != 0;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
@@ -439,11 +432,11 @@ hipError_t launch_clipped_f8_dma(const TnPlan& p, const void* A, const void* G, 
     a.A = static_cast<const unsigned char*>(A); a.G = static_cast<const unsigned char*>(G); a.clip = clip;
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.splits = p.splits;
-    a.stages_total = (int)((int64_t)B * ceil_div8(T, DK8));
+    a.stages_total = (int)((int64_t)B * ceil_div(T, DK8));
     a.stages_per_split = p.kchunk / DK8;
     const int64_t n = (int64_t)M * N;
     const int tiles = p.tiles_m * p.tiles_n;
-    a.per_xcd = ceil_div8((int64_t)tiles * p.splits, 8);
+    a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
     const hipError_t e = launch_any8<0>(p.big, a, p.zero_head, fmt, st);
@@ -455,7 +448,7 @@ TnPlan plan_direct_f8_dma(int B, int T, int M, int N) {
     const Geo8Dims gd = geo8_dims(pick_geometry8(T, M, N, B));      // one workgroup per (example, tile)
     TnPlan p;
     p.tile_m = gd.tm; p.tile_n = gd.tn;
-    p.tiles_m = ceil_div8(M, p.tile_m); p.tiles_n = ceil_div8(N, p.tile_n);
+    p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.big = gd.tm == Geo8L::TM; p.dma = true;
     p.zero_head = (T % DK8) != 0;
     p.splits = 1; p.kchunk = 0; p.epu = 1;
@@ -476,13 +469,13 @@ hipError_t launch_direct_f8_dma(const TnPlan& p, const void* A, const void* G, i
     a.B = B; a.T = T; a.M = M; a.N = N;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n;
     a.splits = B;
-    a.stages_total = (int)((int64_t)B * ceil_div8(T, DK8));
-    a.stages_per_split = ceil_div8(T, DK8);
+    a.stages_total = (int)((int64_t)B * ceil_div(T, DK8));
+    a.stages_per_split = ceil_div(T, DK8);
     a.out = partial; a.slice = 0; a.accumulate = 0;
     const int tiles = a.tiles_m * a.tiles_n;
     const int64_t total = (int64_t)tiles * B;
     if (total >= (int64_t(1) << 28)) return hipErrorInvalidValue;
-    a.per_xcd = ceil_div8(total, 8);
+    a.per_xcd = ceil_div(total, 8);
     const hipError_t e = launch_any8<1>(p.big, a, p.zero_head, fmt, st);
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
