@@ -351,3 +351,54 @@ def test_f8_empty_problems_and_argument_errors(dp):
                                None) == dp.DP_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert torch.all(sq == 9.0)
+
+
+def test_f8_step_with_groups_and_biases_is_graph_capturable(dp):
+    """A step on 8-bit inputs with per-layer clipping, bias rows (their own pass for 8-bit layers), a widened layer,
+    clipped sums of weights and biases and fused noise, captured into a HIP graph: every replay (with eager work in
+    between) reproduces the eager results bit for bit."""
+    B = 4
+    shapes = [(256, 256, 384), (128, 136, 128), (192, 128, 256)]           # the second one runs widened to fp16
+    devs = [draw(70 + k, B, T, di, do, "f8")[1] for k, (T, di, do) in enumerate(shapes)]
+    m = len(devs)
+    sq = [torch.zeros(B, device="cuda") for _ in range(m)]
+    cl = [torch.zeros(B, device="cuda") for _ in range(m)]
+    rows = [torch.zeros((B, do), device="cuda") for _, _, do in shapes]
+    sizes = [di * do + do for _, di, do in shapes]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.zeros(sum(sizes), device="cuda")
+    grads = [flat[starts[i]:starts[i] + di * do].view(di, do) for i, (_, di, do) in enumerate(shapes)]
+    gbs = [flat[starts[i] + di * do:starts[i + 1]] for i, (_, di, do) in enumerate(shapes)]
+    groups = [(sq[l], cl[l], 0.05) for l in range(m)]
+    d1 = dp.layer_descs(devs, bias_rows=rows, groups=groups)
+    d2 = dp.layer_descs(devs, grads, starts[:-1], bias_rows=rows, groups=groups, grad_bs=gbs,
+                        bias_noise_offsets=[starts[i] + di * do for i, (_, di, do) in enumerate(shapes)])
+    ws1 = torch.empty(max(16, dp.layers_workspace_bytes(d1[0], B, d1[2])), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(max(16, dp.layers_clipped_workspace_bytes(d2[0], B, d2[2])), dtype=torch.uint8, device="cuda")
+    unused = torch.zeros(B, device="cuda")
+
+    def step():
+        dp.layers_sqnorm(devs, unused, workspace=ws1, descs=d1)
+        dp.layers_clipped_grad(devs, None, workspace=ws2, descs=d2, noise_std=0.25, seed=5)
+
+    outs = sq + cl + rows + [flat]
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    assert all((c > 0).all() and (c <= 1).all() for c in cl) and any((c < 1).any() for c in cl)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in outs:
+            t.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outs, want):
+            assert torch.equal(got, ref), rep
+        _ = torch.randn(1 << 18, device="cuda").sum().item()        # eager work and a synchronisation between replays
