@@ -830,9 +830,36 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
     for (int64_t l = 0; l < n_layers; ++l)
         if (B > 0 && !clip && !layers[l].clip) return DP_ERR_INVALID_ARG;          // neither the layer's own factors nor the call's
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
+    // float32 layers with a short contraction (a model of small dense layers) share launches, 8 layers each
+    std::vector<char> done((size_t)n_layers, 0);
+    if (dtype == DP_F32 && B > 0 && !(stddev > 0.0f)) {
+        ShortLayerDesc batch[8];
+        int64_t which[8];
+        int nb = 0;
+        auto flush = [&]() -> hipError_t {
+            hipError_t e = hipSuccess;
+            if (nb >= 2) {
+                e = launch_clipped_f32_short_layers(batch, nb, (int)B, accumulate != 0, static_cast<hipStream_t>(hip_stream));
+                for (int i = 0; i < nb; ++i) done[(size_t)which[i]] = 1;
+            }
+            nb = 0;
+            return e;
+        };
+        for (int64_t l = 0; l < n_layers; ++l) {
+            const dp_layer_desc& y = layers[l];
+            if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+            if (!clipped_f32_is_short(plan_clipped_f32((int)B, (int)y.T, (int)y.d_in, (int)y.d_out))) continue;
+            which[nb] = l;
+            batch[nb++] = ShortLayerDesc{static_cast<const float*>(y.A), static_cast<const float*>(y.G), y.clip ? y.clip : clip, y.grad,
+                                         (int)y.T, (int)y.d_in, (int)y.d_out};
+            if (nb == 8 && flush() != hipSuccess) return DP_ERR_HIP;
+        }
+        if (flush() != hipSuccess) return DP_ERR_HIP;
+    }
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
-        const dp_status s1 = clipped_grad_noise(y.A, y.G, y.clip ? y.clip : clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
+        const dp_status s1 = done[(size_t)l] ? DP_OK
+                           : clipped_grad_noise(y.A, y.G, y.clip ? y.clip : clip, B, y.T, y.d_in, y.d_out, dtype, accumulate, y.grad, workspace,
                                                 workspace_bytes, hip_stream, stddev, seed, y.noise_offset);
         if (s1 != DP_OK) return s1;
         if (y.grad_b && y.d_out > 0) {

@@ -108,6 +108,11 @@ hipError_t launch_clipped_f8_dma(const TnPlan& p, const void* A, const void* G, 
                                  int fmt, const NoiseArgs* noise);
 hipError_t launch_direct_f8_dma(const TnPlan& p, const void* A, const void* G, int B, int T, int M, int N,
                                 bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co = nullptr);
+// float32 layers with a short contraction (B T <= 512: plan_clipped_f32 gives them one 32 x 32-tile kernel without K
+// slices), up to 8 in one launch; per layer the same arithmetic as launch_clipped_f32
+bool clipped_f32_is_short(const TnPlan& p);
+struct ShortLayerDesc { const float* A; const float* G; const float* clip; float* grad; int T, M, N; };
+hipError_t launch_clipped_f32_short_layers(const ShortLayerDesc* layers, int n_layers, int B, bool accumulate, hipStream_t st);
 hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, const float* clip,
                               int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
                               const NoiseArgs* noise);

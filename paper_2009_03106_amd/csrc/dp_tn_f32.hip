@@ -155,14 +155,13 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
 // workgroups.  No K slices: the whole sum is finished in the kernel.
 constexpr int SBK = 64, STM = 32, STN = 32;
 template <bool VEC>
-__global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) {
+__device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile) {
     constexpr int NV = 2;               // float4 pieces of either operand per thread and stage
     __shared__ __attribute__((aligned(16))) float sA[SBK][STM];
     __shared__ __attribute__((aligned(16))) float sG[SBK][STN];
     __shared__ __attribute__((aligned(16))) float part[4][STM][STN + 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tile = blockIdx.x;
     const int tm = tile / a.tiles_n, tn = tile % a.tiles_n;
     const int m0 = tm * STM, n0 = tn * STN;
     const int k_end = a.K;
@@ -252,6 +251,20 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) {
     }
 }
 
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) { tn_f32_short_tile<VEC>(a, blockIdx.x); }
+
+// The same for several layers in one launch (a model of small dense layers is a chain of launches of a few
+// microseconds each otherwise): the layers' tiles form one list, in the order given.
+constexpr int kShortBatch = 8;
+struct TnShortLayers { int n_layers; int first_tile[kShortBatch + 1]; TnArgsF layer[kShortBatch]; };
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void k_tn_f32_short_layers(TnShortLayers t) {
+    int li = 0;
+    while (li + 1 < t.n_layers && (int)blockIdx.x >= t.first_tile[li + 1]) ++li;
+    const TnArgsF a = t.layer[li];
+    tn_f32_short_tile<VEC>(a, (int)blockIdx.x - t.first_tile[li]);
+}
 
 // the short-contraction kernel takes K up to this many rows
 constexpr int kShortK = 512;
@@ -322,6 +335,33 @@ hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, c
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
+}
+
+bool clipped_f32_is_short(const TnPlan& p) { return p.tile_m == STM && p.splits == 1; }
+
+hipError_t launch_clipped_f32_short_layers(const ShortLayerDesc* layers, int n_layers, int B, bool accumulate, hipStream_t st) {
+    if (n_layers < 1 || n_layers > kShortBatch) return hipErrorInvalidValue;
+    TnShortLayers t;
+    t.n_layers = n_layers;
+    bool vec = true;
+    int64_t first = 0;
+    for (int l = 0; l < kShortBatch; ++l) {
+        t.first_tile[l] = (int)first;
+        if (l >= n_layers) { t.layer[l] = TnArgsF{nullptr, nullptr, nullptr, nullptr, 0, 0, 1, 0, 0, 0, 0, 0, 0}; continue; }
+        const ShortLayerDesc& y = layers[l];
+        TnArgsF& a = t.layer[l];
+        a.A = y.A; a.G = y.G; a.clip = y.clip;
+        a.K = B * y.T; a.T = y.T; a.M = y.M; a.N = y.N;
+        a.tiles_m = ceil_div(y.M, STM); a.tiles_n = ceil_div(y.N, STN); a.kchunk = a.K;
+        a.out = y.grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0;
+        vec = vec && ((y.M | y.N) & 3) == 0;
+        first += (int64_t)a.tiles_m * a.tiles_n;
+        if (first >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    }
+    t.first_tile[kShortBatch] = (int)first;
+    if (vec) k_tn_f32_short_layers<true><<<(unsigned)first, kThreads, 0, st>>>(t);
+    else     k_tn_f32_short_layers<false><<<(unsigned)first, kThreads, 0, st>>>(t);
+    return hipGetLastError();
 }
 
 hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, int B, int T, int M, int N,
