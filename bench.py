@@ -326,6 +326,26 @@ def main():
         bias_out["sqnorm_without_ms"] = tf[1]
         del ws_wb
     del rows, gbs
+    # LayerNorm scale and shift rows (Algorithm 5) of a layer of the first layer's input width: G and the normalised
+    # input of the same shape, read once each (the first layer's A and a same-shaped slice of values stand in)
+    A0 = pipe.dev[0][0]
+    if A0.dim() == 3:
+        H0 = torch.roll(A0.view(torch.uint8) if w.dtype.startswith("f8") else A0, 1, 0)
+        H0 = H0.view(A0.dtype) if w.dtype.startswith("f8") else H0
+        tl = 0.0
+        for rep in range(5 + 2):
+            evb[0].record()
+            dp.layernorm_sqnorm(H0, A0, pipe.s, accumulate=True)
+            evb[1].record()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                tl += evb[0].elapsed_time(evb[1])
+        tl /= 5
+        ln_bytes = 2 * A0.numel() * A0.element_size() + 2 * 4 * A0.shape[0] * A0.shape[2]
+        bias_out["layernorm_sqnorm_ms"] = tl
+        bias_out["layernorm_sqnorm_gbs"] = ln_bytes / (tl * 1e-3) / 1e9
+        bias_out["layernorm_shape"] = [int(x) for x in A0.shape]
+        del H0
 
     others = {}
     if not args.no_others and args.batch is None:
