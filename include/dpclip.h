@@ -145,7 +145,7 @@ typedef struct {
                                    per-example bias gradients sum_t G_i[t, :] there and adds their squared norms (what
                                    dp_bias_sqnorm does), for layers that have a bias */
     /* Per-layer and grouped clipping (a threshold per layer, e.g. c / sqrt(m) for m layers, or per group of layers;
-     * Section 2).  A layer that names an array of its own is added to that array instead of the call's sqnorm:
+     * Section 4).  A layer that names an array of its own is added to that array instead of the call's sqnorm:
      * layers naming the same array form a group.  All NULL / 0: the layer belongs to the call's own array. */
     float* sqnorm;              /* NULL, or device float32[B]: dp_layers_sqnorm(_clip) adds this layer's squared norm
                                    (bias share included) here; `accumulate` applies to these arrays too */
@@ -157,7 +157,10 @@ typedef struct {
     float* grad_b;              /* NULL, or device float32[d_out]: dp_layers_clipped_grad(_noise) also writes the clipped
                                    sum of the layer's bias gradients, sum_i clip[i] bias_rows[i, :] (what
                                    dp_clipped_bias_grad does; bias_rows as dp_layers_sqnorm left them) */
-    uint64_t bias_noise_offset; /* position of grad_b[0] in the noise stream: dp_layers_clipped_grad_noise only */
+    uint64_t bias_noise_offset; /* position of grad_b[0] in the noise stream: dp_layers_clipped_grad_noise only.  The
+                                   stretches [noise_offset, + d_in*d_out) and [bias_noise_offset, + d_out) of all layers
+                                   must be pairwise disjoint, or gradients share draws and the noise is no longer the
+                                   independent N(0, sigma^2) per coordinate of the Gaussian mechanism (not checked here) */
 } dp_layer_desc;
 
 dp_status dp_layers_sqnorm(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
@@ -232,7 +235,13 @@ dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C,
  * With 16-bit inputs the factor is applied either to the fp32 accumulators
  * (one fp32 rounding per example) or, in the kernels for unaligned shapes, to
  * the rows of A, which are then rounded back to the input format (relative
- * error 2^-9 per element for bf16, 2^-12 for fp16, unbiased). */
+ * error at most 2^-8 per element for bf16, 2^-11 for fp16, unbiased).
+ * clip[i] == 0 leaves example i out (finite inputs): masked examples, and the
+ * factor that dp_clip_factors gives a norm that overflowed, are safe.  The
+ * kernels that scale accumulators keep their running sum in units of the
+ * current example's factor: a factor so far below its predecessor that their
+ * ratio overflows float32 counts as 0 there, and factors that differ by more
+ * than about 30 orders of magnitude inside one call can overflow the sum. */
 dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
                           int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                           dp_dtype dtype, int accumulate, float* grad,
@@ -333,6 +342,15 @@ size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t 
 /* The AUTO rule: DP_PATH_GRAM iff T*(T+1)*(d_in+d_out) < 2*T*d_in*d_out,
  * else DP_PATH_DIRECT (a tie goes to DIRECT). */
 dp_path dp_choose_path(int64_t T, int64_t d_in, int64_t d_out);
+
+/* Test hook: how dp_clipped_grad applies the clip factors for this shape and
+ * type.  0: in float32 (to the accumulators or to a per-example tile; the
+ * result differs from exact arithmetic on the stored inputs only by float32
+ * rounding).  1: to the rows of A, which are rounded back to the 16-bit input
+ * format (relative error at most 2^-8 per element for bf16, 2^-11 for fp16).  -1 for
+ * invalid arguments.  Lets a test hold each kernel to the accuracy it should
+ * reach instead of the loosest bound. */
+int dp_clipped_grad_rounds_inputs(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype);
 
 /* Static, never-NULL description of a status code. */
 const char* dp_status_string(dp_status status);

@@ -149,6 +149,15 @@ size_t dp_workspace_bytes(dp_op op, int64_t B, int64_t T, int64_t d_in, int64_t 
     return 0;
 }
 
+int dp_clipped_grad_rounds_inputs(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
+    if (check_dims(B, T, d_in, d_out) != DP_OK || !valid_dtype(dtype)) return -1;
+    if (B == 0 || T == 0 || d_in == 0 || d_out == 0 || dtype == DP_F32) return 0;
+    if (is8(dtype) && dma8_clipped_ok((int)T, (int)d_in, (int)d_out)) return 0;
+    // 16-bit inputs, and 8-bit ones widened to fp16: the copy-pipeline and the example-by-example kernels scale in float32
+    const TnPlan p = plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out);
+    return (p.dma || (!p.big && p.segmented)) ? 0 : 1;
+}
+
 dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                           dp_dtype dtype, dp_path path, int accumulate, float* sqnorm,
                           void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -682,7 +691,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
 
 namespace {
 
-// dp_layers_sqnorm_clip when layers name output arrays of their own (per-layer or grouped clipping, Section 2: a
+// dp_layers_sqnorm_clip when layers name output arrays of their own (per-layer or grouped clipping, Section 4: a
 // threshold per layer or per group of layers).  A group is an output array: the layers' `sqnorm` pointers, and the
 // call's own array for the layers that name none.  Every group's norms are complete when its last layer (and bias
 // pass) has been added; the kernel that adds it writes the group's clip factors where it can, else a clip-factor

@@ -24,6 +24,11 @@
 // rounding per example.  It needs every 32-row stage to lie inside one
 // example: T % 32 == 0, or the ragged mode below, which pads every example
 // with rows of zeros.  K slices are arbitrary ranges of stages.
+// An example whose factor is zero (a masked example, or the factor that
+// dp_clip_factors gives an overflowed norm), or so far below the tile's
+// current unit that c_cur / c_next is not finite in fp32, cannot become the
+// unit: its MFMAs are skipped instead and the unit stays, i.e. the example
+// counts with factor 0, as the weighted sum defines for a zero factor.
 #include "dp_common.h"
 #include "dp_internal.h"
 
@@ -284,6 +289,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
     float vclip = 1.0f;
     if (MODE == 0) vclip = a.clip[min(ex0 + lane, a.B - 1)];
     float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
+    bool skip = false;                              // the current example is left out (see the head of this file)
 
     // prologue: all NST buffers are free, fill them
 #pragma unroll
@@ -330,8 +336,10 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
             sub = 0;
             ++ex;
             const float c_next = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), ex - ex0));
-            if (c_next != c_cur) {
-                const float ratio = c_cur / c_next;
+            const float ratio = c_cur / c_next;
+            // a zero factor (or one so small that the ratio overflows) after a non-zero one: leave this example out
+            skip = __builtin_isinf(ratio);
+            if (c_next != c_cur && !skip) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -339,7 +347,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
             }
-            c_cur = c_next;
+            if (!skip) c_cur = c_next;
         }
         ++sub;
 #pragma unroll
@@ -357,7 +365,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
                 if (st + NST < n_stages) issue(st % NST);
                 read_kstep(f[0], (uint32_t)((st + 1) % NST) * STAGE_BYTES, 0);
             }
-            mfma_kstep(f[ks & 1]);
+            if (MODE != 0 || !skip) mfma_kstep(f[ks & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
     }

@@ -211,6 +211,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
     float vclip = 1.0f;
     if (MODE == 0) vclip = a.clip[min(ex0 + lane, a.B - 1)];
     float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
+    bool skip = false;                              // the current example is left out (zero factor, see below)
 
     // prologue: all NST buffers are free, fill them
 #pragma unroll
@@ -260,8 +261,11 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
             sub = 0;
             ++ex;
             const float c_next = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), ex - ex0));
-            if (c_next != c_cur) {
-                const float ratio = c_cur / c_next;
+            const float ratio = c_cur / c_next;
+            // a zero factor (or one so small that the ratio overflows) after a non-zero one cannot become the tile's
+            // unit: the example's MFMAs are skipped and the unit stays, i.e. it counts with factor 0
+            skip = __builtin_isinf(ratio);
+            if (c_next != c_cur && !skip) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
             }
-            c_cur = c_next;
+            if (!skip) c_cur = c_next;
         }
         ++sub;
         __builtin_amdgcn_s_waitcnt(0xC07F);                                              // lgkmcnt(0): this stage's fragments
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
             if (st + NST < n_stages) issue(st % NST);
             read_stage(f[CUR ^ 1], (uint32_t)((st + 1) % NST) * STAGE_BYTES);
         }
-        mfma_stage(f[CUR]);
+        if (MODE != 0 || !skip) mfma_stage(f[CUR]);
         __builtin_amdgcn_sched_barrier(0);
     };
     for (int st = 0; st < n_stages; st += 2) {

@@ -24,7 +24,8 @@ _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
 EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_sqnorm_clip", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
            "dp_layers_clipped_grad_noise", "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
-           "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw")
+           "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw",
+           "dp_clipped_grad_rounds_inputs")
 
 _lib = None
 
@@ -94,6 +95,8 @@ def load_library() -> ctypes.CDLL:
     lib.dp_status_string.restype = ctypes.c_char_p
     lib.dp_philox_raw.argtypes = [vp, i64, u64, u64, vp]
     lib.dp_philox_raw.restype = ci
+    lib.dp_clipped_grad_rounds_inputs.argtypes = [i64, i64, i64, i64, ci]
+    lib.dp_clipped_grad_rounds_inputs.restype = ci
     _lib = lib
     return lib
 
@@ -147,6 +150,31 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return t.data_ptr() if t.numel() > 0 else None
 
 
+def _f32(t: Optional[torch.Tensor], shape, name: str) -> Optional[int]:
+    """Pointer of a float32 device tensor that the library reads or writes as `shape`: a tensor of another type,
+    size or layout would become an out-of-bounds access on the device, so it is refused here."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous float32 device tensor")
+    n = 1
+    for d in shape:
+        n *= int(d)
+    if t.numel() != n:
+        raise ValueError(f"{name} must hold {tuple(shape)} = {n} elements, got {tuple(t.shape)}")
+    return t.data_ptr() if n > 0 else None
+
+
+def _on_stream(stream: Optional[torch.cuda.Stream], *tensors) -> None:
+    """Temporaries that this module allocated (on torch's current stream) for a call issued on another stream:
+    tell the caching allocator, or it could hand the block out again while the kernel still runs."""
+    if stream is None or stream == torch.cuda.current_stream():
+        return
+    for t in tensors:
+        if t is not None and t.numel() > 0:
+            t.record_stream(stream)
+
+
 def _shape3(A: torch.Tensor, G: torch.Tensor):
     if A.dim() == 2:
         A = A.unsqueeze(1)
@@ -190,11 +218,45 @@ def layer_sqnorm(A: torch.Tensor, G: torch.Tensor, sqnorm: Optional[torch.Tensor
             raise ValueError("accumulate needs an existing sqnorm tensor")
         sqnorm = torch.empty(B, dtype=torch.float32, device=A.device)
     ws = _workspace(lambda: workspace_bytes(DP_OP_SQNORM, B, T, d_in, d_out, dt, path), A.device, workspace)
+    _on_stream(stream, None if workspace is not None else ws)
     st = lib.dp_layer_sqnorm(_ptr(A), _ptr(G), B, T, d_in, d_out, dt, _PATHS[path], int(bool(accumulate)),
-                             _ptr(sqnorm), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                             _f32(sqnorm, (B,), "sqnorm"), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                              _stream_ptr(stream))
     _check(st, "dp_layer_sqnorm")
     return sqnorm
+
+
+def check_noise_ranges(ranges) -> None:
+    """Raise unless the [offset, offset + n) stretches of the noise stream are pairwise disjoint: two gradients that
+    shared draws would not get the independent N(0, sigma^2) per coordinate that the Gaussian mechanism asks for."""
+    end = -1
+    for off, n in sorted(r for r in ranges if r[1] > 0):
+        if off < end:
+            raise ValueError("noise offsets overlap: every weight and bias gradient needs its own stretch of the stream")
+        end = off + n
+
+
+def noise_layout(sizes, has_bias, noise_offsets=None, bias_noise_offsets=None):
+    """Positions in the noise stream of every layer's weight gradient and bias gradient.
+    sizes: (d_in, d_out) per layer; has_bias: per layer, whether a bias gradient draws noise.
+    Defaults: the weight gradients back to back from 0 in the order given, the bias gradients back to back behind
+    the last weight gradient.  Returns (weight offsets, bias offsets (0 where there is no bias)); raises if any two
+    stretches overlap."""
+    w_offs, running = [], 0
+    for i, (d_in, d_out) in enumerate(sizes):
+        w_offs.append(running if noise_offsets is None else int(noise_offsets[i]))
+        running += d_in * d_out
+    bias_running = max([o + d_in * d_out for o, (d_in, d_out) in zip(w_offs, sizes)], default=0)
+    b_offs = []
+    for i, (d_in, d_out) in enumerate(sizes):
+        if not has_bias[i]:
+            b_offs.append(0)
+            continue
+        b_offs.append(bias_running if bias_noise_offsets is None else int(bias_noise_offsets[i]))
+        bias_running += d_out
+    check_noise_ranges([(o, d_in * d_out) for o, (d_in, d_out) in zip(w_offs, sizes)] +
+                       [(o, d_out) for o, (_, d_out), hb in zip(b_offs, sizes, has_bias) if hb])
+    return w_offs, b_offs
 
 
 def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=None, grad_bs=None, bias_noise_offsets=None):
@@ -208,7 +270,11 @@ def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=N
     layers_sqnorm adds up in that tensor (and whose clip factors it writes to clip), and whose clip factors
     layers_clipped_grad uses for these layers.
     grad_bs: one float32 [d_out] tensor (or None) per layer: layers_clipped_grad then also writes the clipped sum of the
-    layer's bias rows there (bias_noise_offsets: their positions in the noise stream, default 0).
+    layer's bias rows there.  bias_noise_offsets: their positions in the noise stream; by default the bias gradients
+    follow the last weight gradient back to back, in the order of the list, so that every parameter of the model
+    draws its own stretch of the stream (the Gaussian mechanism needs independent noise per coordinate).  Offsets
+    given by the caller are checked: the ranges [offset, offset + n) of all weight and bias gradients must be
+    pairwise disjoint.
     The tensors must stay alive (and contiguous: the pointers are taken here) while the array is used."""
     if len(layers) == 0:
         raise ValueError("no layers")
@@ -216,7 +282,9 @@ def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=N
         raise ValueError("one gradient tensor per layer")
     arr = (LayerDesc * len(layers))()
     B0, dt0 = None, None
-    running = 0
+    w_offs, b_offs = noise_layout([(int(A.shape[-1]), int(G.shape[-1])) for A, G in layers],
+                                  [grad_bs is not None and grad_bs[i] is not None for i in range(len(layers))],
+                                  noise_offsets, bias_noise_offsets)
     for i, (A, G) in enumerate(layers):
         if not (A.is_contiguous() and G.is_contiguous()):
             raise ValueError("layer tensors must be contiguous")
@@ -249,9 +317,7 @@ def layer_descs(layers, grads=None, noise_offsets=None, bias_rows=None, groups=N
             if grad_bs[i].dtype != torch.float32 or tuple(grad_bs[i].shape) != (d_out,):
                 raise ValueError("bias gradients must be float32 [d_out]")
             gbp = _ptr(grad_bs[i])
-        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, running if noise_offsets is None else int(noise_offsets[i]), bp,
-                           sp, cp, float(cC), gbp, 0 if bias_noise_offsets is None else int(bias_noise_offsets[i]))
-        running += d_in * d_out
+        arr[i] = LayerDesc(_ptr(A), _ptr(G), T, d_in, d_out, gp, w_offs[i], bp, sp, cp, float(cC), gbp, b_offs[i])
     return arr, B0, dt0
 
 
@@ -273,10 +339,11 @@ def layers_sqnorm(layers, sqnorm: Optional[torch.Tensor] = None, *, path: str = 
             raise ValueError("accumulate needs an existing sqnorm tensor")
         sqnorm = torch.empty(B, dtype=torch.float32, device=dev)
     ws = _workspace(lambda: layers_workspace_bytes(arr, B, dt, path), dev, workspace)
+    _on_stream(stream, None if workspace is not None else ws)
     if (C is None) != (clip is None):
         raise ValueError("C and clip go together")
-    st = lib.dp_layers_sqnorm_clip(arr, len(arr), B, dt, _PATHS[path], int(bool(accumulate)), _ptr(sqnorm),
-                                   0.0 if C is None else float(C), _ptr(clip), _ptr(ws),
+    st = lib.dp_layers_sqnorm_clip(arr, len(arr), B, dt, _PATHS[path], int(bool(accumulate)), _f32(sqnorm, (B,), "sqnorm"),
+                                   0.0 if C is None else float(C), _f32(clip, (B,), "clip"), _ptr(ws),
                                    0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
     _check(st, "dp_layers_sqnorm_clip")
     return sqnorm
@@ -301,7 +368,8 @@ def layers_clipped_grad(layers, clip: torch.Tensor, grads=None, *, accumulate: b
         descs = layer_descs(layers, grads)
     arr, B, dt = descs
     ws = _workspace(lambda: layers_clipped_workspace_bytes(arr, B, dt), layers[0][0].device, workspace)
-    st = lib.dp_layers_clipped_grad_noise(arr, len(arr), B, _ptr(clip), dt, int(bool(accumulate)), float(noise_std),
+    _on_stream(stream, None if workspace is not None else ws)
+    st = lib.dp_layers_clipped_grad_noise(arr, len(arr), B, _f32(clip, (B,), "clip"), dt, int(bool(accumulate)), float(noise_std),
                                           int(seed) & (2 ** 64 - 1), _ptr(ws),
                                           0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
     _check(st, "dp_layers_clipped_grad_noise")
@@ -314,7 +382,8 @@ def clip_factors(sqnorm: torch.Tensor, C: float, clip: Optional[torch.Tensor] = 
     lib = load_library()
     if clip is None:
         clip = torch.empty_like(sqnorm)
-    st = lib.dp_clip_factors(_ptr(sqnorm), sqnorm.numel(), float(C), _ptr(clip), _stream_ptr(stream))
+    n = sqnorm.numel()
+    st = lib.dp_clip_factors(_f32(sqnorm, (n,), "sqnorm"), n, float(C), _f32(clip, (n,), "clip"), _stream_ptr(stream))
     _check(st, "dp_clip_factors")
     return clip
 
@@ -331,8 +400,9 @@ def clipped_grad(A: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, grad: Opt
             raise ValueError("accumulate needs an existing grad tensor")
         grad = torch.empty((d_in, d_out), dtype=torch.float32, device=A.device)
     ws = _workspace(lambda: workspace_bytes(DP_OP_CLIPPED_GRAD, B, T, d_in, d_out, dt), A.device, workspace)
-    st = lib.dp_clipped_grad(_ptr(A), _ptr(G), _ptr(clip), B, T, d_in, d_out, dt, int(bool(accumulate)),
-                             _ptr(grad), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+    _on_stream(stream, None if workspace is not None else ws)
+    st = lib.dp_clipped_grad(_ptr(A), _ptr(G), _f32(clip, (B,), "clip"), B, T, d_in, d_out, dt, int(bool(accumulate)),
+                             _f32(grad, (d_in, d_out), "grad"), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                              _stream_ptr(stream))
     _check(st, "dp_clipped_grad")
     return grad
@@ -346,7 +416,9 @@ def bias_sqnorm(G: torch.Tensor, sqnorm: Optional[torch.Tensor] = None, bias_row
         G = G.unsqueeze(1)
     if G.dim() != 3:
         raise ValueError("G must be [B, d_out] or [B, T, d_out]")
-    G = G.contiguous()
+    Gc = G.contiguous()
+    _on_stream(stream, None if Gc is G else Gc)
+    G = Gc
     B, T, d_out = G.shape
     if sqnorm is None:
         if accumulate:
@@ -354,8 +426,8 @@ def bias_sqnorm(G: torch.Tensor, sqnorm: Optional[torch.Tensor] = None, bias_row
         sqnorm = torch.empty(B, dtype=torch.float32, device=G.device)
     if bias_rows is None:
         bias_rows = torch.empty((B, d_out), dtype=torch.float32, device=G.device)
-    st = lib.dp_bias_sqnorm(_ptr(G), B, T, d_out, _dtype_code(G), int(bool(accumulate)), _ptr(sqnorm), _ptr(bias_rows),
-                            _stream_ptr(stream))
+    st = lib.dp_bias_sqnorm(_ptr(G), B, T, d_out, _dtype_code(G), int(bool(accumulate)), _f32(sqnorm, (B,), "sqnorm"),
+                            _f32(bias_rows, (B, d_out), "bias_rows"), _stream_ptr(stream))
     _check(st, "dp_bias_sqnorm")
     return sqnorm, bias_rows
 
@@ -370,7 +442,9 @@ def layernorm_sqnorm(G: torch.Tensor, Hbar: torch.Tensor, sqnorm: Optional[torch
     if G.dim() != 3 or G.shape != Hbar.shape:
         raise ValueError("G and Hbar must have the same [B, T, d] shape")
     dt = _dtype_code(Hbar, G)               # one dtype, or Hbar e4m3 (an activation) with G e5m2
-    G, Hbar = G.contiguous(), Hbar.contiguous()
+    Gc, Hc = G.contiguous(), Hbar.contiguous()
+    _on_stream(stream, None if Gc is G else Gc, None if Hc is Hbar else Hc)
+    G, Hbar = Gc, Hc
     B, T, d = G.shape
     if sqnorm is None:
         if accumulate:
@@ -378,7 +452,7 @@ def layernorm_sqnorm(G: torch.Tensor, Hbar: torch.Tensor, sqnorm: Optional[torch
         sqnorm = torch.empty(B, dtype=torch.float32, device=G.device)
     gam = torch.empty((B, d), dtype=torch.float32, device=G.device)
     bet = torch.empty((B, d), dtype=torch.float32, device=G.device)
-    st = lib.dp_layernorm_sqnorm(_ptr(G), _ptr(Hbar), B, T, d, dt, int(bool(accumulate)), _ptr(sqnorm),
+    st = lib.dp_layernorm_sqnorm(_ptr(G), _ptr(Hbar), B, T, d, dt, int(bool(accumulate)), _f32(sqnorm, (B,), "sqnorm"),
                                  _ptr(gam), _ptr(bet), _stream_ptr(stream))
     _check(st, "dp_layernorm_sqnorm")
     return sqnorm, gam, bet
@@ -395,7 +469,8 @@ def clipped_bias_grad(bias_rows: torch.Tensor, clip: torch.Tensor, grad_b: Optio
         if accumulate:
             raise ValueError("accumulate needs an existing grad_b tensor")
         grad_b = torch.empty(d_out, dtype=torch.float32, device=bias_rows.device)
-    st = lib.dp_clipped_bias_grad(_ptr(bias_rows), _ptr(clip), B, d_out, int(bool(accumulate)), _ptr(grad_b),
+    st = lib.dp_clipped_bias_grad(_ptr(bias_rows), _f32(clip, (B,), "clip"), B, d_out, int(bool(accumulate)),
+                                  _f32(grad_b, (d_out,), "grad_b"),
                                   _stream_ptr(stream))
     _check(st, "dp_clipped_bias_grad")
     return grad_b
@@ -404,7 +479,8 @@ def clipped_bias_grad(bias_rows: torch.Tensor, clip: torch.Tensor, grad_b: Optio
 def _conv_args(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int):
     if X.dim() != 4 or G.dim() != 3 or X.shape[0] != G.shape[0]:
         raise ValueError("X must be [B, H, W, C] (channels last) and G [B, H_out*W_out, d_out]")
-    X, G = X.contiguous(), G.contiguous()
+    if not (X.is_contiguous() and G.is_contiguous()):
+        raise ValueError("X and G must be contiguous (X channels last: [B, H, W, C] in memory)")
     B, H, W, C = X.shape
     T = (H + 2 * pad - KH + 1) * (W + 2 * pad - KW + 1)
     if G.shape[1] != T:
@@ -429,7 +505,8 @@ def conv_sqnorm(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int, sq
             raise ValueError("accumulate needs an existing sqnorm tensor")
         sqnorm = torch.empty(B, dtype=torch.float32, device=X.device)
     ws = _workspace(lambda: conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
-    st = lib.dp_conv_sqnorm(_ptr(X), _ptr(G), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)), _ptr(sqnorm),
+    _on_stream(stream, None if workspace is not None else ws)
+    st = lib.dp_conv_sqnorm(_ptr(X), _ptr(G), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)), _f32(sqnorm, (B,), "sqnorm"),
                             _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
     _check(st, "dp_conv_sqnorm")
     return sqnorm
@@ -447,8 +524,9 @@ def conv_clipped_grad(X: torch.Tensor, G: torch.Tensor, clip: torch.Tensor, KH: 
             raise ValueError("accumulate needs an existing grad tensor")
         grad = torch.empty((KH * KW * C, d_out), dtype=torch.float32, device=X.device)
     ws = _workspace(lambda: conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dt), X.device, workspace)
-    st = lib.dp_conv_clipped_grad(_ptr(X), _ptr(G), _ptr(clip), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)),
-                                  _ptr(grad), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+    _on_stream(stream, None if workspace is not None else ws)
+    st = lib.dp_conv_clipped_grad(_ptr(X), _ptr(G), _f32(clip, (B,), "clip"), B, H, W, C, KH, KW, pad, d_out, dt, int(bool(accumulate)),
+                                  _f32(grad, (KH * KW * C, d_out), "grad"), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                   _stream_ptr(stream))
     _check(st, "dp_conv_clipped_grad")
     return grad
@@ -458,12 +536,18 @@ def add_noise(grad: torch.Tensor, stddev: float, seed: int, offset: int = 0, *,
               stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
     """grad += stddev * N(0,1)[seed, offset + j] in place via dp_add_noise."""
     lib = load_library()
-    if grad.dtype != torch.float32:
-        raise TypeError("grad must be float32")
-    st = lib.dp_add_noise(_ptr(grad), grad.numel(), float(stddev), int(seed) & (2 ** 64 - 1), int(offset),
+    st = lib.dp_add_noise(_f32(grad, (grad.numel(),), "grad"), grad.numel(), float(stddev), int(seed) & (2 ** 64 - 1), int(offset),
                           _stream_ptr(stream))
     _check(st, "dp_add_noise")
     return grad
+
+
+def clipped_grad_rounds_inputs(B: int, T: int, d_in: int, d_out: int, dtype: int) -> bool:
+    """Test hook: whether clipped_grad folds the clip factors into re-rounded 16-bit rows of A for this shape."""
+    r = load_library().dp_clipped_grad_rounds_inputs(B, T, d_in, d_out, dtype)
+    if r < 0:
+        raise ValueError("invalid arguments")
+    return bool(r)
 
 
 def philox_raw(n_counters: int, seed: int, first_counter: int, device="cuda") -> torch.Tensor:

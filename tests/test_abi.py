@@ -186,6 +186,37 @@ def test_layer_descriptor_layout_and_argument_checks(lib):
     assert cg(descs(grad=[fake(5), None]), 2, B, fake(13), dt, 0, 0.0, 0, None, 0, None) == dpclip.DP_ERR_INVALID_ARG
 
 
+def test_noise_layout_gives_every_gradient_its_own_stretch():
+    """Host logic only: the default positions in the noise stream (weights back to back, then the biases) are pairwise
+    disjoint, also next to weight offsets given by the caller; overlapping offsets are refused.  Independent noise
+    per coordinate is what the Gaussian mechanism needs (Algorithm 1, the line that adds the noise)."""
+    sizes = [(5, 3), (7, 2), (4, 4), (1, 9)]
+    has_bias = [True, False, True, True]
+
+    def stretches(w, b):
+        return sorted([(o, di * do) for o, (di, do) in zip(w, sizes)] + [(o, do) for o, (_, do), h in zip(b, sizes, has_bias) if h])
+
+    def disjoint(st):
+        return all(a[0] + a[1] <= c[0] for a, c in zip(st, st[1:]))
+
+    w, b = dpclip.noise_layout(sizes, has_bias)
+    assert w == [0, 15, 29, 45] and b == [54, 0, 57, 61]
+    assert disjoint(stretches(w, b))
+    # weights placed by the caller (a flat parameter vector with gaps): the default biases start behind the last one
+    w, b = dpclip.noise_layout(sizes, has_bias, noise_offsets=[100, 0, 40, 60])
+    assert w == [100, 0, 40, 60] and b[0] == 115 and disjoint(stretches(w, b))
+    # each layer's weights followed by its own bias, as a model's flat gradient lays them out
+    w, b = dpclip.noise_layout(sizes, has_bias, noise_offsets=[0, 18, 32, 52], bias_noise_offsets=[15, 0, 48, 61])
+    assert disjoint(stretches(w, b))
+    # what the earlier default did (every bias at 0) shares draws with the first weight gradient: refused
+    with pytest.raises(ValueError):
+        dpclip.noise_layout(sizes, has_bias, bias_noise_offsets=[0, 0, 0, 0])
+    with pytest.raises(ValueError):
+        dpclip.noise_layout(sizes, [False] * 4, noise_offsets=[0, 14, 29, 45])      # weights overlapping by one element
+    # layers without parameters take no room
+    assert dpclip.noise_layout([(0, 3), (2, 2)], [False, False]) == ([0, 0], [0, 0])
+
+
 def test_missing_library_raises(monkeypatch):
     monkeypatch.setattr(dpclip, "_lib", None)
     monkeypatch.setattr(dpclip, "LIB_PATH", "/nonexistent/libdpclip.so")

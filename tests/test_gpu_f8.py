@@ -105,6 +105,34 @@ def test_f8_clipped_grad(dp, dtype, shape):
     np.testing.assert_array_equal(h.cpu().numpy(), g.cpu().numpy() + np.float32(2.0))
 
 
+@pytest.mark.parametrize("shape", [(9, 64, 512, 256), (9, 128, 256, 256), (7, 168, 240, 256), (9, 40, 136, 128)])
+def test_f8_zero_and_tiny_clip_factors(dp, shape):
+    """Zero factors (masked examples, overflowed norms) and factors far below their neighbours at the first, a middle
+    and the last example of a K slice: finite, and the weighted sum of the oracle."""
+    B, T, d_in, d_out = shape
+    (A, G), (Ad, Gd) = draw(15, B, T, d_in, d_out, "f8")
+    rng = np.random.default_rng(B + T)
+    base = (0.1 + 0.9 * rng.random(B)).astype(np.float32)
+    pats = []
+    for val in (0.0, 1e-30, 1e-45):
+        a = base.copy(); a[[0, B // 2, B - 1]] = val; pats.append(a)
+        b = base.copy(); b[1:3] = val; b[B - 3:B - 1] = val; pats.append(b)
+    pats.append(np.zeros(B, dtype=np.float32))
+    z = base.copy(); z[::2] = 0.0; pats.append(z)
+    for clip in pats:
+        ref = orc.clipped_grad(A, G, clip.astype(np.float64))
+        scale = orc.clipped_grad(np.abs(A), np.abs(G), clip.astype(np.float64))
+        got = dp.clipped_grad(Ad, Gd, torch.from_numpy(clip).cuda()).cpu().numpy()
+        assert np.all(np.isfinite(got)), clip
+        # 8-bit shapes outside their own kernels run widened through the fp16 kernels, which may re-round c * a
+        # (the 64-deep 8-bit matrix instruction adds its products more coarsely than the 16-bit one: 2e-5 of the sum
+        # of the terms' magnitudes has been seen per element, against 1e-6 for 16-bit inputs)
+        unit = 2.0 ** -11 * 1.01 if dp.clipped_grad_rounds_inputs(B, T, d_in, d_out, dp.DP_F8_E4M3_E5M2) else 6e-5
+        assert np.all(np.abs(got - ref) <= unit * scale + 1e-300), (clip, float(np.max(np.abs(got - ref) / (scale + 1e-300))))
+        if not clip.any():
+            assert not got.any()
+
+
 def test_f8_all_ones_clip_is_the_plain_sum(dp):
     """c_i = 1: the clipped sum is A^T G over all B T rows, whatever the example boundaries."""
     (A, G), (Ad, Gd) = draw(14, 6, 128, 256, 256, "f8")
@@ -197,7 +225,7 @@ def test_f8_other_shapes_run_widened(dp, dtype, shape):
     rng = np.random.default_rng(6)
     clip = (0.1 + 0.9 * rng.random(B)).astype(np.float32)
     g = dp.clipped_grad(Ad, Gd, torch.from_numpy(clip).cuda()).cpu().numpy()
-    # the fp16 kernels for these shapes re-round c_i * a to fp16: 2^-12 relative per element
+    # the fp16 kernels for these shapes re-round c_i * a to fp16: at most 2^-11 relative per element
     assert fro_err(g, orc.clipped_grad(A, G, clip.astype(np.float64))) <= 2e-3
     # bit for bit what the fp16 entry points give on the widened values
     A16 = torch.from_numpy(A.astype(np.float16)).cuda()

@@ -24,6 +24,17 @@ FRO_TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-3}
 # what the kernels are expected to reach in practice (fp32 accumulation of exact bf16 products);
 # looser than this but inside the stated tolerance would point at a real defect
 SQ_TIGHT = {"f32": 1e-5, "bf16": 2e-4, "f16": 2e-4}
+# The clipped sum, given the clip factors the GPU itself used.  Kernels that apply the factors in float32 differ from
+# exact arithmetic on the stored inputs only by float32 rounding (products of 16-bit values are exact in float32):
+# 1e-4 relative Frobenius error for every type, and per element 5e-6 of the sum of the magnitudes of the element's
+# terms, sum_i |c_i| sum_t |a||g| (one 32-row stage dropped from a contraction of 32768 rows is about 2e-4 of it,
+# one wrong column of 2304 is 2e-2 in Frobenius norm).  Kernels that fold the factor into re-rounded 16-bit rows of A
+# carry the format's rounding unit per term: 2^-8 (bf16, 8 significant bits) / 2^-11 (fp16, 11 bits) of the same sum of magnitudes per element, in
+# the worst case, and a Frobenius error well below it.
+FRO_TIGHT = 1e-4
+ELEM_TIGHT = 5e-6
+UNIT = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11}
+DTYPE_CODE = {"f32": 0, "bf16": 1, "f16": 2}
 
 
 @pytest.fixture(scope="module")
@@ -48,7 +59,27 @@ def fro_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-def run_gpu_pipeline(dp, layers_np, C, path="auto", noise_std=0.0, seed=0):
+def check_clipped_sum(dp, A, G, c_gpu, got, dtype, where=""):
+    """got = dp.clipped_grad(A, G, c_gpu) without noise, against the oracle's clipped sum for the same factors, at the
+    accuracy the kernel that ran should reach (see FRO_TIGHT above)."""
+    c64 = np.asarray(c_gpu, dtype=np.float64)
+    ref = orc.clipped_grad(A, G, c64)
+    scale = orc.clipped_grad(np.abs(orc.widen(A)), np.abs(orc.widen(G)), np.abs(c64))     # sum of the terms' magnitudes
+    A3 = A if A.ndim == 3 else A[:, None, :]
+    B, T, d_in = A3.shape
+    d_out = G.shape[-1]
+    rounds = dtype != "f32" and dp.clipped_grad_rounds_inputs(B, T, d_in, d_out, DTYPE_CODE[dtype])
+    err = np.abs(np.asarray(got, dtype=np.float64) - ref)
+    tiny = 1e-30 * max(float(scale.max()), 1e-300)
+    if rounds:
+        assert np.all(err <= UNIT[dtype] * 1.01 * scale + tiny), (where, "element", float(np.max(err / (scale + tiny))))
+        assert fro_err(got, ref) <= UNIT[dtype], (where, "fro", fro_err(got, ref))
+    else:
+        assert np.all(err <= ELEM_TIGHT * scale + tiny), (where, "element", float(np.max(err / (scale + tiny))))
+        assert fro_err(got, ref) <= FRO_TIGHT, (where, "fro", fro_err(got, ref))
+
+
+def run_gpu_pipeline(dp, layers_np, C, path="auto", noise_std=0.0, seed=0, clean=None):
     dev = [(to_dev(A), to_dev(G)) for A, G in layers_np]
     s = None
     for li, (A, G) in enumerate(dev):
@@ -58,6 +89,8 @@ def run_gpu_pipeline(dp, layers_np, C, path="auto", noise_std=0.0, seed=0):
     off = 0
     for A, G in dev:
         g = dp.clipped_grad(A, G, c)
+        if clean is not None:
+            clean.append(g.cpu().numpy())           # before the noise
         if noise_std > 0:
             dp.add_noise(g, noise_std, seed, off)
         off += g.numel()
@@ -72,7 +105,10 @@ def check_pipeline(dp, name, B=None, straddle=False, path="auto", with_noise=Fal
         w = dataclasses.replace(w, dtype=dtype or w.dtype, C=w.C * g_scale)
     std = w.noise_std if with_noise else 0.0
     s_ref, c_ref, g_ref = orc.run_pipeline(layers, w.C, std, w.noise_seed)
-    s, c, g = run_gpu_pipeline(dp, layers, w.C, path=path, noise_std=std, seed=w.noise_seed)
+    clean = []
+    s, c, g = run_gpu_pipeline(dp, layers, w.C, path=path, noise_std=std, seed=w.noise_seed, clean=clean)
+    for li, ((A, G), gc) in enumerate(zip(layers, clean)):
+        check_clipped_sum(dp, A, G, c, gc, w.dtype, (name, li))
     assert rel_err(s, s_ref) <= SQ_TOL[w.dtype], (name, "sqnorm", rel_err(s, s_ref))
     assert rel_err(s, s_ref) <= SQ_TIGHT[w.dtype], (name, "sqnorm (expected accuracy)", rel_err(s, s_ref))
     assert rel_err(c, c_ref) <= SQ_TOL[w.dtype], (name, "clip", rel_err(c, c_ref))
@@ -621,6 +657,7 @@ def test_ragged_shapes(dp, dtype, B, T, d_in, d_out):
     assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL[dtype]
     g = dp.clipped_grad(Ad, Gd, c)
     assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL[dtype]
+    check_clipped_sum(dp, A, G, c.cpu().numpy(), g.cpu().numpy(), dtype, (B, T, d_in, d_out))
 
 
 def _drawn_shapes(n, seed):
@@ -655,6 +692,7 @@ def test_drawn_shapes(dp, B, T, d_in, d_out, dtype):
     assert rel_err(c.cpu().numpy(), c_ref) <= SQ_TOL[dtype]
     g = dp.clipped_grad(Ad, Gd, c)
     assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL[dtype]
+    check_clipped_sum(dp, A, G, c.cpu().numpy(), g.cpu().numpy(), dtype, (B, T, d_in, d_out))
     g2 = torch.full_like(g, 0.5)
     dp.clipped_grad(Ad, Gd, c, g2, accumulate=True)
     assert fro_err(g2.cpu().numpy() - 0.5, g_ref) <= FRO_TOL[dtype] + 1e-6 * 0.5 * np.sqrt(g_ref.size) / max(np.linalg.norm(g_ref), 1e-30)
@@ -678,6 +716,64 @@ def test_large_shapes(dp, B, T, d_in, d_out):
     c = dp.clip_factors(s, C)
     g = dp.clipped_grad(Ad, Gd, c)
     assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL["bf16"]
+    check_clipped_sum(dp, A, G, c.cpu().numpy(), g.cpu().numpy(), "bf16", (B, T, d_in, d_out))
+
+
+def _factor_patterns(B, rng):
+    """Clip arrays with zeros and very small factors at the first, a middle and the last example of a K slice, runs
+    of them, and nothing but zeros; the other factors lie in [0.1, 1]."""
+    base = (0.1 + 0.9 * rng.random(B)).astype(np.float32)
+    pats = {}
+    for name, val in (("zero", 0.0), ("1e-30", 1e-30), ("subnormal", 1e-45)):
+        a = base.copy(); a[[0, B // 2, B - 1]] = val; pats[name + " first/middle/last"] = a
+        b = base.copy(); b[1:3] = val; b[B - 3:B - 1] = val; pats[name + " runs"] = b
+    pats["all zero"] = np.zeros(B, dtype=np.float32)
+    z = base.copy(); z[::2] = 0.0; pats["every other zero"] = z
+    m = base.copy(); m[B // 3] = 0.0; m[B // 3 + 1] = 1e-30; m[B // 3 + 2] = 1e-45; pats["mixed"] = m
+    return pats
+
+
+# zero factors (masked examples; the factor of an overflowed norm) and factors far below their neighbours: every
+# clipped-sum kernel must give the weighted sum, whichever way it applies the factors
+ZERO_SHAPES = [
+    (9, 64, 512, 256),      # copy pipeline, 256 x 256 tiles, three examples per K slice
+    (12, 32, 576, 128),     # copy pipeline, 192 x 128 tiles
+    (9, 64, 256, 128),      # copy pipeline, 128 x 128 tiles
+    (7, 130, 768, 384),     # copy pipeline, ragged T, K slices that cut through examples
+    (9, 40, 456, 248),      # 256 x 256 tiles, rows of A scaled and re-rounded
+    (9, 40, 136, 72),       # example-by-example kernel
+    (9, 5, 33, 65),         # row-scaling kernel for any shape
+    (9, 1, 256, 64),        # dense layer
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("B,T,d_in,d_out", ZERO_SHAPES)
+def test_zero_and_tiny_clip_factors(dp, dtype, B, T, d_in, d_out):
+    A, G = wl.random_layer(99 + T + d_in, B, T, d_in, d_out, dtype)
+    Ad, Gd = to_dev(A), to_dev(G)
+    for name, clip in _factor_patterns(B, np.random.default_rng(B + T)).items():
+        c = torch.from_numpy(clip).cuda()
+        g = dp.clipped_grad(Ad, Gd, c)
+        got = g.cpu().numpy()
+        assert np.all(np.isfinite(got)), (name, "not finite")
+        check_clipped_sum(dp, A, G, clip, got, dtype, (name, B, T, d_in, d_out))
+        if not clip.any():
+            assert not got.any(), (name, "all-zero factors must give an all-zero sum")
+        h = torch.full_like(g, 0.25)
+        dp.clipped_grad(Ad, Gd, c, h, accumulate=True)
+        np.testing.assert_allclose(h.cpu().numpy(), got + np.float32(0.25), rtol=0, atol=1e-6 * (1 + np.abs(got).max()))
+
+
+def test_zero_clip_factors_conv_from_image(dp):
+    spec, X, G = wl.generate_conv_image(B=18, H=8, W=8, C=64, d_out=128)        # four examples per K slice
+    Xd, Gd = to_dev(X), to_dev(G)
+    A = orc.conv_unfold(X, spec["KH"], spec["KW"], spec["pad"])
+    for name, clip in _factor_patterns(18, np.random.default_rng(3)).items():
+        g = dp.conv_clipped_grad(Xd, Gd, torch.from_numpy(clip).cuda(), spec["KH"], spec["KW"], spec["pad"])
+        got = g.cpu().numpy()
+        assert np.all(np.isfinite(got)), (name, "not finite")
+        check_clipped_sum(dp, A, G, clip, got, "bf16", ("conv", name))
 
 
 def test_accumulate_flags(dp):

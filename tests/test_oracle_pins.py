@@ -296,12 +296,44 @@ def test_multi_layer_global_clip():
     np.testing.assert_allclose(grads[0], orc.clipped_grad_by_clip_function(L1[0], L1[1], C, other), rtol=1e-12)
 
 
+def test_pipeline_noise_is_one_stream_over_the_flat_parameter_gradient():
+    """Algorithm 1 adds one draw of N(0, sigma^2 I) to the whole parameter gradient.  run_pipeline hands the layers
+    consecutive stretches of the stream: what it adds, layer after layer, must be the stream of standard_normals
+    (pinned above against Box-Muller on raw words) over the concatenated gradient from position 0, scaled by sigma,
+    and the clean part must be the noise-free pipeline.  A wrong running offset (reset per layer, counted in rows
+    instead of elements, advanced before instead of after the layer) fails one of the three checks."""
+    layers = [(_rand(31, 4, 1, 6), _rand(32, 4, 1, 5)), (_rand(33, 4, 3, 2), _rand(34, 4, 3, 7)), (_rand(35, 4, 2, 3), _rand(36, 4, 2, 3))]
+    C, std, seed = 0.8, 0.37, 123456789
+    s0, c0, clean = orc.run_pipeline(layers, C)
+    s1, c1, noisy = orc.run_pipeline(layers, C, std, seed)
+    np.testing.assert_array_equal(s0, s1)
+    np.testing.assert_array_equal(c0, c1)
+    sizes = [g.size for g in clean]
+    assert sizes == [30, 14, 9]
+    added = np.concatenate([(n - g).ravel() for n, g in zip(noisy, clean)])
+    z = orc.standard_normals(sum(sizes), seed, 0)
+    np.testing.assert_allclose(added, std * z, rtol=0, atol=1e-12)
+    # layer l starts where layer l - 1 ended: its first value is z[sum of the earlier sizes], not z[0]
+    starts = np.concatenate([[0], np.cumsum(sizes)])
+    for l in (1, 2):
+        first = (noisy[l] - clean[l]).ravel()[0]
+        assert abs(first - std * z[starts[l]]) <= 1e-12 and abs(first - std * z[0]) > 1e-6
+    # no draw is used twice, and a layer alone at its own offset reproduces its part
+    assert len(np.unique(np.round(added / std, 9))) == added.size
+    alone = orc.add_noise(clean[2], std, seed, int(starts[2]))
+    np.testing.assert_allclose(alone, noisy[2], rtol=0, atol=1e-12)
+    # std = 0 adds nothing
+    _, _, same = orc.run_pipeline(layers, C, 0.0, seed)
+    for a, b in zip(same, clean):
+        np.testing.assert_array_equal(a, b)
+
+
 # ---------------------------------------------------------------- storage widening
 def test_bf16_widening_exact():
     x = np.array([1.0, -2.5, 0.15625, 3.0e-5, 1e20], dtype=np.float32)
     bits = wl.f32_to_bf16_bits(x)
     back = orc.widen(bits)
-    # bf16 keeps 8 significant bits: relative error <= 2^-9, and exactly representable values survive
+    # bf16 keeps 8 significant bits: relative error <= 2^-8 (asserted below), and exactly representable values survive
     assert back[0] == 1.0 and back[1] == -2.5 and back[2] == 0.15625
     assert np.all(np.abs(back - x.astype(np.float64)) <= np.abs(x) * 2.0 ** -8)
     np.testing.assert_array_equal(back, wl.bf16_bits_to_f32(bits).astype(np.float64))
