@@ -113,6 +113,26 @@ dp_status dp_layer_sqnorm(const void* A, const void* G,
                           float* sqnorm, void* workspace, size_t workspace_bytes,
                           void* hip_stream);
 
+/* dp_layer_sqnorm for callers that cannot allocate or hand over device
+ * memory of their own for scratch: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results
+ * (bit for bit) as dp_layer_sqnorm, without `workspace`: the partial sums go
+ * to a fixed array of DP_STATIC_SCRATCH_BYTES bytes inside the library's device
+ * image (one copy per GPU, held until the process ends).  The call allocates
+ * nothing and frees nothing; on the first call on a device it looks up that
+ * device's copy of the array (no allocation either; make that first call outside
+ * a graph capture).  A problem whose dp_workspace_bytes(DP_OP_SQNORM, ...)
+ * exceeds DP_STATIC_SCRATCH_BYTES gives DP_ERR_WORKSPACE and launches nothing.
+ * Every call on a GPU uses the same array: calls that may overlap on one GPU
+ * (different streams, or a captured graph replayed next to an eager call) race
+ * and must be ordered by the caller.  Nothing in the array has to start at
+ * zero: every partial sum is written before it is read. */
+#define DP_STATIC_SCRATCH_BYTES (4u << 20)
+dp_status dp_layer_sqnorm_static(const void* A, const void* G,
+                                 int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                 dp_dtype dtype, dp_path path, int accumulate,
+                                 float* sqnorm, void* hip_stream);
+
 /* The same for several layers of one model in one call (the whole-model norm
  * is the sum over the layers; Section 5, paragraph before 5.1):
  *     sqnorm[i] = (accumulate ? sqnorm[i] : 0) + sum_l ||A_l,i^T G_l,i||_F^2.

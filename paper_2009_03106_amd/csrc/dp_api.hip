@@ -3,11 +3,35 @@
 // synchronisation, no host reads of device memory.
 #include "../../include/dpclip.h"
 #include "dp_internal.h"
+#include <mutex>
 #include <vector>
 
 using namespace dpk;
 
+// Scratch of dp_layer_sqnorm_static: lives in the device image, one copy per GPU.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels and launchers get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[DP_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};              // device address of `scratch` on each GPU, looked up once
+
+// the current device's copy of `scratch`
+dp_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return DP_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return DP_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DP_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DP_OK;
+}
 
 constexpr int64_t kMaxRows = (int64_t(1) << 31) - 1;   // B*T
 constexpr int64_t kMaxDim = int64_t(1) << 24;          // d_in, d_out
@@ -162,6 +186,23 @@ dp_status dp_layer_sqnorm(const void* A, const void* G, int64_t B, int64_t T, in
                           dp_dtype dtype, dp_path path, int accumulate, float* sqnorm,
                           void* workspace, size_t workspace_bytes, void* hip_stream) {
     return layer_sqnorm_clip(A, G, B, T, d_in, d_out, dtype, path, accumulate, sqnorm, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+dp_status dp_layer_sqnorm_static(const void* A, const void* G, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                 dp_dtype dtype, dp_path path, int accumulate, float* sqnorm, void* hip_stream) {
+    const dp_status st = check_dims(B, T, d_in, d_out);
+    if (st != DP_OK) return st;
+    if (!valid_dtype(dtype) || !valid_path(path)) return DP_ERR_INVALID_ARG;
+    // what dp_layer_sqnorm would ask of its workspace argument (0 for empty and dense problems)
+    const size_t need = dp_workspace_bytes(DP_OP_SQNORM, B, T, d_in, d_out, dtype, path);
+    if (need > (size_t)DP_STATIC_SCRATCH_BYTES) return DP_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (need > 0) {
+        const dp_status s2 = static_scratch(&ws);
+        if (s2 != DP_OK) return s2;
+    }
+    return layer_sqnorm_clip(A, G, B, T, d_in, d_out, dtype, path, accumulate, sqnorm, ws, need > 0 ? (size_t)DP_STATIC_SCRATCH_BYTES : 0,
+                             hip_stream, nullptr);
 }
 
 }  // extern "C"

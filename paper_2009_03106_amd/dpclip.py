@@ -22,7 +22,7 @@ DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_DIRECT = 0, 1, 2
 DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
-EXPORTS = ("dp_layer_sqnorm", "dp_layers_sqnorm", "dp_layers_sqnorm_clip", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
+EXPORTS = ("dp_layer_sqnorm", "dp_layer_sqnorm_static", "dp_layers_sqnorm", "dp_layers_sqnorm_clip", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
            "dp_layers_clipped_grad_noise", "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw",
            "dp_clipped_grad_rounds_inputs")
@@ -57,6 +57,8 @@ def load_library() -> ctypes.CDLL:
                                  ctypes.c_float, ctypes.c_int)
     lib.dp_layer_sqnorm.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp, sz, vp]
     lib.dp_layer_sqnorm.restype = ci
+    lib.dp_layer_sqnorm_static.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp]
+    lib.dp_layer_sqnorm_static.restype = ci
     lib.dp_layers_sqnorm.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci, ci, vp, vp, sz, vp]
     lib.dp_layers_sqnorm.restype = ci
     lib.dp_layers_sqnorm_clip.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci, ci, vp, f32, vp, vp, sz, vp]
@@ -234,6 +236,23 @@ def check_noise_ranges(ranges) -> None:
         if off < end:
             raise ValueError("noise offsets overlap: every weight and bias gradient needs its own stretch of the stream")
         end = off + n
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def layer_sqnorm_static(A: torch.Tensor, G: torch.Tensor, sqnorm: torch.Tensor, *, path: str = "auto",
+                        accumulate: bool = False, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """layer_sqnorm through dp_layer_sqnorm_static: no workspace, nothing allocated (sqnorm is the caller's); problems
+    needing more than STATIC_SCRATCH_BYTES of scratch raise DP_ERR_WORKSPACE."""
+    lib = load_library()
+    if not (A.is_contiguous() and G.is_contiguous()):
+        raise ValueError("A and G must be contiguous")
+    A, G, B, T, d_in, d_out = _shape3(A, G)
+    st = lib.dp_layer_sqnorm_static(_ptr(A), _ptr(G), B, T, d_in, d_out, _dtype_code(A, G), _PATHS[path],
+                                    int(bool(accumulate)), _f32(sqnorm, (B,), "sqnorm"), _stream_ptr(stream))
+    _check(st, "dp_layer_sqnorm_static")
+    return sqnorm
 
 
 def noise_layout(sizes, has_bias, noise_offsets=None, bias_noise_offsets=None):
