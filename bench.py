@@ -187,22 +187,78 @@ def time_steps_cold(pipe, torch, steps, flush):
     return phases / steps
 
 
-def cpu_baseline(name, sample_B):
+def measured_peaks(torch, dp):
+    """What this part sustains, from the library's own probe kernels (include/dpclip_probes.h), each timed with HIP
+    events over a launch of about 10 ms after the same spin-up as the steps: the matrix units with operands in
+    registers (constant operands reach the published peak; pseudo-random ones, which is what streaming data looks
+    like to the multipliers, make the part lower its clock), a plain read of 1 GiB (four times the last-level
+    cache, so every pass comes from HBM), and the LDS reads of the Gram kernel (ds_read_b128) and of the
+    clipped-sum kernels (ds_read_b64_tr_b16) with 8 waves per compute unit."""
+    sink = torch.zeros(dp.PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+    def timed(launch, reps=3):
+        t_spin = time.perf_counter()
+        while time.perf_counter() - t_spin < SPINUP_S:
+            launch()
+            torch.cuda.synchronize()
+        best, work = None, 0.0
+        for _ in range(reps):
+            ev[0].record()
+            work = launch()
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1])
+            best = ms if best is None else min(best, ms)
+        return work / (best * 1e-3), best
+
+    out = {}
+    for name, code, iters in (("bf16", dp.DP_BF16, 12000), ("f16", dp.DP_F16, 12000), ("f8_e4m3_e5m2", dp.DP_F8_E4M3_E5M2, 6000)):
+        for rnd in (0, 1):
+            rate, ms = timed(lambda: dp.probe_mfma(code, rnd, iters, sink))
+            out[f"mfma_{name}_{'random' if rnd else 'constant'}_operands_tflops"] = rate / 1e12
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    rate, ms = timed(lambda: dp.probe_read(src, sink), reps=5)
+    out["hbm_read_gbs"] = rate / 1e9
+    small = src[: (96 << 20) // 4]
+    rate, ms = timed(lambda: dp.probe_read(small, sink), reps=5)
+    out["last_level_cache_read_gbs"] = rate / 1e9
+    del src, small
+    for name, kind in (("lds_read_b128", 0), ("lds_read_b64_tr_b16", 1)):
+        rate, ms = timed(lambda: dp.probe_lds_read(kind, 20000, sink))
+        out[f"{name}_gb_per_s_per_cu"] = rate / 1e9 / 256
+    out["note"] = "probe kernels of libdpclip.so (dp_probe_*), best of 3-5 launches of about 10 ms each, HIP events"
+    return out
+
+
+def cpu_baseline(name, sample_B, threads=None):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     from oracle import dp_oracle as orc
     from paper_2009_03106_amd import workloads as wl
+    import contextlib
+    limit = contextlib.nullcontext()
     try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        from threadpoolctl import threadpool_info, threadpool_limits
+        if threads is not None:
+            limit = threadpool_limits(limits=int(threads))
+        else:
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
-        threads = 1
+        threads = 1 if threads is None else threads
     w, layers = wl.generate(name, B=sample_B)
-    t0 = time.perf_counter()
-    orc.run_pipeline(layers, w.C, w.noise_std, w.noise_seed)
-    dt = time.perf_counter() - t0
-    return {"value": sample_B / dt, "unit": "examples/s", "cores": int(threads), "kind": "oracle",
+    reps = 0
+    with limit:
+        t0 = time.perf_counter()
+        while True:                                   # tiny configurations: repeat until the clock can see them
+            orc.run_pipeline(layers, w.C, w.noise_std, w.noise_seed)
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt > 0.2 or reps >= 200:
+                break
+    return {"value": sample_B * reps / dt, "unit": "examples/s", "cores": int(threads), "host_cpus": os.cpu_count(),
+            "kind": "oracle",
             "sample": f"{name} configuration with B={sample_B} of {w.B} examples, all layers, float64, "
-                      f"{dt:.2f} s wall"}
+                      f"{reps} pass(es) in {dt:.2f} s wall, {int(threads)} BLAS thread(s)"}
 
 
 def main():
@@ -217,6 +273,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the configuration's batch size (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the probe kernels that measure what the part sustains")
+    ap.add_argument("--peaks", action="store_true", help="only measure the peaks (probe kernels) and print them")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic) so that a rocprofv3 "
                          "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
@@ -233,6 +291,10 @@ def main():
     torch.cuda.set_device(0)
     dp.load_library()
 
+    if args.peaks:
+        print(json.dumps({"measured_peaks": measured_peaks(torch, dp)}))
+        return
+
     if args.calib_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -246,6 +308,18 @@ def main():
     pipe = Pipeline(w, layers, torch, dp, args.path)
     del layers
     B = pipe.B
+    # the same K steps after W warm-up steps straight from an idle device, without the spin-up that time_steps puts
+    # in front (the power management's start-up transient is inside this figure; it is reported, not `value`)
+    torch.cuda.synchronize()
+    time.sleep(0.5)
+    for _ in range(args.warmup):
+        pipe.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        pipe.step()
+    torch.cuda.synchronize()
+    ms_from_idle = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
     ms, phases = time_steps(pipe, torch, args.steps, args.warmup)
     work = algorithmic_work(w, B)
 
@@ -347,6 +421,48 @@ def main():
         bias_out["layernorm_shape"] = [int(x) for x in A0.shape]
         del H0
 
+    if not args.no_others and args.batch is None and not w.dtype.startswith("f8"):
+        # the row kernels at sizes where their launches no longer count: one layer's G of the widest and of the
+        # narrowest output (and a G / Hbar pair for the LayerNorm rows) at the configuration's batch and at four times
+        # it, cold (a 512 MB buffer is read in between), values drawn on the device (the timing does not depend on them)
+        tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
+        fl = torch.zeros(1 << 27, dtype=torch.float32, device="cuda")
+        Tm = max(spec.T for spec in w.layers)
+        sweep = {}
+        for d in sorted({max(spec.d_out for spec in w.layers), min(spec.d_out for spec in w.layers)}):
+            for mult in (1, 4):
+                Bs = B * mult
+                Gs = torch.randn((Bs, Tm, d), device="cuda", dtype=torch.float32).to(tdt)
+                Hs = torch.randn((Bs, Tm, d), device="cuda", dtype=torch.float32).to(tdt)
+                ss = torch.zeros(Bs, device="cuda")
+                us = torch.empty((Bs, d), device="cuda")
+                tt = np.zeros(2)
+                for rep in range(2 + 5):
+                    fl.max()
+                    evb[0].record()
+                    dp.bias_sqnorm(Gs, ss, us)
+                    evb[1].record()
+                    fl.max()
+                    torch.cuda.synchronize()
+                    t_b = evb[0].elapsed_time(evb[1])
+                    evb[0].record()
+                    dp.layernorm_sqnorm(Gs, Hs, ss)
+                    evb[1].record()
+                    torch.cuda.synchronize()
+                    if rep >= 2:
+                        tt += [t_b, evb[0].elapsed_time(evb[1])]
+                tt /= 5
+                nb = Gs.numel() * Gs.element_size()
+                sweep[f"B={Bs},T={Tm},d={d}"] = {
+                    "bias_sqnorm_ms": tt[0], "bias_sqnorm_gbs": (nb + 4 * Bs * d) / (tt[0] * 1e-3) / 1e9,
+                    "bias_sqnorm_hbm_frac": (nb + 4 * Bs * d) / (tt[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                    "layernorm_sqnorm_ms": tt[1], "layernorm_sqnorm_gbs": (2 * nb + 8 * Bs * d) / (tt[1] * 1e-3) / 1e9,
+                    "layernorm_sqnorm_hbm_frac": (2 * nb + 8 * Bs * d) / (tt[1] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                    "input_mb": nb / 1e6}
+                del Gs, Hs, ss, us
+        bias_out["sweep_cold"] = sweep
+        del fl
+
     others = {}
     if not args.no_others and args.batch is None:
         flush = torch.zeros(1 << 27, dtype=torch.float32, device="cuda")
@@ -392,6 +508,28 @@ def main():
                                     "sqnorm_gbs": wk2["norm_bytes"] / (pc[0] * 1e-3) / 1e9,
                                     "clipped_grad_gbs": wk2["gemm_bytes"] / (pc[2] * 1e-3) / 1e9}
             del p2, l2
+            if name in ("dense", "mlp", "rnn"):
+                # the same per-example shapes at many times the batch (up to 200 - 600 MB of inputs), cold: at the
+                # configuration's own size the step is a few launches of a few microseconds, here the kernels have
+                # bytes to move
+                sweep = {}
+                for mult in {"dense": (256, 4096, 16384), "mlp": (16, 64, 256), "rnn": (16, 64)}[name]:
+                    ws_, ls_ = wl.generate(name, B=w2.B * mult)
+                    ps_ = Pipeline(ws_, ls_, torch, dp, "auto")
+                    del ls_
+                    for _ in range(2):
+                        ps_.step()
+                    pcs = time_steps_cold(ps_, torch, 6, flush)
+                    wks = algorithmic_work(ws_, ps_.B)
+                    sweep[f"B={ps_.B}"] = {
+                        "sqnorm_ms": pcs[0], "clipped_grad_ms": pcs[2],
+                        "sqnorm_gbs": wks["norm_bytes"] / (pcs[0] * 1e-3) / 1e9,
+                        "sqnorm_hbm_frac": wks["norm_bytes"] / (pcs[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                        "clipped_grad_gbs": wks["gemm_bytes"] / (pcs[2] * 1e-3) / 1e9,
+                        "clipped_grad_tflops": wks["gemm_flops"] / (pcs[2] * 1e-3) / 1e12,
+                        "input_mb": wks["norm_bytes"] / 1e6}
+                    del ps_
+                others[name]["sweep_cold"] = sweep
         # the transformer configuration with fp16 inputs (G and C carry a loss scale of 1024): the same kernels with
         # the fp16 matrix instruction
         w16, l16 = wl.generate("transformer", dtype="f16", g_scale=1024.0)
@@ -491,8 +629,29 @@ def main():
                    "path": args.path, "parallelism": "single GPU", "untimed_spinup_s": SPINUP_S},
         "roofline": roof, "phases": phases_out, "bias_terms": bias_out, "other_workloads": others,
     }
+    out["ms_per_step_from_idle"] = ms_from_idle
+    if not args.no_peaks:
+        peaks = measured_peaks(torch, dp)
+        out["measured_peaks"] = peaks
+        if roof["bound"] == "mfma":
+            key = {"bf16": "bf16", "f16": "f16"}.get(w.dtype, "f8_e4m3_e5m2" if w.dtype.startswith("f8") else None)
+            if key is not None:
+                roof["peak_measured"] = peaks[f"mfma_{key}_random_operands_tflops"]
+                roof["frac_of_measured"] = roof["achieved"] / roof["peak_measured"]
+        else:
+            roof["peak_measured"] = peaks["hbm_read_gbs"]
+            roof["frac_of_measured"] = roof["achieved"] / roof["peak_measured"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w.name, min(w.B, B))
+        if not args.no_others and args.batch is None:
+            # the oracle on every other configuration (all host threads; one thread too for the three small ones)
+            for name in wl.WORKLOADS:
+                if name == w.name or name not in others:
+                    continue
+                sample = min(wl.WORKLOADS[name].B, 16) if name == "conv" else wl.WORKLOADS[name].B
+                others[name]["cpu_baseline"] = cpu_baseline(name, sample)
+                if name in ("dense", "mlp", "rnn"):
+                    others[name]["cpu_baseline_1_thread"] = cpu_baseline(name, sample, threads=1)
     print(json.dumps(out))
 
 

@@ -412,8 +412,7 @@ dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_
     // 8-bit types: Hbar is an activation (stored like A), G a backpropagated gradient
     const int gdt = dtype == DP_F8_E4M3 ? 3 : dtype == DP_F8_E5M2 ? 4 : dtype == DP_F8_E4M3_E5M2 ? 5 : (int)dtype;
     hipError_t e = launch_bias_rows(G, Hbar, (int)B, (int)T, (int)d, gdt, gamma_rows, beta_rows, stream);
-    if (e == hipSuccess) e = launch_rows_sqnorm(gamma_rows, (int)B, (int)d, accumulate != 0, sqnorm, stream);
-    if (e == hipSuccess) e = launch_rows_sqnorm(beta_rows, (int)B, (int)d, true, sqnorm, stream);
+    if (e == hipSuccess) e = launch_rows_sqnorm(gamma_rows, (int)B, (int)d, accumulate != 0, sqnorm, stream, beta_rows);
     return e == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 

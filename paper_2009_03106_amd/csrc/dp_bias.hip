@@ -146,14 +146,40 @@ __global__ __launch_bounds__(kThreads) void k_bias_rows_scalar(const void* __res
     if (PROD) u2[(size_t)ex * D + q] = acc2;
 }
 
-// s_i (+)= sum_q u[i, q]^2: one wave per example, lane l adds columns l, l + 64, ..., then a shuffle tree.
-__global__ __launch_bounds__(kWave) void k_rows_sqnorm(const float* __restrict__ u, int D, int accumulate, float* __restrict__ sqnorm) {
-    const int ex = blockIdx.x, lane = threadIdx.x;
-    const float* p = u + (size_t)ex * D;
+// s_i (+)= sum_q u[i, q]^2 (+ sum_q u2[i, q]^2 when u2 is given: LayerNorm's scale and shift rows in one launch):
+// one wave per example, four per workgroup; lane l adds the 16-byte pieces l, l + 64, ... of the row (four loads in
+// flight), then a shuffle tree.  The order of the additions is fixed.
+__device__ __forceinline__ float row_sq(const float* __restrict__ p, int D, int lane) {
     float acc = 0.f;
-    for (int q = lane; q < D; q += kWave) { const float v = p[q]; acc += v * v; }
-    acc = wave_sum(acc);
-    if (lane == 0) sqnorm[ex] = accumulate ? sqnorm[ex] + acc : acc;
+    if ((D & 3) == 0 && (reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+        const float4* p4 = reinterpret_cast<const float4*>(p);
+        const int n4 = D >> 2;
+        int q = lane;
+        for (; q + 3 * kWave < n4; q += 4 * kWave) {
+            const float4 a = p4[q], b = p4[q + kWave], c = p4[q + 2 * kWave], d = p4[q + 3 * kWave];
+            acc += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+            acc += b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+            acc += c.x * c.x + c.y * c.y + c.z * c.z + c.w * c.w;
+            acc += d.x * d.x + d.y * d.y + d.z * d.z + d.w * d.w;
+        }
+        for (; q < n4; q += kWave) { const float4 a = p4[q]; acc += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w; }
+    } else {
+        for (int q = lane; q < D; q += kWave) { const float v = p[q]; acc += v * v; }
+    }
+    return wave_sum(acc);
+}
+__global__ __launch_bounds__(kThreads) void k_rows_sqnorm(const float* __restrict__ u, const float* __restrict__ u2, int B, int D,
+                                                          int accumulate, float* __restrict__ sqnorm) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    if (ex >= B) return;
+    const float a = row_sq(u + (size_t)ex * D, D, lane);
+    const float b = u2 ? row_sq(u2 + (size_t)ex * D, D, lane) : 0.f;
+    if (lane == 0) {
+        float s = accumulate ? sqnorm[ex] + a : a;
+        if (u2) s += b;
+        sqnorm[ex] = s;
+    }
 }
 
 // grad_b[q] (+)= sum_i nu_i u[i, q].  A workgroup owns 32 columns; its 8 row groups add examples g, g + 8, ... in
@@ -259,8 +285,9 @@ hipError_t launch_bias_fold(const float* upart, int B, int nt, int D, bool accum
     return hipGetLastError();
 }
 
-hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st) {
-    k_rows_sqnorm<<<(unsigned)B, kWave, 0, st>>>(u, D, accumulate ? 1 : 0, sqnorm);
+hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st, const float* u2) {
+    const int per_block = kThreads / kWave;
+    k_rows_sqnorm<<<(unsigned)((B + per_block - 1) / per_block), kThreads, 0, st>>>(u, u2, B, D, accumulate ? 1 : 0, sqnorm);
     return hipGetLastError();
 }
 

@@ -56,7 +56,8 @@ hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed,
 hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, int dt, float* u, float* u2, hipStream_t st);
 // u[i, :] = sum over nt row tiles of upart[i, tt, :];  s_i (+)= ||u[i, :]||^2
 hipError_t launch_bias_fold(const float* upart, int B, int nt, int D, bool accumulate, float* u, float* sqnorm, hipStream_t st);
-hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st);
+// s_i (+)= ||u[i, :]||^2, then + ||u2[i, :]||^2 where u2 is given
+hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, float* sqnorm, hipStream_t st, const float* u2 = nullptr);
 hipError_t launch_clipped_bias(const float* u, const float* clip, int B, int D, bool accumulate, float* grad_b, hipStream_t st);
 hipError_t launch_philox_raw(uint32_t* out, int64_t n_counters, uint64_t seed, uint64_t first, hipStream_t st);
 

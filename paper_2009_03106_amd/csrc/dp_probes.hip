@@ -1,0 +1,159 @@
+// Measurement probes declared in include/dpclip_probes.h: one small kernel per unit (matrix units, memory reads,
+// LDS reads), used by the benchmark to quote the library's kernels against what the part sustains.
+#include "../../include/dpclip_probes.h"
+#include "dp_common.h"
+
+namespace dpk {
+namespace {
+
+typedef int v8i32 __attribute__((ext_vector_type(8)));
+typedef int v4i32 __attribute__((ext_vector_type(4)));
+typedef int v2i32 __attribute__((ext_vector_type(2)));
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+
+constexpr int kProbeWgs = 1024;
+
+__device__ __forceinline__ uint32_t xorshift(uint32_t& x) { x ^= x << 13; x ^= x >> 17; x ^= x << 5; return x; }
+
+// KIND 0: bf16, 1: fp16, 2: 8-bit (FA / FG = the instruction's format fields: 0 e4m3, 1 e5m2)
+template <int KIND, int FA, int FG>
+__global__ __launch_bounds__(256, 2) void k_probe_mfma(int iters, int random_operands, float* sink) {
+    f32x16 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    uint32_t x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    // words of 16-bit or 8-bit values: 1.0 everywhere, or sign / mantissa / lowest exponent bit pseudo-random
+    uint32_t w[4][16];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t r = random_operands ? xorshift(x) : 0u;
+            if (KIND == 0)      w[p][j] = ((r & 0x807f807fu) | 0x3f803f80u) ^ (r & 0x00800080u);
+            else if (KIND == 1) w[p][j] = ((r & 0x83ff83ffu) | 0x3c003c00u) ^ (r & 0x04000400u);
+            else                w[p][j] = ((r & 0x87878787u) | 0x38383838u) ^ (r & 0x08080808u);   // e4m3 1.0 = 0x38; as e5m2: 0.5
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int pa = j & 3, pb = (j + (j >> 2)) & 3;
+            if (KIND == 2) {
+                const v8i32 a = {(int)w[pa][0], (int)w[pa][1], (int)w[pa][2], (int)w[pa][3], (int)w[pa][4], (int)w[pa][5], (int)w[pa][6], (int)w[pa][7]};
+                const v8i32 b = {(int)w[pb][8], (int)w[pb][9], (int)w[pb][10], (int)w[pb][11], (int)w[pb][12], (int)w[pb][13], (int)w[pb][14], (int)w[pb][15]};
+                acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[j], FA, FG, 0, 0, 0, 0);
+            } else {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(w[pa][0], w[pa][1], w[pa][2], w[pa][3]));
+                const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(w[pb][4], w[pb][5], w[pb][6], w[pb][7]));
+                acc[j] = In16<KIND == 1>::mfma(a, b, acc[j]);
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void k_probe_read(const uint4* __restrict__ src, size_t n16, float* sink) {
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].w;
+    }
+    for (; i < n16; i += stride) { const uint4 v = src[i]; acc += v.x ^ v.w; }
+    if (acc == 0x12345678u) sink[0] = 1.f;            // keeps the loads; practically never true
+}
+
+template <int KIND>
+__global__ __launch_bounds__(256, 2) void k_probe_lds(int iters, float* sink) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[65536];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 65536 / 4; i += 256) reinterpret_cast<uint32_t*>(lds)[i] = i * 2654435761u;
+    __syncthreads();
+    const uint32_t lb = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))lds;
+    uint32_t base[8];
+    if (KIND == 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) base[j] = lb + wave * 8192 + j * 1024 + lane * 16;
+    } else {
+        // the clipped-sum kernel's fragment reads: lane l of a 16-lane group reads 8 bytes of source row (l % 16) / 4;
+        // rows of 512 bytes, 16-byte chunk c of row r at chunk position c ^ ((r & 3) << 2)
+        const int g16 = lane >> 4, s16 = lane & 15;
+        const int rsrc = 8 * (g16 >> 1) + (s16 >> 2);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int col = ((wave >> 1) * 4 + (j >> 1)) * 32 + 16 * (g16 & 1) + 4 * (s16 & 3);
+            base[j] = lb + (rsrc + 4 * (j & 1)) * 512 + ((((col >> 3) ^ ((rsrc & 3) << 2)) << 4) | ((col & 7) << 1));
+        }
+    }
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        if (KIND == 0) {
+            v4i32 r[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) asm volatile("ds_read_b128 %0, %1" : "=v"(r[j]) : "v"(base[j]));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc ^= (uint32_t)(r[j][0] ^ r[j][3]);
+        } else {
+            v2i32 r[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r[j]) : "v"(base[j]));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc ^= (uint32_t)(r[j][0] ^ r[j][1]);
+        }
+    }
+    sink[blockIdx.x * 256 + tid] = __uint_as_float(acc & 0x3fffffffu);
+}
+
+}  // namespace
+}  // namespace dpk
+
+using namespace dpk;
+
+extern "C" {
+
+dp_status dp_probe_mfma(dp_dtype dtype, int random_operands, int64_t iters, float* sink, double* flops, void* hip_stream) {
+    if (iters < 0 || iters > (int64_t(1) << 30) || !sink) return DP_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int it = (int)iters, rnd = random_operands ? 1 : 0;
+    int depth = 16;
+    switch (dtype) {
+        case DP_BF16: k_probe_mfma<0, 0, 0><<<kProbeWgs, 256, 0, st>>>(it, rnd, sink); break;
+        case DP_F16: k_probe_mfma<1, 0, 0><<<kProbeWgs, 256, 0, st>>>(it, rnd, sink); break;
+        case DP_F8_E4M3: depth = 64; k_probe_mfma<2, 0, 0><<<kProbeWgs, 256, 0, st>>>(it, rnd, sink); break;
+        case DP_F8_E5M2: depth = 64; k_probe_mfma<2, 1, 1><<<kProbeWgs, 256, 0, st>>>(it, rnd, sink); break;
+        case DP_F8_E4M3_E5M2: depth = 64; k_probe_mfma<2, 0, 1><<<kProbeWgs, 256, 0, st>>>(it, rnd, sink); break;
+        default: return DP_ERR_UNSUPPORTED;
+    }
+    if (flops) *flops = (double)kProbeWgs * 4.0 * (double)iters * 8.0 * 2.0 * 32.0 * 32.0 * depth;
+    return hipGetLastError() == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_probe_read(const void* src, size_t bytes, float* sink, void* hip_stream) {
+    if (!src || !sink || (bytes & 15) != 0 || (reinterpret_cast<uintptr_t>(src) & 15) != 0) return DP_ERR_INVALID_ARG;
+    if (bytes == 0) return DP_OK;
+    k_probe_read<<<2048, 256, 0, static_cast<hipStream_t>(hip_stream)>>>(static_cast<const uint4*>(src), bytes / 16, sink);
+    return hipGetLastError() == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dp_probe_lds_read(int kind, int64_t iters, float* sink, double* bytes, void* hip_stream) {
+    if (iters < 0 || iters > (int64_t(1) << 30) || !sink || (kind != 0 && kind != 1)) return DP_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (kind == 0) k_probe_lds<0><<<kProbeWgs, 256, 0, st>>>((int)iters, sink);
+    else           k_probe_lds<1><<<kProbeWgs, 256, 0, st>>>((int)iters, sink);
+    if (bytes) *bytes = (double)kProbeWgs * 256.0 * (double)iters * 8.0 * (kind == 0 ? 16.0 : 8.0);
+    return hipGetLastError() == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+}  // extern "C"

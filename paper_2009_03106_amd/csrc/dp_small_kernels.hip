@@ -17,26 +17,34 @@ __device__ __forceinline__ float clip_factor_of(float s, float C) {
     return 1.0f / (!(m <= 1.0f) ? m : 1.0f);
 }
 
-__device__ __forceinline__ float row_sumsq_f32(const float* __restrict__ row, int d, int lane) {
+// Sum of squares of one row by the `lpe` lanes (a power of two, 4 .. 64) that share an example; `sl` = this lane's
+// place among them.  Short rows get few lanes, so that a wave takes several examples at once and every lane has a
+// load of its own in flight (a whole wave on a 256-byte row would leave three quarters of its lanes idle).
+__device__ __forceinline__ float group_sum(float v, int lpe) {
+    for (int off = lpe >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float row_sumsq_f32(const float* __restrict__ row, int d, int sl, int lpe) {
     float acc = 0.f;
     if ((d & 3) == 0) {
         const float4* r4 = reinterpret_cast<const float4*>(row);
-        for (int c = lane; c < (d >> 2); c += kWave) {
+        for (int c = sl; c < (d >> 2); c += lpe) {
             float4 v = r4[c];
             acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         }
     } else {
-        for (int c = lane; c < d; c += kWave) { float v = row[c]; acc += v * v; }
+        for (int c = sl; c < d; c += lpe) { float v = row[c]; acc += v * v; }
     }
-    return wave_sum(acc);
+    return group_sum(acc, lpe);
 }
 
 template <bool F16>
-__device__ __forceinline__ float row_sumsq_16(const uint16_t* __restrict__ row, int d, int lane) {
+__device__ __forceinline__ float row_sumsq_16(const uint16_t* __restrict__ row, int d, int sl, int lpe) {
     float acc = 0.f;
     if ((d & 7) == 0) {
         const uint4* r8 = reinterpret_cast<const uint4*>(row);
-        for (int c = lane; c < (d >> 3); c += kWave) {
+        for (int c = sl; c < (d >> 3); c += lpe) {
             uint4 v = r8[c];
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -46,28 +54,38 @@ __device__ __forceinline__ float row_sumsq_16(const uint16_t* __restrict__ row, 
             }
         }
     } else {
-        for (int c = lane; c < d; c += kWave) { float v = In16<F16>::lo(row[c]); acc += v * v; }
+        for (int c = sl; c < d; c += lpe) { float v = In16<F16>::lo(row[c]); acc += v * v; }
     }
-    return wave_sum(acc);
+    return group_sum(acc, lpe);
 }
 
-// DT: 0 = float32, 1 = bf16, 2 = fp16
+// Lanes per example for rows of d_max elements of `es` bytes: enough for one 16-byte piece per lane, between 4 and 64.
+inline int dense_lanes_per_example(int d_max, int es) {
+    const int pieces = (int)(((int64_t)d_max * es + 15) / 16);
+    int lpe = 4;
+    while (lpe < 64 && lpe < pieces) lpe <<= 1;
+    return lpe;
+}
+
+// DT: 0 = float32, 1 = bf16, 2 = fp16.  lpe lanes per example: example = (global wave) * (64 / lpe) + lane / lpe.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restrict__ A, const void* __restrict__ G,
                                                            int B, int d_in, int d_out, int accumulate,
-                                                           float* __restrict__ sqnorm, float C, float* __restrict__ clip) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
-    if (ex >= B) return;
+                                                           float* __restrict__ sqnorm, float C, float* __restrict__ clip, int lpe) {
+    const int lane = threadIdx.x & (kWave - 1), sl = lane & (lpe - 1);
+    const int64_t gwave = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t ex64 = gwave * (kWave / lpe) + lane / lpe;
+    // lanes past the last example run on the last one (the shuffles need every lane) and write nothing
+    const int ex = (int)(ex64 < B ? ex64 : B - 1);
     float sa, sg;
     if (DT != 0) {
-        sa = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(A) + (size_t)ex * d_in, d_in, lane);
-        sg = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(G) + (size_t)ex * d_out, d_out, lane);
+        sa = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(A) + (size_t)ex * d_in, d_in, sl, lpe);
+        sg = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(G) + (size_t)ex * d_out, d_out, sl, lpe);
     } else {
-        sa = row_sumsq_f32(static_cast<const float*>(A) + (size_t)ex * d_in, d_in, lane);
-        sg = row_sumsq_f32(static_cast<const float*>(G) + (size_t)ex * d_out, d_out, lane);
+        sa = row_sumsq_f32(static_cast<const float*>(A) + (size_t)ex * d_in, d_in, sl, lpe);
+        sg = row_sumsq_f32(static_cast<const float*>(G) + (size_t)ex * d_out, d_out, sl, lpe);
     }
-    if (lane == 0) {
+    if (sl == 0 && ex64 < B) {
         float s = sa * sg;
         s = accumulate ? sqnorm[ex] + s : s;
         sqnorm[ex] = s;
@@ -79,51 +97,126 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense(const void* __restric
 // ||a_l,i||^2 ||g_l,i||^2  (one launch instead of one per layer: these layers are a few microseconds each).
 template <int DT>
 __global__ __launch_bounds__(kThreads) void k_sqnorm_dense_layers(DenseLayers t, int B, int accumulate, float* __restrict__ sqnorm,
-                                                                  float C, float* __restrict__ clip) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int ex = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
-    if (ex >= B) return;
+                                                                  float C, float* __restrict__ clip, int lpe) {
+    const int lane = threadIdx.x & (kWave - 1), sl = lane & (lpe - 1);
+    const int64_t gwave = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t ex64 = gwave * (kWave / lpe) + lane / lpe;
+    const int ex = (int)(ex64 < B ? ex64 : B - 1);
     float s = 0.f;
     for (int l = 0; l < t.n_layers; ++l) {
         const int d_in = t.d_in[l], d_out = t.d_out[l];
         float sa, sg;
         if (DT != 0) {
-            sa = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(t.A[l]) + (size_t)ex * d_in, d_in, lane);
-            sg = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(t.G[l]) + (size_t)ex * d_out, d_out, lane);
+            sa = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(t.A[l]) + (size_t)ex * d_in, d_in, sl, lpe);
+            sg = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(t.G[l]) + (size_t)ex * d_out, d_out, sl, lpe);
         } else {
-            sa = row_sumsq_f32(static_cast<const float*>(t.A[l]) + (size_t)ex * d_in, d_in, lane);
-            sg = row_sumsq_f32(static_cast<const float*>(t.G[l]) + (size_t)ex * d_out, d_out, lane);
+            sa = row_sumsq_f32(static_cast<const float*>(t.A[l]) + (size_t)ex * d_in, d_in, sl, lpe);
+            sg = row_sumsq_f32(static_cast<const float*>(t.G[l]) + (size_t)ex * d_out, d_out, sl, lpe);
         }
         s += sa * sg;
     }
-    if (lane == 0) {
+    if (sl == 0 && ex64 < B) {
         s = accumulate ? sqnorm[ex] + s : s;
         sqnorm[ex] = s;
         if (clip) clip[ex] = clip_factor_of(s, C);
     }
 }
 
+// Short rows (every row of every layer at most 512 bytes, a whole number of 16-byte pieces): a lane holds at most one
+// piece of a row, so the loads of ITER examples per lane group are issued together before anything is added: rows of
+// a few hundred bytes otherwise leave one or two loads in flight per wave, far from what HBM needs.
+template <int DT> __device__ __forceinline__ float piece_sumsq(const uint4& v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (DT == 0) { const float x = __uint_as_float(w[j]); acc += x * x; }
+        else { const float lo = In16<DT == 2>::lo(w[j]), hi = In16<DT == 2>::hi(w[j]); acc += lo * lo + hi * hi; }
+    }
+    return acc;
+}
+template <int DT, int ITER>
+__global__ __launch_bounds__(kThreads) void k_sqnorm_dense_short(DenseLayers t, int B, int accumulate, float* __restrict__ sqnorm,
+                                                                 float C, float* __restrict__ clip, int lpe) {
+    constexpr int ES = DT == 0 ? 4 : 2;
+    const int lane = threadIdx.x & (kWave - 1), sl = lane & (lpe - 1), epw = kWave / lpe;
+    const int64_t gwave = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t ex0 = gwave * epw * ITER + lane / lpe;            // this lane group's examples: ex0 + k * epw
+    float s[ITER];
+#pragma unroll
+    for (int k = 0; k < ITER; ++k) s[k] = 0.f;
+    for (int l = 0; l < t.n_layers; ++l) {
+        const int rba = t.d_in[l] * ES, rbg = t.d_out[l] * ES;       // row bytes
+        const unsigned char* A = static_cast<const unsigned char*>(t.A[l]);
+        const unsigned char* G = static_cast<const unsigned char*>(t.G[l]);
+        uint4 a[ITER], g[ITER];
+#pragma unroll
+        for (int k = 0; k < ITER; ++k) {
+            const int64_t ex = ex0 + (int64_t)k * epw;
+            a[k] = make_uint4(0u, 0u, 0u, 0u); g[k] = a[k];
+            if (ex < B && sl * 16 < rba) a[k] = *reinterpret_cast<const uint4*>(A + (size_t)ex * rba + sl * 16);
+            if (ex < B && sl * 16 < rbg) g[k] = *reinterpret_cast<const uint4*>(G + (size_t)ex * rbg + sl * 16);
+        }
+#pragma unroll
+        for (int k = 0; k < ITER; ++k) s[k] += group_sum(piece_sumsq<DT>(a[k]), lpe) * group_sum(piece_sumsq<DT>(g[k]), lpe);
+    }
+#pragma unroll
+    for (int k = 0; k < ITER; ++k) {
+        const int64_t ex = ex0 + (int64_t)k * epw;
+        if (sl == 0 && ex < B) {
+            const float v = accumulate ? sqnorm[ex] + s[k] : s[k];
+            sqnorm[ex] = v;
+            if (clip) clip[ex] = clip_factor_of(v, C);
+        }
+    }
+}
+constexpr int kShortIter = 4;
+// every row of every layer a whole number of 16-byte pieces, at most 32 of them
+bool dense_rows_short(const DenseLayers& t, int es) {
+    for (int l = 0; l < t.n_layers; ++l)
+        for (int d : {t.d_in[l], t.d_out[l]})
+            if (((int64_t)d * es) % 16 != 0 || (int64_t)d * es > 512) return false;
+    return t.n_layers > 0;
+}
+
 hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool accumulate, float* sqnorm, hipStream_t st,
                                       const ClipOut* co) {
-    const int per_block = kThreads / kWave;
-    dim3 grid((B + per_block - 1) / per_block);
+    int d_max = 1;
+    for (int l = 0; l < t.n_layers; ++l) d_max = t.d_in[l] > d_max ? t.d_in[l] : d_max, d_max = t.d_out[l] > d_max ? t.d_out[l] : d_max;
+    const int lpe = dense_lanes_per_example(d_max, dt == 0 ? 4 : 2);
     const float C = co ? co->C : 0.f;
     float* clip = co ? co->clip : nullptr;
-    if (dt == 2)      k_sqnorm_dense_layers<2><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip);
-    else if (dt == 1) k_sqnorm_dense_layers<1><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip);
-    else              k_sqnorm_dense_layers<0><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip);
+    if (dense_rows_short(t, dt == 0 ? 4 : 2)) {
+        const int64_t per_blk = (int64_t)(kThreads / kWave) * (kWave / lpe) * kShortIter;
+        dim3 g((unsigned)((B + per_blk - 1) / per_blk));
+        if (dt == 2)      k_sqnorm_dense_short<2, kShortIter><<<g, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+        else if (dt == 1) k_sqnorm_dense_short<1, kShortIter><<<g, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+        else              k_sqnorm_dense_short<0, kShortIter><<<g, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+        return hipGetLastError();
+    }
+    const int64_t per_block = (int64_t)(kThreads / kWave) * (kWave / lpe);
+    dim3 grid((unsigned)((B + per_block - 1) / per_block));
+    if (dt == 2)      k_sqnorm_dense_layers<2><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+    else if (dt == 1) k_sqnorm_dense_layers<1><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+    else              k_sqnorm_dense_layers<0><<<grid, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
     return hipGetLastError();
 }
 
 hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
                                bool accumulate, float* sqnorm, hipStream_t st, const ClipOut* co) {
-    const int per_block = kThreads / kWave;
-    dim3 grid((B + per_block - 1) / per_block);
+    {
+        DenseLayers one;
+        one.n_layers = 1; one.A[0] = A; one.G[0] = G; one.d_in[0] = d_in; one.d_out[0] = d_out;
+        if (dense_rows_short(one, dt == 0 ? 4 : 2)) return launch_sqnorm_dense_layers(one, B, dt, accumulate, sqnorm, st, co);
+    }
+    const int lpe = dense_lanes_per_example(d_in > d_out ? d_in : d_out, dt == 0 ? 4 : 2);
+    const int64_t per_block = (int64_t)(kThreads / kWave) * (kWave / lpe);
+    dim3 grid((unsigned)((B + per_block - 1) / per_block));
     const float C = co ? co->C : 0.f;
     float* clip = co ? co->clip : nullptr;
-    if (dt == 2)      k_sqnorm_dense<2><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip);
-    else if (dt == 1) k_sqnorm_dense<1><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip);
-    else              k_sqnorm_dense<0><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip);
+    if (dt == 2)      k_sqnorm_dense<2><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+    else if (dt == 1) k_sqnorm_dense<1><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+    else              k_sqnorm_dense<0><<<grid, kThreads, 0, st>>>(A, G, B, d_in, d_out, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
     return hipGetLastError();
 }
 

@@ -27,6 +27,10 @@ EXPORTS = ("dp_layer_sqnorm", "dp_layer_sqnorm_static", "dp_layers_sqnorm", "dp_
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw",
            "dp_clipped_grad_rounds_inputs")
 
+# the measurement probes of include/dpclip_probes.h
+PROBE_EXPORTS = ("dp_probe_mfma", "dp_probe_read", "dp_probe_lds_read")
+PROBE_SINK_FLOATS = 1024 * 256
+
 _lib = None
 
 
@@ -99,6 +103,12 @@ def load_library() -> ctypes.CDLL:
     lib.dp_philox_raw.restype = ci
     lib.dp_clipped_grad_rounds_inputs.argtypes = [i64, i64, i64, i64, ci]
     lib.dp_clipped_grad_rounds_inputs.restype = ci
+    lib.dp_probe_mfma.argtypes = [ci, ci, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.dp_probe_mfma.restype = ci
+    lib.dp_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.dp_probe_read.restype = ci
+    lib.dp_probe_lds_read.argtypes = [ci, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.dp_probe_lds_read.restype = ci
     _lib = lib
     return lib
 
@@ -567,6 +577,34 @@ def clipped_grad_rounds_inputs(B: int, T: int, d_in: int, d_out: int, dtype: int
     if r < 0:
         raise ValueError("invalid arguments")
     return bool(r)
+
+
+def probe_mfma(dtype: int, random_operands: bool, iters: int, sink: torch.Tensor, *,
+               stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Launch the register-resident matrix-unit probe (dp_probe_mfma); returns the flops of the launch."""
+    work = ctypes.c_double(0.0)
+    st = load_library().dp_probe_mfma(dtype, int(bool(random_operands)), int(iters), _f32(sink, (PROBE_SINK_FLOATS,), "sink"),
+                                      ctypes.byref(work), _stream_ptr(stream))
+    _check(st, "dp_probe_mfma")
+    return work.value
+
+
+def probe_read(src: torch.Tensor, sink: torch.Tensor, *, stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Launch the streaming-read probe over all of src (dp_probe_read); returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    st = load_library().dp_probe_read(_ptr(src), nbytes, _f32(sink, (PROBE_SINK_FLOATS,), "sink"), _stream_ptr(stream))
+    _check(st, "dp_probe_read")
+    return float(nbytes)
+
+
+def probe_lds_read(kind: int, iters: int, sink: torch.Tensor, *, stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Launch the LDS read probe (dp_probe_lds_read; kind 0: ds_read_b128, 1: ds_read_b64_tr_b16); returns the bytes
+    that the lanes of the launch received."""
+    work = ctypes.c_double(0.0)
+    st = load_library().dp_probe_lds_read(int(kind), int(iters), _f32(sink, (PROBE_SINK_FLOATS,), "sink"),
+                                          ctypes.byref(work), _stream_ptr(stream))
+    _check(st, "dp_probe_lds_read")
+    return work.value
 
 
 def philox_raw(n_counters: int, seed: int, first_counter: int, device="cuda") -> torch.Tensor:

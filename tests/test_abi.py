@@ -21,8 +21,8 @@ def lib():
     return dpclip.load_library()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "dpclip.h")).read()
+def declared_symbols(header="dpclip.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(dp_[a-z_]+)\s*\(", text)))
 
@@ -32,6 +32,12 @@ def test_exports_match_header(lib):
     assert set(syms) == set(dpclip.EXPORTS)
     for s in syms:
         assert getattr(lib, s) is not None
+    probes = declared_symbols("dpclip_probes.h")
+    assert set(probes) == set(dpclip.PROBE_EXPORTS)
+    for s in probes:
+        assert getattr(lib, s) is not None
+    # every header under include/ is covered here
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["dpclip.h", "dpclip_probes.h"]
 
 
 def test_status_strings(lib):

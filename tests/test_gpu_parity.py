@@ -624,6 +624,8 @@ def test_layers_call_empty_and_errors(dp):
 RAGGED = [
     # B, T, d_in, d_out
     (3, 1, 5, 3), (7, 1, 130, 67), (5, 1, 1024, 8),
+    # dense layers with short rows (at most 512 bytes, whole 16-byte pieces): several examples per wave
+    (37, 1, 64, 32), (300, 1, 8, 256), (70, 1, 128, 8), (5, 1, 4, 4), (1, 1, 16, 128), (131, 1, 24, 40),
     (2, 3, 8, 8), (3, 17, 72, 40), (2, 70, 136, 264), (3, 129, 200, 24), (2, 257, 64, 320),
     (1, 64, 7, 9), (2, 33, 129, 65),
     # large aligned tiles with ragged edges (256 x 256 clipped-sum kernels), T % 32 == 0 and T % 8 == 0 only
