@@ -3,6 +3,7 @@
 // synchronisation, no host reads of device memory.
 #include "../../include/dpclip.h"
 #include "dp_internal.h"
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -111,6 +112,13 @@ bool gram_batchable(int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_p
 }
 
 size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
+
+// a layer that the joint clipped-sum launch of dp_layers_clipped_grad(_noise) can take (by shape and type)
+bool clipped_joinable(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
+    if (!is16(dtype) || B == 0 || T == 0 || d_in == 0 || d_out == 0) return false;
+    if (!plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out).dma) return false;
+    return dma_joint_ok((int)T, (int)d_in, (int)d_out);
+}
 
 constexpr size_t kConvZeroBytes = 256;                // head of the conv workspace: a line of zeros for the padding
 
@@ -845,10 +853,22 @@ extern "C" {
 size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype) {
     if (check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, false, DP_OP_CLIPPED_GRAD) != DP_OK) return 0;
     size_t need = 0;
+    JointShape sh[kJointLayers];
+    int nj = 0;
+    auto joint_need = [&]() {
+        if (nj >= 2) need = std::max(need, joint_workspace_floats(sh, nj, (int)B) * sizeof(float));
+        nj = 0;
+    };
     for (int64_t l = 0; l < n_layers; ++l) {
-        const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, layers[l].T, layers[l].d_in, layers[l].d_out, dtype, DP_PATH_AUTO);
+        const dp_layer_desc& y = layers[l];
+        const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
         if (n > need) need = n;
+        if (clipped_joinable(B, y.T, y.d_in, y.d_out, dtype)) {
+            sh[nj++] = JointShape{(int)y.T, (int)y.d_in, (int)y.d_out};
+            if (nj == kJointLayers) joint_need();
+        }
     }
+    joint_need();
     return round16(need);
 }
 
@@ -878,9 +898,49 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
     }
     for (int64_t l = 0; l < n_layers; ++l)
         if (B > 0 && !clip && !layers[l].clip) return DP_ERR_INVALID_ARG;          // neither the layer's own factors nor the call's
+    // Aligned 16-bit layers with 256 x 256 tiles share launches, up to kJointLayers each (groups of at least two):
+    // one launch whose items fill the chip a whole number of times, the K slices folded (and the noise added) inside
+    // it.  With noise the kernel adds it four elements at a time, so the layer's offset and size must be multiples of 4.
+    std::vector<std::vector<int64_t>> joint_groups;
+    {
+        std::vector<int64_t> cur;
+        for (int64_t l = 0; l < n_layers; ++l) {
+            const dp_layer_desc& y = layers[l];
+            if (!clipped_joinable(B, y.T, y.d_in, y.d_out, dtype)) continue;
+            if (stddev > 0.0f && !splitk_noise_ok(y.d_in * y.d_out, y.noise_offset)) continue;
+            cur.push_back(l);
+            if ((int)cur.size() == kJointLayers) { joint_groups.push_back(cur); cur.clear(); }
+        }
+        if (cur.size() >= 2) joint_groups.push_back(cur);
+        // the largest layers first: the tiles that are folded when the launch ends are then the smallest layer's
+        for (auto& g : joint_groups)
+            std::stable_sort(g.begin(), g.end(), [&](int64_t a, int64_t b) {
+                return layers[a].d_in * layers[a].d_out * layers[a].T > layers[b].d_in * layers[b].d_out * layers[b].T; });
+        for (const auto& g : joint_groups) {
+            JointShape sh[kJointLayers];
+            for (size_t k = 0; k < g.size(); ++k) {
+                const dp_layer_desc& y = layers[g[k]];
+                sh[k] = JointShape{(int)y.T, (int)y.d_in, (int)y.d_out};
+            }
+            need = std::max(need, joint_workspace_floats(sh, (int)g.size(), (int)B) * sizeof(float));
+        }
+    }
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
     // float32 layers with a short contraction (a model of small dense layers) share launches, 8 layers each
     std::vector<char> done((size_t)n_layers, 0);
+    for (const auto& g : joint_groups) {
+        JointShape sh[kJointLayers];
+        JointOperands op[kJointLayers];
+        for (size_t k = 0; k < g.size(); ++k) {
+            const dp_layer_desc& y = layers[g[k]];
+            sh[k] = JointShape{(int)y.T, (int)y.d_in, (int)y.d_out};
+            op[k] = JointOperands{static_cast<const uint16_t*>(y.A), static_cast<const uint16_t*>(y.G), y.clip ? y.clip : clip, y.grad,
+                                  y.noise_offset};
+            done[(size_t)g[k]] = 1;
+        }
+        if (launch_clipped_bf16_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
+                                          static_cast<hipStream_t>(hip_stream), dtype == DP_F16) != hipSuccess) return DP_ERR_HIP;
+    }
     if (dtype == DP_F32 && B > 0 && !(stddev > 0.0f)) {
         ShortLayerDesc batch[8];
         int64_t which[8];

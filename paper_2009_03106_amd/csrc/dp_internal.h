@@ -93,6 +93,19 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
                                    const ConvGeom* cg, const uint16_t* zero, bool f16, const NoiseArgs* noise);
+// Several layers' clipped sums in one launch (16-bit inputs, 256 x 256 tiles, T a multiple of 32): the K slices of all
+// layers are cut to about one length so that the launch fills the chip a whole number of times; the layers' slices
+// are then folded (+ noise) by the split-K reduce kernel as after a launch per layer.  Same arithmetic per slice and
+// the same ascending fold; the slices are cut differently, so the results agree with the per-layer launch up to the
+// rounding of the float32 sum over slices.
+constexpr int kJointLayers = 16;
+struct JointShape { int T, M, N; };
+struct JointOperands { const uint16_t* A; const uint16_t* G; const float* clip; float* grad; uint64_t noise_offset; };
+bool dma_joint_ok(int T, int M, int N);
+size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B);
+// noise: stddev == 0 for none, else every layer's d_in * d_out and noise_offset are multiples of 4
+hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
+                                         float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16);
 // direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);

@@ -29,6 +29,7 @@
 // current unit that c_cur / c_next is not finite in fp32, cannot become the
 // unit: its MFMAs are skipped instead and the unit stays, i.e. the example
 // counts with factor 0, as the weighted sum defines for a zero factor.
+#include <algorithm>
 #include "dp_common.h"
 #include "dp_internal.h"
 
@@ -107,8 +108,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn
 // AM = 2 (ragged): T is not a multiple of the 32-row stage.  Every example then takes ceil(T / 32) stages, and
 // the rows past its end in the last one are copied from the line of zeros (rows of zeros add nothing to the
 // product); the per-lane addresses are 64-bit as in the convolution mode.
+// `L`: the (slice, tile) pair of this workgroup among the layer's tiles * splits
 template <class GEO, int MODE, int AM, bool F16>
-__global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs a) {
+__device__ __forceinline__ void tn_dma_tile(const DmaArgs& a, const int L) {
     constexpr bool CONV = AM == 1, RAG = AM == 2;
     constexpr int NST = GEO::NST, FM = GEO::FM, FN = GEO::FN, NF = FM + FN;
     constexpr int RBA = GEO::RBA, RBG = GEO::RBG, IPA = GEO::IPA, IPG = GEO::IPG, LPS = GEO::LPS;
@@ -119,9 +121,6 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles = a.tiles_m * a.tiles_n;
-    // workgroup b runs on XCD b % 8: give each XCD a contiguous run of (slice, tile) pairs so that
-    // its workgroups stream the same rows of A and G through one L2
-    const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
     if (L >= tiles * a.splits) return;
     const int z = L / tiles, tile = L - z * tiles;
     const int tm = tile / a.tiles_n, tn = tile - tm * a.tiles_n;
@@ -419,6 +418,46 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
         }
 }
 
+template <class GEO, int MODE, int AM, bool F16>
+__global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs a) {
+    // workgroup b runs on XCD b % 8: give each XCD a contiguous run of (slice, tile) pairs so that
+    // its workgroups stream the same rows of A and G through one L2
+    tn_dma_tile<GEO, MODE, AM, F16>(a, (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3));
+}
+
+// Several layers' clipped sums in one launch (256 x 256 tiles, flat operands): the launch is a list of (layer, K slice,
+// tile) items, a layer's items slice-major, dealt to the XCDs in contiguous runs like a single layer's.  All layers
+// cut their K range into slices of about the same length, chosen so that the items fill the chip a whole number of
+// times: a launch per layer has to fill it exactly once, which takes more and shorter slices (more partial tiles to
+// store and to fold) and leaves a gap between the layers.
+constexpr int kJointMax = kJointLayers;
+struct JointLayer {
+    const uint16_t* A; const uint16_t* G; const float* clip;
+    float* slices;
+    int T, M, N, tiles_m, tiles_n, splits, stages_total, stages_per_split, first_item;
+};
+struct JointArgs {
+    JointLayer layer[kJointMax];
+    int n_layers, n_items, per_xcd, B;
+};
+template <bool F16>
+__global__ __launch_bounds__(GeoL::THREADS, GeoL::OCC) void k_tn_bf16_dma_joint(JointArgs j) {
+    const int L = (blockIdx.x & 7) * j.per_xcd + (blockIdx.x >> 3);
+    if (L >= j.n_items) return;
+    int l = 0;
+    while (l + 1 < j.n_layers && L >= j.layer[l + 1].first_item) ++l;
+    const JointLayer& y = j.layer[l];
+    DmaArgs a;
+    a.A = y.A; a.G = y.G; a.clip = y.clip;
+    a.out = y.slices; a.slice = (((int64_t)y.M * y.N) + 3) & ~(int64_t)3;        // splitk_slice_elems
+    a.B = j.B; a.T = y.T; a.M = y.M; a.N = y.N;
+    a.tiles_m = y.tiles_m; a.tiles_n = y.tiles_n; a.splits = y.splits;
+    a.stages_total = y.stages_total; a.stages_per_split = y.stages_per_split;
+    a.per_xcd = 0; a.accumulate = 0;
+    a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0; a.zero = nullptr;
+    tn_dma_tile<GeoL, 0, 0, F16>(a, L - y.first_item);
+}
+
 
 // 0: not for this kernel; 1: GeoL; 2: GeoS; 3: GeoT (the first that fits, in the order of flop per copied byte)
 int dma_geometry(int T, int M, int N) {
@@ -479,6 +518,7 @@ template <int MODE> hipError_t launch_any(int geo, const DmaArgs& a, int am, boo
 
 void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
     a.zero = zero;
+
     if (cg) { a.H = cg->H; a.W = cg->W; a.C = cg->C; a.KW = cg->KW; a.pad = cg->pad; a.Wout = cg->W + 2 * cg->pad - cg->KW + 1; }
     else { a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0; }
 }
@@ -536,6 +576,90 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     const hipError_t e = launch_any<0>(geo_of_plan(p), a, am, f16, st);
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
+}
+
+// ---- joint launch of several layers' clipped sums
+bool dma_joint_ok(int T, int M, int N) { return T > 0 && (T % DK) == 0 && dma_geometry(T, M, N) == 1; }
+
+namespace {
+
+struct JointPlan { int n_layers; int tiles_m[kJointMax], tiles_n[kJointMax], splits[kJointMax], sps[kJointMax]; int64_t items; };
+
+// One slice length for all layers (each layer rounds it to a whole number of equal slices), chosen to minimise
+//     rounds of 256 workgroups  x  (stages of the longest slice + what an item costs besides its stages):
+// slices long enough that their start-up, their store and their fold stay small, and a number of items that fills
+// the chip's 256 compute units a whole number of times.
+JointPlan plan_joint(const JointShape* sh, int n_layers, int B) {
+    constexpr int64_t kItemOverhead = 16;            // prologue + slice store + the slice's share of the fold, in stage times
+    JointPlan best{};
+    int64_t best_cost = -1;
+    int64_t stages_max = 1;
+    for (int l = 0; l < n_layers; ++l) stages_max = std::max(stages_max, (int64_t)B * (sh[l].T / DK));
+    for (int64_t S = 1; S <= 512 && S <= stages_max; ++S) {
+        const int64_t len = (stages_max + S - 1) / S;
+        if (len < 8 && S > 1) break;
+        JointPlan p{};
+        p.n_layers = n_layers;
+        int64_t longest = 0;
+        for (int l = 0; l < n_layers; ++l) {
+            const int64_t spe = sh[l].T / DK, stages = (int64_t)B * spe;
+            int64_t want = std::min(len, 63 * spe);       // a slice touches at most 64 examples (one clip factor per lane)
+            int64_t splits = (stages + want - 1) / want;
+            int64_t sps = (stages + splits - 1) / splits;
+            splits = (stages + sps - 1) / sps;            // no empty slice
+            p.tiles_m[l] = ceil_div(sh[l].M, GeoL::TM); p.tiles_n[l] = ceil_div(sh[l].N, GeoL::TN);
+            p.splits[l] = (int)splits; p.sps[l] = (int)sps;
+            p.items += (int64_t)p.tiles_m[l] * p.tiles_n[l] * splits;
+            longest = std::max(longest, sps);
+        }
+        const int64_t cost = ((p.items + 255) / 256) * (longest + kItemOverhead);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = p; }
+    }
+    return best;
+}
+
+}  // namespace
+
+// floats of workspace: every layer's slices, one layer after the other
+size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B) {
+    const JointPlan p = plan_joint(sh, n_layers, B);
+    size_t slices = 0;
+    for (int l = 0; l < n_layers; ++l) slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
+    return slices;
+}
+
+hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
+                                         float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16) {
+    if (n_layers < 1 || n_layers > kJointMax) return hipErrorInvalidValue;
+    const JointPlan p = plan_joint(sh, n_layers, B);
+    if (p.items >= (int64_t(1) << 28)) return hipErrorInvalidValue;
+    JointArgs j;
+    float* slices = ws;
+    int64_t first = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        JointLayer& y = j.layer[l];
+        y.A = op[l].A; y.G = op[l].G; y.clip = op[l].clip;
+        y.slices = slices;
+        y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
+        y.tiles_m = p.tiles_m[l]; y.tiles_n = p.tiles_n[l]; y.splits = p.splits[l];
+        y.stages_total = (int)((int64_t)B * (sh[l].T / DK)); y.stages_per_split = p.sps[l];
+        y.first_item = (int)first;
+        first += (int64_t)p.tiles_m[l] * p.tiles_n[l] * p.splits[l];
+        slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
+    }
+    for (int l = n_layers; l < kJointMax; ++l) j.layer[l] = j.layer[0];
+    j.n_layers = n_layers; j.n_items = (int)p.items; j.per_xcd = ceil_div(p.items, 8);
+    j.B = B;
+    if (f16) k_tn_bf16_dma_joint<true><<<8u * (unsigned)j.per_xcd, GeoL::THREADS, 0, st>>>(j);
+    else     k_tn_bf16_dma_joint<false><<<8u * (unsigned)j.per_xcd, GeoL::THREADS, 0, st>>>(j);
+    hipError_t e = hipGetLastError();
+    // the folds of the layers' slices (+ noise), each as after a launch of the layer alone
+    for (int l = 0; l < n_layers && e == hipSuccess; ++l) {
+        const NoiseArgs nz{stddev, (uint32_t)seed, (uint32_t)(seed >> 32), op[l].noise_offset};
+        e = launch_splitk_reduce(j.layer[l].slices, (int64_t)sh[l].M * sh[l].N, p.splits[l], accumulate, op[l].grad, st,
+                                 stddev != 0.0f ? &nz : nullptr);
+    }
+    return e;
 }
 
 // implicit unfolding: whole 16-byte pieces must stay inside one pixel's channels, image offsets must fit 32 bits

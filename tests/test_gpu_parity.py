@@ -79,6 +79,17 @@ def check_clipped_sum(dp, A, G, c_gpu, got, dtype, where=""):
         assert fro_err(got, ref) <= FRO_TIGHT, (where, "fro", fro_err(got, ref))
 
 
+def assert_same_sums(got, want, joint):
+    """Clipped sums of the several-layers call against the per-layer calls: bit for bit, except where aligned 16-bit
+    layers share the joint launch, which cuts the contraction into other K slices: there the two are float32 sums of
+    the same terms in another grouping (1e-5 of the largest entry; the entries are sums of thousands of terms)."""
+    got, want = np.asarray(got), np.asarray(want)
+    if joint:
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-5 * float(np.abs(want).max()))
+    else:
+        np.testing.assert_array_equal(got, want)
+
+
 def run_gpu_pipeline(dp, layers_np, C, path="auto", noise_std=0.0, seed=0, clean=None):
     dev = [(to_dev(A), to_dev(G)) for A, G in layers_np]
     s = None
@@ -325,7 +336,7 @@ def test_per_layer_clipping_in_the_layers_calls(dp):
     dp.layers_clipped_grad(dev, None, descs=descs_g)
     for l, ((A, G), g) in enumerate(zip(layers, grads)):
         assert fro_err(g.cpu().numpy(), orc.clipped_grad(A, G, orc.clip_factors(s_l[l], Cl))) <= FRO_TOL["bf16"]
-        np.testing.assert_array_equal(g.cpu().numpy(), dp.clipped_grad(dev[l][0], dev[l][1], cl[l]).cpu().numpy())
+        assert_same_sums(g.cpu().numpy(), dp.clipped_grad(dev[l][0], dev[l][1], cl[l]).cpu().numpy(), joint=True)
     # every per-layer clipped gradient has norm <= C / sqrt(m) * sqrt(m) = C overall: sum over layers of (nu_l ||g_l||)^2 <= m Cl^2
     tot = sum((cl[l].cpu().numpy().astype(np.float64) ** 2) * s_l[l] for l in range(m))
     assert np.all(tot <= m * Cl * Cl * (1 + 1e-3))
@@ -364,7 +375,7 @@ def test_layers_calls_with_weights_and_biases(dp, name, B):
         dp.clipped_grad(A, G, c, ref[starts[i]:starts[i] + nw].view(A.shape[-1], G.shape[-1]))
         dp.clipped_bias_grad(rows[i], c, ref[starts[i] + nw:starts[i + 1]])
     dp.add_noise(ref, 0.5, 77, 0)
-    assert torch.equal(flat, ref)
+    assert_same_sums(flat.cpu().numpy(), ref.cpu().numpy(), joint=name == "transformer")
     # ... and against the oracle, noise included
     cn = c.cpu().numpy().astype(np.float64)
     want = np.concatenate([np.concatenate([orc.clipped_grad(A, G, cn).ravel(), orc.clipped_bias_grad(G, cn)]) for A, G in layers])
@@ -472,7 +483,7 @@ def test_layers_clipped_grad_equals_per_layer_calls(dp, name, B):
     c = to_dev(c_ref.astype(np.float32))
     grads = dp.layers_clipped_grad(dev, c)
     for (A, G), (An, Gn), g in zip(dev, layers, grads):
-        np.testing.assert_array_equal(g.cpu().numpy(), dp.clipped_grad(A, G, c).cpu().numpy())      # same kernels, same order
+        assert_same_sums(g.cpu().numpy(), dp.clipped_grad(A, G, c).cpu().numpy(), joint=name == "transformer")     # same kernels
         assert fro_err(g.cpu().numpy(), orc.clipped_grad(An, Gn, c_ref)) <= FRO_TOL[w.dtype]
     again = [torch.full_like(g, 2.0) for g in grads]
     dp.layers_clipped_grad(dev, c, again, accumulate=True)
