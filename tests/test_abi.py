@@ -146,10 +146,16 @@ def test_layers_workspace_sizes(lib):
     mixed = descs([(1, 64, 32), (1024, 576, 128), (0, 8, 8)])
     assert f(mixed, 128, dpclip.DP_BF16) == (dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 128, 1024, 576, 128, dpclip.DP_BF16) + 15) // 16 * 16
     assert f(descs([(512, 1 << 24, 64)]), 2, dpclip.DP_BF16) == 0         # width out of range
-    # the clipped sums of several layers run one after the other and share the largest layer's scratch
+    # the clipped sums of several layers run one after the other and share the largest layer's scratch ...
     h = dpclip.layers_clipped_workspace_bytes
     shapes = [(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)]
-    assert h(tr, 64, dpclip.DP_BF16) == max((dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *sh, dpclip.DP_BF16) + 15) // 16 * 16 for sh in shapes)
+    single = max((dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *sh, dpclip.DP_BF16) + 15) // 16 * 16 for sh in shapes)
+    assert h(descs(shapes[:1]), 64, dpclip.DP_BF16) == (dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *shapes[0], dpclip.DP_BF16) + 15) // 16 * 16
+    assert h(tr, 64, dpclip.DP_F32) == max((dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *sh, dpclip.DP_F32) + 15) // 16 * 16 for sh in shapes)
+    # ... except aligned 16-bit layers on 256 x 256 tiles, which share one launch and keep all their K slices at once:
+    # 64 * 16 stages per layer cut into 7 slices (756 items = 3 rounds of the 256 compute units)
+    assert h(tr, 64, dpclip.DP_BF16) == 7 * sum(di * do for _, di, do in shapes) * 4 > single
+    assert h(tr, 64, dpclip.DP_F16) == h(tr, 64, dpclip.DP_BF16)
     assert h(descs([(1, 784, 512), (1, 512, 256), (1, 256, 10)]), 256, dpclip.DP_F32) == 0    # short contractions: no K slices
 
 
