@@ -209,11 +209,11 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
  * Same kernels as one dp_clipped_grad call per layer.  It saves the caller's
  * per-call cost, which is what bounds models made of many small layers, and
  * it lets layers share launches: float32 layers with a short contraction
- * (B*T <= 512), eight per launch, and 16-bit layers that run on 256 x 256
- * tiles with T a multiple of 32 (groups of 2 to 16): one launch whose work
- * items fill the chip a whole number of times, where a launch per layer has
- * to fill it exactly once.  Results: bit for bit the per-layer calls, except
- * for those 16-bit groups, whose contraction is cut into other K slices: the
+ * (B*T <= 512), eight per launch, and 16-bit / 8-bit layers that run on 256 x
+ * 256 tiles with T a multiple of the 32- / 64-row stage (groups of 2 to 16):
+ * one launch whose work items fill the chip a whole number of times, where a
+ * launch per layer has to fill it exactly once.  Results: bit for bit the
+ * per-layer calls, except for those groups, whose contraction is cut into other K slices: the
  * float32 partial sums are then grouped differently (differences at the level
  * of float32 rounding; still bit-reproducible from call to call).
  *   workspace  device scratch of at least dp_layers_clipped_workspace_bytes(...)
@@ -230,7 +230,7 @@ size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_
  *     layers[l].grad[j] += stddev * z[layers[l].noise_offset + j],
  * z = the stream of dp_add_noise for `seed`.  Bit-identical to
  * dp_layers_clipped_grad followed by dp_add_noise(grad, d_in*d_out, stddev, seed,
- * noise_offset) per layer (for the 16-bit groups above: to the same call without
+ * noise_offset) per layer (for the groups that share a launch: to the same call without
  * noise followed by dp_add_noise); where a layer's clipped sum ends in the kernel that
  * folds its K slices (and d_in*d_out and noise_offset are multiples of 4), that
  * kernel adds the noise while it holds the sums, which saves the extra pass over

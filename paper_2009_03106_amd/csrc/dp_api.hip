@@ -115,9 +115,13 @@ size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
 
 // a layer that the joint clipped-sum launch of dp_layers_clipped_grad(_noise) can take (by shape and type)
 bool clipped_joinable(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
-    if (!is16(dtype) || B == 0 || T == 0 || d_in == 0 || d_out == 0) return false;
-    if (!plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out).dma) return false;
+    if (B == 0 || T == 0 || d_in == 0 || d_out == 0) return false;
+    if (is8(dtype)) return dma8_clipped_ok((int)T, (int)d_in, (int)d_out) && dma8_joint_ok((int)T, (int)d_in, (int)d_out);
+    if (!is16(dtype) || !plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out).dma) return false;
     return dma_joint_ok((int)T, (int)d_in, (int)d_out);
+}
+size_t joint_ws_bytes(const JointShape* sh, int n, int64_t B, dp_dtype dtype) {
+    return (is8(dtype) ? joint8_workspace_floats(sh, n, (int)B) : joint_workspace_floats(sh, n, (int)B)) * sizeof(float);
 }
 
 constexpr size_t kConvZeroBytes = 256;                // head of the conv workspace: a line of zeros for the padding
@@ -856,7 +860,7 @@ size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_
     JointShape sh[kJointLayers];
     int nj = 0;
     auto joint_need = [&]() {
-        if (nj >= 2) need = std::max(need, joint_workspace_floats(sh, nj, (int)B) * sizeof(float));
+        if (nj >= 2) need = std::max(need, joint_ws_bytes(sh, nj, B, dtype));
         nj = 0;
     };
     for (int64_t l = 0; l < n_layers; ++l) {
@@ -898,7 +902,7 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
     }
     for (int64_t l = 0; l < n_layers; ++l)
         if (B > 0 && !clip && !layers[l].clip) return DP_ERR_INVALID_ARG;          // neither the layer's own factors nor the call's
-    // Aligned 16-bit layers with 256 x 256 tiles share launches, up to kJointLayers each (groups of at least two):
+    // Aligned 16-bit and 8-bit layers with 256 x 256 tiles share launches, up to kJointLayers each (groups of at least two):
     // one launch whose items fill the chip a whole number of times, the K slices folded (and the noise added) inside
     // it.  With noise the kernel adds it four elements at a time, so the layer's offset and size must be multiples of 4.
     std::vector<std::vector<int64_t>> joint_groups;
@@ -922,7 +926,7 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
                 const dp_layer_desc& y = layers[g[k]];
                 sh[k] = JointShape{(int)y.T, (int)y.d_in, (int)y.d_out};
             }
-            need = std::max(need, joint_workspace_floats(sh, (int)g.size(), (int)B) * sizeof(float));
+            need = std::max(need, joint_ws_bytes(sh, (int)g.size(), B, dtype));
         }
     }
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
@@ -938,8 +942,12 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
                                   y.noise_offset};
             done[(size_t)g[k]] = 1;
         }
-        if (launch_clipped_bf16_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
-                                          static_cast<hipStream_t>(hip_stream), dtype == DP_F16) != hipSuccess) return DP_ERR_HIP;
+        const hipError_t ej = is8(dtype)
+            ? launch_clipped_f8_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
+                                          static_cast<hipStream_t>(hip_stream), fmt_of(dtype))
+            : launch_clipped_bf16_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
+                                            static_cast<hipStream_t>(hip_stream), dtype == DP_F16);
+        if (ej != hipSuccess) return DP_ERR_HIP;
     }
     if (dtype == DP_F32 && B > 0 && !(stddev > 0.0f)) {
         ShortLayerDesc batch[8];

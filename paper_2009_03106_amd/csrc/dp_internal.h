@@ -101,8 +101,45 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
 constexpr int kJointLayers = 16;
 struct JointShape { int T, M, N; };
 struct JointOperands { const uint16_t* A; const uint16_t* G; const float* clip; float* grad; uint64_t noise_offset; };
+// One slice length for all layers of a joint launch (each layer rounds it to a whole number of equal slices), chosen
+// to minimise   rounds of 256 workgroups  x  (stages of the longest slice + what an item costs besides its stages):
+// slices long enough that their start-up, their store and their fold stay small, and a number of items that fills
+// the chip's 256 compute units a whole number of times.  dk: rows per stage; tile: the square output tile.
+struct JointPlan { int n_layers; int tiles_m[kJointLayers], tiles_n[kJointLayers], splits[kJointLayers], sps[kJointLayers]; int64_t items; };
+inline JointPlan plan_joint(const JointShape* sh, int n_layers, int B, int dk, int tile) {
+    constexpr int64_t kItemOverhead = 16;            // prologue + slice store + the slice's share of the fold, in stage times
+    JointPlan best{};
+    int64_t best_cost = -1, stages_max = 1;
+    for (int l = 0; l < n_layers; ++l) stages_max = stages_max > (int64_t)B * (sh[l].T / dk) ? stages_max : (int64_t)B * (sh[l].T / dk);
+    for (int64_t S = 1; S <= 512 && S <= stages_max; ++S) {
+        const int64_t len = (stages_max + S - 1) / S;
+        if (len < 8 && S > 1) break;
+        JointPlan p{};
+        p.n_layers = n_layers;
+        int64_t longest = 0;
+        for (int l = 0; l < n_layers; ++l) {
+            const int64_t spe = sh[l].T / dk, stages = (int64_t)B * spe;
+            const int64_t want = len < 63 * spe ? len : 63 * spe;   // a slice touches at most 64 examples (one clip factor per lane)
+            int64_t splits = (stages + want - 1) / want;
+            const int64_t sps = (stages + splits - 1) / splits;
+            splits = (stages + sps - 1) / sps;                      // no empty slice
+            p.tiles_m[l] = ceil_div(sh[l].M, tile); p.tiles_n[l] = ceil_div(sh[l].N, tile);
+            p.splits[l] = (int)splits; p.sps[l] = (int)sps;
+            p.items += (int64_t)p.tiles_m[l] * p.tiles_n[l] * splits;
+            longest = longest > sps ? longest : sps;
+        }
+        const int64_t cost = ((p.items + 255) / 256) * (longest + kItemOverhead);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = p; }
+    }
+    return best;
+}
 bool dma_joint_ok(int T, int M, int N);
 size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B);
+// the same for 8-bit inputs (dp_tn_f8_dma.hip; 256 x 256 tiles, T a multiple of 64); A, G of JointOperands are byte pointers
+bool dma8_joint_ok(int T, int M, int N);
+size_t joint8_workspace_floats(const JointShape* sh, int n_layers, int B);
+hipError_t launch_clipped_f8_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
+                                       float stddev, uint64_t seed, float* ws, hipStream_t st, int fmt);
 // noise: stddev == 0 for none, else every layer's d_in * d_out and noise_offset are multiples of 4
 hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
                                          float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16);

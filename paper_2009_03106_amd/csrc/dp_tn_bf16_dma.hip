@@ -581,48 +581,9 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
 // ---- joint launch of several layers' clipped sums
 bool dma_joint_ok(int T, int M, int N) { return T > 0 && (T % DK) == 0 && dma_geometry(T, M, N) == 1; }
 
-namespace {
-
-struct JointPlan { int n_layers; int tiles_m[kJointMax], tiles_n[kJointMax], splits[kJointMax], sps[kJointMax]; int64_t items; };
-
-// One slice length for all layers (each layer rounds it to a whole number of equal slices), chosen to minimise
-//     rounds of 256 workgroups  x  (stages of the longest slice + what an item costs besides its stages):
-// slices long enough that their start-up, their store and their fold stay small, and a number of items that fills
-// the chip's 256 compute units a whole number of times.
-JointPlan plan_joint(const JointShape* sh, int n_layers, int B) {
-    constexpr int64_t kItemOverhead = 16;            // prologue + slice store + the slice's share of the fold, in stage times
-    JointPlan best{};
-    int64_t best_cost = -1;
-    int64_t stages_max = 1;
-    for (int l = 0; l < n_layers; ++l) stages_max = std::max(stages_max, (int64_t)B * (sh[l].T / DK));
-    for (int64_t S = 1; S <= 512 && S <= stages_max; ++S) {
-        const int64_t len = (stages_max + S - 1) / S;
-        if (len < 8 && S > 1) break;
-        JointPlan p{};
-        p.n_layers = n_layers;
-        int64_t longest = 0;
-        for (int l = 0; l < n_layers; ++l) {
-            const int64_t spe = sh[l].T / DK, stages = (int64_t)B * spe;
-            int64_t want = std::min(len, 63 * spe);       // a slice touches at most 64 examples (one clip factor per lane)
-            int64_t splits = (stages + want - 1) / want;
-            int64_t sps = (stages + splits - 1) / splits;
-            splits = (stages + sps - 1) / sps;            // no empty slice
-            p.tiles_m[l] = ceil_div(sh[l].M, GeoL::TM); p.tiles_n[l] = ceil_div(sh[l].N, GeoL::TN);
-            p.splits[l] = (int)splits; p.sps[l] = (int)sps;
-            p.items += (int64_t)p.tiles_m[l] * p.tiles_n[l] * splits;
-            longest = std::max(longest, sps);
-        }
-        const int64_t cost = ((p.items + 255) / 256) * (longest + kItemOverhead);
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = p; }
-    }
-    return best;
-}
-
-}  // namespace
-
 // floats of workspace: every layer's slices, one layer after the other
 size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B) {
-    const JointPlan p = plan_joint(sh, n_layers, B);
+    const JointPlan p = plan_joint(sh, n_layers, B, DK, GeoL::TM);
     size_t slices = 0;
     for (int l = 0; l < n_layers; ++l) slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
     return slices;
@@ -631,7 +592,7 @@ size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B) {
 hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
                                          float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16) {
     if (n_layers < 1 || n_layers > kJointMax) return hipErrorInvalidValue;
-    const JointPlan p = plan_joint(sh, n_layers, B);
+    const JointPlan p = plan_joint(sh, n_layers, B, DK, GeoL::TM);
     if (p.items >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     JointArgs j;
     float* slices = ws;

@@ -81,8 +81,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt8() { __builtin_amdgc
 // and reduced to one float per (example, tile) instead of being stored (Algorithm 3 / 4 without their output).
 // RAG: T is not a multiple of the 64-row stage.  Every example then takes ceil(T / 64) stages, and the rows past
 // its end in the last one are copied from the line of zeros (rows of zeros add nothing to the product).
+// `L`: the (slice, tile) pair of this workgroup among the layer's tiles * splits
 template <class GEO, int MODE, bool RAG, int FA, int FG>
-__global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a) {
+__device__ __forceinline__ void tn_f8_tile(const Dma8Args& a, const int L) {
     constexpr int NST = GEO::NST, FM = GEO::FM, FN = GEO::FN, NF = FM + FN;
     constexpr int RBA = GEO::RBA, RBG = GEO::RBG, IPA = GEO::IPA, IPG = GEO::IPG, LPS = GEO::LPS;
     constexpr int OPA = GEO::OPA, STAGE_BYTES = GEO::STAGE_BYTES;
@@ -91,9 +92,6 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles = a.tiles_m * a.tiles_n;
-    // workgroup b runs on XCD b % 8: give each XCD a contiguous run of (slice, tile) pairs so that
-    // its workgroups stream the same rows of A and G through one L2
-    const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
     if (L >= tiles * a.splits) return;
     const int z = L / tiles, tile = L - z * tiles;
     const int tm = tile / a.tiles_n, tn = tile - tm * a.tiles_n;
@@ -343,6 +341,41 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
 }
 
 
+template <class GEO, int MODE, bool RAG, int FA, int FG>
+__global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a) {
+    // workgroup b runs on XCD b % 8: give each XCD a contiguous run of (slice, tile) pairs so that
+    // its workgroups stream the same rows of A and G through one L2
+    tn_f8_tile<GEO, MODE, RAG, FA, FG>(a, (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3));
+}
+
+// Several layers' clipped sums in one launch (256 x 256 tiles, T a multiple of 64), as for the 16-bit inputs: a list
+// of (layer, K slice, tile) items, all layers' slices of about one length, filling the chip a whole number of times.
+struct Joint8Layer {
+    const unsigned char* A; const unsigned char* G; const float* clip;
+    float* slices;
+    int T, M, N, tiles_m, tiles_n, splits, stages_total, stages_per_split, first_item;
+};
+struct Joint8Args {
+    Joint8Layer layer[kJointLayers];
+    int n_layers, n_items, per_xcd, B;
+};
+template <int FA, int FG>
+__global__ __launch_bounds__(Geo8L::THREADS, Geo8L::OCC) void k_tn_f8_dma_joint(Joint8Args j) {
+    const int L = (blockIdx.x & 7) * j.per_xcd + (blockIdx.x >> 3);
+    if (L >= j.n_items) return;
+    int l = 0;
+    while (l + 1 < j.n_layers && L >= j.layer[l + 1].first_item) ++l;
+    const Joint8Layer& y = j.layer[l];
+    Dma8Args a;
+    a.A = y.A; a.G = y.G; a.clip = y.clip;
+    a.out = y.slices; a.slice = (((int64_t)y.M * y.N) + 3) & ~(int64_t)3;        // splitk_slice_elems
+    a.B = j.B; a.T = y.T; a.M = y.M; a.N = y.N;
+    a.tiles_m = y.tiles_m; a.tiles_n = y.tiles_n; a.splits = y.splits;
+    a.stages_total = y.stages_total; a.stages_per_split = y.stages_per_split;
+    a.per_xcd = 0; a.accumulate = 0; a.zero = nullptr;
+    tn_f8_tile<Geo8L, 0, false, FA, FG>(a, L - y.first_item);
+}
+
 // 0: not for this kernel; 1: Geo8L; 2: Geo8T
 int dma8_geometry(int T, int M, int N) {
     if (((M | N) & 15) != 0) return 0;
@@ -446,6 +479,53 @@ hipError_t launch_clipped_f8_dma(const TnPlan& p, const void* A, const void* G, 
     const hipError_t e = launch_any8<0>(p.big, a, p.zero_head, fmt, st);
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
+}
+
+// ---- joint launch of several layers' clipped sums
+bool dma8_joint_ok(int T, int M, int N) { return T > 0 && (T % DK8) == 0 && dma8_geometry(T, M, N) == 1; }
+
+size_t joint8_workspace_floats(const JointShape* sh, int n_layers, int B) {
+    const JointPlan p = plan_joint(sh, n_layers, B, DK8, Geo8L::TM);
+    size_t slices = 0;
+    for (int l = 0; l < n_layers; ++l) slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
+    return slices;
+}
+
+hipError_t launch_clipped_f8_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
+                                       float stddev, uint64_t seed, float* ws, hipStream_t st, int fmt) {
+    if (n_layers < 1 || n_layers > kJointLayers) return hipErrorInvalidValue;
+    const JointPlan p = plan_joint(sh, n_layers, B, DK8, Geo8L::TM);
+    if (p.items >= (int64_t(1) << 28)) return hipErrorInvalidValue;
+    Joint8Args j;
+    float* slices = ws;
+    int64_t first = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        Joint8Layer& y = j.layer[l];
+        y.A = reinterpret_cast<const unsigned char*>(op[l].A); y.G = reinterpret_cast<const unsigned char*>(op[l].G); y.clip = op[l].clip;
+        y.slices = slices;
+        y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
+        y.tiles_m = p.tiles_m[l]; y.tiles_n = p.tiles_n[l]; y.splits = p.splits[l];
+        y.stages_total = (int)((int64_t)B * (sh[l].T / DK8)); y.stages_per_split = p.sps[l];
+        y.first_item = (int)first;
+        first += (int64_t)p.tiles_m[l] * p.tiles_n[l] * p.splits[l];
+        slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
+    }
+    for (int l = n_layers; l < kJointLayers; ++l) j.layer[l] = j.layer[0];
+    j.n_layers = n_layers; j.n_items = (int)p.items; j.per_xcd = ceil_div(p.items, 8);
+    j.B = B;
+    const unsigned grid = 8u * (unsigned)j.per_xcd;
+    if (fmt == 2)      k_tn_f8_dma_joint<0, 0><<<grid, Geo8L::THREADS, 0, st>>>(j);
+    else if (fmt == 3) k_tn_f8_dma_joint<1, 1><<<grid, Geo8L::THREADS, 0, st>>>(j);
+    else if (fmt == 4) k_tn_f8_dma_joint<0, 1><<<grid, Geo8L::THREADS, 0, st>>>(j);
+    else return hipErrorInvalidValue;
+    hipError_t e = hipGetLastError();
+    // the folds of the layers' slices (+ noise), each as after a launch of the layer alone
+    for (int l = 0; l < n_layers && e == hipSuccess; ++l) {
+        const NoiseArgs nz{stddev, (uint32_t)seed, (uint32_t)(seed >> 32), op[l].noise_offset};
+        e = launch_splitk_reduce(j.layer[l].slices, (int64_t)sh[l].M * sh[l].N, p.splits[l], accumulate, op[l].grad, st,
+                                 stddev != 0.0f ? &nz : nullptr);
+    }
+    return e;
 }
 
 TnPlan plan_direct_f8_dma(int B, int T, int M, int N) {
