@@ -29,9 +29,9 @@ import numpy as np  # noqa: E402
 # `bench.py --calib-copy`, scaled by what the same counters read for the 1 GiB copy (see profiles/).
 # None until measured for the current kernels.
 MEASURED_TRAFFIC = {
-    # one dp_clipped_grad call (GEMM + split-K reduce), mean of the 4 layers: 286.3 + 65.5 MB read,
-    # 65.5 + 7.1 MB written (profiles/transformer_hbm_traffic.md)
-    "transformer": 424.4e6,
+    # the clipped-sum phase of one step: the launch that takes all four layers (1153.9 MB read, 198.2 MB written) and
+    # the four split-K folds (49.6 MB read, 7.1 MB written each) (profiles/transformer_hbm_traffic.md)
+    "transformer": 1578.8e6,
 }
 
 PEAK_HBM_GBS = 8000.0
@@ -327,7 +327,7 @@ def main():
     norm_ms, clip_ms, grad_ms, noise_ms = phases
     nlayers = len(w.layers)
     if grad_ms >= norm_ms:
-        flops, byts, dur_ms, kname = work["gemm_flops"], work["gemm_bytes"], grad_ms, "clipped-sum GEMM with its split-K reduce (and the noise that the reduce adds, where the configuration has noise)"
+        flops, byts, dur_ms, kname = work["gemm_flops"], work["gemm_bytes"], grad_ms, "clipped-sum GEMMs of all layers with their split-K folds (and the noise that the folds add, where the configuration has noise); aligned 16-bit / 8-bit layers share one GEMM launch"
     else:
         flops, byts, dur_ms, kname = work["norm_flops"], work["norm_bytes"], norm_ms, "squared-norm kernel (dp_layer_sqnorm)"
     peak_tf = PEAK_MFMA_TFLOPS[w.dtype]
@@ -339,8 +339,10 @@ def main():
         ach = byts / (dur_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
     traffic = MEASURED_TRAFFIC.get(w.name) if (args.batch is None and args.path == "auto" and args.dtype is None) else None
-    roof.update({"traffic": traffic, "kernel": kname, "launches_per_step": nlayers,
-                 "avg_launch_ms": dur_ms / nlayers,
+    # achieved / traffic are per step: the phase of the dominant kernel (for the transformer configuration one GEMM
+    # launch for the four layers and a fold per layer), timed with HIP events inside the timed steps
+    roof.update({"traffic": traffic, "kernel": kname, "layers_per_step": nlayers,
+                 "phase_ms": dur_ms,
                  "algorithmic_flops_per_step": flops, "algorithmic_bytes_per_step": byts})
 
     phases_out = {
