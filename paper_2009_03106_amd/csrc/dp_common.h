@@ -55,6 +55,12 @@ template <> struct In16<true> {                    // IEEE half
 __device__ __forceinline__ uint32_t pack_lo16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
 __device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
+// nu = 1 / max(1, sqrt(s) / C)   (clip function of Section 3.2); the max lets a NaN norm through
+__device__ __forceinline__ float clip_factor_of(float s, float C) {
+    const float m = sqrtf(s) / C;
+    return 1.0f / (!(m <= 1.0f) ? m : 1.0f);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);

@@ -26,6 +26,10 @@ struct GramArgs {
     float* partial;      // [B][npairs]
     int T, d_in, d_out;
     int nt, npairs;
+    // one tile pair per example (T <= 64): the kernel completes the norm itself, no second launch
+    float* sqnorm;       // nullptr: write partial[]
+    int accumulate;
+    float C; float* clip;
 };
 
 // Rows [row0, row0 + TT) x columns [k0, k0 + 64) of X_i[T, D] -> LDS tile (zero padded).
@@ -142,7 +146,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_gram_bf16(GramArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s += accP[i][j][r] * accQ[i][j][r];
     s = block_sum_256(s, red);
-    if (threadIdx.x == 0) a.partial[blockIdx.x] = diag ? s : 2.0f * s;
+    if (threadIdx.x == 0) {
+        const float v = diag ? s : 2.0f * s;
+        if (a.sqnorm) {
+            const float t = a.accumulate ? a.sqnorm[ex] + v : v;
+            a.sqnorm[ex] = t;
+            if (a.clip) a.clip[ex] = clip_factor_of(t, a.C);
+        } else {
+            a.partial[blockIdx.x] = v;
+        }
+    }
 }
 
 }  // namespace
@@ -163,11 +176,14 @@ hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t
     a.A = A; a.G = G; a.partial = partial;
     a.T = T; a.d_in = d_in; a.d_out = d_out;
     a.nt = p.nt; a.npairs = p.npairs;
+    const bool direct = p.npairs == 1;
+    a.sqnorm = direct ? sqnorm : nullptr; a.accumulate = accumulate ? 1 : 0;
+    a.C = co ? co->C : 0.f; a.clip = co ? co->clip : nullptr;
     const unsigned grid = (unsigned)((int64_t)B * p.npairs);
     if (p.tile == 64) { if (f16) k_gram_bf16<64, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16<64, false><<<grid, kThreads, 0, st>>>(a); }
     else              { if (f16) k_gram_bf16<128, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16<128, false><<<grid, kThreads, 0, st>>>(a); }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || direct) return e;
     return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st, co);
 }
 

@@ -12,11 +12,6 @@ namespace dpk {
 // reduction.  Rows whose length is not a multiple of the vector width (or
 // whose start is therefore unaligned) take the scalar loop.
 // ---------------------------------------------------------------------------
-// nu = 1 / max(1, sqrt(s) / C)   (clip function of Section 3.2); the max lets a NaN norm through
-__device__ __forceinline__ float clip_factor_of(float s, float C) {
-    const float m = sqrtf(s) / C;
-    return 1.0f / (!(m <= 1.0f) ? m : 1.0f);
-}
 
 // Sum of squares of one row by the `lpe` lanes (a power of two, 4 .. 64) that share an example; `sl` = this lane's
 // place among them.  Short rows get few lanes, so that a wave takes several examples at once and every lane has a
