@@ -231,6 +231,59 @@ def measured_peaks(torch, dp):
     return out
 
 
+def power_trace(pipe, torch, dp, seconds=2.0):
+    """Socket power and shader clock (amdsmi, sampled every 100 ms by a thread) while each phase of the step, and
+    each of the probe kernels, loops for `seconds`: tells whether a kernel runs at the part's clock limit or at its
+    power limit.  The first half second of every loop (the transient) is left out of the means."""
+    import threading
+    import amdsmi
+    amdsmi.amdsmi_init()
+    h = amdsmi.amdsmi_get_processor_handles()[0]
+    out = {"power_limit_w": amdsmi.amdsmi_get_power_info(h)["power_limit"] / 1e6}
+
+    def during(work):
+        rows, stop = [], threading.Event()
+
+        def sample():
+            while not stop.is_set():
+                rows.append((time.perf_counter(), amdsmi.amdsmi_get_power_info(h)["current_socket_power"],
+                             amdsmi.amdsmi_get_clock_info(h, amdsmi.AmdSmiClkType.GFX)["clk"]))
+                time.sleep(0.1)
+        th = threading.Thread(target=sample)
+        t0 = time.perf_counter()
+        th.start()
+        n = 0
+        while time.perf_counter() - t0 < seconds:
+            work()
+            n += 1
+            torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        stop.set()
+        th.join()
+        kept = [r for r in rows if r[0] - t0 > 0.5] or rows
+        return {"socket_power_w": float(np.mean([r[1] for r in kept])), "gfx_clock_mhz": float(np.mean([r[2] for r in kept])),
+                "samples": len(kept), "rounds_per_s": n / dt}
+
+    sink = torch.zeros(dp.PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    out["idle"] = during(lambda: time.sleep(0.05))
+    out["steps"] = during(lambda: [pipe.step() for _ in range(20)])
+    out["steps"]["ms_per_step"] = 1e3 / (20 * out["steps"].pop("rounds_per_s"))
+    out["sqnorm_phase"] = during(lambda: [pipe.phase_sqnorm() for _ in range(40)])
+    out["sqnorm_phase"]["ms"] = 1e3 / (40 * out["sqnorm_phase"].pop("rounds_per_s"))
+    out["clipped_grad_phase"] = during(lambda: [pipe.phase_grad() for _ in range(20)])
+    out["clipped_grad_phase"]["ms"] = 1e3 / (20 * out["clipped_grad_phase"].pop("rounds_per_s"))
+    for name, rnd in (("mfma_probe_random_operands", 1), ("mfma_probe_constant_operands", 0)):
+        flops = dp.probe_mfma(dp.DP_BF16, rnd, 12000, sink)
+        out[name] = during(lambda: dp.probe_mfma(dp.DP_BF16, rnd, 12000, sink))
+        out[name]["tflops"] = flops * out[name].pop("rounds_per_s") / 1e12
+    nbytes = dp.probe_read(src, sink)
+    out["hbm_read_probe"] = during(lambda: [dp.probe_read(src, sink) for _ in range(10)])
+    out["hbm_read_probe"]["gbs"] = 10 * nbytes * out["hbm_read_probe"].pop("rounds_per_s") / 1e9
+    out["idle"].pop("rounds_per_s")
+    return out
+
+
 def cpu_baseline(name, sample_B, threads=None):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     from oracle import dp_oracle as orc
@@ -275,6 +328,8 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--no-peaks", action="store_true", help="skip the probe kernels that measure what the part sustains")
     ap.add_argument("--peaks", action="store_true", help="only measure the peaks (probe kernels) and print them")
+    ap.add_argument("--power", action="store_true",
+                    help="only sample socket power and shader clock (amdsmi) while the phases and the probe kernels loop")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic) so that a rocprofv3 "
                          "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
@@ -308,6 +363,9 @@ def main():
     pipe = Pipeline(w, layers, torch, dp, args.path)
     del layers
     B = pipe.B
+    if args.power:
+        print(json.dumps({"workload": w.name, "dtype": w.dtype, "power": power_trace(pipe, torch, dp)}))
+        return
     # the same K steps after W warm-up steps straight from an idle device, without the spin-up that time_steps puts
     # in front (the power management's start-up transient is inside this figure; it is reported, not `value`)
     torch.cuda.synchronize()
