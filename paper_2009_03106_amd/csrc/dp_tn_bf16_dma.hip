@@ -123,7 +123,12 @@ __device__ __forceinline__ void tn_dma_tile(const DmaArgs& a, const int L) {
     const int tiles = a.tiles_m * a.tiles_n;
     if (L >= tiles * a.splits) return;
     const int z = L / tiles, tile = L - z * tiles;
-    const int tm = tile / a.tiles_n, tn = tile - tm * a.tiles_n;
+    // Consecutive items walk the short side of the tile grid first: the workgroups that run at the same time on an
+    // XCD then form a block of whole columns (or rows) of tiles, and a run of items that ends inside a slice's tile
+    // set leaves few panels of A and G to be fetched a second time by the items behind it.
+    int tm, tn;
+    if (a.tiles_m < a.tiles_n) { tn = tile / a.tiles_m; tm = tile - tn * a.tiles_m; }
+    else { tm = tile / a.tiles_n; tn = tile - tm * a.tiles_n; }
     const int m0 = tm * GEO::TM, n0 = tn * GEO::TN;
     const int s_begin = z * a.stages_per_split;
     const int s_end = min(a.stages_total, s_begin + a.stages_per_split);
