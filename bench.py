@@ -81,6 +81,8 @@ class Pipeline:
         self.descs_cg = dp.layer_descs(self.dev_cg, [self.grads[li] for li in order], [starts[li] for li in order])
         self.ws_cg_all = torch.empty(max(16, dp.layers_clipped_workspace_bytes(self.descs_cg[0], self.B, dt)), dtype=torch.uint8, device="cuda")
         self.ws_layers = torch.empty(max(16, dp.layers_workspace_bytes(self.descs[0], self.B, dt, path)), dtype=torch.uint8, device="cuda")
+        need = max(16, dp.layers_workspace_bytes(self.descs_cg[0], self.B, dt, path), self.ws_cg_all.numel())
+        self.ws_step = self.ws_cg_all if need <= self.ws_cg_all.numel() else torch.empty(need, dtype=torch.uint8, device="cuda")
 
     def phase_sqnorm(self):
         # all layers in one call: the copy-pipeline Gram layers share a launch, dense layers share one, and the
@@ -102,6 +104,11 @@ class Pipeline:
         pass                                                   # added in phase_grad
 
     def step(self, events=None):
+        if events is None:
+            # the whole step in one library call (dp_layers_step): the same launches as the two calls below
+            self.dp.layers_step(self.descs_cg, self.w.C, self.s, self.c, self.ws_step, path=self.path,
+                                noise_std=self.w.noise_std, seed=self.w.noise_seed)
+            return
         if events is not None:
             events[0].record()
         self.phase_sqnorm()

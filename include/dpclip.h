@@ -242,6 +242,26 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
                                        float stddev, uint64_t seed,
                                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* One private step over a model's layers in a single call (the body of Algorithm 1's
+ * loop after the backward pass: per-example norms, the factors nu_i, the clipped
+ * sum, the noise):  dp_layers_sqnorm_clip(layers, ..., accumulate = 0, sqnorm, C,
+ * clip, ...) followed by dp_layers_clipped_grad_noise(layers, ..., clip,
+ * accumulate = 0, stddev, seed, ...) on the same stream, with the same launches and
+ * bit-identical results; what it saves is one crossing of the boundary per step,
+ * which is what bounds models of a few small layers.
+ *   sqnorm, clip  device float32[B], written.
+ *   workspace     device scratch of at least the larger of
+ *                 dp_layers_workspace_bytes(...) and
+ *                 dp_layers_clipped_workspace_bytes(...) bytes; the two stages use
+ *                 it one after the other.
+ * Errors: the arguments of the norm stage are checked before anything is launched;
+ * if the clipped-sum stage then rejects its own (a layer without grad, a workspace
+ * too small for it), sqnorm and clip have already been written. */
+dp_status dp_layers_step(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
+                         dp_dtype dtype, dp_path path, float C, float* sqnorm, float* clip,
+                         float stddev, uint64_t seed,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Clip factors (Algorithm 1, the line defining nu_i; Eq. per_example_weight;
  * clip function of Section 3.2):
  *     clip[i] = 1 / max(1, sqrt(sqnorm[i]) / C)  =  min(1, C / ||g_i||),

@@ -881,6 +881,15 @@ dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, 
     return dp_layers_clipped_grad_noise(layers, n_layers, B, clip, dtype, accumulate, 0.0f, 0, workspace, workspace_bytes, hip_stream);
 }
 
+dp_status dp_layers_step(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path, float C,
+                         float* sqnorm, float* clip, float stddev, uint64_t seed, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    if (!clip || !(stddev >= 0.0f)) return DP_ERR_INVALID_ARG;
+    const dp_status st = dp_layers_sqnorm_clip(layers, n_layers, B, dtype, path, 0, sqnorm, C, clip, workspace, workspace_bytes, hip_stream);
+    if (st != DP_OK) return st;
+    return dp_layers_clipped_grad_noise(layers, n_layers, B, clip, dtype, 0, stddev, seed, workspace, workspace_bytes, hip_stream);
+}
+
 dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_layers, int64_t B, const float* clip, dp_dtype dtype,
                                        int accumulate, float stddev, uint64_t seed, void* workspace, size_t workspace_bytes,
                                        void* hip_stream) {

@@ -118,6 +118,35 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense_layers(DenseLayers t,
     }
 }
 
+// The same sums for a small batch: one workgroup per example, its lane groups take the 2 * n_layers rows of the example
+// (row 2 l: a_l,i; row 2 l + 1: g_l,i) side by side instead of one after the other, so that a model of a few layers
+// costs one or two memory round trips and not two per layer; the row sums meet in LDS and thread 0 adds the layers'
+// products in the order given.  Every row is summed by `lpe` lanes exactly as in the kernel above: same bits.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_sqnorm_dense_layers_rows(DenseLayers t, int accumulate, float* __restrict__ sqnorm,
+                                                                       float C, float* __restrict__ clip, int lpe) {
+    __shared__ float rs[2 * kDenseBatch];
+    const int ex = blockIdx.x, sl = threadIdx.x & (lpe - 1), groups = kThreads / lpe;
+    for (int r = threadIdx.x / lpe; r < 2 * t.n_layers; r += groups) {
+        const int l = r >> 1;
+        const int d = (r & 1) ? t.d_out[l] : t.d_in[l];
+        const void* base = (r & 1) ? t.G[l] : t.A[l];
+        float v;
+        if (DT != 0) v = row_sumsq_16<DT == 2>(static_cast<const uint16_t*>(base) + (size_t)ex * d, d, sl, lpe);
+        else         v = row_sumsq_f32(static_cast<const float*>(base) + (size_t)ex * d, d, sl, lpe);
+        if (sl == 0) rs[r] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int l = 0; l < t.n_layers; ++l) s += rs[2 * l] * rs[2 * l + 1];
+        s = accumulate ? sqnorm[ex] + s : s;
+        sqnorm[ex] = s;
+        if (clip) clip[ex] = clip_factor_of(s, C);
+    }
+}
+constexpr int kDenseRowsMaxB = 1024;     // beyond this the batch fills the chip with one wave per example
+
 // Short rows (every row of every layer at most 512 bytes, a whole number of 16-byte pieces): a lane holds at most one
 // piece of a row, so the loads of ITER examples per lane group are issued together before anything is added: rows of
 // a few hundred bytes otherwise leave one or two loads in flight per wave, far from what HBM needs.
@@ -188,6 +217,12 @@ hipError_t launch_sqnorm_dense_layers(const DenseLayers& t, int B, int dt, bool 
         if (dt == 2)      k_sqnorm_dense_short<2, kShortIter><<<g, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
         else if (dt == 1) k_sqnorm_dense_short<1, kShortIter><<<g, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
         else              k_sqnorm_dense_short<0, kShortIter><<<g, kThreads, 0, st>>>(t, B, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+        return hipGetLastError();
+    }
+    if (t.n_layers > 1 && B <= kDenseRowsMaxB) {
+        if (dt == 2)      k_sqnorm_dense_layers_rows<2><<<B, kThreads, 0, st>>>(t, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+        else if (dt == 1) k_sqnorm_dense_layers_rows<1><<<B, kThreads, 0, st>>>(t, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
+        else              k_sqnorm_dense_layers_rows<0><<<B, kThreads, 0, st>>>(t, accumulate ? 1 : 0, sqnorm, C, clip, lpe);
         return hipGetLastError();
     }
     const int64_t per_block = (int64_t)(kThreads / kWave) * (kWave / lpe);

@@ -154,12 +154,14 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
 // fills only (d_in / 64)(d_out / 64) compute units; here a wave runs K / 8 and there are four times as many
 // workgroups.  No K slices: the whole sum is finished in the kernel.
 constexpr int SBK = 64, STM = 32, STN = 32;
+#define SHORT_LDS                                                          \
+    __shared__ __attribute__((aligned(16))) float sA[SBK][STM];            \
+    __shared__ __attribute__((aligned(16))) float sG[SBK][STN];            \
+    __shared__ __attribute__((aligned(16))) float part[4][STM][STN + 1]
 template <bool VEC>
-__device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile) {
+__device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile, float (*sA)[STM], float (*sG)[STN],
+                                                  float (*part)[STM][STN + 1]) {
     constexpr int NV = 2;               // float4 pieces of either operand per thread and stage
-    __shared__ __attribute__((aligned(16))) float sA[SBK][STM];
-    __shared__ __attribute__((aligned(16))) float sG[SBK][STN];
-    __shared__ __attribute__((aligned(16))) float part[4][STM][STN + 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tm = tile / a.tiles_n, tn = tile % a.tiles_n;
@@ -181,57 +183,66 @@ __device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
-    float xa[NV][4], xg[NV][4], cl[NV];
-    bool inr[NV];
-    auto fetch = [&](int k0) {
+    // The loads of GS stages (256 rows: a whole contraction of the dense configurations) are issued before any of
+    // them is used, so that a workgroup waits for memory once per 256 rows and not once per stage: with K = B = 256
+    // the kernel is one memory latency, four short MFMA chains and the epilogue.
+    constexpr int GS = 4;
+    float xa[GS][NV][4], xg[GS][NV][4], cl[GS][NV];
+    auto fetch = [&](int g, int k0) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int row = k0 + lr + 32 * v;
-            inr[v] = row < k_end;
-            const int rc = inr[v] ? row : k_end - 1;
+            const int rc = row < k_end ? row : k_end - 1;
             const float* pa = a.A + (size_t)rc * a.M;
             const float* pg = a.G + (size_t)rc * a.N;
             if (VEC) {
                 const float4 qa = *reinterpret_cast<const float4*>(pa + colA[0]);
                 const float4 qg = *reinterpret_cast<const float4*>(pg + colG[0]);
-                xa[v][0] = qa.x; xa[v][1] = qa.y; xa[v][2] = qa.z; xa[v][3] = qa.w;
-                xg[v][0] = qg.x; xg[v][1] = qg.y; xg[v][2] = qg.z; xg[v][3] = qg.w;
+                xa[g][v][0] = qa.x; xa[g][v][1] = qa.y; xa[g][v][2] = qa.z; xa[g][v][3] = qa.w;
+                xg[g][v][0] = qg.x; xg[g][v][1] = qg.y; xg[g][v][2] = qg.z; xg[g][v][3] = qg.w;
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) { xa[v][j] = pa[colA[j]]; xg[v][j] = pg[colG[j]]; }
+                for (int j = 0; j < 4; ++j) { xa[g][v][j] = pa[colA[j]]; xg[g][v][j] = pg[colG[j]]; }
             }
-            cl[v] = a.clip[a.T == 1 ? rc : rc / a.T];
+            cl[g][v] = a.clip[a.T == 1 ? rc : rc / a.T];
         }
     };
-    auto commit = [&]() {
+    auto commit = [&](int g, int k0) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
+            const bool inr = k0 + lr + 32 * v < k_end;
             float ya[4], yg[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                ya[j] = (inr[v] && okA[j]) ? xa[v][j] * cl[v] : 0.f;
-                yg[j] = (inr[v] && okG[j]) ? xg[v][j] : 0.f;
+                ya[j] = (inr && okA[j]) ? xa[g][v][j] * cl[g][v] : 0.f;
+                yg[j] = (inr && okG[j]) ? xg[g][v][j] : 0.f;
             }
             *reinterpret_cast<float4*>(&sA[lr + 32 * v][lc]) = make_float4(ya[0], ya[1], ya[2], ya[3]);
             *reinterpret_cast<float4*>(&sG[lr + 32 * v][lc]) = make_float4(yg[0], yg[1], yg[2], yg[3]);
         }
     };
 
-    if (k_end > 0) fetch(0);
-    for (int k0 = 0; k0 < k_end; k0 += SBK) {
-        commit();
-        __syncthreads();
-        if (k0 + SBK < k_end) fetch(k0 + SBK);
-        float fa[8], fb[8];
+    for (int kg = 0; kg < k_end; kg += GS * SBK) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            fa[j] = sA[wave * 16 + j * 2 + lhalf][lrow];
-            fb[j] = sG[wave * 16 + j * 2 + lhalf][lrow];
+        for (int g = 0; g < GS; ++g)
+            if (kg + g * SBK < k_end) fetch(g, kg + g * SBK);
+#pragma unroll
+        for (int g = 0; g < GS; ++g) {
+            const int k0 = kg + g * SBK;
+            if (k0 >= k_end) break;
+            commit(g, k0);
+            __syncthreads();
+            float fa[8], fb[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                fa[j] = sA[wave * 16 + j * 2 + lhalf][lrow];
+                fb[j] = sG[wave * 16 + j * 2 + lhalf][lrow];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], acc, 0, 0, 0);
+            __syncthreads();
         }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], acc, 0, 0, 0);
-        __syncthreads();
     }
 
     // accumulator element r of a lane: row 8 (r / 4) + 4 lhalf + r % 4, column lrow of the 32 x 32 tile
@@ -252,18 +263,23 @@ __device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile) {
 }
 
 template <bool VEC>
-__global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) { tn_f32_short_tile<VEC>(a, blockIdx.x); }
+__global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) {
+    SHORT_LDS;
+    tn_f32_short_tile<VEC>(a, blockIdx.x, sA, sG, part);
+}
 
 // The same for several layers in one launch (a model of small dense layers is a chain of launches of a few
 // microseconds each otherwise): the layers' tiles form one list, in the order given.
 constexpr int kShortBatch = 8;
 struct TnShortLayers { int n_layers; int first_tile[kShortBatch + 1]; TnArgsF layer[kShortBatch]; };
-template <bool VEC>
 __global__ __launch_bounds__(kThreads) void k_tn_f32_short_layers(TnShortLayers t) {
+    SHORT_LDS;
     int li = 0;
     while (li + 1 < t.n_layers && (int)blockIdx.x >= t.first_tile[li + 1]) ++li;
     const TnArgsF a = t.layer[li];
-    tn_f32_short_tile<VEC>(a, (int)blockIdx.x - t.first_tile[li]);
+    // 16-byte loads for the layers whose widths allow them (a 256 -> 10 head must not cost the wide layers theirs)
+    if (((a.M | a.N) & 3) == 0) tn_f32_short_tile<true>(a, (int)blockIdx.x - t.first_tile[li], sA, sG, part);
+    else                        tn_f32_short_tile<false>(a, (int)blockIdx.x - t.first_tile[li], sA, sG, part);
 }
 
 // the short-contraction kernel takes K up to this many rows
@@ -343,24 +359,27 @@ hipError_t launch_clipped_f32_short_layers(const ShortLayerDesc* layers, int n_l
     if (n_layers < 1 || n_layers > kShortBatch) return hipErrorInvalidValue;
     TnShortLayers t;
     t.n_layers = n_layers;
-    bool vec = true;
     int64_t first = 0;
+    // the layers that cannot use 16-byte loads first: their workgroups take about twice as long, and the workgroups of
+    // a launch start in the order of their ids (536 of them for the MLP configuration start over several microseconds)
+    int order[kShortBatch], no = 0;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int l = 0; l < n_layers; ++l)
+            if ((((layers[l].M | layers[l].N) & 3) != 0) == (pass == 0)) order[no++] = l;
     for (int l = 0; l < kShortBatch; ++l) {
         t.first_tile[l] = (int)first;
         if (l >= n_layers) { t.layer[l] = TnArgsF{nullptr, nullptr, nullptr, nullptr, 0, 0, 1, 0, 0, 0, 0, 0, 0}; continue; }
-        const ShortLayerDesc& y = layers[l];
+        const ShortLayerDesc& y = layers[order[l]];
         TnArgsF& a = t.layer[l];
         a.A = y.A; a.G = y.G; a.clip = y.clip;
         a.K = B * y.T; a.T = y.T; a.M = y.M; a.N = y.N;
         a.tiles_m = ceil_div(y.M, STM); a.tiles_n = ceil_div(y.N, STN); a.kchunk = a.K;
         a.out = y.grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0;
-        vec = vec && ((y.M | y.N) & 3) == 0;
         first += (int64_t)a.tiles_m * a.tiles_n;
         if (first >= (int64_t(1) << 31)) return hipErrorInvalidValue;
     }
     t.first_tile[kShortBatch] = (int)first;
-    if (vec) k_tn_f32_short_layers<true><<<(unsigned)first, kThreads, 0, st>>>(t);
-    else     k_tn_f32_short_layers<false><<<(unsigned)first, kThreads, 0, st>>>(t);
+    k_tn_f32_short_layers<<<(unsigned)first, kThreads, 0, st>>>(t);
     return hipGetLastError();
 }
 

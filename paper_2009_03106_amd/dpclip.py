@@ -23,7 +23,7 @@ DP_OP_SQNORM, DP_OP_CLIPPED_GRAD = 0, 1
 _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
 EXPORTS = ("dp_layer_sqnorm", "dp_layer_sqnorm_static", "dp_layers_sqnorm", "dp_layers_sqnorm_clip", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
-           "dp_layers_clipped_grad_noise", "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
+           "dp_layers_clipped_grad_noise", "dp_layers_step", "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
            "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw",
            "dp_clipped_grad_rounds_inputs")
 
@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.dp_layers_clipped_grad.restype = ci
     lib.dp_layers_clipped_grad_noise.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, vp, ci, ci, f32, u64, vp, sz, vp]
     lib.dp_layers_clipped_grad_noise.restype = ci
+    lib.dp_layers_step.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci, ci, f32, vp, vp, f32, u64, vp, sz, vp]
+    lib.dp_layers_step.restype = ci
     lib.dp_layers_clipped_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i64, i64, ci]
     lib.dp_layers_clipped_workspace_bytes.restype = sz
     lib.dp_clip_factors.argtypes = [vp, i64, f32, vp, vp]
@@ -403,6 +405,19 @@ def layers_clipped_grad(layers, clip: torch.Tensor, grads=None, *, accumulate: b
                                           0 if ws is None else ws.numel() * ws.element_size(), _stream_ptr(stream))
     _check(st, "dp_layers_clipped_grad_noise")
     return grads
+
+
+def layers_step(descs, C: float, sqnorm: torch.Tensor, clip: torch.Tensor, workspace: torch.Tensor, *, path: str = "auto",
+                noise_std: float = 0.0, seed: int = 0, stream: Optional[torch.cuda.Stream] = None):
+    """Norms, clip factors, clipped sums and noise of all layers in one call (dp_layers_step).  descs: the result of
+    layer_descs(layers, grads, ...); workspace: at least max(layers_workspace_bytes, layers_clipped_workspace_bytes) bytes."""
+    lib = load_library()
+    arr, B, dt = descs
+    _on_stream(stream, None)
+    st = lib.dp_layers_step(arr, len(arr), B, dt, _PATHS[path], float(C), _f32(sqnorm, (B,), "sqnorm"), _f32(clip, (B,), "clip"),
+                            float(noise_std), int(seed) & (2 ** 64 - 1), _ptr(workspace),
+                            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(st, "dp_layers_step")
 
 
 def clip_factors(sqnorm: torch.Tensor, C: float, clip: Optional[torch.Tensor] = None, *,

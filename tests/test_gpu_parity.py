@@ -1204,3 +1204,40 @@ def test_noise_moments(dp):
     assert abs(z.mean().item()) < 4.0 / np.sqrt(n)
     assert abs(z.var().item() - 1.0) < 3e-3
     assert abs((z ** 4).mean().item() - 3.0) < 2e-2
+
+
+@pytest.mark.parametrize("name", ["dense", "mlp", "rnn"])
+def test_layers_step_equals_the_two_calls(dp, name):
+    """dp_layers_step = dp_layers_sqnorm_clip then dp_layers_clipped_grad_noise: same launches, so the norms, the
+    factors and the (noisy) clipped sums are bit for bit those of the two calls, and they match the oracle."""
+    w, layers = wl.generate(name)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    B = dev[0][0].shape[0]
+    std, seed = 0.7, 1234
+    sizes = [A.shape[-1] * G.shape[-1] for A, G in dev]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+
+    def run(fused):
+        flat = torch.zeros(sum(sizes), dtype=torch.float32, device="cuda")
+        grads = [flat[starts[i]:starts[i + 1]].view(dev[i][0].shape[-1], dev[i][1].shape[-1]) for i in range(len(dev))]
+        descs = dp.layer_descs(dev, grads, starts[:-1])
+        arr, _, dt = descs
+        ws = torch.empty(max(16, dp.layers_workspace_bytes(arr, B, dt, "auto"), dp.layers_clipped_workspace_bytes(arr, B, dt)),
+                         dtype=torch.uint8, device="cuda")
+        s = torch.zeros(B, device="cuda")
+        c = torch.zeros(B, device="cuda")
+        if fused:
+            dp.layers_step(descs, w.C, s, c, ws, noise_std=std, seed=seed)
+        else:
+            dp.layers_sqnorm(dev, s, workspace=ws, descs=descs, C=w.C, clip=c)
+            dp.layers_clipped_grad(dev, c, workspace=ws, descs=descs, noise_std=std, seed=seed)
+        torch.cuda.synchronize()
+        return s.cpu().numpy(), c.cpu().numpy(), flat.cpu().numpy()
+
+    s1, c1, g1 = run(True)
+    s2, c2, g2 = run(False)
+    assert np.array_equal(s1, s2) and np.array_equal(c1, c2) and np.array_equal(g1, g2)
+    s_ref, c_ref, g_ref = orc.run_pipeline(layers, w.C, std, seed)
+    assert rel_err(s1, s_ref) <= SQ_TIGHT[w.dtype]
+    assert rel_err(c1, c_ref) <= SQ_TOL[w.dtype]
+    assert fro_err(g1, np.concatenate([g.ravel() for g in g_ref])) <= FRO_TOL[w.dtype]
