@@ -548,27 +548,32 @@ def main():
                             "clipped_grad_gbs": wk2["gemm_bytes"] / (ph2[2] * 1e-3) / 1e9}
             # the same step captured once into a HIP graph and replayed (the library neither allocates nor
             # synchronises, so a step is capturable): takes the host's launch rate out of the small configurations
-            try:
-                side = torch.cuda.Stream()
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.stream(side):
-                    p2.step()
-                    side.synchronize()
-                    with torch.cuda.graph(graph, stream=side):
+            # once as a graph of one step and once as a graph of 16 steps: a replay costs the runtime about 10 us
+            # whatever the graph holds, which a one-step graph of a 10-20 us step cannot win back
+            for n_in_graph, key in ((1, "ms_per_step_graph"), (16, "ms_per_step_graph_of_16_steps")):
+                try:
+                    side = torch.cuda.Stream()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.stream(side):
                         p2.step()
-                torch.cuda.synchronize()
-                for _ in range(5):
-                    graph.replay()
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                for _ in range(50):
-                    graph.replay()
-                torch.cuda.synchronize()
-                others[name]["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / 50
-                del graph
-            except Exception as exc:          # reported, never fatal for the benchmark line
-                others[name]["ms_per_step_graph"] = None
-                others[name]["graph_error"] = str(exc)[:200]
+                        side.synchronize()
+                        with torch.cuda.graph(graph, stream=side):
+                            for _ in range(n_in_graph):
+                                p2.step()
+                    torch.cuda.synchronize()
+                    for _ in range(5):
+                        graph.replay()
+                    torch.cuda.synchronize()
+                    reps = max(4, 64 // n_in_graph)
+                    t0 = time.perf_counter()
+                    for _ in range(reps):
+                        graph.replay()
+                    torch.cuda.synchronize()
+                    others[name][key] = (time.perf_counter() - t0) * 1e3 / (reps * n_in_graph)
+                    del graph
+                except Exception as exc:          # reported, never fatal for the benchmark line
+                    others[name][key] = None
+                    others[name]["graph_error"] = str(exc)[:200]
             # the same with cold caches (the timings above are back-to-back steps over inputs that fit the caches)
             pc = time_steps_cold(p2, torch, 10, flush)
             others[name]["cold"] = {"sqnorm_ms": pc[0], "clipped_grad_ms": pc[2],
