@@ -71,7 +71,7 @@ struct TnPlan {
     int epu;                // segmented: examples per K slice
     bool big;               // 16-bit clipped sum only: 256 x 256 tiles, one workgroup per compute unit
     bool zero_head = false; // the kernel needs a line of zeros: the first kZeroHeadFloats floats of the workspace are set aside for it
-    bool dma;               // 16-bit inputs only: copy-pipeline kernel (direct-to-LDS copies, transposing LDS reads); tile_m x tile_n names its geometry
+    bool dma;               // copy-pipeline kernel (direct-to-LDS copies); tile_m x tile_n names its geometry (16-bit inputs) or is 128 x 128 (float32)
 };
 constexpr int kZeroHeadFloats = 64;   // 256 bytes
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
@@ -83,6 +83,13 @@ bool dma_conv_ok(const ConvGeom& g, int d_out);
 bool dma_clipped_ok(int B, int T, int M, int N);
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N);
 TnPlan plan_direct_f32(int T, int M, int N);
+// float32 copy-pipeline kernel (dp_tn_f32_dma.hip): 128 x 128 tiles, 16-row stages; the plans above choose it (dma = true)
+// for long contractions of shapes it fits
+bool f32_dma_ok(int64_t K, int M, int N);
+int f32_dma_tile();
+int f32_dma_stage_rows();
+hipError_t launch_tn_f32_dma(int mode, const TnPlan& p, const float* A, const float* G, const float* clip, int B, int T,
+                             int M, int N, float* out, int64_t slice, bool accumulate, hipStream_t st);
 
 // The 16-bit launchers below take bf16 bits, or fp16 bits when f16 is set.
 // out: splits == 1 -> nullptr workspace allowed and the tile goes straight to `grad` (overwrite

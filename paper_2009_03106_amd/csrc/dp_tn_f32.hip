@@ -302,6 +302,33 @@ TnPlan plan_clipped_f32(int B, int T, int M, int N) {
         p.splits = 1; p.kchunk = (int)K;
         return p;
     }
+    if (f32_dma_ok(K, M, N) && K < (int64_t(1) << 31)) {
+        // 128 x 128 tiles on the copy pipeline: two workgroups per compute unit, slices of at least 16 stages
+        const int t = f32_dma_tile(), dk = f32_dma_stage_rows();
+        p.dma = true;
+        p.tile_m = p.tile_n = t;
+        p.tiles_m = ceil_div(M, t); p.tiles_n = ceil_div(N, t);
+        const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+        // K slices: the (tile, slice) items run 512 at a time (two workgroups per compute unit); an item costs its
+        // stages plus about 16 stage times of start-up, store and fold.  Take the slice count with the smallest
+        // rounds x (stages per slice + 16): a count that just spills into one more round (540 items) costs a whole
+        // extra round, many short slices cost their overheads.
+        const int64_t stages = (K + dk - 1) / dk;
+        int64_t max_splits = stages / 16;
+        if (max_splits < 1) max_splits = 1;
+        if (max_splits > 256) max_splits = 256;
+        int64_t best = 1, best_cost = -1;
+        for (int64_t sp = 1; sp <= max_splits; ++sp) {
+            const int64_t sps = (stages + sp - 1) / sp, real = (stages + sps - 1) / sps;
+            const int64_t rounds = (tiles * real + 511) / 512;
+            const int64_t cost = rounds * (sps + 16);
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sp; }
+        }
+        const int64_t kchunk = ((stages + best - 1) / best) * dk;
+        p.kchunk = (int)kchunk;
+        p.splits = (int)((K + kchunk - 1) / kchunk);
+        return p;
+    }
     p.tile_m = FBM; p.tile_n = FBN;
     p.tiles_m = ceil_div(M, FBM); p.tiles_n = ceil_div(N, FBN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
@@ -320,9 +347,16 @@ TnPlan plan_clipped_f32(int B, int T, int M, int N) {
 }
 
 TnPlan plan_direct_f32(int T, int M, int N) {
-    (void)T;
     TnPlan p;
     p.segmented = false; p.epu = 0; p.big = false; p.dma = false;
+    if (f32_dma_ok(T, M, N)) {
+        const int t = f32_dma_tile();
+        p.dma = true;
+        p.tile_m = p.tile_n = t;
+        p.tiles_m = ceil_div(M, t); p.tiles_n = ceil_div(N, t);
+        p.splits = 1; p.kchunk = 0;
+        return p;
+    }
     p.tile_m = FBM; p.tile_n = FBN;
     p.tiles_m = ceil_div(M, FBM); p.tiles_n = ceil_div(N, FBN);
     p.splits = 1; p.kchunk = 0;
@@ -339,6 +373,11 @@ hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, c
     const int64_t n = (int64_t)M * N;
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
+    if (p.dma) {
+        hipError_t e = launch_tn_f32_dma(0, p, A, G, clip, B, T, M, N, a.out, a.slice, a.accumulate != 0, st);
+        if (e != hipSuccess || p.splits == 1) return e;
+        return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
+    }
     if (p.tile_m == STM) {
         a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0;
         const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n);
@@ -391,6 +430,17 @@ hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, in
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.kchunk = 0;
     a.slice = 0; a.accumulate = 0;
     const int tiles = p.tiles_m * p.tiles_n;
+    if (p.dma) {
+        // one launch of (example, tile) items; batches beyond the 32-bit item count go in pieces
+        const int64_t per = ((int64_t(1) << 30) / tiles);
+        for (int64_t b0 = 0; b0 < B; b0 += per) {
+            const int nb = (int)((B - b0 < per) ? (B - b0) : per);
+            hipError_t e = launch_tn_f32_dma(1, p, A + (size_t)b0 * T * M, G + (size_t)b0 * T * N, nullptr, nb, T, M, N,
+                                             partial + (size_t)b0 * tiles, 0, false, st);
+            if (e != hipSuccess) return e;
+        }
+        return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
+    }
     for (int b0 = 0; b0 < B; b0 += 65535) {
         const int nb = (B - b0 < 65535) ? (B - b0) : 65535;
         a.A = A + (size_t)b0 * T * M;

@@ -1241,3 +1241,32 @@ def test_layers_step_equals_the_two_calls(dp, name):
     assert rel_err(s1, s_ref) <= SQ_TIGHT[w.dtype]
     assert rel_err(c1, c_ref) <= SQ_TOL[w.dtype]
     assert fro_err(g1, np.concatenate([g.ravel() for g in g_ref])) <= FRO_TOL[w.dtype]
+
+
+# float32 copy-pipeline kernel (128 x 128 tiles, 16-row stages): T = 1 with a ragged last stage, sequence lengths that
+# do and do not divide the stage, one K slice (the tile goes straight to the gradient) and many, ragged tile edges
+F32_DMA_SHAPES = [(300, 1, 784, 512), (64, 24, 256, 384), (3, 512, 768, 768), (40, 7, 232, 248), (2, 1000, 1024, 128),
+                  (16, 16, 256, 256), (1, 256, 128, 128), (1200, 1, 128, 640)]
+
+
+@pytest.mark.parametrize("B,T,d_in,d_out", F32_DMA_SHAPES)
+def test_f32_copy_pipeline_shapes(dp, B, T, d_in, d_out):
+    A, G = wl.random_layer(77 + B + T + d_in, B, T, d_in, d_out, "f32", g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    C = float(np.sqrt(np.median(s_ref))) if B > 1 else float(np.sqrt(s_ref[0]) / 3)
+    Ad, Gd = to_dev(A), to_dev(G)
+    for path in (["auto"] if T == 1 else ["direct", "gram"]):
+        s = dp.layer_sqnorm(Ad, Gd, path=path)
+        assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["f32"], (path, rel_err(s.cpu().numpy(), s_ref))
+    factors = [orc.clip_factors(s_ref, C).astype(np.float32)]
+    if B >= 9:
+        pats = _factor_patterns(B, np.random.default_rng(B + T))
+        factors += [pats["zero first/middle/last"], pats["mixed"], pats["all zero"]]
+    for c in factors:
+        cd = torch.from_numpy(np.ascontiguousarray(c, dtype=np.float32)).cuda()
+        g = dp.clipped_grad(Ad, Gd, cd)
+        got = g.cpu().numpy()
+        check_clipped_sum(dp, A, G, c, got, "f32", (B, T, d_in, d_out))
+        g2 = torch.full_like(g, 0.25)
+        dp.clipped_grad(Ad, Gd, cd, g2, accumulate=True)
+        np.testing.assert_allclose(g2.cpu().numpy(), got + np.float32(0.25), rtol=0, atol=1e-6 * (1 + np.abs(got).max()))
