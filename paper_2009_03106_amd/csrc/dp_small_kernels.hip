@@ -21,13 +21,20 @@ __device__ __forceinline__ float group_sum(float v, int lpe) {
     return v;
 }
 
+// The 16-byte loads of four steps of the row are issued together, from clamped (valid) positions and without a branch
+// between them, and added in the order of the plain loop: a guarded load per step costs a memory round trip each.
 __device__ __forceinline__ float row_sumsq_f32(const float* __restrict__ row, int d, int sl, int lpe) {
     float acc = 0.f;
     if ((d & 3) == 0) {
         const float4* r4 = reinterpret_cast<const float4*>(row);
-        for (int c = sl; c < (d >> 2); c += lpe) {
-            float4 v = r4[c];
-            acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        const int n4 = d >> 2;
+        for (int c0 = sl; c0 < n4; c0 += 4 * lpe) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = r4[min(c0 + u * lpe, n4 - 1)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (c0 + u * lpe < n4) acc += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
         }
     } else {
         for (int c = sl; c < d; c += lpe) { float v = row[c]; acc += v * v; }
@@ -40,13 +47,20 @@ __device__ __forceinline__ float row_sumsq_16(const uint16_t* __restrict__ row, 
     float acc = 0.f;
     if ((d & 7) == 0) {
         const uint4* r8 = reinterpret_cast<const uint4*>(row);
-        for (int c = sl; c < (d >> 3); c += lpe) {
-            uint4 v = r8[c];
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const int n8 = d >> 3;
+        for (int c0 = sl; c0 < n8; c0 += 4 * lpe) {
+            uint4 v[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float lo = In16<F16>::lo(w[j]), hi = In16<F16>::hi(w[j]);
-                acc += lo * lo + hi * hi;
+            for (int u = 0; u < 4; ++u) v[u] = r8[min(c0 + u * lpe, n8 - 1)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (c0 + u * lpe >= n8) continue;
+                const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float lo = In16<F16>::lo(w[j]), hi = In16<F16>::hi(w[j]);
+                    acc += lo * lo + hi * hi;
+                }
             }
         }
     } else {
@@ -178,9 +192,13 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm_dense_short(DenseLayers t, 
 #pragma unroll
         for (int k = 0; k < ITER; ++k) {
             const int64_t ex = ex0 + (int64_t)k * epw;
-            a[k] = make_uint4(0u, 0u, 0u, 0u); g[k] = a[k];
-            if (ex < B && sl * 16 < rba) a[k] = *reinterpret_cast<const uint4*>(A + (size_t)ex * rba + sl * 16);
-            if (ex < B && sl * 16 < rbg) g[k] = *reinterpret_cast<const uint4*>(G + (size_t)ex * rbg + sl * 16);
+            // unconditional loads from clamped positions, zeroed afterwards: no branch between the 2 ITER loads
+            const size_t exc = (size_t)(ex < B ? ex : B - 1);
+            const uint4 ra = *reinterpret_cast<const uint4*>(A + exc * rba + (sl * 16 < rba ? sl * 16 : 0));
+            const uint4 rg = *reinterpret_cast<const uint4*>(G + exc * rbg + (sl * 16 < rbg ? sl * 16 : 0));
+            const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+            a[k] = (ex < B && sl * 16 < rba) ? ra : zero;
+            g[k] = (ex < B && sl * 16 < rbg) ? rg : zero;
         }
 #pragma unroll
         for (int k = 0; k < ITER; ++k) s[k] += group_sum(piece_sumsq<DT>(a[k]), lpe) * group_sum(piece_sumsq<DT>(g[k]), lpe);
