@@ -307,7 +307,7 @@ dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
  *   G          device, [B,T,d_out] of `dtype`, read only
  *   bias_rows  device, float32[B, d_out], written; keep it for dp_clipped_bias_grad
  *   sqnorm     device, float32[B]
- * B must be < 65536 (DP_ERR_UNSUPPORTED otherwise).  No workspace. */
+ * No workspace. */
 dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
                          dp_dtype dtype, int accumulate, float* sqnorm,
                          float* bias_rows, void* hip_stream);
@@ -319,7 +319,7 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out,
  *     beta_rows[i, :]  = sum_t G_i[t, :]
  *     sqnorm[i] = (accumulate ? sqnorm[i] : 0) + ||gamma_rows[i]||^2 + ||beta_rows[i]||^2
  * gamma_rows, beta_rows: device float32[B, d], written; their clipped sums
- * are two calls of dp_clipped_bias_grad.  B must be < 65536.  No workspace.
+ * are two calls of dp_clipped_bias_grad.  No workspace.
  * With the 8-bit pair type DP_F8_E4M3_E5M2, G is e5m2 and Hbar e4m3. */
 dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_t T, int64_t d,
                               dp_dtype dtype, int accumulate, float* sqnorm,

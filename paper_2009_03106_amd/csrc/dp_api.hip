@@ -378,7 +378,6 @@ dp_status dp_bias_sqnorm(const void* G, int64_t B, int64_t T, int64_t d_out, dp_
     dp_status st = check_dims(B, T, 1, d_out);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
-    if (B >= 65536) return DP_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (B == 0) return DP_OK;
     if (!sqnorm) return DP_ERR_INVALID_ARG;
@@ -405,7 +404,6 @@ dp_status dp_layernorm_sqnorm(const void* G, const void* Hbar, int64_t B, int64_
     dp_status st = check_dims(B, T, 1, d);
     if (st != DP_OK) return st;
     if (!valid_dtype(dtype)) return DP_ERR_INVALID_ARG;
-    if (B >= 65536) return DP_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (B == 0) return DP_OK;
     if (!sqnorm) return DP_ERR_INVALID_ARG;
@@ -577,7 +575,6 @@ dp_status check_layers(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
         if (st != DP_OK) return st;
         if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (pointers && (!y.A || !y.G || !aligned16(y.A) || !aligned16(y.G))) return DP_ERR_INVALID_ARG;
-        if (pointers && y.bias_rows && B > 65535) return DP_ERR_UNSUPPORTED;                      // as dp_bias_sqnorm
     }
     return DP_OK;
 }

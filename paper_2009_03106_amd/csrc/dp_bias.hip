@@ -235,14 +235,25 @@ template <int DT, int DTH = DT> void launch_bias_rows_dt(const void* G, const vo
 // Hb == nullptr: u = column sums of G.  Otherwise u = column sums of G (*) Hb and u2 = column sums of G.
 // dt: type of G and Hb as above; 5: G e5m2 with Hb e4m3.
 hipError_t launch_bias_rows(const void* G, const void* Hb, int B, int T, int D, int dt, float* u, float* u2, hipStream_t st) {
-    if (B > 65535) return hipErrorInvalidValue;          // grid.y
-    if (dt == 5)      launch_bias_rows_dt<4, 3>(G, Hb, B, T, D, u, u2, st);
-    else if (dt == 4) launch_bias_rows_dt<4>(G, Hb, B, T, D, u, u2, st);
-    else if (dt == 3) launch_bias_rows_dt<3>(G, Hb, B, T, D, u, u2, st);
-    else if (dt == 2) launch_bias_rows_dt<2>(G, Hb, B, T, D, u, u2, st);
-    else if (dt == 1) launch_bias_rows_dt<1>(G, Hb, B, T, D, u, u2, st);
-    else              launch_bias_rows_dt<0>(G, Hb, B, T, D, u, u2, st);
-    return hipGetLastError();
+    // the examples are the grid's y dimension (at most 65535): larger batches go in several launches
+    const size_t es = dt == 0 ? 4 : (dt >= 3 ? 1 : 2);
+    for (int b0 = 0; b0 < B; b0 += 65535) {
+        const int nb = (B - b0 < 65535) ? (B - b0) : 65535;
+        const size_t in_off = (size_t)b0 * T * D * es, out_off = (size_t)b0 * D;
+        const void* g = static_cast<const unsigned char*>(G) + in_off;
+        const void* h = Hb ? static_cast<const unsigned char*>(Hb) + in_off : nullptr;
+        float* pu = u + out_off;
+        float* pu2 = u2 ? u2 + out_off : nullptr;
+        if (dt == 5)      launch_bias_rows_dt<4, 3>(g, h, nb, T, D, pu, pu2, st);
+        else if (dt == 4) launch_bias_rows_dt<4>(g, h, nb, T, D, pu, pu2, st);
+        else if (dt == 3) launch_bias_rows_dt<3>(g, h, nb, T, D, pu, pu2, st);
+        else if (dt == 2) launch_bias_rows_dt<2>(g, h, nb, T, D, pu, pu2, st);
+        else if (dt == 1) launch_bias_rows_dt<1>(g, h, nb, T, D, pu, pu2, st);
+        else              launch_bias_rows_dt<0>(g, h, nb, T, D, pu, pu2, st);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // Bias rows from the per-row-tile column sums that the Gram kernel leaves behind:

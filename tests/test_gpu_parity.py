@@ -977,11 +977,10 @@ def test_bias_empty_and_errors(dp):
     assert lib.dp_clipped_bias_grad(u.data_ptr(), s.data_ptr(), 0, 6, 0, gb.data_ptr(), None) == 0
     torch.cuda.synchronize()
     assert float(gb.abs().sum()) == 0.0
-    # errors: negative sizes, null pointers, unknown dtype, too many examples
+    # errors: negative sizes, null pointers, unknown dtype
     assert lib.dp_bias_sqnorm(u.data_ptr(), -1, 1, 6, dp.DP_F32, 0, s.data_ptr(), u.data_ptr(), None) == 1
     assert lib.dp_bias_sqnorm(None, 4, 1, 6, dp.DP_F32, 0, s.data_ptr(), u.data_ptr(), None) == 1
     assert lib.dp_bias_sqnorm(u.data_ptr(), 4, 1, 6, 7, 0, s.data_ptr(), u.data_ptr(), None) == 1
-    assert lib.dp_bias_sqnorm(u.data_ptr(), 70000, 1, 6, dp.DP_F32, 0, s.data_ptr(), u.data_ptr(), None) == 2
     assert lib.dp_clipped_bias_grad(u.data_ptr(), None, 4, 6, 0, gb.data_ptr(), None) == 1
 
 
@@ -1270,3 +1269,21 @@ def test_f32_copy_pipeline_shapes(dp, B, T, d_in, d_out):
         g2 = torch.full_like(g, 0.25)
         dp.clipped_grad(Ad, Gd, cd, g2, accumulate=True)
         np.testing.assert_allclose(g2.cpu().numpy(), got + np.float32(0.25), rtol=0, atol=1e-6 * (1 + np.abs(got).max()))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bias_and_layernorm_rows_beyond_65535_examples(dp, dtype):
+    """The row kernels take the examples as a grid dimension of at most 65535: larger batches go in several
+    launches, and the examples on both sides of the seam must come out like all others."""
+    B, T, d = 65535 + 300, 2, 8
+    H, G = wl.random_layer(4242, B, T, d, d, dtype)
+    Gd, Hd = to_dev(G), to_dev(H)
+    Gw, Hw = orc.widen(G).reshape(B, T, d), orc.widen(H).reshape(B, T, d)
+    s, u = dp.bias_sqnorm(Gd)
+    assert np.all(np.abs(u.cpu().numpy() - orc.bias_rows(G)) <= 1e-6 * np.maximum(np.abs(Gw).sum(1), 1e-30))
+    assert rel_err(s.cpu().numpy(), orc.bias_sqnorm(G)) <= 1e-5
+    s2, ga, be = dp.layernorm_sqnorm(Gd, Hd)
+    ga_ref, be_ref = orc.layernorm_rows(G, H)
+    assert np.all(np.abs(ga.cpu().numpy() - ga_ref) <= 2e-6 * np.maximum(np.abs(Gw * Hw).sum(1), 1e-30))
+    assert np.all(np.abs(be.cpu().numpy() - be_ref) <= 1e-6 * np.maximum(np.abs(Gw).sum(1), 1e-30))
+    assert rel_err(s2.cpu().numpy(), orc.layernorm_sqnorm(G, H)) <= 1e-5
