@@ -182,30 +182,33 @@ __global__ __launch_bounds__(kThreads) void k_rows_sqnorm(const float* __restric
     }
 }
 
-// grad_b[q] (+)= sum_i nu_i u[i, q].  A workgroup owns 32 columns; its 8 row groups add examples g, g + 8, ... in
-// ascending order (four loads in flight each), and the 8 partial sums are added in the order g = 0 .. 7: a fixed
-// order, so the result is reproducible.  (One thread per column walking all B examples one dependent load after
-// the other took 17 us for 256 examples.)
-__global__ __launch_bounds__(kThreads) void k_clipped_bias(const float* __restrict__ u, const float* __restrict__ clip, int B, int D,
-                                                           int accumulate, float* __restrict__ grad_b) {
-    __shared__ float part[8][32];
+// grad_b[q] (+)= sum_i nu_i u[i, q].  A workgroup owns 32 columns; its NG row groups add examples g, g + NG, ... in
+// ascending order (four loads in flight each), and the NG partial sums are added in the order g = 0 .. NG - 1: a
+// fixed order, so the result is reproducible.  (One thread per column walking all B examples one dependent load
+// after the other took 17 us for 256 examples.)  NG = 8 for small batches; 32 (1024 threads per workgroup) from
+// 2048 examples on: the grid is only d_out / 32 workgroups, so a long batch needs the loads of many threads in
+// flight per workgroup (B = 65536, d_out = 512: 0.70 ms with 8 groups).
+template <int NG>
+__global__ __launch_bounds__(NG * 32) void k_clipped_bias(const float* __restrict__ u, const float* __restrict__ clip, int B, int D,
+                                                          int accumulate, float* __restrict__ grad_b) {
+    __shared__ float part[NG][32];
     const int g = threadIdx.x >> 5, cl = threadIdx.x & 31;
     const int q = blockIdx.x * 32 + cl;
     float acc = 0.f;
     if (q < D) {
         int i = g;
-        for (; i + 24 < B; i += 32) {
-            const float v0 = u[(size_t)i * D + q], v1 = u[(size_t)(i + 8) * D + q];
-            const float v2 = u[(size_t)(i + 16) * D + q], v3 = u[(size_t)(i + 24) * D + q];
-            acc += clip[i] * v0; acc += clip[i + 8] * v1; acc += clip[i + 16] * v2; acc += clip[i + 24] * v3;
+        for (; i + 3 * NG < B; i += 4 * NG) {
+            const float v0 = u[(size_t)i * D + q], v1 = u[(size_t)(i + NG) * D + q];
+            const float v2 = u[(size_t)(i + 2 * NG) * D + q], v3 = u[(size_t)(i + 3 * NG) * D + q];
+            acc += clip[i] * v0; acc += clip[i + NG] * v1; acc += clip[i + 2 * NG] * v2; acc += clip[i + 3 * NG] * v3;
         }
-        for (; i < B; i += 8) acc += clip[i] * u[(size_t)i * D + q];
+        for (; i < B; i += NG) acc += clip[i] * u[(size_t)i * D + q];
     }
     part[g][cl] = acc;
     __syncthreads();
     if (g == 0 && q < D) {
 #pragma unroll
-        for (int k = 1; k < 8; ++k) acc += part[k][cl];
+        for (int k = 1; k < NG; ++k) acc += part[k][cl];
         grad_b[q] = accumulate ? grad_b[q] + acc : acc;
     }
 }
@@ -303,7 +306,8 @@ hipError_t launch_rows_sqnorm(const float* u, int B, int D, bool accumulate, flo
 }
 
 hipError_t launch_clipped_bias(const float* u, const float* clip, int B, int D, bool accumulate, float* grad_b, hipStream_t st) {
-    k_clipped_bias<<<(unsigned)((D + 31) / 32), kThreads, 0, st>>>(u, clip, B, D, accumulate ? 1 : 0, grad_b);
+    if (B >= 2048) k_clipped_bias<32><<<(unsigned)((D + 31) / 32), 1024, 0, st>>>(u, clip, B, D, accumulate ? 1 : 0, grad_b);
+    else           k_clipped_bias<8><<<(unsigned)((D + 31) / 32), kThreads, 0, st>>>(u, clip, B, D, accumulate ? 1 : 0, grad_b);
     return hipGetLastError();
 }
 

@@ -1287,3 +1287,8 @@ def test_bias_and_layernorm_rows_beyond_65535_examples(dp, dtype):
     assert np.all(np.abs(ga.cpu().numpy() - ga_ref) <= 2e-6 * np.maximum(np.abs(Gw * Hw).sum(1), 1e-30))
     assert np.all(np.abs(be.cpu().numpy() - be_ref) <= 1e-6 * np.maximum(np.abs(Gw).sum(1), 1e-30))
     assert rel_err(s2.cpu().numpy(), orc.layernorm_sqnorm(G, H)) <= 1e-5
+    # the clipped sum of that many rows (the kernel's long-batch form)
+    c = (0.05 + 0.95 * np.random.default_rng(5).random(B)).astype(np.float32)
+    u_ref = orc.bias_rows(G)
+    got = dp.clipped_bias_grad(u, to_dev(c)).cpu().numpy()
+    assert np.all(np.abs(got - orc.clipped_rows_sum(u_ref, c)) <= 1e-5 * np.maximum(np.abs(u_ref * c[:, None]).sum(0), 1e-30))
