@@ -31,9 +31,10 @@ struct TnArgsF {
 
 // The loads of a stage are issued unconditionally from clamped (valid) addresses and zeroed afterwards: no branch
 // sits between them, so they are all in flight together (a guarded load costs one memory round trip each).
-// VEC: d_in and d_out are multiples of 4, so every 16-byte piece is all inside or all outside a row and is one
-// load; otherwise a piece is four 4-byte loads.
-template <int MODE, int FBK, bool VEC>
+// VECA / VECG: d_in / d_out is a multiple of 4, so every 16-byte piece of that operand is all inside or all outside a
+// row and is one load; otherwise a piece is four 4-byte loads (each operand by itself: a 256 -> 10 classifier head
+// still reads its wide operand in 16-byte pieces).
+template <int MODE, int FBK, bool VECA, bool VECG>
 __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
     constexpr int NV = FBK / 16;        // float4 pieces of either operand per thread and stage
     __shared__ __attribute__((aligned(16))) float sA[FBK][FBM];
@@ -77,14 +78,19 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
             const int rc = inr[v] ? row : k_end - 1;                    // k_begin < k_end whenever a stage is fetched
             const float* pa = a.A + (size_t)rc * a.M;
             const float* pg = a.G + (size_t)rc * a.N;
-            if (VEC) {
+            if (VECA) {
                 const float4 qa = *reinterpret_cast<const float4*>(pa + colA[0]);
-                const float4 qg = *reinterpret_cast<const float4*>(pg + colG[0]);
                 xa[v][0] = qa.x; xa[v][1] = qa.y; xa[v][2] = qa.z; xa[v][3] = qa.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xa[v][j] = pa[colA[j]];
+            }
+            if (VECG) {
+                const float4 qg = *reinterpret_cast<const float4*>(pg + colG[0]);
                 xg[v][0] = qg.x; xg[v][1] = qg.y; xg[v][2] = qg.z; xg[v][3] = qg.w;
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) { xa[v][j] = pa[colA[j]]; xg[v][j] = pg[colG[j]]; }
+                for (int j = 0; j < 4; ++j) xg[v][j] = pg[colG[j]];
             }
             cl[v] = (MODE == 0) ? a.clip[a.T == 1 ? rc : rc / a.T] : 1.0f;
         }
@@ -158,7 +164,7 @@ constexpr int SBK = 64, STM = 32, STN = 32;
     __shared__ __attribute__((aligned(16))) float sA[SBK][STM];            \
     __shared__ __attribute__((aligned(16))) float sG[SBK][STN];            \
     __shared__ __attribute__((aligned(16))) float part[4][STM][STN + 1]
-template <bool VEC>
+template <bool VECA, bool VECG>
 __device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile, float (*sA)[STM], float (*sG)[STN],
                                                   float (*part)[STM][STN + 1]) {
     constexpr int NV = 2;               // float4 pieces of either operand per thread and stage
@@ -195,14 +201,19 @@ __device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile, fl
             const int rc = row < k_end ? row : k_end - 1;
             const float* pa = a.A + (size_t)rc * a.M;
             const float* pg = a.G + (size_t)rc * a.N;
-            if (VEC) {
+            if (VECA) {
                 const float4 qa = *reinterpret_cast<const float4*>(pa + colA[0]);
-                const float4 qg = *reinterpret_cast<const float4*>(pg + colG[0]);
                 xa[g][v][0] = qa.x; xa[g][v][1] = qa.y; xa[g][v][2] = qa.z; xa[g][v][3] = qa.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xa[g][v][j] = pa[colA[j]];
+            }
+            if (VECG) {
+                const float4 qg = *reinterpret_cast<const float4*>(pg + colG[0]);
                 xg[g][v][0] = qg.x; xg[g][v][1] = qg.y; xg[g][v][2] = qg.z; xg[g][v][3] = qg.w;
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) { xa[g][v][j] = pa[colA[j]]; xg[g][v][j] = pg[colG[j]]; }
+                for (int j = 0; j < 4; ++j) xg[g][v][j] = pg[colG[j]];
             }
             cl[g][v] = a.clip[a.T == 1 ? rc : rc / a.T];
         }
@@ -262,10 +273,17 @@ __device__ __forceinline__ void tn_f32_short_tile(const TnArgsF& a, int tile, fl
     }
 }
 
-template <bool VEC>
+// 16-byte loads for each operand whose width allows them (a 256 -> 10 head must not cost a wide layer its loads,
+// nor its own wide operand)
+__device__ __forceinline__ void tn_f32_short_dispatch(const TnArgsF& a, int tile, float (*sA)[STM], float (*sG)[STN],
+                                                      float (*part)[STM][STN + 1]) {
+    const bool va = (a.M & 3) == 0, vg = (a.N & 3) == 0;
+    if (va) { if (vg) tn_f32_short_tile<true, true>(a, tile, sA, sG, part); else tn_f32_short_tile<true, false>(a, tile, sA, sG, part); }
+    else    { if (vg) tn_f32_short_tile<false, true>(a, tile, sA, sG, part); else tn_f32_short_tile<false, false>(a, tile, sA, sG, part); }
+}
 __global__ __launch_bounds__(kThreads) void k_tn_f32_short(TnArgsF a) {
     SHORT_LDS;
-    tn_f32_short_tile<VEC>(a, blockIdx.x, sA, sG, part);
+    tn_f32_short_dispatch(a, blockIdx.x, sA, sG, part);
 }
 
 // The same for several layers in one launch (a model of small dense layers is a chain of launches of a few
@@ -277,17 +295,19 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32_short_layers(TnShortLayers 
     int li = 0;
     while (li + 1 < t.n_layers && (int)blockIdx.x >= t.first_tile[li + 1]) ++li;
     const TnArgsF a = t.layer[li];
-    // 16-byte loads for the layers whose widths allow them (a 256 -> 10 head must not cost the wide layers theirs)
-    if (((a.M | a.N) & 3) == 0) tn_f32_short_tile<true>(a, (int)blockIdx.x - t.first_tile[li], sA, sG, part);
-    else                        tn_f32_short_tile<false>(a, (int)blockIdx.x - t.first_tile[li], sA, sG, part);
+    tn_f32_short_dispatch(a, (int)blockIdx.x - t.first_tile[li], sA, sG, part);
 }
 
 // the short-contraction kernel takes K up to this many rows
 constexpr int kShortK = 512;
 
-template <int MODE> void launch_f32(bool deep, bool vec, dim3 grid, const TnArgsF& a, hipStream_t st) {
-    if (deep) { if (vec) k_tn_f32<MODE, 64, true><<<grid, kThreads, 0, st>>>(a); else k_tn_f32<MODE, 64, false><<<grid, kThreads, 0, st>>>(a); }
-    else      { if (vec) k_tn_f32<MODE, 16, true><<<grid, kThreads, 0, st>>>(a); else k_tn_f32<MODE, 16, false><<<grid, kThreads, 0, st>>>(a); }
+template <int MODE, int FBK> void launch_f32_k(bool veca, bool vecg, dim3 grid, const TnArgsF& a, hipStream_t st) {
+    if (veca) { if (vecg) k_tn_f32<MODE, FBK, true, true><<<grid, kThreads, 0, st>>>(a); else k_tn_f32<MODE, FBK, true, false><<<grid, kThreads, 0, st>>>(a); }
+    else      { if (vecg) k_tn_f32<MODE, FBK, false, true><<<grid, kThreads, 0, st>>>(a); else k_tn_f32<MODE, FBK, false, false><<<grid, kThreads, 0, st>>>(a); }
+}
+template <int MODE> void launch_f32(bool deep, bool veca, bool vecg, dim3 grid, const TnArgsF& a, hipStream_t st) {
+    if (deep) launch_f32_k<MODE, 64>(veca, vecg, grid, a, st);
+    else      launch_f32_k<MODE, 16>(veca, vecg, grid, a, st);
 }
 
 }  // namespace
@@ -381,12 +401,11 @@ hipError_t launch_clipped_f32(const TnPlan& p, const float* A, const float* G, c
     if (p.tile_m == STM) {
         a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0;
         const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n);
-        if (((M | N) & 3) == 0) k_tn_f32_short<true><<<tiles, kThreads, 0, st>>>(a);
-        else                    k_tn_f32_short<false><<<tiles, kThreads, 0, st>>>(a);
+        k_tn_f32_short<<<tiles, kThreads, 0, st>>>(a);
         return hipGetLastError();
     }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.splits);
-    launch_f32<0>(stage_rows(a.K) == 64, ((M | N) & 3) == 0, grid, a, st);
+    launch_f32<0>(stage_rows(a.K) == 64, (M & 3) == 0, (N & 3) == 0, grid, a, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
@@ -447,7 +466,7 @@ hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, in
         a.G = G + (size_t)b0 * T * N;
         a.out = partial + (size_t)b0 * tiles;
         dim3 grid((unsigned)tiles, (unsigned)nb);
-        launch_f32<1>(stage_rows(T) == 64, ((M | N) & 3) == 0, grid, a, st);
+        launch_f32<1>(stage_rows(T) == 64, (M & 3) == 0, (N & 3) == 0, grid, a, st);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
