@@ -32,31 +32,36 @@ struct GramArgs {
     float C; float* clip;
 };
 
-// Rows [row0, row0 + TT) x columns [k0, k0 + 64) of X_i[T, D] -> LDS tile (zero padded).
+// Rows [row0, row0 + TT) x columns [k0, k0 + 64) of X_i[T, D] -> LDS tile (zero padded).  Every load is issued
+// unconditionally from a clamped (valid) address and zeroed afterwards (a branch around each load sends a thread's
+// loads out one memory round trip after the other); widths that are multiples of 4 only take 8-byte pieces.
 template <int TT>
 __device__ __forceinline__ void gram_fetch(const uint16_t* __restrict__ Xi, int T, int D, bool vec_ok,
                                            int row0, int k0, int tid, uint4 (&st)[TT / 32]) {
     const int c = tid & 7;
+    const int col = k0 + c * 8;
 #pragma unroll
     for (int it = 0; it < TT / 32; ++it) {
         const int row = row0 + (tid >> 3) + it * 32;
-        const int col = k0 + c * 8;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (row < T) {
-            const uint16_t* p = Xi + (size_t)row * D;
-            if (vec_ok) {
-                if (col < D) v = *reinterpret_cast<const uint4*>(p + col);
-            } else {
-                uint32_t w[4] = {0u, 0u, 0u, 0u};
+        const bool in = row < T;
+        const uint16_t* p = Xi + (size_t)min(row, T - 1) * D;
+        if (vec_ok) {
+            const bool ok = col < D;
+            const uint4 v = *reinterpret_cast<const uint4*>(p + (ok ? col : 0));
+            st[it] = (in && ok) ? v : make_uint4(0u, 0u, 0u, 0u);
+        } else if ((D & 3) == 0) {
+            const bool ok0 = col < D, ok1 = col + 4 < D;
+            const uint2 lo = *reinterpret_cast<const uint2*>(p + (ok0 ? col : 0)), hi = *reinterpret_cast<const uint2*>(p + (ok1 ? col + 4 : 0));
+            st[it] = make_uint4((in && ok0) ? lo.x : 0u, (in && ok0) ? lo.y : 0u, (in && ok1) ? hi.x : 0u, (in && ok1) ? hi.y : 0u);
+        } else {
+            uint32_t e[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t e = (col + j < D) ? (uint32_t)p[col + j] : 0u;
-                    w[j >> 1] |= e << ((j & 1) * 16);
-                }
-                v = make_uint4(w[0], w[1], w[2], w[3]);
-            }
+            for (int j = 0; j < 8; ++j) e[j] = p[min(col + j, D - 1)];
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[j >> 1] |= ((in && col + j < D) ? e[j] : 0u) << ((j & 1) * 16);
+            st[it] = make_uint4(w[0], w[1], w[2], w[3]);
         }
-        st[it] = v;
     }
 }
 

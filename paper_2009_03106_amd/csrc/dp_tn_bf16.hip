@@ -49,30 +49,48 @@ struct TnArgs {
 };
 
 // Load an 8(k) x 8(col) block starting at (row0, col0) of X[K, D]; rows >= k_end and
-// columns >= D read as zero.
+// columns >= D read as zero.  Every load is issued unconditionally from a clamped (valid) address and zeroed
+// afterwards: with a branch around each, a thread's loads went out one memory round trip after the other.
+// k_end >= 1 and D >= 1 (the launchers never start an empty slice).
 __device__ __forceinline__ void load_block(const uint16_t* __restrict__ X, int D, bool vec_ok,
                                            int row0, int k_end, int col0, uint4 (&r)[8]) {
     if (vec_ok) {
         const bool col_ok = col0 < D;     // D % 8 == 0 and col0 % 8 == 0: the piece is all in or all out
+        const int cc = col_ok ? col0 : 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = row0 + i;
-            if (col_ok && row < k_end) r[i] = *reinterpret_cast<const uint4*>(X + (size_t)row * D + col0);
-            else r[i] = make_uint4(0u, 0u, 0u, 0u);
+            const uint4 v = *reinterpret_cast<const uint4*>(X + (size_t)min(row, k_end - 1) * D + cc);
+            r[i] = (col_ok && row < k_end) ? v : make_uint4(0u, 0u, 0u, 0u);
+        }
+    } else if ((D & 3) == 0) {
+        // widths that are multiples of 4 only (300, 500, 20 ...): 8-byte pieces, each all in or all out, rows 8-byte aligned
+        const bool ok0 = col0 < D, ok1 = col0 + 4 < D;
+        const int c0 = ok0 ? col0 : 0, c1 = ok1 ? col0 + 4 : 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = row0 + i;
+            const uint16_t* p = X + (size_t)min(row, k_end - 1) * D;
+            const uint2 lo = *reinterpret_cast<const uint2*>(p + c0), hi = *reinterpret_cast<const uint2*>(p + c1);
+            const bool in = row < k_end;
+            r[i] = make_uint4((in && ok0) ? lo.x : 0u, (in && ok0) ? lo.y : 0u, (in && ok1) ? hi.x : 0u, (in && ok1) ? hi.y : 0u);
         }
     } else {
+        int cc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cc[j] = min(col0 + j, D - 1);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = row0 + i;
-            uint32_t w[4] = {0u, 0u, 0u, 0u};
-            if (row < k_end) {
-                const uint16_t* p = X + (size_t)row * D;
+            const uint16_t* p = X + (size_t)min(row, k_end - 1) * D;
+            uint32_t v[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int col = col0 + j;
-                    const uint32_t v = (col < D) ? (uint32_t)p[col] : 0u;
-                    w[j >> 1] |= v << ((j & 1) * 16);
-                }
+            for (int j = 0; j < 8; ++j) v[j] = p[cc[j]];
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t x = (row < k_end && col0 + j < D) ? v[j] : 0u;
+                w[j >> 1] |= x << ((j & 1) * 16);
             }
             r[i] = make_uint4(w[0], w[1], w[2], w[3]);
         }
