@@ -646,7 +646,9 @@ TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
         p.segmented = false; p.epu = 0;
         return p;
     }
-    p.segmented = (T >= kSegMinT);
+    // the example-by-example kernel has at most one K slice per example: with few examples (a handful of long
+    // sequences) it would leave most of the chip idle, and the kernel below, whose K slices are any rows, takes over
+    p.segmented = (T >= kSegMinT) && (int64_t)B * tiles >= 64;
     if (p.segmented) {
         // K slices are whole examples.  Aim for a few workgroups per compute unit, in multiples of the
         // 8 XCDs, without multiplying the fp32 slice traffic more than needed.
