@@ -162,7 +162,7 @@ def test_layers_workspace_sizes(lib):
 def test_layer_descriptor_layout_and_argument_checks(lib):
     """Host logic only: every field of dp_layer_desc is read where the header says (the checks below fail before any
     launch, so the pointers are never touched; they are made-up, 16-byte aligned addresses)."""
-    B, T, di, do = 4, 64, 72, 40
+    B, T, di, do = 64, 64, 72, 40
     fake = lambda k: 0x10000000 + 0x100000 * k
 
     def descs(**over):
