@@ -32,9 +32,10 @@ struct GramArgs {
     float C; float* clip;
 };
 
-// Rows [row0, row0 + TT) x columns [k0, k0 + 64) of X_i[T, D] -> LDS tile (zero padded).  Every load is issued
-// unconditionally from a clamped (valid) address and zeroed afterwards (a branch around each load sends a thread's
-// loads out one memory round trip after the other); widths that are multiples of 4 only take 8-byte pieces.
+// Rows [row0, row0 + TT) x columns [k0, k0 + 64) of X_i[T, D] -> LDS tile (zero padded).  For widths that are not
+// multiples of 8 the loads are issued unconditionally from clamped (valid) addresses and zeroed afterwards (with a
+// branch around each of the 8 scalar loads of a piece they went out one memory round trip after the other); widths
+// that are multiples of 4 take 8-byte pieces.
 template <int TT>
 __device__ __forceinline__ void gram_fetch(const uint16_t* __restrict__ Xi, int T, int D, bool vec_ok,
                                            int row0, int k0, int tid, uint4 (&st)[TT / 32]) {
@@ -46,9 +47,9 @@ __device__ __forceinline__ void gram_fetch(const uint16_t* __restrict__ Xi, int 
         const bool in = row < T;
         const uint16_t* p = Xi + (size_t)min(row, T - 1) * D;
         if (vec_ok) {
-            const bool ok = col < D;
-            const uint4 v = *reinterpret_cast<const uint4*>(p + (ok ? col : 0));
-            st[it] = (in && ok) ? v : make_uint4(0u, 0u, 0u, 0u);
+            // (16-byte pieces: the guarded form is the faster one here, measured)
+            st[it] = make_uint4(0u, 0u, 0u, 0u);
+            if (in && col < D) st[it] = *reinterpret_cast<const uint4*>(Xi + (size_t)row * D + col);
         } else if ((D & 3) == 0) {
             const bool ok0 = col < D, ok1 = col + 4 < D;
             const uint2 lo = *reinterpret_cast<const uint2*>(p + (ok0 ? col : 0)), hi = *reinterpret_cast<const uint2*>(p + (ok1 ? col + 4 : 0));

@@ -49,19 +49,19 @@ struct TnArgs {
 };
 
 // Load an 8(k) x 8(col) block starting at (row0, col0) of X[K, D]; rows >= k_end and
-// columns >= D read as zero.  Every load is issued unconditionally from a clamped (valid) address and zeroed
-// afterwards: with a branch around each, a thread's loads went out one memory round trip after the other.
+// columns >= D read as zero.  For widths that are not multiples of 8 every load is issued unconditionally from a
+// clamped (valid) address and zeroed afterwards: with a branch around each of the 64 scalar loads, a thread's loads
+// went out one memory round trip after the other (16-byte pieces: the guarded form is the faster one, measured).
 // k_end >= 1 and D >= 1 (the launchers never start an empty slice).
 __device__ __forceinline__ void load_block(const uint16_t* __restrict__ X, int D, bool vec_ok,
                                            int row0, int k_end, int col0, uint4 (&r)[8]) {
     if (vec_ok) {
         const bool col_ok = col0 < D;     // D % 8 == 0 and col0 % 8 == 0: the piece is all in or all out
-        const int cc = col_ok ? col0 : 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = row0 + i;
-            const uint4 v = *reinterpret_cast<const uint4*>(X + (size_t)min(row, k_end - 1) * D + cc);
-            r[i] = (col_ok && row < k_end) ? v : make_uint4(0u, 0u, 0u, 0u);
+            if (col_ok && row < k_end) r[i] = *reinterpret_cast<const uint4*>(X + (size_t)row * D + col0);
+            else r[i] = make_uint4(0u, 0u, 0u, 0u);
         }
     } else if ((D & 3) == 0) {
         // widths that are multiples of 4 only (300, 500, 20 ...): 8-byte pieces, each all in or all out, rows 8-byte aligned
