@@ -129,6 +129,99 @@ __global__ __launch_bounds__(kThreads) void k_gram_f32(GramArgsF a) {
     if (threadIdx.x == 0) a.partial[blockIdx.x] = diag ? s : 2.0f * s;
 }
 
+// Short sequences (T <= 32: the late convolutions of an image model, 16 positions of 2304 to 4608 inputs): the kernel
+// above would give the one useful 32 x 32 tile to one wave, a chain of d / 2 dependent 64-cycle MFMAs (75 to 135 us
+// for such layers), while three waves multiply zeros.  Here the four waves split the contraction: every stage holds
+// 128 columns of the example's rows, wave w takes columns 32 w .. 32 w + 31 of it, and the four partial tiles are
+// added through LDS in the order w = 0 .. 3, first for A A^T, then for G G^T; the tile is diagonal, so both MFMA
+// operands are the same fragment.  One workgroup per example.
+constexpr int SK = 128;       // contraction elements per stage
+constexpr int SP = SK + 1;    // padded row length in LDS
+template <bool VEC>
+__device__ __forceinline__ void gram_small_product(const float* __restrict__ Xi, int T, int D, float (*sX)[SP],
+                                                   float (*part)[32][33], float (*out)[33]) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    // global -> LDS: a thread moves four 4-column pieces per stage: rows lr + 8 v, columns lc .. lc + 3
+    const int lr = tid >> 5, lc = (tid & 31) * 4;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    float x[2][4][4];
+    auto fetch = [&](int b, int k0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = lr + 8 * v;
+            const float* p = Xi + (size_t)(row < T ? row : T - 1) * D;
+            if (VEC) {
+                const int c = (k0 + lc < D) ? k0 + lc : 0;
+                const float4 q = *reinterpret_cast<const float4*>(p + c);
+                x[b][v][0] = q.x; x[b][v][1] = q.y; x[b][v][2] = q.z; x[b][v][3] = q.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) x[b][v][j] = p[(k0 + lc + j < D) ? k0 + lc + j : 0];
+            }
+        }
+    };
+    auto commit = [&](int b, int k0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                sX[lr + 8 * v][lc + j] = (lr + 8 * v < T && k0 + lc + j < D) ? x[b][v][j] : 0.f;
+    };
+    // two stages of loads in flight
+    if (D > 0) fetch(0, 0);
+    if (D > SK) fetch(1, SK);
+    for (int k0 = 0; k0 < D; k0 += 2 * SK) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int kb = k0 + b * SK;
+            if (kb >= D) break;
+            commit(b, kb);
+            __syncthreads();
+            if (kb + 2 * SK < D) fetch(b, kb + 2 * SK);
+            float f[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) f[j] = sX[lrow][wave * 32 + 2 * j + lhalf];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f[j], f[j], acc, 0, 0, 0);
+            __syncthreads();
+        }
+    }
+    // accumulator element r of a lane: row 8 (r / 4) + 4 lhalf + r % 4, column lrow
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave][8 * (r >> 2) + 4 * lhalf + (r & 3)][lrow] = acc[r];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int idx = tid + 256 * e, mr = idx >> 5, nc = idx & 31;
+        out[mr][nc] = ((part[0][mr][nc] + part[1][mr][nc]) + part[2][mr][nc]) + part[3][mr][nc];
+    }
+    __syncthreads();
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void k_gram_f32_small(GramArgsF a) {
+    __shared__ float sX[32][SP];
+    __shared__ float part[4][32][33];
+    __shared__ float P[32][33], Q[32][33];
+    __shared__ float red[4];
+    const int ex = blockIdx.x;
+    gram_small_product<VEC>(a.A + (size_t)ex * a.T * a.d_in, a.T, a.d_in, sX, part, P);
+    gram_small_product<VEC>(a.G + (size_t)ex * a.T * a.d_out, a.T, a.d_out, sX, part, Q);
+    // rows beyond T were stored as zeros, so their entries of both tiles are zero
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int idx = threadIdx.x + 256 * e, mr = idx >> 5, nc = idx & 31;
+        s += P[mr][nc] * Q[mr][nc];
+    }
+    s = block_sum_256(s, red);
+    if (threadIdx.x == 0) a.partial[ex] = s;
+}
+
 }  // namespace
 
 GramPlan plan_gram_f32(int T) {
@@ -147,8 +240,11 @@ hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, in
     a.nt = p.nt; a.npairs = p.npairs;
     const int64_t grid = (int64_t)B * p.npairs;
     if (grid >= (int64_t(1) << 31)) return hipErrorInvalidValue;
-    if (((d_in | d_out) & 3) == 0) k_gram_f32<true><<<(unsigned)grid, kThreads, 0, st>>>(a);
-    else                           k_gram_f32<false><<<(unsigned)grid, kThreads, 0, st>>>(a);
+    if (T <= 32) {              // one tile pair per example (p.npairs == 1): the four waves split the contraction
+        if (((d_in | d_out) & 3) == 0) k_gram_f32_small<true><<<(unsigned)B, kThreads, 0, st>>>(a);
+        else                           k_gram_f32_small<false><<<(unsigned)B, kThreads, 0, st>>>(a);
+    } else if (((d_in | d_out) & 3) == 0) k_gram_f32<true><<<(unsigned)grid, kThreads, 0, st>>>(a);
+    else                                  k_gram_f32<false><<<(unsigned)grid, kThreads, 0, st>>>(a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, p.npairs, accumulate, sqnorm, st, co);

@@ -1292,3 +1292,17 @@ def test_bias_and_layernorm_rows_beyond_65535_examples(dp, dtype):
     u_ref = orc.bias_rows(G)
     got = dp.clipped_bias_grad(u, to_dev(c)).cpu().numpy()
     assert np.all(np.abs(got - orc.clipped_rows_sum(u_ref, c)) <= 1e-5 * np.maximum(np.abs(u_ref * c[:, None]).sum(0), 1e-30))
+
+
+@pytest.mark.parametrize("B,T,d_in,d_out", [(5, 16, 2304, 512), (3, 32, 260, 1000), (4, 7, 33, 65), (2, 2, 4, 4), (6, 31, 129, 256)])
+def test_f32_gram_short_sequences(dp, B, T, d_in, d_out):
+    """float32 Gram norms of at most 32 positions: the four waves split the contraction over the widths."""
+    A, G = wl.random_layer(31 + B + T + d_in, B, T, d_in, d_out, "f32", g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    Ad, Gd = to_dev(A), to_dev(G)
+    s = dp.layer_sqnorm(Ad, Gd, path="gram")
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["f32"]
+    s2 = torch.full((B,), 1.5, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, s2, path="gram", accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 1.5) <= SQ_TIGHT["f32"]
+    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="gram").cpu().numpy(), s.cpu().numpy())
