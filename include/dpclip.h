@@ -212,10 +212,16 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
  * (B*T <= 512), eight per launch, and 16-bit / 8-bit layers that run on 256 x
  * 256 tiles with T a multiple of the 32- / 64-row stage (groups of 2 to 16):
  * one launch whose work items fill the chip a whole number of times, where a
- * launch per layer has to fill it exactly once.  Results: bit for bit the
+ * launch per layer has to fill it exactly once.  The other 16-bit layers whose
+ * widths are multiples of 8 and at least 64, with T a multiple of 32 (the
+ * unfolded convolutions of an image model: 576 -> 64, 1152 -> 128, ...), form
+ * groups of their own (2 to 16 layers) on 128 x 128 tiles.  Results: bit for bit the
  * per-layer calls, except for those groups, whose contraction is cut into other K slices: the
  * float32 partial sums are then grouped differently (differences at the level
- * of float32 rounding; still bit-reproducible from call to call).
+ * of float32 rounding; still bit-reproducible from call to call).  The groups
+ * apply the clip factors to float32 sums, also for the shapes where the layer's
+ * own kernel multiplies them into 16-bit inputs (dp_clipped_grad_rounds_inputs):
+ * there the two differ by that rounding.
  *   workspace  device scratch of at least dp_layers_clipped_workspace_bytes(...)
  *              bytes (the largest single layer's need, or a group's slices). */
 dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, int64_t B,

@@ -113,15 +113,18 @@ bool gram_batchable(int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_p
 
 size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
 
-// a layer that the joint clipped-sum launch of dp_layers_clipped_grad(_noise) can take (by shape and type)
-bool clipped_joinable(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
-    if (B == 0 || T == 0 || d_in == 0 || d_out == 0) return false;
-    if (is8(dtype)) return dma8_clipped_ok((int)T, (int)d_in, (int)d_out) && dma8_joint_ok((int)T, (int)d_in, (int)d_out);
-    if (!is16(dtype) || !plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out).dma) return false;
-    return dma_joint_ok((int)T, (int)d_in, (int)d_out);
+// Which joint clipped-sum launch of dp_layers_clipped_grad(_noise) can take a layer (by shape and type): 0 none,
+// 1 the 256 x 256-tile launch, 3 the 128 x 128-tile launch for aligned 16-bit layers of a few hundred columns
+int clipped_join_class(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
+    if (B == 0 || T == 0 || d_in == 0 || d_out == 0) return 0;
+    if (is8(dtype)) return (dma8_clipped_ok((int)T, (int)d_in, (int)d_out) && dma8_joint_ok((int)T, (int)d_in, (int)d_out)) ? 1 : 0;
+    if (!is16(dtype)) return 0;
+    if (plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out).dma && dma_joint_ok((int)T, (int)d_in, (int)d_out)) return 1;
+    if (B * T < (int64_t(1) << 31) && dma_joint_mid_ok((int)T, (int)d_in, (int)d_out)) return 3;
+    return 0;
 }
-size_t joint_ws_bytes(const JointShape* sh, int n, int64_t B, dp_dtype dtype) {
-    return (is8(dtype) ? joint8_workspace_floats(sh, n, (int)B) : joint_workspace_floats(sh, n, (int)B)) * sizeof(float);
+size_t joint_ws_bytes(const JointShape* sh, int n, int64_t B, dp_dtype dtype, int geo) {
+    return (is8(dtype) ? joint8_workspace_floats(sh, n, (int)B) : joint_workspace_floats(sh, n, (int)B, geo)) * sizeof(float);
 }
 
 constexpr size_t kConvZeroBytes = 256;                // head of the conv workspace: a line of zeros for the padding
@@ -854,22 +857,26 @@ extern "C" {
 size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype) {
     if (check_layers(layers, n_layers, B, dtype, DP_PATH_DIRECT, false, DP_OP_CLIPPED_GRAD) != DP_OK) return 0;
     size_t need = 0;
-    JointShape sh[kJointLayers];
-    int nj = 0;
-    auto joint_need = [&]() {
-        if (nj >= 2) need = std::max(need, joint_ws_bytes(sh, nj, B, dtype));
-        nj = 0;
-    };
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
         const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
         if (n > need) need = n;
-        if (clipped_joinable(B, y.T, y.d_in, y.d_out, dtype)) {
+    }
+    for (int geo : {1, 3}) {                              // the two classes of joint launches, each in groups of its own
+        JointShape sh[kJointLayers];
+        int nj = 0;
+        auto joint_need = [&]() {
+            if (nj >= 2) need = std::max(need, joint_ws_bytes(sh, nj, B, dtype, geo));
+            nj = 0;
+        };
+        for (int64_t l = 0; l < n_layers; ++l) {
+            const dp_layer_desc& y = layers[l];
+            if (clipped_join_class(B, y.T, y.d_in, y.d_out, dtype) != geo) continue;
             sh[nj++] = JointShape{(int)y.T, (int)y.d_in, (int)y.d_out};
             if (nj == kJointLayers) joint_need();
         }
+        joint_need();
     }
-    joint_need();
     return round16(need);
 }
 
@@ -911,34 +918,38 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
     // Aligned 16-bit and 8-bit layers with 256 x 256 tiles share launches, up to kJointLayers each (groups of at least two):
     // one launch whose items fill the chip a whole number of times, the K slices folded (and the noise added) inside
     // it.  With noise the kernel adds it four elements at a time, so the layer's offset and size must be multiples of 4.
+    // A second class of joint launches (128 x 128 tiles) takes the aligned 16-bit layers of a few hundred columns.
     std::vector<std::vector<int64_t>> joint_groups;
-    {
+    std::vector<int> joint_geo;
+    for (int geo : {1, 3}) {
         std::vector<int64_t> cur;
+        const size_t first_group = joint_groups.size();
         for (int64_t l = 0; l < n_layers; ++l) {
             const dp_layer_desc& y = layers[l];
-            if (!clipped_joinable(B, y.T, y.d_in, y.d_out, dtype)) continue;
+            if (clipped_join_class(B, y.T, y.d_in, y.d_out, dtype) != geo) continue;
             if (stddev > 0.0f && !splitk_noise_ok(y.d_in * y.d_out, y.noise_offset)) continue;
             cur.push_back(l);
-            if ((int)cur.size() == kJointLayers) { joint_groups.push_back(cur); cur.clear(); }
+            if ((int)cur.size() == kJointLayers) { joint_groups.push_back(cur); joint_geo.push_back(geo); cur.clear(); }
         }
-        if (cur.size() >= 2) joint_groups.push_back(cur);
+        if (cur.size() >= 2) { joint_groups.push_back(cur); joint_geo.push_back(geo); }
         // the largest layers first: the tiles that are folded when the launch ends are then the smallest layer's
-        for (auto& g : joint_groups)
+        for (size_t gi = first_group; gi < joint_groups.size(); ++gi) {
+            auto& g = joint_groups[gi];
             std::stable_sort(g.begin(), g.end(), [&](int64_t a, int64_t b) {
                 return layers[a].d_in * layers[a].d_out * layers[a].T > layers[b].d_in * layers[b].d_out * layers[b].T; });
-        for (const auto& g : joint_groups) {
             JointShape sh[kJointLayers];
             for (size_t k = 0; k < g.size(); ++k) {
                 const dp_layer_desc& y = layers[g[k]];
                 sh[k] = JointShape{(int)y.T, (int)y.d_in, (int)y.d_out};
             }
-            need = std::max(need, joint_ws_bytes(sh, (int)g.size(), B, dtype));
+            need = std::max(need, joint_ws_bytes(sh, (int)g.size(), B, dtype, geo));
         }
     }
     if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return DP_ERR_WORKSPACE;
     // float32 layers with a short contraction (a model of small dense layers) share launches, 8 layers each
     std::vector<char> done((size_t)n_layers, 0);
-    for (const auto& g : joint_groups) {
+    for (size_t gi = 0; gi < joint_groups.size(); ++gi) {
+        const auto& g = joint_groups[gi];
         JointShape sh[kJointLayers];
         JointOperands op[kJointLayers];
         for (size_t k = 0; k < g.size(); ++k) {
@@ -952,7 +963,7 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
             ? launch_clipped_f8_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
                                           static_cast<hipStream_t>(hip_stream), fmt_of(dtype))
             : launch_clipped_bf16_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
-                                            static_cast<hipStream_t>(hip_stream), dtype == DP_F16);
+                                            static_cast<hipStream_t>(hip_stream), dtype == DP_F16, joint_geo[gi]);
         if (ej != hipSuccess) return DP_ERR_HIP;
     }
     if (dtype == DP_F32 && B > 0 && !(stddev > 0.0f)) {

@@ -111,9 +111,10 @@ struct JointOperands { const uint16_t* A; const uint16_t* G; const float* clip; 
 // One slice length for all layers of a joint launch (each layer rounds it to a whole number of equal slices), chosen
 // to minimise   rounds of 256 workgroups  x  (stages of the longest slice + what an item costs besides its stages):
 // slices long enough that their start-up, their store and their fold stay small, and a number of items that fills
-// the chip's 256 compute units a whole number of times.  dk: rows per stage; tile: the square output tile.
+// the chip's 256 compute units a whole number of times.  dk: rows per stage; tile: the square output tile; slots:
+// workgroups resident at a time (256 x workgroups per compute unit).
 struct JointPlan { int n_layers; int tiles_m[kJointLayers], tiles_n[kJointLayers], splits[kJointLayers], sps[kJointLayers]; int64_t items; };
-inline JointPlan plan_joint(const JointShape* sh, int n_layers, int B, int dk, int tile) {
+inline JointPlan plan_joint(const JointShape* sh, int n_layers, int B, int dk, int tile, int slots = 256) {
     constexpr int64_t kItemOverhead = 16;            // prologue + slice store + the slice's share of the fold, in stage times
     JointPlan best{};
     int64_t best_cost = -1, stages_max = 1;
@@ -135,13 +136,14 @@ inline JointPlan plan_joint(const JointShape* sh, int n_layers, int B, int dk, i
             p.items += (int64_t)p.tiles_m[l] * p.tiles_n[l] * splits;
             longest = longest > sps ? longest : sps;
         }
-        const int64_t cost = ((p.items + 255) / 256) * (longest + kItemOverhead);
+        const int64_t cost = ((p.items + slots - 1) / slots) * (longest + kItemOverhead);
         if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = p; }
     }
     return best;
 }
 bool dma_joint_ok(int T, int M, int N);
-size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B);
+bool dma_joint_mid_ok(int T, int M, int N);      // the second class: 128 x 128 tiles, geo = 3 below
+size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B, int geo = 1);
 // the same for 8-bit inputs (dp_tn_f8_dma.hip; 256 x 256 tiles, T a multiple of 64); A, G of JointOperands are byte pointers
 bool dma8_joint_ok(int T, int M, int N);
 size_t joint8_workspace_floats(const JointShape* sh, int n_layers, int B);
@@ -149,7 +151,7 @@ hipError_t launch_clipped_f8_dma_joint(const JointShape* sh, const JointOperands
                                        float stddev, uint64_t seed, float* ws, hipStream_t st, int fmt);
 // noise: stddev == 0 for none, else every layer's d_in * d_out and noise_offset are multiples of 4
 hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
-                                         float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16);
+                                         float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16, int geo = 1);
 // direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);

@@ -445,8 +445,8 @@ struct JointArgs {
     JointLayer layer[kJointMax];
     int n_layers, n_items, per_xcd, B;
 };
-template <bool F16>
-__global__ __launch_bounds__(GeoL::THREADS, GeoL::OCC) void k_tn_bf16_dma_joint(JointArgs j) {
+template <class GEO, bool F16>
+__global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma_joint(JointArgs j) {
     const int L = (blockIdx.x & 7) * j.per_xcd + (blockIdx.x >> 3);
     if (L >= j.n_items) return;
     int l = 0;
@@ -460,7 +460,7 @@ __global__ __launch_bounds__(GeoL::THREADS, GeoL::OCC) void k_tn_bf16_dma_joint(
     a.stages_total = y.stages_total; a.stages_per_split = y.stages_per_split;
     a.per_xcd = 0; a.accumulate = 0;
     a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0; a.zero = nullptr;
-    tn_dma_tile<GeoL, 0, 0, F16>(a, L - y.first_item);
+    tn_dma_tile<GEO, 0, 0, F16>(a, L - y.first_item);
 }
 
 
@@ -583,21 +583,35 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
 }
 
-// ---- joint launch of several layers' clipped sums
+// ---- joint launch of several layers' clipped sums.  Two classes of layers, each with launches of its own:
+//      geo 1: 256 x 256 tiles (one workgroup per compute unit), layers whose clipped sum is bound by the MFMA rate;
+//      geo 3: 128 x 128 tiles (two workgroups per compute unit) for the aligned layers of a few hundred columns
+//             that the first class does not take (the 3 x 3 convolutions of an image model, unfolded: 576 -> 64,
+//             1152 -> 128, ...): alone each of them is a launch of 10 to 30 us that fills a fraction of the chip and
+//             a fold behind it; tiles may be mostly padding, these layers are bound by latency and bandwidth.
 bool dma_joint_ok(int T, int M, int N) { return T > 0 && (T % DK) == 0 && dma_geometry(T, M, N) == 1; }
+bool dma_joint_mid_ok(int T, int M, int N) {
+    if (T <= 0 || (T % DK) != 0 || ((M | N) & 7) != 0 || M < 64 || N < 64) return false;
+    if ((int64_t)DK * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;        // 32-bit lane offsets inside a stage
+    return dma_geometry(T, M, N) != 1;
+}
+namespace {
+inline int joint_tile(int geo) { return geo == 1 ? GeoL::TM : GeoT::TM; }
+inline int joint_slots(int geo) { return geo == 1 ? 256 * GeoL::OCC : 256 * GeoT::OCC; }
+}
 
 // floats of workspace: every layer's slices, one layer after the other
-size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B) {
-    const JointPlan p = plan_joint(sh, n_layers, B, DK, GeoL::TM);
+size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B, int geo) {
+    const JointPlan p = plan_joint(sh, n_layers, B, DK, joint_tile(geo), joint_slots(geo));
     size_t slices = 0;
     for (int l = 0; l < n_layers; ++l) slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
     return slices;
 }
 
 hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
-                                         float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16) {
-    if (n_layers < 1 || n_layers > kJointMax) return hipErrorInvalidValue;
-    const JointPlan p = plan_joint(sh, n_layers, B, DK, GeoL::TM);
+                                         float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16, int geo) {
+    if (n_layers < 1 || n_layers > kJointMax || (geo != 1 && geo != 3)) return hipErrorInvalidValue;
+    const JointPlan p = plan_joint(sh, n_layers, B, DK, joint_tile(geo), joint_slots(geo));
     if (p.items >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     JointArgs j;
     float* slices = ws;
@@ -616,8 +630,14 @@ hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperan
     for (int l = n_layers; l < kJointMax; ++l) j.layer[l] = j.layer[0];
     j.n_layers = n_layers; j.n_items = (int)p.items; j.per_xcd = ceil_div(p.items, 8);
     j.B = B;
-    if (f16) k_tn_bf16_dma_joint<true><<<8u * (unsigned)j.per_xcd, GeoL::THREADS, 0, st>>>(j);
-    else     k_tn_bf16_dma_joint<false><<<8u * (unsigned)j.per_xcd, GeoL::THREADS, 0, st>>>(j);
+    const unsigned grid = 8u * (unsigned)j.per_xcd;
+    if (geo == 1) {
+        if (f16) k_tn_bf16_dma_joint<GeoL, true><<<grid, GeoL::THREADS, 0, st>>>(j);
+        else     k_tn_bf16_dma_joint<GeoL, false><<<grid, GeoL::THREADS, 0, st>>>(j);
+    } else {
+        if (f16) k_tn_bf16_dma_joint<GeoT, true><<<grid, GeoT::THREADS, 0, st>>>(j);
+        else     k_tn_bf16_dma_joint<GeoT, false><<<grid, GeoT::THREADS, 0, st>>>(j);
+    }
     hipError_t e = hipGetLastError();
     // the folds of the layers' slices (+ noise), each as after a launch of the layer alone
     for (int l = 0; l < n_layers && e == hipSuccess; ++l) {

@@ -503,6 +503,57 @@ def test_layers_clipped_grad_equals_per_layer_calls(dp, name, B):
     assert all(torch.all(k == 5.0) for k in keep)
 
 
+# Unfolded 3 x 3 and 1 x 1 convolutions of an image model (positions x patch columns -> channels), smallest batch
+# that still gives every layer several K slices; one shape that is not aligned (the first convolution's 27 patch
+# columns) keeps to the launches of its own between the others.
+CNN_STACK = [(256, 27, 64), (256, 576, 64), (256, 576, 64), (64, 576, 128), (64, 1152, 128), (64, 64, 128),
+             (32, 1152, 256), (32, 2304, 256), (32, 128, 256)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("noise", [False, True])
+def test_layers_clipped_grad_image_model_layers_share_a_launch(dp, dtype, noise):
+    """Aligned 16-bit layers of a few hundred columns share one launch of 128 x 128 tiles in the several-layers call.
+    Against the oracle, and against the per-layer calls as sums of the same terms in another grouping; the noise is
+    bit for bit what dp_add_noise adds afterwards."""
+    B = 24
+    layers = [wl.random_layer(4100 + i, B, T, di, do, dtype, a_dist="relu", g_std=0.02, g_row_scale=np.exp(np.linspace(-2, 2, B)))
+              for i, (T, di, do) in enumerate(CNN_STACK)]
+    s_ref = orc.total_sqnorm(layers)
+    C = float(np.sqrt(np.median(s_ref)))
+    c_ref = orc.clip_factors(s_ref, C)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    c = to_dev(c_ref.astype(np.float32))
+    sizes = [A.shape[-1] * G.shape[-1] for A, G in dev]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.full((sum(sizes),), 7.0, device="cuda")
+    grads = [flat[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)]
+    dp.layers_clipped_grad(dev, c, grads)
+    for (A, G), (An, Gn), g, (T, di, do) in zip(dev, layers, grads, CNN_STACK):
+        ref = orc.clipped_grad(An, Gn, c_ref)
+        alone = dp.clipped_grad(A, G, c).cpu().numpy()
+        if di % 8 == 0:
+            # the shared launch applies the factors to float32 sums, whatever the layer's own kernel does
+            assert fro_err(g.cpu().numpy(), ref) <= FRO_TIGHT, (T, di, do)
+            if dp.clipped_grad_rounds_inputs(B, T, di, do, DTYPE_CODE[dtype]):
+                assert fro_err(g.cpu().numpy(), alone) <= UNIT[dtype], (T, di, do)
+            else:
+                assert_same_sums(g.cpu().numpy(), alone, joint=True)
+        else:
+            assert fro_err(g.cpu().numpy(), ref) <= FRO_TOL[dtype], (T, di, do)
+            np.testing.assert_array_equal(g.cpu().numpy(), alone)
+    clean = flat.clone()
+    np.testing.assert_array_equal(dp.layers_clipped_grad(dev, c)[3].cpu().numpy(), grads[3].cpu().numpy())   # reruns
+    if noise:
+        descs = dp.layer_descs(dev, grads, starts[:-1])
+        dp.layers_clipped_grad(dev, c, descs=descs, noise_std=0.25, seed=11)
+        dp.add_noise(clean, 0.25, 11, 0)
+        assert torch.equal(flat, clean)
+    else:
+        dp.layers_clipped_grad(dev, c, grads, accumulate=True)
+        np.testing.assert_allclose(flat.cpu().numpy(), 2 * clean.cpu().numpy(), rtol=0, atol=1e-6 * float(clean.abs().max()))
+
+
 @pytest.mark.parametrize("name,B,base", [("transformer", 6, 0), ("transformer", 3, 4096), ("mlp", None, 0), ("rnn", None, 7),
                                          ("conv", 8, 12)])
 def test_layers_clipped_grad_with_noise_equals_separate_calls(dp, name, B, base):
