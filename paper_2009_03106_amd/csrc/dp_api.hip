@@ -85,6 +85,10 @@ bool g_is_e5m2(dp_dtype d) { return d != DP_F8_E4M3; }
 size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
     if (is8(dtype) && !f8_path_ok(path, dtype, T, d_in, d_out)) return 0;
     if (path == DP_PATH_GRAM) {
+        if (is16(dtype)) {
+            const GramColsPlan c = plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out);
+            if (c.use) return c.ws_floats * sizeof(float);
+        }
         GramPlan g = (is16(dtype) || is8(dtype)) ? plan_gram_bf16((int)T, (int)d_in, (int)d_out) : plan_gram_f32((int)T);
         return (size_t)B * g.npairs * sizeof(float);
     }
@@ -271,6 +275,10 @@ dp_status layer_sqnorm_clip(const void* A, const void* G, int64_t B, int64_t T, 
     } else if (p == DP_PATH_GRAM && !is16(dtype)) {
         e = launch_gram_f32(plan_gram_f32((int)T), static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, co);
+    } else if (p == DP_PATH_GRAM && plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out).use) {
+        e = launch_gram_cols(plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out), static_cast<const uint16_t*>(A),
+                             static_cast<const uint16_t*>(G), (int)B, (int)T, (int)d_in, (int)d_out, accumulate != 0, sqnorm,
+                             partial, stream, dtype == DP_F16, co);
     } else if (p == DP_PATH_GRAM) {
         GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
         e = launch_gram_bf16(g, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,

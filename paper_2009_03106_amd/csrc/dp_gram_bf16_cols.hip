@@ -1,0 +1,209 @@
+// Gram path for the per-example squared norm (Section 5.2, the sum over position pairs of
+// (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}), 16-bit inputs, for layers of few positions (T <= 64) and wide rows in a
+// small batch: the late convolutions of an image model (4 x 4 or 8 x 8 positions, 2304 -> 256 or 4608 -> 512
+// unfolded columns, 20 to 32 examples).  One workgroup per example walks thousands of columns alone there and
+// leaves most of the chip idle, so here the COLUMNS are split: every wave takes a range of the columns of A and G
+// (one after the other), forms its share of A_i A_i^T and of G_i G_i^T straight from registers, the four waves of a
+// workgroup add their shares through LDS, and a second kernel adds the workgroups' shares of an example in a fixed
+// order, multiplies the two T x T products entry by entry and sums.
+//
+// No LDS staging of the inputs: both operands of a Gram product are rows of the same matrix, and a lane's 16-byte
+// piece of global memory (8 consecutive columns of one row) is exactly an MFMA operand of the 32 x 32 x 16
+// instruction (row = lane % 32, columns 8 * (lane / 32) .. + 7 of the step) for the left and for the right side.
+// A wave issues the loads of 8 steps before the first MFMA, so a range of 128 columns is one memory round trip.
+#include "dp_common.h"
+#include "dp_internal.h"
+
+namespace dpk {
+
+namespace {
+
+constexpr int kColsSteps = 8;        // 16-column steps whose loads are in flight together
+
+struct GramColsArgs {
+    const uint16_t* A;
+    const uint16_t* G;
+    float* part;         // [B][W][2][NT][16][64]: the workgroups' shares of the two products, in accumulator layout
+    int T, d_in, d_out;
+    int steps_a;         // 16-column steps of A; the steps of G follow them
+    int steps;           // of A and G together
+    int W;               // workgroups per example
+    int per_wave;        // steps per wave
+};
+
+// acc[tile] += X[rows of block b0] . X[rows of block b1]^T over the steps [kb, ke) of X_i[T, D]; tiles in the
+// order (0,0), (0,1), (1,1) for two 32-row blocks.  Rows >= T and columns >= D read as zero (loads go to clamped,
+// valid addresses).
+template <int NB, bool F16>
+__device__ __forceinline__ void gram_cols_run(const uint16_t* __restrict__ X, int T, int D, int kb, int ke, int lane,
+                                              f32x16 (&acc)[NB * (NB + 1) / 2]) {
+    const int row = lane & 31, half = lane >> 5;
+    const uint16_t* p[NB];
+    bool in[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int r = b * 32 + row;
+        in[b] = r < T;
+        p[b] = X + (size_t)(r < T ? r : T - 1) * D;
+    }
+    for (int k = kb; k < ke; k += kColsSteps) {
+        uint4 f[kColsSteps][NB];
+#pragma unroll
+        for (int u = 0; u < kColsSteps; ++u) {
+            const int col = (k + u) * 16 + half * 8;
+            const bool ok = (k + u) < ke && col < D;                 // D is a multiple of 8: a piece is inside or outside
+            const int c = ok ? col : 0;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const uint4 v = *reinterpret_cast<const uint4*>(p[b] + c);
+                const bool keep = ok && in[b];
+                f[u][b] = make_uint4(keep ? v.x : 0u, keep ? v.y : 0u, keep ? v.z : 0u, keep ? v.w : 0u);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kColsSteps; ++u) {
+            const bf16x8 f0 = __builtin_bit_cast(bf16x8, f[u][0]);
+            acc[0] = In16<F16>::mfma(f0, f0, acc[0]);
+            if constexpr (NB == 2) {
+                const bf16x8 f1 = __builtin_bit_cast(bf16x8, f[u][1]);
+                acc[1] = In16<F16>::mfma(f0, f1, acc[1]);
+                acc[2] = In16<F16>::mfma(f1, f1, acc[2]);
+            }
+        }
+    }
+}
+
+// NB: 32-row blocks of positions (1: T <= 32, 2: T <= 64)
+template <int NB, bool F16>
+__global__ __launch_bounds__(kThreads, 2) void k_gram16_cols(GramColsArgs a) {
+    constexpr int NT = NB * (NB + 1) / 2;            // tiles of the upper triangle
+    constexpr int SHARE = 2 * NT * 16 * 64;          // floats of one wave's share (both products)
+    __shared__ float red[2 * SHARE];
+    const int ex = blockIdx.x / a.W, w = blockIdx.x - ex * a.W;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    f32x16 acc[2][NT];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[q][t][r] = 0.f;
+
+    const int k0 = (w * 4 + wave) * a.per_wave;
+    const int k1 = min(k0 + a.per_wave, a.steps);
+    if (k0 < a.steps_a)
+        gram_cols_run<NB, F16>(a.A + (size_t)ex * a.T * a.d_in, a.T, a.d_in, k0, min(k1, a.steps_a), lane, acc[0]);
+    if (k1 > a.steps_a)
+        gram_cols_run<NB, F16>(a.G + (size_t)ex * a.T * a.d_out, a.T, a.d_out, max(k0, a.steps_a) - a.steps_a, k1 - a.steps_a, lane, acc[1]);
+
+    // waves 2, 3 -> LDS; waves 0, 1 add them; wave 1 -> LDS; wave 0 adds it and stores the workgroup's share
+    auto put = [&](float* slot) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) slot[((q * NT + t) * 16 + r) * 64 + lane] = acc[q][t][r];
+    };
+    auto add = [&](const float* slot) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[q][t][r] += slot[((q * NT + t) * 16 + r) * 64 + lane];
+    };
+    if (wave >= 2) put(red + (wave - 2) * SHARE);
+    __syncthreads();
+    if (wave < 2) add(red + wave * SHARE);
+    __syncthreads();
+    if (wave == 1) put(red);
+    __syncthreads();
+    if (wave == 0) {
+        add(red);
+        put(a.part + (size_t)blockIdx.x * SHARE);
+    }
+}
+
+// sqnorm[ex] (+)= sum over the entries of (sum_w P_w) * (sum_w Q_w), the tile (0,1) counted twice (it stands for
+// its mirror image too); one workgroup of 1024 threads per example, the shares added in the order of the workgroups
+constexpr int kFinishThreads = 1024;
+template <int NB>
+__global__ __launch_bounds__(kFinishThreads) void k_gram16_cols_finish(const float* __restrict__ part, int W, int accumulate,
+                                                                       float* __restrict__ sqnorm, float C, float* __restrict__ clip) {
+    constexpr int NT = NB * (NB + 1) / 2;
+    constexpr int HALF = NT * 16 * 64;
+    constexpr int PER = HALF / kFinishThreads;       // entries per thread: 1 or 3 (one of each tile)
+    __shared__ float red[kFinishThreads / 64];
+    const int ex = blockIdx.x;
+    const float* base = part + (size_t)ex * W * 2 * HALF + threadIdx.x;
+    float p[PER], q[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) { p[i] = 0.f; q[i] = 0.f; }
+#pragma unroll 4
+    for (int w = 0; w < W; ++w) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            p[i] += base[(size_t)w * 2 * HALF + i * kFinishThreads];
+            q[i] += base[(size_t)w * 2 * HALF + HALF + i * kFinishThreads];
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) s += (NB == 2 && i == 1) ? 2.0f * (p[i] * q[i]) : p[i] * q[i];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float v = 0.f;
+#pragma unroll
+        for (int i = 0; i < kFinishThreads / 64; ++i) v += red[i];
+        const float t = accumulate ? sqnorm[ex] + v : v;
+        sqnorm[ex] = t;
+        if (clip) clip[ex] = clip_factor_of(t, C);
+    }
+}
+
+}  // namespace
+
+GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out) {
+    GramColsPlan p{};
+    if (B < 1 || T < 2 || T > 64 || d_in < 8 || d_out < 8 || ((d_in | d_out) & 7) != 0) return p;
+    const int steps = ceil_div(d_in, 16) + ceil_div(d_out, 16);
+    // fill the chip (2 workgroups on each of 256 compute units) with waves of at least kColsSteps steps
+    int W = ceil_div(512, B);
+    const int w_max = steps / (4 * kColsSteps);
+    if (W > w_max) W = w_max;
+    if (W > 64) W = 64;
+    if (W < 2) return p;                                 // enough examples, or rows too narrow to split
+    p.use = true;
+    p.nb = T <= 32 ? 1 : 2;
+    p.per_wave = ceil_div(steps, 4 * W);
+    p.W = ceil_div(steps, 4 * p.per_wave);               // no workgroup without a step
+    const int nt = p.nb * (p.nb + 1) / 2;
+    p.ws_floats = (size_t)B * p.W * 2 * nt * 16 * 64;
+    return p;
+}
+
+hipError_t launch_gram_cols(const GramColsPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, bool f16, const ClipOut* co) {
+    if (!p.use) return hipErrorInvalidValue;
+    GramColsArgs a;
+    a.A = A; a.G = G; a.part = ws;
+    a.T = T; a.d_in = d_in; a.d_out = d_out;
+    a.steps_a = ceil_div(d_in, 16); a.steps = a.steps_a + ceil_div(d_out, 16);
+    a.W = p.W; a.per_wave = p.per_wave;
+    const unsigned grid = (unsigned)((int64_t)B * p.W);
+    if (p.nb == 1) { if (f16) k_gram16_cols<1, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<1, false><<<grid, kThreads, 0, st>>>(a); }
+    else           { if (f16) k_gram16_cols<2, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<2, false><<<grid, kThreads, 0, st>>>(a); }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const float C = co ? co->C : 0.f;
+    float* clip = co ? co->clip : nullptr;
+    if (p.nb == 1) k_gram16_cols_finish<1><<<B, kFinishThreads, 0, st>>>(ws, p.W, accumulate ? 1 : 0, sqnorm, C, clip);
+    else           k_gram16_cols_finish<2><<<B, kFinishThreads, 0, st>>>(ws, p.W, accumulate ? 1 : 0, sqnorm, C, clip);
+    return hipGetLastError();
+}
+
+}  // namespace dpk

@@ -48,6 +48,13 @@ struct NoiseArgs { float stddev; uint32_t k0, k1; uint64_t offset; };
 bool splitk_noise_ok(int64_t n, uint64_t offset);       // n and offset multiples of 4
 hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool accumulate, float* grad, hipStream_t st,
                                 const NoiseArgs* noise);
+// the folds of up to kJointLayers layers in one launch; the caller fills ws, grad, n, splits, noise_offset and n_layers
+constexpr int kJointLayers = 16;
+struct FoldLayers {
+    const float* ws[kJointLayers]; float* grad[kJointLayers]; int64_t n[kJointLayers], slice[kJointLayers];
+    uint64_t noise_offset[kJointLayers]; int splits[kJointLayers]; unsigned first_block[kJointLayers]; int n_layers;
+};
+hipError_t launch_splitk_reduce_layers(FoldLayers& f, bool accumulate, hipStream_t st, float stddev, uint64_t seed);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 // dst[j] = fp16 bits of the 8-bit float src[j] (e4m3, or e5m2 when e5m2 is set), exact
 hipError_t launch_widen_f8(const void* src, uint16_t* dst, int64_t n, bool e5m2, hipStream_t st);
@@ -105,7 +112,6 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
 // are then folded (+ noise) by the split-K reduce kernel as after a launch per layer.  Same arithmetic per slice and
 // the same ascending fold; the slices are cut differently, so the results agree with the per-layer launch up to the
 // rounding of the float32 sum over slices.
-constexpr int kJointLayers = 16;
 struct JointShape { int T, M, N; };
 struct JointOperands { const uint16_t* A; const uint16_t* G; const float* clip; float* grad; uint64_t noise_offset; };
 // One slice length for all layers of a joint launch (each layer rounds it to a whole number of equal slices), chosen
@@ -202,6 +208,12 @@ hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers
                                        float* partial, hipStream_t st, int fmt, float C = 0.f, float* clip = nullptr);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
                                 bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co = nullptr);
+// few positions (T <= 64), wide rows, small batch (dp_gram_bf16_cols.hip): the columns are split over workgroups.
+// use: whether this kernel takes the shape; ws_floats: its scratch
+struct GramColsPlan { bool use; int nb, W, per_wave; size_t ws_floats; };
+GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out);
+hipError_t launch_gram_cols(const GramColsPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, bool f16, const ClipOut* co = nullptr);
 // float32 inputs (dp_gram_f32.hip): 64-row tiles
 GramPlan plan_gram_f32(int T);
 hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, int B, int T, int d_in, int d_out,

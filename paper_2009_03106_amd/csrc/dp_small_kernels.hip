@@ -441,6 +441,58 @@ hipError_t launch_splitk_reduce(const float* ws, int64_t n, int splits, bool acc
     return hipGetLastError();
 }
 
+// The same fold for the layers of a joint launch in ONE launch (z ascending for every entry, as k_splitk_reduce):
+// a fold per layer is a launch of a few microseconds each, which for a dozen small layers is longer than their sums
+// took.  A workgroup takes 256 groups of 4 entries of one layer.
+template <bool NOISE>
+__global__ __launch_bounds__(256) void k_splitk_reduce_layers(FoldLayers f, int accumulate, NoiseArgs nz) {
+    int l = 0;
+    while (l + 1 < f.n_layers && blockIdx.x >= f.first_block[l + 1]) ++l;
+    const int64_t c = (int64_t)(blockIdx.x - f.first_block[l]) * 256 + threadIdx.x;
+    if (c >= (f.n[l] >> 2)) return;
+    const float* ws = f.ws[l];
+    const int64_t slice = f.slice[l];
+    const int splits = f.splits[l];
+    float4 acc = reinterpret_cast<const float4*>(ws)[c];
+    int z = 1;
+    for (; z + 3 < splits; z += 4) {
+        const float4 v0 = reinterpret_cast<const float4*>(ws + (size_t)z * slice)[c];
+        const float4 v1 = reinterpret_cast<const float4*>(ws + (size_t)(z + 1) * slice)[c];
+        const float4 v2 = reinterpret_cast<const float4*>(ws + (size_t)(z + 2) * slice)[c];
+        const float4 v3 = reinterpret_cast<const float4*>(ws + (size_t)(z + 3) * slice)[c];
+        acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+        acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+        acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+        acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
+    }
+    for (; z < splits; ++z) {
+        const float4 v = reinterpret_cast<const float4*>(ws + (size_t)z * slice)[c];
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    float4* o = reinterpret_cast<float4*>(f.grad[l]) + c;
+    if (accumulate) { const float4 g = *o; acc.x += g.x; acc.y += g.y; acc.z += g.z; acc.w += g.w; }
+    if (NOISE) add_noise4(acc, (f.noise_offset[l] >> 2) + (uint64_t)c, nz);
+    *o = acc;
+}
+
+// every layer: n a multiple of 4, slices spaced splitk_slice_elems(n) apart; with noise, noise_offset a multiple of 4
+hipError_t launch_splitk_reduce_layers(FoldLayers& f, bool accumulate, hipStream_t st, float stddev, uint64_t seed) {
+    if (f.n_layers < 1 || f.n_layers > kJointLayers) return hipErrorInvalidValue;
+    int64_t blocks = 0;
+    for (int l = 0; l < f.n_layers; ++l) {
+        if ((f.n[l] & 3) != 0 || (stddev != 0.0f && (f.noise_offset[l] & 3) != 0)) return hipErrorInvalidValue;
+        f.first_block[l] = (unsigned)blocks;
+        f.slice[l] = splitk_slice_elems(f.n[l]);
+        blocks += ((f.n[l] >> 2) + 255) / 256;
+        if (blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    }
+    for (int l = f.n_layers; l < kJointLayers; ++l) { f.first_block[l] = (unsigned)blocks; f.slice[l] = 0; }
+    const NoiseArgs nz{stddev, (uint32_t)seed, (uint32_t)(seed >> 32), 0};
+    if (stddev != 0.0f) k_splitk_reduce_layers<true><<<(unsigned)blocks, 256, 0, st>>>(f, accumulate ? 1 : 0, nz);
+    else                k_splitk_reduce_layers<false><<<(unsigned)blocks, 256, 0, st>>>(f, accumulate ? 1 : 0, nz);
+    return hipGetLastError();
+}
+
 __global__ void k_fill_zero(float* __restrict__ p, int64_t n) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) p[j] = 0.f;

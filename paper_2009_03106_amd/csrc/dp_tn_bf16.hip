@@ -628,15 +628,30 @@ TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    // Every K slice beyond the first costs a write and a read of M*N floats: a short contraction into a large
+    // matrix (a few examples of a few positions, thousands of columns) is bound by its output, and slices to fill
+    // the chip would multiply exactly that.  The slices' traffic stays below the bytes of the inputs.
+    const int64_t in_bytes = (int64_t)B * T * ((int64_t)M + N) * 2;
+    int64_t traffic_cap = in_bytes / ((int64_t)M * N * 8);
+    if (traffic_cap < 1) traffic_cap = 1;
     p.big = big_ok(T, M, N);
+    if (p.big) {
+        // one workgroup per compute unit: as many K slices as fit in 256 workgroups
+        const int64_t bt = (int64_t)ceil_div(M, GM) * ceil_div(N, GN);
+        int64_t splits = 256 / bt;
+        if (splits < 1) splits = 1;
+        if (splits > traffic_cap) splits = traffic_cap;
+        // few large tiles and no slices to multiply them: the 128 x 128 tiles below give four times the workgroups
+        if (bt * splits < 128 && bt * splits < tiles) p.big = false;
+    }
     if (p.big) {
         p.tile_m = GM; p.tile_n = GN;
         p.tiles_m = ceil_div(M, GM); p.tiles_n = ceil_div(N, GN);
         const int64_t bt = (int64_t)p.tiles_m * p.tiles_n;
         const int64_t K = (int64_t)B * T;
-        // one workgroup per compute unit: as many K slices as fit in 256 workgroups
         int64_t splits = 256 / bt;
         if (splits < 1) splits = 1;
+        if (splits > traffic_cap) splits = traffic_cap;
         const int64_t max_splits = (K + 2 * BK - 1) / (2 * BK);
         if (splits > max_splits) splits = max_splits;
         int64_t kchunk = (K + splits - 1) / splits;
@@ -671,6 +686,7 @@ TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
     int64_t want = (512 + tiles - 1) / tiles;
     int64_t max_splits = (K + 4 * BK - 1) / (4 * BK);
     if (want > max_splits) want = max_splits;
+    if (want > traffic_cap) want = traffic_cap;
     if (want < 1) want = 1;
     int64_t kchunk = (K + want - 1) / want;
     kchunk = ((kchunk + BK - 1) / BK) * BK;

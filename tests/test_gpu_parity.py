@@ -313,7 +313,7 @@ def test_layers_call_clip_factors_whatever_kernel_writes_them(dp, dtype, kinds):
 
 
 def test_per_layer_clipping_in_the_layers_calls(dp):
-    """Per-layer clipping (threshold c / sqrt(m) for each of the m layers, Section 2) through the several-layers calls:
+    """Per-layer clipping (threshold c / sqrt(m) for each of the m layers, Section 4) through the several-layers calls:
     every layer names its own norm and clip arrays, the Gram launch is still shared, and the clipped sums take each
     layer's own factors.  Norms are bit for bit those of the per-layer entry point."""
     w, layers = wl.generate("transformer", B=5, straddle=True)
@@ -395,7 +395,7 @@ def test_layers_calls_with_weights_and_biases(dp, name, B):
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("accumulate", [False, True])
 def test_grouped_clipping_mixed_kinds(dp, dtype, accumulate):
-    """Groups of layers with a threshold each (Section 2: a different amount of clipping for each group): dense, direct,
+    """Groups of layers with a threshold each (Section 4: a different amount of clipping for each group): dense, direct,
     shared-Gram and empty layers, with and without bias rows, spread over four groups, one of them the call's own
     array.  Against the oracle's sums over each group's layers."""
     B = 6
@@ -1357,3 +1357,33 @@ def test_f32_gram_short_sequences(dp, B, T, d_in, d_out):
     dp.layer_sqnorm(Ad, Gd, s2, path="gram", accumulate=True)
     assert rel_err(s2.cpu().numpy(), s_ref + 1.5) <= SQ_TIGHT["f32"]
     np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="gram").cpu().numpy(), s.cpu().numpy())
+
+
+# Few positions, wide rows, small batch (the late convolutions of an image model): the 16-bit Gram norm splits the
+# COLUMNS over workgroups.  T <= 32 and T <= 64 variants, one example, column counts that leave the last wave or the
+# last 16-column step partly empty, a range that spans the end of A and the start of G, and a batch at which the
+# split is 2 workgroups per example.
+GRAM_COLS_SHAPES = [(32, 16, 4608, 512), (20, 64, 2304, 256), (3, 33, 1032, 264), (7, 2, 256, 1024), (1, 64, 1152, 256),
+                    (5, 32, 8, 2048), (255, 17, 520, 520), (9, 48, 2056, 24)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,T,d_in,d_out", GRAM_COLS_SHAPES)
+def test_gram_column_split_few_positions(dp, dtype, B, T, d_in, d_out):
+    A, G = wl.random_layer(5150 + B + T + d_in, B, T, d_in, d_out, dtype, g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    Ad, Gd = to_dev(A), to_dev(G)
+    s = dp.layer_sqnorm(Ad, Gd, path="gram")
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], rel_err(s.cpu().numpy(), s_ref)
+    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="gram").cpu().numpy(), s.cpu().numpy())     # reruns
+    d = dp.layer_sqnorm(Ad, Gd, path="direct")
+    assert rel_err(s.cpu().numpy(), d.cpu().numpy().astype(np.float64)) <= 2 * SQ_TIGHT[dtype]
+    s2 = torch.full((B,), 0.5, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, s2, path="gram", accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
+    # through the several-layers call, which also writes the clip factors
+    C = float(np.sqrt(np.median(s_ref)))
+    c = torch.full((B,), -1.0, device="cuda")
+    s3 = dp.layers_sqnorm([(Ad, Gd), (Ad, Gd)], C=C, clip=c, path="gram")
+    assert rel_err(s3.cpu().numpy(), 2 * s_ref) <= SQ_TIGHT[dtype]
+    np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s3, C).cpu().numpy())
