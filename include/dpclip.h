@@ -139,11 +139,14 @@ dp_status dp_layer_sqnorm_static(const void* A, const void* G,
  * Layers on the Gram path whose widths are multiples of 64 (16-bit inputs;
  * multiples of 128 for 8-bit inputs) with T > 64 share kernel launches, up to 16 layers each: the workgroups of one
  * layer then fill the idle tail of another's, which a per-layer launch leaves
- * empty.  Dense layers (T == 1) share launches too, 16 each.  Every other
- * layer is handled exactly as dp_layer_sqnorm handles it.  The result equals
- * per-layer calls up to the order of the float32 additions over layers (dense
- * layers first, then those other layers, both in the order given; then the
- * shared Gram launches, widest layer first).
+ * empty.  Dense layers (T == 1) share launches too, 16 each, and so do 16-bit
+ * Gram layers of at most 64 positions with wide rows in a batch of fewer than
+ * 512 (their columns are split over workgroups).  Every other layer runs the
+ * kernels dp_layer_sqnorm runs for it; where there are two or more of them,
+ * their per-tile partial sums are added by one launch at the end instead of
+ * one per layer.  The result equals per-layer calls up to the order of the
+ * float32 additions (column-split Gram layers first, dense layers, then the
+ * other layers, then the shared Gram launches, widest layer first).
  *   layers     HOST array of n_layers descriptors, read during the call only;
  *              A and G are device pointers as in dp_layer_sqnorm; all layers
  *              share B, dtype and path
@@ -223,7 +226,9 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
  * own kernel multiplies them into 16-bit inputs (dp_clipped_grad_rounds_inputs):
  * there the two differ by that rounding.
  *   workspace  device scratch of at least dp_layers_clipped_workspace_bytes(...)
- *              bytes (the largest single layer's need, or a group's slices). */
+ *              bytes (the largest single layer's need, or a group's slices).
+ * A third kind of group takes such 16-bit layers whose T is at least 16 and not
+ * a multiple of 32 (4 x 4 or 7 x 7 positions). */
 dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
                                  const float* clip, dp_dtype dtype, int accumulate,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);

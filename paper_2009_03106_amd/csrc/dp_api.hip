@@ -115,16 +115,27 @@ bool gram_batchable(int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_p
     return gram_dma_ok((int)T, (int)d_in, (int)d_out, fmt_of(dtype));
 }
 
+// a layer that the shared column-split Gram launches of dp_layers_sqnorm take (few positions, wide rows, small batch):
+// 0 = no, else the launch class (the plan's number of 32-row blocks)
+int gram_cols_class(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
+    if (!is16(dtype) || T <= 1 || T > 64 || d_in == 0 || d_out == 0 || B >= (int64_t(1) << 20)) return 0;
+    if (resolve_path(path, dtype, T, d_in, d_out) != DP_PATH_GRAM) return 0;
+    const GramColsPlan c = plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out);
+    return c.use ? c.nb : 0;
+}
+
 size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
 
 // Which joint clipped-sum launch of dp_layers_clipped_grad(_noise) can take a layer (by shape and type): 0 none,
-// 1 the 256 x 256-tile launch, 3 the 128 x 128-tile launch for aligned 16-bit layers of a few hundred columns
+// 1 the 256 x 256-tile launch, 3 the 128 x 128-tile launch for aligned 16-bit layers of a few hundred columns, 4 the
+// same for such layers whose T is not a multiple of the 32-row stage
 int clipped_join_class(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
     if (B == 0 || T == 0 || d_in == 0 || d_out == 0) return 0;
     if (is8(dtype)) return (dma8_clipped_ok((int)T, (int)d_in, (int)d_out) && dma8_joint_ok((int)T, (int)d_in, (int)d_out)) ? 1 : 0;
     if (!is16(dtype)) return 0;
     if (plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out).dma && dma_joint_ok((int)T, (int)d_in, (int)d_out)) return 1;
     if (B * T < (int64_t(1) << 31) && dma_joint_mid_ok((int)T, (int)d_in, (int)d_out)) return 3;
+    if (B * T < (int64_t(1) << 31) && dma_joint_ragged_ok((int)T, (int)d_in, (int)d_out)) return 4;
     return 0;
 }
 size_t joint_ws_bytes(const JointShape* sh, int n, int64_t B, dp_dtype dtype, int geo) {
@@ -596,11 +607,12 @@ dp_status layers_sqnorm_grouped(const dp_layer_desc* layers, int64_t n_layers, i
 
 // scratch: the layers that run one by one reuse one region, and so do the batched launches
 size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B, dp_dtype dtype, dp_path path) {
-    size_t single = 0, batch = 0, batch_max = 0;
+    size_t single = 0, single_sum = 0, batch = 0, batch_max = 0;
     int in_batch = 0;
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
         if (B == 0 || y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
+        if (gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != 0) continue;      // below
         if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) {
             if (in_batch == kGramBatch) { in_batch = 0; batch = 0; }
             const GramPlan g = plan_gram_bf16((int)y.T, (int)y.d_in, (int)y.d_out);
@@ -611,6 +623,23 @@ size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
         } else {
             const size_t n = dp_workspace_bytes(DP_OP_SQNORM, B, y.T, y.d_in, y.d_out, dtype, path);
             if (n > single) single = n;
+            if (!(y.T == 1 && !is8(dtype))) single_sum += round16(n);
+        }
+    }
+    // the layers that run one by one keep their partial sums apart until one launch folds them (up to a limit: with
+    // less scratch the fold comes earlier)
+    if (!is8(dtype) && single_sum > single && single_sum <= (size_t(256) << 20)) single = single_sum;
+    // the shared column-split Gram launches, one class after the other, kGramColsLayers layers each
+    for (int cls = 1; cls <= 2; ++cls) {
+        size_t group = 0;
+        int in_group = 0;
+        for (int64_t l = 0; l < n_layers; ++l) {
+            const dp_layer_desc& y = layers[l];
+            if (B == 0 || gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != cls) continue;
+            if (in_group == kGramColsLayers) { in_group = 0; group = 0; }
+            group += plan_gram_cols((int)B, (int)y.T, (int)y.d_in, (int)y.d_out).ws_floats * sizeof(float);
+            ++in_group;
+            if (group > batch_max) batch_max = group;
         }
     }
     return round16(single > batch_max ? single : batch_max);
@@ -652,7 +681,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
     // Which kernel completes the norms and can write the clip factors with them: the last shared Gram launch if
     // there is one; else, unless a bias pass follows, the last layer that runs on its own; else the last launch
     // of dense layers.  Otherwise (bias passes at the end, or nothing to launch) the clip kernel runs.
-    int64_t n_dense = 0, last_single = -1;
+    int64_t n_dense = 0, n_cols = 0, last_single = -1;
     bool any_gram = false, any_bias_pass = false;
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
@@ -661,9 +690,35 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (y.T == 0 || y.d_in == 0 || y.d_out == 0) continue;
         if (y.T == 1 && !is8(dtype)) ++n_dense;
         else if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) any_gram = true;
+        else if (gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != 0) ++n_cols;
         else last_single = l;
     }
     const ClipOut clip_out{C, clip};
+    // layers of few positions and wide rows in a small batch: shared column-split Gram launches, first of all (they
+    // write the clip factors only when nothing else follows)
+    const bool clip_with_cols = clip && !any_gram && !any_bias_pass && last_single < 0 && n_dense == 0 && n_cols > 0;
+    {
+        int64_t cols_done = 0;
+        for (int cls = 1; cls <= 2; ++cls) {
+            GramLayerDesc group[kGramColsLayers];
+            int ng = 0;
+            auto flush_cols = [&]() -> hipError_t {
+                if (ng == 0) return hipSuccess;
+                cols_done += ng;
+                const hipError_t e = launch_gram_cols_layers(group, ng, (int)B, acc != 0, sqnorm, static_cast<float*>(workspace), stream,
+                                                             dtype == DP_F16, (clip_with_cols && cols_done == n_cols) ? &clip_out : nullptr);
+                ng = 0; acc = 1; launched = true;
+                return e;
+            };
+            for (int64_t l = 0; l < n_layers; ++l) {
+                const dp_layer_desc& y = layers[l];
+                if (gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != cls) continue;
+                group[ng++] = GramLayerDesc{y.A, y.G, (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, nullptr};
+                if (ng == kGramColsLayers && flush_cols() != hipSuccess) return DP_ERR_HIP;
+            }
+            if (flush_cols() != hipSuccess) return DP_ERR_HIP;
+        }
+    }
     const bool clip_with_single = clip && !any_gram && !any_bias_pass && last_single >= 0;
     const bool clip_with_dense = clip && !any_gram && !any_bias_pass && last_single < 0 && n_dense > 0;
     // dense layers (T = 1, closed form): up to kDenseBatch per launch, in the order given
@@ -686,15 +741,51 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (dense.n_layers == kDenseBatch && flush_dense() != hipSuccess) return DP_ERR_HIP;
     }
     if (flush_dense() != hipSuccess) return DP_ERR_HIP;
-    // layers outside the batched launches, in the order given
+    // layers outside the batched launches, in the order given.  Two or more of them: their partial sums are folded by
+    // one launch at the end (FinalizeQueue) instead of a launch of a few microseconds behind every layer.
+    int64_t n_single = 0;
+    for (int64_t l = 0; l < n_layers; ++l) {
+        const dp_layer_desc& y = layers[l];
+        if (y.T == 0 || (y.T == 1 && !is8(dtype)) || y.d_in == 0 || y.d_out == 0) continue;
+        if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path) || gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != 0) continue;
+        ++n_single;
+    }
+    const bool defer_on = n_single >= 2 && !is8(dtype);
+    FinalizeQueue queue;
+    size_t ws_off = 0;
+    auto flush_queue = [&](bool with_clip) -> hipError_t {
+        if (queue.count == 0) return hipSuccess;
+        const hipError_t e = launch_finalize_queue(queue, (int)B, acc != 0, sqnorm, stream, with_clip ? &clip_out : nullptr);
+        queue.count = 0; ws_off = 0; acc = 1; launched = true;
+        return e;
+    };
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
         if (y.T == 0 || (y.T == 1 && !is8(dtype)) || y.d_in == 0 || y.d_out == 0) continue;     // empty layers add nothing
         if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
-        const dp_status s1 = layer_sqnorm_clip(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes,
-                                               hip_stream, (clip_with_single && l == last_single) ? &clip_out : nullptr);
+        if (gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != 0) continue;
+        if (!defer_on) {
+            const dp_status s1 = layer_sqnorm_clip(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes,
+                                                   hip_stream, (clip_with_single && l == last_single) ? &clip_out : nullptr);
+            if (s1 != DP_OK) return s1;
+            acc = 1; launched = true;
+            continue;
+        }
+        // the layer's own region of the scratch: its partial sums stay there until the queue is folded
+        const size_t need_l = round16(dp_workspace_bytes(DP_OP_SQNORM, B, y.T, y.d_in, y.d_out, dtype, path));
+        if ((queue.count == FinalizeQueue::kMax || ws_off + need_l > workspace_bytes) && flush_queue(false) != hipSuccess) return DP_ERR_HIP;
+        const ClipOut co_defer{C, nullptr, &queue};
+        const int before = queue.count;
+        const dp_status s1 = layer_sqnorm_clip(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm,
+                                               static_cast<char*>(workspace) + ws_off, workspace_bytes - ws_off, hip_stream, &co_defer);
         if (s1 != DP_OK) return s1;
-        acc = 1; launched = true;
+        if (queue.count == before) { acc = 1; launched = true; }      // the layer's kernel added its norms itself
+        else ws_off += need_l;
+    }
+    if (defer_on) {
+        const bool queued = queue.count > 0;
+        if (flush_queue(clip_with_single) != hipSuccess) return DP_ERR_HIP;
+        if (clip_with_single && !queued && launch_clip_factors(sqnorm, (int)B, C, clip, stream) != hipSuccess) return DP_ERR_HIP;
     }
     // bias terms of the layers above (dense ones included): their own pass over G
     for (int64_t l = 0; l < n_layers; ++l) {
@@ -740,7 +831,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         if (nb == kGramBatch && flush(false) != hipSuccess) return DP_ERR_HIP;       // full, and another layer follows
         batch[nb++] = GramLayerDesc{y.A, y.G, (int)y.T, (int)y.d_in, (int)y.d_out, nullptr, is8(dtype) ? nullptr : y.bias_rows};
     }
-    const bool clip_done = clip != nullptr && (nb > 0 || clip_with_single || clip_with_dense);
+    const bool clip_done = clip != nullptr && (nb > 0 || clip_with_single || clip_with_dense || clip_with_cols);
     if (flush(true) != hipSuccess) return DP_ERR_HIP;
     if (!launched && !accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
     if (clip && !clip_done && launch_clip_factors(sqnorm, (int)B, C, clip, stream) != hipSuccess) return DP_ERR_HIP;
@@ -870,7 +961,7 @@ size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_
         const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
         if (n > need) need = n;
     }
-    for (int geo : {1, 3}) {                              // the two classes of joint launches, each in groups of its own
+    for (int geo : {1, 3, 4}) {                              // the two classes of joint launches, each in groups of its own
         JointShape sh[kJointLayers];
         int nj = 0;
         auto joint_need = [&]() {
@@ -929,7 +1020,7 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
     // A second class of joint launches (128 x 128 tiles) takes the aligned 16-bit layers of a few hundred columns.
     std::vector<std::vector<int64_t>> joint_groups;
     std::vector<int> joint_geo;
-    for (int geo : {1, 3}) {
+    for (int geo : {1, 3, 4}) {
         std::vector<int64_t> cur;
         const size_t first_group = joint_groups.size();
         for (int64_t l = 0; l < n_layers; ++l) {

@@ -20,15 +20,23 @@ namespace {
 
 constexpr int kColsSteps = 8;        // 16-column steps whose loads are in flight together
 
-struct GramColsArgs {
+struct GramColsLayer {
     const uint16_t* A;
     const uint16_t* G;
-    float* part;         // [B][W][2][NT][16][64]: the workgroups' shares of the two products, in accumulator layout
+    size_t part_off;     // floats: where the layer's shares start in the scratch
     int T, d_in, d_out;
     int steps_a;         // 16-column steps of A; the steps of G follow them
     int steps;           // of A and G together
     int W;               // workgroups per example
     int per_wave;        // steps per wave
+    unsigned first_block;
+};
+// Several layers in one launch (the same number of 32-row blocks NB for all): a layer alone is a few hundred
+// workgroups that each make one memory round trip, so the launches of a model's layers mostly wait.
+struct GramColsArgs {
+    GramColsLayer layer[kGramColsLayers];
+    float* part;         // per layer [B][W][2][NT][16][64]: the workgroups' shares of the two products, in accumulator layout
+    int n_layers;
 };
 
 // acc[tile] += X[rows of block b0] . X[rows of block b1]^T over the steps [kb, ke) of X_i[T, D]; tiles in the
@@ -75,11 +83,15 @@ __device__ __forceinline__ void gram_cols_run(const uint16_t* __restrict__ X, in
 
 // NB: 32-row blocks of positions (1: T <= 32, 2: T <= 64)
 template <int NB, bool F16>
-__global__ __launch_bounds__(kThreads, 2) void k_gram16_cols(GramColsArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void k_gram16_cols(GramColsArgs j) {
     constexpr int NT = NB * (NB + 1) / 2;            // tiles of the upper triangle
     constexpr int SHARE = 2 * NT * 16 * 64;          // floats of one wave's share (both products)
     __shared__ float red[2 * SHARE];
-    const int ex = blockIdx.x / a.W, w = blockIdx.x - ex * a.W;
+    int li = 0;
+    while (li + 1 < j.n_layers && blockIdx.x >= j.layer[li + 1].first_block) ++li;
+    const GramColsLayer& a = j.layer[li];
+    const int item = blockIdx.x - a.first_block;
+    const int ex = item / a.W, w = item - ex * a.W;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     f32x16 acc[2][NT];
@@ -122,36 +134,42 @@ __global__ __launch_bounds__(kThreads, 2) void k_gram16_cols(GramColsArgs a) {
     __syncthreads();
     if (wave == 0) {
         add(red);
-        put(a.part + (size_t)blockIdx.x * SHARE);
+        put(j.part + a.part_off + (size_t)item * SHARE);
     }
 }
 
-// sqnorm[ex] (+)= sum over the entries of (sum_w P_w) * (sum_w Q_w), the tile (0,1) counted twice (it stands for
-// its mirror image too); one workgroup of 1024 threads per example, the shares added in the order of the workgroups
+// sqnorm[ex] (+)= sum over the layers of the sum over the entries of (sum_w P_w) * (sum_w Q_w), the tile (0,1)
+// counted twice (it stands for its mirror image too); one workgroup of 1024 threads per example, the shares added in
+// the order of the workgroups, the layers in the order of the launch
 constexpr int kFinishThreads = 1024;
 template <int NB>
-__global__ __launch_bounds__(kFinishThreads) void k_gram16_cols_finish(const float* __restrict__ part, int W, int accumulate,
+__global__ __launch_bounds__(kFinishThreads) void k_gram16_cols_finish(GramColsArgs j, int accumulate,
                                                                        float* __restrict__ sqnorm, float C, float* __restrict__ clip) {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int HALF = NT * 16 * 64;
     constexpr int PER = HALF / kFinishThreads;       // entries per thread: 1 or 3 (one of each tile)
     __shared__ float red[kFinishThreads / 64];
     const int ex = blockIdx.x;
-    const float* base = part + (size_t)ex * W * 2 * HALF + threadIdx.x;
-    float p[PER], q[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) { p[i] = 0.f; q[i] = 0.f; }
-#pragma unroll 4
-    for (int w = 0; w < W; ++w) {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            p[i] += base[(size_t)w * 2 * HALF + i * kFinishThreads];
-            q[i] += base[(size_t)w * 2 * HALF + HALF + i * kFinishThreads];
-        }
-    }
     float s = 0.f;
+    for (int li = 0; li < j.n_layers; ++li) {
+        const int W = j.layer[li].W;
+        const float* base = j.part + j.layer[li].part_off + (size_t)ex * W * 2 * HALF + threadIdx.x;
+        float p[PER], q[PER];
 #pragma unroll
-    for (int i = 0; i < PER; ++i) s += (NB == 2 && i == 1) ? 2.0f * (p[i] * q[i]) : p[i] * q[i];
+        for (int i = 0; i < PER; ++i) { p[i] = 0.f; q[i] = 0.f; }
+#pragma unroll 4
+        for (int w = 0; w < W; ++w) {
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                p[i] += base[(size_t)w * 2 * HALF + i * kFinishThreads];
+                q[i] += base[(size_t)w * 2 * HALF + HALF + i * kFinishThreads];
+            }
+        }
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) t += (NB == 2 && i == 1) ? 2.0f * (p[i] * q[i]) : p[i] * q[i];
+        s += t;
+    }
     s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
@@ -186,24 +204,49 @@ GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out) {
     return p;
 }
 
-hipError_t launch_gram_cols(const GramColsPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, bool f16, const ClipOut* co) {
-    if (!p.use) return hipErrorInvalidValue;
+// layers: every one with plan_gram_cols(...).use and the same .nb; ws: the sum of their ws_floats
+hipError_t launch_gram_cols_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm, float* ws,
+                                   hipStream_t st, bool f16, const ClipOut* co) {
+    if (n_layers < 1 || n_layers > kGramColsLayers) return hipErrorInvalidValue;
     GramColsArgs a;
-    a.A = A; a.G = G; a.part = ws;
-    a.T = T; a.d_in = d_in; a.d_out = d_out;
-    a.steps_a = ceil_div(d_in, 16); a.steps = a.steps_a + ceil_div(d_out, 16);
-    a.W = p.W; a.per_wave = p.per_wave;
-    const unsigned grid = (unsigned)((int64_t)B * p.W);
-    if (p.nb == 1) { if (f16) k_gram16_cols<1, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<1, false><<<grid, kThreads, 0, st>>>(a); }
-    else           { if (f16) k_gram16_cols<2, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<2, false><<<grid, kThreads, 0, st>>>(a); }
+    a.part = ws; a.n_layers = n_layers;
+    int nb = 0;
+    int64_t blocks = 0;
+    size_t off = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const GramLayerDesc& y = layers[l];
+        const GramColsPlan p = plan_gram_cols(B, y.T, y.d_in, y.d_out);
+        if (!p.use || (l > 0 && p.nb != nb)) return hipErrorInvalidValue;
+        nb = p.nb;
+        GramColsLayer& g = a.layer[l];
+        g.A = static_cast<const uint16_t*>(y.A); g.G = static_cast<const uint16_t*>(y.G);
+        g.part_off = off;
+        g.T = y.T; g.d_in = y.d_in; g.d_out = y.d_out;
+        g.steps_a = ceil_div(y.d_in, 16); g.steps = g.steps_a + ceil_div(y.d_out, 16);
+        g.W = p.W; g.per_wave = p.per_wave;
+        g.first_block = (unsigned)blocks;
+        blocks += (int64_t)B * p.W;
+        off += p.ws_floats;
+    }
+    for (int l = n_layers; l < kGramColsLayers; ++l) a.layer[l] = a.layer[0];
+    if (blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)blocks;
+    if (nb == 1) { if (f16) k_gram16_cols<1, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<1, false><<<grid, kThreads, 0, st>>>(a); }
+    else         { if (f16) k_gram16_cols<2, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<2, false><<<grid, kThreads, 0, st>>>(a); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const float C = co ? co->C : 0.f;
     float* clip = co ? co->clip : nullptr;
-    if (p.nb == 1) k_gram16_cols_finish<1><<<B, kFinishThreads, 0, st>>>(ws, p.W, accumulate ? 1 : 0, sqnorm, C, clip);
-    else           k_gram16_cols_finish<2><<<B, kFinishThreads, 0, st>>>(ws, p.W, accumulate ? 1 : 0, sqnorm, C, clip);
+    if (nb == 1) k_gram16_cols_finish<1><<<B, kFinishThreads, 0, st>>>(a, accumulate ? 1 : 0, sqnorm, C, clip);
+    else         k_gram16_cols_finish<2><<<B, kFinishThreads, 0, st>>>(a, accumulate ? 1 : 0, sqnorm, C, clip);
     return hipGetLastError();
+}
+
+hipError_t launch_gram_cols(const GramColsPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
+                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, bool f16, const ClipOut* co) {
+    if (!p.use) return hipErrorInvalidValue;
+    GramLayerDesc y{A, G, T, d_in, d_out, nullptr, nullptr};
+    return launch_gram_cols_layers(&y, 1, B, accumulate, sqnorm, ws, st, f16, co);
 }
 
 }  // namespace dpk

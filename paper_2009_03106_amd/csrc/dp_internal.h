@@ -19,7 +19,12 @@ inline bool tiles_fit(int M, int N, int TM, int TN) {
 // dt: 0 = float32, 1 = bf16, 2 = fp16 (the values of dp_dtype)
 // Where a norm launcher's last kernel completes the norms of the whole model, it can write the clip factors
 // clip[i] = 1 / max(1, sqrt(s_i) / C) too (co != nullptr), which saves the launch of their own kernel.
-struct ClipOut { float C; float* clip; };
+// defer: the several-layers call collects the partial sums of its layers that run one by one and folds them all in
+// one launch at the end (launch_finalize_queue) instead of one small launch per layer; a launcher that ends in
+// launch_finalize_partials then only records where its partial sums are.
+struct FinalizeQueue { static constexpr int kMax = 16; const float* partial[kMax]; int n[kMax]; int count = 0; };
+struct ClipOut { float C; float* clip; FinalizeQueue* defer = nullptr; };
+hipError_t launch_finalize_queue(const FinalizeQueue& q, int B, bool accumulate, float* sqnorm, hipStream_t st, const ClipOut* co);
 hipError_t launch_sqnorm_dense(const void* A, const void* G, int B, int d_in, int d_out, int dt,
                                bool accumulate, float* sqnorm, hipStream_t st, const ClipOut* co = nullptr);
 constexpr int kDenseBatch = 16;        // dense (T = 1) layers per launch of the several-layers call
@@ -124,7 +129,7 @@ inline JointPlan plan_joint(const JointShape* sh, int n_layers, int B, int dk, i
     constexpr int64_t kItemOverhead = 16;            // prologue + slice store + the slice's share of the fold, in stage times
     JointPlan best{};
     int64_t best_cost = -1, stages_max = 1;
-    for (int l = 0; l < n_layers; ++l) stages_max = stages_max > (int64_t)B * (sh[l].T / dk) ? stages_max : (int64_t)B * (sh[l].T / dk);
+    for (int l = 0; l < n_layers; ++l) stages_max = stages_max > (int64_t)B * ceil_div(sh[l].T, dk) ? stages_max : (int64_t)B * ceil_div(sh[l].T, dk);
     for (int64_t S = 1; S <= 512 && S <= stages_max; ++S) {
         const int64_t len = (stages_max + S - 1) / S;
         if (len < 8 && S > 1) break;
@@ -132,7 +137,7 @@ inline JointPlan plan_joint(const JointShape* sh, int n_layers, int B, int dk, i
         p.n_layers = n_layers;
         int64_t longest = 0;
         for (int l = 0; l < n_layers; ++l) {
-            const int64_t spe = sh[l].T / dk, stages = (int64_t)B * spe;
+            const int64_t spe = ceil_div(sh[l].T, dk), stages = (int64_t)B * spe;
             const int64_t want = len < 63 * spe ? len : 63 * spe;   // a slice touches at most 64 examples (one clip factor per lane)
             int64_t splits = (stages + want - 1) / want;
             const int64_t sps = (stages + splits - 1) / splits;
@@ -149,6 +154,7 @@ inline JointPlan plan_joint(const JointShape* sh, int n_layers, int B, int dk, i
 }
 bool dma_joint_ok(int T, int M, int N);
 bool dma_joint_mid_ok(int T, int M, int N);      // the second class: 128 x 128 tiles, geo = 3 below
+bool dma_joint_ragged_ok(int T, int M, int N);   // the same tiles, T not a multiple of the stage: geo = 4
 size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B, int geo = 1);
 // the same for 8-bit inputs (dp_tn_f8_dma.hip; 256 x 256 tiles, T a multiple of 64); A, G of JointOperands are byte pointers
 bool dma8_joint_ok(int T, int M, int N);
@@ -204,16 +210,21 @@ bool gram_dma_ok(int T, int d_in, int d_out, int fmt = 0);
 // array's clip factors go once the launch's last layer naming it has been added
 struct GramLayerDesc { const void* A; const void* G; int T, d_in, d_out; float* upart; float* bias_rows;
                        float* out = nullptr; bool out_acc = false; float out_C = 0.f; float* out_clip = nullptr; };
-hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
-                                       float* partial, hipStream_t st, int fmt, float C = 0.f, float* clip = nullptr);
-hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
-                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co = nullptr);
 // few positions (T <= 64), wide rows, small batch (dp_gram_bf16_cols.hip): the columns are split over workgroups.
 // use: whether this kernel takes the shape; ws_floats: its scratch
 struct GramColsPlan { bool use; int nb, W, per_wave; size_t ws_floats; };
 GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out);
+// several such layers (all with the same plan .nb) in one launch; ws: the sum of their ws_floats (A, G, T, d_in, d_out of
+// the descriptors are used)
+constexpr int kGramColsLayers = 16;
+hipError_t launch_gram_cols_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm, float* ws,
+                                   hipStream_t st, bool f16, const ClipOut* co = nullptr);
 hipError_t launch_gram_cols(const GramColsPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
                             bool accumulate, float* sqnorm, float* ws, hipStream_t st, bool f16, const ClipOut* co = nullptr);
+hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
+                                       float* partial, hipStream_t st, int fmt, float C = 0.f, float* clip = nullptr);
+hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
+                                bool accumulate, float* sqnorm, float* partial, hipStream_t st, int fmt, const ClipOut* co = nullptr);
 // float32 inputs (dp_gram_f32.hip): 64-row tiles
 GramPlan plan_gram_f32(int T);
 hipError_t launch_gram_f32(const GramPlan& p, const float* A, const float* G, int B, int T, int d_in, int d_out,

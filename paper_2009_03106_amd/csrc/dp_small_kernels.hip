@@ -285,8 +285,38 @@ __global__ void k_finalize_partials(const float* __restrict__ partial, int B, in
     if (clip) clip[i] = clip_factor_of(s, C);
 }
 
+// The partial sums of several layers, each [B][n_l]: one wave per example; lane j adds entries j, j + 64, ... of every
+// layer in the order of the queue, then the lanes' sums are added in the fixed order of wave_sum.
+__global__ __launch_bounds__(64) void k_finalize_queue(FinalizeQueue q, int accumulate, float* __restrict__ sqnorm, float C,
+                                                       float* __restrict__ clip) {
+    const int i = blockIdx.x, lane = threadIdx.x;
+    float v = 0.f;
+#pragma unroll 4
+    for (int l = 0; l < q.count; ++l) {
+        const float* p = q.partial[l] + (size_t)i * q.n[l];
+        for (int j = lane; j < q.n[l]; j += 64) v += p[j];
+    }
+    v = wave_sum(v);
+    if (lane == 0) {
+        const float s = accumulate ? sqnorm[i] + v : v;
+        sqnorm[i] = s;
+        if (clip) clip[i] = clip_factor_of(s, C);
+    }
+}
+
+hipError_t launch_finalize_queue(const FinalizeQueue& q, int B, bool accumulate, float* sqnorm, hipStream_t st, const ClipOut* co) {
+    if (q.count < 1 || q.count > FinalizeQueue::kMax || B < 1) return hipErrorInvalidValue;
+    k_finalize_queue<<<(unsigned)B, 64, 0, st>>>(q, accumulate ? 1 : 0, sqnorm, co ? co->C : 0.f, co ? co->clip : nullptr);
+    return hipGetLastError();
+}
+
 hipError_t launch_finalize_partials(const float* partial, int B, int n, bool accumulate, float* sqnorm, hipStream_t st,
                                     const ClipOut* co) {
+    if (co && co->defer && co->defer->count < FinalizeQueue::kMax) {
+        FinalizeQueue& q = *co->defer;
+        q.partial[q.count] = partial; q.n[q.count] = n; ++q.count;
+        return hipSuccess;
+    }
     k_finalize_partials<<<(B + 63) / 64, 64, 0, st>>>(partial, B, n, accumulate ? 1 : 0, sqnorm, co ? co->C : 0.f, co ? co->clip : nullptr);
     return hipGetLastError();
 }

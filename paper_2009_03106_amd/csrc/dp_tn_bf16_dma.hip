@@ -445,7 +445,11 @@ struct JointArgs {
     JointLayer layer[kJointMax];
     int n_layers, n_items, per_xcd, B;
 };
-template <class GEO, bool F16>
+// the ragged mode's line of zeros (never written)
+__device__ __attribute__((aligned(256))) unsigned int g_zero_line[64];
+
+// AM: 0 = every layer's T is a multiple of the 32-row stage, 2 = ragged T (stages padded with the line of zeros)
+template <class GEO, bool F16, int AM>
 __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma_joint(JointArgs j) {
     const int L = (blockIdx.x & 7) * j.per_xcd + (blockIdx.x >> 3);
     if (L >= j.n_items) return;
@@ -459,8 +463,9 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma_joint(Jo
     a.tiles_m = y.tiles_m; a.tiles_n = y.tiles_n; a.splits = y.splits;
     a.stages_total = y.stages_total; a.stages_per_split = y.stages_per_split;
     a.per_xcd = 0; a.accumulate = 0;
-    a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0; a.zero = nullptr;
-    tn_dma_tile<GEO, 0, 0, F16>(a, L - y.first_item);
+    a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0;
+    a.zero = AM == 2 ? reinterpret_cast<const uint16_t*>(g_zero_line) : nullptr;
+    tn_dma_tile<GEO, 0, AM, F16>(a, L - y.first_item);
 }
 
 
@@ -590,10 +595,16 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
 //             1152 -> 128, ...): alone each of them is a launch of 10 to 30 us that fills a fraction of the chip and
 //             a fold behind it; tiles may be mostly padding, these layers are bound by latency and bandwidth.
 bool dma_joint_ok(int T, int M, int N) { return T > 0 && (T % DK) == 0 && dma_geometry(T, M, N) == 1; }
+//      geo 4: the same tiles for such layers whose T is not a multiple of the 32-row stage (at least 16 positions:
+//             4 x 4 positions of a late convolution); the stages of an example's last rows are filled up with zeros.
 bool dma_joint_mid_ok(int T, int M, int N) {
     if (T <= 0 || (T % DK) != 0 || ((M | N) & 7) != 0 || M < 64 || N < 64) return false;
     if ((int64_t)DK * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;        // 32-bit lane offsets inside a stage
     return dma_geometry(T, M, N) != 1;
+}
+bool dma_joint_ragged_ok(int T, int M, int N) {
+    if (T < 16 || (T % DK) == 0 || ((M | N) & 7) != 0 || M < 64 || N < 64) return false;
+    return (int64_t)T * (M > N ? M : N) * 2 < (int64_t(1) << 31);                      // 32-bit lane offsets inside an example
 }
 namespace {
 inline int joint_tile(int geo) { return geo == 1 ? GeoL::TM : GeoT::TM; }
@@ -610,7 +621,7 @@ size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B, int geo
 
 hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
                                          float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16, int geo) {
-    if (n_layers < 1 || n_layers > kJointMax || (geo != 1 && geo != 3)) return hipErrorInvalidValue;
+    if (n_layers < 1 || n_layers > kJointMax || (geo != 1 && geo != 3 && geo != 4)) return hipErrorInvalidValue;
     const JointPlan p = plan_joint(sh, n_layers, B, DK, joint_tile(geo), joint_slots(geo));
     if (p.items >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     JointArgs j;
@@ -622,7 +633,7 @@ hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperan
         y.slices = slices;
         y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
         y.tiles_m = p.tiles_m[l]; y.tiles_n = p.tiles_n[l]; y.splits = p.splits[l];
-        y.stages_total = (int)((int64_t)B * (sh[l].T / DK)); y.stages_per_split = p.sps[l];
+        y.stages_total = (int)((int64_t)B * ceil_div(sh[l].T, DK)); y.stages_per_split = p.sps[l];
         y.first_item = (int)first;
         first += (int64_t)p.tiles_m[l] * p.tiles_n[l] * p.splits[l];
         slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
@@ -632,14 +643,17 @@ hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperan
     j.B = B;
     const unsigned grid = 8u * (unsigned)j.per_xcd;
     if (geo == 1) {
-        if (f16) k_tn_bf16_dma_joint<GeoL, true><<<grid, GeoL::THREADS, 0, st>>>(j);
-        else     k_tn_bf16_dma_joint<GeoL, false><<<grid, GeoL::THREADS, 0, st>>>(j);
+        if (f16) k_tn_bf16_dma_joint<GeoL, true, 0><<<grid, GeoL::THREADS, 0, st>>>(j);
+        else     k_tn_bf16_dma_joint<GeoL, false, 0><<<grid, GeoL::THREADS, 0, st>>>(j);
+    } else if (geo == 3) {
+        if (f16) k_tn_bf16_dma_joint<GeoT, true, 0><<<grid, GeoT::THREADS, 0, st>>>(j);
+        else     k_tn_bf16_dma_joint<GeoT, false, 0><<<grid, GeoT::THREADS, 0, st>>>(j);
     } else {
-        if (f16) k_tn_bf16_dma_joint<GeoT, true><<<grid, GeoT::THREADS, 0, st>>>(j);
-        else     k_tn_bf16_dma_joint<GeoT, false><<<grid, GeoT::THREADS, 0, st>>>(j);
+        if (f16) k_tn_bf16_dma_joint<GeoT, true, 2><<<grid, GeoT::THREADS, 0, st>>>(j);
+        else     k_tn_bf16_dma_joint<GeoT, false, 2><<<grid, GeoT::THREADS, 0, st>>>(j);
     }
     hipError_t e = hipGetLastError();
-    if (geo == 3 && e == hipSuccess) {
+    if (geo != 1 && e == hipSuccess) {
         // many small layers: one launch folds them all
         FoldLayers f;
         f.n_layers = n_layers;
@@ -666,13 +680,24 @@ bool dma_conv_ok(const ConvGeom& g, int N) {
     if ((int64_t)g.H * g.W * g.C * 2 >= (int64_t(1) << 31)) return false;
     const int64_t T = Hout * Wout, M = (int64_t)g.KH * g.KW * g.C;
     if (T >= (int64_t(1) << 31) || M >= (int64_t(1) << 24)) return false;
-    return dma_direct_ok((int)T, (int)M, N);
+    return T >= 64 && dma_geometry((int)T, (int)M, N) != 0;
 }
 
-bool dma_direct_ok(int T, int M, int N) { return T >= 64 && dma_geometry(T, M, N) != 0; }
+// The direct norm stores nothing, and for long examples of few columns (positions x (576 -> 64) of an unfolded
+// convolution) it is bound by reading them: there 128 x 128 tiles that are up to 60 % padding still beat the kernels
+// that repack through registers (clamped columns are read again from L2, their products are masked out).
+static bool direct_padded_ok(int T, int M, int N) {
+    if (((M | N) & 7) != 0 || M < 32 || N < 32 || T < 4 * DK) return false;
+    if ((T % DK) != 0 && (int64_t)ceil_div(T, DK) * DK * 4 > (int64_t)T * 5) return false;
+    if ((int64_t)DK * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;
+    const int64_t padded = (int64_t)ceil_div(M, GeoT::TM) * GeoT::TM * ceil_div(N, GeoT::TN) * GeoT::TN;
+    return padded * 2 <= (int64_t)M * N * 5;
+}
+bool dma_direct_ok(int T, int M, int N) { return T >= 64 && (dma_geometry(T, M, N) != 0 || direct_padded_ok(T, M, N)); }
 
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N) {
-    const GeoDims gd = geo_dims(pick_geometry(T, M, N, B));      // one workgroup per (example, tile)
+    const int geo = dma_geometry(T, M, N) != 0 ? pick_geometry(T, M, N, B) : 3;
+    const GeoDims gd = geo_dims(geo);      // one workgroup per (example, tile)
     TnPlan p;
     p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);

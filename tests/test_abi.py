@@ -123,7 +123,8 @@ def test_workspace_sizes_over_many_shapes(lib):
 
 def test_layers_workspace_sizes(lib):
     """Host logic of the several-layers call: the copy-pipeline Gram layers of one launch (at most 16) have their partial
-    sums side by side, every other layer needs what dp_layer_sqnorm needs, and the two groups share the space."""
+    sums side by side, the layers that run one by one each have what dp_layer_sqnorm needs, side by side too (one launch
+    folds them at the end), and the two groups share the space."""
     import ctypes
     def descs(shapes):
         arr = (dpclip.LayerDesc * len(shapes))()
@@ -134,10 +135,16 @@ def test_layers_workspace_sizes(lib):
     tr = descs([(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)])
     assert f(tr, 64, dpclip.DP_BF16) == 4 * 64 * 10 * 4                  # 10 pairs of 128-row tiles per example and layer
     assert f(tr, 64, dpclip.DP_F16) == f(tr, 64, dpclip.DP_BF16)
-    assert f(tr, 64, dpclip.DP_F32) == 64 * 36 * 4                        # fp32 Gram: 8 tiles of 64 rows, 36 pairs, one layer at a time
-    assert f(tr, 64, dpclip.DP_F32, "direct") == max(dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 64, *sh, dpclip.DP_F32, "direct")
+    assert f(tr, 64, dpclip.DP_F32) == 4 * 64 * 36 * 4                    # fp32 Gram: 8 tiles of 64 rows, 36 pairs, four layers
+    assert f(tr, 64, dpclip.DP_F32, "direct") == sum((dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 64, *sh, dpclip.DP_F32, "direct") + 15) // 16 * 16
                                             for sh in [(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)])
-    assert f(tr, 64, dpclip.DP_F32, "gram") == 64 * 36 * 4
+    assert f(tr, 64, dpclip.DP_F32, "gram") == 4 * 64 * 36 * 4
+    assert f(descs([(512, 768, 2304)]), 64, dpclip.DP_F32) == 64 * 36 * 4
+    # few positions, wide rows, small batch (16-bit): the shared column-split Gram launch keeps every layer's shares
+    cols = descs([(16, 4608, 512), (16, 2304, 512), (64, 2304, 256)])
+    one = [dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 32, *sh, dpclip.DP_BF16, "gram") for sh in [(16, 4608, 512), (16, 2304, 512), (64, 2304, 256)]]
+    assert all(n > 32 * 4 for n in one)
+    assert f(cols, 32, dpclip.DP_BF16, "gram") == max(one[0] + one[1], one[2])     # T <= 32 and T <= 64 in launches of their own
     wb = descs([(512, 768, 2304), (512, 768, 768)])
     wb[0].bias_rows = 16                    # any non-null value: only the sizes are looked at
     assert f(wb, 64, dpclip.DP_BF16) == 2 * 64 * 10 * 4 + 64 * 4 * 2304 * 4     # + column sums per 128-row tile

@@ -507,7 +507,9 @@ def test_layers_clipped_grad_equals_per_layer_calls(dp, name, B):
 # that still gives every layer several K slices; one shape that is not aligned (the first convolution's 27 patch
 # columns) keeps to the launches of its own between the others.
 CNN_STACK = [(256, 27, 64), (256, 576, 64), (256, 576, 64), (64, 576, 128), (64, 1152, 128), (64, 64, 128),
-             (32, 1152, 256), (32, 2304, 256), (32, 128, 256)]
+             (32, 1152, 256), (32, 2304, 256), (32, 128, 256),
+             # position counts that are not multiples of the 32-row stage (4 x 4, 7 x 7, 10 x 10): a launch of their own
+             (16, 2304, 512), (16, 256, 512), (49, 1152, 256), (100, 576, 64)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
@@ -1387,3 +1389,48 @@ def test_gram_column_split_few_positions(dp, dtype, B, T, d_in, d_out):
     s3 = dp.layers_sqnorm([(Ad, Gd), (Ad, Gd)], C=C, clip=c, path="gram")
     assert rel_err(s3.cpu().numpy(), 2 * s_ref) <= SQ_TIGHT[dtype]
     np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s3, C).cpu().numpy())
+
+
+# Long examples of few columns (unfolded convolutions with 64 output channels): the direct norm takes 128 x 128 tiles
+# that are more than half padding, whose clamped columns must not reach the sum.  One column tile and several, a
+# ragged last stage, padding on both sides.
+DIRECT_PADDED_SHAPES = [(3, 160, 576, 64), (2, 128, 64, 192), (4, 200, 72, 328), (5, 136, 72, 96)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,T,d_in,d_out", DIRECT_PADDED_SHAPES)
+def test_direct_norm_padded_tiles(dp, dtype, B, T, d_in, d_out):
+    A, G = wl.random_layer(6200 + T + d_in, B, T, d_in, d_out, dtype, g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    Ad, Gd = to_dev(A), to_dev(G)
+    s = dp.layer_sqnorm(Ad, Gd, path="direct")
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], rel_err(s.cpu().numpy(), s_ref)
+    s2 = torch.full((B,), 0.5, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, s2, path="direct", accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
+    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_layers_sqnorm_many_layers_that_run_one_by_one(dp, dtype):
+    """Twenty layers outside the shared launches (direct path, unaligned widths, short Gram layers): their partial
+    sums are folded by one launch per 16 layers, together with kernels that add their norms themselves; the clip
+    factors come from the last fold."""
+    B = 24
+    shapes = [(40, 72, 40), (33, 27, 64), (64, 40, 24), (130, 36, 20), (7, 300, 10)] * 4
+    layers = [wl.random_layer(7300 + i, B, T, di, do, dtype, g_row_scale=np.exp(np.linspace(-1, 1, B))) for i, (T, di, do) in enumerate(shapes)]
+    s_ref = orc.total_sqnorm(layers)
+    C = float(np.sqrt(np.median(s_ref)))
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    c = torch.full((B,), -1.0, device="cuda")
+    s = dp.layers_sqnorm(dev, C=C, clip=c)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype]
+    np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s, C).cpu().numpy())
+    one_by_one = None
+    for li, (A, G) in enumerate(dev):
+        one_by_one = dp.layer_sqnorm(A, G, one_by_one, accumulate=li > 0)
+    assert rel_err(s.cpu().numpy(), one_by_one.cpu().numpy().astype(np.float64)) <= 2e-6      # float32 order of the sums
+    s2 = torch.full((B,), 0.5, device="cuda")
+    dp.layers_sqnorm(dev, s2, accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
+    np.testing.assert_array_equal(dp.layers_sqnorm(dev).cpu().numpy(), s.cpu().numpy())       # reruns are bit-identical
