@@ -652,25 +652,17 @@ hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperan
         if (f16) k_tn_bf16_dma_joint<GeoT, true, 2><<<grid, GeoT::THREADS, 0, st>>>(j);
         else     k_tn_bf16_dma_joint<GeoT, false, 2><<<grid, GeoT::THREADS, 0, st>>>(j);
     }
-    hipError_t e = hipGetLastError();
-    if (geo != 1 && e == hipSuccess) {
-        // many small layers: one launch folds them all
-        FoldLayers f;
-        f.n_layers = n_layers;
-        for (int l = 0; l < n_layers; ++l) {
-            f.ws[l] = j.layer[l].slices; f.grad[l] = op[l].grad; f.n[l] = (int64_t)sh[l].M * sh[l].N;
-            f.splits[l] = p.splits[l]; f.noise_offset[l] = op[l].noise_offset;
-        }
-        for (int l = n_layers; l < kJointLayers; ++l) { f.ws[l] = f.ws[0]; f.grad[l] = f.grad[0]; f.n[l] = 0; f.splits[l] = 0; f.noise_offset[l] = 0; }
-        return launch_splitk_reduce_layers(f, accumulate, st, stddev, seed);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // one launch folds the slices of all layers (+ noise): a fold per layer is a launch of a few microseconds each
+    FoldLayers f;
+    f.n_layers = n_layers;
+    for (int l = 0; l < n_layers; ++l) {
+        f.ws[l] = j.layer[l].slices; f.grad[l] = op[l].grad; f.n[l] = (int64_t)sh[l].M * sh[l].N;
+        f.splits[l] = p.splits[l]; f.noise_offset[l] = op[l].noise_offset;
     }
-    // the folds of the layers' slices (+ noise), each as after a launch of the layer alone
-    for (int l = 0; l < n_layers && e == hipSuccess; ++l) {
-        const NoiseArgs nz{stddev, (uint32_t)seed, (uint32_t)(seed >> 32), op[l].noise_offset};
-        e = launch_splitk_reduce(j.layer[l].slices, (int64_t)sh[l].M * sh[l].N, p.splits[l], accumulate, op[l].grad, st,
-                                 stddev != 0.0f ? &nz : nullptr);
-    }
-    return e;
+    for (int l = n_layers; l < kJointLayers; ++l) { f.ws[l] = f.ws[0]; f.grad[l] = f.grad[0]; f.n[l] = 0; f.splits[l] = 0; f.noise_offset[l] = 0; }
+    return launch_splitk_reduce_layers(f, accumulate, st, stddev, seed);
 }
 
 // implicit unfolding: whole 16-byte pieces must stay inside one pixel's channels, image offsets must fit 32 bits

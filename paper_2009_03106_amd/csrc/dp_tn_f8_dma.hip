@@ -523,14 +523,18 @@ hipError_t launch_clipped_f8_dma_joint(const JointShape* sh, const JointOperands
     else if (fmt == 3) k_tn_f8_dma_joint<1, 1><<<grid, Geo8L::THREADS, 0, st>>>(j);
     else if (fmt == 4) k_tn_f8_dma_joint<0, 1><<<grid, Geo8L::THREADS, 0, st>>>(j);
     else return hipErrorInvalidValue;
-    hipError_t e = hipGetLastError();
-    // the folds of the layers' slices (+ noise), each as after a launch of the layer alone
-    for (int l = 0; l < n_layers && e == hipSuccess; ++l) {
-        const NoiseArgs nz{stddev, (uint32_t)seed, (uint32_t)(seed >> 32), op[l].noise_offset};
-        e = launch_splitk_reduce(j.layer[l].slices, (int64_t)sh[l].M * sh[l].N, p.splits[l], accumulate, op[l].grad, st,
-                                 stddev != 0.0f ? &nz : nullptr);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // one launch folds the slices of all layers (+ noise)
+    FoldLayers f;
+    f.n_layers = n_layers;
+    for (int l = 0; l < kJointLayers; ++l) {
+        const int k = l < n_layers ? l : 0;
+        f.ws[l] = j.layer[k].slices; f.grad[l] = op[k].grad;
+        f.n[l] = l < n_layers ? (int64_t)sh[l].M * sh[l].N : 0; f.splits[l] = l < n_layers ? p.splits[l] : 0;
+        f.noise_offset[l] = op[k].noise_offset;
     }
-    return e;
+    return launch_splitk_reduce_layers(f, accumulate, st, stddev, seed);
 }
 
 TnPlan plan_direct_f8_dma(int B, int T, int M, int N) {
