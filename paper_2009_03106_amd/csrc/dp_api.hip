@@ -85,8 +85,8 @@ bool g_is_e5m2(dp_dtype d) { return d != DP_F8_E4M3; }
 size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
     if (is8(dtype) && !f8_path_ok(path, dtype, T, d_in, d_out)) return 0;
     if (path == DP_PATH_GRAM) {
-        if (is16(dtype)) {
-            const GramColsPlan c = plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out);
+        if (!is8(dtype)) {
+            const GramColsPlan c = plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out, (int)dtype);
             if (c.use) return c.ws_floats * sizeof(float);
         }
         GramPlan g = (is16(dtype) || is8(dtype)) ? plan_gram_bf16((int)T, (int)d_in, (int)d_out) : plan_gram_f32((int)T);
@@ -118,9 +118,9 @@ bool gram_batchable(int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_p
 // a layer that the shared column-split Gram launches of dp_layers_sqnorm take (few positions, wide rows, small batch):
 // 0 = no, else the launch class (the plan's number of 32-row blocks)
 int gram_cols_class(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
-    if (!is16(dtype) || T <= 1 || T > 64 || d_in == 0 || d_out == 0 || B >= (int64_t(1) << 20)) return 0;
+    if (is8(dtype) || T <= 1 || T > 64 || d_in == 0 || d_out == 0 || B >= (int64_t(1) << 20)) return 0;
     if (resolve_path(path, dtype, T, d_in, d_out) != DP_PATH_GRAM) return 0;
-    const GramColsPlan c = plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out);
+    const GramColsPlan c = plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out, (int)dtype);
     return c.use ? c.nb : 0;
 }
 
@@ -283,13 +283,12 @@ dp_status layer_sqnorm_clip(const void* A, const void* G, int64_t B, int64_t T, 
         else
             e = launch_direct_f8_dma(plan_direct_f8_dma((int)B, (int)T, (int)d_in, (int)d_out), A, G, (int)B, (int)T, (int)d_in,
                                      (int)d_out, accumulate != 0, sqnorm, partial, stream, fmt_of(dtype), co);
+    } else if (p == DP_PATH_GRAM && plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out, (int)dtype).use) {
+        e = launch_gram_cols(plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out, (int)dtype), A, G, (int)B, (int)T, (int)d_in,
+                             (int)d_out, accumulate != 0, sqnorm, partial, stream, (int)dtype, co);
     } else if (p == DP_PATH_GRAM && !is16(dtype)) {
         e = launch_gram_f32(plan_gram_f32((int)T), static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
                             (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, co);
-    } else if (p == DP_PATH_GRAM && plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out).use) {
-        e = launch_gram_cols(plan_gram_cols((int)B, (int)T, (int)d_in, (int)d_out), static_cast<const uint16_t*>(A),
-                             static_cast<const uint16_t*>(G), (int)B, (int)T, (int)d_in, (int)d_out, accumulate != 0, sqnorm,
-                             partial, stream, dtype == DP_F16, co);
     } else if (p == DP_PATH_GRAM) {
         GramPlan g = plan_gram_bf16((int)T, (int)d_in, (int)d_out);
         e = launch_gram_bf16(g, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
@@ -637,7 +636,7 @@ size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
             const dp_layer_desc& y = layers[l];
             if (B == 0 || gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != cls) continue;
             if (in_group == kGramColsLayers) { in_group = 0; group = 0; }
-            group += plan_gram_cols((int)B, (int)y.T, (int)y.d_in, (int)y.d_out).ws_floats * sizeof(float);
+            group += plan_gram_cols((int)B, (int)y.T, (int)y.d_in, (int)y.d_out, (int)dtype).ws_floats * sizeof(float);
             ++in_group;
             if (group > batch_max) batch_max = group;
         }
@@ -706,7 +705,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
                 if (ng == 0) return hipSuccess;
                 cols_done += ng;
                 const hipError_t e = launch_gram_cols_layers(group, ng, (int)B, acc != 0, sqnorm, static_cast<float*>(workspace), stream,
-                                                             dtype == DP_F16, (clip_with_cols && cols_done == n_cols) ? &clip_out : nullptr);
+                                                             (int)dtype, (clip_with_cols && cols_done == n_cols) ? &clip_out : nullptr);
                 ng = 0; acc = 1; launched = true;
                 return e;
             };

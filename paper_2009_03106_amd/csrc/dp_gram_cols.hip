@@ -1,16 +1,19 @@
 // Gram path for the per-example squared norm (Section 5.2, the sum over position pairs of
-// (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}), 16-bit inputs, for layers of few positions (T <= 64) and wide rows in a
-// small batch: the late convolutions of an image model (4 x 4 or 8 x 8 positions, 2304 -> 256 or 4608 -> 512
-// unfolded columns, 20 to 32 examples).  One workgroup per example walks thousands of columns alone there and
-// leaves most of the chip idle, so here the COLUMNS are split: every wave takes a range of the columns of A and G
-// (one after the other), forms its share of A_i A_i^T and of G_i G_i^T straight from registers, the four waves of a
-// workgroup add their shares through LDS, and a second kernel adds the workgroups' shares of an example in a fixed
-// order, multiplies the two T x T products entry by entry and sums.
+// (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}) for layers of few positions (T <= 64) and wide rows in a small batch: the late
+// convolutions of an image model (4 x 4 or 8 x 8 positions, 2304 -> 256 or 4608 -> 512 unfolded columns, 20 to 32
+// examples).  One workgroup per example walks thousands of columns alone there and leaves most of the chip idle, so
+// here the COLUMNS are split: every wave takes a range of the columns of A and G (one after the other), forms its
+// share of A_i A_i^T and of G_i G_i^T straight from registers, the four waves of a workgroup add their shares
+// through LDS, and a second kernel adds the workgroups' shares of an example in a fixed order, multiplies the two
+// T x T products entry by entry and sums.
 //
-// No LDS staging of the inputs: both operands of a Gram product are rows of the same matrix, and a lane's 16-byte
-// piece of global memory (8 consecutive columns of one row) is exactly an MFMA operand of the 32 x 32 x 16
-// instruction (row = lane % 32, columns 8 * (lane / 32) .. + 7 of the step) for the left and for the right side.
-// A wave issues the loads of 8 steps before the first MFMA, so a range of 128 columns is one memory round trip.
+// No LDS staging of the inputs: both operands of a Gram product are rows of the same matrix, so a lane's 16-byte
+// piece of global memory serves the left and the right side of the MFMA alike.  16-bit inputs: the piece (8
+// consecutive columns of one row) is one operand of the 32 x 32 x 16 instruction (row = lane % 32, columns
+// 8 * (lane / 32) .. + 7 of a 16-column step).  float32: the piece (4 columns) feeds four 32 x 32 x 2 instructions,
+// entry j of lanes 0-31 and of lanes 32-63 being the two columns of the j-th; which columns meet in an instruction
+// does not matter to the sum, and both sides use the same register.  A wave issues the loads of 8 steps before the
+// first MFMA, so a range of 128 (64) columns is one memory round trip.
 #include "dp_common.h"
 #include "dp_internal.h"
 
@@ -21,11 +24,11 @@ namespace {
 constexpr int kColsSteps = 8;        // 16-column steps whose loads are in flight together
 
 struct GramColsLayer {
-    const uint16_t* A;
-    const uint16_t* G;
+    const void* A;
+    const void* G;
     size_t part_off;     // floats: where the layer's shares start in the scratch
     int T, d_in, d_out;
-    int steps_a;         // 16-column steps of A; the steps of G follow them
+    int steps_a;         // steps (16 columns of 16-bit inputs, 8 of float32) of A; the steps of G follow them
     int steps;           // of A and G together
     int W;               // workgroups per example
     int per_wave;        // steps per wave
@@ -43,8 +46,8 @@ struct GramColsArgs {
 // order (0,0), (0,1), (1,1) for two 32-row blocks.  Rows >= T and columns >= D read as zero (loads go to clamped,
 // valid addresses).
 template <int NB, bool F16>
-__device__ __forceinline__ void gram_cols_run(const uint16_t* __restrict__ X, int T, int D, int kb, int ke, int lane,
-                                              f32x16 (&acc)[NB * (NB + 1) / 2]) {
+__device__ __forceinline__ void gram_cols_run16(const uint16_t* __restrict__ X, int T, int D, int kb, int ke, int lane,
+                                                f32x16 (&acc)[NB * (NB + 1) / 2]) {
     const int row = lane & 31, half = lane >> 5;
     const uint16_t* p[NB];
     bool in[NB];
@@ -81,9 +84,61 @@ __device__ __forceinline__ void gram_cols_run(const uint16_t* __restrict__ X, in
     }
 }
 
+// float32: a step is 8 columns, the lane's piece columns 4 * (lane / 32) .. + 3 of it (D a multiple of 4)
+template <int NB>
+__device__ __forceinline__ void gram_cols_run32(const float* __restrict__ X, int T, int D, int kb, int ke, int lane,
+                                                f32x16 (&acc)[NB * (NB + 1) / 2]) {
+    const int row = lane & 31, half = lane >> 5;
+    const float* p[NB];
+    bool in[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int r = b * 32 + row;
+        in[b] = r < T;
+        p[b] = X + (size_t)(r < T ? r : T - 1) * D;
+    }
+    for (int k = kb; k < ke; k += kColsSteps) {
+        float4 f[kColsSteps][NB];
+#pragma unroll
+        for (int u = 0; u < kColsSteps; ++u) {
+            const int col = (k + u) * 8 + half * 4;
+            const bool ok = (k + u) < ke && col < D;
+            const int c = ok ? col : 0;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float4 v = *reinterpret_cast<const float4*>(p[b] + c);
+                const bool keep = ok && in[b];
+                f[u][b] = make_float4(keep ? v.x : 0.f, keep ? v.y : 0.f, keep ? v.z : 0.f, keep ? v.w : 0.f);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kColsSteps; ++u) {
+            const float a0[4] = {f[u][0].x, f[u][0].y, f[u][0].z, f[u][0].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], a0[e], acc[0], 0, 0, 0);
+            if constexpr (NB == 2) {
+                const float a1[4] = {f[u][1].x, f[u][1].y, f[u][1].z, f[u][1].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], a1[e], acc[1], 0, 0, 0);
+                    acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], a1[e], acc[2], 0, 0, 0);
+                }
+            }
+        }
+    }
+}
+
+// X_i of whichever type: DT 0 = float32, 1 = bf16, 2 = fp16 (the values of dp_dtype)
+template <int NB, int DT>
+__device__ __forceinline__ void gram_cols_run(const void* X, size_t ex, int T, int D, int kb, int ke, int lane,
+                                              f32x16 (&acc)[NB * (NB + 1) / 2]) {
+    if constexpr (DT == 0) gram_cols_run32<NB>(static_cast<const float*>(X) + ex * T * D, T, D, kb, ke, lane, acc);
+    else gram_cols_run16<NB, DT == 2>(static_cast<const uint16_t*>(X) + ex * T * D, T, D, kb, ke, lane, acc);
+}
+
 // NB: 32-row blocks of positions (1: T <= 32, 2: T <= 64)
-template <int NB, bool F16>
-__global__ __launch_bounds__(kThreads, 2) void k_gram16_cols(GramColsArgs j) {
+template <int NB, int DT>
+__global__ __launch_bounds__(kThreads, 2) void k_gram_cols(GramColsArgs j) {
     constexpr int NT = NB * (NB + 1) / 2;            // tiles of the upper triangle
     constexpr int SHARE = 2 * NT * 16 * 64;          // floats of one wave's share (both products)
     __shared__ float red[2 * SHARE];
@@ -105,9 +160,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_gram16_cols(GramColsArgs j) {
     const int k0 = (w * 4 + wave) * a.per_wave;
     const int k1 = min(k0 + a.per_wave, a.steps);
     if (k0 < a.steps_a)
-        gram_cols_run<NB, F16>(a.A + (size_t)ex * a.T * a.d_in, a.T, a.d_in, k0, min(k1, a.steps_a), lane, acc[0]);
+        gram_cols_run<NB, DT>(a.A, (size_t)ex, a.T, a.d_in, k0, min(k1, a.steps_a), lane, acc[0]);
     if (k1 > a.steps_a)
-        gram_cols_run<NB, F16>(a.G + (size_t)ex * a.T * a.d_out, a.T, a.d_out, max(k0, a.steps_a) - a.steps_a, k1 - a.steps_a, lane, acc[1]);
+        gram_cols_run<NB, DT>(a.G, (size_t)ex, a.T, a.d_out, max(k0, a.steps_a) - a.steps_a, k1 - a.steps_a, lane, acc[1]);
 
     // waves 2, 3 -> LDS; waves 0, 1 add them; wave 1 -> LDS; wave 0 adds it and stores the workgroup's share
     auto put = [&](float* slot) {
@@ -143,7 +198,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_gram16_cols(GramColsArgs j) {
 // the order of the workgroups, the layers in the order of the launch
 constexpr int kFinishThreads = 1024;
 template <int NB>
-__global__ __launch_bounds__(kFinishThreads) void k_gram16_cols_finish(GramColsArgs j, int accumulate,
+__global__ __launch_bounds__(kFinishThreads) void k_gram_cols_finish(GramColsArgs j, int accumulate,
                                                                        float* __restrict__ sqnorm, float C, float* __restrict__ clip) {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int HALF = NT * 16 * 64;
@@ -185,10 +240,11 @@ __global__ __launch_bounds__(kFinishThreads) void k_gram16_cols_finish(GramColsA
 
 }  // namespace
 
-GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out) {
+GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out, int dt) {
     GramColsPlan p{};
-    if (B < 1 || T < 2 || T > 64 || d_in < 8 || d_out < 8 || ((d_in | d_out) & 7) != 0) return p;
-    const int steps = ceil_div(d_in, 16) + ceil_div(d_out, 16);
+    const int piece = dt == 0 ? 4 : 8;                   // columns of a 16-byte piece; a step is two pieces
+    if (B < 1 || T < 2 || T > 64 || dt < 0 || dt > 2 || d_in < piece || d_out < piece || ((d_in | d_out) % piece) != 0) return p;
+    const int steps = ceil_div(d_in, 2 * piece) + ceil_div(d_out, 2 * piece);
     // fill the chip (2 workgroups on each of 256 compute units) with waves of at least kColsSteps steps
     int W = ceil_div(512, B);
     const int w_max = steps / (4 * kColsSteps);
@@ -204,25 +260,35 @@ GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out) {
     return p;
 }
 
-// layers: every one with plan_gram_cols(...).use and the same .nb; ws: the sum of their ws_floats
+namespace {
+template <int NB> hipError_t launch_cols_nb(const GramColsArgs& a, unsigned grid, int dt, hipStream_t st) {
+    if (dt == 0)      k_gram_cols<NB, 0><<<grid, kThreads, 0, st>>>(a);
+    else if (dt == 1) k_gram_cols<NB, 1><<<grid, kThreads, 0, st>>>(a);
+    else              k_gram_cols<NB, 2><<<grid, kThreads, 0, st>>>(a);
+    return hipGetLastError();
+}
+}  // namespace
+
+// layers: every one with plan_gram_cols(...).use and the same .nb; ws: the sum of their ws_floats; dt: 0 float32, 1 bf16, 2 fp16
 hipError_t launch_gram_cols_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm, float* ws,
-                                   hipStream_t st, bool f16, const ClipOut* co) {
-    if (n_layers < 1 || n_layers > kGramColsLayers) return hipErrorInvalidValue;
+                                   hipStream_t st, int dt, const ClipOut* co) {
+    if (n_layers < 1 || n_layers > kGramColsLayers || dt < 0 || dt > 2) return hipErrorInvalidValue;
     GramColsArgs a;
     a.part = ws; a.n_layers = n_layers;
+    const int step = dt == 0 ? 8 : 16;
     int nb = 0;
     int64_t blocks = 0;
     size_t off = 0;
     for (int l = 0; l < n_layers; ++l) {
         const GramLayerDesc& y = layers[l];
-        const GramColsPlan p = plan_gram_cols(B, y.T, y.d_in, y.d_out);
+        const GramColsPlan p = plan_gram_cols(B, y.T, y.d_in, y.d_out, dt);
         if (!p.use || (l > 0 && p.nb != nb)) return hipErrorInvalidValue;
         nb = p.nb;
         GramColsLayer& g = a.layer[l];
-        g.A = static_cast<const uint16_t*>(y.A); g.G = static_cast<const uint16_t*>(y.G);
+        g.A = y.A; g.G = y.G;
         g.part_off = off;
         g.T = y.T; g.d_in = y.d_in; g.d_out = y.d_out;
-        g.steps_a = ceil_div(y.d_in, 16); g.steps = g.steps_a + ceil_div(y.d_out, 16);
+        g.steps_a = ceil_div(y.d_in, step); g.steps = g.steps_a + ceil_div(y.d_out, step);
         g.W = p.W; g.per_wave = p.per_wave;
         g.first_block = (unsigned)blocks;
         blocks += (int64_t)B * p.W;
@@ -230,23 +296,20 @@ hipError_t launch_gram_cols_layers(const GramLayerDesc* layers, int n_layers, in
     }
     for (int l = n_layers; l < kGramColsLayers; ++l) a.layer[l] = a.layer[0];
     if (blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
-    const unsigned grid = (unsigned)blocks;
-    if (nb == 1) { if (f16) k_gram16_cols<1, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<1, false><<<grid, kThreads, 0, st>>>(a); }
-    else         { if (f16) k_gram16_cols<2, true><<<grid, kThreads, 0, st>>>(a); else k_gram16_cols<2, false><<<grid, kThreads, 0, st>>>(a); }
-    hipError_t e = hipGetLastError();
+    const hipError_t e = nb == 1 ? launch_cols_nb<1>(a, (unsigned)blocks, dt, st) : launch_cols_nb<2>(a, (unsigned)blocks, dt, st);
     if (e != hipSuccess) return e;
     const float C = co ? co->C : 0.f;
     float* clip = co ? co->clip : nullptr;
-    if (nb == 1) k_gram16_cols_finish<1><<<B, kFinishThreads, 0, st>>>(a, accumulate ? 1 : 0, sqnorm, C, clip);
-    else         k_gram16_cols_finish<2><<<B, kFinishThreads, 0, st>>>(a, accumulate ? 1 : 0, sqnorm, C, clip);
+    if (nb == 1) k_gram_cols_finish<1><<<B, kFinishThreads, 0, st>>>(a, accumulate ? 1 : 0, sqnorm, C, clip);
+    else         k_gram_cols_finish<2><<<B, kFinishThreads, 0, st>>>(a, accumulate ? 1 : 0, sqnorm, C, clip);
     return hipGetLastError();
 }
 
-hipError_t launch_gram_cols(const GramColsPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, bool f16, const ClipOut* co) {
+hipError_t launch_gram_cols(const GramColsPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
+                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, int dt, const ClipOut* co) {
     if (!p.use) return hipErrorInvalidValue;
     GramLayerDesc y{A, G, T, d_in, d_out, nullptr, nullptr};
-    return launch_gram_cols_layers(&y, 1, B, accumulate, sqnorm, ws, st, f16, co);
+    return launch_gram_cols_layers(&y, 1, B, accumulate, sqnorm, ws, st, dt, co);
 }
 
 }  // namespace dpk

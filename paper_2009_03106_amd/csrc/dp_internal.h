@@ -210,17 +210,17 @@ bool gram_dma_ok(int T, int d_in, int d_out, int fmt = 0);
 // array's clip factors go once the launch's last layer naming it has been added
 struct GramLayerDesc { const void* A; const void* G; int T, d_in, d_out; float* upart; float* bias_rows;
                        float* out = nullptr; bool out_acc = false; float out_C = 0.f; float* out_clip = nullptr; };
-// few positions (T <= 64), wide rows, small batch (dp_gram_bf16_cols.hip): the columns are split over workgroups.
-// use: whether this kernel takes the shape; ws_floats: its scratch
+// few positions (T <= 64), wide rows, small batch (dp_gram_cols.hip): the columns are split over workgroups.
+// dt: 0 float32, 1 bf16, 2 fp16 (the values of dp_dtype); use: whether this kernel takes the shape; ws_floats: its scratch
 struct GramColsPlan { bool use; int nb, W, per_wave; size_t ws_floats; };
-GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out);
+GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out, int dt);
 // several such layers (all with the same plan .nb) in one launch; ws: the sum of their ws_floats (A, G, T, d_in, d_out of
 // the descriptors are used)
 constexpr int kGramColsLayers = 16;
 hipError_t launch_gram_cols_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm, float* ws,
-                                   hipStream_t st, bool f16, const ClipOut* co = nullptr);
-hipError_t launch_gram_cols(const GramColsPlan& p, const uint16_t* A, const uint16_t* G, int B, int T, int d_in, int d_out,
-                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, bool f16, const ClipOut* co = nullptr);
+                                   hipStream_t st, int dt, const ClipOut* co = nullptr);
+hipError_t launch_gram_cols(const GramColsPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,
+                            bool accumulate, float* sqnorm, float* ws, hipStream_t st, int dt, const ClipOut* co = nullptr);
 hipError_t launch_gram_bf16_dma_layers(const GramLayerDesc* layers, int n_layers, int B, bool accumulate, float* sqnorm,
                                        float* partial, hipStream_t st, int fmt, float C = 0.f, float* clip = nullptr);
 hipError_t launch_gram_bf16_dma(const GramPlan& p, const void* A, const void* G, int B, int T, int d_in, int d_out,

@@ -1369,8 +1369,8 @@ GRAM_COLS_SHAPES = [(32, 16, 4608, 512), (20, 64, 2304, 256), (3, 33, 1032, 264)
                     (5, 32, 8, 2048), (255, 17, 520, 520), (9, 48, 2056, 24)]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("B,T,d_in,d_out", GRAM_COLS_SHAPES)
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("B,T,d_in,d_out", GRAM_COLS_SHAPES + [(6, 40, 1028, 516)])
 def test_gram_column_split_few_positions(dp, dtype, B, T, d_in, d_out):
     A, G = wl.random_layer(5150 + B + T + d_in, B, T, d_in, d_out, dtype, g_row_scale=np.exp(np.linspace(-2, 1, B)))
     s_ref = orc.layer_sqnorm(A, G)
