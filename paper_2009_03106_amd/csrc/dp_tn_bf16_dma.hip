@@ -438,8 +438,8 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma(DmaArgs 
 constexpr int kJointMax = kJointLayers;
 struct JointLayer {
     const uint16_t* A; const uint16_t* G; const float* clip;
-    float* slices;
-    int T, M, N, tiles_m, tiles_n, splits, stages_total, stages_per_split, first_item;
+    float* slices;       // the layer's K slices; the gradient itself where one slice is the whole sum (then `accumulate` applies)
+    int T, M, N, tiles_m, tiles_n, splits, stages_total, stages_per_split, first_item, accumulate;
 };
 struct JointArgs {
     JointLayer layer[kJointMax];
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma_joint(Jo
     a.B = j.B; a.T = y.T; a.M = y.M; a.N = y.N;
     a.tiles_m = y.tiles_m; a.tiles_n = y.tiles_n; a.splits = y.splits;
     a.stages_total = y.stages_total; a.stages_per_split = y.stages_per_split;
-    a.per_xcd = 0; a.accumulate = 0;
+    a.per_xcd = 0; a.accumulate = y.accumulate;
     a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0;
     a.zero = AM == 2 ? reinterpret_cast<const uint16_t*>(g_zero_line) : nullptr;
     tn_dma_tile<GEO, 0, AM, F16>(a, L - y.first_item);
@@ -630,7 +630,10 @@ hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperan
     for (int l = 0; l < n_layers; ++l) {
         JointLayer& y = j.layer[l];
         y.A = op[l].A; y.G = op[l].G; y.clip = op[l].clip;
-        y.slices = slices;
+        // one slice and no noise to add: the launch writes the gradient itself, nothing to fold
+        const bool whole = p.splits[l] == 1 && stddev == 0.0f;
+        y.slices = whole ? op[l].grad : slices;
+        y.accumulate = whole && accumulate ? 1 : 0;
         y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
         y.tiles_m = p.tiles_m[l]; y.tiles_n = p.tiles_n[l]; y.splits = p.splits[l];
         y.stages_total = (int)((int64_t)B * ceil_div(sh[l].T, DK)); y.stages_per_split = p.sps[l];
@@ -656,12 +659,16 @@ hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperan
     if (e != hipSuccess) return e;
     // one launch folds the slices of all layers (+ noise): a fold per layer is a launch of a few microseconds each
     FoldLayers f;
-    f.n_layers = n_layers;
+    int nf = 0;
     for (int l = 0; l < n_layers; ++l) {
-        f.ws[l] = j.layer[l].slices; f.grad[l] = op[l].grad; f.n[l] = (int64_t)sh[l].M * sh[l].N;
-        f.splits[l] = p.splits[l]; f.noise_offset[l] = op[l].noise_offset;
+        if (j.layer[l].slices == op[l].grad) continue;                 // written by the launch itself
+        f.ws[nf] = j.layer[l].slices; f.grad[nf] = op[l].grad; f.n[nf] = (int64_t)sh[l].M * sh[l].N;
+        f.splits[nf] = p.splits[l]; f.noise_offset[nf] = op[l].noise_offset;
+        ++nf;
     }
-    for (int l = n_layers; l < kJointLayers; ++l) { f.ws[l] = f.ws[0]; f.grad[l] = f.grad[0]; f.n[l] = 0; f.splits[l] = 0; f.noise_offset[l] = 0; }
+    if (nf == 0) return hipSuccess;
+    f.n_layers = nf;
+    for (int l = nf; l < kJointLayers; ++l) { f.ws[l] = f.ws[0]; f.grad[l] = f.grad[0]; f.n[l] = 0; f.splits[l] = 0; f.noise_offset[l] = 0; }
     return launch_splitk_reduce_layers(f, accumulate, st, stddev, seed);
 }
 

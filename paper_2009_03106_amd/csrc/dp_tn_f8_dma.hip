@@ -357,8 +357,8 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_f8_dma(Dma8Args a
 // of (layer, K slice, tile) items, all layers' slices of about one length, filling the chip a whole number of times.
 struct Joint8Layer {
     const unsigned char* A; const unsigned char* G; const float* clip;
-    float* slices;
-    int T, M, N, tiles_m, tiles_n, splits, stages_total, stages_per_split, first_item;
+    float* slices;       // the layer's K slices; the gradient itself where one slice is the whole sum (then `accumulate` applies)
+    int T, M, N, tiles_m, tiles_n, splits, stages_total, stages_per_split, first_item, accumulate;
 };
 struct Joint8Args {
     Joint8Layer layer[kJointLayers];
@@ -377,7 +377,7 @@ __global__ __launch_bounds__(Geo8L::THREADS, Geo8L::OCC) void k_tn_f8_dma_joint(
     a.B = j.B; a.T = y.T; a.M = y.M; a.N = y.N;
     a.tiles_m = y.tiles_m; a.tiles_n = y.tiles_n; a.splits = y.splits;
     a.stages_total = y.stages_total; a.stages_per_split = y.stages_per_split;
-    a.per_xcd = 0; a.accumulate = 0; a.zero = nullptr;
+    a.per_xcd = 0; a.accumulate = y.accumulate; a.zero = nullptr;
     tn_f8_tile<Geo8L, 0, false, FA, FG>(a, L - y.first_item);
 }
 
@@ -507,7 +507,10 @@ hipError_t launch_clipped_f8_dma_joint(const JointShape* sh, const JointOperands
     for (int l = 0; l < n_layers; ++l) {
         Joint8Layer& y = j.layer[l];
         y.A = reinterpret_cast<const unsigned char*>(op[l].A); y.G = reinterpret_cast<const unsigned char*>(op[l].G); y.clip = op[l].clip;
-        y.slices = slices;
+        // one slice and no noise to add: the launch writes the gradient itself, nothing to fold
+        const bool whole = p.splits[l] == 1 && stddev == 0.0f;
+        y.slices = whole ? op[l].grad : slices;
+        y.accumulate = whole && accumulate ? 1 : 0;
         y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
         y.tiles_m = p.tiles_m[l]; y.tiles_n = p.tiles_n[l]; y.splits = p.splits[l];
         y.stages_total = (int)((int64_t)B * (sh[l].T / DK8)); y.stages_per_split = p.sps[l];
@@ -527,13 +530,16 @@ hipError_t launch_clipped_f8_dma_joint(const JointShape* sh, const JointOperands
     if (e != hipSuccess) return e;
     // one launch folds the slices of all layers (+ noise)
     FoldLayers f;
-    f.n_layers = n_layers;
-    for (int l = 0; l < kJointLayers; ++l) {
-        const int k = l < n_layers ? l : 0;
-        f.ws[l] = j.layer[k].slices; f.grad[l] = op[k].grad;
-        f.n[l] = l < n_layers ? (int64_t)sh[l].M * sh[l].N : 0; f.splits[l] = l < n_layers ? p.splits[l] : 0;
-        f.noise_offset[l] = op[k].noise_offset;
+    int nf = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (j.layer[l].slices == op[l].grad) continue;                 // written by the launch itself
+        f.ws[nf] = j.layer[l].slices; f.grad[nf] = op[l].grad; f.n[nf] = (int64_t)sh[l].M * sh[l].N;
+        f.splits[nf] = p.splits[l]; f.noise_offset[nf] = op[l].noise_offset;
+        ++nf;
     }
+    if (nf == 0) return hipSuccess;
+    f.n_layers = nf;
+    for (int l = nf; l < kJointLayers; ++l) { f.ws[l] = f.ws[0]; f.grad[l] = f.grad[0]; f.n[l] = 0; f.splits[l] = 0; f.noise_offset[l] = 0; }
     return launch_splitk_reduce_layers(f, accumulate, st, stddev, seed);
 }
 

@@ -1434,3 +1434,37 @@ def test_layers_sqnorm_many_layers_that_run_one_by_one(dp, dtype):
     dp.layers_sqnorm(dev, s2, accumulate=True)
     assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
     np.testing.assert_array_equal(dp.layers_sqnorm(dev).cpu().numpy(), s.cpu().numpy())       # reruns are bit-identical
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_joint_launch_whose_layers_are_one_slice_each(dp, dtype):
+    """Few rows and many tiles (4 examples of 64 positions into the transformer configuration's four matrices): the
+    shared launch has one K slice per layer and writes the gradients itself (nothing to fold) unless noise is asked
+    for; accumulate and noise must come out as on the folded way."""
+    B, T = 4, 64
+    shapes = [(T, 768, 2304), (T, 768, 768), (T, 768, 3072), (T, 3072, 768)]
+    layers = [wl.random_layer(8100 + i, B, t, di, do, dtype, g_row_scale=np.exp(np.linspace(-1, 1, B))) for i, (t, di, do) in enumerate(shapes)]
+    s_ref = orc.total_sqnorm(layers)
+    c_ref = orc.clip_factors(s_ref, float(np.sqrt(np.median(s_ref))))
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    c = to_dev(c_ref.astype(np.float32))
+    sizes = [A.shape[-1] * G.shape[-1] for A, G in dev]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.full((sum(sizes),), 7.0, device="cuda")
+    grads = [flat[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)]
+    dp.layers_clipped_grad(dev, c, grads)
+    for (A, G), (An, Gn), g in zip(dev, layers, grads):
+        assert fro_err(g.cpu().numpy(), orc.clipped_grad(An, Gn, c_ref)) <= FRO_TIGHT
+        assert_same_sums(g.cpu().numpy(), dp.clipped_grad(A, G, c).cpu().numpy(), joint=True)
+    clean = flat.clone()
+    dp.layers_clipped_grad(dev, c, grads, accumulate=True)
+    np.testing.assert_allclose(flat.cpu().numpy(), 2 * clean.cpu().numpy(), rtol=0, atol=1e-6 * float(clean.abs().max()))
+    descs = dp.layer_descs(dev, grads, starts[:-1])
+    dp.layers_clipped_grad(dev, c, descs=descs, noise_std=0.25, seed=11)
+    dp.add_noise(clean, 0.25, 11, 0)
+    assert torch.equal(flat, clean)
+    dp.layers_clipped_grad(dev, c, descs=descs, noise_std=0.25, seed=12, accumulate=True)
+    ref = clean.clone()
+    dp.layers_clipped_grad(dev, c, [ref[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)], accumulate=True)
+    dp.add_noise(ref, 0.25, 12, 0)
+    assert torch.equal(flat, ref)
