@@ -46,7 +46,33 @@ struct TnArgs {
     int tiles_m, tiles_n;
     int kchunk;            // clipped: rows per K slice
     int accumulate;        // clipped with one slice: add to out
+    int slices_per_example = 1;    // MODE 2
 };
+
+// Direct norm of few, long examples of a small layer (the first convolution of an image model: thousands of
+// positions, 27 or 147 patch columns, 64 channels, 20-32 examples): one workgroup per (example, tile) is a few dozen
+// workgroups that each walk thousands of rows.  The positions are cut into chunks instead (k_tn_bf16_rows<2>), every
+// chunk stores its share of the small matrix A_i^T G_i, and this kernel adds an example's shares entry by entry in
+// the order of the chunks, squares and sums: partial[ex][block].  The layer's per-example gradients exist for a
+// moment, as in the paper's own implementation, but only where they are small next to the inputs.
+__global__ __launch_bounds__(kThreads) void k_direct_chunks_finish(const float* __restrict__ ws, int64_t slice, int S, int n,
+                                                                   int nblk, float* __restrict__ partial) {
+    __shared__ float red[4];
+    const int ex = blockIdx.y;
+    const float* base = ws + (size_t)ex * S * slice;
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int e = blockIdx.x * 1024 + k * kThreads + threadIdx.x;
+        const int ec = e < n ? e : 0;
+        float v = 0.f;
+#pragma unroll 4
+        for (int z = 0; z < S; ++z) v += base[(size_t)z * slice + ec];
+        s += e < n ? v * v : 0.f;
+    }
+    s = block_sum_256(s, red);
+    if (threadIdx.x == 0) partial[(size_t)ex * nblk + blockIdx.x] = s;
+}
 
 // Load an 8(k) x 8(col) block starting at (row0, col0) of X[K, D]; rows >= k_end and
 // columns >= D read as zero.  For widths that are not multiples of 8 every load is issued unconditionally from a
@@ -135,7 +161,8 @@ __device__ __forceinline__ void transpose8x8_scaled(const uint4 (&r)[8], const f
     }
 }
 
-// MODE 0: clipped sum (scale A rows, store the tile).  MODE 1: direct squared norm.
+// MODE 0: clipped sum (scale A rows, store the tile).  MODE 1: direct squared norm.  MODE 2: a chunk of one example's
+// positions, its share of A_i^T G_i stored unscaled (direct norm of few long examples, see k_direct_chunks_finish).
 template <int MODE, bool F16>
 __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_rows(TnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BM * 128];   // A^T tile then G^T tile: [col][64 k]
@@ -150,6 +177,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_rows(TnArgs a) {
     if (MODE == 0) {
         k_begin = z * a.kchunk;
         k_end = min(a.K, k_begin + a.kchunk);
+    } else if (MODE == 2) {
+        // slice z = (example, chunk of its positions): a.slices_per_example chunks of a.kchunk rows
+        const int ex = z / a.slices_per_example, ch = z - ex * a.slices_per_example;
+        k_begin = ex * a.T + ch * a.kchunk;
+        k_end = min(ex * a.T + a.T, k_begin + a.kchunk);
     } else {
         k_begin = z * a.T;
         k_end = k_begin + a.T;
@@ -226,7 +258,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_bf16_rows(TnArgs a) {
         __syncthreads();
     }
 
-    if (MODE == 0) {
+    if (MODE == 0 || MODE == 2) {
         // accumulator element r of lane: row 8*(r/4) + 4*lhalf + r%4, column lrow of the 32 x 32 MFMA tile
         float* out = a.out + (size_t)z * a.slice;
 #pragma unroll
@@ -706,6 +738,17 @@ TnPlan plan_direct_bf16(int B, int T, int M, int N) {
     p.segmented = (T >= kSegMinT);
     p.big = false; p.dma = false;
     p.splits = 1; p.kchunk = 0; p.epu = 1;
+    // few long examples of a small layer: chunks of positions (see k_direct_chunks_finish), about 1024 workgroups of
+    // at least 256 rows, as long as the chunks' shares are written and read in fewer bytes than the inputs
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    if (T >= 1024 && (int64_t)B * tiles < 256 && B <= 4096) {
+        int64_t S = (1024 + B * tiles - 1) / (B * tiles);
+        if (S > T / 256) S = T / 256;
+        int64_t kchunk = ((T + S - 1) / S + BK - 1) / BK * BK;
+        S = (T + kchunk - 1) / kchunk;
+        const int64_t in_bytes = (int64_t)B * T * ((int64_t)M + N) * 2;
+        if (S >= 2 && B * S <= 65535 && B * S * (int64_t)M * N * 8 <= in_bytes) { p.splits = (int)S; p.kchunk = (int)kchunk; }
+    }
     return p;
 }
 
@@ -754,6 +797,27 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
                               bool accumulate, float* sqnorm, float* partial, hipStream_t st, bool f16, const ClipOut* co) {
     if (p.dma) return launch_direct_bf16_dma(p, A, G, B, T, M, N, accumulate, sqnorm, partial, st, nullptr, nullptr, f16, co);
     const int tiles = p.tiles_m * p.tiles_n;
+    if (p.splits > 1) {
+        // chunks of positions: workspace = the chunks' shares [B][S][slice], then partial[B][nblk]
+        const int64_t n = (int64_t)M * N, slice = splitk_slice_elems(n);
+        const int nblk = (int)((n + 1023) / 1024);
+        float* shares = partial;
+        float* sums = partial + (size_t)B * p.splits * slice;
+        TnArgs a;
+        a.A = A; a.G = G; a.clip = nullptr;
+        a.K = B * T; a.T = T; a.M = M; a.N = N;
+        a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.kchunk = p.kchunk;
+        a.out = shares; a.slice = slice; a.accumulate = 0; a.slices_per_example = p.splits;
+        dim3 grid((unsigned)tiles, (unsigned)(B * p.splits));
+        if (f16) k_tn_bf16_rows<2, true><<<grid, kThreads, 0, st>>>(a);
+        else     k_tn_bf16_rows<2, false><<<grid, kThreads, 0, st>>>(a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        k_direct_chunks_finish<<<dim3((unsigned)nblk, (unsigned)B), kThreads, 0, st>>>(shares, slice, p.splits, (int)n, nblk, sums);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_finalize_partials(sums, B, nblk, accumulate, sqnorm, st, co);
+    }
     if (p.segmented) {
         // one launch covers at most 2^20 examples so that the workgroup count stays far below 2^31
         for (int b0 = 0; b0 < B; b0 += (1 << 20)) {

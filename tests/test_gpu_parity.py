@@ -1468,3 +1468,28 @@ def test_joint_launch_whose_layers_are_one_slice_each(dp, dtype):
     dp.layers_clipped_grad(dev, c, [ref[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)], accumulate=True)
     dp.add_noise(ref, 0.25, 12, 0)
     assert torch.equal(flat, ref)
+
+
+# Few long examples of a small layer (the first convolution of an image model): the direct norm cuts the positions
+# into chunks whose shares of A_i^T G_i are added before squaring.  A ragged last chunk, one and two column tiles,
+# aligned and unaligned widths.
+DIRECT_CHUNK_SHAPES = [(3, 1100, 27, 64), (2, 2048, 147, 64), (5, 1024, 40, 24), (1, 4096, 27, 64)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,T,d_in,d_out", DIRECT_CHUNK_SHAPES)
+def test_direct_norm_in_chunks_of_positions(dp, dtype, B, T, d_in, d_out):
+    A, G = wl.random_layer(9100 + T + d_in, B, T, d_in, d_out, dtype, a_dist="relu", g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    Ad, Gd = to_dev(A), to_dev(G)
+    s = dp.layer_sqnorm(Ad, Gd, path="direct")
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], rel_err(s.cpu().numpy(), s_ref)
+    s2 = torch.full((B,), 0.5, device="cuda")
+    dp.layer_sqnorm(Ad, Gd, s2, path="direct", accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
+    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
+    C = float(np.sqrt(np.median(s_ref)))
+    c = torch.full((B,), -1.0, device="cuda")
+    s3 = dp.layers_sqnorm([(Ad, Gd), (Ad, Gd)], C=C, clip=c, path="direct")
+    assert rel_err(s3.cpu().numpy(), 2 * s_ref) <= SQ_TIGHT[dtype]
+    np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s3, C).cpu().numpy())
