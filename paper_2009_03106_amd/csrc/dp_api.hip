@@ -94,8 +94,8 @@ size_t sqnorm_ws_bytes(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dty
     }
     TnPlan p = is8(dtype)  ? plan_direct_f8_dma((int)B, (int)T, (int)d_in, (int)d_out)
              : is16(dtype) ? plan_direct_bf16((int)B, (int)T, (int)d_in, (int)d_out)
-                           : plan_direct_f32((int)T, (int)d_in, (int)d_out);
-    if (is16(dtype) && !p.dma && p.splits > 1)         // chunks of positions: their shares of A_i^T G_i, then the blocks' sums
+                           : plan_direct_f32((int)B, (int)T, (int)d_in, (int)d_out);
+    if (!is8(dtype) && !p.dma && p.splits > 1)         // chunks of positions: their shares of A_i^T G_i, then the blocks' sums
         return ((size_t)B * p.splits * (size_t)splitk_slice_elems(d_in * d_out) + (size_t)B * (size_t)((d_in * d_out + 1023) / 1024)) * sizeof(float);
     return (size_t)B * p.tiles_m * p.tiles_n * sizeof(float) + (p.zero_head ? kZeroHeadFloats * sizeof(float) : 0);
 }
@@ -300,7 +300,7 @@ dp_status layer_sqnorm_clip(const void* A, const void* G, int64_t B, int64_t T, 
         e = launch_direct_bf16(t, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(G), (int)B, (int)T,
                                (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, dtype == DP_F16, co);
     } else {
-        TnPlan t = plan_direct_f32((int)T, (int)d_in, (int)d_out);
+        TnPlan t = plan_direct_f32((int)B, (int)T, (int)d_in, (int)d_out);
         e = launch_direct_f32(t, static_cast<const float*>(A), static_cast<const float*>(G), (int)B, (int)T,
                               (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, co);
     }

@@ -86,6 +86,11 @@ struct TnPlan {
     bool dma;               // copy-pipeline kernel (direct-to-LDS copies); tile_m x tile_n names its geometry (16-bit inputs) or is 128 x 128 (float32)
 };
 constexpr int kZeroHeadFloats = 64;   // 256 bytes
+// direct norm in chunks of positions (few long examples of a small layer): sets p.splits (chunks per example) and
+// p.kchunk (rows per chunk) where that pays; the chunks' shares [B][splits][splitk_slice_elems(M N)] are added, squared
+// and summed into sums[B][ceil(M N / 1024)] by launch_direct_chunks_finish
+void plan_direct_chunks(TnPlan& p, int B, int T, int M, int N, int esize, int stage);
+hipError_t launch_direct_chunks_finish(const float* shares, int64_t slice, int S, int n, int B, float* sums, hipStream_t st);
 TnPlan plan_clipped_bf16(int B, int T, int M, int N);
 TnPlan plan_clipped_f32(int B, int T, int M, int N);
 TnPlan plan_direct_bf16(int B, int T, int M, int N);
@@ -94,7 +99,7 @@ struct ConvGeom { int H, W, C, KH, KW, pad; };
 bool dma_conv_ok(const ConvGeom& g, int d_out);
 bool dma_clipped_ok(int B, int T, int M, int N);
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N);
-TnPlan plan_direct_f32(int T, int M, int N);
+TnPlan plan_direct_f32(int B, int T, int M, int N);
 // float32 copy-pipeline kernel (dp_tn_f32_dma.hip): 128 x 128 tiles, 16-row stages; the plans above choose it (dma = true)
 // for long contractions of shapes it fits
 bool f32_dma_ok(int64_t K, int M, int N);

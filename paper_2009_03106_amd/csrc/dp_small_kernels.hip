@@ -523,6 +523,51 @@ hipError_t launch_splitk_reduce_layers(FoldLayers& f, bool accumulate, hipStream
     return hipGetLastError();
 }
 
+// Direct norm of few, long examples of a small layer (the first convolution of an image model: thousands of
+// positions, 27 or 147 patch columns, 64 channels, 20-32 examples): one workgroup per (example, tile) is a few dozen
+// workgroups that each walk thousands of rows.  The positions are cut into chunks instead (mode 2 of k_tn_bf16_rows / k_tn_f32), every
+// chunk stores its share of the small matrix A_i^T G_i, and this kernel adds an example's shares entry by entry in
+// the order of the chunks, squares and sums: partial[ex][block].  The layer's per-example gradients exist for a
+// moment, as in the paper's own implementation, but only where they are small next to the inputs.
+__global__ __launch_bounds__(kThreads) void k_direct_chunks_finish(const float* __restrict__ ws, int64_t slice, int S, int n,
+                                                                   int nblk, float* __restrict__ partial) {
+    __shared__ float red[4];
+    const int ex = blockIdx.y;
+    const float* base = ws + (size_t)ex * S * slice;
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int e = blockIdx.x * 1024 + k * kThreads + threadIdx.x;
+        const int ec = e < n ? e : 0;
+        float v = 0.f;
+#pragma unroll 4
+        for (int z = 0; z < S; ++z) v += base[(size_t)z * slice + ec];
+        s += e < n ? v * v : 0.f;
+    }
+    s = block_sum_256(s, red);
+    if (threadIdx.x == 0) partial[(size_t)ex * nblk + blockIdx.x] = s;
+}
+
+hipError_t launch_direct_chunks_finish(const float* shares, int64_t slice, int S, int n, int B, float* sums, hipStream_t st) {
+    const int nblk = (n + 1023) / 1024;
+    if (S < 1 || n < 1 || B < 1 || B > 65535) return hipErrorInvalidValue;
+    k_direct_chunks_finish<<<dim3((unsigned)nblk, (unsigned)B), kThreads, 0, st>>>(shares, slice, S, n, nblk, sums);
+    return hipGetLastError();
+}
+
+// few long examples of a small layer: about 1024 workgroups of at least 256 rows, as long as the chunks' shares are
+// written and read in fewer bytes than the inputs (esize: bytes per input element; stage: rows per stage of the kernel)
+void plan_direct_chunks(TnPlan& p, int B, int T, int M, int N, int esize, int stage) {
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    if (T < 1024 || (int64_t)B * tiles >= 256 || B > 4096) return;
+    int64_t S = (1024 + B * tiles - 1) / (B * tiles);
+    if (S > T / 256) S = T / 256;
+    const int64_t kchunk = ((T + S - 1) / S + stage - 1) / stage * stage;
+    S = (T + kchunk - 1) / kchunk;
+    const int64_t in_bytes = (int64_t)B * T * ((int64_t)M + N) * esize;
+    if (S >= 2 && B * S <= 65535 && B * S * (int64_t)M * N * 8 <= in_bytes) { p.splits = (int)S; p.kchunk = (int)kchunk; }
+}
+
 __global__ void k_fill_zero(float* __restrict__ p, int64_t n) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) p[j] = 0.f;

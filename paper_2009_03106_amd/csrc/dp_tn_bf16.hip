@@ -49,30 +49,6 @@ struct TnArgs {
     int slices_per_example = 1;    // MODE 2
 };
 
-// Direct norm of few, long examples of a small layer (the first convolution of an image model: thousands of
-// positions, 27 or 147 patch columns, 64 channels, 20-32 examples): one workgroup per (example, tile) is a few dozen
-// workgroups that each walk thousands of rows.  The positions are cut into chunks instead (k_tn_bf16_rows<2>), every
-// chunk stores its share of the small matrix A_i^T G_i, and this kernel adds an example's shares entry by entry in
-// the order of the chunks, squares and sums: partial[ex][block].  The layer's per-example gradients exist for a
-// moment, as in the paper's own implementation, but only where they are small next to the inputs.
-__global__ __launch_bounds__(kThreads) void k_direct_chunks_finish(const float* __restrict__ ws, int64_t slice, int S, int n,
-                                                                   int nblk, float* __restrict__ partial) {
-    __shared__ float red[4];
-    const int ex = blockIdx.y;
-    const float* base = ws + (size_t)ex * S * slice;
-    float s = 0.f;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int e = blockIdx.x * 1024 + k * kThreads + threadIdx.x;
-        const int ec = e < n ? e : 0;
-        float v = 0.f;
-#pragma unroll 4
-        for (int z = 0; z < S; ++z) v += base[(size_t)z * slice + ec];
-        s += e < n ? v * v : 0.f;
-    }
-    s = block_sum_256(s, red);
-    if (threadIdx.x == 0) partial[(size_t)ex * nblk + blockIdx.x] = s;
-}
 
 // Load an 8(k) x 8(col) block starting at (row0, col0) of X[K, D]; rows >= k_end and
 // columns >= D read as zero.  For widths that are not multiples of 8 every load is issued unconditionally from a
@@ -738,17 +714,7 @@ TnPlan plan_direct_bf16(int B, int T, int M, int N) {
     p.segmented = (T >= kSegMinT);
     p.big = false; p.dma = false;
     p.splits = 1; p.kchunk = 0; p.epu = 1;
-    // few long examples of a small layer: chunks of positions (see k_direct_chunks_finish), about 1024 workgroups of
-    // at least 256 rows, as long as the chunks' shares are written and read in fewer bytes than the inputs
-    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    if (T >= 1024 && (int64_t)B * tiles < 256 && B <= 4096) {
-        int64_t S = (1024 + B * tiles - 1) / (B * tiles);
-        if (S > T / 256) S = T / 256;
-        int64_t kchunk = ((T + S - 1) / S + BK - 1) / BK * BK;
-        S = (T + kchunk - 1) / kchunk;
-        const int64_t in_bytes = (int64_t)B * T * ((int64_t)M + N) * 2;
-        if (S >= 2 && B * S <= 65535 && B * S * (int64_t)M * N * 8 <= in_bytes) { p.splits = (int)S; p.kchunk = (int)kchunk; }
-    }
+    plan_direct_chunks(p, B, T, M, N, 2, BK);
     return p;
 }
 
@@ -813,8 +779,7 @@ hipError_t launch_direct_bf16(const TnPlan& p, const uint16_t* A, const uint16_t
         else     k_tn_bf16_rows<2, false><<<grid, kThreads, 0, st>>>(a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        k_direct_chunks_finish<<<dim3((unsigned)nblk, (unsigned)B), kThreads, 0, st>>>(shares, slice, p.splits, (int)n, nblk, sums);
-        e = hipGetLastError();
+        e = launch_direct_chunks_finish(shares, slice, p.splits, (int)n, B, sums, st);
         if (e != hipSuccess) return e;
         return launch_finalize_partials(sums, B, nblk, accumulate, sqnorm, st, co);
     }

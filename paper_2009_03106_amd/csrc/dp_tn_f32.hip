@@ -27,6 +27,7 @@ struct TnArgsF {
     int tiles_m, tiles_n;
     int kchunk;
     int accumulate;
+    int slices_per_example = 1;     // mode 2
 };
 
 // The loads of a stage are issued unconditionally from clamped (valid) addresses and zeroed afterwards: no branch
@@ -48,6 +49,13 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
     const int z = blockIdx.y;
     int k_begin, k_end;
     if (MODE == 0) { k_begin = z * a.kchunk; k_end = min(a.K, k_begin + a.kchunk); }
+    else if (MODE == 2) {
+        // slice z = (example, chunk of its positions), its share of A_i^T G_i stored unscaled (direct norm of few long
+        // examples of a small layer, see plan_direct_chunks)
+        const int ex = z / a.slices_per_example, ch = z - ex * a.slices_per_example;
+        k_begin = ex * a.T + ch * a.kchunk;
+        k_end = min(ex * a.T + a.T, k_begin + a.kchunk);
+    }
     else { k_begin = z * a.T; k_end = k_begin + a.T; }
 
     // each thread moves NV float4 of A and of G per stage: rows lr, lr + 16, ..., columns lc .. lc + 3 of the tile
@@ -131,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void k_tn_f32(TnArgsF a) {
         __syncthreads();
     }
 
-    if (MODE == 0) {
+    if (MODE == 0 || MODE == 2) {
         float* out = a.out + (size_t)z * a.slice;
         const int n = n0 + wn * 32 + lrow;
         if (n < a.N) {
@@ -366,7 +374,7 @@ TnPlan plan_clipped_f32(int B, int T, int M, int N) {
     return p;
 }
 
-TnPlan plan_direct_f32(int T, int M, int N) {
+TnPlan plan_direct_f32(int B, int T, int M, int N) {
     TnPlan p;
     p.segmented = false; p.epu = 0; p.big = false; p.dma = false;
     if (f32_dma_ok(T, M, N)) {
@@ -380,6 +388,7 @@ TnPlan plan_direct_f32(int T, int M, int N) {
     p.tile_m = FBM; p.tile_n = FBN;
     p.tiles_m = ceil_div(M, FBM); p.tiles_n = ceil_div(N, FBN);
     p.splits = 1; p.kchunk = 0;
+    plan_direct_chunks(p, B, T, M, N, 4, 64);
     return p;
 }
 
@@ -459,6 +468,21 @@ hipError_t launch_direct_f32(const TnPlan& p, const float* A, const float* G, in
             if (e != hipSuccess) return e;
         }
         return launch_finalize_partials(partial, B, tiles, accumulate, sqnorm, st, co);
+    }
+    if (p.splits > 1) {
+        // chunks of positions: workspace = the chunks' shares [B][S][slice], then sums[B][nblk]
+        const int64_t n = (int64_t)M * N, slice = splitk_slice_elems(n);
+        const int nblk = (int)((n + 1023) / 1024);
+        float* sums = partial + (size_t)B * p.splits * slice;
+        a.A = A; a.G = G;
+        a.kchunk = p.kchunk; a.out = partial; a.slice = slice; a.slices_per_example = p.splits;
+        dim3 grid((unsigned)tiles, (unsigned)(B * p.splits));
+        launch_f32<2>(true, (M & 3) == 0, (N & 3) == 0, grid, a, st);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        e = launch_direct_chunks_finish(partial, slice, p.splits, (int)n, B, sums, st);
+        if (e != hipSuccess) return e;
+        return launch_finalize_partials(sums, B, nblk, accumulate, sqnorm, st, co);
     }
     for (int b0 = 0; b0 < B; b0 += 65535) {
         const int nb = (B - b0 < 65535) ? (B - b0) : 65535;

@@ -1476,7 +1476,7 @@ def test_joint_launch_whose_layers_are_one_slice_each(dp, dtype):
 DIRECT_CHUNK_SHAPES = [(3, 1100, 27, 64), (2, 2048, 147, 64), (5, 1024, 40, 24), (1, 4096, 27, 64)]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("B,T,d_in,d_out", DIRECT_CHUNK_SHAPES)
 def test_direct_norm_in_chunks_of_positions(dp, dtype, B, T, d_in, d_out):
     A, G = wl.random_layer(9100 + T + d_in, B, T, d_in, d_out, dtype, a_dist="relu", g_row_scale=np.exp(np.linspace(-2, 1, B)))
