@@ -29,9 +29,9 @@ import numpy as np  # noqa: E402
 # `bench.py --calib-copy`, scaled by what the same counters read for the 1 GiB copy (see profiles/).
 # None until measured for the current kernels.
 MEASURED_TRAFFIC = {
-    # the clipped-sum phase of one step: the launch that takes all four layers (995.3 MB read, 198.1 MB written) and
-    # the four split-K folds (49.6 MB read, 7.1 MB written each) (profiles/transformer_hbm_traffic.md)
-    "transformer": 1420.2e6,
+    # the clipped-sum phase of one step: the launch that takes all four layers (995.3 MB read, 198.2 MB written) and
+    # the launch that folds their K slices (198.2 MB read, 28.3 MB written) (profiles/transformer_hbm_traffic.md)
+    "transformer": 1420.0e6,
 }
 
 PEAK_HBM_GBS = 8000.0
