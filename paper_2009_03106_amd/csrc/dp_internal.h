@@ -98,7 +98,8 @@ TnPlan plan_direct_bf16(int B, int T, int M, int N);
 struct ConvGeom { int H, W, C, KH, KW, pad; };
 bool dma_conv_ok(const ConvGeom& g, int d_out);
 bool dma_clipped_ok(int B, int T, int M, int N);
-TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N);
+// flat: the rows of A lie in memory as they are (not the implicit unfolding of an image)
+TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N, bool flat = false);
 TnPlan plan_direct_f32(int B, int T, int M, int N);
 // float32 copy-pipeline kernel (dp_tn_f32_dma.hip): 128 x 128 tiles, 16-row stages; the plans above choose it (dma = true)
 // for long contractions of shapes it fits

@@ -630,7 +630,7 @@ constexpr int kSegMinT = 32;      // below this an LDS stage would be mostly pad
 }  // namespace
 
 TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
-    if (dma_clipped_ok(B, T, M, N)) return plan_clipped_bf16_dma(B, T, M, N);
+    if (dma_clipped_ok(B, T, M, N)) return plan_clipped_bf16_dma(B, T, M, N, true);
     TnPlan p;
     p.dma = false;
     p.tile_m = BM; p.tile_n = BN;

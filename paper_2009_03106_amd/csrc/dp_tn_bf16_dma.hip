@@ -67,6 +67,10 @@ using GeoS = Geo<2, 2, 3, 2, 3, 2>;
 // layers of a few hundred columns that neither of the above tiles without much padding (256 x 128, 128 x 128,
 // 640 x 384, ...): 128 x 128 tile, 4 waves of 64 x 64, four 16 KB stages, two workgroups per compute unit
 using GeoT = Geo<2, 2, 2, 2, 4, 2>;
+// clipped sums of a small matrix over many rows (a recurrent layer: 256 x 256 from 8192 rows): a handful of tiles,
+// so the chip is filled with K slices, every one a partial matrix to store and to fold.  64 x 64 tiles, 4 waves of
+// 32 x 32, four 8 KB stages: four times the tiles, a quarter of the slices.
+using GeoU = Geo<2, 2, 1, 1, 4, 4>;
 
 struct DmaArgs {
     const uint16_t* A;
@@ -508,7 +512,7 @@ int pick_geometry(int T, int M, int N, int64_t units) {
 }
 
 // the plan names its geometry by the tile shape
-int geo_of_plan(const TnPlan& p) { return p.tile_m == GeoL::TM ? 1 : (p.tile_m == GeoS::TM ? 2 : 3); }
+int geo_of_plan(const TnPlan& p) { return p.tile_m == GeoL::TM ? 1 : (p.tile_m == GeoS::TM ? 2 : (p.tile_m == GeoT::TM ? 3 : 4)); }
 
 // am: 0 = rows of A as they lie in memory, 1 = implicit unfolding of an image, 2 = ragged T
 template <class GEO, int MODE, bool F16> hipError_t launch_geo(const DmaArgs& a, int am, hipStream_t st) {
@@ -537,11 +541,28 @@ void set_conv(DmaArgs& a, const ConvGeom* cg, const uint16_t* zero) {
 
 bool dma_clipped_ok(int B, int T, int M, int N) { (void)B; return dma_geometry(T, M, N) != 0; }
 
-TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N) {
+TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N, bool flat) {
     const int64_t spe = ceil_div(T, DK);
     const int64_t stages = (int64_t)B * spe;
     const GeoDims gd = geo_dims(pick_geometry(T, M, N, (stages + 7) / 8));
     TnPlan p;
+    // A small matrix (at most 16 tiles of 128 x 128) whose rows lie flat in memory, T a multiple of the stage, and so
+    // many stages that the larger tiles would be cut into 16 slices or more: 64 x 64 tiles, slices of at least 16 stages
+    if (flat && (T % DK) == 0 && ((M | N) & 63) == 0 && (int64_t)M * N <= 16 * 128 * 128 && stages >= 256 &&
+        (int64_t)ceil_div(M, gd.tm) * ceil_div(N, gd.tn) * 16 <= 256 * gd.occ) {
+        p.tile_m = GeoU::TM; p.tile_n = GeoU::TN;
+        p.tiles_m = M / GeoU::TM; p.tiles_n = N / GeoU::TN;
+        p.segmented = false; p.epu = 0; p.big = false; p.dma = true; p.zero_head = false;
+        const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+        int64_t splits = 512 / tiles;                 // two workgroups per compute unit
+        if (splits < 1) splits = 1;
+        if (splits > stages / 16) splits = stages / 16;
+        int64_t sps = (stages + splits - 1) / splits;
+        if (sps > 63 * spe) sps = 63 * spe;
+        p.kchunk = (int)(sps * DK);
+        p.splits = (int)((stages + sps - 1) / sps);
+        return p;
+    }
     p.tile_m = gd.tm; p.tile_n = gd.tn;
     p.tiles_m = ceil_div(M, p.tile_m); p.tiles_n = ceil_div(N, p.tile_n);
     p.segmented = false; p.epu = 0; p.big = false; p.dma = true;
@@ -583,7 +604,15 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     a.per_xcd = ceil_div((int64_t)tiles * p.splits, 8);
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
-    const hipError_t e = launch_any<0>(geo_of_plan(p), a, am, f16, st);
+    hipError_t e;
+    if (geo_of_plan(p) == 4) {
+        if (am != 0) return hipErrorInvalidValue;     // the 64 x 64 tiles are planned for flat rows only
+        if (f16) k_tn_bf16_dma<GeoU, 0, 0, true><<<8u * (unsigned)a.per_xcd, GeoU::THREADS, 0, st>>>(a);
+        else     k_tn_bf16_dma<GeoU, 0, 0, false><<<8u * (unsigned)a.per_xcd, GeoU::THREADS, 0, st>>>(a);
+        e = hipGetLastError();
+    } else {
+        e = launch_any<0>(geo_of_plan(p), a, am, f16, st);
+    }
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);
 }

@@ -1493,3 +1493,28 @@ def test_direct_norm_in_chunks_of_positions(dp, dtype, B, T, d_in, d_out):
     s3 = dp.layers_sqnorm([(Ad, Gd), (Ad, Gd)], C=C, clip=c, path="direct")
     assert rel_err(s3.cpu().numpy(), 2 * s_ref) <= SQ_TIGHT[dtype]
     np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s3, C).cpu().numpy())
+
+
+# Small matrices over many rows (a recurrent layer's 256 x 256 from thousands of rows): clipped sums on 64 x 64 tiles.
+# K slices that end inside an example, one position block per example, a single column of tiles.
+SMALL_TILE_SHAPES = [(130, 64, 256, 256), (67, 128, 64, 512), (300, 32, 128, 192), (256, 32, 64, 64)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,T,d_in,d_out", SMALL_TILE_SHAPES)
+def test_clipped_sum_small_matrix_many_rows(dp, dtype, B, T, d_in, d_out):
+    A, G = wl.random_layer(9900 + B + d_in, B, T, d_in, d_out, dtype, g_row_scale=np.exp(np.linspace(-2, 1, B)))
+    s_ref = orc.layer_sqnorm(A, G)
+    C = float(np.sqrt(np.median(s_ref)))
+    Ad, Gd = to_dev(A), to_dev(G)
+    pats = _factor_patterns(B, np.random.default_rng(B + T))
+    # (factors within the 30 orders of magnitude that the accumulator-scaling kernels document)
+    for c in [orc.clip_factors(s_ref, C).astype(np.float32), pats["zero first/middle/last"], pats["1e-30 first/middle/last"], pats["every other zero"]]:
+        cd = torch.from_numpy(np.ascontiguousarray(c, dtype=np.float32)).cuda()
+        g = dp.clipped_grad(Ad, Gd, cd)
+        got = g.cpu().numpy()
+        check_clipped_sum(dp, A, G, c, got, dtype, (B, T, d_in, d_out))
+        g2 = torch.full_like(g, 0.25)
+        dp.clipped_grad(Ad, Gd, cd, g2, accumulate=True)
+        np.testing.assert_allclose(g2.cpu().numpy(), got + np.float32(0.25), rtol=0, atol=1e-6 * (1 + np.abs(got).max()))
+    np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, cd).cpu().numpy(), got)       # reruns are bit-identical
