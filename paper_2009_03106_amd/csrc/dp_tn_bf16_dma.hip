@@ -10,11 +10,12 @@
 //     one column, memory has consecutive columns for one k) is done by the
 //     LDS read itself (ds_read_b64_tr_b16): 16 lanes read a 4(k) x 16(col)
 //     patch and each lane gets the 4 k values of one column.
-//   * three tile geometries (struct Geo below): 256 x 256 per workgroup of 8
+//   * four tile geometries (struct Geo below): 256 x 256 per workgroup of 8
 //     waves, one workgroup per compute unit, for layers whose clipped sum is
 //     bound by the MFMA rate; 192 x 128 per workgroup of 4 waves, two
 //     workgroups per compute unit, for narrow layers bound by HBM; 128 x 128
-//     for the mid-size layers that neither tiles without much padding.
+//     for the mid-size layers that neither tiles without much padding; 64 x 64
+//     for the clipped sum of a small matrix over many rows.
 //
 // Clip factors are applied to the fp32 accumulators, not to the 16-bit inputs:
 // the tile holds  (1 / c_cur) * sum_{j <= cur} c_j g_j ; when the rows of the
