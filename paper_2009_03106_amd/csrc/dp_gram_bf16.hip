@@ -164,6 +164,66 @@ __global__ __launch_bounds__(kThreads, 2) void k_gram_bf16(GramArgs a) {
     }
 }
 
+// One tile pair per example (T <= 64), 8 waves: waves 0-3 form A_i A_i^T while waves 4-7 form G_i G_i^T, each
+// wave a 32 x 32 block of its 64 x 64 product, and the two meet through LDS at the end.  A launch of B workgroups is a
+// chain of memory round trips, one per 64-column stage, and this halves the chain.
+template <bool F16>
+__global__ __launch_bounds__(512) void k_gram_bf16_two(GramArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][64 * 128];
+    __shared__ float xq[4][16][64];
+    __shared__ float red[4];
+    const int ex = blockIdx.x;
+    const int side = threadIdx.x >> 8;                       // 0: A, 1: G
+    const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int D = side ? a.d_out : a.d_in;
+    const uint16_t* Xi = side ? a.G + (size_t)ex * a.T * a.d_out : a.A + (size_t)ex * a.T * a.d_in;
+    const int Dmax = a.d_in > a.d_out ? a.d_in : a.d_out;
+    const bool vec_ok = (D & 7) == 0;
+    unsigned char* tile = lds[side];
+
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    uint4 st[2];
+    gram_fetch<64>(Xi, a.T, D, vec_ok, 0, 0, tid, st);
+    for (int k0 = 0; k0 < Dmax; k0 += GBK) {
+        const bool on = k0 < D;                              // uniform over a side's waves
+        if (on) gram_commit<64>(tile, tid, st);
+        __syncthreads();
+        if (k0 + GBK < D) gram_fetch<64>(Xi, a.T, D, vec_ok, 0, k0 + GBK, tid, st);
+        if (on) {
+#pragma unroll
+            for (int ks = 0; ks < GBK / 16; ++ks) {
+                const bf16x8 fa = *reinterpret_cast<const bf16x8*>(tile + lds_off_bytes(wm * 32 + lrow, ks * 2 + lhalf));
+                const bf16x8 fb = *reinterpret_cast<const bf16x8*>(tile + lds_off_bytes(wn * 32 + lrow, ks * 2 + lhalf));
+                acc = In16<F16>::mfma(fa, fb, acc);
+            }
+        }
+        __syncthreads();
+    }
+    if (side == 1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xq[wave][r][lane] = acc[r];
+    }
+    __syncthreads();
+    float s = 0.f;
+    if (side == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[r] * xq[wave][r][lane];
+        s = wave_sum(s);
+        if (lane == 0) red[wave] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float v = (red[0] + red[1]) + (red[2] + red[3]);
+        const float t = a.accumulate ? a.sqnorm[ex] + v : v;
+        a.sqnorm[ex] = t;
+        if (a.clip) a.clip[ex] = clip_factor_of(t, a.C);
+    }
+}
+
 }  // namespace
 
 GramPlan plan_gram_bf16(int T, int d_in, int d_out) {
@@ -186,7 +246,7 @@ hipError_t launch_gram_bf16(const GramPlan& p, const uint16_t* A, const uint16_t
     a.sqnorm = direct ? sqnorm : nullptr; a.accumulate = accumulate ? 1 : 0;
     a.C = co ? co->C : 0.f; a.clip = co ? co->clip : nullptr;
     const unsigned grid = (unsigned)((int64_t)B * p.npairs);
-    if (p.tile == 64) { if (f16) k_gram_bf16<64, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16<64, false><<<grid, kThreads, 0, st>>>(a); }
+    if (p.tile == 64) { if (f16) k_gram_bf16_two<true><<<grid, 512, 0, st>>>(a); else k_gram_bf16_two<false><<<grid, 512, 0, st>>>(a); }
     else              { if (f16) k_gram_bf16<128, true><<<grid, kThreads, 0, st>>>(a); else k_gram_bf16<128, false><<<grid, kThreads, 0, st>>>(a); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || direct) return e;
