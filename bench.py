@@ -688,7 +688,47 @@ def main():
                          "clipped_grad_tflops": 2.0 * Bc * T * d_in * d_out / (b * 1e-3) / 1e12}
         res["input_bytes"] = int(Xd.numel() * 2 + Gd.numel() * 2)
         others["conv_from_image"] = res
-        del flush
+        del flush, Xd, Gd
+        # Stacks of unfolded convolutions shaped like the paper's image models (Section 6: ResNet / VGG at 20-32 examples):
+        # every layer's norms, the clip factors and the clipped sums with noise through dp_layers_step, bf16.
+        # (positions, patch columns, channels) per layer; N(0, 1) inputs drawn on the device.
+        stacks = {
+            "resnet18_like_32x32_B32": (32, [(1024, 27, 64)] + [(1024, 576, 64)] * 4 + [(256, 576, 128)] + [(256, 1152, 128)] * 3
+                                        + [(64, 1152, 256)] + [(64, 2304, 256)] * 3 + [(16, 2304, 512)] + [(16, 4608, 512)] * 3 + [(1, 512, 10)]),
+            "resnet18_like_256x256_B20": (20, [(16384, 147, 64)] + [(4096, 576, 64)] * 4 + [(1024, 576, 128), (1024, 64, 128)]
+                                          + [(1024, 1152, 128)] * 3 + [(256, 1152, 256), (256, 128, 256)] + [(256, 2304, 256)] * 3
+                                          + [(64, 2304, 512), (64, 256, 512)] + [(64, 4608, 512)] * 3 + [(1, 512, 10)]),
+        }
+        stack_out = {}
+        for sname, (Bs, shapes) in stacks.items():
+            gen = torch.Generator(device="cuda").manual_seed(wl.BASE_SEED + 77)
+            lay = []
+            for (T, di, do) in shapes:
+                shp_a, shp_g = ((Bs, T, di), (Bs, T, do)) if T > 1 else ((Bs, di), (Bs, do))
+                lay.append((torch.randn(shp_a, device="cuda", generator=gen).to(torch.bfloat16),
+                            torch.randn(shp_g, device="cuda", generator=gen).to(torch.bfloat16)))
+            sizes = [di * do for (_, di, do) in shapes]
+            starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+            flat = torch.zeros(int(sum(sizes)), device="cuda")
+            grads = [flat[starts[i]:starts[i + 1]].view(di, do) for i, (_, di, do) in enumerate(shapes)]
+            descs = dp.layer_descs(lay, grads, starts[:-1])
+            arr, _, dtc = descs
+            wss = torch.empty(max(16, dp.layers_workspace_bytes(arr, Bs, dtc, "auto"), dp.layers_clipped_workspace_bytes(arr, Bs, dtc)),
+                              dtype=torch.uint8, device="cuda")
+            sq, cl = torch.zeros(Bs, device="cuda"), torch.zeros(Bs, device="cuda")
+            for _ in range(3):
+                dp.layers_step(descs, 1.0, sq, cl, wss, noise_std=1.0, seed=1)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                dp.layers_step(descs, 1.0, sq, cl, wss, noise_std=1.0, seed=1)
+            torch.cuda.synchronize()
+            mss = (time.perf_counter() - t0) / 20 * 1e3
+            in_bytes = sum(Bs * T * (di + do) * 2 for (T, di, do) in shapes)
+            stack_out[sname] = {"layers": len(shapes), "examples_per_s": Bs / (mss * 1e-3), "ms_per_step": mss,
+                                "input_mb": in_bytes / 1e6, "clipped_sum_gflop": sum(2.0 * Bs * T * di * do for (T, di, do) in shapes) / 1e9}
+            del lay, grads, flat, wss
+        others["image_model_stacks"] = stack_out
 
     out = {
         "metric": "examples/sec for norm+clip+clipped-sum per layer",
