@@ -73,6 +73,7 @@ __device__ __forceinline__ void gram_cols_run16(const uint16_t* __restrict__ X, 
         }
 #pragma unroll
         for (int u = 0; u < kColsSteps; ++u) {
+            if (k + u >= ke) break;                                  // uniform: the steps past the range hold zeros
             const bf16x8 f0 = __builtin_bit_cast(bf16x8, f[u][0]);
             acc[0] = In16<F16>::mfma(f0, f0, acc[0]);
             if constexpr (NB == 2) {
@@ -84,8 +85,9 @@ __device__ __forceinline__ void gram_cols_run16(const uint16_t* __restrict__ X, 
     }
 }
 
-// float32: a step is 8 columns, the lane's piece columns 4 * (lane / 32) .. + 3 of it (D a multiple of 4)
-template <int NB>
+// float32: a step is 8 columns, the lane's piece columns 4 * (lane / 32) .. + 3 of it; where D is not a multiple of 4
+// (rows then start at any 4-byte address) the piece is four clamped 4-byte loads
+template <int NB, bool VEC>
 __device__ __forceinline__ void gram_cols_run32(const float* __restrict__ X, int T, int D, int kb, int ke, int lane,
                                                 f32x16 (&acc)[NB * (NB + 1) / 2]) {
     const int row = lane & 31, half = lane >> 5;
@@ -106,13 +108,19 @@ __device__ __forceinline__ void gram_cols_run32(const float* __restrict__ X, int
             const int c = ok ? col : 0;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const float4 v = *reinterpret_cast<const float4*>(p[b] + c);
                 const bool keep = ok && in[b];
-                f[u][b] = make_float4(keep ? v.x : 0.f, keep ? v.y : 0.f, keep ? v.z : 0.f, keep ? v.w : 0.f);
+                if (VEC) {
+                    const float4 v = *reinterpret_cast<const float4*>(p[b] + c);
+                    f[u][b] = make_float4(keep ? v.x : 0.f, keep ? v.y : 0.f, keep ? v.z : 0.f, keep ? v.w : 0.f);
+                } else {
+                    const float x = p[b][c], y = p[b][min(c + 1, D - 1)], z = p[b][min(c + 2, D - 1)], w = p[b][min(c + 3, D - 1)];
+                    f[u][b] = make_float4(keep ? x : 0.f, (keep && c + 1 < D) ? y : 0.f, (keep && c + 2 < D) ? z : 0.f, (keep && c + 3 < D) ? w : 0.f);
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < kColsSteps; ++u) {
+            if (k + u >= ke) break;                                  // uniform: the steps past the range hold zeros
             const float a0[4] = {f[u][0].x, f[u][0].y, f[u][0].z, f[u][0].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], a0[e], acc[0], 0, 0, 0);
@@ -132,7 +140,11 @@ __device__ __forceinline__ void gram_cols_run32(const float* __restrict__ X, int
 template <int NB, int DT>
 __device__ __forceinline__ void gram_cols_run(const void* X, size_t ex, int T, int D, int kb, int ke, int lane,
                                               f32x16 (&acc)[NB * (NB + 1) / 2]) {
-    if constexpr (DT == 0) gram_cols_run32<NB>(static_cast<const float*>(X) + ex * T * D, T, D, kb, ke, lane, acc);
+    if constexpr (DT == 0) {
+        // (the choice sits outside the loops: a branch around every load would make each wait for the one before)
+        if ((D & 3) == 0) gram_cols_run32<NB, true>(static_cast<const float*>(X) + ex * T * D, T, D, kb, ke, lane, acc);
+        else              gram_cols_run32<NB, false>(static_cast<const float*>(X) + ex * T * D, T, D, kb, ke, lane, acc);
+    }
     else gram_cols_run16<NB, DT == 2>(static_cast<const uint16_t*>(X) + ex * T * D, T, D, kb, ke, lane, acc);
 }
 
@@ -243,7 +255,8 @@ __global__ __launch_bounds__(kFinishThreads) void k_gram_cols_finish(GramColsArg
 GramColsPlan plan_gram_cols(int B, int T, int d_in, int d_out, int dt) {
     GramColsPlan p{};
     const int piece = dt == 0 ? 4 : 8;                   // columns of a 16-byte piece; a step is two pieces
-    if (B < 1 || T < 2 || T > 64 || dt < 0 || dt > 2 || d_in < piece || d_out < piece || ((d_in | d_out) % piece) != 0) return p;
+    if (B < 1 || T < 2 || T > 64 || dt < 0 || dt > 2 || d_in < 1 || d_out < 1) return p;
+    if (dt != 0 && ((d_in | d_out) % piece) != 0) return p;     // 16-bit rows: whole 16-byte pieces only
     const int steps = ceil_div(d_in, 2 * piece) + ceil_div(d_out, 2 * piece);
     // fill the chip (2 workgroups on each of 256 compute units) with waves of at least kColsSteps steps
     int W = ceil_div(512, B);

@@ -1370,7 +1370,7 @@ GRAM_COLS_SHAPES = [(32, 16, 4608, 512), (20, 64, 2304, 256), (3, 33, 1032, 264)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
-@pytest.mark.parametrize("B,T,d_in,d_out", GRAM_COLS_SHAPES + [(6, 40, 1028, 516)])
+@pytest.mark.parametrize("B,T,d_in,d_out", GRAM_COLS_SHAPES + [(6, 40, 1028, 516), (128, 64, 500, 50), (9, 33, 1030, 21)])
 def test_gram_column_split_few_positions(dp, dtype, B, T, d_in, d_out):
     A, G = wl.random_layer(5150 + B + T + d_in, B, T, d_in, d_out, dtype, g_row_scale=np.exp(np.linspace(-2, 1, B)))
     s_ref = orc.layer_sqnorm(A, G)
