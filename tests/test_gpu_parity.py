@@ -1518,3 +1518,76 @@ def test_clipped_sum_small_matrix_many_rows(dp, dtype, B, T, d_in, d_out):
         dp.clipped_grad(Ad, Gd, cd, g2, accumulate=True)
         np.testing.assert_allclose(g2.cpu().numpy(), got + np.float32(0.25), rtol=0, atol=1e-6 * (1 + np.abs(got).max()))
     np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, cd).cpu().numpy(), got)       # reruns are bit-identical
+
+
+# Drawn model stacks: 6 to 28 layers taken at random from the kinds of layers that the several-layers calls treat
+# differently (dense, column-split Gram in both sizes, the joint clipped-sum classes with 256 x 256 tiles, 128 x 128
+# tiles and ragged T, copy-pipeline Gram, unaligned widths, a long first convolution), some with bias rows.
+STACK_PALETTE = [(1, 200, 50), (1, 64, 10), (16, 1024, 64), (4, 520, 520), (40, 1032, 264), (32, 576, 64), (64, 128, 72),
+                 (32, 1152, 128), (16, 256, 64), (49, 128, 136), (32, 512, 256), (64, 256, 512), (33, 27, 64), (7, 300, 10),
+                 (128, 64, 64), (96, 128, 64), (1024, 27, 16)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("seed", range(8))
+def test_drawn_model_stacks(dp, dtype, seed):
+    """Norms with bias terms, clip factors and clipped sums with noise of a drawn stack through the two several-layers
+    calls and through dp_layers_step, against the oracle layer by layer."""
+    rng = np.random.default_rng(31000 + seed)
+    B = int(rng.integers(3, 14))
+    n_layers = int(rng.integers(6, 29))
+    shapes = [STACK_PALETTE[int(k)] for k in rng.integers(0, len(STACK_PALETTE), n_layers)]
+    with_bias = rng.random(n_layers) < 0.3
+    layers = [wl.random_layer(32000 + 100 * seed + i, B, T, di, do, dtype, a_dist="relu", g_row_scale=np.exp(np.linspace(-1, 1, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    s_ref = orc.total_sqnorm(layers) + sum(orc.bias_sqnorm(G) for (A, G), wb in zip(layers, with_bias) if wb)
+    C = float(np.sqrt(np.median(s_ref)))
+    c_ref = orc.clip_factors(s_ref, C)
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    rows = [torch.empty((B, G.shape[-1]), device="cuda") if wb else None for (A, G), wb in zip(dev, with_bias)]
+    # every gradient starts at a multiple of 4 floats (the library wants 16-byte aligned outputs); the gaps stay untouched
+    sizes = [(A.shape[-1] * G.shape[-1] + 3) // 4 * 4 + ((G.shape[-1] + 3) // 4 * 4 if wb else 0) for (A, G), wb in zip(dev, with_bias)]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.full((int(sum(sizes)),), 3.0, device="cuda")
+    grads, gbs, offs_b = [], [], []
+    for i, ((A, G), wb) in enumerate(zip(dev, with_bias)):
+        nw = A.shape[-1] * G.shape[-1]
+        nb = (nw + 3) // 4 * 4
+        grads.append(flat[starts[i]:starts[i] + nw].view(A.shape[-1], G.shape[-1]))
+        gbs.append(flat[starts[i] + nb:starts[i] + nb + G.shape[-1]] if wb else None)
+        offs_b.append(starts[i] + nb)
+    descs = dp.layer_descs(dev, grads, starts[:-1], bias_rows=rows, grad_bs=gbs, bias_noise_offsets=offs_b)
+    c = torch.full((B,), -1.0, device="cuda")
+    s = dp.layers_sqnorm(dev, descs=descs, C=C, clip=c)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], (shapes, rel_err(s.cpu().numpy(), s_ref))
+    np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s, C).cpu().numpy())
+    dp.layers_clipped_grad(dev, c, descs=descs, noise_std=0.5, seed=77)
+    cn = c.cpu().numpy().astype(np.float64)
+    got = flat.cpu().numpy().astype(np.float64)
+    noise = orc.add_noise(np.zeros(int(sum(sizes))), 0.5, 77, 0)
+    for i, ((A, G), wb) in enumerate(zip(layers, with_bias)):
+        nw = A.shape[-1] * G.shape[-1]
+        want = orc.clipped_grad(A, G, cn).ravel()
+        err = np.linalg.norm(got[starts[i]:starts[i] + nw] - noise[starts[i]:starts[i] + nw] - want) / max(np.linalg.norm(want), 1e-300)
+        assert err <= FRO_TOL[dtype], (shapes[i], err)
+        if wb:
+            wantb = orc.clipped_bias_grad(G, cn)
+            b0 = offs_b[i]
+            errb = np.max(np.abs(got[b0:b0 + wantb.size] - noise[b0:b0 + wantb.size] - wantb))
+            assert errb <= 1e-4 * (1 + np.max(np.abs(wantb))), (shapes[i], errb)
+    # one call for the whole step: the same bits
+    flat2 = torch.full_like(flat, -5.0)
+    grads2 = [flat2[starts[i]:starts[i] + g.numel()].view_as(g) for i, g in enumerate(grads)]
+    gbs2 = [flat2[offs_b[i]:offs_b[i] + gbs[i].numel()] if wb else None for i, wb in enumerate(with_bias)]
+    descs2 = dp.layer_descs(dev, grads2, starts[:-1], bias_rows=rows, grad_bs=gbs2, bias_noise_offsets=offs_b)
+    arr, _, dtc = descs2
+    ws = torch.empty(max(16, dp.layers_workspace_bytes(arr, B, dtc, "auto"), dp.layers_clipped_workspace_bytes(arr, B, dtc)), dtype=torch.uint8, device="cuda")
+    s2, c2 = torch.empty(B, device="cuda"), torch.empty(B, device="cuda")
+    dp.layers_step(descs2, C, s2, c2, ws, noise_std=0.5, seed=77)
+    touched = torch.zeros_like(flat, dtype=torch.bool)
+    for i, g in enumerate(grads):
+        touched[starts[i]:starts[i] + g.numel()] = True
+        if with_bias[i]:
+            touched[offs_b[i]:offs_b[i] + gbs[i].numel()] = True
+    assert torch.equal(s2, s) and torch.equal(c2, c) and torch.equal(flat2[touched], flat[touched])
+    assert torch.all(flat[~touched] == 3.0) and torch.all(flat2[~touched] == -5.0)           # the gaps are not written
