@@ -1591,3 +1591,32 @@ def test_drawn_model_stacks(dp, dtype, seed):
             touched[offs_b[i]:offs_b[i] + gbs[i].numel()] = True
     assert torch.equal(s2, s) and torch.equal(c2, c) and torch.equal(flat2[touched], flat[touched])
     assert torch.all(flat[~touched] == 3.0) and torch.all(flat2[~touched] == -5.0)           # the gaps are not written
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("seed", range(4))
+def test_drawn_model_stacks_with_per_layer_clipping(dp, dtype, seed):
+    """The same kinds of layers with a norm array, a clip array and a threshold per layer (Section 4: per-layer
+    clipping): every layer's norms, factors and clipped sum against the oracle's for that layer alone."""
+    rng = np.random.default_rng(41000 + seed)
+    B = int(rng.integers(3, 12))
+    n_layers = int(rng.integers(5, 20))
+    shapes = [STACK_PALETTE[int(k)] for k in rng.integers(0, len(STACK_PALETTE), n_layers)]
+    layers = [wl.random_layer(42000 + 100 * seed + i, B, T, di, do, dtype, a_dist="relu", g_row_scale=np.exp(np.linspace(-1, 1, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    s_l = [orc.layer_sqnorm(A, G) for A, G in layers]
+    Cl = [float(np.sqrt(np.median(s))) for s in s_l]
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    sq = [torch.full((B,), 9.0, device="cuda") for _ in range(n_layers)]
+    cl = [torch.full((B,), -1.0, device="cuda") for _ in range(n_layers)]
+    grads = [torch.full((A.shape[-1], G.shape[-1]), 7.0, device="cuda") for A, G in dev]
+    groups = [(sq[l], cl[l], Cl[l]) for l in range(n_layers)]
+    dp.layers_sqnorm(dev, descs=dp.layer_descs(dev, groups=groups))
+    for l in range(n_layers):
+        assert rel_err(sq[l].cpu().numpy(), s_l[l]) <= SQ_TIGHT[dtype], (shapes[l], rel_err(sq[l].cpu().numpy(), s_l[l]))
+        np.testing.assert_array_equal(cl[l].cpu().numpy(), dp.clip_factors(sq[l], Cl[l]).cpu().numpy())
+    assert any((c == 1.0).any() for c in cl) and any((c < 1.0).any() for c in cl)
+    dp.layers_clipped_grad(dev, None, descs=dp.layer_descs(dev, grads, groups=groups))
+    for l, ((A, G), g) in enumerate(zip(layers, grads)):
+        want = orc.clipped_grad(A, G, cl[l].cpu().numpy().astype(np.float64))
+        assert fro_err(g.cpu().numpy(), want) <= FRO_TOL[dtype], (shapes[l], fro_err(g.cpu().numpy(), want))
