@@ -1,5 +1,6 @@
-// Gram path for the per-example squared norm (Section 5.2, the sum over position pairs of
-// (A_i A_i^T)_{ts} (G_i G_i^T)_{ts}) for layers of few positions (T <= 64) and wide rows in a small batch: the late
+// Gram path for the per-example squared norm of a layer whose weights are shared by T positions (Sections 5.2 and
+// 5.3: g_i = A_i^T G_i; its squared Frobenius norm is the sum over position pairs of (A_i A_i^T)_{ts} (G_i G_i^T)_{ts})
+// for layers of few positions (T <= 64) and wide rows in a small batch: the late
 // convolutions of an image model (4 x 4 or 8 x 8 positions, 2304 -> 256 or 4608 -> 512 unfolded columns, 20 to 32
 // examples).  One workgroup per example walks thousands of columns alone there and leaves most of the chip idle, so
 // here the COLUMNS are split: every wave takes a range of the columns of A and G (one after the other), forms its
