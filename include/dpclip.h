@@ -141,7 +141,9 @@ dp_status dp_layer_sqnorm_static(const void* A, const void* G,
  * layer then fill the idle tail of another's, which a per-layer launch leaves
  * empty.  Dense layers (T == 1) share launches too, 16 each, and so do 16-bit
  * Gram layers of at most 64 positions with wide rows in a batch of fewer than
- * 512 (their columns are split over workgroups).  Every other layer runs the
+ * 512 (their columns are split over workgroups), and 16-bit layers on the
+ * direct path with T >= 64 and widths that are multiples of 8, unless they
+ * are large enough to do better alone.  Every other layer runs the
  * kernels dp_layer_sqnorm runs for it; where there are two or more of them,
  * their per-tile partial sums are added by one launch at the end instead of
  * one per layer.  The result equals per-layer calls up to the order of the

@@ -128,6 +128,22 @@ int gram_cols_class(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype 
 
 size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
 
+// a layer whose direct norm the shared copy-pipeline launch of dp_layers_sqnorm can take (16-bit, direct path, T >= 64,
+// aligned widths), and the scratch such a layer needs in the several-layers call: the larger of its own call's and
+// the shared launch's (one sum per example and 128 x 128 tile)
+bool direct_joinable(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
+    if (!is16(dtype) || T <= 1 || d_in == 0 || d_out == 0 || B >= (int64_t(1) << 20)) return false;
+    if (gram_batchable(T, d_in, d_out, dtype, path) || gram_cols_class(B, T, d_in, d_out, dtype, path) != 0) return false;
+    if (resolve_path(path, dtype, T, d_in, d_out) != DP_PATH_DIRECT) return false;
+    return dma_direct_joint_ok((int)B, (int)T, (int)d_in, (int)d_out);
+}
+size_t single_layer_need(int64_t B, const dp_layer_desc& y, dp_dtype dtype, dp_path path) {
+    size_t n = dp_workspace_bytes(DP_OP_SQNORM, B, y.T, y.d_in, y.d_out, dtype, path);
+    if (direct_joinable(B, y.T, y.d_in, y.d_out, dtype, path))
+        n = std::max(n, (size_t)B * (size_t)direct_joint_tiles((int)y.d_in, (int)y.d_out) * sizeof(float));
+    return round16(n);
+}
+
 // Which joint clipped-sum launch of dp_layers_clipped_grad(_noise) can take a layer (by shape and type): 0 none,
 // 1 the 256 x 256-tile launch, 3 the 128 x 128-tile launch for aligned 16-bit layers of a few hundred columns, 4 the
 // same for such layers whose T is not a multiple of the 32-row stage
@@ -622,9 +638,9 @@ size_t layers_ws_bytes(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
             ++in_batch;
             if (batch > batch_max) batch_max = batch;
         } else {
-            const size_t n = dp_workspace_bytes(DP_OP_SQNORM, B, y.T, y.d_in, y.d_out, dtype, path);
+            const size_t n = single_layer_need(B, y, dtype, path);
             if (n > single) single = n;
-            if (!(y.T == 1 && !is8(dtype))) single_sum += round16(n);
+            if (!(y.T == 1 && !is8(dtype))) single_sum += n;
         }
     }
     // the layers that run one by one keep their partial sums apart until one launch folds them (up to a limit: with
@@ -760,11 +776,55 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
         queue.count = 0; ws_off = 0; acc = 1; launched = true;
         return e;
     };
+    // Two or more of them with aligned widths on the direct path: their norms share copy-pipeline launches of up to
+    // kJointLayers layers (a launch each is a few hundred workgroups and a tail), the sums join the queue.
+    int64_t n_dj = 0;
+    for (int64_t l = 0; l < n_layers; ++l)
+        if (direct_joinable(B, layers[l].T, layers[l].d_in, layers[l].d_out, dtype, path)) ++n_dj;
+    const bool join_direct = defer_on && n_dj >= 2;
+    if (join_direct) {
+        JointShape sh[kJointLayers];
+        JointOperands op[kJointLayers];
+        float* part[kJointLayers];
+        int tiles[kJointLayers];
+        int ng = 0;
+        size_t group_bytes = 0;
+        auto flush_group = [&]() -> hipError_t {
+            if (ng == 0) return hipSuccess;
+            if (queue.count + ng > FinalizeQueue::kMax || ws_off + group_bytes > workspace_bytes) {
+                const hipError_t e = flush_queue(false);
+                if (e != hipSuccess) return e;
+            }
+            for (int k = 0; k < ng; ++k) {
+                part[k] = reinterpret_cast<float*>(static_cast<char*>(workspace) + ws_off);
+                ws_off += round16((size_t)B * tiles[k] * sizeof(float));
+            }
+            const hipError_t e = launch_direct_bf16_dma_joint(sh, op, part, ng, (int)B, stream, dtype == DP_F16);
+            for (int k = 0; k < ng; ++k) { queue.partial[queue.count] = part[k]; queue.n[queue.count] = tiles[k]; ++queue.count; }
+            ng = 0; group_bytes = 0;
+            return e;
+        };
+        for (int64_t l = 0; l < n_layers; ++l) {
+            const dp_layer_desc& y = layers[l];
+            if (!direct_joinable(B, y.T, y.d_in, y.d_out, dtype, path)) continue;
+            const int t = direct_joint_tiles((int)y.d_in, (int)y.d_out);
+            // (a layer's sums alone always fit: the scratch is at least the largest single layer's need)
+            if (ng > 0 && group_bytes + round16((size_t)B * t * sizeof(float)) > workspace_bytes && flush_group() != hipSuccess) return DP_ERR_HIP;
+            sh[ng] = JointShape{(int)y.T, (int)y.d_in, (int)y.d_out};
+            op[ng] = JointOperands{static_cast<const uint16_t*>(y.A), static_cast<const uint16_t*>(y.G), nullptr, nullptr, 0};
+            tiles[ng] = t;
+            group_bytes += round16((size_t)B * tiles[ng] * sizeof(float));
+            ++ng;
+            if (ng == kJointLayers && flush_group() != hipSuccess) return DP_ERR_HIP;
+        }
+        if (flush_group() != hipSuccess) return DP_ERR_HIP;
+    }
     for (int64_t l = 0; l < n_layers; ++l) {
         const dp_layer_desc& y = layers[l];
         if (y.T == 0 || (y.T == 1 && !is8(dtype)) || y.d_in == 0 || y.d_out == 0) continue;     // empty layers add nothing
         if (gram_batchable(y.T, y.d_in, y.d_out, dtype, path)) continue;
         if (gram_cols_class(B, y.T, y.d_in, y.d_out, dtype, path) != 0) continue;
+        if (join_direct && direct_joinable(B, y.T, y.d_in, y.d_out, dtype, path)) continue;
         if (!defer_on) {
             const dp_status s1 = layer_sqnorm_clip(y.A, y.G, B, y.T, y.d_in, y.d_out, dtype, path, acc, sqnorm, workspace, workspace_bytes,
                                                    hip_stream, (clip_with_single && l == last_single) ? &clip_out : nullptr);
@@ -773,7 +833,7 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
             continue;
         }
         // the layer's own region of the scratch: its partial sums stay there until the queue is folded
-        const size_t need_l = round16(dp_workspace_bytes(DP_OP_SQNORM, B, y.T, y.d_in, y.d_out, dtype, path));
+        const size_t need_l = single_layer_need(B, y, dtype, path);
         if ((queue.count == FinalizeQueue::kMax || ws_off + need_l > workspace_bytes) && flush_queue(false) != hipSuccess) return DP_ERR_HIP;
         const ClipOut co_defer{C, nullptr, &queue};
         const int before = queue.count;

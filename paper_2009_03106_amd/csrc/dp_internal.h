@@ -170,6 +170,12 @@ hipError_t launch_clipped_f8_dma_joint(const JointShape* sh, const JointOperands
 // noise: stddev == 0 for none, else every layer's d_in * d_out and noise_offset are multiples of 4
 hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
                                          float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16, int geo = 1);
+// several layers' direct norms in one launch (128 x 128 tiles; T >= 64, widths multiples of 8); partial[l]: the layer's
+// [B][direct_joint_tiles(M, N)] sums of squares per (example, tile), to be added by the caller
+bool dma_direct_joint_ok(int B, int T, int M, int N);
+int direct_joint_tiles(int M, int N);
+hipError_t launch_direct_bf16_dma_joint(const JointShape* sh, const JointOperands* op, float* const* partial, int n_layers,
+                                        int B, hipStream_t st, bool f16);
 // direct squared norm with the copy-pipeline kernel; partial[B][tiles_m * tiles_n]
 bool dma_direct_ok(int T, int M, int N);
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N);

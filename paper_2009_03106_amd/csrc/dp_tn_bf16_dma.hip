@@ -454,7 +454,8 @@ struct JointArgs {
 __device__ __attribute__((aligned(256))) unsigned int g_zero_line[64];
 
 // AM: 0 = every layer's T is a multiple of the 32-row stage, 2 = ragged T (stages padded with the line of zeros)
-template <class GEO, bool F16, int AM>
+// MODE 1: the layers' direct squared norms (a layer's "K slices" are its examples, `slices` is partial[B][tiles])
+template <class GEO, bool F16, int AM, int MODE = 0>
 __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma_joint(JointArgs j) {
     const int L = (blockIdx.x & 7) * j.per_xcd + (blockIdx.x >> 3);
     if (L >= j.n_items) return;
@@ -470,7 +471,7 @@ __global__ __launch_bounds__(GEO::THREADS, GEO::OCC) void k_tn_bf16_dma_joint(Jo
     a.per_xcd = 0; a.accumulate = y.accumulate;
     a.H = a.W = a.C = a.KW = a.Wout = 1; a.pad = 0;
     a.zero = AM == 2 ? reinterpret_cast<const uint16_t*>(g_zero_line) : nullptr;
-    tn_dma_tile<GEO, 0, AM, F16>(a, L - y.first_item);
+    tn_dma_tile<GEO, MODE, AM, F16>(a, L - y.first_item);
 }
 
 
@@ -723,6 +724,53 @@ static bool direct_padded_ok(int T, int M, int N) {
     return padded * 2 <= (int64_t)M * N * 5;
 }
 bool dma_direct_ok(int T, int M, int N) { return T >= 64 && (dma_geometry(T, M, N) != 0 || direct_padded_ok(T, M, N)); }
+
+// Several layers' direct norms in one launch of 128 x 128 tiles (the long, narrow convolutions of an image model:
+// a launch each is a few hundred workgroups and a tail; together they stream).  partial: per layer [B][tiles].
+bool dma_direct_joint_ok(int B, int T, int M, int N) {
+    if (!dma_direct_ok(T, M, N)) return false;
+    // layers that tile well with 192 x 128 do better alone on those tiles once they are large (more flop per copied byte)
+    if (dma_geometry(T, M, N) == 2 && (int64_t)B * T * ((int64_t)M + N) * 2 > (int64_t(32) << 20)) return false;
+    if ((int64_t)T * (M > N ? M : N) * 2 >= (int64_t(1) << 31)) return false;       // ragged mode: lane offsets inside an example
+    if (dma_geometry(T, M, N) == 1) return false;     // layers that fill 256 x 256 tiles are bound by the MFMA rate: their own launch
+    return tiles_fit(M, N, GeoT::TM, GeoT::TN) || direct_padded_ok(T, M, N);
+}
+int direct_joint_tiles(int M, int N) { return ceil_div(M, GeoT::TM) * ceil_div(N, GeoT::TN); }
+
+hipError_t launch_direct_bf16_dma_joint(const JointShape* sh, const JointOperands* op, float* const* partial, int n_layers,
+                                        int B, hipStream_t st, bool f16) {
+    if (n_layers < 1 || n_layers > kJointMax) return hipErrorInvalidValue;
+    JointArgs j;
+    int64_t first = 0;
+    bool ragged = false;
+    for (int l = 0; l < n_layers; ++l) {
+        JointLayer& y = j.layer[l];
+        y.A = op[l].A; y.G = op[l].G; y.clip = nullptr;
+        y.slices = partial[l];
+        y.accumulate = 0;
+        y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
+        y.tiles_m = ceil_div(sh[l].M, GeoT::TM); y.tiles_n = ceil_div(sh[l].N, GeoT::TN);
+        y.splits = B;                                   // one "slice" per example
+        y.stages_per_split = ceil_div(sh[l].T, DK);
+        y.stages_total = (int)((int64_t)B * y.stages_per_split);
+        y.first_item = (int)first;
+        first += (int64_t)y.tiles_m * y.tiles_n * B;
+        ragged = ragged || (sh[l].T % DK) != 0;
+    }
+    if (first >= (int64_t(1) << 28)) return hipErrorInvalidValue;
+    for (int l = n_layers; l < kJointMax; ++l) j.layer[l] = j.layer[0];
+    j.n_layers = n_layers; j.n_items = (int)first; j.per_xcd = ceil_div(first, 8);
+    j.B = B;
+    const unsigned grid = 8u * (unsigned)j.per_xcd;
+    if (ragged) {
+        if (f16) k_tn_bf16_dma_joint<GeoT, true, 2, 1><<<grid, GeoT::THREADS, 0, st>>>(j);
+        else     k_tn_bf16_dma_joint<GeoT, false, 2, 1><<<grid, GeoT::THREADS, 0, st>>>(j);
+    } else {
+        if (f16) k_tn_bf16_dma_joint<GeoT, true, 0, 1><<<grid, GeoT::THREADS, 0, st>>>(j);
+        else     k_tn_bf16_dma_joint<GeoT, false, 0, 1><<<grid, GeoT::THREADS, 0, st>>>(j);
+    }
+    return hipGetLastError();
+}
 
 TnPlan plan_direct_bf16_dma(int B, int T, int M, int N) {
     const int geo = dma_geometry(T, M, N) != 0 ? pick_geometry(T, M, N, B) : 3;

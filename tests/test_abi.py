@@ -152,6 +152,9 @@ def test_layers_workspace_sizes(lib):
     assert f(many, 8, dpclip.DP_BF16, "gram") == 16 * 8 * 1 * 4           # launches of 16 and 4 layers reuse the space
     mixed = descs([(1, 64, 32), (1024, 576, 128), (0, 8, 8)])
     assert f(mixed, 128, dpclip.DP_BF16) == (dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 128, 1024, 576, 128, dpclip.DP_BF16) + 15) // 16 * 16
+    # at 16 examples the shared copy-pipeline launch of direct norms can take that layer: one sum per example and 128 x 128
+    # tile (5 tiles), at least its own call's need (3 tiles of 192 x 128)
+    assert f(mixed, 16, dpclip.DP_BF16) == 16 * 5 * 4 >= (dpclip.workspace_bytes(dpclip.DP_OP_SQNORM, 16, 1024, 576, 128, dpclip.DP_BF16) + 15) // 16 * 16
     assert f(descs([(512, 1 << 24, 64)]), 2, dpclip.DP_BF16) == 0         # width out of range
     # the clipped sums of several layers run one after the other and share the largest layer's scratch ...
     h = dpclip.layers_clipped_workspace_bytes

@@ -1620,3 +1620,34 @@ def test_drawn_model_stacks_with_per_layer_clipping(dp, dtype, seed):
     for l, ((A, G), g) in enumerate(zip(layers, grads)):
         want = orc.clipped_grad(A, G, cl[l].cpu().numpy().astype(np.float64))
         assert fro_err(g.cpu().numpy(), want) <= FRO_TOL[dtype], (shapes[l], fro_err(g.cpu().numpy(), want))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_layers_sqnorm_direct_norms_share_a_launch(dp, dtype):
+    """Aligned layers on the direct path share a copy-pipeline launch of 128 x 128 tiles in the several-layers call
+    (ragged T, tiles that are mostly padding, one and several tiles), next to layers that run alone (an unaligned one,
+    a dense one); the sums of all of them are folded by one launch, which writes the clip factors."""
+    B = 5
+    shapes = [(160, 576, 64), (128, 64, 192), (200, 72, 328), (136, 72, 96), (256, 576, 128), (64, 1152, 128), (33, 27, 64), (1, 64, 10),
+              (96, 256, 256)]
+    layers = [wl.random_layer(11000 + i, B, T, di, do, dtype, a_dist="relu", g_row_scale=np.exp(np.linspace(-1, 1, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    s_ref = orc.total_sqnorm(layers)
+    C = float(np.sqrt(np.median(s_ref)))
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    c = torch.full((B,), -1.0, device="cuda")
+    s = dp.layers_sqnorm(dev, C=C, clip=c, path="direct")
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], rel_err(s.cpu().numpy(), s_ref)
+    np.testing.assert_array_equal(c.cpu().numpy(), dp.clip_factors(s, C).cpu().numpy())
+    one_by_one = None
+    for li, (A, G) in enumerate(dev):
+        one_by_one = dp.layer_sqnorm(A, G, one_by_one, path="direct", accumulate=li > 0)
+    assert rel_err(s.cpu().numpy(), one_by_one.cpu().numpy().astype(np.float64)) <= 2e-6      # float32 order of the sums
+    s2 = torch.full((B,), 0.5, device="cuda")
+    dp.layers_sqnorm(dev, s2, path="direct", accumulate=True)
+    assert rel_err(s2.cpu().numpy(), s_ref + 0.5) <= SQ_TIGHT[dtype]
+    np.testing.assert_array_equal(dp.layers_sqnorm(dev, path="direct").cpu().numpy(), s.cpu().numpy())
+    # each shared layer alone against the oracle (a wrong tile mask or a ragged stage would hide in the total)
+    for (A, G), (Ad, Gd), sh in zip(layers[:6], dev[:6], shapes[:6]):
+        pair = dp.layers_sqnorm([(Ad, Gd), (Ad, Gd)], path="direct")
+        assert rel_err(pair.cpu().numpy(), 2 * orc.layer_sqnorm(A, G)) <= SQ_TIGHT[dtype], sh
