@@ -640,10 +640,25 @@ bool dma_joint_ragged_ok(int T, int M, int N) {
 namespace {
 inline int joint_tile(int geo) { return geo == 1 ? GeoL::TM : GeoT::TM; }
 inline int joint_slots(int geo) { return geo == 1 ? 256 * GeoL::OCC : 256 * GeoT::OCC; }
+// A group of the first class whose 256 x 256 tiles are so few and whose contractions are so short that the tiles
+// would be cut into 4 or more K slices of at most 16 stages (a few examples of 64 positions into 2304 x 256: 9 tiles
+// per layer, slices of 8 stages) runs on the second class's tiles: four times the tiles, half the slices to store
+// and fold, and nothing there is bound by the MFMA rate.
+inline int joint_group_geo(const JointShape* sh, int n_layers, int B, int geo) {
+    if (geo != 1) return geo;
+    const JointPlan p = plan_joint(sh, n_layers, B, DK, GeoL::TM, 256 * GeoL::OCC);
+    int most = 1, longest = 1;
+    for (int l = 0; l < n_layers; ++l) {
+        most = most > p.splits[l] ? most : p.splits[l];
+        longest = longest > p.sps[l] ? longest : p.sps[l];
+    }
+    return (most >= 4 && longest <= 16) ? 3 : 1;
+}
 }
 
 // floats of workspace: every layer's slices, one layer after the other
 size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B, int geo) {
+    geo = joint_group_geo(sh, n_layers, B, geo);
     const JointPlan p = plan_joint(sh, n_layers, B, DK, joint_tile(geo), joint_slots(geo));
     size_t slices = 0;
     for (int l = 0; l < n_layers; ++l) slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
@@ -653,6 +668,7 @@ size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B, int geo
 hipError_t launch_clipped_bf16_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
                                          float stddev, uint64_t seed, float* ws, hipStream_t st, bool f16, int geo) {
     if (n_layers < 1 || n_layers > kJointMax || (geo != 1 && geo != 3 && geo != 4)) return hipErrorInvalidValue;
+    geo = joint_group_geo(sh, n_layers, B, geo);
     const JointPlan p = plan_joint(sh, n_layers, B, DK, joint_tile(geo), joint_slots(geo));
     if (p.items >= (int64_t(1) << 28)) return hipErrorInvalidValue;
     JointArgs j;
