@@ -135,7 +135,8 @@ bool direct_joinable(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype
     if (!is16(dtype) || T <= 1 || d_in == 0 || d_out == 0 || B >= (int64_t(1) << 20)) return false;
     if (gram_batchable(T, d_in, d_out, dtype, path) || gram_cols_class(B, T, d_in, d_out, dtype, path) != 0) return false;
     if (resolve_path(path, dtype, T, d_in, d_out) != DP_PATH_DIRECT) return false;
-    return dma_direct_joint_ok((int)B, (int)T, (int)d_in, (int)d_out);
+    if (!dma_direct_joint_ok((int)B, (int)T, (int)d_in, (int)d_out)) return false;
+    return B * direct_joint_tiles((int)d_in, (int)d_out) < (int64_t(1) << 24);       // 16 layers' items stay below the launch's 2^28
 }
 size_t single_layer_need(int64_t B, const dp_layer_desc& y, dp_dtype dtype, dp_path path) {
     size_t n = dp_workspace_bytes(DP_OP_SQNORM, B, y.T, y.d_in, y.d_out, dtype, path);
