@@ -230,7 +230,8 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
  *   workspace  device scratch of at least dp_layers_clipped_workspace_bytes(...)
  *              bytes (the largest single layer's need, or a group's slices).
  * A third kind of group takes such 16-bit layers whose T is at least 16 and not
- * a multiple of 32 (4 x 4 or 7 x 7 positions). */
+ * a multiple of 32 (4 x 4 or 7 x 7 positions); float32 layers with at least 256
+ * rows B*T and widths that are multiples of 4 form groups of their own. */
 dp_status dp_layers_clipped_grad(const dp_layer_desc* layers, int64_t n_layers, int64_t B,
                                  const float* clip, dp_dtype dtype, int accumulate,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -147,17 +147,23 @@ size_t single_layer_need(int64_t B, const dp_layer_desc& y, dp_dtype dtype, dp_p
 
 // Which joint clipped-sum launch of dp_layers_clipped_grad(_noise) can take a layer (by shape and type): 0 none,
 // 1 the 256 x 256-tile launch, 3 the 128 x 128-tile launch for aligned 16-bit layers of a few hundred columns, 4 the
-// same for such layers whose T is not a multiple of the 32-row stage
+// same for such layers whose T is not a multiple of the 32-row stage, 5 the float32 launch
 int clipped_join_class(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype) {
     if (B == 0 || T == 0 || d_in == 0 || d_out == 0) return 0;
     if (is8(dtype)) return (dma8_clipped_ok((int)T, (int)d_in, (int)d_out) && dma8_joint_ok((int)T, (int)d_in, (int)d_out)) ? 1 : 0;
-    if (!is16(dtype)) return 0;
+    if (!is16(dtype)) {
+        // float32: the layers of the copy-pipeline kernel (long contractions, widths multiples of 4) share launches too
+        if (B * T >= (int64_t(1) << 31)) return 0;
+        const TnPlan p = plan_clipped_f32((int)B, (int)T, (int)d_in, (int)d_out);
+        return (p.dma && !clipped_f32_is_short(p)) ? 5 : 0;
+    }
     if (plan_clipped_bf16((int)B, (int)T, (int)d_in, (int)d_out).dma && dma_joint_ok((int)T, (int)d_in, (int)d_out)) return 1;
     if (B * T < (int64_t(1) << 31) && dma_joint_mid_ok((int)T, (int)d_in, (int)d_out)) return 3;
     if (B * T < (int64_t(1) << 31) && dma_joint_ragged_ok((int)T, (int)d_in, (int)d_out)) return 4;
     return 0;
 }
 size_t joint_ws_bytes(const JointShape* sh, int n, int64_t B, dp_dtype dtype, int geo) {
+    if (geo == 5) return joint_f32_workspace_floats(sh, n, (int)B) * sizeof(float);
     return (is8(dtype) ? joint8_workspace_floats(sh, n, (int)B) : joint_workspace_floats(sh, n, (int)B, geo)) * sizeof(float);
 }
 
@@ -1023,7 +1029,7 @@ size_t dp_layers_clipped_workspace_bytes(const dp_layer_desc* layers, int64_t n_
         const size_t n = dp_workspace_bytes(DP_OP_CLIPPED_GRAD, B, y.T, y.d_in, y.d_out, dtype, DP_PATH_AUTO);
         if (n > need) need = n;
     }
-    for (int geo : {1, 3, 4}) {                              // the two classes of joint launches, each in groups of its own
+    for (int geo : {1, 3, 4, 5}) {                              // the two classes of joint launches, each in groups of its own
         JointShape sh[kJointLayers];
         int nj = 0;
         auto joint_need = [&]() {
@@ -1082,7 +1088,7 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
     // A second class of joint launches (128 x 128 tiles) takes the aligned 16-bit layers of a few hundred columns.
     std::vector<std::vector<int64_t>> joint_groups;
     std::vector<int> joint_geo;
-    for (int geo : {1, 3, 4}) {
+    for (int geo : {1, 3, 4, 5}) {
         std::vector<int64_t> cur;
         const size_t first_group = joint_groups.size();
         for (int64_t l = 0; l < n_layers; ++l) {
@@ -1120,7 +1126,10 @@ dp_status dp_layers_clipped_grad_noise(const dp_layer_desc* layers, int64_t n_la
                                   y.noise_offset};
             done[(size_t)g[k]] = 1;
         }
-        const hipError_t ej = is8(dtype)
+        const hipError_t ej = joint_geo[gi] == 5
+            ? launch_clipped_f32_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
+                                           static_cast<hipStream_t>(hip_stream))
+            : is8(dtype)
             ? launch_clipped_f8_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),
                                           static_cast<hipStream_t>(hip_stream), fmt_of(dtype))
             : launch_clipped_bf16_dma_joint(sh, op, (int)g.size(), (int)B, accumulate != 0, stddev, seed, static_cast<float*>(workspace),

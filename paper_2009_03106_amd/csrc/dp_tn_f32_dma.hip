@@ -13,6 +13,7 @@
 // Two uses, as in the 16-bit file: clipped sum (Eq. weighted_loss) over K slices, and direct squared norm (Algorithm
 // 3 / 4 without their output tensor): the slice is one example and the finished tile is squared and summed.
 // Needs d_in and d_out multiples of 4 (16-byte pieces) and 16-byte aligned operands.
+#include <algorithm>
 #include "dp_common.h"
 #include "dp_internal.h"
 
@@ -49,14 +50,12 @@ __device__ float g_factor_consts[2] = {0.0f, 1.0f};
 template <int N> __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14)); }
 
 // MODE 0: clipped sum over K slice z = rows [z kchunk, (z + 1) kchunk).  MODE 1: direct squared norm of example z.
+// item L of the launch: (slice, tile), slice-major
 template <int MODE>
-__global__ __launch_bounds__(kThreads, 2) void k_tn_f32_dma(F32DmaArgs a) {
+__device__ __forceinline__ void tn_f32_dma_tile(const F32DmaArgs& a, const int L) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NSTF * STAGE_B + NSTF * 4 * CSB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // workgroup b runs on XCD b % 8: each XCD takes a contiguous run of (slice, tile) items, slice-major, so that
-    // its workgroups stream the same rows of A and G through one L2
-    const int L = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
     const int tiles = a.tiles_m * a.tiles_n;
     if (L >= (int64_t)tiles * a.splits) return;
     const int z = L / tiles, tile = L - z * tiles;
@@ -244,7 +243,116 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_f32_dma(F32DmaArgs a) {
         }
 }
 
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 2) void k_tn_f32_dma(F32DmaArgs a) {
+    // workgroup b runs on XCD b % 8: each XCD takes a contiguous run of (slice, tile) items, slice-major, so that
+    // its workgroups stream the same rows of A and G through one L2
+    tn_f32_dma_tile<MODE>(a, (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3));
+}
+
+// Several layers' clipped sums in one launch, as for the 16-bit inputs (dp_tn_bf16_dma.hip): the launch is a list of
+// (layer, K slice, tile) items, a layer's items slice-major, dealt to the XCDs in contiguous runs.
+struct F32JointLayer {
+    const float* A; const float* G; const float* clip;
+    float* out;            // the layer's K slices; the gradient itself where one slice is the whole sum
+    int K, T, M, N, tiles_m, tiles_n, splits, kchunk, first_item, accumulate;
+};
+struct F32JointArgs {
+    F32JointLayer layer[kJointLayers];
+    int n_layers, n_items, per_xcd;
+};
+__global__ __launch_bounds__(kThreads, 2) void k_tn_f32_dma_joint(F32JointArgs j) {
+    const int L = (blockIdx.x & 7) * j.per_xcd + (blockIdx.x >> 3);
+    if (L >= j.n_items) return;
+    int l = 0;
+    while (l + 1 < j.n_layers && L >= j.layer[l + 1].first_item) ++l;
+    const F32JointLayer& y = j.layer[l];
+    F32DmaArgs a;
+    a.A = y.A; a.G = y.G; a.clip = y.clip;
+    a.out = y.out; a.slice = (((int64_t)y.M * y.N) + 3) & ~(int64_t)3;          // splitk_slice_elems
+    a.K = y.K; a.T = y.T; a.M = y.M; a.N = y.N;
+    a.tiles_m = y.tiles_m; a.tiles_n = y.tiles_n; a.splits = y.splits; a.kchunk = y.kchunk;
+    a.per_xcd = 0; a.accumulate = y.accumulate;
+    tn_f32_dma_tile<0>(a, L - y.first_item);
+}
+
+// One slice length (in 16-row stages) for all layers of a joint launch, each layer rounding it to equal slices:
+// minimise  rounds of 512 workgroups x (stages of the longest slice + what an item costs besides its stages).
+struct F32JointPlan { int splits[kJointLayers], kchunk[kJointLayers], tiles_m[kJointLayers], tiles_n[kJointLayers]; int64_t items; };
+F32JointPlan plan_joint_f32(const JointShape* sh, int n_layers, int B) {
+    constexpr int64_t kItemOverhead = 16, kSlots = 512;
+    F32JointPlan best{};
+    int64_t best_cost = -1, stages_max = 1;
+    for (int l = 0; l < n_layers; ++l) stages_max = std::max<int64_t>(stages_max, ceil_div((int64_t)B * sh[l].T, DKF));
+    for (int64_t S = 1; S <= 512 && S <= stages_max; ++S) {
+        const int64_t len = (stages_max + S - 1) / S;
+        if (len < 8 && S > 1) break;
+        F32JointPlan p{};
+        int64_t longest = 0;
+        for (int l = 0; l < n_layers; ++l) {
+            const int64_t stages = ceil_div((int64_t)B * sh[l].T, DKF);
+            int64_t splits = (stages + len - 1) / len;
+            const int64_t sps = (stages + splits - 1) / splits;
+            splits = (stages + sps - 1) / sps;
+            p.tiles_m[l] = ceil_div(sh[l].M, TMF); p.tiles_n[l] = ceil_div(sh[l].N, TNF);
+            p.splits[l] = (int)splits; p.kchunk[l] = (int)(sps * DKF);
+            p.items += (int64_t)p.tiles_m[l] * p.tiles_n[l] * splits;
+            longest = std::max(longest, sps);
+        }
+        const int64_t cost = ((p.items + kSlots - 1) / kSlots) * (longest + kItemOverhead);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = p; }
+    }
+    return best;
+}
+
 }  // namespace
+
+size_t joint_f32_workspace_floats(const JointShape* sh, int n_layers, int B) {
+    const F32JointPlan p = plan_joint_f32(sh, n_layers, B);
+    size_t slices = 0;
+    for (int l = 0; l < n_layers; ++l) slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
+    return slices;
+}
+
+// noise: stddev == 0 for none, else every layer's d_in * d_out and noise_offset are multiples of 4.  A, G of the
+// operands are float pointers here.
+hipError_t launch_clipped_f32_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
+                                        float stddev, uint64_t seed, float* ws, hipStream_t st) {
+    if (n_layers < 1 || n_layers > kJointLayers) return hipErrorInvalidValue;
+    const F32JointPlan p = plan_joint_f32(sh, n_layers, B);
+    if (p.items >= (int64_t(1) << 28)) return hipErrorInvalidValue;
+    F32JointArgs j;
+    FoldLayers f;
+    int nf = 0;
+    float* slices = ws;
+    int64_t first = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        F32JointLayer& y = j.layer[l];
+        y.A = reinterpret_cast<const float*>(op[l].A); y.G = reinterpret_cast<const float*>(op[l].G); y.clip = op[l].clip;
+        // one slice and no noise to add: the launch writes the gradient itself, nothing to fold
+        const bool whole = p.splits[l] == 1 && stddev == 0.0f;
+        y.out = whole ? op[l].grad : slices;
+        y.accumulate = whole && accumulate ? 1 : 0;
+        y.K = B * sh[l].T; y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
+        y.tiles_m = p.tiles_m[l]; y.tiles_n = p.tiles_n[l]; y.splits = p.splits[l]; y.kchunk = p.kchunk[l];
+        y.first_item = (int)first;
+        first += (int64_t)p.tiles_m[l] * p.tiles_n[l] * p.splits[l];
+        if (!whole) {
+            f.ws[nf] = slices; f.grad[nf] = op[l].grad; f.n[nf] = (int64_t)sh[l].M * sh[l].N;
+            f.splits[nf] = p.splits[l]; f.noise_offset[nf] = op[l].noise_offset;
+            ++nf;
+        }
+        slices += (size_t)p.splits[l] * (size_t)splitk_slice_elems((int64_t)sh[l].M * sh[l].N);
+    }
+    for (int l = n_layers; l < kJointLayers; ++l) j.layer[l] = j.layer[0];
+    j.n_layers = n_layers; j.n_items = (int)p.items; j.per_xcd = ceil_div(p.items, 8);
+    k_tn_f32_dma_joint<<<8u * (unsigned)j.per_xcd, kThreads, 0, st>>>(j);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nf == 0) return e;
+    f.n_layers = nf;
+    for (int l = nf; l < kJointLayers; ++l) { f.ws[l] = f.ws[0]; f.grad[l] = f.grad[0]; f.n[l] = 0; f.splits[l] = 0; f.noise_offset[l] = 0; }
+    return launch_splitk_reduce_layers(f, accumulate, st, stddev, seed);
+}
 
 // Shapes for this kernel: 16-byte pieces, and tiles of 128 that are not mostly padding.
 bool f32_dma_ok(int64_t K, int M, int N) {

@@ -161,7 +161,9 @@ def test_layers_workspace_sizes(lib):
     shapes = [(512, 768, 2304), (512, 768, 768), (512, 768, 3072), (512, 3072, 768)]
     single = max((dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *sh, dpclip.DP_BF16) + 15) // 16 * 16 for sh in shapes)
     assert h(descs(shapes[:1]), 64, dpclip.DP_BF16) == (dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *shapes[0], dpclip.DP_BF16) + 15) // 16 * 16
-    assert h(tr, 64, dpclip.DP_F32) == max((dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *sh, dpclip.DP_F32) + 15) // 16 * 16 for sh in shapes)
+    # (float32 too: 2048 stages of 16 rows per layer cut into 7 slices, 432 tiles of 128 x 128 x 7 = 5.9 rounds of 512 workgroups)
+    assert h(tr, 64, dpclip.DP_F32) == 7 * sum(di * do for _, di, do in shapes) * 4
+    assert h(descs(shapes[:1]), 64, dpclip.DP_F32) == (dpclip.workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 64, *shapes[0], dpclip.DP_F32) + 15) // 16 * 16
     # ... except aligned 16-bit layers on 256 x 256 tiles, which share one launch and keep all their K slices at once:
     # 64 * 16 stages per layer cut into 7 slices (756 items = 3 rounds of the 256 compute units)
     assert h(tr, 64, dpclip.DP_BF16) == 7 * sum(di * do for _, di, do in shapes) * 4 > single

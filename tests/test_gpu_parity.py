@@ -1651,3 +1651,34 @@ def test_layers_sqnorm_direct_norms_share_a_launch(dp, dtype):
     for (A, G), (Ad, Gd), sh in zip(layers[:6], dev[:6], shapes[:6]):
         pair = dp.layers_sqnorm([(Ad, Gd), (Ad, Gd)], path="direct")
         assert rel_err(pair.cpu().numpy(), 2 * orc.layer_sqnorm(A, G)) <= SQ_TIGHT[dtype], sh
+
+
+@pytest.mark.parametrize("noise", [False, True])
+def test_layers_clipped_grad_float32_layers_share_a_launch(dp, noise):
+    """float32 layers of the copy-pipeline kernel (long contractions, widths multiples of 4) share one launch in the
+    several-layers call; next to them a layer of an odd width and a short one, which keep launches of their own."""
+    B = 24
+    shapes = [(64, 576, 128), (32, 1152, 256), (16, 2304, 256), (128, 128, 128), (64, 27, 64), (2, 128, 128), (48, 260, 380)]
+    layers = [wl.random_layer(12000 + i, B, T, di, do, "f32", a_dist="relu", g_std=0.02, g_row_scale=np.exp(np.linspace(-2, 2, B)))
+              for i, (T, di, do) in enumerate(shapes)]
+    s_ref = orc.total_sqnorm(layers)
+    c_ref = orc.clip_factors(s_ref, float(np.sqrt(np.median(s_ref))))
+    dev = [(to_dev(A), to_dev(G)) for A, G in layers]
+    c = to_dev(c_ref.astype(np.float32))
+    sizes = [A.shape[-1] * G.shape[-1] for A, G in dev]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    flat = torch.full((sum(sizes),), 7.0, device="cuda")
+    grads = [flat[starts[i]:starts[i + 1]].view(A.shape[-1], G.shape[-1]) for i, (A, G) in enumerate(dev)]
+    dp.layers_clipped_grad(dev, c, grads)
+    for (A, G), (An, Gn), g in zip(dev, layers, grads):
+        check_clipped_sum(dp, An, Gn, c_ref.astype(np.float32), g.cpu().numpy(), "f32", tuple(An.shape) + (Gn.shape[-1],))
+        assert_same_sums(g.cpu().numpy(), dp.clipped_grad(A, G, c).cpu().numpy(), joint=True)
+    clean = flat.clone()
+    np.testing.assert_array_equal(dp.layers_clipped_grad(dev, c)[1].cpu().numpy(), grads[1].cpu().numpy())    # reruns
+    if noise:
+        dp.layers_clipped_grad(dev, c, descs=dp.layer_descs(dev, grads, starts[:-1]), noise_std=0.25, seed=11)
+        dp.add_noise(clean, 0.25, 11, 0)
+        assert torch.equal(flat, clean)
+    else:
+        dp.layers_clipped_grad(dev, c, grads, accumulate=True)
+        np.testing.assert_allclose(flat.cpu().numpy(), 2 * clean.cpu().numpy(), rtol=0, atol=1e-6 * float(clean.abs().max()))
