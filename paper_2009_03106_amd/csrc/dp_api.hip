@@ -132,10 +132,15 @@ size_t round16(size_t n) { return (n + 15) & ~size_t(15); }
 // aligned widths), and the scratch such a layer needs in the several-layers call: the larger of its own call's and
 // the shared launch's (one sum per example and 128 x 128 tile)
 bool direct_joinable(int64_t B, int64_t T, int64_t d_in, int64_t d_out, dp_dtype dtype, dp_path path) {
-    if (!is16(dtype) || T <= 1 || d_in == 0 || d_out == 0 || B >= (int64_t(1) << 20)) return false;
+    if (is8(dtype) || T <= 1 || d_in == 0 || d_out == 0 || B >= (int64_t(1) << 20)) return false;
     if (gram_batchable(T, d_in, d_out, dtype, path) || gram_cols_class(B, T, d_in, d_out, dtype, path) != 0) return false;
     if (resolve_path(path, dtype, T, d_in, d_out) != DP_PATH_DIRECT) return false;
-    if (!dma_direct_joint_ok((int)B, (int)T, (int)d_in, (int)d_out)) return false;
+    if (!is16(dtype)) {
+        // float32: the layers whose direct norm runs on the copy-pipeline kernel (128 x 128 tiles as well)
+        if (B * T >= (int64_t(1) << 31)) return false;
+        const TnPlan p = plan_direct_f32((int)B, (int)T, (int)d_in, (int)d_out);
+        if (!p.dma) return false;
+    } else if (!dma_direct_joint_ok((int)B, (int)T, (int)d_in, (int)d_out)) return false;
     return B * direct_joint_tiles((int)d_in, (int)d_out) < (int64_t(1) << 24);       // 16 layers' items stay below the launch's 2^28
 }
 size_t single_layer_need(int64_t B, const dp_layer_desc& y, dp_dtype dtype, dp_path path) {
@@ -806,7 +811,8 @@ dp_status dp_layers_sqnorm_clip(const dp_layer_desc* layers, int64_t n_layers, i
                 part[k] = reinterpret_cast<float*>(static_cast<char*>(workspace) + ws_off);
                 ws_off += round16((size_t)B * tiles[k] * sizeof(float));
             }
-            const hipError_t e = launch_direct_bf16_dma_joint(sh, op, part, ng, (int)B, stream, dtype == DP_F16);
+            const hipError_t e = is16(dtype) ? launch_direct_bf16_dma_joint(sh, op, part, ng, (int)B, stream, dtype == DP_F16)
+                                             : launch_direct_f32_dma_joint(sh, op, part, ng, (int)B, stream);
             for (int k = 0; k < ng; ++k) { queue.partial[queue.count] = part[k]; queue.n[queue.count] = tiles[k]; ++queue.count; }
             ng = 0; group_bytes = 0;
             return e;

@@ -164,6 +164,8 @@ bool dma_joint_ragged_ok(int T, int M, int N);   // the same tiles, T not a mult
 size_t joint_workspace_floats(const JointShape* sh, int n_layers, int B, int geo = 1);
 // the same for float32 inputs (dp_tn_f32_dma.hip; 128 x 128 tiles, any T); A, G of JointOperands are float pointers
 size_t joint_f32_workspace_floats(const JointShape* sh, int n_layers, int B);
+hipError_t launch_direct_f32_dma_joint(const JointShape* sh, const JointOperands* op, float* const* partial, int n_layers,
+                                       int B, hipStream_t st);
 hipError_t launch_clipped_f32_dma_joint(const JointShape* sh, const JointOperands* op, int n_layers, int B, bool accumulate,
                                         float stddev, uint64_t seed, float* ws, hipStream_t st);
 // the same for 8-bit inputs (dp_tn_f8_dma.hip; 256 x 256 tiles, T a multiple of 64); A, G of JointOperands are byte pointers

@@ -261,6 +261,8 @@ struct F32JointArgs {
     F32JointLayer layer[kJointLayers];
     int n_layers, n_items, per_xcd;
 };
+// MODE 1: the layers' direct squared norms (a layer's "K slices" are its examples, `out` is partial[B][tiles])
+template <int MODE>
 __global__ __launch_bounds__(kThreads, 2) void k_tn_f32_dma_joint(F32JointArgs j) {
     const int L = (blockIdx.x & 7) * j.per_xcd + (blockIdx.x >> 3);
     if (L >= j.n_items) return;
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_tn_f32_dma_joint(F32JointArgs j
     a.K = y.K; a.T = y.T; a.M = y.M; a.N = y.N;
     a.tiles_m = y.tiles_m; a.tiles_n = y.tiles_n; a.splits = y.splits; a.kchunk = y.kchunk;
     a.per_xcd = 0; a.accumulate = y.accumulate;
-    tn_f32_dma_tile<0>(a, L - y.first_item);
+    tn_f32_dma_tile<MODE>(a, L - y.first_item);
 }
 
 // One slice length (in 16-row stages) for all layers of a joint launch, each layer rounding it to equal slices:
@@ -346,7 +348,7 @@ hipError_t launch_clipped_f32_dma_joint(const JointShape* sh, const JointOperand
     }
     for (int l = n_layers; l < kJointLayers; ++l) j.layer[l] = j.layer[0];
     j.n_layers = n_layers; j.n_items = (int)p.items; j.per_xcd = ceil_div(p.items, 8);
-    k_tn_f32_dma_joint<<<8u * (unsigned)j.per_xcd, kThreads, 0, st>>>(j);
+    k_tn_f32_dma_joint<0><<<8u * (unsigned)j.per_xcd, kThreads, 0, st>>>(j);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess || nf == 0) return e;
     f.n_layers = nf;
@@ -381,6 +383,30 @@ hipError_t launch_tn_f32_dma(int mode, const TnPlan& p, const float* A, const fl
     const unsigned grid = 8u * (unsigned)a.per_xcd;
     if (mode == 0) k_tn_f32_dma<0><<<grid, kThreads, 0, st>>>(a);
     else           k_tn_f32_dma<1><<<grid, kThreads, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+// Several layers' direct norms in one launch; partial[l]: the layer's [B][tiles of 128 x 128] sums of squares, to be
+// added by the caller.  Every layer: f32_dma_ok(T, M, N).
+hipError_t launch_direct_f32_dma_joint(const JointShape* sh, const JointOperands* op, float* const* partial, int n_layers,
+                                       int B, hipStream_t st) {
+    if (n_layers < 1 || n_layers > kJointLayers) return hipErrorInvalidValue;
+    F32JointArgs j;
+    int64_t first = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        F32JointLayer& y = j.layer[l];
+        y.A = reinterpret_cast<const float*>(op[l].A); y.G = reinterpret_cast<const float*>(op[l].G); y.clip = nullptr;
+        y.out = partial[l]; y.accumulate = 0;
+        y.K = B * sh[l].T; y.T = sh[l].T; y.M = sh[l].M; y.N = sh[l].N;
+        y.tiles_m = ceil_div(sh[l].M, TMF); y.tiles_n = ceil_div(sh[l].N, TNF);
+        y.splits = B; y.kchunk = sh[l].T;
+        y.first_item = (int)first;
+        first += (int64_t)y.tiles_m * y.tiles_n * B;
+    }
+    if (first >= (int64_t(1) << 28)) return hipErrorInvalidValue;
+    for (int l = n_layers; l < kJointLayers; ++l) j.layer[l] = j.layer[0];
+    j.n_layers = n_layers; j.n_items = (int)first; j.per_xcd = ceil_div(first, 8);
+    k_tn_f32_dma_joint<1><<<8u * (unsigned)j.per_xcd, kThreads, 0, st>>>(j);
     return hipGetLastError();
 }
 

@@ -1622,7 +1622,7 @@ def test_drawn_model_stacks_with_per_layer_clipping(dp, dtype, seed):
         assert fro_err(g.cpu().numpy(), want) <= FRO_TOL[dtype], (shapes[l], fro_err(g.cpu().numpy(), want))
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 def test_layers_sqnorm_direct_norms_share_a_launch(dp, dtype):
     """Aligned layers on the direct path share a copy-pipeline launch of 128 x 128 tiles in the several-layers call
     (ragged T, tiles that are mostly padding, one and several tiles), next to layers that run alone (an unaligned one,
@@ -1630,6 +1630,9 @@ def test_layers_sqnorm_direct_norms_share_a_launch(dp, dtype):
     B = 5
     shapes = [(160, 576, 64), (128, 64, 192), (200, 72, 328), (136, 72, 96), (256, 576, 128), (64, 1152, 128), (33, 27, 64), (1, 64, 10),
               (96, 256, 256)]
+    if dtype == "f32":      # the float32 copy-pipeline kernel: at least 256 positions, widths multiples of 4, tiles of 128
+        shapes = [(256, 576, 128), (300, 256, 124), (256, 384, 128), (272, 128, 252), (520, 120, 128), (260, 640, 256), (33, 27, 64),
+                  (1, 64, 10), (96, 256, 256)]
     layers = [wl.random_layer(11000 + i, B, T, di, do, dtype, a_dist="relu", g_row_scale=np.exp(np.linspace(-1, 1, B)))
               for i, (T, di, do) in enumerate(shapes)]
     s_ref = orc.total_sqnorm(layers)
