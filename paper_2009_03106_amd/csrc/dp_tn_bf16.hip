@@ -636,11 +636,12 @@ TnPlan plan_clipped_bf16(int B, int T, int M, int N) {
     p.tile_m = BM; p.tile_n = BN;
     p.tiles_m = ceil_div(M, BM); p.tiles_n = ceil_div(N, BN);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    // Every K slice beyond the first costs a write and a read of M*N floats: a short contraction into a large
-    // matrix (a few examples of a few positions, thousands of columns) is bound by its output, and slices to fill
-    // the chip would multiply exactly that.  The slices' traffic stays below the bytes of the inputs.
+    // Every K slice beyond the first costs a write and a read of M*N floats.  Where that outweighs the inputs (a short
+    // contraction into a large matrix: a few examples of a few positions, thousands of columns), the layer is bound
+    // by its output and slices of a few stages to fill the chip multiply exactly that: slices of at least 16 stages
+    // there (a long contraction still gains more from the parallel slices than their traffic costs).
     const int64_t in_bytes = (int64_t)B * T * ((int64_t)M + N) * 2;
-    int64_t traffic_cap = in_bytes / ((int64_t)M * N * 8);
+    int64_t traffic_cap = (int64_t)M * N * 8 > in_bytes ? (int64_t)B * T / (16 * BK) : (int64_t(1) << 40);
     if (traffic_cap < 1) traffic_cap = 1;
     p.big = big_ok(T, M, N);
     if (p.big) {
