@@ -364,7 +364,12 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
  * of padding up to the next multiple of 32 (e.g. 784, 196, 1024), and a
  * [d_in, d_out] that tiles into 256 x 256, 192 x 128 or 128 x 128 blocks with at
  * most a quarter of padding; anything else is DP_ERR_UNSUPPORTED (unfold and use the
- * general entry points).  workspace: at least dp_conv_workspace_bytes(...). */
+ * general entry points).  workspace: at least dp_conv_workspace_bytes(...).
+ * 3 x 3 kernels with C a multiple of 64, T a multiple of 32 and a padded image
+ * row of at most about 100 pixels run on a kernel of their own that keeps the
+ * padded image rows in LDS and fetches every pixel once instead of once per
+ * tap (dp_conv_rows_resident tells); its results are those of the general
+ * entry points up to the order of the float32 sums. */
 dp_status dp_conv_sqnorm(const void* X, const void* G,
                          int64_t B, int64_t H, int64_t W, int64_t C,
                          int64_t KH, int64_t KW, int64_t pad, int64_t d_out,
@@ -379,6 +384,13 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip,
  * invalid or unsupported arguments. */
 size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_t C,
                                int64_t KH, int64_t KW, int64_t pad, int64_t d_out, dp_dtype dtype);
+/* Test hook: 1 when the two calls above run this geometry on the kernel that
+ * keeps the image rows in LDS (then they equal the general entry points on the
+ * unfolded matrix up to float32 summation order), 0 when they run the general
+ * kernels with implicit unfolding (then bit for bit), -1 for invalid or
+ * unsupported arguments. */
+int dp_conv_rows_resident(int64_t B, int64_t H, int64_t W, int64_t C,
+                          int64_t KH, int64_t KW, int64_t pad, int64_t d_out, dp_dtype dtype);
 
 /* Gaussian mechanism (Section 2, Gaussian-mechanism lemma; Algorithm 1, the
  * update line): grad[j] += stddev * z[offset + j], j in [0, n), with z an

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdpclip.so")
 
-SOURCES = ["dp_api.hip", "dp_small_kernels.hip", "dp_bias.hip", "dp_tn_bf16.hip", "dp_tn_bf16_dma.hip", "dp_tn_f32.hip", "dp_tn_f32_dma.hip", "dp_gram_bf16.hip", "dp_gram_cols.hip", "dp_gram_bf16_dma.hip", "dp_gram_f32.hip", "dp_tn_f8_dma.hip", "dp_probes.hip"]
+SOURCES = ["dp_api.hip", "dp_small_kernels.hip", "dp_bias.hip", "dp_tn_bf16.hip", "dp_tn_bf16_dma.hip", "dp_tn_f32.hip", "dp_tn_f32_dma.hip", "dp_gram_bf16.hip", "dp_gram_cols.hip", "dp_conv_rows.hip", "dp_gram_bf16_dma.hip", "dp_gram_f32.hip", "dp_tn_f8_dma.hip", "dp_probes.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

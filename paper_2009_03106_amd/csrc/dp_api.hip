@@ -503,7 +503,16 @@ size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_
         const size_t inner = dp_conv_workspace_bytes(op, B, H, W, C, KH, KW, pad, d_out, DP_F16);
         return inner == 0 ? 0 : widen_bytes(B * H * W * C) + widen_bytes(B * T * d_out) + inner;
     }
-    if (!is16(dtype) || !dma_conv_ok(g, (int)d_out)) return 0;
+    if (!is16(dtype)) return 0;
+    if (conv_rows_ok(g, (int)d_out, (int)B)) {
+        if (op == DP_OP_SQNORM) return kConvZeroBytes + (size_t)B * conv_rows_tiles(g, (int)d_out) * sizeof(float);
+        if (op == DP_OP_CLIPPED_GRAD) {
+            const int splits = conv_rows_splits(g, (int)d_out, (int)B);
+            return kConvZeroBytes + (splits <= 1 ? 0 : (size_t)splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float));
+        }
+        return 0;
+    }
+    if (!dma_conv_ok(g, (int)d_out)) return 0;
     if (op == DP_OP_SQNORM) {
         const TnPlan p = plan_direct_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
         return kConvZeroBytes + (size_t)B * p.tiles_m * p.tiles_n * sizeof(float);
@@ -513,6 +522,15 @@ size_t dp_conv_workspace_bytes(dp_op op, int64_t B, int64_t H, int64_t W, int64_
         return kConvZeroBytes + (p.splits <= 1 ? 0 : (size_t)p.splits * (size_t)splitk_slice_elems(d_in * d_out) * sizeof(float));
     }
     return 0;
+}
+
+int dp_conv_rows_resident(int64_t B, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW, int64_t pad, int64_t d_out,
+                          dp_dtype dtype) {
+    ConvGeom g; int64_t T, d_in;
+    if (conv_geometry(B, H, W, C, KH, KW, pad, d_out, dtype, &g, &T, &d_in) != DP_OK) return -1;
+    if (!(is16(dtype) || is8(dtype)) || B == 0 || T == 0 || d_in == 0 || d_out == 0) return -1;
+    if (conv_rows_ok(g, (int)d_out, (int)B)) return 1;
+    return dma_conv_ok(g, (int)d_out) ? 0 : -1;
 }
 
 dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW,
@@ -528,7 +546,8 @@ dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int
         if (!accumulate && launch_fill_zero(sqnorm, B, stream) != hipSuccess) return DP_ERR_HIP;
         return DP_OK;
     }
-    if (!(is16(dtype) || is8(dtype)) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    const bool rows = conv_rows_ok(g, (int)d_out, (int)B);
+    if (!(is16(dtype) || is8(dtype)) || !(rows || dma_conv_ok(g, (int)d_out))) return DP_ERR_UNSUPPORTED;
     if (!X || !G || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
     if (is8(dtype)) {
         const size_t nx = widen_bytes(B * H * W * C), ng = widen_bytes(B * T * d_out);
@@ -546,6 +565,12 @@ dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int
     float* zero = static_cast<float*>(workspace);
     float* partial = zero + kConvZeroBytes / sizeof(float);
     if (launch_fill_zero(zero, kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+    if (rows) {
+        const hipError_t er = launch_direct_conv_rows(g, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), (int)B,
+                                                      (int)d_out, accumulate != 0, sqnorm, partial, stream,
+                                                      reinterpret_cast<const uint16_t*>(zero), dtype == DP_F16);
+        return er == hipSuccess ? DP_OK : DP_ERR_HIP;
+    }
     const TnPlan p = plan_direct_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
     const hipError_t e = launch_direct_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), (int)B, (int)T,
                                                 (int)d_in, (int)d_out, accumulate != 0, sqnorm, partial, stream, &g,
@@ -566,7 +591,8 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, 
         if (!accumulate && launch_fill_zero(grad, d_in * d_out, stream) != hipSuccess) return DP_ERR_HIP;
         return DP_OK;
     }
-    if (!(is16(dtype) || is8(dtype)) || !dma_conv_ok(g, (int)d_out)) return DP_ERR_UNSUPPORTED;
+    const bool rows = conv_rows_ok(g, (int)d_out, (int)B);
+    if (!(is16(dtype) || is8(dtype)) || !(rows || dma_conv_ok(g, (int)d_out))) return DP_ERR_UNSUPPORTED;
     if (!X || !G || !clip || !aligned16(X) || !aligned16(G)) return DP_ERR_INVALID_ARG;
     if (is8(dtype)) {
         const size_t nx = widen_bytes(B * H * W * C), ng = widen_bytes(B * T * d_out);
@@ -583,6 +609,12 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, 
     float* zero = static_cast<float*>(workspace);
     float* ws = zero + kConvZeroBytes / sizeof(float);
     if (launch_fill_zero(zero, kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+    if (rows) {
+        const hipError_t er = launch_clipped_conv_rows(g, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), clip,
+                                                       (int)B, (int)d_out, accumulate != 0, grad, ws, stream,
+                                                       reinterpret_cast<const uint16_t*>(zero), dtype == DP_F16, nullptr);
+        return er == hipSuccess ? DP_OK : DP_ERR_HIP;
+    }
     const TnPlan p = plan_clipped_bf16_dma((int)B, (int)T, (int)d_in, (int)d_out);
     const hipError_t e = launch_clipped_bf16_dma(p, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), clip, (int)B,
                                                  (int)T, (int)d_in, (int)d_out, accumulate != 0, grad, ws, stream, &g,

@@ -97,6 +97,11 @@ TnPlan plan_direct_bf16(int B, int T, int M, int N);
 // stride-1 convolution given by its channels-last input image (implicit unfolding in the copy-pipeline kernel)
 struct ConvGeom { int H, W, C, KH, KW, pad; };
 bool dma_conv_ok(const ConvGeom& g, int d_out);
+// 3 x 3 kernels over at least 64 channels (a multiple of 64), a multiple of 32 output positions: the kernel that keeps
+// the image rows in LDS and copies every pixel once (dp_conv_rows.hip)
+bool conv_rows_ok(const ConvGeom& g, int d_out, int B);
+int conv_rows_tiles(const ConvGeom& g, int d_out);              // partial sums per example of the direct norm
+int conv_rows_splits(const ConvGeom& g, int d_out, int B);      // K slices of the clipped sum
 bool dma_clipped_ok(int B, int T, int M, int N);
 // flat: the rows of A lie in memory as they are (not the implicit unfolding of an image)
 TnPlan plan_clipped_bf16_dma(int B, int T, int M, int N, bool flat = false);
@@ -118,6 +123,12 @@ hipError_t launch_clipped_bf16(const TnPlan& p, const uint16_t* A, const uint16_
 hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uint16_t* G, const float* clip,
                                    int B, int T, int M, int N, bool accumulate, float* grad, float* ws, hipStream_t st,
                                    const ConvGeom* cg, const uint16_t* zero, bool f16, const NoiseArgs* noise);
+hipError_t launch_direct_conv_rows(const ConvGeom& g, const uint16_t* X, const uint16_t* G, int B, int N, bool accumulate,
+                                   float* sqnorm, float* partial, hipStream_t st, const uint16_t* zero, bool f16,
+                                   const ClipOut* co = nullptr);
+hipError_t launch_clipped_conv_rows(const ConvGeom& g, const uint16_t* X, const uint16_t* G, const float* clip, int B, int N,
+                                    bool accumulate, float* grad, float* ws, hipStream_t st, const uint16_t* zero, bool f16,
+                                    const NoiseArgs* noise);
 // Several layers' clipped sums in one launch (16-bit inputs, 256 x 256 tiles, T a multiple of 32): the K slices of all
 // layers are cut to about one length so that the launch fills the chip a whole number of times; the layers' slices
 // are then folded (+ noise) by the split-K reduce kernel as after a launch per layer.  Same arithmetic per slice and

@@ -24,7 +24,7 @@ _PATHS = {"auto": DP_PATH_AUTO, "gram": DP_PATH_GRAM, "direct": DP_PATH_DIRECT}
 
 EXPORTS = ("dp_layer_sqnorm", "dp_layer_sqnorm_static", "dp_layers_sqnorm", "dp_layers_sqnorm_clip", "dp_layers_workspace_bytes", "dp_layers_clipped_grad",
            "dp_layers_clipped_grad_noise", "dp_layers_step", "dp_layers_clipped_workspace_bytes", "dp_clip_factors", "dp_clipped_grad", "dp_bias_sqnorm", "dp_clipped_bias_grad", "dp_layernorm_sqnorm",
-           "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw",
+           "dp_conv_sqnorm", "dp_conv_clipped_grad", "dp_conv_workspace_bytes", "dp_conv_rows_resident", "dp_add_noise", "dp_workspace_bytes", "dp_choose_path", "dp_status_string", "dp_philox_raw",
            "dp_clipped_grad_rounds_inputs")
 
 # the measurement probes of include/dpclip_probes.h
@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
     lib.dp_conv_clipped_grad.restype = ci
     lib.dp_conv_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, i64, i64, i64, i64, ci]
     lib.dp_conv_workspace_bytes.restype = sz
+    lib.dp_conv_rows_resident.argtypes = [i64, i64, i64, i64, i64, i64, i64, i64, ci]
+    lib.dp_conv_rows_resident.restype = ci
     lib.dp_add_noise.argtypes = [vp, i64, f32, u64, u64, vp]
     lib.dp_add_noise.restype = ci
     lib.dp_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci, ci]
@@ -535,6 +537,14 @@ def _conv_args(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int):
 
 def conv_workspace_bytes(op: int, B: int, H: int, W: int, C: int, KH: int, KW: int, pad: int, d_out: int, dtype: int) -> int:
     return int(load_library().dp_conv_workspace_bytes(op, B, H, W, C, KH, KW, pad, d_out, dtype))
+
+
+def conv_rows_resident(B: int, H: int, W: int, C: int, KH: int, KW: int, pad: int, d_out: int, dtype: int) -> bool:
+    """Test hook: whether the convolution calls run this geometry on the kernel that keeps the image rows in LDS."""
+    r = load_library().dp_conv_rows_resident(B, H, W, C, KH, KW, pad, d_out, dtype)
+    if r < 0:
+        raise ValueError("invalid or unsupported arguments")
+    return bool(r)
 
 
 def conv_sqnorm(X: torch.Tensor, G: torch.Tensor, KH: int, KW: int, pad: int, sqnorm: Optional[torch.Tensor] = None, *,

@@ -1048,6 +1048,13 @@ CONV_GEOMS = [
     (2, 9, 9, 32, 2, 2, 0, 128),        # 2 x 2 kernel, d_in = 128 (128 x 128 tiles)
     (3, 28, 28, 64, 3, 3, 1, 128),      # 784 output positions: not a multiple of the 32-position stage
     (2, 14, 14, 64, 3, 3, 1, 128),      # 196 positions
+    # 3 x 3 kernels over multiples of 64 channels and of 32 positions: the kernel that keeps the image rows in LDS
+    (5, 16, 16, 128, 3, 3, 1, 72),      # two channel groups, ragged d_out (two column tiles, the second of 8 columns)
+    (70, 16, 16, 64, 3, 3, 1, 64),      # K slices of several examples
+    (3, 8, 64, 64, 3, 3, 1, 64),        # long rows (11 copy units per padded row), W_out = 2 stages
+    (2, 16, 98, 64, 3, 3, 1, 40),       # the widest padded row that fits (100 pixels); W_out = 98 splits stages unevenly
+    (4, 18, 12, 192, 3, 3, 0, 136),     # no padding, W_out = 10, three channel groups, three column tiles
+    (3, 6, 18, 64, 3, 3, 2, 64),        # two rings of zeros around the image
 ]
 
 
@@ -1072,13 +1079,25 @@ def test_conv_from_image(dp, B, H, W, C, KH, KW, pad, d_out):
     g2 = torch.ones_like(g)
     dp.conv_clipped_grad(Xd, Gd, c, KH, KW, pad, g2, accumulate=True)
     assert fro_err(g2.cpu().numpy() - 1.0, g_ref) <= FRO_TOL["bf16"]
-    # the same layer through the general entry points on the unfolded patch matrix (same kernels, same order)
     Ad = to_dev(wl.f32_to_bf16_bits(A.astype(np.float32)))
-    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
-    np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
+    if dp.conv_rows_resident(B, H, W, C, KH, KW, pad, d_out, dp.DP_BF16):
+        # a kernel of its own that scales in float32: held to that accuracy, element by element
+        assert KH == 3 and KW == 3 and C % 64 == 0
+        for pattern in (c.cpu().numpy(), np.ones(B, np.float32)):
+            gp = dp.conv_clipped_grad(Xd, Gd, torch.from_numpy(pattern).cuda(), KH, KW, pad)
+            err = np.abs(gp.cpu().numpy().astype(np.float64) - orc.clipped_grad(A, G, pattern.astype(np.float64)))
+            scale = orc.clipped_grad(np.abs(orc.widen(A)), np.abs(orc.widen(G)), np.abs(pattern.astype(np.float64)))
+            assert np.all(err <= ELEM_TIGHT * scale + 1e-30 * scale.max()), float(np.max(err / (scale + 1e-300)))
+            assert fro_err(gp.cpu().numpy(), orc.clipped_grad(A, G, pattern.astype(np.float64))) <= FRO_TIGHT
+    else:
+        # the same layer through the general entry points on the unfolded patch matrix (same kernels, same order)
+        assert not (KH == 3 and KW == 3 and C % 64 == 0 and G.shape[1] % 32 == 0)
+        np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
+        np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
 
 
-@pytest.mark.parametrize("B,H,W,C,KH,KW,pad,d_out", [CONV_GEOMS[0], CONV_GEOMS[1], CONV_GEOMS[3], CONV_GEOMS[6]])
+@pytest.mark.parametrize("B,H,W,C,KH,KW,pad,d_out", [CONV_GEOMS[0], CONV_GEOMS[1], CONV_GEOMS[3], CONV_GEOMS[6], CONV_GEOMS[8],
+                                                     CONV_GEOMS[12]])
 def test_conv_from_image_fp16(dp, B, H, W, C, KH, KW, pad, d_out):
     """fp16 images and gradients (G carries a loss scale of 1024) through the implicit unfolding."""
     spec, X, G = wl.generate_conv_image(B=B, H=H, W=W, C=C, KH=KH, KW=KW, pad=pad, d_out=d_out,
@@ -1095,8 +1114,11 @@ def test_conv_from_image_fp16(dp, B, H, W, C, KH, KW, pad, d_out):
     g = dp.conv_clipped_grad(Xd, Gd, c, KH, KW, pad)
     assert fro_err(g.cpu().numpy(), g_ref) <= FRO_TOL["f16"], fro_err(g.cpu().numpy(), g_ref)
     Ad = to_dev(A.astype(np.float16))                 # exact: the patches are copies of fp16 values
-    np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
-    np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
+    if dp.conv_rows_resident(B, H, W, C, KH, KW, pad, d_out, dp.DP_F16):
+        check_clipped_sum(dp, A.astype(np.float16), G, c.cpu().numpy(), g.cpu().numpy(), "f16", ("conv f16", H, W, C))
+    else:
+        np.testing.assert_array_equal(dp.layer_sqnorm(Ad, Gd, path="direct").cpu().numpy(), s.cpu().numpy())
+        np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
 
 
 def test_conv_unsupported_geometries_fail_loudly(dp):
