@@ -562,9 +562,13 @@ dp_status dp_conv_sqnorm(const void* X, const void* G, int64_t B, int64_t H, int
     const size_t need = dp_conv_workspace_bytes(DP_OP_SQNORM, B, H, W, C, KH, KW, pad, d_out, dtype);
     if (need >= (size_t(1) << 33)) return DP_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
-    float* zero = static_cast<float*>(workspace);
-    float* partial = zero + kConvZeroBytes / sizeof(float);
-    if (launch_fill_zero(zero, kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+    // the line of zeros for the padding: the one in the device image, else the head of the workspace
+    const float* zero = static_cast<const float*>(device_zero_line(stream));
+    float* partial = static_cast<float*>(workspace) + kConvZeroBytes / sizeof(float);
+    if (!zero) {
+        if (launch_fill_zero(static_cast<float*>(workspace), kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+        zero = static_cast<const float*>(workspace);
+    }
     if (rows) {
         const hipError_t er = launch_direct_conv_rows(g, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), (int)B,
                                                       (int)d_out, accumulate != 0, sqnorm, partial, stream,
@@ -606,9 +610,12 @@ dp_status dp_conv_clipped_grad(const void* X, const void* G, const float* clip, 
     }
     const size_t need = dp_conv_workspace_bytes(DP_OP_CLIPPED_GRAD, B, H, W, C, KH, KW, pad, d_out, dtype);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DP_ERR_WORKSPACE;
-    float* zero = static_cast<float*>(workspace);
-    float* ws = zero + kConvZeroBytes / sizeof(float);
-    if (launch_fill_zero(zero, kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+    const float* zero = static_cast<const float*>(device_zero_line(stream));
+    float* ws = static_cast<float*>(workspace) + kConvZeroBytes / sizeof(float);
+    if (!zero) {
+        if (launch_fill_zero(static_cast<float*>(workspace), kConvZeroBytes / sizeof(float), stream) != hipSuccess) return DP_ERR_HIP;
+        zero = static_cast<const float*>(workspace);
+    }
     if (rows) {
         const hipError_t er = launch_clipped_conv_rows(g, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(G), clip,
                                                        (int)B, (int)d_out, accumulate != 0, grad, ws, stream,

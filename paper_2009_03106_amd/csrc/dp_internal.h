@@ -61,6 +61,10 @@ struct FoldLayers {
 };
 hipError_t launch_splitk_reduce_layers(FoldLayers& f, bool accumulate, hipStream_t st, float stddev, uint64_t seed);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+// kZeroHeadFloats floats of zeros that live in the device image of the current GPU (nothing to fill, no launch), or
+// nullptr when they cannot be looked up now (first use on this GPU while `st` is being captured): the caller then
+// fills the head of its workspace as before.
+const void* device_zero_line(hipStream_t st);
 // dst[j] = fp16 bits of the 8-bit float src[j] (e4m3, or e5m2 when e5m2 is set), exact
 hipError_t launch_widen_f8(const void* src, uint16_t* dst, int64_t n, bool e5m2, hipStream_t st);
 hipError_t launch_add_noise(float* grad, int64_t n, float stddev, uint64_t seed, uint64_t offset, hipStream_t st);

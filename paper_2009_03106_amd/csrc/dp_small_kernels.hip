@@ -3,6 +3,7 @@
 #include "dp_common.h"
 #include "dp_internal.h"
 #include "dp_noise.h"
+#include <atomic>
 
 namespace dpk {
 
@@ -608,6 +609,27 @@ hipError_t launch_widen_f8(const void* src, uint16_t* dst, int64_t n, bool e5m2,
     if (e5m2) k_widen_f8<true><<<(unsigned)blocks, 256, 0, st>>>(static_cast<const unsigned char*>(src), dst, n);
     else      k_widen_f8<false><<<(unsigned)blocks, 256, 0, st>>>(static_cast<const unsigned char*>(src), dst, n);
     return hipGetLastError();
+}
+
+// A line of zeros in the device image (never written), one copy per GPU: what the copy-pipeline kernels read where a
+// stage reaches past an example's rows or into the padding of an image.  In host code the array's name is only a
+// handle for the lookup.
+static __device__ __align__(256) unsigned char zero_line[kZeroHeadFloats * sizeof(float)];
+
+const void* device_zero_line(hipStream_t st) {
+    constexpr int kDevices = 64;
+    static std::atomic<void*> cache[kDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kDevices) return nullptr;
+    void* p = cache[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    // the first lookup on a device may load the code object: not while the caller's stream is being captured
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    if (cs != hipStreamCaptureStatusNone) return nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(zero_line)) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+    cache[dev].store(p, std::memory_order_release);
+    return p;
 }
 
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {

@@ -588,9 +588,12 @@ hipError_t launch_clipped_bf16_dma(const TnPlan& p, const uint16_t* A, const uin
     int am = cg ? 1 : 0;
     if (!cg && p.zero_head) {
         // ragged T: the head of the workspace is the line of zeros
-        const hipError_t ez = launch_fill_zero(ws, kZeroHeadFloats, st);
-        if (ez != hipSuccess) return ez;
-        zero = reinterpret_cast<const uint16_t*>(ws);
+        zero = static_cast<const uint16_t*>(device_zero_line(st));
+        if (!zero) {
+            const hipError_t ez = launch_fill_zero(ws, kZeroHeadFloats, st);
+            if (ez != hipSuccess) return ez;
+            zero = reinterpret_cast<const uint16_t*>(ws);
+        }
         ws += kZeroHeadFloats;
         am = 2;
     }
@@ -805,9 +808,12 @@ hipError_t launch_direct_bf16_dma(const TnPlan& p, const uint16_t* A, const uint
                                   const ConvGeom* cg, const uint16_t* zero, bool f16, const ClipOut* co) {
     int am = cg ? 1 : 0;
     if (!cg && p.zero_head) {
-        const hipError_t ez = launch_fill_zero(partial, kZeroHeadFloats, st);
-        if (ez != hipSuccess) return ez;
-        zero = reinterpret_cast<const uint16_t*>(partial);
+        zero = static_cast<const uint16_t*>(device_zero_line(st));
+        if (!zero) {
+            const hipError_t ez = launch_fill_zero(partial, kZeroHeadFloats, st);
+            if (ez != hipSuccess) return ez;
+            zero = reinterpret_cast<const uint16_t*>(partial);
+        }
         partial += kZeroHeadFloats;
         am = 2;
     }

@@ -466,9 +466,12 @@ hipError_t launch_clipped_f8_dma(const TnPlan& p, const void* A, const void* G, 
     a.zero = nullptr;
     if (p.zero_head) {
         // ragged T: the head of the workspace is the line of zeros
-        const hipError_t ez = launch_fill_zero(ws, kZeroHeadFloats, st);
-        if (ez != hipSuccess) return ez;
-        a.zero = reinterpret_cast<const unsigned char*>(ws);
+        a.zero = static_cast<const unsigned char*>(device_zero_line(st));
+        if (!a.zero) {
+            const hipError_t ez = launch_fill_zero(ws, kZeroHeadFloats, st);
+            if (ez != hipSuccess) return ez;
+            a.zero = reinterpret_cast<const unsigned char*>(ws);
+        }
         ws += kZeroHeadFloats;
     }
     a.A = static_cast<const unsigned char*>(A); a.G = static_cast<const unsigned char*>(G); a.clip = clip;
@@ -559,9 +562,12 @@ hipError_t launch_direct_f8_dma(const TnPlan& p, const void* A, const void* G, i
     Dma8Args a;
     a.zero = nullptr;
     if (p.zero_head) {
-        const hipError_t ez = launch_fill_zero(partial, kZeroHeadFloats, st);
-        if (ez != hipSuccess) return ez;
-        a.zero = reinterpret_cast<const unsigned char*>(partial);
+        a.zero = static_cast<const unsigned char*>(device_zero_line(st));
+        if (!a.zero) {
+            const hipError_t ez = launch_fill_zero(partial, kZeroHeadFloats, st);
+            if (ez != hipSuccess) return ez;
+            a.zero = reinterpret_cast<const unsigned char*>(partial);
+        }
         partial += kZeroHeadFloats;
     }
     a.A = static_cast<const unsigned char*>(A); a.G = static_cast<const unsigned char*>(G); a.clip = nullptr;
