@@ -172,6 +172,14 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { accP[i][j][r] = 0.f; accQ[i][j][r] = 0.f; }
+    // A diagonal pair is symmetric: the 64 x 64 block of wave (0, 1) is the transpose of wave (1, 0)'s, and inside the
+    // blocks of waves (0, 0) and (1, 1) the 32 x 32 block (0, 1) is the transpose of block (1, 0).  The upper ones are
+    // not computed (wave (0, 1) issues no MFMA and reads no fragment, it only copies and keeps the barriers) and the
+    // lower ones count twice: 10 of the 16 MFMAs of a k step.  (Letting waves (0, 0) and (1, 1) also use their t
+    // fragments as s fragments, two LDS reads fewer per k step, made the kernel 50 % slower: a second MFMA sequence
+    // on other registers in the pipelined loop.)
+    const bool skip_wave = __builtin_amdgcn_readfirstlane((int)(diag && wm < wn)) != 0;
+    const bool skip_upper = __builtin_amdgcn_readfirstlane((int)(diag && wm == wn)) != 0;
 
     // ---- BIAS: operands of the column sums.  Wave w takes rows 32 w .. 32 w + 31 of the t-tile as two 16-row k steps.
     const bool do_bias = BIAS && diag && ly.upart != nullptr;
@@ -223,6 +231,7 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     // MFMAs of the current one run, also across the stage boundary; the stage barrier sits in front of the
     // last k step of a stage, when every wave has retired its reads of that stage.
     auto read_kstep = [&](bf16x8 (&f)[4], int buf, int ks) {
+        if (skip_wave) return;
         const unsigned char* sb = lds + buf * GSTAGE;
         // chunk (2 ks + lhalf) ^ swz == (lhalf ^ swz) ^ (2 ks): flip bits 5-6 of the byte offset
 #pragma unroll
@@ -231,11 +240,11 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
         for (int j = 0; j < 2; ++j) f[2 + j] = *reinterpret_cast<const bf16x8*>(sb + (rd_s[j] ^ (ks << 5)));
     };
     auto mfma_kstep = [&](const bf16x8 (&f)[4], f32x16 (&acc)[2][2]) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = In16<F16>::mfma(f[i], f[2 + j], acc[i][j]);
+        if (skip_wave) return;
+        acc[0][0] = In16<F16>::mfma(f[0], f[2], acc[0][0]);
+        acc[1][0] = In16<F16>::mfma(f[1], f[2], acc[1][0]);
+        acc[1][1] = In16<F16>::mfma(f[1], f[3], acc[1][1]);
+        if (!skip_upper) acc[0][1] = In16<F16>::mfma(f[0], f[3], acc[0][1]);
     };
     bf16x8 f[2][4];
     // wait until at most `stages` later stages' copies are outstanding (4 per wave and stage on a diagonal pair, else 8)
@@ -299,6 +308,7 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
     // operands agree, and they are read the same way.
     v8i32 f8[2][4];
     auto read_k8 = [&](v8i32 (&g)[4], int buf, int K) {
+        if (skip_wave) return;
         const unsigned char* sb = lds + buf * GSTAGE;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -321,10 +331,12 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
                 if (st + GNST < n_stages) issue(st + GNST, st % GNST);
                 read_k8(f8[0], (st + 1) % GNST, 0);
             }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma8<F>(f8[K][i], f8[K][2 + j], acc[i][j]);
+            if (!skip_wave) {
+                acc[0][0] = mfma8<F>(f8[K][0], f8[K][2], acc[0][0]);
+                acc[1][0] = mfma8<F>(f8[K][1], f8[K][2], acc[1][0]);
+                acc[1][1] = mfma8<F>(f8[K][1], f8[K][3], acc[1][1]);
+                if (!skip_upper) acc[0][1] = mfma8<F>(f8[K][0], f8[K][3], acc[0][1]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -355,7 +367,8 @@ __global__ __launch_bounds__(kThreads, GNST * GSTAGE <= 65536 ? 2 : 1) void k_gr
             for (int r = 0; r < 16; ++r) {
                 const int row = tt * GT + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
                 const float v = accP[i][j][r] * accQ[i][j][r];
-                s += (row < ly.T && col < ly.T) ? v : 0.f;
+                const float wgt = !diag ? 1.f : wm > wn ? 2.f : (i == j ? 1.f : i > j ? 2.f : 0.f);   // skipped blocks hold zeros
+                s += (row < ly.T && col < ly.T) ? wgt * v : 0.f;
             }
         }
     __syncthreads();
