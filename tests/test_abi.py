@@ -246,3 +246,28 @@ def test_missing_library_raises(monkeypatch):
     monkeypatch.setattr(dpclip, "LIB_PATH", "/nonexistent/libdpclip.so")
     with pytest.raises(RuntimeError):
         dpclip.load_library()
+
+
+def test_conv_rows_resident_host_logic(lib):
+    """Host logic only: which convolution geometries the image-rows-in-LDS kernel takes (3 x 3, C a multiple of 64,
+    T a multiple of 32, a padded row that fits its copy table), and that the workspace query follows the choice."""
+    q = dpclip.conv_rows_resident
+    bf = dpclip.DP_BF16
+    assert q(128, 32, 32, 64, 3, 3, 1, 128, bf) is True             # the convolution configuration
+    assert q(128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F16) is True
+    assert q(128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F8_E4M3) is True      # widened to fp16 first
+    assert q(2, 16, 98, 64, 3, 3, 1, 40, bf) is True                # 100-pixel padded row: the widest that fits
+    assert q(3, 28, 28, 64, 3, 3, 1, 128, bf) is False              # 784 positions: general kernel
+    assert q(2, 8, 16, 64, 5, 5, 2, 120, bf) is False               # 5 x 5
+    assert q(2, 9, 9, 32, 2, 2, 0, 128, bf) is False                # 32 channels
+    assert q(2, 16, 128, 64, 3, 3, 1, 128, bf) is False             # 130-pixel padded row: general kernel
+    for bad in ((2, 8, 8, 12, 3, 3, 1, 64, bf), (2, 6, 6, 64, 3, 3, 1, 128, bf), (2, 8, 8, 64, 3, 3, 1, 64, dpclip.DP_F32),
+                (-1, 8, 8, 64, 3, 3, 1, 64, bf), (2, 1, 1, 64, 3, 3, 0, 64, bf)):
+        with pytest.raises(ValueError):
+            q(*bad)
+    # workspace: a line of zeros + one float per (example, 576-row x 64-column tile) for the norm
+    assert dpclip.conv_workspace_bytes(dpclip.DP_OP_SQNORM, 128, 32, 32, 64, 3, 3, 1, 128, bf) == 256 + 128 * 2 * 4
+    assert dpclip.conv_workspace_bytes(dpclip.DP_OP_SQNORM, 5, 16, 16, 128, 3, 3, 1, 72, bf) == 256 + 5 * 4 * 4
+    # clipped sum: whole float32 slices of the 576 x 128 gradient
+    w = dpclip.conv_workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 128, 32, 32, 64, 3, 3, 1, 128, bf)
+    assert (w - 256) % (576 * 128 * 4) == 0 and w > 256
