@@ -300,9 +300,10 @@ dp_status dp_clip_factors(const float* sqnorm, int64_t B, float C,
  * clip[i] == 0 leaves example i out (finite inputs): masked examples, and the
  * factor that dp_clip_factors gives a norm that overflowed, are safe.  The
  * kernels that scale accumulators keep their running sum in units of the
- * current example's factor: a factor so far below its predecessor that their
- * ratio overflows float32 counts as 0 there, and factors that differ by more
- * than about 30 orders of magnitude inside one call can overflow the sum. */
+ * current example's factor, which must stay in the float32 range: a factor
+ * below 2^-40 (about 1e-12) of the largest earlier factor of the same K slice
+ * (up to 64 consecutive examples) counts as 0 there.  Such a term is below the
+ * float32 resolution of a sum in which the larger one takes part. */
 dp_status dp_clipped_grad(const void* A, const void* G, const float* clip,
                           int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                           dp_dtype dtype, int accumulate, float* grad,

@@ -333,6 +333,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
     if (MODE == 0) vclip = a.clip[min(ex0 + lane, a.B - 1)];
     float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
     bool skip = false;
+    float c_ref = c_cur;                            // the largest factor accumulated so far
 
     __builtin_amdgcn_s_barrier();                   // stage 0 has landed
     px_[0] = px_[1] = 0; roff[0] = roff[1] = 0;
@@ -356,7 +357,9 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
             // first stage of the next example: the tile holds (1 / c_cur) * sum, move it to the new unit
             const float c_next = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), e));
             const float ratio = c_cur / c_next;
-            skip = __builtin_isinf(ratio);          // a zero factor after a non-zero one: the example is left out
+            // a zero factor, or one below 2^-40 of the largest so far (the tile in that unit would leave the float32
+            // range), after a non-zero one: the example is left out
+            skip = __builtin_isinf(ratio) || c_next < c_ref * 0x1p-40f;
             if (c_next != c_cur && !skip) {
 #pragma unroll
                 for (int t = 0; t < TAPS; ++t)
@@ -365,7 +368,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) acc[t][jn][r] *= ratio;
             }
-            if (!skip) c_cur = c_next;
+            if (!skip) { c_cur = c_next; c_ref = fmaxf(c_ref, c_next); }
         }
         int ne = e, nsub = sub + 1;
         if (nsub == spe) { nsub = 0; ++ne; }

@@ -26,10 +26,12 @@
 // example: T % 32 == 0, or the ragged mode below, which pads every example
 // with rows of zeros.  K slices are arbitrary ranges of stages.
 // An example whose factor is zero (a masked example, or the factor that
-// dp_clip_factors gives an overflowed norm), or so far below the tile's
-// current unit that c_cur / c_next is not finite in fp32, cannot become the
-// unit: its MFMAs are skipped instead and the unit stays, i.e. the example
-// counts with factor 0, as the weighted sum defines for a zero factor.
+// dp_clip_factors gives an overflowed norm), or below 2^-40 of the largest
+// factor the K slice has accumulated so far, cannot become the unit (the tile
+// in that unit, sum / c_next, would leave the float32 range): its MFMAs are
+// skipped instead and the unit stays, i.e. the example counts with factor 0,
+// as the weighted sum defines for a zero factor; a factor 10^12 times below
+// another one of the same sum is below that sum's float32 resolution.
 #include <algorithm>
 #include "dp_common.h"
 #include "dp_internal.h"
@@ -299,6 +301,7 @@ __device__ __forceinline__ void tn_dma_tile(const DmaArgs& a, const int L) {
     if (MODE == 0) vclip = a.clip[min(ex0 + lane, a.B - 1)];
     float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
     bool skip = false;                              // the current example is left out (see the head of this file)
+    float c_ref = c_cur;                            // the largest factor accumulated so far
 
     // prologue: all NST buffers are free, fill them
 #pragma unroll
@@ -346,8 +349,8 @@ __device__ __forceinline__ void tn_dma_tile(const DmaArgs& a, const int L) {
             ++ex;
             const float c_next = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), ex - ex0));
             const float ratio = c_cur / c_next;
-            // a zero factor (or one so small that the ratio overflows) after a non-zero one: leave this example out
-            skip = __builtin_isinf(ratio);
+            // a zero factor, or one far below the largest so far, after a non-zero one: leave this example out
+            skip = __builtin_isinf(ratio) || c_next < c_ref * 0x1p-40f;
             if (c_next != c_cur && !skip) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
@@ -356,7 +359,7 @@ __device__ __forceinline__ void tn_dma_tile(const DmaArgs& a, const int L) {
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
             }
-            if (!skip) c_cur = c_next;
+            if (!skip) { c_cur = c_next; c_ref = fmaxf(c_ref, c_next); }
         }
         ++sub;
 #pragma unroll

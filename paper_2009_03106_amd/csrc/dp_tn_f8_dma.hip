@@ -215,6 +215,7 @@ __device__ __forceinline__ void tn_f8_tile(const Dma8Args& a, const int L) {
     if (MODE == 0) vclip = a.clip[min(ex0 + lane, a.B - 1)];
     float c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), 0));
     bool skip = false;                              // the current example is left out (zero factor, see below)
+    float c_ref = c_cur;                            // the largest factor accumulated so far
 
     // prologue: all NST buffers are free, fill them
 #pragma unroll
@@ -265,9 +266,10 @@ __device__ __forceinline__ void tn_f8_tile(const Dma8Args& a, const int L) {
             ++ex;
             const float c_next = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vclip), ex - ex0));
             const float ratio = c_cur / c_next;
-            // a zero factor (or one so small that the ratio overflows) after a non-zero one cannot become the tile's
-            // unit: the example's MFMAs are skipped and the unit stays, i.e. it counts with factor 0
-            skip = __builtin_isinf(ratio);
+            // a zero factor, or one below 2^-40 of the largest so far (the tile in that unit would leave the float32
+            // range), after a non-zero one cannot become the tile's unit: the example's MFMAs are skipped and the unit
+            // stays, i.e. it counts with factor 0
+            skip = __builtin_isinf(ratio) || c_next < c_ref * 0x1p-40f;
             if (c_next != c_cur && !skip) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
@@ -276,7 +278,7 @@ __device__ __forceinline__ void tn_f8_tile(const Dma8Args& a, const int L) {
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
             }
-            if (!skip) c_cur = c_next;
+            if (!skip) { c_cur = c_next; c_ref = fmaxf(c_ref, c_next); }
         }
         ++sub;
         __builtin_amdgcn_s_waitcnt(0xC07F);                                              // lgkmcnt(0): this stage's fragments

@@ -796,6 +796,12 @@ def _factor_patterns(B, rng):
     pats["all zero"] = np.zeros(B, dtype=np.float32)
     z = base.copy(); z[::2] = 0.0; pats["every other zero"] = z
     m = base.copy(); m[B // 3] = 0.0; m[B // 3 + 1] = 1e-30; m[B // 3 + 2] = 1e-45; pats["mixed"] = m
+    # factors falling by 20 orders of magnitude from one example to the next: a tile kept in units of the last factor
+    # would leave the float32 range although the sum itself is of order 1
+    d = base.copy()
+    for k in range(0, B - 2, 3):
+        d[k:k + 3] = (0.5, 1e-20, 1e-40)
+    pats["falling"] = d
     return pats
 
 
@@ -840,6 +846,35 @@ def test_zero_clip_factors_conv_from_image(dp):
         got = g.cpu().numpy()
         assert np.all(np.isfinite(got)), (name, "not finite")
         check_clipped_sum(dp, A, G, clip, got, "bf16", ("conv", name))
+
+
+# The image-rows-in-LDS kernel streams several examples per K slice once the batch is large: zero and tiny factors at
+# the first, a middle and the last example of its slices (2, 4 and 8 examples; one stage per example in the last two)
+@pytest.mark.parametrize("B,H,W,d_out", [(1031, 8, 8, 64), (2100, 4, 8, 64), (2100, 4, 8, 128)])
+def test_zero_clip_factors_conv_rows_slices_of_several_examples(dp, B, H, W, d_out):
+    spec, X, G = wl.generate_conv_image(B=B, H=H, W=W, C=64, d_out=d_out, g_row_scale=np.exp(np.linspace(-1, 1, B)))
+    assert dp.conv_rows_resident(B, H, W, 64, 3, 3, spec["pad"], d_out, dp.DP_BF16)
+    Xd, Gd = to_dev(X), to_dev(G)
+    A = orc.conv_unfold(X, spec["KH"], spec["KW"], spec["pad"])
+    s_ref = orc.layer_sqnorm(A, G)
+    s = dp.conv_sqnorm(Xd, Gd, spec["KH"], spec["KW"], spec["pad"])
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT["bf16"]
+    pats = _factor_patterns(B, np.random.default_rng(5))
+    odd = pats["every other zero"].copy(); odd[::2] = 0.5; odd[1::2] = 0.0; pats["every other zero, odd"] = odd
+    absA, absG = np.abs(orc.widen(A)), np.abs(orc.widen(G))
+    for name, clip in pats.items():
+        g = dp.conv_clipped_grad(Xd, Gd, torch.from_numpy(clip).cuda(), spec["KH"], spec["KW"], spec["pad"])
+        got = g.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got)), (name, "not finite")
+        c64 = clip.astype(np.float64)
+        ref = orc.clipped_grad(A, G, c64)
+        scale = orc.clipped_grad(absA, absG, c64)              # sum of the terms' magnitudes
+        err = np.abs(got - ref)
+        assert np.all(err <= ELEM_TIGHT * scale + 1e-30 * max(float(scale.max()), 1e-300)), (name, float(np.max(err / (scale + 1e-300))))
+        if clip.any():
+            assert fro_err(got, ref) <= FRO_TIGHT, (name, fro_err(got, ref))
+        else:
+            assert not got.any(), (name, "all-zero factors must give an all-zero sum")
 
 
 def test_accumulate_flags(dp):
