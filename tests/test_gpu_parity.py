@@ -1090,6 +1090,8 @@ CONV_GEOMS = [
     (2, 16, 98, 64, 3, 3, 1, 40),       # the widest padded row that fits (100 pixels); W_out = 98 splits stages unevenly
     (4, 18, 12, 192, 3, 3, 0, 136),     # no padding, W_out = 10, three channel groups, three column tiles
     (3, 6, 18, 64, 3, 3, 2, 64),        # two rings of zeros around the image
+    (1, 8, 8, 64, 3, 3, 1, 64),         # one example: one K slice, the kernel writes (or adds to) the gradient itself
+    (2, 4, 8, 128, 3, 3, 1, 64),        # 32 positions: one stage per example
 ]
 
 
