@@ -82,7 +82,11 @@ __device__ unsigned long long g_trace[8 * 256];
 template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14)); }
 
 // MODE 0: clipped sum over the examples of a K slice.  MODE 1: direct squared norm of one example's tile.
-template <int MODE, bool F16>
+// RAG: the output positions of an example are not a multiple of the 32-position stage (28 x 28, 14 x 14, 7 x 7 ...):
+// every example takes ceil(T / 32) stages; the rows of G past its end are copied from the line of zeros, and the
+// image fragments of those positions are whatever the ring holds there - finite values, since the ring is cleared
+// before the first copy - so their products are exact zeros.
+template <int MODE, bool F16, bool RAG>
 __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_MAX];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -98,7 +102,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
     const int cbase = tm * CG, n0 = tn * TN;
     const int ex0 = z * a.ex_per_slice;
     const int E = min(a.ex_per_slice, a.B - ex0);
-    const int spe = a.T / DK;
+    const int spe = RAG ? (a.T + DK - 1) / DK : a.T / DK;
     const int n_stages = E * spe;
     const uint32_t upr = (uint32_t)a.rowbytes >> 10;                  // copy units per padded row
     const uint32_t ring_units = (uint32_t)a.ring_rows * upr;
@@ -116,6 +120,11 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
         const uint32_t px = c / CPP, ch = c - px * CPP, ix = px - (uint32_t)a.pad;
         table[c] = (ch < CG / 8 && ix < (uint32_t)a.W) ? (ix * (uint32_t)a.C + ch * 8u) * 2u : 0xFFFFFFFFu;
     }
+    if (RAG) {
+        const uint32_t n16 = ((uint32_t)a.ring_rows * (uint32_t)a.rowbytes) >> 4;
+        LDS_PTR(f32x4) ring16 = (LDS_PTR(f32x4))((LDS_PTR(unsigned char))lds + LDS_FIXED);
+        for (uint32_t c = tid; c < n16; c += THREADS) ring16[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     __syncthreads();
 
     // ---- copies.  G: a stage is 32 rows of 128 bytes = 4 units, one per wave; the 32-byte window v of row r sits at
@@ -130,6 +139,8 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
     }
     const uint16_t* baseG = a.G + (size_t)ex0 * a.T * a.N;
     const size_t stepG = (size_t)DK * a.N;
+    const int rowG = (wave * 64 + lane) >> 3;       // RAG: this lane's row of the stage, and the stage being issued
+    int ie = 0, isub = 0;
     const uint16_t* baseX = a.X + (size_t)ex0 * a.H * a.W * a.C + cbase;
     int oe = 0, osub = 0;                           // the oldest stage that still reads the ring: example, stage in it
 
@@ -193,10 +204,19 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
     };
     auto issue_stage = [&](int buf) {
         c3 = c2; c2 = c1; c1 = 1;
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :: "s"(lds_g + buf * G_STAGE), "v"(offG), "s"(baseG) : "memory", "m0");
-
-        baseG += stepG;
+        if (RAG) {
+            // rows past the example's end come from the line of zeros; the next example starts T rows, not a whole
+            // number of stages, behind this one
+            const uint64_t src = (uint64_t)(uintptr_t)(a.G + ((size_t)(ex0 + ie) * a.T + (size_t)isub * DK) * a.N) + offG;
+            const uint64_t addr = isub * DK + rowG < a.T ? src : (uint64_t)(uintptr_t)a.zero;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(lds_g + buf * G_STAGE), "v"(addr) : "memory", "m0");
+            if (++isub == spe) { isub = 0; ++ie; }
+        } else {
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(lds_g + buf * G_STAGE), "v"(offG), "s"(baseG) : "memory", "m0");
+            baseG += stepG;
+        }
         issue_image();
     };
     // stage s (relative) landed once at most `ahead` later stages' copies are outstanding
@@ -458,10 +478,10 @@ __global__ __launch_bounds__(THREADS, 1) void k_conv3x3_rows(ConvRowsArgs a) {
 // rows issued in time.  Fills the rounds of image copies needed before the first stage.
 bool schedule_ok(const ConvGeom& g, int E, int rps, int ring_rows, int* pre_rounds) {
     const int Hp = g.H + 2 * g.pad, Wout = g.W + 2 * g.pad - 2, Hout = g.H + 2 * g.pad - 2;
-    const int T = Hout * Wout, spe = T / DK;
+    const int T = Hout * Wout, spe = (T + DK - 1) / DK;
     const int64_t rows_total = (int64_t)E * Hp;
     auto need = [&](int e, int sub) {
-        const int64_t yb = (int64_t)(sub * DK + DK - 1) / Wout;
+        const int64_t yb = std::min<int64_t>((int64_t)(sub * DK + DK - 1) / Wout, Hout - 1);   // positions past T need no rows
         return std::min(rows_total, (int64_t)e * Hp + yb + 3);
     };
     auto limit = [&](int oe, int osub) {
@@ -507,7 +527,9 @@ RowsPlan plan_rows(const ConvGeom& g, int N, int B, int E) {
     const int64_t Hout = (int64_t)g.H + 2 * g.pad - 2, Wout = (int64_t)g.W + 2 * g.pad - 2;
     if (Hout < 1 || Wout < 2) return p;
     const int64_t T = Hout * Wout, Hp = g.H + 2 * g.pad, Wp = g.W + 2 * g.pad;
-    if ((T % DK) != 0 || T >= (int64_t(1) << 24) || Wp > 4096 || Hp > 4096) return p;
+    // whole stages of 32 positions, or at most a quarter of a ragged example's stages beyond its end (49, 196, 784 ...)
+    const int64_t Tp = (T + DK - 1) / DK * DK;
+    if (Tp * 3 > T * 4 || T >= (int64_t(1) << 24) || Wp > 4096 || Hp > 4096) return p;
     const int64_t rowbytes = (Wp * PITCH + 1023) / 1024 * 1024;
     if (rowbytes < 2048 || rowbytes * 64 / 1024 * 4 > TABLE_BYTES) return p;      // 2 .. 16 copy units per row
     p.tiles_m = g.C / CG;
@@ -574,8 +596,14 @@ hipError_t launch_direct_conv_rows(const ConvGeom& g, const uint16_t* X, const u
     fill_args(a, p, g, X, G, B, N, zero);
     a.clip = nullptr; a.out = partial; a.slice = 0; a.accumulate = 0;
     const unsigned grid = 8u * (unsigned)a.per_xcd;
-    if (f16) k_conv3x3_rows<1, true><<<grid, THREADS, 0, st>>>(a);
-    else     k_conv3x3_rows<1, false><<<grid, THREADS, 0, st>>>(a);
+    const bool rag = (a.T % DK) != 0;
+    if (rag) {
+        if (f16) k_conv3x3_rows<1, true, true><<<grid, THREADS, 0, st>>>(a);
+        else     k_conv3x3_rows<1, false, true><<<grid, THREADS, 0, st>>>(a);
+    } else {
+        if (f16) k_conv3x3_rows<1, true, false><<<grid, THREADS, 0, st>>>(a);
+        else     k_conv3x3_rows<1, false, false><<<grid, THREADS, 0, st>>>(a);
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_finalize_partials(partial, B, p.tiles_m * p.tiles_n, accumulate, sqnorm, st, co);
@@ -593,8 +621,14 @@ hipError_t launch_clipped_conv_rows(const ConvGeom& g, const uint16_t* X, const 
     if (p.splits == 1) { a.out = grad; a.slice = 0; a.accumulate = accumulate ? 1 : 0; }
     else { a.out = ws; a.slice = splitk_slice_elems(n); a.accumulate = 0; }
     const unsigned grid = 8u * (unsigned)a.per_xcd;
-    if (f16) k_conv3x3_rows<0, true><<<grid, THREADS, 0, st>>>(a);
-    else     k_conv3x3_rows<0, false><<<grid, THREADS, 0, st>>>(a);
+    const bool rag = (a.T % DK) != 0;
+    if (rag) {
+        if (f16) k_conv3x3_rows<0, true, true><<<grid, THREADS, 0, st>>>(a);
+        else     k_conv3x3_rows<0, false, true><<<grid, THREADS, 0, st>>>(a);
+    } else {
+        if (f16) k_conv3x3_rows<0, true, false><<<grid, THREADS, 0, st>>>(a);
+        else     k_conv3x3_rows<0, false, false><<<grid, THREADS, 0, st>>>(a);
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_splitk_reduce(ws, n, p.splits, accumulate, grad, st, noise);

@@ -250,14 +250,15 @@ def test_missing_library_raises(monkeypatch):
 
 def test_conv_rows_resident_host_logic(lib):
     """Host logic only: which convolution geometries the image-rows-in-LDS kernel takes (3 x 3, C a multiple of 64,
-    T a multiple of 32, a padded row that fits its copy table), and that the workspace query follows the choice."""
+    a padded row that fits its copy table), and that the workspace query follows the choice."""
     q = dpclip.conv_rows_resident
     bf = dpclip.DP_BF16
     assert q(128, 32, 32, 64, 3, 3, 1, 128, bf) is True             # the convolution configuration
     assert q(128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F16) is True
     assert q(128, 32, 32, 64, 3, 3, 1, 128, dpclip.DP_F8_E4M3) is True      # widened to fp16 first
     assert q(2, 16, 98, 64, 3, 3, 1, 40, bf) is True                # 100-pixel padded row: the widest that fits
-    assert q(3, 28, 28, 64, 3, 3, 1, 128, bf) is False              # 784 positions: general kernel
+    assert q(3, 28, 28, 64, 3, 3, 1, 128, bf) is True               # 784 positions: 24.5 stages per example
+    assert q(4, 7, 7, 128, 3, 3, 1, 64, bf) is True                 # 49 positions
     assert q(2, 8, 16, 64, 5, 5, 2, 120, bf) is False               # 5 x 5
     assert q(2, 9, 9, 32, 2, 2, 0, 128, bf) is False                # 32 channels
     assert q(2, 16, 128, 64, 3, 3, 1, 128, bf) is False             # 130-pixel padded row: general kernel
