@@ -583,7 +583,16 @@ void fill_args(ConvRowsArgs& a, const RowsPlan& p, const ConvGeom& g, const uint
 
 }  // namespace
 
-bool conv_rows_ok(const ConvGeom& g, int d_out, int B) { return plan_rows(g, d_out, B, 1).ok && plan_rows(g, d_out, B, 0).ok; }
+// This kernel spends about 7 stage times per workgroup outside its stages, and its norm mode takes one example per
+// workgroup: with fewer than 16 stages per example (images below about 23 x 23) the general copy-pipeline kernel with
+// implicit unfolding is as fast or faster where it takes the geometry at all (measured from the image, bf16, this
+// kernel against that one: 32 x 32 x 64 -> 128, B = 128: 26 / 40 us against 39 / 47; 28 x 28: 26 / 36 against
+// 33 / 41; 16 x 16 x 128 -> 128, B = 256: 39 / 51 against 38 / 46; 8 x 8 x 256 -> 256, B = 256: 81 / 60 against 57 / 49).
+bool conv_rows_ok(const ConvGeom& g, int d_out, int B) {
+    if (!plan_rows(g, d_out, B, 1).ok || !plan_rows(g, d_out, B, 0).ok) return false;
+    const int64_t T = (int64_t)(g.H + 2 * g.pad - 2) * (g.W + 2 * g.pad - 2);
+    return T >= 16 * DK || !dma_conv_ok(g, d_out);
+}
 int conv_rows_tiles(const ConvGeom& g, int d_out) { return (g.C / CG) * ((d_out + TN - 1) / TN); }
 int conv_rows_splits(const ConvGeom& g, int d_out, int B) { return plan_rows(g, d_out, B, 0).splits; }
 
