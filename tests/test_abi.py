@@ -272,3 +272,39 @@ def test_conv_rows_resident_host_logic(lib):
     # clipped sum: whole float32 slices of the 576 x 128 gradient
     w = dpclip.conv_workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, 128, 32, 32, 64, 3, 3, 1, 128, bf)
     assert (w - 256) % (576 * 128 * 4) == 0 and w > 256
+
+
+def test_conv_geometry_queries_over_many_shapes(lib):
+    """Host logic only: the kernel choice and the workspace sizes of the convolution calls answer consistently over a
+    sweep of image sizes, paddings, channel counts and batch sizes (the choice replays the copy schedule of the
+    image-rows-in-LDS kernel on the host for every geometry it accepts)."""
+    bf = dpclip.DP_BF16
+    n_rows = n_general = n_none = 0
+    for H in (1, 3, 4, 7, 8, 9, 14, 16, 17, 28, 32, 33, 56, 64, 98, 100, 112):
+        for W in (4, 7, 8, 14, 16, 24, 28, 32, 56, 64, 98, 100, 130):
+            for pad in (0, 1, 2):
+                if H + 2 * pad < 3 or W + 2 * pad < 3:
+                    continue
+                for (C, N, B) in ((64, 64, 1), (64, 128, 128), (128, 72, 5), (192, 256, 1100), (256, 40, 33)):
+                    geo = (B, H, W, C, 3, 3, pad, N, bf)
+                    ws_s = dpclip.conv_workspace_bytes(dpclip.DP_OP_SQNORM, *geo)
+                    ws_c = dpclip.conv_workspace_bytes(dpclip.DP_OP_CLIPPED_GRAD, *geo)
+                    try:
+                        rows = dpclip.conv_rows_resident(*geo)
+                    except ValueError:
+                        n_none += 1
+                        assert ws_s == 0 and ws_c == 0, geo
+                        continue
+                    assert ws_s >= 256 + 4 * B and ws_c >= 256 and ws_s % 4 == 0 and ws_c % 4 == 0, geo
+                    T = (H + 2 * pad - 2) * (W + 2 * pad - 2)
+                    if rows:
+                        n_rows += 1
+                        assert W + 2 * pad <= 102 and 4 * T >= 3 * (-(-T // 32) * 32), geo
+                        assert ws_s == 256 + 4 * B * (C // 64) * (-(-N // 64)), geo
+                        assert (ws_c - 256) % (9 * C * N * 4) == 0, geo
+                    else:
+                        n_general += 1
+                        # the general kernel: short examples, rows too wide for the other kernel's copy table, or so
+                        # narrow that a 32-position stage consumes more image rows than a round of copies brings
+                        assert T >= 64 and (T < 512 or W + 2 * pad > 102 or W + 2 * pad - 2 < 8), geo
+    assert n_rows > 500 and n_general > 100 and n_none > 100, (n_rows, n_general, n_none)
