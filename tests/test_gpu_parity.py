@@ -1135,6 +1135,47 @@ def test_conv_from_image(dp, B, H, W, C, KH, KW, pad, d_out):
         np.testing.assert_array_equal(dp.clipped_grad(Ad, Gd, c).cpu().numpy(), g.cpu().numpy())
 
 
+def _drawn_conv_rows_geometries(n, seed):
+    """Seeded draws of 3 x 3 geometries that the image-rows-in-LDS kernel takes: image sides 3 .. 100, padding 0 .. 2,
+    64 or 128 channels, d_out a multiple of 8 up to 136, 1 .. 3 examples."""
+    from paper_2009_03106_amd import dpclip
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        H, W = int(rng.integers(3, 101)), int(rng.integers(3, 101))
+        pad, C = int(rng.integers(0, 3)), int(rng.choice([64, 128]))
+        d_out, B = 8 * int(rng.integers(1, 18)), int(rng.integers(1, 4))
+        if H + 2 * pad < 3 or W + 2 * pad < 4 or (H + 2 * pad - 2) * (W + 2 * pad - 2) * B > 12000:
+            continue
+        try:
+            if dpclip.conv_rows_resident(B, H, W, C, 3, 3, pad, d_out, dpclip.DP_BF16):
+                out.append((B, H, W, C, pad, d_out))
+        except ValueError:
+            pass
+    return out
+
+
+@pytest.mark.parametrize("B,H,W,C,pad,d_out", _drawn_conv_rows_geometries(40, 20260))
+def test_conv_rows_drawn_geometries(dp, B, H, W, C, pad, d_out):
+    """The copy schedule of the image-rows-in-LDS kernel (ring size, rows per round, rounds ahead) depends on the
+    geometry: norms and clipped sums against the oracle on drawn geometries, alternating bf16 and fp16."""
+    dtype = "bf16" if (H + W) % 2 == 0 else "f16"
+    spec, X, G = wl.generate_conv_image(B=B, H=H, W=W, C=C, KH=3, KW=3, pad=pad, d_out=d_out, seed=wl.BASE_SEED + H * 101 + W,
+                                        g_row_scale=(1024.0 if dtype == "f16" else 1.0) * np.exp(np.linspace(-1, 1, B)), dtype=dtype)
+    A = orc.conv_unfold(X, 3, 3, pad)
+    s_ref = orc.layer_sqnorm(A, G)
+    Xd, Gd = to_dev(X), to_dev(G)
+    s = dp.conv_sqnorm(Xd, Gd, 3, 3, pad)
+    assert rel_err(s.cpu().numpy(), s_ref) <= SQ_TIGHT[dtype], rel_err(s.cpu().numpy(), s_ref)
+    clip = (0.25 + 0.75 * np.random.default_rng(H * W).random(B)).astype(np.float32)
+    g = dp.conv_clipped_grad(Xd, Gd, torch.from_numpy(clip).cuda(), 3, 3, pad)
+    ref = orc.clipped_grad(A, G, clip.astype(np.float64))
+    scale = orc.clipped_grad(np.abs(orc.widen(A)), np.abs(orc.widen(G)), clip.astype(np.float64))
+    err = np.abs(g.cpu().numpy().astype(np.float64) - ref)
+    assert np.all(err <= ELEM_TIGHT * scale + 1e-30 * scale.max()), float(np.max(err / (scale + 1e-300)))
+    assert fro_err(g.cpu().numpy(), ref) <= FRO_TIGHT
+
+
 @pytest.mark.parametrize("B,H,W,C,KH,KW,pad,d_out", [CONV_GEOMS[0], CONV_GEOMS[1], CONV_GEOMS[3], CONV_GEOMS[6], CONV_GEOMS[8],
                                                      CONV_GEOMS[12], CONV_GEOMS[16]])
 def test_conv_from_image_fp16(dp, B, H, W, C, KH, KW, pad, d_out):
