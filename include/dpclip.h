@@ -361,18 +361,21 @@ dp_status dp_clipped_bias_grad(const float* bias_rows, const float* clip,
  * dp_conv_sqnorm and dp_conv_clipped_grad compute exactly what
  * dp_layer_sqnorm (direct path) and dp_clipped_grad compute on the unfolded
  * A[B, T, d_in]; arguments not listed here mean the same as there.
- * Supported: DP_BF16, DP_F16 and the 8-bit types (widened to fp16), C % 8 == 0, d_out % 8 == 0, T >= 64 with at most a quarter
- * of padding up to the next multiple of 32 (e.g. 784, 196, 1024), and a
- * [d_in, d_out] that tiles into 256 x 256, 192 x 128 or 128 x 128 blocks with at
- * most a quarter of padding; anything else is DP_ERR_UNSUPPORTED (unfold and use the
- * general entry points).  workspace: at least dp_conv_workspace_bytes(...).
- * 3 x 3 kernels with C a multiple of 64, a padded image row of at most about
- * 100 pixels and T of at least three quarters of the next multiple of 32 can
- * run on a kernel of their own that keeps the padded image rows in LDS and
- * fetches every pixel once instead of once per tap; it is used for T >= 512
- * and for every geometry that the general kernels above do not take (d_out or
- * 9 C that do not tile, T < 64): dp_conv_rows_resident tells.  Its results are
- * those of the general entry points up to the order of the float32 sums. */
+ * Types: DP_BF16, DP_F16 and the 8-bit types (widened to fp16); d_out % 8 == 0.
+ * Two families of geometries are taken, anything else is DP_ERR_UNSUPPORTED
+ * (unfold and use the general entry points):
+ * (1) C % 8 == 0, T >= 64 with at most a quarter of padding up to the next
+ *     multiple of 32 (e.g. 784, 196, 1024), and a [d_in, d_out] that tiles into
+ *     256 x 256, 192 x 128 or 128 x 128 blocks with at most a quarter of
+ *     padding: the general kernels with the patches formed by their copies;
+ * (2) 3 x 3 kernels with C a multiple of 64, a padded image row of at most
+ *     about 100 pixels and T of at least three quarters of the next multiple
+ *     of 32: a kernel of its own that keeps the padded image rows in LDS and
+ *     fetches every pixel once instead of once per tap.  It is used for
+ *     T >= 512 and wherever (1) does not apply (d_out or 9 C that do not tile,
+ *     T < 64); dp_conv_rows_resident tells.  Its results are those of the
+ *     general entry points up to the order of the float32 sums.
+ * workspace: at least dp_conv_workspace_bytes(...). */
 dp_status dp_conv_sqnorm(const void* X, const void* G,
                          int64_t B, int64_t H, int64_t W, int64_t C,
                          int64_t KH, int64_t KW, int64_t pad, int64_t d_out,
