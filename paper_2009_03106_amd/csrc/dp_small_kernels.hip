@@ -280,7 +280,14 @@ __global__ void k_finalize_partials(const float* __restrict__ partial, int B, in
     if (i >= B) return;
     const float* p = partial + (size_t)i * n;
     float s = 0.f;
-    for (int j = 0; j < n; ++j) s += p[j];
+    for (int j0 = 0; j0 < n; j0 += 8) {             // eight loads in flight, added in order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[min(j0 + u, n - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (j0 + u < n) s += v[u];
+    }
     s = accumulate ? sqnorm[i] + s : s;
     sqnorm[i] = s;
     if (clip) clip[i] = clip_factor_of(s, C);
@@ -365,13 +372,32 @@ hipError_t launch_finalize_layers(const float* partial, const FinalizeLayers& f,
 
 // One output array per layer; arrays may repeat (layers of one group), so they are read and written layer after
 // layer by the example's one thread and are not declared restrict.
-__global__ void k_finalize_each(const float* __restrict__ partial, FinalizeEach f, int B) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= B) return;
+__global__ __launch_bounds__(256) void k_finalize_each(const float* __restrict__ partial, FinalizeEach f, int B) {
+    // the layers' sums as in k_finalize_layers (four threads per example), then the example's first thread walks the
+    // output arrays in the order given
+    __shared__ float tl[kGramBatch][64];
+    const int e = threadIdx.x & 63, k = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + e;
+    if (i < B) {
+        for (int l = k; l < f.n_layers; l += 4) {
+            const int n = f.n[l];
+            const float* p = partial + (size_t)f.first[l] + (size_t)i * n;
+            float t = 0.f;
+            for (int j0 = 0; j0 < n; j0 += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = p[min(j0 + u, n - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (j0 + u < n) t += v[u];
+            }
+            tl[l][e] = t;
+        }
+    }
+    __syncthreads();
+    if (k != 0 || i >= B) return;
     for (int l = 0; l < f.n_layers; ++l) {
-        const float* p = partial + (size_t)f.first[l] + (size_t)i * f.n[l];
-        float t = 0.f;
-        for (int j = 0; j < f.n[l]; ++j) t += p[j];
+        const float t = tl[l][e];
         float* out = f.out[l];
         const float s = f.acc[l] ? out[i] + t : t;
         out[i] = s;
@@ -380,7 +406,7 @@ __global__ void k_finalize_each(const float* __restrict__ partial, FinalizeEach 
 }
 
 hipError_t launch_finalize_each(const float* partial, const FinalizeEach& f, int B, hipStream_t st) {
-    k_finalize_each<<<(B + 63) / 64, 64, 0, st>>>(partial, f, B);
+    k_finalize_each<<<(B + 63) / 64, 256, 0, st>>>(partial, f, B);
     return hipGetLastError();
 }
 
