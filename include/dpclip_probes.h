@@ -35,7 +35,8 @@ dp_status dp_probe_mfma(dp_dtype dtype, int random_operands, int64_t iters,
                         float* sink, double* flops, void* hip_stream);
 
 /* Plain streaming read of `bytes` bytes (a multiple of 16) at `src`, 16 bytes
- * per lane and eight loads in flight per lane: what a kernel that only reads
+ * per lane and sixteen loads in flight per lane, every workgroup on a
+ * contiguous range of its own: what a kernel that only reads
  * can get from HBM (src larger than the 256 MB last-level cache) or from that
  * cache (src smaller, second pass). */
 dp_status dp_probe_read(const void* src, size_t bytes, float* sink, void* hip_stream);
